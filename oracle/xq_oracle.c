@@ -1,0 +1,340 @@
+/*
+ * XQuant decode hot path -- CPU ORACLE.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, obviously-correct host implementation of what the GPU library
+ * computes.  It is the checker, never the product: only the test-suite, the
+ * smoke entry and the benchmark's cpu_baseline leg may build, load or call it.
+ * It shares no source, header, table or helper with the HIP path.
+ *
+ * What is implemented, and the passage of the paper each step follows
+ * (arxiv 2508.10395):
+ *
+ *   xqo_quantize_rows      Sec. 3.1 + Sec. 4 "Empirical Results" setup: uniform
+ *                          asymmetric b-bit quantization of the post-norm layer
+ *                          input X, per token, groups of G consecutive hidden
+ *                          channels, one scale and one zero-point per group,
+ *                          16 bits each (the normalised cache sizes printed in
+ *                          Tables 1 and 4 fix 32 metadata bits per group).
+ *   xqo_pack_rows /        storage format of the codes: one little-endian bit
+ *   xqo_unpack_rows        string per token row (the paper is silent on it).
+ *   xqo_dequantize_rows    x^ = code * scale + zero.
+ *   xqo_cl_delta_rows      Sec. 3.2: dX_i = X_i - X^_{i-1} (delta against the
+ *                          running approximation, not the true previous X).
+ *   xqo_cl_accumulate_rows Sec. 3.2: X^_i = X^_{i-1} + dX^_i, the accumulator
+ *                          form of X^_i = X_0 + sum_j dX^_j.
+ *   xqo_remat_head         Sec. 3.1: K = X^ Wk, V = X^ Wv for one head.
+ *   xqo_attention          softmax(q K^T * scale) V for one decode query
+ *                          (textbook attention; two passes, in double).
+ *   xqo_remat_attn_pairs   composition of the above for a list of
+ *                          (sequence, query-head) pairs; nothing else.
+ *
+ * Arithmetic: everything the bit-exact contract covers (min/max, scale, zero,
+ * codes, accumulator) is done in IEEE fp32 with explicit fmaf where a fused
+ * operation is meant; everything compared by tolerance (K, V, scores, softmax,
+ * output) is accumulated in double, index ascending.  Build WITHOUT fast-math
+ * and with -ffp-contract=off.
+ *
+ * Readings taken where the paper gives no formula (also listed in the design
+ * notes): zero-point = group minimum stored as bf16 (round-to-nearest-even),
+ * scale = (max-min)/(2^b-1) in fp32, stored as bf16 (RNE); codes are computed
+ * from the STORED scale and zero: clamp(rint((x - zero)/scale), 0, 2^b-1) with
+ * fp32 subtract, fp32 IEEE divide and round-half-to-even; a group whose stored
+ * scale is zero gets all-zero codes; a zero-point that is a zero of either sign
+ * is stored as +0.
+ *
+ * Parity pins (tests/test_oracle_*.py, all CPU): closed-form code grids, tie
+ * cases, monotonicity, the half-step round-trip bound, hand-written pack bytes,
+ * cache sizes printed in the paper's tables, identity-quantiser remat == numpy
+ * matmul, the cross-layer telescoping identity and depth-independent error
+ * bound, attention closed forms (uniform scores, two-token logistic weight,
+ * shift/permutation/split invariance) and scipy softmax.  The absolute
+ * attention outputs on the synthetic benchmark inputs have no printed value in
+ * the paper: for those, parity is pinned only through the chain above.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---------------------------------------------------------------- bf16 --- */
+
+static float bf16_bits_to_float(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* round-to-nearest-even from fp32 to the upper 16 bits (finite inputs) */
+static uint16_t float_to_bf16_bits_rne(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    uint32_t lower = u & 0xFFFFu;
+    uint32_t upper = u >> 16;
+    if (lower > 0x8000u || (lower == 0x8000u && (upper & 1u)))
+        upper += 1u;
+    return (uint16_t)upper;
+}
+
+void xqo_bf16_to_f32(const uint16_t *in, int64_t n, float *out)
+{
+    for (int64_t i = 0; i < n; ++i)
+        out[i] = bf16_bits_to_float(in[i]);
+}
+
+void xqo_f32_to_bf16(const float *in, int64_t n, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i)
+        out[i] = float_to_bf16_bits_rne(in[i]);
+}
+
+/* ------------------------------------------------------------ quantize --- */
+
+/*
+ * Sec. 3.1 / Sec. 4 setup.  x: [rows][d] fp32 (for the X cache these are bf16
+ * values widened exactly; for cross-layer deltas they are fp32 differences).
+ * codes: [rows][d], one byte per code (unpacked).  scale, zero: [rows][d/G]
+ * bf16 bit patterns.
+ */
+void xqo_quantize_rows(const float *x, int64_t rows, int d, int G, int bits,
+                       uint8_t *codes, uint16_t *scale, uint16_t *zero)
+{
+    const int ngroups = d / G;
+    const float qmax = (float)((1 << bits) - 1);
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int g = 0; g < ngroups; ++g) {
+            const float *xg = x + r * (int64_t)d + (int64_t)g * G;
+            float mn = xg[0], mx = xg[0];
+            for (int i = 1; i < G; ++i) {
+                if (xg[i] < mn) mn = xg[i];
+                if (xg[i] > mx) mx = xg[i];
+            }
+            uint16_t zb = float_to_bf16_bits_rne(mn);
+            if ((zb & 0x7FFFu) == 0) zb = 0;              /* -0 -> +0 */
+            float range = mx - mn;                        /* fp32 subtract */
+            float step = range / qmax;                    /* fp32 IEEE divide */
+            uint16_t sb = float_to_bf16_bits_rne(step);
+            const float zf = bf16_bits_to_float(zb);
+            const float sf = bf16_bits_to_float(sb);
+            scale[r * ngroups + g] = sb;
+            zero[r * ngroups + g] = zb;
+            uint8_t *qg = codes + r * (int64_t)d + (int64_t)g * G;
+            for (int i = 0; i < G; ++i) {
+                if (sf == 0.0f) { qg[i] = 0; continue; }
+                float num = xg[i] - zf;                   /* fp32 subtract */
+                float quo = num / sf;                     /* fp32 IEEE divide */
+                float rq = rintf(quo);                    /* half to even */
+                if (rq < 0.0f) rq = 0.0f;
+                if (rq > qmax) rq = qmax;
+                qg[i] = (uint8_t)rq;
+            }
+        }
+    }
+}
+
+/* ---------------------------------------------------------------- pack --- */
+
+/*
+ * Code j of a row occupies bits [j*bits, (j+1)*bits) of the row's bit string;
+ * byte k of the row holds bits 8k .. 8k+7, least significant first.
+ */
+void xqo_pack_rows(const uint8_t *codes, int64_t rows, int d, int bits,
+                   uint8_t *packed)
+{
+    const int64_t row_bytes = ((int64_t)d * bits) / 8;
+    memset(packed, 0, (size_t)(rows * row_bytes));
+    for (int64_t r = 0; r < rows; ++r) {
+        uint8_t *p = packed + r * row_bytes;
+        for (int j = 0; j < d; ++j) {
+            unsigned c = codes[r * (int64_t)d + j];
+            for (int k = 0; k < bits; ++k) {
+                int64_t bit = (int64_t)j * bits + k;
+                if ((c >> k) & 1u)
+                    p[bit >> 3] |= (uint8_t)(1u << (bit & 7));
+            }
+        }
+    }
+}
+
+void xqo_unpack_rows(const uint8_t *packed, int64_t rows, int d, int bits,
+                     uint8_t *codes)
+{
+    const int64_t row_bytes = ((int64_t)d * bits) / 8;
+    for (int64_t r = 0; r < rows; ++r) {
+        const uint8_t *p = packed + r * row_bytes;
+        for (int j = 0; j < d; ++j) {
+            unsigned c = 0;
+            for (int k = 0; k < bits; ++k) {
+                int64_t bit = (int64_t)j * bits + k;
+                c |= (unsigned)((p[bit >> 3] >> (bit & 7)) & 1u) << k;
+            }
+            codes[r * (int64_t)d + j] = (uint8_t)c;
+        }
+    }
+}
+
+/* ---------------------------------------------------------- dequantize --- */
+
+/* x^ = code*scale + zero, one fp32 fused multiply-add, not rounded further */
+void xqo_dequantize_rows(const uint8_t *codes, const uint16_t *scale,
+                         const uint16_t *zero, int64_t rows, int d, int G,
+                         float *xhat)
+{
+    const int ngroups = d / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int c = 0; c < d; ++c) {
+            int g = c / G;
+            float sf = bf16_bits_to_float(scale[r * ngroups + g]);
+            float zf = bf16_bits_to_float(zero[r * ngroups + g]);
+            xhat[r * (int64_t)d + c] = fmaf((float)codes[r * (int64_t)d + c], sf, zf);
+        }
+}
+
+/* ------------------------------------------------- cross-layer (Sec 3.2) --- */
+
+/* dX = X_i - X^_{i-1}: both operands bf16, difference in fp32 */
+void xqo_cl_delta_rows(const uint16_t *x_bf16, const uint16_t *acc_bf16,
+                       int64_t n, float *delta)
+{
+    for (int64_t i = 0; i < n; ++i)
+        delta[i] = bf16_bits_to_float(x_bf16[i]) - bf16_bits_to_float(acc_bf16[i]);
+}
+
+/*
+ * X^_i = X^_{i-1} + dX^_i on a bf16 accumulator: fp32 fma for the dequantised
+ * delta, fp32 add, one RNE rounding back to bf16.  init != 0 starts from +0
+ * (the base layer X_0 enters the accumulator this way).
+ */
+void xqo_cl_accumulate_rows(uint16_t *acc_bf16, const uint8_t *codes,
+                            const uint16_t *scale, const uint16_t *zero,
+                            int64_t rows, int d, int G, int init)
+{
+    const int ngroups = d / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int c = 0; c < d; ++c) {
+            int g = c / G;
+            float sf = bf16_bits_to_float(scale[r * ngroups + g]);
+            float zf = bf16_bits_to_float(zero[r * ngroups + g]);
+            float dq = fmaf((float)codes[r * (int64_t)d + c], sf, zf);
+            float prev = init ? 0.0f : bf16_bits_to_float(acc_bf16[r * (int64_t)d + c]);
+            float sum = prev + dq;
+            acc_bf16[r * (int64_t)d + c] = float_to_bf16_bits_rne(sum);
+        }
+}
+
+/* ------------------------------------------------ rematerialise (Sec 3.1) --- */
+
+/*
+ * out[t][n] = sum_c xhat[t][c] * W[c][col0 + n], n < hd, accumulated in
+ * double with c ascending.  W is bf16 [d][ncols] row-major.
+ */
+void xqo_remat_head(const float *xhat, const uint16_t *W, int L, int d,
+                    int ncols, int col0, int hd, double *out)
+{
+    for (int t = 0; t < L; ++t) {
+        double *o = out + (int64_t)t * hd;
+        for (int n = 0; n < hd; ++n) o[n] = 0.0;
+        for (int c = 0; c < d; ++c) {
+            double xv = (double)xhat[(int64_t)t * d + c];
+            const uint16_t *wrow = W + (int64_t)c * ncols + col0;
+            for (int n = 0; n < hd; ++n)
+                o[n] += xv * (double)bf16_bits_to_float(wrow[n]);
+        }
+    }
+}
+
+/* ------------------------------------------------------------ attention --- */
+
+/*
+ * One decode query against L rematerialised rows:
+ *   s_t = (sum_n q[n] K[t][n]) * softmax_scale
+ *   p   = softmax(s)   (max subtracted, two passes)
+ *   out[n] = sum_t p_t V[t][n]
+ */
+void xqo_attention(const uint16_t *q_bf16, const double *K, const double *V,
+                   int L, int hd, double softmax_scale, float *out)
+{
+    double *s = (double *)malloc(sizeof(double) * (size_t)L);
+    double smax = -INFINITY;
+    for (int t = 0; t < L; ++t) {
+        double a = 0.0;
+        for (int n = 0; n < hd; ++n)
+            a += (double)bf16_bits_to_float(q_bf16[n]) * K[(int64_t)t * hd + n];
+        s[t] = a * softmax_scale;
+        if (s[t] > smax) smax = s[t];
+    }
+    double denom = 0.0;
+    for (int t = 0; t < L; ++t) {
+        s[t] = exp(s[t] - smax);
+        denom += s[t];
+    }
+    for (int n = 0; n < hd; ++n) {
+        double a = 0.0;
+        for (int t = 0; t < L; ++t)
+            a += s[t] * V[(int64_t)t * hd + n];
+        out[n] = (float)(a / denom);
+    }
+    free(s);
+}
+
+/* ----------------------------------------------------------- composition --- */
+
+/*
+ * For each listed (sequence b, query head hq): take the first len[b] rows of
+ * that sequence's input approximation, rematerialise its KV head, attend.
+ * Exactly one source is used:
+ *   packed != NULL : X cache (packed codes + scale + zero), dequantised here;
+ *   acc_bf16 != NULL : cross-layer accumulator, widened to fp32.
+ * Layouts: packed [B][cap][d*bits/8], scale/zero [B][cap][d/G],
+ * acc [B][cap][d], q [B][Hq][hd], Wk/Wv [d][Hkv*hd], out [npairs][hd].
+ */
+void xqo_remat_attn_pairs(const uint8_t *packed, const uint16_t *scale,
+                          const uint16_t *zero, const uint16_t *acc_bf16,
+                          int cap, int d, int G, int bits,
+                          const uint16_t *q_bf16, const uint16_t *Wk,
+                          const uint16_t *Wv, int Hq, int Hkv, int hd,
+                          double softmax_scale, const int32_t *len,
+                          const int32_t *pair_b, const int32_t *pair_hq,
+                          int npairs, float *out)
+{
+    const int ngroups = d / G;
+    const int64_t row_bytes = ((int64_t)d * bits) / 8;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int p = 0; p < npairs; ++p) {
+        const int b = pair_b[p], hq = pair_hq[p];
+        const int hkv = hq / (Hq / Hkv);
+        const int L = len[b];
+        float *xhat = (float *)malloc(sizeof(float) * (size_t)L * d);
+        if (packed) {
+            uint8_t *codes = (uint8_t *)malloc((size_t)L * d);
+            xqo_unpack_rows(packed + (int64_t)b * cap * row_bytes, L, d, bits, codes);
+            xqo_dequantize_rows(codes, scale + (int64_t)b * cap * ngroups,
+                                zero + (int64_t)b * cap * ngroups, L, d, G, xhat);
+            free(codes);
+        } else {
+            xqo_bf16_to_f32(acc_bf16 + (int64_t)b * cap * d, (int64_t)L * d, xhat);
+        }
+        double *K = (double *)malloc(sizeof(double) * (size_t)L * hd);
+        double *V = (double *)malloc(sizeof(double) * (size_t)L * hd);
+        xqo_remat_head(xhat, Wk, L, d, Hkv * hd, hkv * hd, hd, K);
+        xqo_remat_head(xhat, Wv, L, d, Hkv * hd, hkv * hd, hd, V);
+        xqo_attention(q_bf16 + ((int64_t)b * Hq + hq) * hd, K, V, L, hd,
+                      softmax_scale, out + (int64_t)p * hd);
+        free(K); free(V); free(xhat);
+    }
+}
+
+int xqo_max_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

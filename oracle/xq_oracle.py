@@ -1,0 +1,174 @@
+"""ctypes front-end of the CPU oracle (oracle/xq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke entry and by the
+benchmark's cpu_baseline leg.  The product package never imports this module.
+All arrays are host numpy arrays; bf16 tensors travel as uint16 bit patterns.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        _LIB = C.CDLL(_build.build())
+        _LIB.xqo_max_threads.restype = C.c_int
+    return _LIB
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == dtype, (a.dtype, dtype)
+    return a
+
+
+def max_threads():
+    return int(lib().xqo_max_threads())
+
+
+def bf16_to_f32(bits):
+    bits = _c(bits, np.uint16)
+    out = np.empty(bits.shape, np.float32)
+    lib().xqo_bf16_to_f32(_p(bits), C.c_int64(bits.size), _p(out))
+    return out
+
+
+def f32_to_bf16(x):
+    x = _c(x, np.float32)
+    out = np.empty(x.shape, np.uint16)
+    lib().xqo_f32_to_bf16(_p(x), C.c_int64(x.size), _p(out))
+    return out
+
+
+def quantize_rows(x_f32, G, bits):
+    """x_f32 [..., d] fp32 -> (codes u8 [..., d], scale u16 [..., d/G], zero u16 [..., d/G])."""
+    x = _c(x_f32, np.float32)
+    d = x.shape[-1]
+    rows = x.size // d
+    assert d % G == 0
+    codes = np.empty(x.shape, np.uint8)
+    scale = np.empty(x.shape[:-1] + (d // G,), np.uint16)
+    zero = np.empty_like(scale)
+    lib().xqo_quantize_rows(_p(x), C.c_int64(rows), C.c_int(d), C.c_int(G), C.c_int(bits),
+                            _p(codes), _p(scale), _p(zero))
+    return codes, scale, zero
+
+
+def pack_rows(codes, bits):
+    codes = _c(codes, np.uint8)
+    d = codes.shape[-1]
+    rows = codes.size // d
+    assert (d * bits) % 8 == 0
+    packed = np.empty(codes.shape[:-1] + (d * bits // 8,), np.uint8)
+    lib().xqo_pack_rows(_p(codes), C.c_int64(rows), C.c_int(d), C.c_int(bits), _p(packed))
+    return packed
+
+
+def unpack_rows(packed, d, bits):
+    packed = _c(packed, np.uint8)
+    rb = packed.shape[-1]
+    assert rb == d * bits // 8
+    rows = packed.size // rb
+    codes = np.empty(packed.shape[:-1] + (d,), np.uint8)
+    lib().xqo_unpack_rows(_p(packed), C.c_int64(rows), C.c_int(d), C.c_int(bits), _p(codes))
+    return codes
+
+
+def dequantize_rows(codes, scale, zero, G):
+    codes = _c(codes, np.uint8)
+    scale = _c(scale, np.uint16)
+    zero = _c(zero, np.uint16)
+    d = codes.shape[-1]
+    rows = codes.size // d
+    out = np.empty(codes.shape, np.float32)
+    lib().xqo_dequantize_rows(_p(codes), _p(scale), _p(zero), C.c_int64(rows), C.c_int(d),
+                              C.c_int(G), _p(out))
+    return out
+
+
+def cl_delta_rows(x_bf16, acc_bf16):
+    x = _c(x_bf16, np.uint16)
+    a = _c(acc_bf16, np.uint16)
+    assert x.shape == a.shape
+    out = np.empty(x.shape, np.float32)
+    lib().xqo_cl_delta_rows(_p(x), _p(a), C.c_int64(x.size), _p(out))
+    return out
+
+
+def cl_accumulate_rows(acc_bf16, codes, scale, zero, G, init):
+    """In place on acc_bf16 (uint16, C-contiguous)."""
+    assert acc_bf16.dtype == np.uint16 and acc_bf16.flags.c_contiguous
+    codes = _c(codes, np.uint8)
+    scale = _c(scale, np.uint16)
+    zero = _c(zero, np.uint16)
+    d = codes.shape[-1]
+    rows = codes.size // d
+    assert acc_bf16.size == codes.size
+    lib().xqo_cl_accumulate_rows(_p(acc_bf16), _p(codes), _p(scale), _p(zero), C.c_int64(rows),
+                                 C.c_int(d), C.c_int(G), C.c_int(1 if init else 0))
+    return acc_bf16
+
+
+def remat_head(xhat_f32, W_bf16, col0, hd):
+    x = _c(xhat_f32, np.float32)
+    W = _c(W_bf16, np.uint16)
+    L, d = x.shape
+    assert W.shape[0] == d
+    out = np.empty((L, hd), np.float64)
+    lib().xqo_remat_head(_p(x), _p(W), C.c_int(L), C.c_int(d), C.c_int(W.shape[1]),
+                         C.c_int(col0), C.c_int(hd), _p(out))
+    return out
+
+
+def attention(q_bf16, K, V, softmax_scale):
+    q = _c(q_bf16, np.uint16)
+    K = _c(K, np.float64)
+    V = _c(V, np.float64)
+    L, hd = K.shape
+    out = np.empty(hd, np.float32)
+    lib().xqo_attention(_p(q), _p(K), _p(V), C.c_int(L), C.c_int(hd),
+                        C.c_double(softmax_scale), _p(out))
+    return out
+
+
+def remat_attn_pairs(*, q_bf16, Wk, Wv, Hq, Hkv, hd, softmax_scale, lens, pairs,
+                     packed=None, scale=None, zero=None, G=0, bits=0, acc_bf16=None):
+    """Attention output [npairs][hd] fp32 for the listed (b, q-head) pairs.
+
+    Either (packed, scale, zero, G, bits) -- the X cache, layouts [B][cap][...] --
+    or acc_bf16 [B][cap][d] -- the cross-layer accumulator.
+    """
+    q = _c(q_bf16, np.uint16)
+    Wk = _c(Wk, np.uint16)
+    Wv = _c(Wv, np.uint16)
+    d = Wk.shape[0]
+    lens = _c(np.asarray(lens, np.int32), np.int32)
+    pb = _c(np.asarray([p[0] for p in pairs], np.int32), np.int32)
+    ph = _c(np.asarray([p[1] for p in pairs], np.int32), np.int32)
+    if packed is not None:
+        packed = _c(packed, np.uint8)
+        scale = _c(scale, np.uint16)
+        zero = _c(zero, np.uint16)
+        cap = packed.shape[1]
+        assert acc_bf16 is None
+    else:
+        acc_bf16 = _c(acc_bf16, np.uint16)
+        cap = acc_bf16.shape[1]
+        G, bits = d, 16
+    out = np.empty((len(pairs), hd), np.float32)
+    lib().xqo_remat_attn_pairs(_p(packed), _p(scale), _p(zero), _p(acc_bf16), C.c_int(cap),
+                               C.c_int(d), C.c_int(G), C.c_int(bits), _p(q), _p(Wk), _p(Wv),
+                               C.c_int(Hq), C.c_int(Hkv), C.c_int(hd),
+                               C.c_double(softmax_scale), _p(lens), _p(pb), _p(ph),
+                               C.c_int(len(pairs)), _p(out))
+    return out
