@@ -1,0 +1,152 @@
+/*
+ * libxquant -- XQuant / XQuant-CL decode hot path for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer is caller-owned memory; "dev" marks device (HBM)
+ * pointers, "host" marks host pointers.  The library allocates nothing, keeps no
+ * state between calls and never synchronises with the host: all work is enqueued
+ * on the HIP stream passed in (a hipStream_t cast to void*, NULL = the default
+ * stream) and results are valid once the caller has synchronised that stream.
+ * Functions return an xq_status_t; nothing throws or aborts across this
+ * boundary.  Argument errors are detected on the host before anything is
+ * launched.  Device pointers must be 16-byte aligned.  Non-finite inputs are
+ * outside the contract.
+ *
+ * Method (arxiv 2508.10395): instead of a K/V cache, cache the post-norm layer
+ * input X quantised to a few bits per element (Sec. 3.1), or, for XQuant-CL,
+ * the quantised differences of X between successive layers summed into a running
+ * accumulator (Sec. 3.2); at attention time rematerialise K = X^ Wk and
+ * V = X^ Wv on the fly (Sec. 3.1, cost model in Sec. 3.4) and attend to them.
+ *
+ * Storage format of a quantised cache (one tensor per layer; Sec. 4 setup:
+ * uniform asymmetric quantisation, one scale and one zero-point per group of
+ * `group` consecutive hidden channels of one token, 16 bits each -- the sizes in
+ * Tables 1 and 4 imply 32 metadata bits per group):
+ *   codes [B][cap][d*bits/8]  each token row is one little-endian bit string,
+ *                             code j at bits [j*bits, (j+1)*bits)
+ *   scale [B][cap][d/group]   bf16 bit patterns
+ *   zero  [B][cap][d/group]   bf16 bit patterns (zero-point = group minimum)
+ *   x^[j] = code[j]*scale + zero            (one fp32 fused multiply-add)
+ * Quantiser: zero = bf16(min), scale = bf16((max-min)/(2^bits-1)), both
+ * round-to-nearest-even; code = clamp(rint((x-zero)/scale), 0, 2^bits-1) in fp32
+ * with round-half-to-even, all codes 0 when the stored scale is 0; a zero-point
+ * equal to -0 is stored as +0.
+ */
+#ifndef XQUANT_H
+#define XQUANT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    XQ_OK = 0,
+    XQ_ERR_INVALID_ARG = -1,  /* NULL/misaligned pointer, inconsistent sizes, row range outside the cache */
+    XQ_ERR_UNSUPPORTED = -2,  /* a shape or format this build has no kernel for */
+    XQ_ERR_WORKSPACE = -3,    /* workspace / output buffer smaller than the matching *_bytes query */
+    XQ_ERR_HIP = -4           /* the HIP runtime refused a launch or a copy */
+} xq_status_t;
+
+#define XQ_MAX_BATCH 128      /* largest B any call accepts */
+
+/* Quantisation format: hidden size d, group size (64 or 128, must divide d), bits in {2,3,4,8}. */
+typedef struct { int32_t d, group, bits; } xq_qfmt_t;
+
+/* A view of a caller-owned quantised cache (layout above).  cap = rows allocated per sequence. */
+typedef struct {
+    uint8_t  *codes;   /* dev */
+    uint16_t *scale;   /* dev */
+    uint16_t *zero;    /* dev */
+    int32_t   B, cap;
+    xq_qfmt_t fmt;
+} xq_cache_t;
+
+/* Attention geometry.  head_dim must be 128; n_q_heads must be a multiple of n_kv_heads. */
+typedef struct { int32_t n_q_heads, n_kv_heads, head_dim; float softmax_scale; } xq_attn_t;
+
+const char *xq_status_string(xq_status_t s);
+int         xq_version(void);
+
+size_t xq_codes_row_bytes(const xq_qfmt_t *f);   /* d*bits/8, 0 if the format is invalid */
+size_t xq_meta_row_elems(const xq_qfmt_t *f);    /* d/group,  0 if the format is invalid */
+
+/*
+ * Sec. 3.1 (Fig. 2): quantise the layer input of T new tokens per sequence and
+ * append them to the X cache.
+ *   x_bf16  dev  [B][T][d] bf16
+ *   start   host [B]; rows start[b] .. start[b]+T-1 of sequence b are written
+ *           (start[b] >= 0, start[b]+T <= cap)
+ * T = 0 is a no-op.
+ */
+xq_status_t xq_quantize_append(const xq_cache_t *cache, const uint16_t *x_bf16, int32_t T,
+                               const int32_t *start, void *stream);
+
+/*
+ * Sec. 3.2 (Fig. 4, and App. A for T > 1): cross-layer delta of T new tokens,
+ *   dX = X_i - X^_{i-1}   (fp32 difference of two bf16 values),
+ * quantised with the same quantiser and written to rows start[b]..start[b]+T-1 of
+ * this layer's delta cache.
+ *   x_bf16   dev [B][T][d]    true input of layer i
+ *   acc_bf16 dev [B][cap][d]  accumulator holding X^_{i-1}; rows start[b]+t are read
+ */
+xq_status_t xq_cl_delta_quantize(const xq_cache_t *delta, const uint16_t *x_bf16,
+                                 const uint16_t *acc_bf16, int32_t T, const int32_t *start,
+                                 void *stream);
+
+/*
+ * Sec. 3.2: X^_i = X^_{i-1} + dX^_i on the running accumulator, for rows
+ * t < len[b] of every sequence:
+ *   acc = bf16( (init ? +0 : acc) + fma(code, scale, zero) )   fp32 add, RNE to bf16.
+ * init != 0 loads the base layer X_0 (itself a quantised cache) into the accumulator.
+ *   acc_bf16 dev [B][cap][d] (cap and d taken from src), updated in place
+ *   len      host [B], 0 <= len[b] <= cap
+ */
+xq_status_t xq_cl_accumulate(uint16_t *acc_bf16, const xq_cache_t *src, const int32_t *len,
+                             int32_t init, void *stream);
+
+/*
+ * Weight preparation (offline, once per layer; weights are static).  Re-lays
+ * [Wk | Wv] (Sec. 3.3.2 writes the column concatenation W_kv) per KV head into the
+ * fragment order the rematerialisation kernel streams, together with per-group
+ * column sums used to apply the zero-points exactly.
+ *   Wk, Wv   dev [d][n_kv_heads*head_dim] bf16, row-major
+ *   src_bits 2, 3 or 4: prepared for an X cache of that bit width and group size
+ *            `group`; 16: prepared for the bf16 cross-layer accumulator (group ignored)
+ *   out      dev, at least xq_prepared_weights_bytes(...) bytes
+ * xq_prepared_weights_bytes returns 0 for an unsupported combination.
+ */
+size_t      xq_prepared_weights_bytes(const xq_attn_t *a, int32_t d, int32_t group, int32_t src_bits);
+xq_status_t xq_prepare_weights(const xq_attn_t *a, int32_t d, int32_t group, int32_t src_bits,
+                               const uint16_t *Wk, const uint16_t *Wv, void *out, size_t out_bytes,
+                               void *stream);
+
+/*
+ * Sec. 3.1 + Sec. 3.4: one decode step of attention over the cached tokens with
+ * K and V rematerialised on the fly and never written to memory.  For every
+ * sequence b and query head h (KV head h / (n_q_heads/n_kv_heads)):
+ *   K = X^[0:len[b]] Wk_h,  V = X^[0:len[b]] Wv_h,
+ *   out[b][h] = softmax(q[b][h] K^T * softmax_scale) V.
+ * Exactly one source of X^ is given:
+ *   xcache != NULL   an X cache (XQuant), x^ = code*scale + zero;
+ *   acc_bf16 != NULL the cross-layer accumulator [B][cap][d] (XQuant-CL).
+ *   q_bf16   dev [B][n_q_heads][head_dim] bf16
+ *   wprep    dev, from xq_prepare_weights with matching d / group / src_bits
+ *   len      host [B], 1 <= len[b] <= cap
+ *   out      dev [B][n_q_heads][head_dim] fp32
+ *   workspace dev, >= xq_remat_attn_workspace_bytes(a, B, max_b len[b]) bytes, 16-byte aligned;
+ *            holds the per-chunk softmax partials; contents are scratch
+ * B is taken from xcache->B, or passed in `B` when acc_bf16 is the source.
+ */
+size_t      xq_remat_attn_workspace_bytes(const xq_attn_t *a, int32_t B, int32_t max_len);
+xq_status_t xq_remat_attn_decode(const xq_attn_t *a, const uint16_t *q_bf16,
+                                 const xq_cache_t *xcache,
+                                 const uint16_t *acc_bf16, int32_t B, int32_t cap, int32_t d,
+                                 const void *wprep, const int32_t *len, float *out,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XQUANT_H */

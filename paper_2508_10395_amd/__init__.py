@@ -1,0 +1,10 @@
+"""XQuant / XQuant-CL decode hot path for MI355X (gfx950): thin Python binding over
+the C-ABI library libxquant.so (see include/xquant.h).  PyTorch is used only for
+device memory and streams; every step of the path runs in the library's kernels."""
+from .binding import (  # noqa: F401
+    XQCache, XQAttn, XQError, alloc_cache, lib_path, load_library,
+    xq_version, xq_status_string, xq_codes_row_bytes, xq_meta_row_elems,
+    xq_quantize_append, xq_cl_delta_quantize, xq_cl_accumulate,
+    xq_prepared_weights_bytes, xq_prepare_weights,
+    xq_remat_attn_workspace_bytes, xq_remat_attn_decode,
+)

@@ -1,0 +1,231 @@
+"""ctypes binding of libxquant.so: argument marshalling only.
+
+Each function has the name and meaning of the C entry point declared in
+include/xquant.h.  Tensors are torch CUDA (ROCm) tensors; the calls enqueue work on
+torch's current stream and return without synchronising.  There is no fallback:
+if the library is missing or a call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+XQ_MAX_BATCH = 128
+SYMBOLS = [
+    "xq_status_string", "xq_version", "xq_codes_row_bytes", "xq_meta_row_elems",
+    "xq_quantize_append", "xq_cl_delta_quantize", "xq_cl_accumulate",
+    "xq_prepared_weights_bytes", "xq_prepare_weights",
+    "xq_remat_attn_workspace_bytes", "xq_remat_attn_decode",
+]
+
+
+class XQError(RuntimeError):
+    pass
+
+
+class _QFmt(C.Structure):
+    _fields_ = [("d", C.c_int32), ("group", C.c_int32), ("bits", C.c_int32)]
+
+
+class _Cache(C.Structure):
+    _fields_ = [("codes", C.c_void_p), ("scale", C.c_void_p), ("zero", C.c_void_p),
+                ("B", C.c_int32), ("cap", C.c_int32), ("fmt", _QFmt)]
+
+
+class _Attn(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("softmax_scale", C.c_float)]
+
+
+def lib_path():
+    return os.path.join(_HERE, "libxquant.so")
+
+
+def load_library():
+    """Load the built library (build it first if it was never built)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build(force=True)
+    lib = C.CDLL(path)
+    lib.xq_status_string.restype = C.c_char_p
+    lib.xq_status_string.argtypes = [C.c_int]
+    lib.xq_version.restype = C.c_int
+    for name in ("xq_codes_row_bytes", "xq_meta_row_elems"):
+        getattr(lib, name).restype = C.c_size_t
+        getattr(lib, name).argtypes = [C.POINTER(_QFmt)]
+    lib.xq_quantize_append.restype = C.c_int
+    lib.xq_quantize_append.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p]
+    lib.xq_cl_delta_quantize.restype = C.c_int
+    lib.xq_cl_delta_quantize.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_int32,
+                                         C.POINTER(C.c_int32), C.c_void_p]
+    lib.xq_cl_accumulate.restype = C.c_int
+    lib.xq_cl_accumulate.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(C.c_int32), C.c_int32, C.c_void_p]
+    lib.xq_prepared_weights_bytes.restype = C.c_size_t
+    lib.xq_prepared_weights_bytes.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32]
+    lib.xq_prepare_weights.restype = C.c_int
+    lib.xq_prepare_weights.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xq_remat_attn_workspace_bytes.restype = C.c_size_t
+    lib.xq_remat_attn_workspace_bytes.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32]
+    lib.xq_remat_attn_decode.restype = C.c_int
+    lib.xq_remat_attn_decode.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
+                                         C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                         C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_size_t,
+                                         C.c_void_p]
+    _LIB = lib
+    return lib
+
+
+@dataclass
+class XQCache:
+    """Caller-owned quantised cache: codes u8 [B][cap][d*bits/8], scale/zero bf16 [B][cap][d/group]."""
+    codes: torch.Tensor
+    scale: torch.Tensor
+    zero: torch.Tensor
+    B: int
+    cap: int
+    d: int
+    group: int
+    bits: int
+
+    def c_struct(self):
+        return _Cache(self.codes.data_ptr(), self.scale.data_ptr(), self.zero.data_ptr(),
+                      self.B, self.cap, _QFmt(self.d, self.group, self.bits))
+
+
+@dataclass
+class XQAttn:
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    softmax_scale: float
+
+    def c_struct(self):
+        return _Attn(self.n_q_heads, self.n_kv_heads, self.head_dim, self.softmax_scale)
+
+
+def alloc_cache(B, cap, d, group, bits, device="cuda"):
+    rb = d * bits // 8
+    return XQCache(torch.zeros((B, cap, rb), dtype=torch.uint8, device=device),
+                   torch.zeros((B, cap, d // group), dtype=torch.bfloat16, device=device),
+                   torch.zeros((B, cap, d // group), dtype=torch.bfloat16, device=device),
+                   B, cap, d, group, bits)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status, what):
+    if status != 0:
+        msg = load_library().xq_status_string(status).decode()
+        raise XQError(f"{what}: {msg} ({status})")
+
+
+def _i32(vals, n):
+    vals = [int(v) for v in vals]
+    if len(vals) != n:
+        raise XQError(f"expected {n} per-sequence integers, got {len(vals)}")
+    return (C.c_int32 * n)(*vals)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+def xq_version():
+    return load_library().xq_version()
+
+
+def xq_status_string(status):
+    return load_library().xq_status_string(status).decode()
+
+
+def xq_codes_row_bytes(d, group, bits):
+    return load_library().xq_codes_row_bytes(C.byref(_QFmt(d, group, bits)))
+
+
+def xq_meta_row_elems(d, group, bits):
+    return load_library().xq_meta_row_elems(C.byref(_QFmt(d, group, bits)))
+
+
+def xq_quantize_append(cache, x_bf16, start):
+    """x_bf16 [B][T][d] bf16; rows start[b]..start[b]+T-1 of the cache are written."""
+    assert x_bf16.dtype == torch.bfloat16 and x_bf16.is_contiguous() and x_bf16.dim() == 3
+    T = x_bf16.shape[1]
+    cs = cache.c_struct()
+    _check(load_library().xq_quantize_append(C.byref(cs), _ptr(x_bf16), T, _i32(start, cache.B), _stream()),
+           "xq_quantize_append")
+
+
+def xq_cl_delta_quantize(delta, x_bf16, acc_bf16, start):
+    assert x_bf16.dtype == torch.bfloat16 and x_bf16.is_contiguous() and x_bf16.dim() == 3
+    assert acc_bf16.dtype == torch.bfloat16 and acc_bf16.is_contiguous()
+    T = x_bf16.shape[1]
+    cs = delta.c_struct()
+    _check(load_library().xq_cl_delta_quantize(C.byref(cs), _ptr(x_bf16), _ptr(acc_bf16), T,
+                                               _i32(start, delta.B), _stream()), "xq_cl_delta_quantize")
+
+
+def xq_cl_accumulate(acc_bf16, src, lens, init):
+    assert acc_bf16.dtype == torch.bfloat16 and acc_bf16.is_contiguous()
+    cs = src.c_struct()
+    _check(load_library().xq_cl_accumulate(_ptr(acc_bf16), C.byref(cs), _i32(lens, src.B),
+                                           1 if init else 0, _stream()), "xq_cl_accumulate")
+
+
+def xq_prepared_weights_bytes(attn, d, group, src_bits):
+    a = attn.c_struct()
+    return load_library().xq_prepared_weights_bytes(C.byref(a), d, group, src_bits)
+
+
+def xq_prepare_weights(attn, d, group, src_bits, Wk, Wv, out=None):
+    """Returns the prepared-weights buffer (uint8 tensor) for xq_remat_attn_decode."""
+    assert Wk.dtype == torch.bfloat16 and Wv.dtype == torch.bfloat16
+    assert Wk.is_contiguous() and Wv.is_contiguous()
+    nbytes = xq_prepared_weights_bytes(attn, d, group, src_bits)
+    if nbytes == 0:
+        raise XQError("xq_prepare_weights: unsupported combination")
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=Wk.device)
+    a = attn.c_struct()
+    _check(load_library().xq_prepare_weights(C.byref(a), d, group, src_bits, _ptr(Wk), _ptr(Wv), _ptr(out),
+                                             out.numel(), _stream()), "xq_prepare_weights")
+    return out
+
+
+def xq_remat_attn_workspace_bytes(attn, B, max_len):
+    a = attn.c_struct()
+    return load_library().xq_remat_attn_workspace_bytes(C.byref(a), B, max_len)
+
+
+def xq_remat_attn_decode(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=None, out=None, workspace=None):
+    """Attention output fp32 [B][Hq][head_dim] over the first lens[b] cached rows."""
+    assert q_bf16.dtype == torch.bfloat16 and q_bf16.is_contiguous()
+    if xcache is not None:
+        B, cap, d = xcache.B, xcache.cap, xcache.d
+        cs = xcache.c_struct()
+        cptr = C.byref(cs)
+    else:
+        assert acc_bf16.dtype == torch.bfloat16 and acc_bf16.is_contiguous() and acc_bf16.dim() == 3
+        B, cap, d = acc_bf16.shape
+        cptr = None
+    lens = [int(v) for v in lens]
+    a = attn.c_struct()
+    need = xq_remat_attn_workspace_bytes(attn, B, max(lens) if lens else 1)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q_bf16.device)
+    if out is None:
+        out = torch.empty((B, attn.n_q_heads, attn.head_dim), dtype=torch.float32, device=q_bf16.device)
+    _check(load_library().xq_remat_attn_decode(C.byref(a), _ptr(q_bf16), cptr, _ptr(acc_bf16), B, cap, d,
+                                               _ptr(wprep), _i32(lens, B), _ptr(out), _ptr(workspace),
+                                               workspace.numel(), _stream()), "xq_remat_attn_decode")
+    return out

@@ -1,0 +1,194 @@
+// C ABI of libxquant: argument validation on the host, then dispatch to the kernels.
+#include "common.hpp"
+#include "remat_layout.hpp"
+
+namespace xq {
+
+struct RematParams;   // defined in remat_attn.hip; re-declared field-for-field below via the builder
+
+hipError_t run_quantize_append(const xq_cache_t* c, const uint16_t* x, const uint16_t* acc, int T,
+                               const BatchI32& start, hipStream_t s);
+hipError_t run_cl_accumulate(uint16_t* acc, const xq_cache_t* c, const BatchI32& len, int max_len,
+                             bool init, hipStream_t s);
+hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, void* out,
+                               hipStream_t s);
+hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
+                                 const uint16_t* acc, int B, int cap, int d, const void* wprep,
+                                 const BatchI32& len, int max_len, float* out, void* ws, hipStream_t s);
+
+static bool fmt_ok(const xq_qfmt_t& f)
+{
+    const bool bits_ok = f.bits == 2 || f.bits == 3 || f.bits == 4 || f.bits == 8;
+    const bool group_ok = f.group == 64 || f.group == 128;
+    return bits_ok && group_ok && f.d > 0 && f.d % 128 == 0;
+}
+
+static xq_status_t check_cache(const xq_cache_t* c)
+{
+    if (!c || !c->codes || !c->scale || !c->zero) return XQ_ERR_INVALID_ARG;
+    if (c->B < 1 || c->cap < 1) return XQ_ERR_INVALID_ARG;
+    if (c->B > XQ_MAX_BATCH) return XQ_ERR_UNSUPPORTED;
+    if (c->fmt.d <= 0 || c->fmt.group <= 0 || c->fmt.d % c->fmt.group != 0) return XQ_ERR_INVALID_ARG;
+    if (!fmt_ok(c->fmt)) return XQ_ERR_UNSUPPORTED;
+    if (!aligned16(c->codes) || !aligned16(c->scale) || !aligned16(c->zero)) return XQ_ERR_INVALID_ARG;
+    return XQ_OK;
+}
+
+static xq_status_t check_attn(const xq_attn_t* a)
+{
+    if (!a) return XQ_ERR_INVALID_ARG;
+    if (a->n_q_heads < 1 || a->n_kv_heads < 1 || a->n_q_heads % a->n_kv_heads != 0) return XQ_ERR_INVALID_ARG;
+    if (a->head_dim != 128) return XQ_ERR_UNSUPPORTED;
+    if (a->n_q_heads / a->n_kv_heads > 16) return XQ_ERR_UNSUPPORTED;
+    return XQ_OK;
+}
+
+static bool wprep_combo_ok(int d, int group, int src_bits)
+{
+    if (d <= 0 || d % 128 != 0) return false;
+    if (src_bits == 16) return true;
+    return (src_bits == 2 || src_bits == 3 || src_bits == 4) && (group == 64 || group == 128);
+}
+
+}  // namespace xq
+
+using namespace xq;
+
+extern "C" {
+
+const char* xq_status_string(xq_status_t s)
+{
+    switch (s) {
+        case XQ_OK: return "ok";
+        case XQ_ERR_INVALID_ARG: return "invalid argument";
+        case XQ_ERR_UNSUPPORTED: return "unsupported shape or format";
+        case XQ_ERR_WORKSPACE: return "workspace or output buffer too small";
+        case XQ_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+int xq_version(void) { return 100; }
+
+size_t xq_codes_row_bytes(const xq_qfmt_t* f)
+{
+    if (!f || f->d <= 0 || f->bits <= 0 || (f->d * f->bits) % 8 != 0) return 0;
+    return (size_t)f->d * f->bits / 8;
+}
+
+size_t xq_meta_row_elems(const xq_qfmt_t* f)
+{
+    if (!f || f->d <= 0 || f->group <= 0 || f->d % f->group != 0) return 0;
+    return (size_t)f->d / f->group;
+}
+
+static xq_status_t quantize_common(const xq_cache_t* cache, const uint16_t* x, const uint16_t* acc,
+                                   bool need_acc, int32_t T, const int32_t* start, void* stream)
+{
+    xq_status_t st = check_cache(cache);
+    if (st != XQ_OK) return st;
+    if (!start || T < 0) return XQ_ERR_INVALID_ARG;
+    if (T > 0 && (!x || !aligned16(x))) return XQ_ERR_INVALID_ARG;   // no rows: x is not read
+    if (T > 0 && need_acc && (!acc || !aligned16(acc))) return XQ_ERR_INVALID_ARG;
+    BatchI32 sv{};
+    for (int b = 0; b < cache->B; ++b) {
+        if (start[b] < 0 || (long long)start[b] + T > cache->cap) return XQ_ERR_INVALID_ARG;
+        sv.v[b] = start[b];
+    }
+    if (T == 0) return XQ_OK;
+    hipError_t e = run_quantize_append(cache, x, need_acc ? acc : nullptr, T, sv, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+xq_status_t xq_quantize_append(const xq_cache_t* cache, const uint16_t* x_bf16, int32_t T,
+                               const int32_t* start, void* stream)
+{
+    return quantize_common(cache, x_bf16, nullptr, false, T, start, stream);
+}
+
+xq_status_t xq_cl_delta_quantize(const xq_cache_t* delta, const uint16_t* x_bf16, const uint16_t* acc_bf16,
+                                 int32_t T, const int32_t* start, void* stream)
+{
+    return quantize_common(delta, x_bf16, acc_bf16, true, T, start, stream);
+}
+
+xq_status_t xq_cl_accumulate(uint16_t* acc_bf16, const xq_cache_t* src, const int32_t* len, int32_t init,
+                             void* stream)
+{
+    xq_status_t st = check_cache(src);
+    if (st != XQ_OK) return st;
+    if (!acc_bf16 || !len || !aligned16(acc_bf16)) return XQ_ERR_INVALID_ARG;
+    BatchI32 lv{};
+    int max_len = 0;
+    for (int b = 0; b < src->B; ++b) {
+        if (len[b] < 0 || len[b] > src->cap) return XQ_ERR_INVALID_ARG;
+        lv.v[b] = len[b];
+        if (len[b] > max_len) max_len = len[b];
+    }
+    hipError_t e = run_cl_accumulate(acc_bf16, src, lv, max_len, init != 0, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+size_t xq_prepared_weights_bytes(const xq_attn_t* a, int32_t d, int32_t group, int32_t src_bits)
+{
+    if (check_attn(a) != XQ_OK || !wprep_combo_ok(d, group, src_bits)) return 0;
+    return make_wprep_layout(d, src_bits == 16 ? 128 : group, src_bits, a->n_kv_heads).total_bytes;
+}
+
+xq_status_t xq_prepare_weights(const xq_attn_t* a, int32_t d, int32_t group, int32_t src_bits,
+                               const uint16_t* Wk, const uint16_t* Wv, void* out, size_t out_bytes,
+                               void* stream)
+{
+    xq_status_t st = check_attn(a);
+    if (st != XQ_OK) return st;
+    if (!Wk || !Wv || !out || !aligned16(Wk) || !aligned16(Wv) || !aligned16(out)) return XQ_ERR_INVALID_ARG;
+    if (d <= 0) return XQ_ERR_INVALID_ARG;
+    if (!wprep_combo_ok(d, group, src_bits)) return XQ_ERR_UNSUPPORTED;
+    const WPrepLayout L = make_wprep_layout(d, src_bits == 16 ? 128 : group, src_bits, a->n_kv_heads);
+    if (out_bytes < L.total_bytes) return XQ_ERR_WORKSPACE;
+    hipError_t e = run_prepare_weights(L, Wk, Wv, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+size_t xq_remat_attn_workspace_bytes(const xq_attn_t* a, int32_t B, int32_t max_len)
+{
+    if (check_attn(a) != XQ_OK || B < 1 || max_len < 1) return 0;
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    const size_t chunks = tiles * (TILE_TOKENS / CHUNK_TOKENS);
+    return (size_t)B * a->n_q_heads * chunks * (128 + 2) * sizeof(float);
+}
+
+xq_status_t xq_remat_attn_decode(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* xcache,
+                                 const uint16_t* acc_bf16, int32_t B, int32_t cap, int32_t d,
+                                 const void* wprep, const int32_t* len, float* out, void* workspace,
+                                 size_t workspace_bytes, void* stream)
+{
+    xq_status_t st = check_attn(a);
+    if (st != XQ_OK) return st;
+    if ((xcache != nullptr) == (acc_bf16 != nullptr)) return XQ_ERR_INVALID_ARG;
+    if (!q_bf16 || !wprep || !len || !out || !workspace) return XQ_ERR_INVALID_ARG;
+    if (!aligned16(q_bf16) || !aligned16(wprep) || !aligned16(out) || !aligned16(workspace))
+        return XQ_ERR_INVALID_ARG;
+    if (xcache) {
+        st = check_cache(xcache);
+        if (st != XQ_OK) return st;
+        if (xcache->fmt.bits == 8) return XQ_ERR_UNSUPPORTED;
+        B = xcache->B; cap = xcache->cap; d = xcache->fmt.d;
+    } else {
+        if (!aligned16(acc_bf16) || B < 1 || cap < 1 || d <= 0) return XQ_ERR_INVALID_ARG;
+        if (B > XQ_MAX_BATCH || d % 128 != 0) return XQ_ERR_UNSUPPORTED;
+    }
+    BatchI32 lv{};
+    int max_len = 0;
+    for (int b = 0; b < B; ++b) {
+        if (len[b] < 1 || len[b] > cap) return XQ_ERR_INVALID_ARG;
+        lv.v[b] = len[b];
+        if (len[b] > max_len) max_len = len[b];
+    }
+    if (workspace_bytes < xq_remat_attn_workspace_bytes(a, B, max_len)) return XQ_ERR_WORKSPACE;
+    hipError_t e = run_remat_attn_decode(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, lv, max_len, out,
+                                         workspace, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,148 @@
+// Offline weight preparation for the rematerialisation kernel (weights are static;
+// run once per layer).  Re-lays [Wk_h | Wv_h] (Sec. 3.1 / the W_kv concatenation of
+// Sec. 3.3.2 in arxiv 2508.10395) into the slab stream described in
+// remat_layout.hpp and appends the per-group column sums the kernel needs to apply
+// zero-points and the unpacker's "+1" offset exactly.
+#include "common.hpp"
+#include "remat_layout.hpp"
+#include "unpack.hpp"
+
+namespace xq {
+
+struct PrepArgs {
+    const uint16_t* Wk;
+    const uint16_t* Wv;
+    uint8_t* out;
+    float* colsum;   // [2][Hkv][ng][256]: plain sums, then sums of the scaled rows
+    int d, G, bits, Hkv, ncols;
+    int n_main_slabs, ng, ng_pad, n_corr_slabs;
+    long long head_bytes;
+    UnpackTable tab;
+};
+
+__device__ __forceinline__ float wval(const PrepArgs& a, int h, int c, int n)
+{
+    const uint16_t* W = n < 128 ? a.Wk : a.Wv;
+    return bf16_bits_to_f32(W[(long long)c * a.ncols + h * 128 + (n & 127)]);
+}
+
+// code position (0..31 inside its unit) of hidden channel c
+__device__ __forceinline__ int code_pos(const PrepArgs& a, int c) { return (c % (a.G / 2)) & 31; }
+
+__global__ __launch_bounds__(256) void colsum_kernel(PrepArgs a)
+{
+    const int n = threadIdx.x;
+    const int g = blockIdx.x, h = blockIdx.y;
+    float s = 0.0f, sp = 0.0f;
+    for (int k = 0; k < a.G; ++k) {
+        const int c = g * a.G + k;
+        const float w = wval(a, h, c, n);
+        s += w;
+        sp += ldexpf(w, a.tab.wexp_of_code[code_pos(a, c)]);
+    }
+    const long long idx = ((long long)h * a.ng + g) * 256 + n;
+    a.colsum[idx] = s;
+    a.colsum[(long long)a.Hkv * a.ng * 256 + idx] = sp;
+}
+
+// one thread = one lane's 16 bytes of one fragment; grid (slab, head), block 512 x 8 k-steps... see launch
+__global__ __launch_bounds__(256) void pack_main_kernel(PrepArgs a)
+{
+    const int s = blockIdx.x, h = blockIdx.y;
+    const bool dense = a.bits == 16;
+    const int ksg_n = a.G / 16;
+    for (int f = threadIdx.x; f < SLAB_KSTEPS * 8 * 64; f += blockDim.x) {
+        const int lane = f & 63, nb = (f >> 6) & 7, ks = f >> 9;
+        const int half = lane >> 5, n = nb * 32 + (lane & 31);
+        uint32_t v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int c, e = 0;
+            if (dense) {
+                c = s * 128 + half * 64 + ks * 8 + i;
+            } else {
+                const int gi = ks / ksg_n, ksg = ks % ksg_n;
+                const int u = ksg >> 2, j = ksg & 3;
+                const int p = a.tab.code_of_slot[j][i];
+                c = s * 128 + gi * a.G + half * (a.G / 2) + u * 32 + p;
+                e = a.tab.wexp_of_code[p];
+            }
+            v[i] = f32_to_bf16_rne(ldexpf(wval(a, h, c, n), e));   // exact: power-of-two scaling
+        }
+        uint4 o;
+        o.x = v[0] | (v[1] << 16); o.y = v[2] | (v[3] << 16);
+        o.z = v[4] | (v[5] << 16); o.w = v[6] | (v[7] << 16);
+        *reinterpret_cast<uint4*>(a.out + (long long)h * a.head_bytes + (long long)s * SLAB_BYTES + (long long)f * 16) = o;
+    }
+}
+
+__device__ __forceinline__ uint32_t split_part(float x, int part)
+{
+    uint32_t hi = f32_to_bf16_rne(x);
+    if (part == 0) return hi;
+    float r1 = x - bf16_bits_to_f32(hi);
+    uint32_t mid = f32_to_bf16_rne(r1);
+    if (part == 1) return mid;
+    float r2 = r1 - bf16_bits_to_f32(mid);
+    return f32_to_bf16_rne(r2);
+}
+
+__global__ __launch_bounds__(256) void pack_corr_kernel(PrepArgs a)
+{
+    const int cs = blockIdx.x, h = blockIdx.y;
+    for (int f = threadIdx.x; f < SLAB_KSTEPS * 8 * 64; f += blockDim.x) {
+        const int lane = f & 63, nb = (f >> 6) & 7, ks = f >> 9;
+        const int half = lane >> 5, n = nb * 32 + (lane & 31);
+        uint32_t v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int kappa = (cs * SLAB_KSTEPS + ks) * 16 + half * 8 + i;
+            const int term = kappa / a.ng_pad, g = kappa % a.ng_pad;
+            uint32_t bits = 0;
+            if (term < N_CORR_TERMS && g < a.ng) {
+                const long long idx = ((long long)h * a.ng + g) * 256 + n;
+                if (term < 2) bits = split_part(a.colsum[idx], term);
+                else bits = split_part(a.colsum[(long long)a.Hkv * a.ng * 256 + idx], term - 2);
+            }
+            v[i] = bits;
+        }
+        uint4 o;
+        o.x = v[0] | (v[1] << 16); o.y = v[2] | (v[3] << 16);
+        o.z = v[4] | (v[5] << 16); o.w = v[6] | (v[7] << 16);
+        *reinterpret_cast<uint4*>(a.out + (long long)h * a.head_bytes +
+                                  (long long)(a.n_main_slabs + cs) * SLAB_BYTES + (long long)f * 16) = o;
+    }
+}
+
+bool unpack_table_for(int bits, UnpackTable* t)
+{
+    switch (bits) {
+        case 2: *t = build_unpack_table<2>(); break;
+        case 3: *t = build_unpack_table<3>(); break;
+        case 4: *t = build_unpack_table<4>(); break;
+        case 16: *t = UnpackTable{}; t->valid = 1; break;
+        default: return false;
+    }
+    return t->valid != 0;
+}
+
+hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, void* out,
+                               hipStream_t s)
+{
+    PrepArgs a{};
+    a.Wk = Wk; a.Wv = Wv;
+    a.out = static_cast<uint8_t*>(out);
+    a.colsum = reinterpret_cast<float*>(a.out + L.stream_bytes);
+    a.d = L.d; a.G = L.G; a.bits = L.bits; a.Hkv = L.Hkv; a.ncols = L.Hkv * 128;
+    a.n_main_slabs = L.n_main_slabs; a.ng = L.ng; a.ng_pad = L.ng_pad; a.n_corr_slabs = L.n_corr_slabs;
+    a.head_bytes = (long long)L.head_bytes;
+    if (!unpack_table_for(L.bits, &a.tab)) return hipErrorInvalidValue;
+    pack_main_kernel<<<dim3(L.n_main_slabs, L.Hkv), dim3(256), 0, s>>>(a);
+    if (L.bits != 16) {
+        colsum_kernel<<<dim3(L.ng, L.Hkv), dim3(256), 0, s>>>(a);
+        pack_corr_kernel<<<dim3(L.n_corr_slabs, L.Hkv), dim3(256), 0, s>>>(a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace xq

@@ -1,0 +1,58 @@
+// Layout of the prepared weight stream consumed by the rematerialisation kernel.
+//
+// Per KV head: (n_main_slabs + n_corr_slabs) slabs of 64 KiB.  A slab is the LDS
+// image of 8 MFMA k-steps (128 contraction indices) x 256 output columns
+// ([Wk_h | Wv_h]):  [k-step 8][column block 8][lane 64][8 bf16], i.e. one 1 KiB
+// 32x16 operand fragment per (k-step, column block), lane-major, so that the copy
+// HBM -> LDS is linear and every lane's ds_read_b128 is conflict-free.
+//
+// Main slab s covers hidden channels [128 s, 128 s + 128).  Lane l feeds row
+// (l % 32) of its column block and, with half = l / 32, the contraction slots
+//   dense source:  channel = 128 s + 64 half + 8 ks + i
+//   coded source:  group gi = ks / (G/16); unit u, k-step j inside the unit;
+//                  channel = 128 s + G gi + (G/2) half + 32 u + code_of_slot[j][i],
+//                  value scaled by 2^wexp_of_code (see unpack.hpp).
+// Correction slabs (coded sources only) hold, for contraction index
+// kappa = 16 kk + 8 half + i, term = kappa / ng_pad, group g = kappa % ng_pad:
+//   term 0,1: bf16 hi, lo parts of S_g[n]  = sum of the group's weight rows
+//   term 2..4: bf16 hi, mid, lo parts of S'_g[n] = sum of the scaled weight rows
+// against which the kernel multiplies the zero-points and minus the scales.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+namespace xq {
+
+constexpr int SLAB_KSTEPS = 8;
+constexpr int SLAB_BYTES = 65536;
+constexpr int N_CORR_TERMS = 5;
+constexpr int TILE_TOKENS = 256;     // tokens per workgroup
+constexpr int CHUNK_TOKENS = 64;     // tokens per wave = one softmax partial
+
+struct WPrepLayout {
+    int d, G, bits, Hkv;
+    int n_main_slabs, ng, ng_pad, n_corr_ksteps, n_corr_slabs;
+    size_t head_bytes, stream_bytes, colsum_bytes, total_bytes;
+};
+
+inline WPrepLayout make_wprep_layout(int d, int G, int bits, int Hkv)
+{
+    WPrepLayout L{};
+    L.d = d; L.G = G; L.bits = bits; L.Hkv = Hkv;
+    L.n_main_slabs = d / 128;
+    if (bits == 16) {
+        L.ng = L.ng_pad = L.n_corr_ksteps = L.n_corr_slabs = 0;
+    } else {
+        L.ng = d / G;
+        L.ng_pad = (L.ng + 7) / 8 * 8;
+        L.n_corr_ksteps = (N_CORR_TERMS * L.ng_pad + 15) / 16;
+        L.n_corr_slabs = (L.n_corr_ksteps + SLAB_KSTEPS - 1) / SLAB_KSTEPS;
+    }
+    L.head_bytes = (size_t)(L.n_main_slabs + L.n_corr_slabs) * SLAB_BYTES;
+    L.stream_bytes = L.head_bytes * Hkv;
+    L.colsum_bytes = (size_t)2 * Hkv * L.ng * 256 * sizeof(float);
+    L.total_bytes = L.stream_bytes + L.colsum_bytes;
+    return L;
+}
+
+}  // namespace xq

@@ -1,0 +1,140 @@
+"""GPU parity: xq_remat_attn_decode (fused dequantise -> remat K,V -> attention) against
+the CPU oracle, within 2e-3 relative error per (sequence, head) and over the whole output."""
+import numpy as np
+import pytest
+import torch
+
+import xq_inputs as xi
+from oracle import xq_oracle as xo
+from tests.util import bits_to_torch, rel_errors, torch_to_bits
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3   # relative error bound on the attention output (bf16 operands, fp32 accumulation)
+
+
+@pytest.fixture(scope="module")
+def xq():
+    import paper_2508_10395_amd as m
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    m.load_library()
+    return m
+
+
+def bf(x):
+    return xi.from_bf16_bits(x)
+
+
+def _check(got, ref, what=""):
+    normwise, maxwise = rel_errors(got, ref)
+    assert np.all(np.isfinite(got)), what
+    assert normwise.max() <= TOL, (what, float(normwise.max()))
+    assert maxwise <= TOL, (what, float(maxwise))
+    return float(normwise.max())
+
+
+def _run_xquant(xq, w, bits, G, lens, pairs=None, x_bits=None, cap=None):
+    """Quantise X with the GPU library, attend with the GPU library, and compare with the
+    oracle attending over the very same cache bytes."""
+    x = xi.gen_x(w) if x_bits is None else x_bits
+    wk, wv = xi.gen_weights(w)
+    q = xi.gen_q(w)
+    cap = w.L if cap is None else cap
+    cache = xq.alloc_cache(w.B, cap, w.d, G, bits)
+    if cap > w.L:   # rows past the data hold junk: they must not be read
+        cache.codes.fill_(0xFF)
+        cache.scale.view(torch.int16).fill_(0x7FC0)     # NaN
+        cache.zero.view(torch.int16).fill_(0x7FC0)
+    xq.xq_quantize_append(cache, bits_to_torch(x), [0] * w.B)
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    wprep = xq.xq_prepare_weights(attn, w.d, G, bits, bits_to_torch(wk), bits_to_torch(wv))
+    out = xq.xq_remat_attn_decode(attn, bits_to_torch(q), wprep, lens, xcache=cache)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    if pairs is None:
+        pairs = [(b, h) for b in range(w.B) for h in range(w.Hq)]
+    ref = xo.remat_attn_pairs(q_bf16=q, Wk=wk, Wv=wv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd,
+                              softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs,
+                              packed=cache.codes.cpu().numpy(), scale=torch_to_bits(cache.scale),
+                              zero=torch_to_bits(cache.zero), G=G, bits=bits)
+    sel = np.array([got[b, h] for b, h in pairs])
+    return _check(sel, ref, w.name)
+
+
+def test_config1_all_heads(xq):
+    _run_xquant(xq, xi.C1, 4, 128, [xi.C1.L])
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("G", [64, 128])
+def test_ragged_lengths_several_tiles(xq, bits, G):
+    """Lengths that end inside a tile, inside a wave's 64 tokens, at 1, and on a tile edge."""
+    w = xi.C2.scaled(B=5, L=600, d=512, Hq=4, Hkv=4, n_outlier=5)
+    _run_xquant(xq, w, bits, G, lens=[600, 257, 64, 1, 512], cap=640)
+
+
+@pytest.mark.parametrize("bits,G", [(2, 64), (3, 128)])
+def test_gqa_heads_share_kv(xq, bits, G):
+    w = xi.C4.scaled(B=2, L=300, d=768, Hq=8, Hkv=2)
+    _run_xquant(xq, w, bits, G, lens=[300, 130])
+
+
+def test_odd_head_count_and_group_count(xq):
+    """Hkv not a multiple of 8 (plain workgroup order) and d/G not a multiple of 8."""
+    w = xi.C2.scaled(B=2, L=200, d=384, Hq=6, Hkv=3, n_outlier=3)
+    _run_xquant(xq, w, 3, 128, lens=[200, 77])
+
+
+def test_constant_groups_and_wide_scale_range(xq):
+    """Groups with zero scale (constant), groups 1000x larger than their neighbours."""
+    w = xi.C2.scaled(B=1, L=256, d=512, Hq=2, Hkv=2, n_outlier=0)
+    x = bf(xi.gen_x(w)).copy()
+    x[0, :, 128:256] = 0.5                       # constant group -> scale 0
+    x[0, ::2, 256:384] *= 1000.0                 # huge group on every other token
+    x[0, 1::2, 384:512] *= 1e-3                  # tiny group on the others
+    x[0, 7, :] = -1.25                           # a fully constant token
+    _run_xquant(xq, w, 3, 128, [256], x_bits=xi.to_bf16_bits(x))
+    _run_xquant(xq, w, 4, 64, [256], x_bits=xi.to_bf16_bits(x))
+
+
+def test_dense_accumulator_source(xq):
+    """XQuant-CL mode: the bf16 accumulator is the source of X^."""
+    w = xi.C3.scaled(B=3, L=330, d=512, Hq=4, Hkv=4)
+    acc = xi.gen_x(w)
+    wk, wv = xi.gen_weights(w)
+    q = xi.gen_q(w)
+    lens = [330, 256, 100]
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    wprep = xq.xq_prepare_weights(attn, w.d, 128, 16, bits_to_torch(wk), bits_to_torch(wv))
+    out = xq.xq_remat_attn_decode(attn, bits_to_torch(q), wprep, lens, acc_bf16=bits_to_torch(acc))
+    torch.cuda.synchronize()
+    pairs = [(b, h) for b in range(w.B) for h in range(w.Hq)]
+    ref = xo.remat_attn_pairs(q_bf16=q, Wk=wk, Wv=wv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd,
+                              softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs, acc_bf16=acc)
+    _check(out.cpu().numpy().reshape(-1, w.hd), ref, "dense")
+
+
+def test_determinism_and_independence_of_batch_order(xq):
+    """Same inputs twice -> identical bits; a sequence's output does not depend on its neighbours."""
+    w = xi.C2.scaled(B=2, L=300, d=512, Hq=4, Hkv=4, n_outlier=5)
+    x, (wk, wv), q = xi.gen_x(w), xi.gen_weights(w), xi.gen_q(w)
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    wprep = xq.xq_prepare_weights(attn, w.d, 128, 3, bits_to_torch(wk), bits_to_torch(wv))
+
+    def run(order):
+        cache = xq.alloc_cache(2, w.L, w.d, 128, 3)
+        xq.xq_quantize_append(cache, bits_to_torch(x[order]), [0, 0])
+        return xq.xq_remat_attn_decode(attn, bits_to_torch(q[order]), wprep, [300, 300], xcache=cache).cpu().numpy()
+
+    a, b, c = run([0, 1]), run([0, 1]), run([1, 0])
+    assert np.array_equal(a, b)
+    assert np.array_equal(a[0], c[1]) and np.array_equal(a[1], c[0])
+
+
+def test_full_size_llama2_7b_sampled_pairs(xq):
+    """The benchmark configuration (B=8, L=4096, d=4096, 32 heads, 3-bit): the whole job runs
+    on the GPU, a seeded sample of (sequence, head) pairs is recomputed by the oracle."""
+    w = xi.C2
+    pairs = xi.sample_pairs(w, 8)
+    worst = _run_xquant(xq, w, w.bits, w.G, [w.L] * w.B, pairs=pairs)
+    print(f"c2 sampled pairs: worst norm-wise rel err {worst:.2e}")

@@ -1,0 +1,105 @@
+"""CPU checks of the C-ABI library: it loads, exports every symbol the header
+declares, and rejects bad arguments on the host without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2508_10395_amd as xq
+from paper_2508_10395_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "xquant.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(xq_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = xq.load_library()
+    declared = _declared_symbols()
+    assert len(declared) >= 11
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(B.SYMBOLS) == declared
+    assert xq.xq_version() >= 100
+    assert xq.xq_status_string(0) == "ok" and "argument" in xq.xq_status_string(-1)
+
+
+def test_format_queries():
+    assert xq.xq_codes_row_bytes(4096, 128, 3) == 1536
+    assert xq.xq_codes_row_bytes(4096, 64, 2) == 1024
+    assert xq.xq_meta_row_elems(4096, 64, 2) == 64
+    assert xq.xq_meta_row_elems(4096, 100, 2) == 0
+    a = xq.XQAttn(32, 32, 128, 0.1)
+    assert xq.xq_remat_attn_workspace_bytes(a, 8, 4096) == 8 * 32 * 64 * 130 * 4
+    assert xq.xq_remat_attn_workspace_bytes(a, 8, 4097) == 8 * 32 * 68 * 130 * 4
+    assert xq.xq_prepared_weights_bytes(a, 4096, 128, 3) > 2 * 4096 * 4096 * 2
+    assert xq.xq_prepared_weights_bytes(a, 4096, 128, 5) == 0
+    assert xq.xq_prepared_weights_bytes(xq.XQAttn(32, 32, 64, 0.1), 4096, 128, 3) == 0
+
+
+def _cache(codes=16, scale=16, zero=16, B_=1, cap=8, d=256, group=128, bits=4):
+    return B._Cache(codes, scale, zero, B_, cap, B._QFmt(d, group, bits))
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    lib = xq.load_library()
+    one = (C.c_int32 * 1)(0)
+    x = C.c_void_p(32)
+    st = C.c_void_p(0)
+    INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
+    assert lib.xq_quantize_append(None, x, 1, one, st) == INVALID
+    assert lib.xq_quantize_append(C.byref(_cache(codes=0)), x, 1, one, st) == INVALID
+    assert lib.xq_quantize_append(C.byref(_cache(codes=8)), x, 1, one, st) == INVALID          # misaligned
+    assert lib.xq_quantize_append(C.byref(_cache()), None, 1, one, st) == INVALID
+    assert lib.xq_quantize_append(C.byref(_cache()), x, -1, one, st) == INVALID
+    assert lib.xq_quantize_append(C.byref(_cache()), x, 9, one, st) == INVALID                 # start+T > cap
+    assert lib.xq_quantize_append(C.byref(_cache()), x, 1, (C.c_int32 * 1)(8), st) == INVALID
+    assert lib.xq_quantize_append(C.byref(_cache(bits=5)), x, 1, one, st) == UNSUPPORTED
+    assert lib.xq_quantize_append(C.byref(_cache(group=32)), x, 1, one, st) == UNSUPPORTED
+    assert lib.xq_quantize_append(C.byref(_cache(d=200, group=100)), x, 1, one, st) == UNSUPPORTED
+    assert lib.xq_quantize_append(C.byref(_cache(d=200)), x, 1, one, st) == INVALID            # group does not divide d
+    assert lib.xq_quantize_append(C.byref(_cache(B_=129)), x, 1, one, st) == UNSUPPORTED
+    assert lib.xq_quantize_append(C.byref(_cache()), x, 0, one, st) == 0                       # T = 0: no-op
+    assert lib.xq_quantize_append(C.byref(_cache()), None, 0, one, st) == 0
+    assert lib.xq_cl_delta_quantize(C.byref(_cache()), x, None, 1, one, st) == INVALID
+    assert lib.xq_cl_accumulate(None, C.byref(_cache()), one, 0, st) == INVALID
+    assert lib.xq_cl_accumulate(x, C.byref(_cache()), (C.c_int32 * 1)(9), 0, st) == INVALID    # len > cap
+    assert lib.xq_cl_accumulate(x, C.byref(_cache()), (C.c_int32 * 1)(0), 0, st) == 0          # nothing to do
+
+    a = B._Attn(4, 2, 128, 0.1)
+    bad_hd = B._Attn(4, 2, 64, 0.1)
+    bad_ratio = B._Attn(5, 2, 128, 0.1)
+    assert lib.xq_prepare_weights(C.byref(bad_hd), 256, 128, 4, x, x, x, 1 << 30, st) == UNSUPPORTED
+    assert lib.xq_prepare_weights(C.byref(bad_ratio), 256, 128, 4, x, x, x, 1 << 30, st) == INVALID
+    assert lib.xq_prepare_weights(C.byref(a), 256, 128, 8, x, x, x, 1 << 30, st) == UNSUPPORTED
+    assert lib.xq_prepare_weights(C.byref(a), 256, 128, 4, x, x, x, 16, st) == WORKSPACE
+    cache = _cache()
+    ok_len = (C.c_int32 * 1)(8)
+    args = lambda **kw: dict(dict(a=C.byref(a), q=x, xc=C.byref(cache), acc=None, B=1, cap=8, d=256, w=x,
+                                  len=ok_len, out=x, ws=x, wsb=1 << 30), **kw)
+
+    def call(**kw):
+        k = args(**kw)
+        return lib.xq_remat_attn_decode(k["a"], k["q"], k["xc"], k["acc"], k["B"], k["cap"], k["d"], k["w"],
+                                        k["len"], k["out"], k["ws"], k["wsb"], st)
+
+    assert call(acc=x) == INVALID                       # both sources given
+    assert call(xc=None) == INVALID                     # no source
+    assert call(len=(C.c_int32 * 1)(0)) == INVALID      # empty sequence
+    assert call(len=(C.c_int32 * 1)(9)) == INVALID      # longer than the cache
+    assert call(wsb=64) == WORKSPACE
+    assert call(xc=C.byref(_cache(bits=8))) == UNSUPPORTED
+    assert call(a=C.byref(bad_hd)) == UNSUPPORTED
+    assert call(out=None) == INVALID
+
+
+def test_binding_has_no_cpu_fallback():
+    src = open(os.path.join(ROOT, "paper_2508_10395_amd", "binding.py")).read()
+    assert "oracle" not in src
+    with pytest.raises(OSError):
+        C.CDLL(os.path.join(ROOT, "paper_2508_10395_amd", "does_not_exist.so"))
