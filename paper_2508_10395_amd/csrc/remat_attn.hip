@@ -204,31 +204,39 @@ __global__ __launch_bounds__(512) void remat_attn_kernel(const RematParams p)
 
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds;
 
-    // prologue: slab 0
-    issue_slab(wsrc, lds0, wave, lane);
+    // Workgroups that run side by side on one XCD stream the same head.  Each starts its
+    // contraction at a different slab (the sum over groups is order-free), so that at any
+    // moment they pull different addresses and the requests spread over all L2 channels.
+    const int rot = (int)((blockIdx.x >> 3) % (unsigned)p.n_main_slabs);
+    auto main_slab_id = [&](int it) { const int s = it + rot; return s >= p.n_main_slabs ? s - p.n_main_slabs : s; };
+
+    // prologue: first slab
+    issue_slab(wsrc + (long long)rot * SLAB_BYTES, lds0, wave, lane);
     if constexpr (DENSE) {
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) bd[tb][ks] = reinterpret_cast<const uint4*>(cbase + coff[tb])[ks];
+            for (int ks = 0; ks < 8; ++ks) bd[tb][ks] = reinterpret_cast<const uint4*>(cbase + coff[tb] + rot * 256)[ks];
     } else {
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
             for (int gi = 0; gi < GPS; ++gi) {
-                load_dwords<NDW_G>(cbase + coff[tb] + gi * GROUP_BYTES, &nxt[tb][gi * NDW_G]);
-                sc_nxt[tb][gi] = sbase[moff[tb] + gi];
+                load_dwords<NDW_G>(cbase + coff[tb] + (rot * GPS + gi) * GROUP_BYTES, &nxt[tb][gi * NDW_G]);
+                sc_nxt[tb][gi] = sbase[moff[tb] + rot * GPS + gi];
             }
     }
 
     // ---- main slabs: the d x 256 contraction
-    for (int s = 0; s < p.n_main_slabs; ++s) {
-        // slab s (and this lane's token-side data for it) has landed; everyone is done with slab s-1
+    for (int it = 0; it < p.n_main_slabs; ++it) {
+        // this slab (and this lane's token-side data for it) has landed; everyone is done with the one before
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (s + 1 < n_slabs)
-            issue_slab(wsrc + (long long)(s + 1) * SLAB_BYTES, lds0 + (uint32_t)(((s + 1) & 1) * SLAB_BYTES), wave, lane);
-        const uint8_t* slab = lds + (s & 1) * SLAB_BYTES + (part * 4 * 64 + lane) * 16;
+        const bool more_main = it + 1 < p.n_main_slabs;
+        const int s_next = more_main ? main_slab_id(it + 1) : p.n_main_slabs;   // then the correction slabs
+        if (it + 1 < n_slabs)
+            issue_slab(wsrc + (long long)s_next * SLAB_BYTES, lds0 + (uint32_t)(((it + 1) & 1) * SLAB_BYTES), wave, lane);
+        const uint8_t* slab = lds + (it & 1) * SLAB_BYTES + (part * 4 * 64 + lane) * 16;
 
         if constexpr (!DENSE) {
 #pragma unroll
@@ -238,13 +246,13 @@ __global__ __launch_bounds__(512) void remat_attn_kernel(const RematParams p)
 #pragma unroll
                 for (int gi = 0; gi < GPS; ++gi) sc_cur[tb][gi] = sc_nxt[tb][gi];
             }
-            if (s + 1 < p.n_main_slabs) {
+            if (more_main) {
 #pragma unroll
                 for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
                     for (int gi = 0; gi < GPS; ++gi) {
-                        load_dwords<NDW_G>(cbase + coff[tb] + ((s + 1) * GPS + gi) * GROUP_BYTES, &nxt[tb][gi * NDW_G]);
-                        sc_nxt[tb][gi] = sbase[moff[tb] + (s + 1) * GPS + gi];
+                        load_dwords<NDW_G>(cbase + coff[tb] + (s_next * GPS + gi) * GROUP_BYTES, &nxt[tb][gi * NDW_G]);
+                        sc_nxt[tb][gi] = sbase[moff[tb] + s_next * GPS + gi];
                     }
             }
         }
@@ -258,8 +266,8 @@ __global__ __launch_bounds__(512) void remat_attn_kernel(const RematParams p)
 #pragma unroll
                 for (int tb = 0; tb < 2; ++tb) {
                     bfrag[tb] = __builtin_bit_cast(bf16x8, bd[tb][ks]);
-                    if (s + 1 < p.n_main_slabs)   // refill this ring slot for the next slab
-                        bd[tb][ks] = reinterpret_cast<const uint4*>(cbase + coff[tb] + (s + 1) * 256)[ks];
+                    if (more_main)   // refill this ring slot for the next slab
+                        bd[tb][ks] = reinterpret_cast<const uint4*>(cbase + coff[tb] + s_next * 256)[ks];
                 }
             } else {
                 const int gi = ks / KSG, ksg = ks % KSG;
