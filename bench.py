@@ -67,7 +67,7 @@ def main():
     x_new = x[:, L - 1:L].contiguous()                                     # the decode step's token
     lens = [L] * B
     out = torch.empty((B, Hq, hd), dtype=torch.float32, device=dev)
-    ws = torch.empty(xq.xq_remat_attn_workspace_bytes(attn, B, L), dtype=torch.uint8, device=dev)
+    ws = torch.empty(xq.xq_remat_attn_workspace_bytes(attn, B, L, d, G), dtype=torch.uint8, device=dev)
 
     def step(ev=None):
         xq.xq_quantize_append(cache, x_new, [L - 1] * B)

@@ -135,11 +135,14 @@ xq_status_t xq_prepare_weights(const xq_attn_t *a, int32_t d, int32_t group, int
  *   wprep    dev, from xq_prepare_weights with matching d / group / src_bits
  *   len      host [B], 1 <= len[b] <= cap
  *   out      dev [B][n_q_heads][head_dim] fp32
- *   workspace dev, >= xq_remat_attn_workspace_bytes(a, B, max_b len[b]) bytes, 16-byte aligned;
- *            holds the per-chunk softmax partials; contents are scratch
+ *   workspace dev, >= xq_remat_attn_workspace_bytes(...) bytes, 16-byte aligned; holds the
+ *            per-chunk softmax partials and a token-major copy of the scales; contents are scratch
  * B is taken from xcache->B, or passed in `B` when acc_bf16 is the source.
+ * xq_remat_attn_workspace_bytes: max_len = max_b len[b]; d and group are those of the X cache,
+ * group = 0 when the accumulator is the source.  Returns 0 for an invalid combination.
  */
-size_t      xq_remat_attn_workspace_bytes(const xq_attn_t *a, int32_t B, int32_t max_len);
+size_t      xq_remat_attn_workspace_bytes(const xq_attn_t *a, int32_t B, int32_t max_len, int32_t d,
+                                          int32_t group);
 xq_status_t xq_remat_attn_decode(const xq_attn_t *a, const uint16_t *q_bf16,
                                  const xq_cache_t *xcache,
                                  const uint16_t *acc_bf16, int32_t B, int32_t cap, int32_t d,

@@ -74,7 +74,7 @@ def load_library():
     lib.xq_prepare_weights.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.xq_remat_attn_workspace_bytes.restype = C.c_size_t
-    lib.xq_remat_attn_workspace_bytes.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32]
+    lib.xq_remat_attn_workspace_bytes.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.xq_remat_attn_decode.restype = C.c_int
     lib.xq_remat_attn_decode.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
                                          C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
@@ -202,9 +202,10 @@ def xq_prepare_weights(attn, d, group, src_bits, Wk, Wv, out=None):
     return out
 
 
-def xq_remat_attn_workspace_bytes(attn, B, max_len):
+def xq_remat_attn_workspace_bytes(attn, B, max_len, d, group):
+    """group = the X cache's group size, or 0 when the bf16 accumulator is the source."""
     a = attn.c_struct()
-    return load_library().xq_remat_attn_workspace_bytes(C.byref(a), B, max_len)
+    return load_library().xq_remat_attn_workspace_bytes(C.byref(a), B, max_len, d, group)
 
 
 def xq_remat_attn_decode(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=None, out=None, workspace=None):
@@ -220,7 +221,8 @@ def xq_remat_attn_decode(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=Non
         cptr = None
     lens = [int(v) for v in lens]
     a = attn.c_struct()
-    need = xq_remat_attn_workspace_bytes(attn, B, max(lens) if lens else 1)
+    need = xq_remat_attn_workspace_bytes(attn, B, max(lens) if lens else 1, d,
+                                         xcache.group if xcache is not None else 0)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q_bf16.device)
     if out is None:

@@ -15,6 +15,7 @@ hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const u
 hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
                                  const BatchI32& len, int max_len, float* out, void* ws, hipStream_t s);
+size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool coded);
 
 static bool fmt_ok(const xq_qfmt_t& f)
 {
@@ -150,12 +151,11 @@ xq_status_t xq_prepare_weights(const xq_attn_t* a, int32_t d, int32_t group, int
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 
-size_t xq_remat_attn_workspace_bytes(const xq_attn_t* a, int32_t B, int32_t max_len)
+size_t xq_remat_attn_workspace_bytes(const xq_attn_t* a, int32_t B, int32_t max_len, int32_t d, int32_t group)
 {
-    if (check_attn(a) != XQ_OK || B < 1 || max_len < 1) return 0;
-    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
-    const size_t chunks = tiles * (TILE_TOKENS / CHUNK_TOKENS);
-    return (size_t)B * a->n_q_heads * chunks * (128 + 2) * sizeof(float);
+    if (check_attn(a) != XQ_OK || B < 1 || max_len < 1 || d <= 0 || d % 128 != 0) return 0;
+    if (group != 0 && group != 64 && group != 128) return 0;
+    return remat_workspace_bytes(B, a->n_q_heads, max_len, d, group ? group : 128, group != 0);
 }
 
 xq_status_t xq_remat_attn_decode(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* xcache,
@@ -185,7 +185,8 @@ xq_status_t xq_remat_attn_decode(const xq_attn_t* a, const uint16_t* q_bf16, con
         lv.v[b] = len[b];
         if (len[b] > max_len) max_len = len[b];
     }
-    if (workspace_bytes < xq_remat_attn_workspace_bytes(a, B, max_len)) return XQ_ERR_WORKSPACE;
+    if (workspace_bytes < xq_remat_attn_workspace_bytes(a, B, max_len, d, xcache ? xcache->fmt.group : 0))
+        return XQ_ERR_WORKSPACE;
     hipError_t e = run_remat_attn_decode(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, lv, max_len, out,
                                          workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;

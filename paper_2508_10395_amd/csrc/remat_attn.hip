@@ -11,11 +11,11 @@
 // is a per-lane scalar.
 //
 // The cached codes are not dequantised to bf16 (that rounding alone would exceed
-// the 2e-3 budget): each lane reads its token's packed codes straight from HBM,
-// drops them into bf16 mantissas (1 + code*2^(o-7), exact) and the MFMA accumulates
-// per quantisation group  P_g = sum_k (1 + c_k 2^(o_k-7)) W'_k.  With e_g = 2^b *
-// scale_g the rematerialised value is
-//     K[n][t] = sum_g e_g P_g[n]  +  sum_g ( zero_g S_g[n] - e_g S'_g[n] ),
+// the 2e-3 budget): the codes are dropped into bf16 mantissas (1 + code*2^(o-7),
+// exact) and the MFMA accumulates per quantisation group
+//     P_g = sum_k (1 + c_k 2^(o_k-7)) W'_k.
+// With e_g = 2^b * scale_g the rematerialised value is
+//     K[n][t] = sum_g e_g P_g[n]  +  sum_g ( zero_g S_g[n] - e_g S'_g[n] ).
 // The first sum is carried in one accumulator by rescaling it with e_{g-1}/e_g at
 // each group boundary (Horner form, one v_mul per register per group, relative
 // error ~2^-23 per group); the second is a rank-(5 d/G) product done by a few extra
@@ -23,6 +23,13 @@
 // (exact in bf16) and whose weight-side operands are 2- and 3-way bf16 splits of
 // the column sums.  A zero stored scale uses e_g = 1 (its codes are all zero, so
 // only the column-sum term matters and it cancels exactly as for any other e_g).
+//
+// Data movement of the coded kernel: everything the contraction loop consumes
+// arrives by LDS-DMA (global_load_lds): the weight slab, the tile's packed codes of
+// the next 128 channels (16-byte pieces, three adjacent lanes per 3-bit row) and the
+// tile's effective scales (from a [tile][group][token] copy made by a small
+// pre-pass, so that they are contiguous).  The loop therefore contains no
+// compiler-visible global load, and one explicit s_waitcnt vmcnt(0) per slab.
 //
 // After the contraction the K waves form the scores q.K[t] for each query head of
 // the KV group, hand them to the V waves through LDS, and each V wave emits one
@@ -37,7 +44,12 @@ namespace xq {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int MAX_GQ = 16;   // query heads per KV head the epilogue's LDS scratch is sized for
+constexpr int LDS_CODES_OFF = 2 * SLAB_BYTES;           // packed codes of one slab for the tile (<= 16 KiB)
+constexpr int LDS_CODES_BYTES = 16384;
+constexpr int LDS_SCALES_OFF = LDS_CODES_OFF + LDS_CODES_BYTES;   // effective scales, 2 groups x 256 tokens
+constexpr int LDS_SCALES_BYTES = 1024;
+constexpr int LDS_TOTAL = LDS_SCALES_OFF + LDS_SCALES_BYTES;
+constexpr int LDS_SCORE_OFF = LDS_CODES_OFF;            // epilogue score scratch reuses the code buffer
 
 struct RematParams {
     const uint16_t* q;       // [B][Hq][128]
@@ -46,6 +58,7 @@ struct RematParams {
     const uint16_t* zero;
     const uint16_t* acc;     // dense source
     const uint8_t* wprep;
+    const uint16_t* eT;      // coded source: effective scales [B][tiles][ng (+1 pad)][256], bf16
     float* part_o;           // [B][Hq][chunks_per_seq][128]
     float* part_ml;          // [B][Hq][chunks_per_seq][2]
     int B, cap, d, Hq, Hkv;
@@ -56,50 +69,33 @@ struct RematParams {
     BatchI32 len;
 };
 
-// LDS-DMA of 16 bytes per lane: the wave's 1 KiB lands at lds_off + 16*lane.  Issued
-// through inline asm so that the compiler's wait-count insertion does not serialise
-// later LDS reads of the *other* buffer against it; completion is awaited explicitly
-// (s_waitcnt vmcnt(0) + workgroup barrier) before the buffer is read.  M0 is not
-// otherwise used by this kernel.
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_off)
+// LDS-DMA: every active lane copies 16 bytes from saddr + voff to LDS at lds_dst + 16 * lane.
+// Issued through inline asm so that the compiler's wait-count insertion does not serialise
+// later LDS reads of other buffers against it; completion is awaited explicitly
+// (s_waitcnt vmcnt(0) + workgroup barrier) before the data is read.  M0 is not otherwise
+// used by these kernels.
+__device__ __forceinline__ void dma_b128(const void* saddr, uint32_t voff, uint32_t lds_dst)
 {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(saddr), "s"(lds_dst) : "memory");
 }
 
-__device__ __forceinline__ void issue_slab(const uint8_t* src, uint32_t lds_base, int wave, int lane)
+// one 64 KiB weight slab: 8 DMA instructions per wave (src / lds_dst already offset by the wave's 1 KiB)
+__device__ __forceinline__ void issue_slab(const uint8_t* src, uint32_t lds_dst, uint32_t voff)
 {
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-        const int chunk = wave + 8 * c;
-        dma16(src + chunk * 1024 + lane * 16, lds_base + chunk * 1024);
-    }
+    for (int c = 0; c < 8; ++c) dma_b128(src + c * 8192, voff, lds_dst + c * 8192);
 }
 
-template <int NDW>
-__device__ __forceinline__ void load_dwords(const uint8_t* p, uint32_t* dst)
+// packed pair of stored scales -> packed pair of -e (bf16), e = 2^bits * scale or 1 for a zero scale
+__device__ __forceinline__ uint32_t neg_eff_scale_pair(uint32_t pair, int bits)
 {
-    if constexpr (NDW % 4 == 0 && true) {
-#pragma unroll
-        for (int i = 0; i < NDW / 4; ++i) {
-            const uint4 v = reinterpret_cast<const uint4*>(p)[i];
-            dst[4 * i] = v.x; dst[4 * i + 1] = v.y; dst[4 * i + 2] = v.z; dst[4 * i + 3] = v.w;
-        }
-    } else if constexpr (NDW % 2 == 0) {
-#pragma unroll
-        for (int i = 0; i < NDW / 2; ++i) {
-            const uint2 v = reinterpret_cast<const uint2*>(p)[i];
-            dst[2 * i] = v.x; dst[2 * i + 1] = v.y;
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < NDW; ++i) dst[i] = reinterpret_cast<const uint32_t*>(p)[i];
-    }
-}
-
-__device__ __forceinline__ float eff_scale(uint32_t sbits, int bits)
-{
-    // e = 2^bits * scale, or 1 for a zero scale
-    return sbits ? __uint_as_float((sbits << 16) + ((uint32_t)bits << 23)) : 1.0f;
+    const uint32_t add = ((uint32_t)bits << 7) * 0x00010001u;
+    uint32_t lo = pair & 0xFFFFu, hi = pair >> 16;
+    uint32_t r = pair + add;
+    if (!lo) r = (r & 0xFFFF0000u) | 0x3F80u;
+    if (!hi) r = (r & 0x0000FFFFu) | 0x3F800000u;
+    return r | 0x80008000u;
 }
 
 __device__ __forceinline__ bf16x8 as_frag(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
@@ -127,244 +123,74 @@ __device__ __forceinline__ float wave32_sum(float v)
     return v;
 }
 
-template <int BITS, int G>   // BITS in {2,3,4}: coded source; 16: dense bf16 accumulator source
-__global__ __launch_bounds__(512) void remat_attn_kernel(const RematParams p)
+// One k-step of one unit for one token block, dispatching on the (compile-time after
+// unrolling) k-step index inside the unit.
+template <int BITS>
+__device__ __forceinline__ void unpack_kstep(const uint32_t* unit, int j, uint32_t one, uint32_t* out)
 {
-    constexpr bool DENSE = BITS == 16;
-    constexpr int KSG = DENSE ? 8 : G / 16;               // k-steps per quantisation group
-    constexpr int GPS = 8 / KSG;                          // groups per slab
-    constexpr int NDW_G = DENSE ? 0 : (G / 2) * BITS / 32;  // code dwords per lane per group
-    constexpr int NDW = DENSE ? 1 : GPS * NDW_G;
-    constexpr int GROUP_BYTES = DENSE ? 0 : G * BITS / 8;
+    switch (j & 3) {
+        case 0: UnpackKStep<BITS, 0>::run(unit, one, out); break;
+        case 1: UnpackKStep<BITS, 1>::run(unit, one, out); break;
+        case 2: UnpackKStep<BITS, 2>::run(unit, one, out); break;
+        default: UnpackKStep<BITS, 3>::run(unit, one, out); break;
+    }
+}
 
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+// which tile this workgroup owns
+struct TileCtx {
+    int hk, b, tile, len, tq, part, half, tl, lane, wave;
+    int tok[2];
+};
 
+__device__ __forceinline__ bool locate_tile(const RematParams& p, TileCtx& c)
+{
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int part = wave >> 2;          // 0: K columns, 1: V columns
-    const int tq = wave & 3;             // which 64 tokens of the tile
-    const int half = lane >> 5, tl = lane & 31;
-
+    c.lane = tid & 63;
+    c.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    c.part = c.wave >> 2;          // 0: K columns, 1: V columns
+    c.tq = c.wave & 3;             // which 64 tokens of the tile
+    c.half = c.lane >> 5;
+    c.tl = c.lane & 31;
     // workgroup -> (KV head, sequence, tile); heads are dealt so that the workgroups
     // resident on one XCD (blockIdx % 8) stream the same head's slabs through its L2
     const int NT = p.B * p.tiles_per_seq;
-    int hk, tile_lin;
+    int tile_lin;
     if ((p.Hkv & 7) == 0) {
         const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-        hk = xcd + 8 * (j / NT);
+        c.hk = xcd + 8 * (j / NT);
         tile_lin = j % NT;
     } else {
-        hk = blockIdx.x / NT;
+        c.hk = blockIdx.x / NT;
         tile_lin = blockIdx.x % NT;
     }
-    const int b = tile_lin / p.tiles_per_seq;
-    const int tile = tile_lin % p.tiles_per_seq;
-    const int len = p.len.v[b];
-    if (tile * TILE_TOKENS >= len) return;
+    c.b = tile_lin / p.tiles_per_seq;
+    c.tile = tile_lin % p.tiles_per_seq;
+    c.len = p.len.v[c.b];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) c.tok[tb] = c.tile * TILE_TOKENS + c.tq * CHUNK_TOKENS + tb * 32 + c.tl;
+    return c.tile * TILE_TOKENS < c.len;
+}
 
-    int tok[2];
-    uint32_t rowi[2];                    // row inside the sequence (clamped: padding rows re-read the last one)
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        tok[tb] = tile * TILE_TOKENS + tq * CHUNK_TOKENS + tb * 32 + tl;
-        rowi[tb] = (uint32_t)min(tok[tb], len - 1);
-    }
-
-    const uint8_t* wsrc = p.wprep + (long long)hk * p.head_bytes;
-    const int n_corr_slabs = (p.n_corr_ksteps + SLAB_KSTEPS - 1) / SLAB_KSTEPS;
-    const int n_slabs = p.n_main_slabs + n_corr_slabs;
-
-    f32x16 acc[2][4];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[tb][nb][i] = 0.0f;
-
-    // ---- per-lane token-side sources: wave-uniform sequence base + 32-bit lane offset
-    const long long seq_row0 = (long long)b * p.cap;
-    const uint8_t* cbase = DENSE ? reinterpret_cast<const uint8_t*>(p.acc) + seq_row0 * p.d * 2
-                                 : p.codes + seq_row0 * ((long long)p.d * BITS / 8);
-    const uint16_t* sbase = DENSE ? nullptr : p.scale + seq_row0 * p.ng;
-    const uint16_t* zbase = DENSE ? nullptr : p.zero + seq_row0 * p.ng;
-    uint32_t coff[2], moff[2];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        if constexpr (DENSE) coff[tb] = rowi[tb] * (uint32_t)(p.d * 2) + half * 128;
-        else coff[tb] = rowi[tb] * (uint32_t)(p.d * BITS / 8) + half * (GROUP_BYTES / 2);
-        moff[tb] = rowi[tb] * (uint32_t)p.ng;
-    }
-
-    uint32_t cur[2][NDW], nxt[2][NDW];
-    uint32_t sc_cur[2][GPS], sc_nxt[2][GPS];
-    uint4 bd[2][8];                       // dense: one slab of operand fragments per token block
-    float e_prev[2] = {1.0f, 1.0f};
-
-    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds;
-
-    // Workgroups that run side by side on one XCD stream the same head.  Each starts its
-    // contraction at a different slab (the sum over groups is order-free), so that at any
-    // moment they pull different addresses and the requests spread over all L2 channels.
-    const int rot = (int)((blockIdx.x >> 3) % (unsigned)p.n_main_slabs);
-    auto main_slab_id = [&](int it) { const int s = it + rot; return s >= p.n_main_slabs ? s - p.n_main_slabs : s; };
-
-    // prologue: first slab
-    issue_slab(wsrc + (long long)rot * SLAB_BYTES, lds0, wave, lane);
-    if constexpr (DENSE) {
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) bd[tb][ks] = reinterpret_cast<const uint4*>(cbase + coff[tb] + rot * 256)[ks];
-    } else {
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int gi = 0; gi < GPS; ++gi) {
-                load_dwords<NDW_G>(cbase + coff[tb] + (rot * GPS + gi) * GROUP_BYTES, &nxt[tb][gi * NDW_G]);
-                sc_nxt[tb][gi] = sbase[moff[tb] + rot * GPS + gi];
-            }
-    }
-
-    // ---- main slabs: the d x 256 contraction
-    for (int it = 0; it < p.n_main_slabs; ++it) {
-        // this slab (and this lane's token-side data for it) has landed; everyone is done with the one before
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        const bool more_main = it + 1 < p.n_main_slabs;
-        const int s_next = more_main ? main_slab_id(it + 1) : p.n_main_slabs;   // then the correction slabs
-        if (it + 1 < n_slabs)
-            issue_slab(wsrc + (long long)s_next * SLAB_BYTES, lds0 + (uint32_t)(((it + 1) & 1) * SLAB_BYTES), wave, lane);
-        const uint8_t* slab = lds + (it & 1) * SLAB_BYTES + (part * 4 * 64 + lane) * 16;
-
-        if constexpr (!DENSE) {
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
-#pragma unroll
-                for (int i = 0; i < NDW; ++i) cur[tb][i] = nxt[tb][i];
-#pragma unroll
-                for (int gi = 0; gi < GPS; ++gi) sc_cur[tb][gi] = sc_nxt[tb][gi];
-            }
-            if (more_main) {
-#pragma unroll
-                for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                    for (int gi = 0; gi < GPS; ++gi) {
-                        load_dwords<NDW_G>(cbase + coff[tb] + (s_next * GPS + gi) * GROUP_BYTES, &nxt[tb][gi * NDW_G]);
-                        sc_nxt[tb][gi] = sbase[moff[tb] + s_next * GPS + gi];
-                    }
-            }
-        }
-
-        uint32_t bu[2][16];
-#pragma unroll
-        for (int ks = 0; ks < SLAB_KSTEPS; ++ks) {
-            __builtin_amdgcn_sched_barrier(0);   // keep each k-step's loads and unpack local
-            bf16x8 bfrag[2];
-            if constexpr (DENSE) {
-#pragma unroll
-                for (int tb = 0; tb < 2; ++tb) {
-                    bfrag[tb] = __builtin_bit_cast(bf16x8, bd[tb][ks]);
-                    if (more_main)   // refill this ring slot for the next slab
-                        bd[tb][ks] = reinterpret_cast<const uint4*>(cbase + coff[tb] + s_next * 256)[ks];
-                }
-            } else {
-                const int gi = ks / KSG, ksg = ks % KSG;
-                if (ksg == 0) {
-#pragma unroll
-                    for (int tb = 0; tb < 2; ++tb) {
-                        const float e = eff_scale(sc_cur[tb][gi], BITS);
-                        const float r = e_prev[tb] * __builtin_amdgcn_rcpf(e);
-                        e_prev[tb] = e;
-#pragma unroll
-                        for (int nb = 0; nb < 4; ++nb) acc[tb][nb] *= r;
-                    }
-                }
-                if ((ksg & 3) == 0) {
-#pragma unroll
-                    for (int tb = 0; tb < 2; ++tb)
-                        UnpackUnit<BITS>::run(&cur[tb][gi * NDW_G + (ksg >> 2) * BITS], bu[tb]);
-                }
-#pragma unroll
-                for (int tb = 0; tb < 2; ++tb) {
-                    const int o = (ksg & 3) * 4;
-                    bfrag[tb] = as_frag(bu[tb][o], bu[tb][o + 1], bu[tb][o + 2], bu[tb][o + 3]);
-                }
-            }
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb) {
-                const bf16x8 a = __builtin_bit_cast(
-                    bf16x8, *reinterpret_cast<const uint4*>(slab + (ks * 8 + nb) * 1024));
-                acc[0][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bfrag[0], acc[0][nb], 0, 0, 0);
-                acc[1][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bfrag[1], acc[1][nb], 0, 0, 0);
-            }
-        }
-    }
-
-    // ---- correction slabs: token-side operands are the stored zero-points / minus the scales
-    if constexpr (!DENSE) {
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb) acc[tb][nb] *= e_prev[tb];
-
-        for (int s = p.n_main_slabs; s < n_slabs; ++s) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (s + 1 < n_slabs)
-                issue_slab(wsrc + (long long)(s + 1) * SLAB_BYTES, lds0 + (uint32_t)(((s + 1) & 1) * SLAB_BYTES), wave, lane);
-            const uint8_t* slab = lds + (s & 1) * SLAB_BYTES + (part * 4 * 64 + lane) * 16;
-            const int kk0 = (s - p.n_main_slabs) * SLAB_KSTEPS;
-            const int nks = min(SLAB_KSTEPS, p.n_corr_ksteps - kk0);
-#pragma unroll 1
-            for (int ks = 0; ks < nks; ++ks) {
-                const int kappa0 = (kk0 + ks) * 16 + half * 8;
-                const int term = kappa0 / p.ng_pad, g0 = kappa0 % p.ng_pad;
-                const bool term_ok = term < N_CORR_TERMS;
-                const uint16_t* mbase = term < 2 ? zbase : sbase;
-                bf16x8 bfrag[2];
-#pragma unroll
-                for (int tb = 0; tb < 2; ++tb) {
-                    uint32_t h[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int g = g0 + i;
-                        uint32_t v = mbase[moff[tb] + min(g, p.ng - 1)];
-                        if (term >= 2) v = (v ? v + ((uint32_t)BITS << 7) : 0x3F80u) | 0x8000u;
-                        h[i] = (term_ok && g < p.ng) ? v : 0u;
-                    }
-                    bfrag[tb] = as_frag(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
-                                        h[6] | (h[7] << 16));
-                }
-#pragma unroll
-                for (int nb = 0; nb < 4; ++nb) {
-                    const bf16x8 a = __builtin_bit_cast(
-                        bf16x8, *reinterpret_cast<const uint4*>(slab + (ks * 8 + nb) * 1024));
-                    acc[0][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bfrag[0], acc[0][nb], 0, 0, 0);
-                    acc[1][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bfrag[1], acc[1][nb], 0, 0, 0);
-                }
-            }
-        }
-    }
-
-    // ------------------------------------------------------------ attention epilogue
-    // accumulator element i of column block nb <-> output column n = 32 nb + 8 (i/4) + 4 half + i%4
-    __syncthreads();                                   // slabs are dead: LDS becomes score scratch
-    float* sc_lds = reinterpret_cast<float*>(lds);     // [4 tq][gq][64]
+// ---- attention on the rematerialised tile.  Accumulator element i of column block nb
+// <-> output column n = 32 nb + 8 (i/4) + 4 half + i%4, token = lane % 32 (+32 tb).
+__device__ __forceinline__ void attention_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[2][4],
+                                                   uint8_t* lds)
+{
+    __syncthreads();                                   // the contraction's LDS traffic is over
+    float* sc_lds = reinterpret_cast<float*>(lds + LDS_SCORE_OFF);     // [4 tq][gq][64]
     const int gq = p.Hq / p.Hkv;
-    const int chunk = tile * 4 + tq;
-    const bool chunk_live = tile * TILE_TOKENS + tq * CHUNK_TOKENS < len;
+    const int chunk = c.tile * 4 + c.tq;
+    const bool chunk_live = c.tile * TILE_TOKENS + c.tq * CHUNK_TOKENS < c.len;
 
-    if (part == 0) {
+    if (c.part == 0) {
         for (int j = 0; j < gq; ++j) {
-            const uint16_t* qv = p.q + ((long long)b * p.Hq + hk * gq + j) * 128;
+            const uint16_t* qv = p.q + ((long long)c.b * p.Hq + c.hk * gq + j) * 128;
             float dot[2] = {0.0f, 0.0f};
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4) {
-                    const uint2 qq = *reinterpret_cast<const uint2*>(qv + nb * 32 + i4 * 8 + half * 4);
+                    const uint2 qq = *reinterpret_cast<const uint2*>(qv + nb * 32 + i4 * 8 + c.half * 4);
                     const float q0 = bf16_lo_to_f32(qq.x), q1 = bf16_hi_to_f32(qq.x);
                     const float q2 = bf16_lo_to_f32(qq.y), q3 = bf16_hi_to_f32(qq.y);
 #pragma unroll
@@ -378,23 +204,23 @@ __global__ __launch_bounds__(512) void remat_attn_kernel(const RematParams p)
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb) {
                 float sfull = dot[tb] + __shfl_xor(dot[tb], 32);
-                sfull = tok[tb] < len ? sfull * p.scale_log2e : -INFINITY;
-                if (half == 0) sc_lds[(tq * gq + j) * 64 + tb * 32 + tl] = sfull;
+                sfull = c.tok[tb] < c.len ? sfull * p.scale_log2e : -INFINITY;
+                if (c.half == 0) sc_lds[(c.tq * gq + j) * 64 + tb * 32 + c.tl] = sfull;
             }
         }
     }
     __syncthreads();
-    if (part == 1 && chunk_live) {
+    if (c.part == 1 && chunk_live) {
         for (int j = 0; j < gq; ++j) {
-            const int hq = hk * gq + j;
+            const int hq = c.hk * gq + j;
             float sv[2], pv[2];
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) sv[tb] = sc_lds[(tq * gq + j) * 64 + tb * 32 + tl];
+            for (int tb = 0; tb < 2; ++tb) sv[tb] = sc_lds[(c.tq * gq + j) * 64 + tb * 32 + c.tl];
             const float m = wave32_max(fmaxf(sv[0], sv[1]));
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb) pv[tb] = __builtin_amdgcn_exp2f(sv[tb] - m);
             const float l = wave32_sum(pv[0] + pv[1]);
-            const long long pidx = ((long long)b * p.Hq + hq) * p.chunks_per_seq + chunk;
+            const long long pidx = ((long long)c.b * p.Hq + hq) * p.chunks_per_seq + chunk;
             float* po = p.part_o + pidx * 128;
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb)
@@ -403,22 +229,406 @@ __global__ __launch_bounds__(512) void remat_attn_kernel(const RematParams p)
                     float o[4];
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
-                        // p = 0 rows (masked tokens) must not import garbage: rows are clamped, so finite
+                        // masked tokens have p = 0 and their rows are clamped copies: always finite
                         float v = pv[0] * acc[0][nb][i4 * 4 + k];
                         v = __builtin_fmaf(pv[1], acc[1][nb][i4 * 4 + k], v);
                         o[k] = wave32_sum(v);
                     }
-                    if (tl == 0) {
+                    if (c.tl == 0) {
                         float4 w; w.x = o[0]; w.y = o[1]; w.z = o[2]; w.w = o[3];
-                        *reinterpret_cast<float4*>(po + nb * 32 + i4 * 8 + half * 4) = w;
+                        *reinterpret_cast<float4*>(po + nb * 32 + i4 * 8 + c.half * 4) = w;
                     }
                 }
-            if (lane == 0) {
+            if (c.lane == 0) {
                 p.part_ml[pidx * 2] = m;
                 p.part_ml[pidx * 2 + 1] = l;
             }
         }
     }
+}
+
+// =====================================================================================
+// coded source (XQuant cache, BITS in {2,3,4})
+// =====================================================================================
+template <int BITS, int G>
+__global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams p)
+{
+    constexpr int KSG = G / 16;                        // k-steps per quantisation group
+    constexpr int GPS = 8 / KSG;                       // groups per slab (1 or 2)
+    constexpr int NDW_G = (G / 2) * BITS / 32;         // code dwords per lane per group
+    constexpr int NDW = GPS * NDW_G;                   // ... per slab (= 2 BITS)
+    constexpr int ROW_SLAB_BYTES = 16 * BITS;          // packed bytes of 128 channels of one token
+    constexpr int NCI = 4 * BITS;                      // code-DMA wave instructions per slab per workgroup
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    TileCtx c;
+    if (!locate_tile(p, c)) return;
+    const int lane = c.lane, wave = c.wave, half = c.half, tl = c.tl;
+
+    const int n_corr_slabs = (p.n_corr_ksteps + SLAB_KSTEPS - 1) / SLAB_KSTEPS;
+    const int n_slabs = p.n_main_slabs + n_corr_slabs;
+    const uint8_t* wsrc = p.wprep + (long long)c.hk * p.head_bytes + wave * 1024;   // this wave's DMA share
+    const uint32_t dma_voff = (uint32_t)lane * 16u;
+    const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds;
+    const uint32_t lds_w = lds_base + wave * 1024;
+
+    // ---- token-side sources
+    const long long seq_row0 = (long long)c.b * p.cap;
+    const uint32_t row_bytes = (uint32_t)(p.d * BITS / 8);
+    const uint8_t* cbase = p.codes + seq_row0 * row_bytes;
+    const uint16_t* sbase = p.scale + seq_row0 * p.ng;
+    const uint16_t* zbase = p.zero + seq_row0 * p.ng;
+    const uint8_t* ebase = reinterpret_cast<const uint8_t*>(p.eT) +
+                           ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.ng + 1) * 512;
+    uint32_t moff[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) moff[tb] = (uint32_t)min(c.tok[tb], c.len - 1) * (uint32_t)p.ng;
+
+    // code DMA: 16-byte piece pc of the tile's slab image = (row pc / BITS, part pc % BITS);
+    // wave instruction i covers pieces [64 i, 64 i + 64); this wave issues i = wave and wave + 8
+    uint32_t cvoff[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int pc = (wave + 8 * k) * 64 + lane;
+        const int rl = pc / BITS, prt = pc % BITS;
+        cvoff[k] = (uint32_t)min(c.tile * TILE_TOKENS + rl, c.len - 1) * row_bytes + prt * 16;
+    }
+    auto issue_tokens = [&](int slab) {      // codes + effective scales of main slab `slab`
+        const uint8_t* src = cbase + slab * ROW_SLAB_BYTES;
+        if (wave < NCI) dma_b128(src, cvoff[0], lds_base + LDS_CODES_OFF + wave * 1024);
+        if (wave + 8 < NCI) dma_b128(src, cvoff[1], lds_base + LDS_CODES_OFF + (wave + 8) * 1024);
+        if (wave == 7) dma_b128(ebase + (long long)slab * GPS * 512, dma_voff, lds_base + LDS_SCALES_OFF);
+    };
+    // this lane's codes / scales inside the LDS images
+    const uint8_t* my_codes[2];
+    const uint16_t* my_scale[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        const int rl = c.tq * CHUNK_TOKENS + tb * 32 + tl;
+        my_codes[tb] = lds + LDS_CODES_OFF + rl * ROW_SLAB_BYTES + half * (NDW_G * 4);
+        my_scale[tb] = reinterpret_cast<const uint16_t*>(lds + LDS_SCALES_OFF) + rl;
+    }
+
+    // Workgroups that run side by side on one XCD stream the same head.  Each starts its
+    // contraction at a different slab (the sum over groups is order-free), so that at any
+    // moment they pull different addresses and the requests spread over all L2 channels.
+    const int rot = (int)((blockIdx.x >> 3) % (unsigned)p.n_main_slabs);
+    auto main_slab_id = [&](int it) { const int s = it + rot; return s >= p.n_main_slabs ? s - p.n_main_slabs : s; };
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[tb][nb][i] = 0.0f;
+
+    // MFMA operands, double-buffered by k-step parity
+    uint4 af[2][4];                      // weight fragments [parity][column block]
+    uint32_t ub[2][2][4];                // token fragments  [parity][token block][dword]
+    uint32_t cur[2][NDW];                // packed codes of the current slab
+    float e_cur[2][GPS];                 // effective scales of the current slab's groups
+    float e_prev[2] = {1.0f, 1.0f};      // e of the group the accumulator is currently scaled by
+    float hr[2] = {1.0f, 1.0f};          // pending Horner factor e_prev / e_next
+    uint32_t one = BF16_ONE_PAIR;
+    asm volatile("" : "+v"(one));        // keep the constant in a VGPR (operand of v_and_or_b32)
+
+    // pull this lane's share of the landed slab out of LDS: codes and scales
+    auto fetch_tokens = [&]() {
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+#pragma unroll
+            for (int gi = 0; gi < GPS; ++gi) {
+                const uint8_t* src = my_codes[tb] + gi * (2 * NDW_G * 4);
+                if constexpr (NDW_G % 4 == 0) {
+#pragma unroll
+                    for (int i = 0; i < NDW_G / 4; ++i) {
+                        const uint4 v = reinterpret_cast<const uint4*>(src)[i];
+                        cur[tb][gi * NDW_G + 4 * i] = v.x; cur[tb][gi * NDW_G + 4 * i + 1] = v.y;
+                        cur[tb][gi * NDW_G + 4 * i + 2] = v.z; cur[tb][gi * NDW_G + 4 * i + 3] = v.w;
+                    }
+                } else if constexpr (NDW_G % 2 == 0) {
+#pragma unroll
+                    for (int i = 0; i < NDW_G / 2; ++i) {
+                        const uint2 v = reinterpret_cast<const uint2*>(src)[i];
+                        cur[tb][gi * NDW_G + 2 * i] = v.x; cur[tb][gi * NDW_G + 2 * i + 1] = v.y;
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < NDW_G; ++i) cur[tb][gi * NDW_G + i] = reinterpret_cast<const uint32_t*>(src)[i];
+                }
+                e_cur[tb][gi] = __uint_as_float((uint32_t)my_scale[tb][gi * TILE_TOKENS] << 16);
+            }
+        }
+    };
+
+    // ---- prologue: first slab
+    issue_slab(wsrc + (long long)rot * SLAB_BYTES, lds_w, dma_voff);
+    issue_tokens(rot);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    fetch_tokens();
+    {
+        const uint8_t* slab0 = lds + (c.part * 4 * 64 + lane) * 16;
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) af[0][nb] = *reinterpret_cast<const uint4*>(slab0 + nb * 1024);
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            e_prev[tb] = e_cur[tb][0];
+            unpack_kstep<BITS>(&cur[tb][0], 0, one, ub[0][tb]);
+        }
+    }
+
+    // ---- main slabs: the d x 256 contraction.  A k-step is 8 slots of one MFMA each
+    // (column block nb = slot/2, token block tb = slot%2); the VALU/LDS work that feeds
+    // later slots is spread over the slots and pinned there with scheduling fences so that
+    // it runs in the shadow of the MFMAs.
+    for (int it = 0; it < p.n_main_slabs; ++it) {
+        // everyone has finished the previous slab's weight buffer and has taken its codes out of LDS
+        __syncthreads();
+        const bool more_main = it + 1 < p.n_main_slabs;
+        const int s_next = more_main ? main_slab_id(it + 1) : p.n_main_slabs;   // then the correction slabs
+        if (it + 1 < n_slabs)
+            issue_slab(wsrc + (long long)s_next * SLAB_BYTES, lds_w + (uint32_t)(((it + 1) & 1) * SLAB_BYTES), dma_voff);
+        if (more_main) issue_tokens(s_next);
+        const uint8_t* slab = lds + (it & 1) * SLAB_BYTES + (c.part * 4 * 64 + lane) * 16;
+        const uint8_t* slab_next = lds + ((it + 1) & 1) * SLAB_BYTES + (c.part * 4 * 64 + lane) * 16;
+        __builtin_amdgcn_sched_barrier(0);
+
+#pragma unroll
+        for (int ks = 0; ks < SLAB_KSTEPS; ++ks) {
+            const int par = ks & 1;
+            const int gi = ks / KSG, ksg = ks % KSG;
+            const bool pre = ksg == KSG - 1;               // last k-step of a group: start rescaling
+            const bool post = ksg == 0;                    // first k-step of a group: finish rescaling
+#pragma unroll
+            for (int m = 0; m < 8; ++m) {
+                const int nb = m >> 1, tb = m & 1;
+                acc[tb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, af[par][nb]),
+                    as_frag(ub[par][tb][0], ub[par][tb][1], ub[par][tb][2], ub[par][tb][3]), acc[tb][nb], 0, 0, 0);
+
+                // weight fragments of the next k-step (at the slab's end: of the next slab, which has landed)
+                if (tb == 0) {
+                    if (ks + 1 < SLAB_KSTEPS) af[par ^ 1][nb] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + nb) * 1024);
+                    else if (more_main) af[par ^ 1][nb] = *reinterpret_cast<const uint4*>(slab_next + nb * 1024);
+                }
+                // token fragments of the next k-step
+                if (ks + 1 < SLAB_KSTEPS) {
+                    if (m < 2) {
+                        const int gi1 = (ks + 1) / KSG, ksg1 = (ks + 1) % KSG;
+                        unpack_kstep<BITS>(&cur[m][gi1 * NDW_G + (ksg1 >> 2) * BITS], ksg1, one, ub[par ^ 1][m]);
+                    }
+                } else if (m >= 6 && more_main) {           // cur already holds the next slab's codes
+                    unpack_kstep<BITS>(&cur[m - 6][0], 0, one, ub[par ^ 1][m - 6]);
+                }
+                // after the last unpack from the old codes: the next slab's data has landed for everyone
+                if (ks == SLAB_KSTEPS - 2 && m == 2) {
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    __syncthreads();
+                    if (more_main) fetch_tokens();
+                }
+                // Horner rescale of the accumulator to the next group's scale, 8 registers a slice
+                if (pre && m == 1) {
+#pragma unroll
+                    for (int t2 = 0; t2 < 2; ++t2) {
+                        // inside a slab the next group's scale is at hand; at the slab's end e_cur
+                        // was just refilled with the next slab's scales
+                        const float e = (gi + 1 < GPS) ? e_cur[t2][(gi + 1) % GPS] : (more_main ? e_cur[t2][0] : 1.0f);
+                        hr[t2] = e_prev[t2] * __builtin_amdgcn_rcpf(e);
+                        e_prev[t2] = e;
+                    }
+                }
+                auto slice = [&](int q) {
+                    const int bm = q >> 1, h8 = (q & 1) * 8;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) acc[bm & 1][bm >> 1][h8 + i] *= hr[bm & 1];
+                };
+                if (pre && m >= 2) slice(m - 2);
+                if (post && !(it == 0 && ks == 0)) {
+                    if (m < 2) slice(6 + m);
+                    else if (m < 6) { slice(8 + 2 * (m - 2)); slice(9 + 2 * (m - 2)); }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    // ---- correction slabs: token-side operands are the stored zero-points / minus the scales
+    // the accumulator is in units of 1 after the last boundary's rescale; finish its slices
+#pragma unroll
+    for (int q = 6; q < 16; ++q) {
+        const int bm = q >> 1, h8 = (q & 1) * 8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[bm & 1][bm >> 1][h8 + i] *= hr[bm & 1];
+    }
+    const bool vec_meta = (p.ng & 7) == 0;
+    // B-side fragment of correction k-step kk for token block tb (raw metadata; transformed at use)
+    auto load_meta = [&](int kk, int tb) -> uint4 {
+        const int kappa0 = kk * 16 + half * 8;
+        const int term = kappa0 / p.ng_pad, g0 = kappa0 % p.ng_pad;
+        const uint16_t* mbase = term < 2 ? zbase : sbase;
+        uint4 v = {0u, 0u, 0u, 0u};
+        if (kk < p.n_corr_ksteps && term < N_CORR_TERMS) {
+            if (vec_meta) {
+                v = *reinterpret_cast<const uint4*>(mbase + moff[tb] + g0);
+            } else {
+                uint32_t h[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int g = g0 + i;
+                    const uint32_t x = mbase[moff[tb] + min(g, p.ng - 1)];
+                    h[i] = g < p.ng ? x : 0u;                   // padding groups: see meta_frag
+                }
+                v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16);
+                v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
+            }
+        }
+        return v;
+    };
+    auto meta_frag = [&](int kk, uint4 raw) -> bf16x8 {
+        const int kappa0 = kk * 16 + half * 8;
+        const int term = kappa0 / p.ng_pad, g0 = kappa0 % p.ng_pad;
+        if (term >= 2 && term < N_CORR_TERMS) {
+            raw.x = neg_eff_scale_pair(raw.x, BITS); raw.y = neg_eff_scale_pair(raw.y, BITS);
+            raw.z = neg_eff_scale_pair(raw.z, BITS); raw.w = neg_eff_scale_pair(raw.w, BITS);
+            if (!vec_meta) {   // padding groups past ng contribute nothing
+                uint32_t* r = reinterpret_cast<uint32_t*>(&raw);
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (g0 + i >= p.ng) r[i >> 1] &= (i & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+            }
+        } else if (term >= N_CORR_TERMS) {
+            raw = uint4{0u, 0u, 0u, 0u};
+        }
+        return __builtin_bit_cast(bf16x8, raw);
+    };
+    constexpr int PF = 4;                      // prefetch distance in k-steps
+    uint4 mring[PF][2];
+#pragma unroll
+    for (int i = 0; i < PF; ++i)
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) mring[i][tb] = load_meta(i, tb);
+
+    for (int s = p.n_main_slabs; s < n_slabs; ++s) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (s + 1 < n_slabs)
+            issue_slab(wsrc + (long long)(s + 1) * SLAB_BYTES, lds_w + (uint32_t)(((s + 1) & 1) * SLAB_BYTES), dma_voff);
+        const uint8_t* slab = lds + (s & 1) * SLAB_BYTES + (c.part * 4 * 64 + lane) * 16;
+        const int kk0 = (s - p.n_main_slabs) * SLAB_KSTEPS;
+        const int nks = min(SLAB_KSTEPS, p.n_corr_ksteps - kk0);
+#pragma unroll 1
+        for (int ks = 0; ks < nks; ++ks) {
+            const int kk = kk0 + ks;
+            bf16x8 bfrag[2];
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                bfrag[tb] = meta_frag(kk, mring[0][tb]);
+#pragma unroll
+                for (int i = 0; i + 1 < PF; ++i) mring[i][tb] = mring[i + 1][tb];
+                mring[PF - 1][tb] = load_meta(kk + PF, tb);
+            }
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                const bf16x8 a = __builtin_bit_cast(
+                    bf16x8, *reinterpret_cast<const uint4*>(slab + (ks * 8 + nb) * 1024));
+                acc[0][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bfrag[0], acc[0][nb], 0, 0, 0);
+                acc[1][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bfrag[1], acc[1][nb], 0, 0, 0);
+            }
+        }
+    }
+
+    attention_epilogue(p, c, acc, lds);
+}
+
+// =====================================================================================
+// dense source (XQuant-CL accumulator, bf16): token fragments come straight from HBM,
+// each lane reading the 128 contiguous bytes of its token's half of the slab
+// =====================================================================================
+__global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    TileCtx c;
+    if (!locate_tile(p, c)) return;
+    const int lane = c.lane, wave = c.wave, half = c.half;
+
+    const uint8_t* wsrc = p.wprep + (long long)c.hk * p.head_bytes + wave * 1024;
+    const uint32_t dma_voff = (uint32_t)lane * 16u;
+    const uint32_t lds_w = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds + wave * 1024;
+    const uint8_t* cbase = reinterpret_cast<const uint8_t*>(p.acc) + (long long)c.b * p.cap * p.d * 2;
+    uint32_t coff[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) coff[tb] = (uint32_t)min(c.tok[tb], c.len - 1) * (uint32_t)(p.d * 2) + half * 128;
+
+    const int rot = (int)((blockIdx.x >> 3) % (unsigned)p.n_main_slabs);
+    auto main_slab_id = [&](int it) { const int s = it + rot; return s >= p.n_main_slabs ? s - p.n_main_slabs : s; };
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[tb][nb][i] = 0.0f;
+
+    uint4 af[2][4];
+    uint4 bd[2][8];                      // one slab of token fragments per token block (ring)
+
+    issue_slab(wsrc + (long long)rot * SLAB_BYTES, lds_w, dma_voff);
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) bd[tb][ks] = reinterpret_cast<const uint4*>(cbase + coff[tb] + rot * 256)[ks];
+
+    for (int it = 0; it < p.n_main_slabs; ++it) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        const bool more_main = it + 1 < p.n_main_slabs;
+        const int s_next = more_main ? main_slab_id(it + 1) : 0;
+        if (more_main)
+            issue_slab(wsrc + (long long)s_next * SLAB_BYTES, lds_w + (uint32_t)(((it + 1) & 1) * SLAB_BYTES), dma_voff);
+        const uint8_t* slab = lds + (it & 1) * SLAB_BYTES + (c.part * 4 * 64 + lane) * 16;
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) af[0][nb] = *reinterpret_cast<const uint4*>(slab + nb * 1024);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < SLAB_KSTEPS; ++ks) {
+            const int par = ks & 1;
+#pragma unroll
+            for (int m = 0; m < 8; ++m) {
+                const int nb = m >> 1, tb = m & 1;
+                acc[tb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, af[par][nb]), __builtin_bit_cast(bf16x8, bd[tb][ks]), acc[tb][nb], 0, 0, 0);
+                if (ks + 1 < SLAB_KSTEPS && tb == 0)
+                    af[par ^ 1][nb] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + nb) * 1024);
+                // the fragment is consumed by its last column block: refill the ring slot for the next slab
+                if (nb == 3 && more_main)
+                    bd[tb][ks] = reinterpret_cast<const uint4*>(cbase + coff[tb] + s_next * 256)[ks];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    attention_epilogue(p, c, acc, lds);
+}
+
+// ---- pre-pass of the coded kernel: effective scales e = 2^bits * scale (1 for a zero scale)
+// as bf16, laid out [sequence][tile][group (+1 pad)][256 tokens] so that a tile's scales of
+// one group are contiguous.  Tokens past len repeat the last row.
+__global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __restrict__ scale,
+                                                              uint16_t* __restrict__ eT, int cap, int ng,
+                                                              int tiles_per_seq, int bits, BatchI32 len)
+{
+    const int tile = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
+    const int L = len.v[b];
+    if (tile * TILE_TOKENS >= L) return;
+    const long long row = (long long)b * cap + min(tile * TILE_TOKENS + t, L - 1);
+    uint16_t* dst = eT + ((long long)b * tiles_per_seq + tile) * (long long)(ng + 1) * TILE_TOKENS + t;
+    for (int g = 0; g < ng; ++g) {
+        const uint32_t sb = scale[row * ng + g];
+        dst[(long long)g * TILE_TOKENS] = (uint16_t)(sb ? sb + ((uint32_t)bits << 7) : 0x3F80u);
+    }
+    dst[(long long)ng * TILE_TOKENS] = 0x3F80u;       // pad group (fetched, never used)
 }
 
 // ---- split-context combine: out[b][h][:] = sum_c w_c o_c / sum_c w_c l_c, w_c = 2^(m_c - M)
@@ -441,19 +651,23 @@ __global__ __launch_bounds__(128) void combine_kernel(const float* __restrict__ 
     out[((long long)b * Hq + h) * 128 + n] = o / L;
 }
 
-template <int BITS, int G>
-static hipError_t launch_remat(const RematParams& p, int grid, hipStream_t s)
+template <typename K>
+static hipError_t launch_with_lds(K kernel, const RematParams& p, int grid, hipStream_t s)
 {
-    static bool attr_set = false;
-    const int lds_bytes = 2 * SLAB_BYTES;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&remat_attn_kernel<BITS, G>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    remat_attn_kernel<BITS, G><<<dim3(grid), dim3(512), lds_bytes, s>>>(p);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL);
+    if (e != hipSuccess) return e;
+    kernel<<<dim3(grid), dim3(512), LDS_TOTAL, s>>>(p);
     return hipGetLastError();
+}
+
+size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool coded)
+{
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    const size_t chunks = tiles * (TILE_TOKENS / CHUNK_TOKENS);
+    size_t bytes = (size_t)B * Hq * chunks * (128 + 2) * sizeof(float);
+    if (coded) bytes += (size_t)B * tiles * (size_t)(d / group + 1) * TILE_TOKENS * sizeof(uint16_t);
+    return bytes;
 }
 
 hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
@@ -479,17 +693,26 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
     p.len = len;
     p.part_o = static_cast<float*>(ws);
     p.part_ml = p.part_o + (size_t)B * p.Hq * p.chunks_per_seq * 128;
+    uint16_t* eT = reinterpret_cast<uint16_t*>(p.part_ml + (size_t)B * p.Hq * p.chunks_per_seq * 2);
+    p.eT = eT;
 
     const int grid = p.Hkv * p.B * p.tiles_per_seq;
     hipError_t e = hipErrorInvalidValue;
+    if (xc) {
+        scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
+            xc->scale, eT, cap, L.ng, p.tiles_per_seq, bits, len);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     switch (bits * 1000 + (bits == 16 ? 0 : G)) {
-        case 2064: e = launch_remat<2, 64>(p, grid, s); break;
-        case 2128: e = launch_remat<2, 128>(p, grid, s); break;
-        case 3064: e = launch_remat<3, 64>(p, grid, s); break;
-        case 3128: e = launch_remat<3, 128>(p, grid, s); break;
-        case 4064: e = launch_remat<4, 64>(p, grid, s); break;
-        case 4128: e = launch_remat<4, 128>(p, grid, s); break;
-        case 16000: e = launch_remat<16, 128>(p, grid, s); break;
+        case 2064: e = launch_with_lds(remat_attn_coded_kernel<2, 64>, p, grid, s); break;
+        case 2128: e = launch_with_lds(remat_attn_coded_kernel<2, 128>, p, grid, s); break;
+        case 3064: e = launch_with_lds(remat_attn_coded_kernel<3, 64>, p, grid, s); break;
+        case 3128: e = launch_with_lds(remat_attn_coded_kernel<3, 128>, p, grid, s); break;
+        case 4064: e = launch_with_lds(remat_attn_coded_kernel<4, 64>, p, grid, s); break;
+        case 4128: e = launch_with_lds(remat_attn_coded_kernel<4, 128>, p, grid, s); break;
+        case 16000: e = launch_with_lds(remat_attn_dense_kernel, p, grid, s); break;
+        default: e = hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
     combine_kernel<<<dim3(p.Hq, p.B), dim3(128), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len);

@@ -2,7 +2,7 @@
 // order) and the rematerialisation kernel (device).
 //
 // A "unit" is 32 consecutive b-bit codes of one token row = b aligned dwords of the
-// row's little-endian bit string.  unpack_unit<b> turns it into 16 dwords, each a
+// row's little-endian bit string.  UnpackUnit<b> turns it into 16 dwords, each a
 // pair of bf16 values of the form 1 + code * 2^(o-7): the code's bits are dropped
 // straight into the bf16 mantissa at bit offset o under the exponent of 1.0
 // (0x3F80), so no integer->float conversion is needed.  Dword 4*ks+v feeds
@@ -25,91 +25,114 @@ namespace xq {
 
 constexpr uint32_t BF16_ONE_PAIR = 0x3F803F80u;
 
-XQ_HD uint32_t and_or(uint32_t a, uint32_t m, uint32_t o) { return (a & m) | o; }
+// (a & m) | BF16_ONE_PAIR.  On the device this is one v_and_or_b32: gfx9 VOP3 takes at
+// most one scalar/literal operand, so the mask goes in an SGPR and the constant in a VGPR.
+XQ_HD uint32_t and_or_one(uint32_t a, uint32_t m, uint32_t one_vgpr)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(m), "v"(one_vgpr));
+    return r;
+#else
+    return (a & m) | one_vgpr;
+#endif
+}
+XQ_HD uint32_t merge16(uint32_t lo_src, uint32_t hi_src)   // low half of lo_src, high half of hi_src
+{
+    return (lo_src & 0x0000FFFFu) | (hi_src & 0xFFFF0000u);
+}
 XQ_HD uint32_t funnel_r(uint32_t hi, uint32_t lo, int s)
 {
     return (uint32_t)((((uint64_t)hi << 32) | lo) >> s);
 }
 
-template <int BITS>
-struct UnpackUnit;
+// UnpackKStep<BITS, J>::run(w, one, out): the 4 operand dwords of k-step J (0..3) of a unit.
+// `w` points at the unit's BITS dwords; `one` must hold BF16_ONE_PAIR.
+template <int BITS, int J>
+struct UnpackKStep;
 
-// 4 bits: dword ks holds the 8 codes of k-step ks; pairs (v, v+4) sit 16 bits apart.
-template <>
-struct UnpackUnit<4> {
-    static XQ_HD void run(const uint32_t* w, uint32_t* out)
+// 4 bits: dword J holds the 8 codes of k-step J; pairs (v, v+4) sit 16 bits apart.
+template <int J>
+struct UnpackKStep<4, J> {
+    static XQ_HD void run(const uint32_t* w, uint32_t one, uint32_t* out)
     {
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const uint32_t d = w[ks];
-            out[4 * ks + 0] = and_or(d << 3, 0x00780078u, BF16_ONE_PAIR);
-            out[4 * ks + 1] = and_or(d >> 1, 0x00780078u, BF16_ONE_PAIR);
-            out[4 * ks + 2] = and_or(d >> 5, 0x00780078u, BF16_ONE_PAIR);
-            out[4 * ks + 3] = and_or(d >> 9, 0x00780078u, BF16_ONE_PAIR);
-        }
+        const uint32_t d = w[J];
+        out[0] = and_or_one(d << 3, 0x00780078u, one);
+        out[1] = and_or_one(d >> 1, 0x00780078u, one);
+        out[2] = and_or_one(d >> 5, 0x00780078u, one);
+        out[3] = and_or_one(d >> 9, 0x00780078u, one);
     }
 };
 
 // 2 bits: one dword = 16 codes = two k-steps; pairs (v, v+8) sit 16 bits apart.
-// Fields sit at mantissa offsets 3 or 5, so four shifted copies serve all 8 pairs.
-template <>
-struct UnpackUnit<2> {
-    static XQ_HD void run(const uint32_t* w, uint32_t* out)
+// Fields sit at mantissa offsets 3 or 5, so two shifted copies serve the 4 pairs of a k-step.
+template <int J>
+struct UnpackKStep<2, J> {
+    static XQ_HD void run(const uint32_t* w, uint32_t one, uint32_t* out)
     {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t d = w[h];
-            const uint32_t a = d << 3;    // codes 0,1 at offsets 3,5
-            const uint32_t b = d >> 1;    // codes 2,3
-            const uint32_t c = d >> 5;    // codes 4,5
-            const uint32_t e = d >> 9;    // codes 6,7
-            out[8 * h + 0] = and_or(a, 0x00180018u, BF16_ONE_PAIR);
-            out[8 * h + 1] = and_or(a, 0x00600060u, BF16_ONE_PAIR);
-            out[8 * h + 2] = and_or(b, 0x00180018u, BF16_ONE_PAIR);
-            out[8 * h + 3] = and_or(b, 0x00600060u, BF16_ONE_PAIR);
-            out[8 * h + 4] = and_or(c, 0x00180018u, BF16_ONE_PAIR);
-            out[8 * h + 5] = and_or(c, 0x00600060u, BF16_ONE_PAIR);
-            out[8 * h + 6] = and_or(e, 0x00180018u, BF16_ONE_PAIR);
-            out[8 * h + 7] = and_or(e, 0x00600060u, BF16_ONE_PAIR);
-        }
+        const uint32_t d = w[J >> 1];
+        const uint32_t a = (J & 1) ? d >> 5 : d << 3;    // codes 0,1 (4,5) at offsets 3,5
+        const uint32_t b = (J & 1) ? d >> 9 : d >> 1;    // codes 2,3 (6,7)
+        out[0] = and_or_one(a, 0x00180018u, one);
+        out[1] = and_or_one(a, 0x00600060u, one);
+        out[2] = and_or_one(b, 0x00180018u, one);
+        out[3] = and_or_one(b, 0x00600060u, one);
     }
 };
 
 // 3 bits: 96 bits in three dwords.  Codes p and p+16 are 48 bits apart, i.e. 16 bits
 // apart once the right halves of two dwords are merged; fields go to offsets 1 or 4.
 // Codes 5, 10, 21, 26 straddle a 16-bit boundary and are fetched with funnel shifts.
-template <>
-struct UnpackUnit<3> {
-    static XQ_HD void run(const uint32_t* w, uint32_t* out)
+//   ea = lo16(d0)|hi16(d1): codes 0-4 | 16-20 at bit 0,3,6,9,12 of each half
+//   eb = lo16(d2)|hi16(d0): codes 22-25 | 6-9  at bit 2,5,8,11
+//   ec = lo16(d1)|hi16(d2): codes 11-15 | 27-31 at bit 1,4,7,10,13
+template <int J>
+struct UnpackKStep<3, J> {
+    static XQ_HD void run(const uint32_t* w, uint32_t one, uint32_t* out)
     {
         const uint32_t d0 = w[0], d1 = w[1], d2 = w[2];
-        const uint32_t ea = (d0 & 0x0000FFFFu) | (d1 & 0xFFFF0000u);   // codes 0-4 | 16-20 at 0,3,6,9,12
-        const uint32_t eb = (d2 & 0x0000FFFFu) | (d0 & 0xFFFF0000u);   // codes 22-25 | 6-9 at 2,5,8,11
-        const uint32_t ec = (d1 & 0x0000FFFFu) | (d2 & 0xFFFF0000u);   // codes 11-15 | 27-31 at 1,4,7,10,13
         const uint32_t M1 = 0x000E000Eu, M4 = 0x00700070u;
-        const uint32_t a0 = ea << 1, a1 = ea >> 5, a2 = ea >> 11;
-        out[0] = and_or(a0, M1, BF16_ONE_PAIR);
-        out[1] = and_or(a0, M4, BF16_ONE_PAIR);
-        out[2] = and_or(a1, M1, BF16_ONE_PAIR);
-        out[3] = and_or(a1, M4, BF16_ONE_PAIR);
-        out[4] = and_or(a2, M1, BF16_ONE_PAIR);
-        const uint32_t b0 = eb >> 1, b1 = eb >> 7;
-        out[5] = and_or(b0, M1, BF16_ONE_PAIR);
-        out[6] = and_or(b0, M4, BF16_ONE_PAIR);
-        out[7] = and_or(b1, M1, BF16_ONE_PAIR);
-        out[8] = and_or(b1, M4, BF16_ONE_PAIR);
-        const uint32_t c1 = ec >> 6, c2 = ec >> 12;
-        out[9] = and_or(ec, M1, BF16_ONE_PAIR);
-        out[10] = and_or(ec, M4, BF16_ONE_PAIR);
-        out[11] = and_or(c1, M1, BF16_ONE_PAIR);
-        out[12] = and_or(c1, M4, BF16_ONE_PAIR);
-        out[13] = and_or(c2, M1, BF16_ONE_PAIR);
-        // code 5 (bits 15-17 of d0) with code 26 (bits 14-16 of d2)
-        const uint32_t x5 = d0 >> 14, y26 = d2 << 3;
-        out[14] = and_or((x5 & 0x0000FFFFu) | (y26 & 0xFFFF0000u), M1, BF16_ONE_PAIR);
-        // code 10 (bits 30-32 of the unit) with code 21 (bits 63-65)
-        const uint32_t x10 = funnel_r(d1, d0, 29), y21 = funnel_r(d2, d1, 14);
-        out[15] = and_or((x10 & 0x0000FFFFu) | (y21 & 0xFFFF0000u), M1, BF16_ONE_PAIR);
+        if (J == 0) {
+            const uint32_t ea = merge16(d0, d1);
+            const uint32_t a0 = ea << 1, a1 = ea >> 5;
+            out[0] = and_or_one(a0, M1, one);
+            out[1] = and_or_one(a0, M4, one);
+            out[2] = and_or_one(a1, M1, one);
+            out[3] = and_or_one(a1, M4, one);
+        } else if (J == 1) {
+            const uint32_t ea = merge16(d0, d1), eb = merge16(d2, d0);
+            const uint32_t b0 = eb >> 1, b1 = eb >> 7;
+            out[0] = and_or_one(ea >> 11, M1, one);
+            out[1] = and_or_one(b0, M1, one);
+            out[2] = and_or_one(b0, M4, one);
+            out[3] = and_or_one(b1, M1, one);
+        } else if (J == 2) {
+            const uint32_t eb = merge16(d2, d0), ec = merge16(d1, d2);
+            const uint32_t c1 = ec >> 6;
+            out[0] = and_or_one(eb >> 7, M4, one);
+            out[1] = and_or_one(ec, M1, one);
+            out[2] = and_or_one(ec, M4, one);
+            out[3] = and_or_one(c1, M1, one);
+        } else {
+            const uint32_t ec = merge16(d1, d2);
+            out[0] = and_or_one(ec >> 6, M4, one);
+            out[1] = and_or_one(ec >> 12, M1, one);
+            // code 5 (bits 15-17 of d0) with code 26 (bits 14-16 of d2)
+            out[2] = and_or_one(merge16(d0 >> 14, d2 << 3), M1, one);
+            // code 10 (bits 30-32 of the unit) with code 21 (bits 63-65)
+            out[3] = and_or_one(merge16(funnel_r(d1, d0, 29), funnel_r(d2, d1, 14)), M1, one);
+        }
+    }
+};
+
+template <int BITS>
+struct UnpackUnit {
+    static XQ_HD void run(const uint32_t* w, uint32_t* out)
+    {
+        UnpackKStep<BITS, 0>::run(w, BF16_ONE_PAIR, out);
+        UnpackKStep<BITS, 1>::run(w, BF16_ONE_PAIR, out + 4);
+        UnpackKStep<BITS, 2>::run(w, BF16_ONE_PAIR, out + 8);
+        UnpackKStep<BITS, 3>::run(w, BF16_ONE_PAIR, out + 12);
     }
 };
 
