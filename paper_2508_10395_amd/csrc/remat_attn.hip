@@ -46,9 +46,9 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int LDS_CODES_OFF = 2 * SLAB_BYTES;           // packed codes of one slab for the tile (<= 16 KiB)
 constexpr int LDS_CODES_BYTES = 16384;
-constexpr int LDS_SCALES_OFF = LDS_CODES_OFF + LDS_CODES_BYTES;   // effective scales, 2 groups x 256 tokens
+constexpr int LDS_SCALES_OFF = LDS_CODES_OFF + LDS_CODES_BYTES;   // effective scales, 2 groups x 256 tokens, x2 buffers
 constexpr int LDS_SCALES_BYTES = 1024;
-constexpr int LDS_TOTAL = LDS_SCALES_OFF + LDS_SCALES_BYTES;
+constexpr int LDS_TOTAL = LDS_SCALES_OFF + 2 * LDS_SCALES_BYTES;
 constexpr int LDS_SCORE_OFF = LDS_CODES_OFF;            // epilogue score scratch reuses the code buffer
 
 struct RematParams {
@@ -293,11 +293,21 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         const int rl = pc / BITS, prt = pc % BITS;
         cvoff[k] = (uint32_t)min(c.tile * TILE_TOKENS + rl, c.len - 1) * row_bytes + prt * 16;
     }
-    auto issue_tokens = [&](int slab) {      // codes + effective scales of main slab `slab`
-        const uint8_t* src = cbase + slab * ROW_SLAB_BYTES;
-        if (wave < NCI) dma_b128(src, cvoff[0], lds_base + LDS_CODES_OFF + wave * 1024);
-        if (wave + 8 < NCI) dma_b128(src, cvoff[1], lds_base + LDS_CODES_OFF + (wave + 8) * 1024);
-        if (wave == 7) dma_b128(ebase + (long long)slab * GPS * 512, dma_voff, lds_base + LDS_SCALES_OFF);
+    // DMA of the next slab is issued piecewise, one instruction at a time between MFMAs (a burst
+    // of ten VMEM instructions per wave at the top of the slab stalls every wave on the address
+    // FIFO).  Steps 0,1: this wave's code pieces; 2: scales (two slabs ahead); 3..10: weight chunks.
+    auto dma_step = [&](int step, int slab_next, bool next_is_main, int slab_next2, bool next2_is_main,
+                        const uint8_t* wnext, uint32_t wdst, int it) {
+        if (step < 2) {
+            if (next_is_main && wave + 8 * step < NCI)
+                dma_b128(cbase + slab_next * ROW_SLAB_BYTES, cvoff[step], lds_base + LDS_CODES_OFF + (wave + 8 * step) * 1024);
+        } else if (step == 2) {
+            if (next2_is_main && wave == 7)
+                dma_b128(ebase + (long long)slab_next2 * GPS * 512, dma_voff,
+                         lds_base + LDS_SCALES_OFF + (uint32_t)((it & 1) * LDS_SCALES_BYTES));
+        } else {
+            dma_b128(wnext + (step - 3) * 8192, dma_voff, wdst + (step - 3) * 8192);
+        }
     };
     // this lane's codes / scales inside the LDS images
     const uint8_t* my_codes[2];
@@ -306,7 +316,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     for (int tb = 0; tb < 2; ++tb) {
         const int rl = c.tq * CHUNK_TOKENS + tb * 32 + tl;
         my_codes[tb] = lds + LDS_CODES_OFF + rl * ROW_SLAB_BYTES + half * (NDW_G * 4);
-        my_scale[tb] = reinterpret_cast<const uint16_t*>(lds + LDS_SCALES_OFF) + rl;
+        my_scale[tb] = reinterpret_cast<const uint16_t*>(lds + LDS_SCALES_OFF) + rl;   // + 512 for the odd buffer
     }
 
     // Workgroups that run side by side on one XCD stream the same head.  Each starts its
@@ -333,7 +343,15 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     uint32_t one = BF16_ONE_PAIR;
     asm volatile("" : "+v"(one));        // keep the constant in a VGPR (operand of v_and_or_b32)
 
-    // pull this lane's share of the landed slab out of LDS: codes and scales
+    // effective scales of the slab processed at iteration `iter` (its buffer is iter & 1)
+    auto fetch_scales = [&](int iter, float (&e)[2][GPS]) {
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int gi = 0; gi < GPS; ++gi)
+                e[tb][gi] = __uint_as_float((uint32_t)my_scale[tb][(iter & 1) * (LDS_SCALES_BYTES / 2) + gi * TILE_TOKENS] << 16);
+    };
+    // pull this lane's codes of the landed slab out of LDS
     auto fetch_tokens = [&]() {
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
@@ -357,17 +375,23 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
 #pragma unroll
                     for (int i = 0; i < NDW_G; ++i) cur[tb][gi * NDW_G + i] = reinterpret_cast<const uint32_t*>(src)[i];
                 }
-                e_cur[tb][gi] = __uint_as_float((uint32_t)my_scale[tb][gi * TILE_TOKENS] << 16);
             }
         }
     };
 
-    // ---- prologue: first slab
+    // ---- prologue: first slab's weights and codes, scales of the first two slabs
     issue_slab(wsrc + (long long)rot * SLAB_BYTES, lds_w, dma_voff);
-    issue_tokens(rot);
+    if (wave < NCI) dma_b128(cbase + rot * ROW_SLAB_BYTES, cvoff[0], lds_base + LDS_CODES_OFF + wave * 1024);
+    if (wave + 8 < NCI) dma_b128(cbase + rot * ROW_SLAB_BYTES, cvoff[1], lds_base + LDS_CODES_OFF + (wave + 8) * 1024);
+    if (wave == 7) {
+        dma_b128(ebase + (long long)rot * GPS * 512, dma_voff, lds_base + LDS_SCALES_OFF);
+        if (p.n_main_slabs > 1)
+            dma_b128(ebase + (long long)main_slab_id(1) * GPS * 512, dma_voff, lds_base + LDS_SCALES_OFF + LDS_SCALES_BYTES);
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     fetch_tokens();
+    fetch_scales(0, e_cur);
     {
         const uint8_t* slab0 = lds + (c.part * 4 * 64 + lane) * 16;
 #pragma unroll
@@ -387,12 +411,15 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         // everyone has finished the previous slab's weight buffer and has taken its codes out of LDS
         __syncthreads();
         const bool more_main = it + 1 < p.n_main_slabs;
+        const bool more_main2 = it + 2 < p.n_main_slabs;
         const int s_next = more_main ? main_slab_id(it + 1) : p.n_main_slabs;   // then the correction slabs
-        if (it + 1 < n_slabs)
-            issue_slab(wsrc + (long long)s_next * SLAB_BYTES, lds_w + (uint32_t)(((it + 1) & 1) * SLAB_BYTES), dma_voff);
-        if (more_main) issue_tokens(s_next);
+        const int s_next2 = more_main2 ? main_slab_id(it + 2) : 0;
+        const bool any_next = it + 1 < n_slabs;
+        const uint8_t* wnext = wsrc + (long long)s_next * SLAB_BYTES;
+        const uint32_t wdst = lds_w + (uint32_t)(((it + 1) & 1) * SLAB_BYTES);
         const uint8_t* slab = lds + (it & 1) * SLAB_BYTES + (c.part * 4 * 64 + lane) * 16;
         const uint8_t* slab_next = lds + ((it + 1) & 1) * SLAB_BYTES + (c.part * 4 * 64 + lane) * 16;
+        float e_nxt[2][GPS];                                 // scales of the next slab (landed one slab ago)
         __builtin_amdgcn_sched_barrier(0);
 
 #pragma unroll
@@ -408,10 +435,21 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                     __builtin_bit_cast(bf16x8, af[par][nb]),
                     as_frag(ub[par][tb][0], ub[par][tb][1], ub[par][tb][2], ub[par][tb][3]), acc[tb][nb], 0, 0, 0);
 
-                // weight fragments of the next k-step (at the slab's end: of the next slab, which has landed)
-                if (tb == 0) {
-                    if (ks + 1 < SLAB_KSTEPS) af[par ^ 1][nb] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + nb) * 1024);
-                    else if (more_main) af[par ^ 1][nb] = *reinterpret_cast<const uint4*>(slab_next + nb * 1024);
+                // DMA of the next slab: 11 steps per wave.  A wave stalls on the address FIFO while it
+                // issues them, so the two waves of a SIMD take turns: the K waves issue theirs during
+                // k-steps 0-1, the V waves during k-steps 2-3, and the partner keeps the MFMA pipe busy.
+                if (ks < 4) {
+                    const int step = (ks & 1) * 8 + m;
+                    if (step < 11 && (ks >> 1) == c.part) {
+                        if (step < 3) dma_step(step, s_next, more_main, s_next2, more_main2, wnext, wdst, it);
+                        else if (any_next) dma_step(step, s_next, more_main, s_next2, more_main2, wnext, wdst, it);
+                    }
+                }
+                // weight fragments of the next k-step (at the slab's end: of the next slab, once it has landed)
+                if (ks + 1 < SLAB_KSTEPS) {
+                    if (tb == 0) af[par ^ 1][nb] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + nb) * 1024);
+                } else if (more_main && m >= 3 && m < 7) {
+                    af[par ^ 1][m - 3] = *reinterpret_cast<const uint4*>(slab_next + (m - 3) * 1024);
                 }
                 // token fragments of the next k-step
                 if (ks + 1 < SLAB_KSTEPS) {
@@ -422,8 +460,10 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                 } else if (m >= 6 && more_main) {           // cur already holds the next slab's codes
                     unpack_kstep<BITS>(&cur[m - 6][0], 0, one, ub[par ^ 1][m - 6]);
                 }
-                // after the last unpack from the old codes: the next slab's data has landed for everyone
-                if (ks == SLAB_KSTEPS - 2 && m == 2) {
+                // the next slab's scales are in LDS since the previous slab
+                if (ks == SLAB_KSTEPS - 2 && m == 4 && more_main) fetch_scales(it + 1, e_nxt);
+                // the old codes are no longer needed: wait until the next slab has landed for everyone
+                if (ks == SLAB_KSTEPS - 1 && m == 2) {
                     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                     __syncthreads();
                     if (more_main) fetch_tokens();
@@ -432,17 +472,23 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                 if (pre && m == 1) {
 #pragma unroll
                     for (int t2 = 0; t2 < 2; ++t2) {
-                        // inside a slab the next group's scale is at hand; at the slab's end e_cur
-                        // was just refilled with the next slab's scales
-                        const float e = (gi + 1 < GPS) ? e_cur[t2][(gi + 1) % GPS] : (more_main ? e_cur[t2][0] : 1.0f);
+                        const float e = (gi + 1 < GPS) ? e_cur[t2][(gi + 1) % GPS] : (more_main ? e_nxt[t2][0] : 1.0f);
                         hr[t2] = e_prev[t2] * __builtin_amdgcn_rcpf(e);
                         e_prev[t2] = e;
                     }
                 }
+                // (the empty asm statements pin the eight multiplies to this slot: pure arithmetic
+                // is otherwise free to drift to the end of the loop body during instruction selection)
                 auto slice = [&](int q) {
                     const int bm = q >> 1, h8 = (q & 1) * 8;
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) acc[bm & 1][bm >> 1][h8 + i] *= hr[bm & 1];
+                    float h = hr[bm & 1];
+                    asm volatile("" : "+v"(h));
+                    f32x16& a = acc[bm & 1][bm >> 1];
+                    float e0 = a[h8 + 0] * h, e1 = a[h8 + 1] * h, e2 = a[h8 + 2] * h, e3 = a[h8 + 3] * h;
+                    float e4 = a[h8 + 4] * h, e5 = a[h8 + 5] * h, e6 = a[h8 + 6] * h, e7 = a[h8 + 7] * h;
+                    asm volatile("" : "+v"(e0), "+v"(e1), "+v"(e2), "+v"(e3), "+v"(e4), "+v"(e5), "+v"(e6), "+v"(e7));
+                    a[h8 + 0] = e0; a[h8 + 1] = e1; a[h8 + 2] = e2; a[h8 + 3] = e3;
+                    a[h8 + 4] = e4; a[h8 + 5] = e5; a[h8 + 6] = e6; a[h8 + 7] = e7;
                 };
                 if (pre && m >= 2) slice(m - 2);
                 if (post && !(it == 0 && ks == 0)) {
@@ -451,6 +497,12 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
+        }
+        if (more_main) {
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int gi = 0; gi < GPS; ++gi) e_cur[tb][gi] = e_nxt[tb][gi];
         }
     }
 
