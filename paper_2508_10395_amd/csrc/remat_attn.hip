@@ -49,7 +49,6 @@ constexpr int LDS_CODES_BYTES = 16384;
 constexpr int LDS_SCALES_OFF = LDS_CODES_OFF + LDS_CODES_BYTES;   // effective scales, 2 groups x 256 tokens, x2 buffers
 constexpr int LDS_SCALES_BYTES = 1024;
 constexpr int LDS_TOTAL = LDS_SCALES_OFF + 2 * LDS_SCALES_BYTES;
-constexpr int LDS_SCORE_OFF = LDS_CODES_OFF;            // epilogue score scratch reuses the code buffer
 
 struct RematParams {
     const uint16_t* q;       // [B][Hq][128]
@@ -59,6 +58,7 @@ struct RematParams {
     const uint16_t* acc;     // dense source
     const uint8_t* wprep;
     const uint16_t* eT;      // coded source: effective scales [B][tiles][ng (+1 pad)][256], bf16
+    const uint16_t* negE;    // coded source: minus the effective scales, token-major [B][tiles*256][ng], bf16
     float* part_o;           // [B][Hq][chunks_per_seq][128]
     float* part_ml;          // [B][Hq][chunks_per_seq][2]
     int B, cap, d, Hq, Hkv;
@@ -85,17 +85,6 @@ __device__ __forceinline__ void issue_slab(const uint8_t* src, uint32_t lds_dst,
 {
 #pragma unroll
     for (int c = 0; c < 8; ++c) dma_b128(src + c * 8192, voff, lds_dst + c * 8192);
-}
-
-// packed pair of stored scales -> packed pair of -e (bf16), e = 2^bits * scale or 1 for a zero scale
-__device__ __forceinline__ uint32_t neg_eff_scale_pair(uint32_t pair, int bits)
-{
-    const uint32_t add = ((uint32_t)bits << 7) * 0x00010001u;
-    uint32_t lo = pair & 0xFFFFu, hi = pair >> 16;
-    uint32_t r = pair + add;
-    if (!lo) r = (r & 0xFFFF0000u) | 0x3F80u;
-    if (!hi) r = (r & 0x0000FFFFu) | 0x3F800000u;
-    return r | 0x80008000u;
 }
 
 __device__ __forceinline__ bf16x8 as_frag(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
@@ -136,10 +125,10 @@ __device__ __forceinline__ void unpack_kstep(const uint32_t* unit, int j, uint32
     }
 }
 
-// which tile this workgroup owns
+// which tile this workgroup owns, and this lane's place in it
 struct TileCtx {
-    int hk, b, tile, len, tq, part, half, tl, lane, wave;
-    int tok[2];
+    int hk, b, tile, len, half, tl, lane, wave;
+    int tok;       // this lane's token (tile * 256 + wave * 32 + lane % 32), may lie past len
 };
 
 __device__ __forceinline__ bool locate_tile(const RematParams& p, TileCtx& c)
@@ -147,8 +136,6 @@ __device__ __forceinline__ bool locate_tile(const RematParams& p, TileCtx& c)
     const int tid = threadIdx.x;
     c.lane = tid & 63;
     c.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    c.part = c.wave >> 2;          // 0: K columns, 1: V columns
-    c.tq = c.wave & 3;             // which 64 tokens of the tile
     c.half = c.lane >> 5;
     c.tl = c.lane & 31;
     // workgroup -> (KV head, sequence, tile); heads are dealt so that the workgroups
@@ -166,83 +153,56 @@ __device__ __forceinline__ bool locate_tile(const RematParams& p, TileCtx& c)
     c.b = tile_lin / p.tiles_per_seq;
     c.tile = tile_lin % p.tiles_per_seq;
     c.len = p.len.v[c.b];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) c.tok[tb] = c.tile * TILE_TOKENS + c.tq * CHUNK_TOKENS + tb * 32 + c.tl;
+    c.tok = c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS + c.tl;
     return c.tile * TILE_TOKENS < c.len;
 }
 
-// ---- attention on the rematerialised tile.  Accumulator element i of column block nb
-// <-> output column n = 32 nb + 8 (i/4) + 4 half + i%4, token = lane % 32 (+32 tb).
-__device__ __forceinline__ void attention_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[2][4],
-                                                   uint8_t* lds)
+// ---- attention on the rematerialised chunk: each wave holds K (blocks 0-3) and V (blocks 4-7)
+// of its 32 tokens.  Accumulator element i of column block nb <-> column 32 (nb%4) + 8 (i/4) +
+// 4 half + i%4 of K or V, token = lane % 32.  No LDS and no barrier: scores, softmax weights and
+// the weighted sum of V stay inside the wave; it emits one partial (m, l, o[128]) per query head.
+__device__ __forceinline__ void attention_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8])
 {
-    __syncthreads();                                   // the contraction's LDS traffic is over
-    float* sc_lds = reinterpret_cast<float*>(lds + LDS_SCORE_OFF);     // [4 tq][gq][64]
+    if (c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS >= c.len) return;     // chunk entirely past len
     const int gq = p.Hq / p.Hkv;
-    const int chunk = c.tile * 4 + c.tq;
-    const bool chunk_live = c.tile * TILE_TOKENS + c.tq * CHUNK_TOKENS < c.len;
-
-    if (c.part == 0) {
-        for (int j = 0; j < gq; ++j) {
-            const uint16_t* qv = p.q + ((long long)c.b * p.Hq + c.hk * gq + j) * 128;
-            float dot[2] = {0.0f, 0.0f};
+    const int chunk = c.tile * (TILE_TOKENS / CHUNK_TOKENS) + c.wave;
+    for (int j = 0; j < gq; ++j) {
+        const int hq = c.hk * gq + j;
+        const uint16_t* qv = p.q + ((long long)c.b * p.Hq + hq) * 128;
+        float dot = 0.0f;
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
+        for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    const uint2 qq = *reinterpret_cast<const uint2*>(qv + nb * 32 + i4 * 8 + c.half * 4);
-                    const float q0 = bf16_lo_to_f32(qq.x), q1 = bf16_hi_to_f32(qq.x);
-                    const float q2 = bf16_lo_to_f32(qq.y), q3 = bf16_hi_to_f32(qq.y);
-#pragma unroll
-                    for (int tb = 0; tb < 2; ++tb) {
-                        dot[tb] = __builtin_fmaf(q0, acc[tb][nb][i4 * 4 + 0], dot[tb]);
-                        dot[tb] = __builtin_fmaf(q1, acc[tb][nb][i4 * 4 + 1], dot[tb]);
-                        dot[tb] = __builtin_fmaf(q2, acc[tb][nb][i4 * 4 + 2], dot[tb]);
-                        dot[tb] = __builtin_fmaf(q3, acc[tb][nb][i4 * 4 + 3], dot[tb]);
-                    }
-                }
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
-                float sfull = dot[tb] + __shfl_xor(dot[tb], 32);
-                sfull = c.tok[tb] < c.len ? sfull * p.scale_log2e : -INFINITY;
-                if (c.half == 0) sc_lds[(c.tq * gq + j) * 64 + tb * 32 + c.tl] = sfull;
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const uint2 qq = *reinterpret_cast<const uint2*>(qv + nb * 32 + i4 * 8 + c.half * 4);
+                dot = __builtin_fmaf(bf16_lo_to_f32(qq.x), acc[nb][i4 * 4 + 0], dot);
+                dot = __builtin_fmaf(bf16_hi_to_f32(qq.x), acc[nb][i4 * 4 + 1], dot);
+                dot = __builtin_fmaf(bf16_lo_to_f32(qq.y), acc[nb][i4 * 4 + 2], dot);
+                dot = __builtin_fmaf(bf16_hi_to_f32(qq.y), acc[nb][i4 * 4 + 3], dot);
             }
-        }
-    }
-    __syncthreads();
-    if (c.part == 1 && chunk_live) {
-        for (int j = 0; j < gq; ++j) {
-            const int hq = c.hk * gq + j;
-            float sv[2], pv[2];
+        float sc = dot + __shfl_xor(dot, 32);
+        sc = c.tok < c.len ? sc * p.scale_log2e : -INFINITY;
+        const float m = wave32_max(sc);
+        const float pv = __builtin_amdgcn_exp2f(sc - m);
+        const float l = wave32_sum(pv);
+        const long long pidx = ((long long)c.b * p.Hq + hq) * p.chunks_per_seq + chunk;
+        float* po = p.part_o + pidx * 128;
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) sv[tb] = sc_lds[(c.tq * gq + j) * 64 + tb * 32 + c.tl];
-            const float m = wave32_max(fmaxf(sv[0], sv[1]));
+        for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) pv[tb] = __builtin_amdgcn_exp2f(sv[tb] - m);
-            const float l = wave32_sum(pv[0] + pv[1]);
-            const long long pidx = ((long long)c.b * p.Hq + hq) * p.chunks_per_seq + chunk;
-            float* po = p.part_o + pidx * 128;
+            for (int i4 = 0; i4 < 4; ++i4) {
+                float o[4];
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    float o[4];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        // masked tokens have p = 0 and their rows are clamped copies: always finite
-                        float v = pv[0] * acc[0][nb][i4 * 4 + k];
-                        v = __builtin_fmaf(pv[1], acc[1][nb][i4 * 4 + k], v);
-                        o[k] = wave32_sum(v);
-                    }
-                    if (c.tl == 0) {
-                        float4 w; w.x = o[0]; w.y = o[1]; w.z = o[2]; w.w = o[3];
-                        *reinterpret_cast<float4*>(po + nb * 32 + i4 * 8 + c.half * 4) = w;
-                    }
+                for (int k = 0; k < 4; ++k)   // masked tokens have p = 0 and their rows are clamped copies: finite
+                    o[k] = wave32_sum(pv * acc[4 + nb][i4 * 4 + k]);
+                if (c.tl == 0) {
+                    float4 w; w.x = o[0]; w.y = o[1]; w.z = o[2]; w.w = o[3];
+                    *reinterpret_cast<float4*>(po + nb * 32 + i4 * 8 + c.half * 4) = w;
                 }
-            if (c.lane == 0) {
-                p.part_ml[pidx * 2] = m;
-                p.part_ml[pidx * 2 + 1] = l;
             }
+        if (c.lane == 0) {
+            p.part_ml[pidx * 2] = m;
+            p.part_ml[pidx * 2 + 1] = l;
         }
     }
 }
@@ -264,25 +224,24 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     TileCtx c;
     if (!locate_tile(p, c)) return;
     const int lane = c.lane, wave = c.wave, half = c.half, tl = c.tl;
+    const int dma_turn = wave >> 2;                    // the two waves of a SIMD take turns issuing DMA
 
     const int n_corr_slabs = (p.n_corr_ksteps + SLAB_KSTEPS - 1) / SLAB_KSTEPS;
-    const int n_slabs = p.n_main_slabs + n_corr_slabs;
     const uint8_t* wsrc = p.wprep + (long long)c.hk * p.head_bytes + wave * 1024;   // this wave's DMA share
     const uint32_t dma_voff = (uint32_t)lane * 16u;
     const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds;
     const uint32_t lds_w = lds_base + wave * 1024;
+    const uint8_t* my_slab = lds + lane * 16;          // + buffer * SLAB_BYTES + (ks * 8 + nb) * 1024
 
     // ---- token-side sources
     const long long seq_row0 = (long long)c.b * p.cap;
     const uint32_t row_bytes = (uint32_t)(p.d * BITS / 8);
     const uint8_t* cbase = p.codes + seq_row0 * row_bytes;
-    const uint16_t* sbase = p.scale + seq_row0 * p.ng;
+    const uint16_t* nbase = p.negE + (long long)c.b * p.tiles_per_seq * TILE_TOKENS * p.ng;   // minus the effective scales
     const uint16_t* zbase = p.zero + seq_row0 * p.ng;
     const uint8_t* ebase = reinterpret_cast<const uint8_t*>(p.eT) +
                            ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.ng + 1) * 512;
-    uint32_t moff[2];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) moff[tb] = (uint32_t)min(c.tok[tb], c.len - 1) * (uint32_t)p.ng;
+    const uint32_t moff = (uint32_t)min(c.tok, c.len - 1) * (uint32_t)p.ng;
 
     // code DMA: 16-byte piece pc of the tile's slab image = (row pc / BITS, part pc % BITS);
     // wave instruction i covers pieces [64 i, 64 i + 64); this wave issues i = wave and wave + 8
@@ -293,31 +252,10 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         const int rl = pc / BITS, prt = pc % BITS;
         cvoff[k] = (uint32_t)min(c.tile * TILE_TOKENS + rl, c.len - 1) * row_bytes + prt * 16;
     }
-    // DMA of the next slab is issued piecewise, one instruction at a time between MFMAs (a burst
-    // of ten VMEM instructions per wave at the top of the slab stalls every wave on the address
-    // FIFO).  Steps 0,1: this wave's code pieces; 2: scales (two slabs ahead); 3..10: weight chunks.
-    auto dma_step = [&](int step, int slab_next, bool next_is_main, int slab_next2, bool next2_is_main,
-                        const uint8_t* wnext, uint32_t wdst, int it) {
-        if (step < 2) {
-            if (next_is_main && wave + 8 * step < NCI)
-                dma_b128(cbase + slab_next * ROW_SLAB_BYTES, cvoff[step], lds_base + LDS_CODES_OFF + (wave + 8 * step) * 1024);
-        } else if (step == 2) {
-            if (next2_is_main && wave == 7)
-                dma_b128(ebase + (long long)slab_next2 * GPS * 512, dma_voff,
-                         lds_base + LDS_SCALES_OFF + (uint32_t)((it & 1) * LDS_SCALES_BYTES));
-        } else {
-            dma_b128(wnext + (step - 3) * 8192, dma_voff, wdst + (step - 3) * 8192);
-        }
-    };
     // this lane's codes / scales inside the LDS images
-    const uint8_t* my_codes[2];
-    const uint16_t* my_scale[2];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        const int rl = c.tq * CHUNK_TOKENS + tb * 32 + tl;
-        my_codes[tb] = lds + LDS_CODES_OFF + rl * ROW_SLAB_BYTES + half * (NDW_G * 4);
-        my_scale[tb] = reinterpret_cast<const uint16_t*>(lds + LDS_SCALES_OFF) + rl;   // + 512 for the odd buffer
-    }
+    const int my_row = wave * CHUNK_TOKENS + tl;
+    const uint8_t* my_codes = lds + LDS_CODES_OFF + my_row * ROW_SLAB_BYTES + half * (NDW_G * 4);
+    const uint16_t* my_scale = reinterpret_cast<const uint16_t*>(lds + LDS_SCALES_OFF) + my_row;
 
     // Workgroups that run side by side on one XCD stream the same head.  Each starts its
     // contraction at a different slab (the sum over groups is order-free), so that at any
@@ -325,101 +263,166 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     const int rot = (int)((blockIdx.x >> 3) % (unsigned)p.n_main_slabs);
     auto main_slab_id = [&](int it) { const int s = it + rot; return s >= p.n_main_slabs ? s - p.n_main_slabs : s; };
 
-    f32x16 acc[2][4];
+    f32x16 acc[8];                       // [column block]: 0-3 K, 4-7 V
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
+    for (int nb = 0; nb < 8; ++nb)
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[tb][nb][i] = 0.0f;
+        for (int i = 0; i < 16; ++i) acc[nb][i] = 0.0f;
 
     // MFMA operands, double-buffered by k-step parity
-    uint4 af[2][4];                      // weight fragments [parity][column block]
-    uint32_t ub[2][2][4];                // token fragments  [parity][token block][dword]
-    uint32_t cur[2][NDW];                // packed codes of the current slab
-    float e_cur[2][GPS];                 // effective scales of the current slab's groups
-    float e_prev[2] = {1.0f, 1.0f};      // e of the group the accumulator is currently scaled by
-    float hr[2] = {1.0f, 1.0f};          // pending Horner factor e_prev / e_next
+    uint4 af[2][8];                      // weight fragments [parity][column block]
+    uint32_t ub[2][4];                   // token fragment   [parity][dword]
+    uint32_t cur[NDW];                   // packed codes of the current slab
+    float e_cur[GPS];                    // effective scales of the current slab's groups
+    float e_prev = 1.0f;                 // e of the group the accumulator is currently scaled by
+    float hr = 1.0f;                     // pending Horner factor e_prev / e_next
     uint32_t one = BF16_ONE_PAIR;
     asm volatile("" : "+v"(one));        // keep the constant in a VGPR (operand of v_and_or_b32)
 
-    // effective scales of the slab processed at iteration `iter` (its buffer is iter & 1)
-    auto fetch_scales = [&](int iter, float (&e)[2][GPS]) {
+    // effective scales of the slab processed at main iteration `iter` (its buffer is iter & 1)
+    auto fetch_scales = [&](int iter, float (&e)[GPS]) {
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int gi = 0; gi < GPS; ++gi)
-                e[tb][gi] = __uint_as_float((uint32_t)my_scale[tb][(iter & 1) * (LDS_SCALES_BYTES / 2) + gi * TILE_TOKENS] << 16);
+        for (int gi = 0; gi < GPS; ++gi)
+            e[gi] = __uint_as_float((uint32_t)my_scale[(iter & 1) * (LDS_SCALES_BYTES / 2) + gi * TILE_TOKENS] << 16);
     };
     // pull this lane's codes of the landed slab out of LDS
     auto fetch_tokens = [&]() {
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
+        for (int gi = 0; gi < GPS; ++gi) {
+            const uint8_t* src = my_codes + gi * (2 * NDW_G * 4);
+            if constexpr (NDW_G % 4 == 0) {
 #pragma unroll
-            for (int gi = 0; gi < GPS; ++gi) {
-                const uint8_t* src = my_codes[tb] + gi * (2 * NDW_G * 4);
-                if constexpr (NDW_G % 4 == 0) {
-#pragma unroll
-                    for (int i = 0; i < NDW_G / 4; ++i) {
-                        const uint4 v = reinterpret_cast<const uint4*>(src)[i];
-                        cur[tb][gi * NDW_G + 4 * i] = v.x; cur[tb][gi * NDW_G + 4 * i + 1] = v.y;
-                        cur[tb][gi * NDW_G + 4 * i + 2] = v.z; cur[tb][gi * NDW_G + 4 * i + 3] = v.w;
-                    }
-                } else if constexpr (NDW_G % 2 == 0) {
-#pragma unroll
-                    for (int i = 0; i < NDW_G / 2; ++i) {
-                        const uint2 v = reinterpret_cast<const uint2*>(src)[i];
-                        cur[tb][gi * NDW_G + 2 * i] = v.x; cur[tb][gi * NDW_G + 2 * i + 1] = v.y;
-                    }
-                } else {
-#pragma unroll
-                    for (int i = 0; i < NDW_G; ++i) cur[tb][gi * NDW_G + i] = reinterpret_cast<const uint32_t*>(src)[i];
+                for (int i = 0; i < NDW_G / 4; ++i) {
+                    const uint4 v = reinterpret_cast<const uint4*>(src)[i];
+                    cur[gi * NDW_G + 4 * i] = v.x; cur[gi * NDW_G + 4 * i + 1] = v.y;
+                    cur[gi * NDW_G + 4 * i + 2] = v.z; cur[gi * NDW_G + 4 * i + 3] = v.w;
                 }
+            } else if constexpr (NDW_G % 2 == 0) {
+#pragma unroll
+                for (int i = 0; i < NDW_G / 2; ++i) {
+                    const uint2 v = reinterpret_cast<const uint2*>(src)[i];
+                    cur[gi * NDW_G + 2 * i] = v.x; cur[gi * NDW_G + 2 * i + 1] = v.y;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < NDW_G; ++i) cur[gi * NDW_G + i] = reinterpret_cast<const uint32_t*>(src)[i];
             }
         }
     };
+    // one piece of the DMA that brings in main slab `slab` (weights to `wdst`): steps 0,1 this wave's
+    // code pieces, 2 its scales (wave 7; `slab2` = the slab after it, into scale buffer `sbuf`), 3..10
+    // the weight chunks
+    auto dma_step = [&](int step, int slab, bool with_tokens, int slab2, bool with_scales2, int sbuf, uint32_t wdst) {
+        if (step < 2) {
+            if (with_tokens && wave + 8 * step < NCI)
+                dma_b128(cbase + slab * ROW_SLAB_BYTES, cvoff[step], lds_base + LDS_CODES_OFF + (wave + 8 * step) * 1024);
+        } else if (step == 2) {
+            if (with_scales2 && wave == 7)
+                dma_b128(ebase + (long long)slab2 * GPS * 512, dma_voff, lds_base + LDS_SCALES_OFF + (uint32_t)(sbuf * LDS_SCALES_BYTES));
+        } else {
+            dma_b128(wsrc + (long long)slab * SLAB_BYTES + (step - 3) * 8192, dma_voff, wdst + (step - 3) * 8192);
+        }
+    };
 
-    // ---- prologue: first slab's weights and codes, scales of the first two slabs
-    issue_slab(wsrc + (long long)rot * SLAB_BYTES, lds_w, dma_voff);
-    if (wave < NCI) dma_b128(cbase + rot * ROW_SLAB_BYTES, cvoff[0], lds_base + LDS_CODES_OFF + wave * 1024);
-    if (wave + 8 < NCI) dma_b128(cbase + rot * ROW_SLAB_BYTES, cvoff[1], lds_base + LDS_CODES_OFF + (wave + 8) * 1024);
-    if (wave == 7) {
-        dma_b128(ebase + (long long)rot * GPS * 512, dma_voff, lds_base + LDS_SCALES_OFF);
-        if (p.n_main_slabs > 1)
-            dma_b128(ebase + (long long)main_slab_id(1) * GPS * 512, dma_voff, lds_base + LDS_SCALES_OFF + LDS_SCALES_BYTES);
+    // ==== phase 1: the zero-point / offset correction (scale 1), a few k-steps whose token-side
+    // operands are the stored zero-points and minus the effective scales.  Its operands are loaded
+    // first thing, so their latency hides behind the first weight DMA.
+    const bool vec_meta = (p.ng & 7) == 0;
+    auto load_meta = [&](int kk) -> uint4 {
+        const int kappa0 = kk * 16 + half * 8;
+        const int term = kappa0 / p.ng_pad, g0 = kappa0 % p.ng_pad;
+        const uint16_t* mbase = term < 2 ? zbase : nbase;
+        uint4 v = {0u, 0u, 0u, 0u};
+        if (kk < p.n_corr_ksteps && term < N_CORR_TERMS) {
+            if (vec_meta) {
+                v = *reinterpret_cast<const uint4*>(mbase + moff + g0);
+            } else {
+                uint32_t h[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int g = g0 + i;
+                    const uint32_t x = mbase[moff + min(g, p.ng - 1)];
+                    h[i] = g < p.ng ? x : 0u;               // padding groups contribute nothing
+                }
+                v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16);
+                v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
+            }
+        }
+        return v;
+    };
+    issue_slab(wsrc + (long long)p.n_main_slabs * SLAB_BYTES, lds_w, dma_voff);        // correction slab 0 -> buffer 0
+    uint4 mfr[SLAB_KSTEPS];
+#pragma unroll
+    for (int ks = 0; ks < SLAB_KSTEPS; ++ks) mfr[ks] = load_meta(ks);
+    for (int cs = 0; cs < n_corr_slabs; ++cs) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        const uint32_t wdst = lds_w + (uint32_t)(((cs + 1) & 1) * SLAB_BYTES);
+        if (cs + 1 < n_corr_slabs) {
+            issue_slab(wsrc + (long long)(p.n_main_slabs + cs + 1) * SLAB_BYTES, wdst, dma_voff);
+        } else {   // the first main slab with its codes and scales, and the scales of the second
+            issue_slab(wsrc + (long long)rot * SLAB_BYTES, wdst, dma_voff);
+            dma_step(0, rot, true, 0, false, 0, 0);
+            dma_step(1, rot, true, 0, false, 0, 0);
+            dma_step(2, 0, false, rot, true, 0, 0);
+            if (p.n_main_slabs > 1) dma_step(2, 0, false, main_slab_id(1), true, 1, 0);
+        }
+        const uint8_t* slab = my_slab + (cs & 1) * SLAB_BYTES;
+        const int nks = min(SLAB_KSTEPS, p.n_corr_ksteps - cs * SLAB_KSTEPS);
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) af[0][nb] = *reinterpret_cast<const uint4*>(slab + nb * 1024);
+#pragma unroll
+        for (int ks = 0; ks < SLAB_KSTEPS; ++ks) {
+            if (ks < nks) {
+                const int par = ks & 1;
+#pragma unroll
+                for (int nb = 0; nb < 8; ++nb) {
+                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[par][nb]),
+                                                                       __builtin_bit_cast(bf16x8, mfr[ks]), acc[nb], 0, 0, 0);
+                    if (ks + 1 < SLAB_KSTEPS)
+                        af[par ^ 1][nb] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + nb) * 1024);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        if (cs + 1 < n_corr_slabs) {
+#pragma unroll
+            for (int ks = 0; ks < SLAB_KSTEPS; ++ks) mfr[ks] = load_meta((cs + 1) * SLAB_KSTEPS + ks);
+        }
     }
+
+    // ==== phase 2: the d x 256 contraction.  First main slab: take codes, scales and fragments out
+    // of LDS and bring the accumulator (now holding the correction, in units of 1) to its scale.
+    const int par0 = n_corr_slabs & 1;                 // weight buffer of main iteration 0
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     fetch_tokens();
     fetch_scales(0, e_cur);
     {
-        const uint8_t* slab0 = lds + (c.part * 4 * 64 + lane) * 16;
+        const uint8_t* slab0 = my_slab + par0 * SLAB_BYTES;
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb) af[0][nb] = *reinterpret_cast<const uint4*>(slab0 + nb * 1024);
+        for (int nb = 0; nb < 8; ++nb) af[0][nb] = *reinterpret_cast<const uint4*>(slab0 + nb * 1024);
+        e_prev = e_cur[0];
+        const float r0 = __builtin_amdgcn_rcpf(e_prev);
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            e_prev[tb] = e_cur[tb][0];
-            unpack_kstep<BITS>(&cur[tb][0], 0, one, ub[0][tb]);
-        }
+        for (int nb = 0; nb < 8; ++nb) acc[nb] *= r0;
+        unpack_kstep<BITS>(&cur[0], 0, one, ub[0]);
     }
 
-    // ---- main slabs: the d x 256 contraction.  A k-step is 8 slots of one MFMA each
-    // (column block nb = slot/2, token block tb = slot%2); the VALU/LDS work that feeds
-    // later slots is spread over the slots and pinned there with scheduling fences so that
+    // A k-step is 8 slots of one MFMA each (slot = column block); the VALU/LDS/DMA work that
+    // feeds later slots is spread over the slots and pinned there with scheduling fences so that
     // it runs in the shadow of the MFMAs.
     for (int it = 0; it < p.n_main_slabs; ++it) {
         // everyone has finished the previous slab's weight buffer and has taken its codes out of LDS
         __syncthreads();
         const bool more_main = it + 1 < p.n_main_slabs;
         const bool more_main2 = it + 2 < p.n_main_slabs;
-        const int s_next = more_main ? main_slab_id(it + 1) : p.n_main_slabs;   // then the correction slabs
+        const int s_next = more_main ? main_slab_id(it + 1) : 0;
         const int s_next2 = more_main2 ? main_slab_id(it + 2) : 0;
-        const bool any_next = it + 1 < n_slabs;
-        const uint8_t* wnext = wsrc + (long long)s_next * SLAB_BYTES;
-        const uint32_t wdst = lds_w + (uint32_t)(((it + 1) & 1) * SLAB_BYTES);
-        const uint8_t* slab = lds + (it & 1) * SLAB_BYTES + (c.part * 4 * 64 + lane) * 16;
-        const uint8_t* slab_next = lds + ((it + 1) & 1) * SLAB_BYTES + (c.part * 4 * 64 + lane) * 16;
-        float e_nxt[2][GPS];                                 // scales of the next slab (landed one slab ago)
+        const uint32_t wdst = lds_w + (uint32_t)(((it + 1 + par0) & 1) * SLAB_BYTES);
+        const uint8_t* slab = my_slab + ((it + par0) & 1) * SLAB_BYTES;
+        const uint8_t* slab_next = my_slab + ((it + 1 + par0) & 1) * SLAB_BYTES;
+        float e_nxt[GPS];                                    // scales of the next slab (landed one slab ago)
         __builtin_amdgcn_sched_barrier(0);
 
 #pragma unroll
@@ -430,60 +433,55 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
             const bool post = ksg == 0;                    // first k-step of a group: finish rescaling
 #pragma unroll
             for (int m = 0; m < 8; ++m) {
-                const int nb = m >> 1, tb = m & 1;
-                acc[tb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8, af[par][nb]),
-                    as_frag(ub[par][tb][0], ub[par][tb][1], ub[par][tb][2], ub[par][tb][3]), acc[tb][nb], 0, 0, 0);
+                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, af[par][m]), as_frag(ub[par][0], ub[par][1], ub[par][2], ub[par][3]),
+                    acc[m], 0, 0, 0);
 
                 // DMA of the next slab: 11 steps per wave.  A wave stalls on the address FIFO while it
-                // issues them, so the two waves of a SIMD take turns: the K waves issue theirs during
-                // k-steps 0-1, the V waves during k-steps 2-3, and the partner keeps the MFMA pipe busy.
-                if (ks < 4) {
+                // issues them, so the two waves of a SIMD take turns (k-steps 0-1 / 2-3) and the
+                // partner keeps the MFMA pipe busy.
+                if (ks < 4 && more_main) {
                     const int step = (ks & 1) * 8 + m;
-                    if (step < 11 && (ks >> 1) == c.part) {
-                        if (step < 3) dma_step(step, s_next, more_main, s_next2, more_main2, wnext, wdst, it);
-                        else if (any_next) dma_step(step, s_next, more_main, s_next2, more_main2, wnext, wdst, it);
-                    }
+                    if (step < 11 && (ks >> 1) == dma_turn)
+                        dma_step(step, s_next, true, s_next2, more_main2, it & 1, wdst);
                 }
-                // weight fragments of the next k-step (at the slab's end: of the next slab, once it has landed)
+                // weight fragment of the next k-step (at the slab's end: of the next slab, once it has landed)
+                if (ks + 1 < SLAB_KSTEPS) af[par ^ 1][m] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + m) * 1024);
+                // token fragment of the next k-step
                 if (ks + 1 < SLAB_KSTEPS) {
-                    if (tb == 0) af[par ^ 1][nb] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + nb) * 1024);
-                } else if (more_main && m >= 3 && m < 7) {
-                    af[par ^ 1][m - 3] = *reinterpret_cast<const uint4*>(slab_next + (m - 3) * 1024);
-                }
-                // token fragments of the next k-step
-                if (ks + 1 < SLAB_KSTEPS) {
-                    if (m < 2) {
+                    if (m == 0) {
                         const int gi1 = (ks + 1) / KSG, ksg1 = (ks + 1) % KSG;
-                        unpack_kstep<BITS>(&cur[m][gi1 * NDW_G + (ksg1 >> 2) * BITS], ksg1, one, ub[par ^ 1][m]);
+                        unpack_kstep<BITS>(&cur[gi1 * NDW_G + (ksg1 >> 2) * BITS], ksg1, one, ub[par ^ 1]);
                     }
-                } else if (m >= 6 && more_main) {           // cur already holds the next slab's codes
-                    unpack_kstep<BITS>(&cur[m - 6][0], 0, one, ub[par ^ 1][m - 6]);
+                } else if (m == 7 && more_main) {            // cur already holds the next slab's codes
+                    unpack_kstep<BITS>(&cur[0], 0, one, ub[par ^ 1]);
                 }
                 // the next slab's scales are in LDS since the previous slab
                 if (ks == SLAB_KSTEPS - 2 && m == 4 && more_main) fetch_scales(it + 1, e_nxt);
-                // the old codes are no longer needed: wait until the next slab has landed for everyone
-                if (ks == SLAB_KSTEPS - 1 && m == 2) {
+                // the old codes are no longer needed: wait until the next slab has landed for everyone,
+                // then take the next slab's codes and first fragments
+                if (ks == SLAB_KSTEPS - 1 && m == 1) {
                     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                     __syncthreads();
-                    if (more_main) fetch_tokens();
+                    if (more_main) {
+                        fetch_tokens();
+#pragma unroll
+                        for (int nb = 0; nb < 8; ++nb) af[par ^ 1][nb] = *reinterpret_cast<const uint4*>(slab_next + nb * 1024);
+                    }
                 }
                 // Horner rescale of the accumulator to the next group's scale, 8 registers a slice
                 if (pre && m == 1) {
-#pragma unroll
-                    for (int t2 = 0; t2 < 2; ++t2) {
-                        const float e = (gi + 1 < GPS) ? e_cur[t2][(gi + 1) % GPS] : (more_main ? e_nxt[t2][0] : 1.0f);
-                        hr[t2] = e_prev[t2] * __builtin_amdgcn_rcpf(e);
-                        e_prev[t2] = e;
-                    }
+                    const float e = (gi + 1 < GPS) ? e_cur[(gi + 1) % GPS] : (more_main ? e_nxt[0] : 1.0f);
+                    hr = e_prev * __builtin_amdgcn_rcpf(e);
+                    e_prev = e;
                 }
                 // (the empty asm statements pin the eight multiplies to this slot: pure arithmetic
                 // is otherwise free to drift to the end of the loop body during instruction selection)
                 auto slice = [&](int q) {
-                    const int bm = q >> 1, h8 = (q & 1) * 8;
-                    float h = hr[bm & 1];
+                    const int h8 = (q & 1) * 8;
+                    float h = hr;
                     asm volatile("" : "+v"(h));
-                    f32x16& a = acc[bm & 1][bm >> 1];
+                    f32x16& a = acc[q >> 1];
                     float e0 = a[h8 + 0] * h, e1 = a[h8 + 1] * h, e2 = a[h8 + 2] * h, e3 = a[h8 + 3] * h;
                     float e4 = a[h8 + 4] * h, e5 = a[h8 + 5] * h, e6 = a[h8 + 6] * h, e7 = a[h8 + 7] * h;
                     asm volatile("" : "+v"(e0), "+v"(e1), "+v"(e2), "+v"(e3), "+v"(e4), "+v"(e5), "+v"(e6), "+v"(e7));
@@ -500,98 +498,17 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         }
         if (more_main) {
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int gi = 0; gi < GPS; ++gi) e_cur[tb][gi] = e_nxt[tb][gi];
+            for (int gi = 0; gi < GPS; ++gi) e_cur[gi] = e_nxt[gi];
         }
     }
-
-    // ---- correction slabs: token-side operands are the stored zero-points / minus the scales
-    // the accumulator is in units of 1 after the last boundary's rescale; finish its slices
+    // the last boundary rescaled towards e = 1: finish its slices, the accumulator is K | V
 #pragma unroll
     for (int q = 6; q < 16; ++q) {
-        const int bm = q >> 1, h8 = (q & 1) * 8;
+        const int h8 = (q & 1) * 8;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[bm & 1][bm >> 1][h8 + i] *= hr[bm & 1];
+        for (int i = 0; i < 8; ++i) acc[q >> 1][h8 + i] *= hr;
     }
-    const bool vec_meta = (p.ng & 7) == 0;
-    // B-side fragment of correction k-step kk for token block tb (raw metadata; transformed at use)
-    auto load_meta = [&](int kk, int tb) -> uint4 {
-        const int kappa0 = kk * 16 + half * 8;
-        const int term = kappa0 / p.ng_pad, g0 = kappa0 % p.ng_pad;
-        const uint16_t* mbase = term < 2 ? zbase : sbase;
-        uint4 v = {0u, 0u, 0u, 0u};
-        if (kk < p.n_corr_ksteps && term < N_CORR_TERMS) {
-            if (vec_meta) {
-                v = *reinterpret_cast<const uint4*>(mbase + moff[tb] + g0);
-            } else {
-                uint32_t h[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int g = g0 + i;
-                    const uint32_t x = mbase[moff[tb] + min(g, p.ng - 1)];
-                    h[i] = g < p.ng ? x : 0u;                   // padding groups: see meta_frag
-                }
-                v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16);
-                v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
-            }
-        }
-        return v;
-    };
-    auto meta_frag = [&](int kk, uint4 raw) -> bf16x8 {
-        const int kappa0 = kk * 16 + half * 8;
-        const int term = kappa0 / p.ng_pad, g0 = kappa0 % p.ng_pad;
-        if (term >= 2 && term < N_CORR_TERMS) {
-            raw.x = neg_eff_scale_pair(raw.x, BITS); raw.y = neg_eff_scale_pair(raw.y, BITS);
-            raw.z = neg_eff_scale_pair(raw.z, BITS); raw.w = neg_eff_scale_pair(raw.w, BITS);
-            if (!vec_meta) {   // padding groups past ng contribute nothing
-                uint32_t* r = reinterpret_cast<uint32_t*>(&raw);
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if (g0 + i >= p.ng) r[i >> 1] &= (i & 1) ? 0x0000FFFFu : 0xFFFF0000u;
-            }
-        } else if (term >= N_CORR_TERMS) {
-            raw = uint4{0u, 0u, 0u, 0u};
-        }
-        return __builtin_bit_cast(bf16x8, raw);
-    };
-    constexpr int PF = 4;                      // prefetch distance in k-steps
-    uint4 mring[PF][2];
-#pragma unroll
-    for (int i = 0; i < PF; ++i)
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) mring[i][tb] = load_meta(i, tb);
-
-    for (int s = p.n_main_slabs; s < n_slabs; ++s) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (s + 1 < n_slabs)
-            issue_slab(wsrc + (long long)(s + 1) * SLAB_BYTES, lds_w + (uint32_t)(((s + 1) & 1) * SLAB_BYTES), dma_voff);
-        const uint8_t* slab = lds + (s & 1) * SLAB_BYTES + (c.part * 4 * 64 + lane) * 16;
-        const int kk0 = (s - p.n_main_slabs) * SLAB_KSTEPS;
-        const int nks = min(SLAB_KSTEPS, p.n_corr_ksteps - kk0);
-#pragma unroll 1
-        for (int ks = 0; ks < nks; ++ks) {
-            const int kk = kk0 + ks;
-            bf16x8 bfrag[2];
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
-                bfrag[tb] = meta_frag(kk, mring[0][tb]);
-#pragma unroll
-                for (int i = 0; i + 1 < PF; ++i) mring[i][tb] = mring[i + 1][tb];
-                mring[PF - 1][tb] = load_meta(kk + PF, tb);
-            }
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb) {
-                const bf16x8 a = __builtin_bit_cast(
-                    bf16x8, *reinterpret_cast<const uint4*>(slab + (ks * 8 + nb) * 1024));
-                acc[0][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bfrag[0], acc[0][nb], 0, 0, 0);
-                acc[1][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bfrag[1], acc[1][nb], 0, 0, 0);
-            }
-        }
-    }
-
-    attention_epilogue(p, c, acc, lds);
+    attention_epilogue(p, c, acc);
 }
 
 // =====================================================================================
@@ -608,30 +525,25 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
     const uint8_t* wsrc = p.wprep + (long long)c.hk * p.head_bytes + wave * 1024;
     const uint32_t dma_voff = (uint32_t)lane * 16u;
     const uint32_t lds_w = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds + wave * 1024;
+    const uint8_t* my_slab = lds + lane * 16;
     const uint8_t* cbase = reinterpret_cast<const uint8_t*>(p.acc) + (long long)c.b * p.cap * p.d * 2;
-    uint32_t coff[2];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) coff[tb] = (uint32_t)min(c.tok[tb], c.len - 1) * (uint32_t)(p.d * 2) + half * 128;
+    const uint32_t coff = (uint32_t)min(c.tok, c.len - 1) * (uint32_t)(p.d * 2) + half * 128;
 
     const int rot = (int)((blockIdx.x >> 3) % (unsigned)p.n_main_slabs);
     auto main_slab_id = [&](int it) { const int s = it + rot; return s >= p.n_main_slabs ? s - p.n_main_slabs : s; };
 
-    f32x16 acc[2][4];
+    f32x16 acc[8];
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
+    for (int nb = 0; nb < 8; ++nb)
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[tb][nb][i] = 0.0f;
+        for (int i = 0; i < 16; ++i) acc[nb][i] = 0.0f;
 
-    uint4 af[2][4];
-    uint4 bd[2][8];                      // one slab of token fragments per token block (ring)
+    uint4 af[2][8];
+    uint4 bd[8];                         // one slab of token fragments (ring)
 
     issue_slab(wsrc + (long long)rot * SLAB_BYTES, lds_w, dma_voff);
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) bd[tb][ks] = reinterpret_cast<const uint4*>(cbase + coff[tb] + rot * 256)[ks];
+    for (int ks = 0; ks < 8; ++ks) bd[ks] = reinterpret_cast<const uint4*>(cbase + coff + rot * 256)[ks];
 
     for (int it = 0; it < p.n_main_slabs; ++it) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -640,35 +552,35 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
         const int s_next = more_main ? main_slab_id(it + 1) : 0;
         if (more_main)
             issue_slab(wsrc + (long long)s_next * SLAB_BYTES, lds_w + (uint32_t)(((it + 1) & 1) * SLAB_BYTES), dma_voff);
-        const uint8_t* slab = lds + (it & 1) * SLAB_BYTES + (c.part * 4 * 64 + lane) * 16;
+        const uint8_t* slab = my_slab + (it & 1) * SLAB_BYTES;
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb) af[0][nb] = *reinterpret_cast<const uint4*>(slab + nb * 1024);
+        for (int nb = 0; nb < 8; ++nb) af[0][nb] = *reinterpret_cast<const uint4*>(slab + nb * 1024);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < SLAB_KSTEPS; ++ks) {
             const int par = ks & 1;
 #pragma unroll
             for (int m = 0; m < 8; ++m) {
-                const int nb = m >> 1, tb = m & 1;
-                acc[tb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8, af[par][nb]), __builtin_bit_cast(bf16x8, bd[tb][ks]), acc[tb][nb], 0, 0, 0);
-                if (ks + 1 < SLAB_KSTEPS && tb == 0)
-                    af[par ^ 1][nb] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + nb) * 1024);
+                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, af[par][m]), __builtin_bit_cast(bf16x8, bd[ks]), acc[m], 0, 0, 0);
+                if (ks + 1 < SLAB_KSTEPS)
+                    af[par ^ 1][m] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + m) * 1024);
                 // the fragment is consumed by its last column block: refill the ring slot for the next slab
-                if (nb == 3 && more_main)
-                    bd[tb][ks] = reinterpret_cast<const uint4*>(cbase + coff[tb] + s_next * 256)[ks];
+                if (m == 7 && more_main) bd[ks] = reinterpret_cast<const uint4*>(cbase + coff + s_next * 256)[ks];
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
-    attention_epilogue(p, c, acc, lds);
+    attention_epilogue(p, c, acc);
 }
 
 // ---- pre-pass of the coded kernel: effective scales e = 2^bits * scale (1 for a zero scale)
 // as bf16, laid out [sequence][tile][group (+1 pad)][256 tokens] so that a tile's scales of
-// one group are contiguous.  Tokens past len repeat the last row.
+// one group are contiguous (tokens past len repeat the last row), and -e token-major
+// [sequence][row][group] as the ready-made operand of the zero-scale correction.
 __global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __restrict__ scale,
-                                                              uint16_t* __restrict__ eT, int cap, int ng,
+                                                              uint16_t* __restrict__ eT,
+                                                              uint16_t* __restrict__ negE, int cap, int ng,
                                                               int tiles_per_seq, int bits, BatchI32 len)
 {
     const int tile = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
@@ -678,7 +590,10 @@ __global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __
     uint16_t* dst = eT + ((long long)b * tiles_per_seq + tile) * (long long)(ng + 1) * TILE_TOKENS + t;
     for (int g = 0; g < ng; ++g) {
         const uint32_t sb = scale[row * ng + g];
-        dst[(long long)g * TILE_TOKENS] = (uint16_t)(sb ? sb + ((uint32_t)bits << 7) : 0x3F80u);
+        const uint32_t e = sb ? sb + ((uint32_t)bits << 7) : 0x3F80u;
+        dst[(long long)g * TILE_TOKENS] = (uint16_t)e;
+        if (tile * TILE_TOKENS + t < L)
+            negE[(((long long)b * tiles_per_seq + tile) * TILE_TOKENS + t) * ng + g] = (uint16_t)(e | 0x8000u);
     }
     dst[(long long)ng * TILE_TOKENS] = 0x3F80u;       // pad group (fetched, never used)
 }
@@ -715,10 +630,14 @@ static hipError_t launch_with_lds(K kernel, const RematParams& p, int grid, hipS
 
 size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool coded)
 {
+    const size_t cap_rows = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS * TILE_TOKENS;   // negE rows per sequence
     const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
     const size_t chunks = tiles * (TILE_TOKENS / CHUNK_TOKENS);
     size_t bytes = (size_t)B * Hq * chunks * (128 + 2) * sizeof(float);
-    if (coded) bytes += (size_t)B * tiles * (size_t)(d / group + 1) * TILE_TOKENS * sizeof(uint16_t);
+    if (coded) {
+        bytes += (size_t)B * tiles * (size_t)(d / group + 1) * TILE_TOKENS * sizeof(uint16_t);   // eT
+        bytes += (size_t)B * cap_rows * (size_t)(d / group) * sizeof(uint16_t);                  // negE
+    }
     return bytes;
 }
 
@@ -746,13 +665,15 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
     p.part_o = static_cast<float*>(ws);
     p.part_ml = p.part_o + (size_t)B * p.Hq * p.chunks_per_seq * 128;
     uint16_t* eT = reinterpret_cast<uint16_t*>(p.part_ml + (size_t)B * p.Hq * p.chunks_per_seq * 2);
+    uint16_t* negE = eT + (size_t)B * p.tiles_per_seq * (size_t)(L.ng + 1) * TILE_TOKENS;
     p.eT = eT;
+    p.negE = negE;
 
     const int grid = p.Hkv * p.B * p.tiles_per_seq;
     hipError_t e = hipErrorInvalidValue;
     if (xc) {
         scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
-            xc->scale, eT, cap, L.ng, p.tiles_per_seq, bits, len);
+            xc->scale, eT, negE, cap, L.ng, p.tiles_per_seq, bits, len);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -15,7 +15,7 @@
 // Correction slabs (coded sources only) hold, for contraction index
 // kappa = 16 kk + 8 half + i, term = kappa / ng_pad, group g = kappa % ng_pad:
 //   term 0,1: bf16 hi, lo parts of S_g[n]  = sum of the group's weight rows
-//   term 2..4: bf16 hi, mid, lo parts of S'_g[n] = sum of the scaled weight rows
+//   term 2,3: bf16 hi, lo parts of S'_g[n] = sum of the scaled weight rows
 // against which the kernel multiplies the zero-points and minus the scales.
 #pragma once
 #include <stddef.h>
@@ -25,9 +25,9 @@ namespace xq {
 
 constexpr int SLAB_KSTEPS = 8;
 constexpr int SLAB_BYTES = 65536;
-constexpr int N_CORR_TERMS = 5;
+constexpr int N_CORR_TERMS = 4;
 constexpr int TILE_TOKENS = 256;     // tokens per workgroup
-constexpr int CHUNK_TOKENS = 64;     // tokens per wave = one softmax partial
+constexpr int CHUNK_TOKENS = 32;     // tokens per wave = one softmax partial
 
 struct WPrepLayout {
     int d, G, bits, Hkv;
