@@ -51,9 +51,14 @@ __global__ __launch_bounds__(256) void pack_main_kernel(PrepArgs a)
     const int s = blockIdx.x, h = blockIdx.y;
     const bool dense = a.bits == 16;
     const int ksg_n = a.G / 16;
+    const int n_ksteps = a.n_main_slabs * SLAB_KSTEPS;
     for (int f = threadIdx.x; f < SLAB_KSTEPS * 8 * 64; f += blockDim.x) {
         const int lane = f & 63, nb = (f >> 6) & 7, ks = f >> 9;
         const int half = lane >> 5, n = nb * 32 + (lane & 31);
+        // coded sources: position (slab s, tick ks, block nb) holds k-step 8 s + ks - (7 - nb), cyclically
+        int kappa = s * SLAB_KSTEPS + ks - (COL_BLOCK_LAG_MAX - nb);
+        if (kappa < 0) kappa += n_ksteps;
+        const int cs_ = kappa / SLAB_KSTEPS, cks = kappa % SLAB_KSTEPS;
         uint32_t v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -61,10 +66,10 @@ __global__ __launch_bounds__(256) void pack_main_kernel(PrepArgs a)
             if (dense) {
                 c = s * 128 + half * 64 + ks * 8 + i;
             } else {
-                const int gi = ks / ksg_n, ksg = ks % ksg_n;
+                const int gi = cks / ksg_n, ksg = cks % ksg_n;
                 const int u = ksg >> 2, j = ksg & 3;
                 const int p = a.tab.code_of_slot[j][i];
-                c = s * 128 + gi * a.G + half * (a.G / 2) + u * 32 + p;
+                c = cs_ * 128 + gi * a.G + half * (a.G / 2) + u * 32 + p;
                 e = a.tab.wexp_of_code[p];
             }
             v[i] = f32_to_bf16_rne(ldexpf(wval(a, h, c, n), e));   // exact: power-of-two scaling

@@ -2,13 +2,12 @@
 // cost model of Sec. 3.4 in arxiv 2508.10395), plus the split-context combine.
 //
 // One workgroup (8 waves) owns a tile of 256 cached tokens of one (sequence, KV
-// head).  Wave w handles tokens [64 (w%4), +64) of the tile and the K columns
-// (w < 4) or the V columns (w >= 4) of [Wk_h | Wv_h]: a 128 x 64 fp32 accumulator
-// block = 128 VGPRs, computed as D[n][t] = sum_c W[c][n] * x^[t][c] with
-// v_mfma_f32_32x32x16_bf16, weights as the A operand (streamed HBM -> LDS as
-// prepared 64 KiB slabs, double buffered) and tokens along the lanes of the B
-// operand, so that everything per token (its scales, its score, its softmax weight)
-// is a per-lane scalar.
+// head).  Wave w handles tokens [32 w, 32 w + 32) of the tile and all 256 columns of
+// [Wk_h | Wv_h]: eight 32 x 32 fp32 accumulator blocks = 128 VGPRs, computed as
+// D[n][t] = sum_c W[c][n] * x^[t][c] with v_mfma_f32_32x32x16_bf16, weights as the A
+// operand (streamed HBM -> LDS as prepared 64 KiB slabs, double buffered) and tokens
+// along the lanes of the B operand, so that everything per token (its codes, its
+// scales, its score, its softmax weight) is a per-lane scalar and is unpacked once.
 //
 // The cached codes are not dequantised to bf16 (that rounding alone would exceed
 // the 2e-3 budget): the codes are dropped into bf16 mantissas (1 + code*2^(o-7),
@@ -18,11 +17,11 @@
 //     K[n][t] = sum_g e_g P_g[n]  +  sum_g ( zero_g S_g[n] - e_g S'_g[n] ).
 // The first sum is carried in one accumulator by rescaling it with e_{g-1}/e_g at
 // each group boundary (Horner form, one v_mul per register per group, relative
-// error ~2^-23 per group); the second is a rank-(5 d/G) product done by a few extra
-// MFMA k-steps whose token-side operands are the stored zero-points and scales
-// (exact in bf16) and whose weight-side operands are 2- and 3-way bf16 splits of
-// the column sums.  A zero stored scale uses e_g = 1 (its codes are all zero, so
-// only the column-sum term matters and it cancels exactly as for any other e_g).
+// error ~2^-23 per group); the second is a rank-(4 d/G) product done by a few extra
+// MFMA k-steps whose token-side operands are the stored zero-points and minus the
+// effective scales (exact in bf16) and whose weight-side operands are bf16 hi/lo
+// splits of the column sums.  A zero stored scale uses e_g = 1 (its codes are all
+// zero, so only the column-sum term matters and it cancels exactly as for any e_g).
 //
 // Data movement of the coded kernel: everything the contraction loop consumes
 // arrives by LDS-DMA (global_load_lds): the weight slab, the tile's packed codes of
@@ -31,24 +30,51 @@
 // pre-pass, so that they are contiguous).  The loop therefore contains no
 // compiler-visible global load, and one explicit s_waitcnt vmcnt(0) per slab.
 //
-// After the contraction the K waves form the scores q.K[t] for each query head of
-// the KV group, hand them to the V waves through LDS, and each V wave emits one
-// online-softmax partial (m, l, o[128]) per query head for its 64 tokens.  A second
-// small kernel merges the partials of a sequence in fixed order.
+// After the contraction each wave holds K (blocks 0-3) and V (blocks 4-7) of its 32
+// tokens, forms the scores q.K[t] for each query head of the KV group, and emits one
+// online-softmax partial (m, l, o[128]) per query head and 32-token chunk without
+// leaving the wave.  A second small kernel merges the partials of a sequence in
+// fixed order.
+#include <type_traits>
+
 #include "common.hpp"
 #include "remat_layout.hpp"
 #include "unpack.hpp"
 
 namespace xq {
 
+constexpr int floordiv_c(int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
+
+// f(integral_constant<int, I>) for I = BEGIN .. END-1, unrolled by construction: the contraction
+// loop indexes register arrays with these values, so they must be compile-time constants
+template <int BEGIN, int END, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (BEGIN < END) {
+        f(std::integral_constant<int, BEGIN>{});
+        static_for<BEGIN + 1, END>(f);
+    }
+}
+#define XQ_INLINE_LAMBDA __attribute__((always_inline))
+
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int LDS_CODES_OFF = 2 * SLAB_BYTES;           // packed codes of one slab for the tile (<= 16 KiB)
-constexpr int LDS_CODES_BYTES = 16384;
-constexpr int LDS_SCALES_OFF = LDS_CODES_OFF + LDS_CODES_BYTES;   // effective scales, 2 groups x 256 tokens, x2 buffers
+// LDS: two weight slabs, then (coded sources) the tile's packed codes of one slab -- two such
+// images when they fit, so that no barrier is needed between taking one slab's codes out and the
+// arrival of the next-but-one's -- then three 1 KiB buffers of effective scales (2 groups x 256
+// tokens each; the third is used once, for the slab the lagging column blocks start in)
+constexpr int LDS_CODES_OFF = 2 * SLAB_BYTES;
 constexpr int LDS_SCALES_BYTES = 1024;
-constexpr int LDS_TOTAL = LDS_SCALES_OFF + 2 * LDS_SCALES_BYTES;
+constexpr int LDS_MAX = 160 * 1024;
+constexpr int code_image_bytes(int bits) { return TILE_TOKENS * 16 * bits; }
+constexpr int n_code_images(int bits)
+{
+    return LDS_CODES_OFF + 2 * code_image_bytes(bits) + 3 * LDS_SCALES_BYTES <= LDS_MAX ? 2 : 1;
+}
+constexpr int lds_scales_off(int bits) { return LDS_CODES_OFF + n_code_images(bits) * code_image_bytes(bits); }
+constexpr int lds_coded_total(int bits) { return lds_scales_off(bits) + 3 * LDS_SCALES_BYTES; }
+constexpr int LDS_DENSE_TOTAL = 2 * SLAB_BYTES;
 
 struct RematParams {
     const uint16_t* q;       // [B][Hq][128]
@@ -76,8 +102,12 @@ struct RematParams {
 // used by these kernels.
 __device__ __forceinline__ void dma_b128(const void* saddr, uint32_t voff, uint32_t lds_dst)
 {
+    const uint64_t a = reinterpret_cast<uint64_t>(saddr);      // wave-uniform by construction
+    const uint32_t a_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));   // (the builtin
+    const uint32_t a_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);           //  returns int)
+    const uint64_t ua = ((uint64_t)a_hi << 32) | (uint64_t)a_lo;
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(saddr), "s"(lds_dst) : "memory");
+                 :: "v"(voff), "s"(ua), "s"(lds_dst) : "memory");
 }
 
 // one 64 KiB weight slab: 8 DMA instructions per wave (src / lds_dst already offset by the wave's 1 KiB)
@@ -150,8 +180,11 @@ __device__ __forceinline__ bool locate_tile(const RematParams& p, TileCtx& c)
         c.hk = blockIdx.x / NT;
         tile_lin = blockIdx.x % NT;
     }
-    c.b = tile_lin / p.tiles_per_seq;
-    c.tile = tile_lin % p.tiles_per_seq;
+    // (runtime divisions are done on the vector ALU: bring the wave-uniform results back to scalar
+    // registers, or every address derived from them would live in vector registers)
+    c.hk = __builtin_amdgcn_readfirstlane(c.hk);
+    c.b = __builtin_amdgcn_readfirstlane(tile_lin / p.tiles_per_seq);
+    c.tile = __builtin_amdgcn_readfirstlane(tile_lin % p.tiles_per_seq);
     c.len = p.len.v[c.b];
     c.tok = c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS + c.tl;
     return c.tile * TILE_TOKENS < c.len;
@@ -219,6 +252,9 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     constexpr int NDW = GPS * NDW_G;                   // ... per slab (= 2 BITS)
     constexpr int ROW_SLAB_BYTES = 16 * BITS;          // packed bytes of 128 channels of one token
     constexpr int NCI = 4 * BITS;                      // code-DMA wave instructions per slab per workgroup
+    constexpr int IMG_BYTES = code_image_bytes(BITS);
+    constexpr int NIMG = n_code_images(BITS);
+    constexpr int LDS_SCALES_OFF = lds_scales_off(BITS);
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     TileCtx c;
@@ -260,7 +296,8 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     // Workgroups that run side by side on one XCD stream the same head.  Each starts its
     // contraction at a different slab (the sum over groups is order-free), so that at any
     // moment they pull different addresses and the requests spread over all L2 channels.
-    const int rot = (int)((blockIdx.x >> 3) % (unsigned)p.n_main_slabs);
+    // (the runtime modulo is done on the vector ALU; readfirstlane returns it to a scalar register)
+    const int rot = __builtin_amdgcn_readfirstlane((int)((blockIdx.x >> 3) % (unsigned)p.n_main_slabs));
     auto main_slab_id = [&](int it) { const int s = it + rot; return s >= p.n_main_slabs ? s - p.n_main_slabs : s; };
 
     f32x16 acc[8];                       // [column block]: 0-3 K, 4-7 V
@@ -269,27 +306,27 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[nb][i] = 0.0f;
 
-    // MFMA operands, double-buffered by k-step parity
-    uint4 af[2][8];                      // weight fragments [parity][column block]
-    uint32_t ub[2][4];                   // token fragment   [parity][dword]
+    // MFMA operands
+    constexpr int NB = 2 * GPS - 1;      // kinds of group boundary a slab's ticks can see
+    uint4 af[8];                         // weight fragments, ring over slots (loaded 7 slots ahead)
+    uint32_t ub[8][4];                   // token fragments, ring over k-steps
     uint32_t cur[NDW];                   // packed codes of the current slab
-    float e_cur[GPS];                    // effective scales of the current slab's groups
-    float e_prev = 1.0f;                 // e of the group the accumulator is currently scaled by
-    float hr = 1.0f;                     // pending Horner factor e_prev / e_next
+    float E[2 * GPS];                    // effective scales: groups of the previous slab, then of the current one
+    float hr_b[NB];                      // Horner factors E[k] / E[k+1] of the boundaries seen this slab
     uint32_t one = BF16_ONE_PAIR;
     asm volatile("" : "+v"(one));        // keep the constant in a VGPR (operand of v_and_or_b32)
 
     // effective scales of the slab processed at main iteration `iter` (its buffer is iter & 1)
-    auto fetch_scales = [&](int iter, float (&e)[GPS]) {
+    auto fetch_scales = [&](int sbuf, float* e) {
 #pragma unroll
         for (int gi = 0; gi < GPS; ++gi)
-            e[gi] = __uint_as_float((uint32_t)my_scale[(iter & 1) * (LDS_SCALES_BYTES / 2) + gi * TILE_TOKENS] << 16);
+            e[gi] = __uint_as_float((uint32_t)my_scale[sbuf * (LDS_SCALES_BYTES / 2) + gi * TILE_TOKENS] << 16);
     };
     // pull this lane's codes of the landed slab out of LDS
-    auto fetch_tokens = [&]() {
+    auto fetch_tokens = [&](int img) {
 #pragma unroll
         for (int gi = 0; gi < GPS; ++gi) {
-            const uint8_t* src = my_codes + gi * (2 * NDW_G * 4);
+            const uint8_t* src = my_codes + img * IMG_BYTES + gi * (2 * NDW_G * 4);
             if constexpr (NDW_G % 4 == 0) {
 #pragma unroll
                 for (int i = 0; i < NDW_G / 4; ++i) {
@@ -310,12 +347,13 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         }
     };
     // one piece of the DMA that brings in main slab `slab` (weights to `wdst`): steps 0,1 this wave's
-    // code pieces, 2 its scales (wave 7; `slab2` = the slab after it, into scale buffer `sbuf`), 3..10
-    // the weight chunks
-    auto dma_step = [&](int step, int slab, bool with_tokens, int slab2, bool with_scales2, int sbuf, uint32_t wdst) {
+    // code pieces (to code image `img`), 2 scales (wave 7; of slab `slab2`, into scale buffer `sbuf`),
+    // 3..10 the weight chunks
+    auto dma_step = [&](int step, int slab, int img, int slab2, bool with_scales2, int sbuf, uint32_t wdst) {
         if (step < 2) {
-            if (with_tokens && wave + 8 * step < NCI)
-                dma_b128(cbase + slab * ROW_SLAB_BYTES, cvoff[step], lds_base + LDS_CODES_OFF + (wave + 8 * step) * 1024);
+            if (wave + 8 * step < NCI)
+                dma_b128(cbase + slab * ROW_SLAB_BYTES, cvoff[step],
+                         lds_base + LDS_CODES_OFF + (uint32_t)(img * IMG_BYTES) + (wave + 8 * step) * 1024);
         } else if (step == 2) {
             if (with_scales2 && wave == 7)
                 dma_b128(ebase + (long long)slab2 * GPS * 512, dma_voff, lds_base + LDS_SCALES_OFF + (uint32_t)(sbuf * LDS_SCALES_BYTES));
@@ -326,7 +364,9 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
 
     // ==== phase 1: the zero-point / offset correction (scale 1), a few k-steps whose token-side
     // operands are the stored zero-points and minus the effective scales.  Its operands are loaded
-    // first thing, so their latency hides behind the first weight DMA.
+    // first thing, so their latency hides behind the first weight DMA.  The codes and scales of the
+    // slab that cyclically precedes the first one arrive meanwhile: the lagging column blocks start
+    // inside it (see phase 2).
     const bool vec_meta = (p.ng & 7) == 0;
     auto load_meta = [&](int kk) -> uint4 {
         const int kappa0 = kk * 16 + half * 8;
@@ -350,7 +390,17 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         }
         return v;
     };
+    const int slab_prev = rot == 0 ? p.n_main_slabs - 1 : rot - 1;
     issue_slab(wsrc + (long long)p.n_main_slabs * SLAB_BYTES, lds_w, dma_voff);        // correction slab 0 -> buffer 0
+    dma_step(0, slab_prev, NIMG - 1, 0, false, 0, 0);                                  // predecessor codes -> last image
+    dma_step(1, slab_prev, NIMG - 1, 0, false, 0, 0);
+    dma_step(2, 0, 0, slab_prev, true, 2, 0);                                          // its scales -> scale buffer 2
+    dma_step(2, 0, 0, rot, true, 0, 0);                                                // first slab's scales -> buffer 0
+    if (p.n_main_slabs > 1) dma_step(2, 0, 0, main_slab_id(1), true, 1, 0);            // second slab's -> buffer 1
+    if constexpr (NIMG == 2) {                                                         // first slab's codes -> image 0
+        dma_step(0, rot, 0, 0, false, 0, 0);
+        dma_step(1, rot, 0, 0, false, 0, 0);
+    }
     uint4 mfr[SLAB_KSTEPS];
 #pragma unroll
     for (int ks = 0; ks < SLAB_KSTEPS; ++ks) mfr[ks] = load_meta(ks);
@@ -358,30 +408,35 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         const uint32_t wdst = lds_w + (uint32_t)(((cs + 1) & 1) * SLAB_BYTES);
-        if (cs + 1 < n_corr_slabs) {
-            issue_slab(wsrc + (long long)(p.n_main_slabs + cs + 1) * SLAB_BYTES, wdst, dma_voff);
-        } else {   // the first main slab with its codes and scales, and the scales of the second
-            issue_slab(wsrc + (long long)rot * SLAB_BYTES, wdst, dma_voff);
-            dma_step(0, rot, true, 0, false, 0, 0);
-            dma_step(1, rot, true, 0, false, 0, 0);
-            dma_step(2, 0, false, rot, true, 0, 0);
-            if (p.n_main_slabs > 1) dma_step(2, 0, false, main_slab_id(1), true, 1, 0);
+        if (cs + 1 < n_corr_slabs) issue_slab(wsrc + (long long)(p.n_main_slabs + cs + 1) * SLAB_BYTES, wdst, dma_voff);
+        else issue_slab(wsrc + (long long)rot * SLAB_BYTES, wdst, dma_voff);           // the first main slab
+        if (cs == 0) {
+            fetch_tokens(NIMG - 1);
+            fetch_scales(2, &E[0]);
         }
         const uint8_t* slab = my_slab + (cs & 1) * SLAB_BYTES;
         const int nks = min(SLAB_KSTEPS, p.n_corr_ksteps - cs * SLAB_KSTEPS);
 #pragma unroll
-        for (int nb = 0; nb < 8; ++nb) af[0][nb] = *reinterpret_cast<const uint4*>(slab + nb * 1024);
+        for (int nb = 0; nb < 8; ++nb) af[nb] = *reinterpret_cast<const uint4*>(slab + nb * 1024);
 #pragma unroll
         for (int ks = 0; ks < SLAB_KSTEPS; ++ks) {
             if (ks < nks) {
-                const int par = ks & 1;
 #pragma unroll
                 for (int nb = 0; nb < 8; ++nb) {
-                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[par][nb]),
+                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[nb]),
                                                                        __builtin_bit_cast(bf16x8, mfr[ks]), acc[nb], 0, 0, 0);
                     if (ks + 1 < SLAB_KSTEPS)
-                        af[par ^ 1][nb] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + nb) * 1024);
+                        af[nb] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + nb) * 1024);
                     __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if constexpr (NIMG == 1) {
+                if (ks == 0 && cs == 0) {
+                    // every wave now holds its predecessor codes in registers: the first slab's
+                    // codes may overwrite the only image
+                    __syncthreads();
+                    dma_step(0, rot, 0, 0, false, 0, 0);
+                    dma_step(1, rot, 0, 0, false, 0, 0);
                 }
             }
         }
@@ -391,30 +446,91 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         }
     }
 
-    // ==== phase 2: the d x 256 contraction.  First main slab: take codes, scales and fragments out
-    // of LDS and bring the accumulator (now holding the correction, in units of 1) to its scale.
+    // ==== phase 2: the d x 256 contraction, as a cyclic walk over the d/16 k-steps that starts
+    // at slab `rot`.  Column block j runs 7 - j k-steps behind the walk: at tick tau it multiplies
+    // the weights of k-step tau - 7 + j (the prepared stream is laid out in this order) with the
+    // token fragment unpacked 7 - j ticks ago, which waits in an 8-deep ring.  The group
+    // boundaries of the eight blocks therefore fall on different ticks, and the Horner rescale
+    // of the accumulator (16 multiplies per block and boundary) spreads evenly over the loop
+    // instead of piling up at the slab boundary, where every wave would do it at once.
+    //
+    // Set-up: the ring's lagging fragments are k-steps 1..7 of the predecessor slab, whose group
+    // scales E[0..GPS) the lagging blocks start from; the accumulators (holding the correction in
+    // units of 1) are brought to those scales.
+#pragma unroll
+    for (int ks = 1; ks < SLAB_KSTEPS; ++ks)
+        unpack_kstep<BITS>(&cur[(ks / KSG) * NDW_G + ((ks % KSG) >> 2) * BITS], ks % KSG, one, ub[ks]);
     const int par0 = n_corr_slabs & 1;                 // weight buffer of main iteration 0
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    fetch_tokens();
-    fetch_scales(0, e_cur);
+    fetch_tokens(0);
+    fetch_scales(0, &E[GPS]);
     {
         const uint8_t* slab0 = my_slab + par0 * SLAB_BYTES;
 #pragma unroll
-        for (int nb = 0; nb < 8; ++nb) af[0][nb] = *reinterpret_cast<const uint4*>(slab0 + nb * 1024);
-        e_prev = e_cur[0];
-        const float r0 = __builtin_amdgcn_rcpf(e_prev);
+        for (int sl = 0; sl < 7; ++sl) af[sl] = *reinterpret_cast<const uint4*>(slab0 + sl * 1024);
 #pragma unroll
-        for (int nb = 0; nb < 8; ++nb) acc[nb] *= r0;
+        for (int j = 0; j < 8; ++j) {
+            const float r0 = __builtin_amdgcn_rcpf(E[floordiv_c(j - 8, KSG) + GPS]);
+            acc[j] *= r0;
+        }
+#pragma unroll
+        for (int k = 0; k < NB; ++k) hr_b[k] = E[k] * __builtin_amdgcn_rcpf(E[k + 1]);
         unpack_kstep<BITS>(&cur[0], 0, one, ub[0]);
     }
 
-    // A k-step is 8 slots of one MFMA each (slot = column block); the VALU/LDS/DMA work that
-    // feeds later slots is spread over the slots and pinned there with scheduling fences so that
-    // it runs in the shadow of the MFMAs.
+    // Multiplies chunk CIDX (of 3,3,3,3,2,2 registers) of one block's accumulator by h.  The empty
+    // asm statements pin the multiplies between the neighbouring scheduling fences: pure
+    // arithmetic is otherwise free to drift during instruction selection.
+    auto rescale_chunk = [&](f32x16& a, auto CIDX, float h) XQ_INLINE_LAMBDA {
+        constexpr int cidx = decltype(CIDX)::value;
+        constexpr int off = cidx < 4 ? 3 * cidx : 12 + 2 * (cidx - 4);
+        float x0 = a[off], x1 = a[off + 1];
+        if constexpr (cidx < 4) {
+            float x2 = a[off + 2];
+            asm volatile("" : "+v"(x0), "+v"(x1), "+v"(x2));
+            x0 *= h; x1 *= h; x2 *= h;
+            asm volatile("" : "+v"(x0), "+v"(x1), "+v"(x2));
+            a[off + 2] = x2;
+        } else {
+            asm volatile("" : "+v"(x0), "+v"(x1));
+            x0 *= h; x1 *= h;
+            asm volatile("" : "+v"(x0), "+v"(x1));
+        }
+        a[off] = x0; a[off + 1] = x1;
+    };
+    // The rescale work of slot SIDX (= 8 tick + block, may name the tail of the previous slab):
+    // a block whose MFMA 1..6 slots ahead is the first of a group gets one chunk done now.
+    auto horner_slot = [&](auto SIDX, const float (&hcur)[NB], const float (&hnext)[NB], auto DO_CUR, bool have_next)
+                           XQ_INLINE_LAMBDA {
+        static_for<1, 7>([&](auto DELTA) XQ_INLINE_LAMBDA {
+            constexpr int delta = decltype(DELTA)::value;
+            constexpr int t = decltype(SIDX)::value + delta;
+            constexpr int jt = t & 7;
+            constexpr int kp = ((t >> 3) & 7) - 7 + jt;    // k-step, relative to the slab of its tick
+            if constexpr (floordiv_c(kp, KSG) * KSG == kp) {
+                constexpr int kind = floordiv_c(kp, KSG) + GPS - 1;
+                if constexpr (t < 64) {
+                    if constexpr (decltype(DO_CUR)::value) rescale_chunk(acc[jt], std::integral_constant<int, 6 - delta>{}, hcur[kind]);
+                } else {
+                    if (have_next) rescale_chunk(acc[jt], std::integral_constant<int, 6 - delta>{}, hnext[kind]);
+                }
+            }
+        });
+    };
+    // boundaries in the first slots of iteration 0 whose chunks belong to "the slab before"
+    static_for<58, 64>([&](auto SIDX) XQ_INLINE_LAMBDA { horner_slot(SIDX, hr_b, hr_b, std::false_type{}, true); });
+
+    // A tick is 8 slots of one MFMA each (slot = column block); the VALU/LDS/DMA work that feeds
+    // later slots is spread over the slots and pinned there with scheduling fences so that it runs
+    // in the shadow of the MFMAs.
     for (int it = 0; it < p.n_main_slabs; ++it) {
-        // everyone has finished the previous slab's weight buffer and has taken its codes out of LDS
-        __syncthreads();
+        // With a single code image, everyone must have taken the previous slab's codes out of it
+        // before this slab's DMA refills it.  (The weight buffer needs no barrier here: its last
+        // read was issued before the landing barrier of the previous iteration.  Iteration 0 keeps
+        // one for the scale buffer that the set-up has just read.)
+        if (NIMG == 1 || it == 0) __syncthreads();
+        const int img_next = NIMG == 2 ? (it + 1) & 1 : 0;
         const bool more_main = it + 1 < p.n_main_slabs;
         const bool more_main2 = it + 2 < p.n_main_slabs;
         const int s_next = more_main ? main_slab_id(it + 1) : 0;
@@ -423,91 +539,72 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         const uint8_t* slab = my_slab + ((it + par0) & 1) * SLAB_BYTES;
         const uint8_t* slab_next = my_slab + ((it + 1 + par0) & 1) * SLAB_BYTES;
         float e_nxt[GPS];                                    // scales of the next slab (landed one slab ago)
+        float hr_bn[NB];                                     // boundary factors of the next iteration
+#pragma unroll
+        for (int k = 0; k < NB; ++k) hr_bn[k] = 1.0f;
         __builtin_amdgcn_sched_barrier(0);
 
-#pragma unroll
-        for (int ks = 0; ks < SLAB_KSTEPS; ++ks) {
-            const int par = ks & 1;
-            const int gi = ks / KSG, ksg = ks % KSG;
-            const bool pre = ksg == KSG - 1;               // last k-step of a group: start rescaling
-            const bool post = ksg == 0;                    // first k-step of a group: finish rescaling
-#pragma unroll
-            for (int m = 0; m < 8; ++m) {
+        static_for<0, 64>([&](auto SIDX) XQ_INLINE_LAMBDA {
+            {
+                constexpr int sidx = decltype(SIDX)::value;
+                constexpr int ks = sidx >> 3, m = sidx & 7;
+                const uint32_t* b = ub[(ks + 1 + m) & 7];
                 acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8, af[par][m]), as_frag(ub[par][0], ub[par][1], ub[par][2], ub[par][3]),
-                    acc[m], 0, 0, 0);
+                    __builtin_bit_cast(bf16x8, af[m]), as_frag(b[0], b[1], b[2], b[3]), acc[m], 0, 0, 0);
 
-                // DMA of the next slab: 11 steps per wave.  A wave stalls on the address FIFO while it
-                // issues them, so the two waves of a SIMD take turns (k-steps 0-1 / 2-3) and the
-                // partner keeps the MFMA pipe busy.
-                if (ks < 4 && more_main) {
-                    const int step = (ks & 1) * 8 + m;
-                    if (step < 11 && (ks >> 1) == dma_turn)
-                        dma_step(step, s_next, true, s_next2, more_main2, it & 1, wdst);
+                // DMA of the next slab: 11 steps per wave, one every other slot; the two waves of a
+                // SIMD use alternate slots.  (Issued in bursts they fill the address FIFO and the
+                // issuing wave stalls with its MFMAs behind them.)
+                if constexpr ((sidx >> 1) < 11) {
+                    if (more_main && (sidx & 1) == dma_turn)
+                        dma_step(sidx >> 1, s_next, img_next, s_next2, more_main2, it & 1, wdst);
                 }
-                // weight fragment of the next k-step (at the slab's end: of the next slab, once it has landed)
-                if (ks + 1 < SLAB_KSTEPS) af[par ^ 1][m] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + m) * 1024);
-                // token fragment of the next k-step
-                if (ks + 1 < SLAB_KSTEPS) {
-                    if (m == 0) {
-                        const int gi1 = (ks + 1) / KSG, ksg1 = (ks + 1) % KSG;
-                        unpack_kstep<BITS>(&cur[gi1 * NDW_G + (ksg1 >> 2) * BITS], ksg1, one, ub[par ^ 1]);
-                    }
-                } else if (m == 7 && more_main) {            // cur already holds the next slab's codes
-                    unpack_kstep<BITS>(&cur[0], 0, one, ub[par ^ 1]);
-                }
-                // the next slab's scales are in LDS since the previous slab
-                if (ks == SLAB_KSTEPS - 2 && m == 4 && more_main) fetch_scales(it + 1, e_nxt);
                 // the old codes are no longer needed: wait until the next slab has landed for everyone,
-                // then take the next slab's codes and first fragments
-                if (ks == SLAB_KSTEPS - 1 && m == 1) {
+                // then take the next slab's codes
+                if constexpr (ks == SLAB_KSTEPS - 1 && m == 1) {
                     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                     __syncthreads();
+                    if (more_main) fetch_tokens(img_next);
+                }
+                // weight fragment of the slot 7 ahead (the last 7 slots of a slab read the next slab)
+                if constexpr (sidx + 7 < 64) af[(sidx + 7) & 7] = *reinterpret_cast<const uint4*>(slab + (sidx + 7) * 1024);
+                else if (more_main) af[(sidx + 7) & 7] = *reinterpret_cast<const uint4*>(slab_next + (sidx + 7 - 64) * 1024);
+                // token fragment of the next tick; its ring entry was last read by this tick's slot 0
+                if constexpr (ks + 1 < SLAB_KSTEPS) {
+                    if constexpr (m == 2) {
+                        constexpr int gi1 = (ks + 1) / KSG, ksg1 = (ks + 1) % KSG;
+                        unpack_kstep<BITS>(&cur[gi1 * NDW_G + (ksg1 >> 2) * BITS], ksg1, one, ub[ks + 1]);
+                    }
+                } else if constexpr (m == 7) {               // cur already holds the next slab's codes
+                    if (more_main) unpack_kstep<BITS>(&cur[0], 0, one, ub[0]);
+                }
+                // the next slab's scales are in LDS since the previous slab
+                if constexpr (ks == SLAB_KSTEPS - 2 && m == 4) { if (more_main) fetch_scales((it + 1) & 1, e_nxt); }
+                if constexpr (ks == SLAB_KSTEPS - 1 && m == 3) {
                     if (more_main) {
-                        fetch_tokens();
-#pragma unroll
-                        for (int nb = 0; nb < 8; ++nb) af[par ^ 1][nb] = *reinterpret_cast<const uint4*>(slab_next + nb * 1024);
+                        static_for<0, NB>([&](auto K) XQ_INLINE_LAMBDA {
+                            constexpr int k = decltype(K)::value;
+                            float en0, en1;
+                            if constexpr (k < GPS) en0 = E[k + GPS]; else en0 = e_nxt[k - GPS];
+                            if constexpr (k + 1 < GPS) en1 = E[k + 1 + GPS]; else en1 = e_nxt[k + 1 - GPS];
+                            hr_bn[k] = en0 * __builtin_amdgcn_rcpf(en1);
+                        });
                     }
                 }
-                // Horner rescale of the accumulator to the next group's scale, 8 registers a slice
-                if (pre && m == 1) {
-                    const float e = (gi + 1 < GPS) ? e_cur[(gi + 1) % GPS] : (more_main ? e_nxt[0] : 1.0f);
-                    hr = e_prev * __builtin_amdgcn_rcpf(e);
-                    e_prev = e;
-                }
-                // (the empty asm statements pin the eight multiplies to this slot: pure arithmetic
-                // is otherwise free to drift to the end of the loop body during instruction selection)
-                auto slice = [&](int q) {
-                    const int h8 = (q & 1) * 8;
-                    float h = hr;
-                    asm volatile("" : "+v"(h));
-                    f32x16& a = acc[q >> 1];
-                    float e0 = a[h8 + 0] * h, e1 = a[h8 + 1] * h, e2 = a[h8 + 2] * h, e3 = a[h8 + 3] * h;
-                    float e4 = a[h8 + 4] * h, e5 = a[h8 + 5] * h, e6 = a[h8 + 6] * h, e7 = a[h8 + 7] * h;
-                    asm volatile("" : "+v"(e0), "+v"(e1), "+v"(e2), "+v"(e3), "+v"(e4), "+v"(e5), "+v"(e6), "+v"(e7));
-                    a[h8 + 0] = e0; a[h8 + 1] = e1; a[h8 + 2] = e2; a[h8 + 3] = e3;
-                    a[h8 + 4] = e4; a[h8 + 5] = e5; a[h8 + 6] = e6; a[h8 + 7] = e7;
-                };
-                if (pre && m >= 2) slice(m - 2);
-                if (post && !(it == 0 && ks == 0)) {
-                    if (m < 2) slice(6 + m);
-                    else if (m < 6) { slice(8 + 2 * (m - 2)); slice(9 + 2 * (m - 2)); }
-                }
+                horner_slot(SIDX, hr_b, hr_bn, std::true_type{}, more_main);
                 __builtin_amdgcn_sched_barrier(0);
             }
-        }
+        });
         if (more_main) {
 #pragma unroll
-            for (int gi = 0; gi < GPS; ++gi) e_cur[gi] = e_nxt[gi];
+            for (int gi = 0; gi < GPS; ++gi) { E[gi] = E[gi + GPS]; E[gi + GPS] = e_nxt[gi]; }
+#pragma unroll
+            for (int k = 0; k < NB; ++k) hr_b[k] = hr_bn[k];
         }
     }
-    // the last boundary rescaled towards e = 1: finish its slices, the accumulator is K | V
+    // every block ends in the slab it started in; leave its group's scale: the accumulator is K | V
 #pragma unroll
-    for (int q = 6; q < 16; ++q) {
-        const int h8 = (q & 1) * 8;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[q >> 1][h8 + i] *= hr;
-    }
+    for (int j = 0; j < 8; ++j) acc[j] *= E[GPS + j / KSG];
     attention_epilogue(p, c, acc);
 }
 
@@ -619,12 +716,12 @@ __global__ __launch_bounds__(128) void combine_kernel(const float* __restrict__ 
 }
 
 template <typename K>
-static hipError_t launch_with_lds(K kernel, const RematParams& p, int grid, hipStream_t s)
+static hipError_t launch_with_lds(K kernel, int lds_bytes, const RematParams& p, int grid, hipStream_t s)
 {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
-    kernel<<<dim3(grid), dim3(512), LDS_TOTAL, s>>>(p);
+    kernel<<<dim3(grid), dim3(512), lds_bytes, s>>>(p);
     return hipGetLastError();
 }
 
@@ -678,13 +775,13 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
         if (e != hipSuccess) return e;
     }
     switch (bits * 1000 + (bits == 16 ? 0 : G)) {
-        case 2064: e = launch_with_lds(remat_attn_coded_kernel<2, 64>, p, grid, s); break;
-        case 2128: e = launch_with_lds(remat_attn_coded_kernel<2, 128>, p, grid, s); break;
-        case 3064: e = launch_with_lds(remat_attn_coded_kernel<3, 64>, p, grid, s); break;
-        case 3128: e = launch_with_lds(remat_attn_coded_kernel<3, 128>, p, grid, s); break;
-        case 4064: e = launch_with_lds(remat_attn_coded_kernel<4, 64>, p, grid, s); break;
-        case 4128: e = launch_with_lds(remat_attn_coded_kernel<4, 128>, p, grid, s); break;
-        case 16000: e = launch_with_lds(remat_attn_dense_kernel, p, grid, s); break;
+        case 2064: e = launch_with_lds(remat_attn_coded_kernel<2, 64>, lds_coded_total(2), p, grid, s); break;
+        case 2128: e = launch_with_lds(remat_attn_coded_kernel<2, 128>, lds_coded_total(2), p, grid, s); break;
+        case 3064: e = launch_with_lds(remat_attn_coded_kernel<3, 64>, lds_coded_total(3), p, grid, s); break;
+        case 3128: e = launch_with_lds(remat_attn_coded_kernel<3, 128>, lds_coded_total(3), p, grid, s); break;
+        case 4064: e = launch_with_lds(remat_attn_coded_kernel<4, 64>, lds_coded_total(4), p, grid, s); break;
+        case 4128: e = launch_with_lds(remat_attn_coded_kernel<4, 128>, lds_coded_total(4), p, grid, s); break;
+        case 16000: e = launch_with_lds(remat_attn_dense_kernel, LDS_DENSE_TOTAL, p, grid, s); break;
         default: e = hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;

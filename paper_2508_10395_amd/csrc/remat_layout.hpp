@@ -6,11 +6,16 @@
 // 32x16 operand fragment per (k-step, column block), lane-major, so that the copy
 // HBM -> LDS is linear and every lane's ds_read_b128 is conflict-free.
 //
-// Main slab s covers hidden channels [128 s, 128 s + 128).  Lane l feeds row
-// (l % 32) of its column block and, with half = l / 32, the contraction slots
-//   dense source:  channel = 128 s + 64 half + 8 ks + i
-//   coded source:  group gi = ks / (G/16); unit u, k-step j inside the unit;
-//                  channel = 128 s + G gi + (G/2) half + 32 u + code_of_slot[j][i],
+// Lane l feeds row (l % 32) of its column block and, with half = l / 32, the
+// contraction slots
+//   dense source:  slab s covers hidden channels [128 s, 128 s + 128):
+//                  channel = 128 s + 64 half + 8 ks + i
+//   coded source:  the kernel walks the d/16 k-steps cyclically and column block nb
+//                  runs 7 - nb k-steps behind the walk, so position (slab s, k-step
+//                  ks, block nb) holds k-step kappa = (8 s + ks - (7 - nb)) mod (d/16)
+//                  = (slab s', k-step ks'):  group gi = ks' / (G/16); unit u, k-step j
+//                  inside the unit;
+//                  channel = 128 s' + G gi + (G/2) half + 32 u + code_of_slot[j][i],
 //                  value scaled by 2^wexp_of_code (see unpack.hpp).
 // Correction slabs (coded sources only) hold, for contraction index
 // kappa = 16 kk + 8 half + i, term = kappa / ng_pad, group g = kappa % ng_pad:
@@ -26,6 +31,7 @@ namespace xq {
 constexpr int SLAB_KSTEPS = 8;
 constexpr int SLAB_BYTES = 65536;
 constexpr int N_CORR_TERMS = 4;
+constexpr int COL_BLOCK_LAG_MAX = 7;  // coded sources: column block nb lags by 7 - nb k-steps
 constexpr int TILE_TOKENS = 256;     // tokens per workgroup
 constexpr int CHUNK_TOKENS = 32;     // tokens per wave = one softmax partial
 
