@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void pack_main_kernel(PrepArgs a)
         for (int i = 0; i < 8; ++i) {
             int c, e = 0;
             if (dense) {
-                c = s * 128 + half * 64 + ks * 8 + i;
+                c = s * 128 + ks * 16 + half * 8 + i;
             } else {
                 const int gi = cks / ksg_n, ksg = cks % ksg_n;
                 const int u = ksg >> 2, j = ksg & 3;

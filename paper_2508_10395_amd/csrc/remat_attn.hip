@@ -293,12 +293,10 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     const uint8_t* my_codes = lds + LDS_CODES_OFF + my_row * ROW_SLAB_BYTES + half * (NDW_G * 4);
     const uint16_t* my_scale = reinterpret_cast<const uint16_t*>(lds + LDS_SCALES_OFF) + my_row;
 
-    // Workgroups that run side by side on one XCD stream the same head.  Each starts its
-    // contraction at a different slab (the sum over groups is order-free), so that at any
-    // moment they pull different addresses and the requests spread over all L2 channels.
-    // (the runtime modulo is done on the vector ALU; readfirstlane returns it to a scalar register)
-    const int rot = __builtin_amdgcn_readfirstlane((int)((blockIdx.x >> 3) % (unsigned)p.n_main_slabs));
-    auto main_slab_id = [&](int it) { const int s = it + rot; return s >= p.n_main_slabs ? s - p.n_main_slabs : s; };
+    // Workgroups that run side by side on one XCD stream the same head and all start the cyclic
+    // walk at slab 0: they advance at about the same pace, so a slab is fetched into the XCD's L2
+    // once and hit by the others.  (Starting each workgroup at a different slab was measured: it
+    // raises the L2 miss traffic by a third and the kernel time by 7 %.)
 
     f32x16 acc[8];                       // [column block]: 0-3 K, 4-7 V
 #pragma unroll
@@ -390,16 +388,16 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         }
         return v;
     };
-    const int slab_prev = rot == 0 ? p.n_main_slabs - 1 : rot - 1;
+    const int slab_prev = p.n_main_slabs - 1;           // the walk is cyclic: the slab "before" slab 0
     issue_slab(wsrc + (long long)p.n_main_slabs * SLAB_BYTES, lds_w, dma_voff);        // correction slab 0 -> buffer 0
     dma_step(0, slab_prev, NIMG - 1, 0, false, 0, 0);                                  // predecessor codes -> last image
     dma_step(1, slab_prev, NIMG - 1, 0, false, 0, 0);
     dma_step(2, 0, 0, slab_prev, true, 2, 0);                                          // its scales -> scale buffer 2
-    dma_step(2, 0, 0, rot, true, 0, 0);                                                // first slab's scales -> buffer 0
-    if (p.n_main_slabs > 1) dma_step(2, 0, 0, main_slab_id(1), true, 1, 0);            // second slab's -> buffer 1
+    dma_step(2, 0, 0, 0, true, 0, 0);                                                // first slab's scales -> buffer 0
+    if (p.n_main_slabs > 1) dma_step(2, 0, 0, 1, true, 1, 0);            // second slab's -> buffer 1
     if constexpr (NIMG == 2) {                                                         // first slab's codes -> image 0
-        dma_step(0, rot, 0, 0, false, 0, 0);
-        dma_step(1, rot, 0, 0, false, 0, 0);
+        dma_step(0, 0, 0, 0, false, 0, 0);
+        dma_step(1, 0, 0, 0, false, 0, 0);
     }
     uint4 mfr[SLAB_KSTEPS];
 #pragma unroll
@@ -409,7 +407,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         __syncthreads();
         const uint32_t wdst = lds_w + (uint32_t)(((cs + 1) & 1) * SLAB_BYTES);
         if (cs + 1 < n_corr_slabs) issue_slab(wsrc + (long long)(p.n_main_slabs + cs + 1) * SLAB_BYTES, wdst, dma_voff);
-        else issue_slab(wsrc + (long long)rot * SLAB_BYTES, wdst, dma_voff);           // the first main slab
+        else issue_slab(wsrc, wdst, dma_voff);                                                   // the first main slab
         if (cs == 0) {
             fetch_tokens(NIMG - 1);
             fetch_scales(2, &E[0]);
@@ -435,8 +433,8 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                     // every wave now holds its predecessor codes in registers: the first slab's
                     // codes may overwrite the only image
                     __syncthreads();
-                    dma_step(0, rot, 0, 0, false, 0, 0);
-                    dma_step(1, rot, 0, 0, false, 0, 0);
+                    dma_step(0, 0, 0, 0, false, 0, 0);
+                    dma_step(1, 0, 0, 0, false, 0, 0);
                 }
             }
         }
@@ -447,7 +445,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     }
 
     // ==== phase 2: the d x 256 contraction, as a cyclic walk over the d/16 k-steps that starts
-    // at slab `rot`.  Column block j runs 7 - j k-steps behind the walk: at tick tau it multiplies
+    // at slab 0.  Column block j runs 7 - j k-steps behind the walk: at tick tau it multiplies
     // the weights of k-step tau - 7 + j (the prepared stream is laid out in this order) with the
     // token fragment unpacked 7 - j ticks ago, which waits in an 8-deep ring.  The group
     // boundaries of the eight blocks therefore fall on different ticks, and the Horner rescale
@@ -533,8 +531,8 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         const int img_next = NIMG == 2 ? (it + 1) & 1 : 0;
         const bool more_main = it + 1 < p.n_main_slabs;
         const bool more_main2 = it + 2 < p.n_main_slabs;
-        const int s_next = more_main ? main_slab_id(it + 1) : 0;
-        const int s_next2 = more_main2 ? main_slab_id(it + 2) : 0;
+        const int s_next = more_main ? it + 1 : 0;
+        const int s_next2 = more_main2 ? it + 2 : 0;
         const uint32_t wdst = lds_w + (uint32_t)(((it + 1 + par0) & 1) * SLAB_BYTES);
         const uint8_t* slab = my_slab + ((it + par0) & 1) * SLAB_BYTES;
         const uint8_t* slab_next = my_slab + ((it + 1 + par0) & 1) * SLAB_BYTES;
@@ -609,8 +607,10 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
 }
 
 // =====================================================================================
-// dense source (XQuant-CL accumulator, bf16): token fragments come straight from HBM,
-// each lane reading the 128 contiguous bytes of its token's half of the slab
+// dense source (XQuant-CL accumulator, bf16): token fragments come straight from HBM.  Per
+// k-step a lane loads the 16 bytes of its token's 8 channels; the two half-waves read adjacent
+// pieces, and the fragments of the next slab are loaded early in the current one into a second
+// register set, so that their latency is hidden by the time the slab barrier waits for them.
 // =====================================================================================
 __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams p)
 {
@@ -618,16 +618,15 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
     TileCtx c;
     if (!locate_tile(p, c)) return;
     const int lane = c.lane, wave = c.wave, half = c.half;
+    const int dma_turn = wave >> 2;
 
     const uint8_t* wsrc = p.wprep + (long long)c.hk * p.head_bytes + wave * 1024;
     const uint32_t dma_voff = (uint32_t)lane * 16u;
     const uint32_t lds_w = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds + wave * 1024;
     const uint8_t* my_slab = lds + lane * 16;
     const uint8_t* cbase = reinterpret_cast<const uint8_t*>(p.acc) + (long long)c.b * p.cap * p.d * 2;
-    const uint32_t coff = (uint32_t)min(c.tok, c.len - 1) * (uint32_t)(p.d * 2) + half * 128;
-
-    const int rot = (int)((blockIdx.x >> 3) % (unsigned)p.n_main_slabs);
-    auto main_slab_id = [&](int it) { const int s = it + rot; return s >= p.n_main_slabs ? s - p.n_main_slabs : s; };
+    // k-step ks of slab s: channels 128 s + 16 ks + 8 half + [0, 8)
+    const uint32_t coff = (uint32_t)min(c.tok, c.len - 1) * (uint32_t)(p.d * 2) + half * 16;
 
     f32x16 acc[8];
 #pragma unroll
@@ -635,37 +634,52 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[nb][i] = 0.0f;
 
-    uint4 af[2][8];
-    uint4 bd[8];                         // one slab of token fragments (ring)
+    uint4 af[8];                         // weight fragments, ring over slots (loaded 7 slots ahead)
+    uint4 bd[8], bdn[8];                 // token fragments of the current / next slab
 
-    issue_slab(wsrc + (long long)rot * SLAB_BYTES, lds_w, dma_voff);
+    issue_slab(wsrc, lds_w, dma_voff);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) bd[ks] = reinterpret_cast<const uint4*>(cbase + coff + rot * 256)[ks];
+    for (int ks = 0; ks < 8; ++ks) bd[ks] = *reinterpret_cast<const uint4*>(cbase + coff + ks * 32);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int sl = 0; sl < 7; ++sl) af[sl] = *reinterpret_cast<const uint4*>(my_slab + sl * 1024);
 
     for (int it = 0; it < p.n_main_slabs; ++it) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
         const bool more_main = it + 1 < p.n_main_slabs;
-        const int s_next = more_main ? main_slab_id(it + 1) : 0;
-        if (more_main)
-            issue_slab(wsrc + (long long)s_next * SLAB_BYTES, lds_w + (uint32_t)(((it + 1) & 1) * SLAB_BYTES), dma_voff);
+        const int s_next = more_main ? it + 1 : it;
+        const uint32_t wdst = lds_w + (uint32_t)(((it + 1) & 1) * SLAB_BYTES);
+        const uint8_t* wnext = wsrc + (long long)s_next * SLAB_BYTES;
         const uint8_t* slab = my_slab + (it & 1) * SLAB_BYTES;
-#pragma unroll
-        for (int nb = 0; nb < 8; ++nb) af[0][nb] = *reinterpret_cast<const uint4*>(slab + nb * 1024);
+        const uint8_t* slab_next = my_slab + ((it + 1) & 1) * SLAB_BYTES;
+        const uint8_t* xnext = cbase + coff + s_next * 256;
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int ks = 0; ks < SLAB_KSTEPS; ++ks) {
-            const int par = ks & 1;
-#pragma unroll
-            for (int m = 0; m < 8; ++m) {
-                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8, af[par][m]), __builtin_bit_cast(bf16x8, bd[ks]), acc[m], 0, 0, 0);
-                if (ks + 1 < SLAB_KSTEPS)
-                    af[par ^ 1][m] = *reinterpret_cast<const uint4*>(slab + ((ks + 1) * 8 + m) * 1024);
-                // the fragment is consumed by its last column block: refill the ring slot for the next slab
-                if (m == 7 && more_main) bd[ks] = reinterpret_cast<const uint4*>(cbase + coff + s_next * 256)[ks];
-                __builtin_amdgcn_sched_barrier(0);
+        static_for<0, 64>([&](auto SIDX) XQ_INLINE_LAMBDA {
+            constexpr int sidx = decltype(SIDX)::value;
+            constexpr int ks = sidx >> 3, m = sidx & 7;
+            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, af[m]), __builtin_bit_cast(bf16x8, bd[ks]), acc[m], 0, 0, 0);
+            // next slab's weights: 8 DMA steps per wave, one every other slot, the two waves of a
+            // SIMD on alternate slots; its token fragments: one load every other slot after that
+            if constexpr ((sidx >> 1) < 8) {
+                if (more_main && (sidx & 1) == dma_turn)
+                    dma_b128(wnext + (sidx >> 1) * 8192, dma_voff, wdst + (sidx >> 1) * 8192);
+            } else if constexpr ((sidx >> 1) < 16) {
+                if (more_main && (sidx & 1) == dma_turn)
+                    bdn[(sidx >> 1) - 8] = *reinterpret_cast<const uint4*>(xnext + ((sidx >> 1) - 8) * 32);
             }
+            // the next slab has landed for everyone (its buffer was last read one slab ago)
+            if constexpr (ks == SLAB_KSTEPS - 1 && m == 1) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+            }
+            if constexpr (sidx + 7 < 64) af[(sidx + 7) & 7] = *reinterpret_cast<const uint4*>(slab + (sidx + 7) * 1024);
+            else if (more_main) af[(sidx + 7) & 7] = *reinterpret_cast<const uint4*>(slab_next + (sidx + 7 - 64) * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        if (more_main) {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) bd[ks] = bdn[ks];
         }
     }
     attention_epilogue(p, c, acc);
@@ -695,24 +709,45 @@ __global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __
     dst[(long long)ng * TILE_TOKENS] = 0x3F80u;       // pad group (fetched, never used)
 }
 
-// ---- split-context combine: out[b][h][:] = sum_c w_c o_c / sum_c w_c l_c, w_c = 2^(m_c - M)
-__global__ __launch_bounds__(128) void combine_kernel(const float* __restrict__ part_o,
-                                                      const float* __restrict__ part_ml,
-                                                      float* __restrict__ out, int Hq, int chunks_per_seq,
-                                                      BatchI32 len)
+// ---- split-context combine: out[b][h][:] = sum_c w_c o_c / sum_c w_c l_c, w_c = 2^(m_c - M).
+// One workgroup per (sequence, query head): COMBINE_GROUPS groups of 128 threads (one per output
+// column) each take every COMBINE_GROUPS-th chunk, so the loads of a group's chunks are
+// independent and overlap; the groups' sums are added in fixed order (deterministic result).
+constexpr int COMBINE_GROUPS = 8;
+__global__ __launch_bounds__(128 * COMBINE_GROUPS) void combine_kernel(const float* __restrict__ part_o,
+                                                                       const float* __restrict__ part_ml,
+                                                                       float* __restrict__ out, int Hq,
+                                                                       int chunks_per_seq, BatchI32 len)
 {
-    const int h = blockIdx.x, b = blockIdx.y, n = threadIdx.x;
+    __shared__ float sm[COMBINE_GROUPS];
+    __shared__ float sl[COMBINE_GROUPS];
+    __shared__ float so[COMBINE_GROUPS][128];
+    const int h = blockIdx.x, b = blockIdx.y, n = threadIdx.x & 127, grp = threadIdx.x >> 7;
     const int nchunks = (len.v[b] + CHUNK_TOKENS - 1) / CHUNK_TOKENS;
     const long long base = ((long long)b * Hq + h) * chunks_per_seq;
-    float M = -INFINITY;
-    for (int c = 0; c < nchunks; ++c) M = fmaxf(M, part_ml[(base + c) * 2]);
+    float m_g = -INFINITY;
+    for (int c = grp; c < nchunks; c += COMBINE_GROUPS) m_g = fmaxf(m_g, part_ml[(base + c) * 2]);
+    if (n == 0) sm[grp] = m_g;
+    __syncthreads();
+    float M = sm[0];
+#pragma unroll
+    for (int g = 1; g < COMBINE_GROUPS; ++g) M = fmaxf(M, sm[g]);
     float L = 0.0f, o = 0.0f;
-    for (int c = 0; c < nchunks; ++c) {
+#pragma unroll 4
+    for (int c = grp; c < nchunks; c += COMBINE_GROUPS) {
         const float w = __builtin_amdgcn_exp2f(part_ml[(base + c) * 2] - M);
         L = __builtin_fmaf(w, part_ml[(base + c) * 2 + 1], L);
         o = __builtin_fmaf(w, part_o[(base + c) * 128 + n], o);
     }
-    out[((long long)b * Hq + h) * 128 + n] = o / L;
+    so[grp][n] = o;
+    if (n == 0) sl[grp] = L;
+    __syncthreads();
+    if (grp == 0) {
+        float Lt = sl[0], ot = so[0][n];
+#pragma unroll
+        for (int g = 1; g < COMBINE_GROUPS; ++g) { Lt += sl[g]; ot += so[g][n]; }
+        out[((long long)b * Hq + h) * 128 + n] = ot / Lt;
+    }
 }
 
 template <typename K>
@@ -785,7 +820,7 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
         default: e = hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
-    combine_kernel<<<dim3(p.Hq, p.B), dim3(128), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len);
+    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len);
     return hipGetLastError();
 }
 

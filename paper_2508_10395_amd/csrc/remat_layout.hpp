@@ -9,7 +9,7 @@
 // Lane l feeds row (l % 32) of its column block and, with half = l / 32, the
 // contraction slots
 //   dense source:  slab s covers hidden channels [128 s, 128 s + 128):
-//                  channel = 128 s + 64 half + 8 ks + i
+//                  channel = 128 s + 16 ks + 8 half + i
 //   coded source:  the kernel walks the d/16 k-steps cyclically and column block nb
 //                  runs 7 - nb k-steps behind the walk, so position (slab s, k-step
 //                  ks, block nb) holds k-step kappa = (8 s + ks - (7 - nb)) mod (d/16)
