@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--profile-copy", action="store_true",
                     help="also run one plain device copy of the 256 MiB X tensor (calibrates HBM byte counters)")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary kernels (profiling runs)")
+    ap.add_argument("--other-configs", action="store_true",
+                    help="also time the fused kernel on the GQA (c4) and long-context (c5) shapes; reported under extra")
     return ap.parse_args()
 
 
@@ -144,6 +146,32 @@ def main():
                                      "TFLOP/s": flops / t_dense / 1e9,
                                      "frac_mfma_peak": flops / t_dense / 1e9 / PEAK_BF16_TFLOPS},
         }
+
+    if args.other_configs and extra is not None:
+        del bulk_cache, acc, wprep_dense
+        torch.cuda.empty_cache()
+        for ow in (xi.C4, xi.C5):
+            oq = dev_bf16(xi.gen_q(ow))
+            owk, owv = xi.gen_weights(ow)
+            oattn = xq.XQAttn(ow.Hq, ow.Hkv, ow.hd, ow.hd ** -0.5)
+            owp = xq.xq_prepare_weights(oattn, ow.d, ow.G, ow.bits, dev_bf16(owk), dev_bf16(owv))
+            ocache = xq.alloc_cache(ow.B, ow.L, ow.d, ow.G, ow.bits)
+            for b0 in range(ow.B):                       # fill one sequence at a time (host memory)
+                one = ow.scaled(B=1, cfg_id=ow.cfg_id * 100 + b0)
+                sub = xq.XQCache(ocache.codes[b0:b0 + 1], ocache.scale[b0:b0 + 1], ocache.zero[b0:b0 + 1],
+                                 1, ow.L, ow.d, ow.G, ow.bits)
+                xq.xq_quantize_append(sub, dev_bf16(xi.gen_x(one)), [0])
+            oout = torch.empty((ow.B, ow.Hq, ow.hd), dtype=torch.float32, device=dev)
+            ows = torch.empty(xq.xq_remat_attn_workspace_bytes(oattn, ow.B, ow.L, ow.d, ow.G), dtype=torch.uint8,
+                              device=dev)
+            olens = [ow.L] * ow.B
+            t_o = timed(lambda: xq.xq_remat_attn_decode(oattn, oq, owp, olens, xcache=ocache, out=oout, workspace=ows),
+                        n=5, warm=2)
+            oflops = 2.0 * ow.B * ow.L * ow.d * (2 * ow.Hkv * ow.hd) + 4.0 * ow.B * ow.L * ow.Hq * ow.hd
+            extra["remat_attn_" + ow.name] = {"ms": t_o, "tokens/s/layer": ow.B * ow.L / (t_o * 1e-3),
+                                              "TFLOP/s": oflops / t_o / 1e9,
+                                              "frac_mfma_peak": oflops / t_o / 1e9 / PEAK_BF16_TFLOPS}
+            del ocache, owp, ows
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")

@@ -260,7 +260,6 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     TileCtx c;
     if (!locate_tile(p, c)) return;
     const int lane = c.lane, wave = c.wave, half = c.half, tl = c.tl;
-    const int dma_turn = wave >> 2;                    // the two waves of a SIMD take turns issuing DMA
 
     const int n_corr_slabs = (p.n_corr_ksteps + SLAB_KSTEPS - 1) / SLAB_KSTEPS;
     const uint8_t* wsrc = p.wprep + (long long)c.hk * p.head_bytes + wave * 1024;   // this wave's DMA share
@@ -531,8 +530,10 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         const int img_next = NIMG == 2 ? (it + 1) & 1 : 0;
         const bool more_main = it + 1 < p.n_main_slabs;
         const bool more_main2 = it + 2 < p.n_main_slabs;
-        const int s_next = more_main ? it + 1 : 0;
-        const int s_next2 = more_main2 ? it + 2 : 0;
+        // (the last iterations issue their DMA all the same, from slabs that exist into buffers that
+        // are not read again: no branches around the issue slots)
+        const int s_next = more_main ? it + 1 : it;
+        const int s_next2 = more_main2 ? it + 2 : it;
         const uint32_t wdst = lds_w + (uint32_t)(((it + 1 + par0) & 1) * SLAB_BYTES);
         const uint8_t* slab = my_slab + ((it + par0) & 1) * SLAB_BYTES;
         const uint8_t* slab_next = my_slab + ((it + 1 + par0) & 1) * SLAB_BYTES;
@@ -550,13 +551,10 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                 acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                     __builtin_bit_cast(bf16x8, af[m]), as_frag(b[0], b[1], b[2], b[3]), acc[m], 0, 0, 0);
 
-                // DMA of the next slab: 11 steps per wave, one every other slot; the two waves of a
-                // SIMD use alternate slots.  (Issued in bursts they fill the address FIFO and the
-                // issuing wave stalls with its MFMAs behind them.)
-                if constexpr ((sidx >> 1) < 11) {
-                    if (more_main && (sidx & 1) == dma_turn)
-                        dma_step(sidx >> 1, s_next, img_next, s_next2, more_main2, it & 1, wdst);
-                }
+                // DMA of the next slab: 11 steps per wave, one every other slot.  (Issued in bursts they
+                // fill the address FIFO and the issuing wave stalls with its MFMAs behind them.)
+                if constexpr ((sidx >> 1) < 11 && (sidx & 1) == 0)
+                    dma_step(sidx >> 1, s_next, img_next, s_next2, true, it & 1, wdst);
                 // the old codes are no longer needed: wait until the next slab has landed for everyone,
                 // then take the next slab's codes
                 if constexpr (ks == SLAB_KSTEPS - 1 && m == 1) {

@@ -138,3 +138,102 @@ def test_full_size_llama2_7b_sampled_pairs(xq):
     pairs = xi.sample_pairs(w, 8)
     worst = _run_xquant(xq, w, w.bits, w.G, [w.L] * w.B, pairs=pairs)
     print(f"c2 sampled pairs: worst norm-wise rel err {worst:.2e}")
+
+
+def test_full_size_llama3_8b_gqa_sampled_pairs(xq):
+    """Config 4 at full size (B=16, L=8192, d=4096, 32 query / 8 KV heads, 2-bit, group 64): the
+    sample holds all four query heads of one KV head besides the first and the last head."""
+    w = xi.C4
+    pairs = xi.sample_pairs(w, 8)
+    worst = _run_xquant(xq, w, w.bits, w.G, [w.L] * w.B, pairs=pairs)
+    print(f"c4 sampled pairs: worst norm-wise rel err {worst:.2e}")
+
+
+def test_full_size_long_context_chunk_then_decode_steps(xq):
+    """Config 5 at full size (B=4, d=4096, 32 heads, 2-bit, group 128): the cache is filled to
+    32192 rows, a 512-token chunk goes through xq_quantize_append, then 64 decode steps each
+    append one token and attend over the grown context (32705 ... 32768 rows = 128 tiles).
+    The appended rows are compared bit for bit, the first and last step's outputs on a sample."""
+    w = xi.C5
+    n_steps, chunk = 64, 512
+    L0 = w.L - chunk - n_steps
+    x = xi.gen_x(w)                                           # [4][32768][4096]
+    wk, wv = xi.gen_weights(w)
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    wprep = xq.xq_prepare_weights(attn, w.d, w.G, w.bits, bits_to_torch(wk), bits_to_torch(wv))
+    cache = xq.alloc_cache(w.B, w.L, w.d, w.G, w.bits)
+    xq.xq_quantize_append(cache, bits_to_torch(x[:, :L0]), [0] * w.B)
+    xq.xq_quantize_append(cache, bits_to_torch(x[:, L0:L0 + chunk]), [L0] * w.B)
+    ws = torch.empty(xq.xq_remat_attn_workspace_bytes(attn, w.B, w.L, w.d, w.G), dtype=torch.uint8, device="cuda")
+    pairs = xi.sample_pairs(w, 4)
+    outs, qs = {}, {}
+    for s in range(n_steps):
+        row = L0 + chunk + s
+        xq.xq_quantize_append(cache, bits_to_torch(x[:, row:row + 1]), [row] * w.B)
+        q = xi.gen_q(w, layer=s)
+        out = xq.xq_remat_attn_decode(attn, bits_to_torch(q), wprep, [row + 1] * w.B, xcache=cache, workspace=ws)
+        if s in (0, n_steps - 1):
+            outs[s], qs[s] = out.cpu().numpy(), q
+    torch.cuda.synchronize()
+    gc, gs, gz = cache.codes.cpu().numpy(), torch_to_bits(cache.scale), torch_to_bits(cache.zero)
+    for b in range(w.B):                                      # the chunk and the 64 decode appends, every byte
+        codes, scale, zero = xo.quantize_rows(bf(x[b, L0:]), w.G, w.bits)
+        assert np.array_equal(gs[b, L0:], scale) and np.array_equal(gz[b, L0:], zero), b
+        assert np.array_equal(gc[b, L0:], xo.pack_rows(codes, w.bits)), b
+    for s in (0, n_steps - 1):
+        lens = [L0 + chunk + s + 1] * w.B
+        ref = xo.remat_attn_pairs(q_bf16=qs[s], Wk=wk, Wv=wv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd,
+                                  softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs, packed=gc, scale=gs,
+                                  zero=gz, G=w.G, bits=w.bits)
+        sel = np.array([outs[s][b, h] for b, h in pairs])
+        worst = _check(sel, ref, f"c5 step {s}")
+        print(f"c5 step {s}: worst norm-wise rel err {worst:.2e}")
+
+
+def test_full_size_cross_layer_stack_first_layers(xq):
+    """Config 3's shape (B=8, L=8192, d=4096, 32 heads; base 4-bit, deltas 2-bit, group 128) for
+    the base layer and two delta layers: accumulator bits on sampled rows against the oracle's
+    own chain, attention from the accumulator on sampled (sequence, head) pairs."""
+    w = xi.C3
+    G, lens = w.G, [w.L] * w.B
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    rng = np.random.default_rng(3)
+    rows = np.sort(rng.choice(w.L, size=48, replace=False))
+    rows[0], rows[-1] = 0, w.L - 1
+    pairs = xi.sample_pairs(w, 4)
+    x = xi.gen_x(w)
+    acc = torch.empty((w.B, w.L, w.d), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(xq.xq_remat_attn_workspace_bytes(attn, w.B, w.L, w.d, 0), dtype=torch.uint8, device="cuda")
+    ref_acc = None                                            # oracle accumulator on the sampled rows [B][48][d]
+    for layer in range(3):
+        bits = w.bits if layer == 0 else w.delta_bits
+        cache = xq.alloc_cache(w.B, w.L, w.d, G, bits)
+        xs = x[:, rows]
+        if layer == 0:
+            xq.xq_quantize_append(cache, bits_to_torch(x), [0] * w.B)
+            src = bf(xs)
+        else:
+            xq.xq_cl_delta_quantize(cache, bits_to_torch(x), acc, [0] * w.B)
+            src = np.stack([xo.cl_delta_rows(xs[b], ref_acc[b]) for b in range(w.B)])
+        xq.xq_cl_accumulate(acc, cache, lens, init=(layer == 0))
+        torch.cuda.synchronize()
+        new_ref = []
+        for b in range(w.B):
+            c, s, z = xo.quantize_rows(src[b], G, bits)
+            prev = np.zeros_like(xs[b]) if layer == 0 else ref_acc[b]
+            new_ref.append(xo.cl_accumulate_rows(prev, c, s, z, G, layer == 0))
+        ref_acc = np.stack(new_ref)
+        acc_bits = torch_to_bits(acc)
+        assert np.array_equal(acc_bits[:, rows], ref_acc), f"accumulator bits, layer {layer}"
+        wk, wv = xi.gen_weights(w, layer=layer)
+        q = xi.gen_q(w, layer=layer)
+        wprep = xq.xq_prepare_weights(attn, w.d, 128, 16, bits_to_torch(wk), bits_to_torch(wv))
+        out = xq.xq_remat_attn_decode(attn, bits_to_torch(q), wprep, lens, acc_bf16=acc, workspace=ws)
+        torch.cuda.synchronize()
+        ref = xo.remat_attn_pairs(q_bf16=q, Wk=wk, Wv=wv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd,
+                                  softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs, acc_bf16=acc_bits)
+        got = out.cpu().numpy()
+        worst = _check(np.array([got[b, h] for b, h in pairs]), ref, f"c3 layer {layer}")
+        print(f"c3 layer {layer}: worst norm-wise rel err {worst:.2e}")
+        if layer < 2:
+            x = xi.gen_next_layer_x(w, x, layer + 1)
