@@ -1,8 +1,9 @@
 // Quantise-and-append kernels: X cache rows (Sec. 3.1) and cross-layer delta rows
-// (Sec. 3.2) of arxiv 2508.10395.  HBM-streaming: every lane loads 8 consecutive
-// bf16 channels (16 B), a group of G channels lives in G/8 adjacent lanes of one
-// 16-lane DPP row, min/max are reduced with DPP, the b-bit codes are packed in
-// registers and written as the row's little-endian bit string.
+// (Sec. 3.2) of arxiv 2508.10395.  HBM-streaming: one workgroup per token row, every
+// lane loads 16 consecutive bf16 channels (32 B), a group of G channels lives in G/16
+// adjacent lanes of one DPP row, min/max are reduced with DPP, the b-bit codes are
+// packed in registers and written as the row's little-endian bit string.  The grid
+// is (token, sequence), so no index arithmetic beyond a few multiplies is needed.
 #include "common.hpp"
 
 namespace xq {
@@ -37,100 +38,125 @@ __device__ __forceinline__ void group_minmax(float& mn, float& mx)
     mx = fmaxf(mx, dpp_f32<DPP_QUAD_XOR1>(mx));
     mn = fminf(mn, dpp_f32<DPP_QUAD_XOR2>(mn));
     mx = fmaxf(mx, dpp_f32<DPP_QUAD_XOR2>(mx));
-    mn = fminf(mn, dpp_f32<DPP_ROW_HALF_MIRROR>(mn));
-    mx = fmaxf(mx, dpp_f32<DPP_ROW_HALF_MIRROR>(mx));
-    if constexpr (LANES == 16) {
-        mn = fminf(mn, dpp_f32<DPP_ROW_MIRROR>(mn));
-        mx = fmaxf(mx, dpp_f32<DPP_ROW_MIRROR>(mx));
+    if constexpr (LANES == 8) {
+        mn = fminf(mn, dpp_f32<DPP_ROW_HALF_MIRROR>(mn));
+        mx = fmaxf(mx, dpp_f32<DPP_ROW_HALF_MIRROR>(mx));
     }
 }
 
-// One thread = one chunk of 8 channels.  x is [B][T][d]; in DELTA mode the value
-// quantised is x - acc[b][start[b]+t] (fp32).  Output row = b*cap + start[b] + t.
-template <int BITS, int G, bool DELTA>
-__global__ __launch_bounds__(256) void quantize_append_kernel(
-    const uint4* __restrict__ x, const uint4* __restrict__ acc, uint8_t* __restrict__ codes,
-    uint16_t* __restrict__ scale, uint16_t* __restrict__ zero, int T, int cap, int d, BatchI32 start,
-    long long nchunks)
-{
-    constexpr int LANES = G / 8;
-    constexpr float QMAX = (float)((1 << BITS) - 1);
-    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const bool live = i < nchunks;
-    const long long ic = live ? i : nchunks - 1;      // keep whole DPP rows active
-    const int cpr = d >> 3;                           // chunks per row
-    const long long row_in = ic / cpr;
-    const int cw = (int)(ic - row_in * cpr);
-    const int b = (int)(row_in / T);
-    const int t = (int)(row_in - (long long)b * T);
-    const long long row_out = (long long)b * cap + start.v[b] + t;
+struct __attribute__((packed, aligned(4))) Dword2 {
+    uint32_t a, b;
+};
 
-    uint4 raw = x[ic];
-    float v[8];
+__device__ __forceinline__ void unpack8(const uint4& raw, float* v)
+{
     v[0] = bf16_lo_to_f32(raw.x); v[1] = bf16_hi_to_f32(raw.x);
     v[2] = bf16_lo_to_f32(raw.y); v[3] = bf16_hi_to_f32(raw.y);
     v[4] = bf16_lo_to_f32(raw.z); v[5] = bf16_hi_to_f32(raw.z);
     v[6] = bf16_lo_to_f32(raw.w); v[7] = bf16_hi_to_f32(raw.w);
-    if constexpr (DELTA) {
-        uint4 a = acc[row_out * cpr + cw];
-        v[0] -= bf16_lo_to_f32(a.x); v[1] -= bf16_hi_to_f32(a.x);
-        v[2] -= bf16_lo_to_f32(a.y); v[3] -= bf16_hi_to_f32(a.y);
-        v[4] -= bf16_lo_to_f32(a.z); v[5] -= bf16_hi_to_f32(a.z);
-        v[6] -= bf16_lo_to_f32(a.w); v[7] -= bf16_hi_to_f32(a.w);
-    }
-    float mn = fminf(fminf(fminf(v[0], v[1]), fminf(v[2], v[3])), fminf(fminf(v[4], v[5]), fminf(v[6], v[7])));
-    float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
-    group_minmax<LANES>(mn, mx);
+}
 
-    uint32_t zb = f32_to_bf16_rne(mn);
-    zb = (zb & 0x7FFFu) ? zb : 0u;                    // -0 -> +0
-    const float range = mx - mn;
-    const float step = range / QMAX;                  // IEEE divide
-    const uint32_t sb = f32_to_bf16_rne(step);
-    const float zf = bf16_bits_to_f32(zb);
-    const float sf = bf16_bits_to_f32(sb);
-    const GroupRecip r = make_recip(sf);
-
-    uint32_t q[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        float n = v[k] - zf;
-        float y = __builtin_fmaf(n, r.rh, n * r.rl);
-        y = fminf(fmaxf(y, 0.0f), QMAX);
-        q[k] = (uint32_t)__builtin_rintf(y);
-    }
-
-    const int g = cw / LANES;
-    const int ngroups = d / G;
-    if (live && (cw % LANES) == 0) {
-        scale[row_out * ngroups + g] = (uint16_t)sb;
-        zero[row_out * ngroups + g] = (uint16_t)zb;
-    }
-
+// Workgroup (t, b) quantises input row b*T + t into cache row b*cap + start[b] + t; a thread
+// takes 16 consecutive channels at a time.  In DELTA mode the value quantised is
+// x - acc[b][start[b]+t] (fp32).  d/16 is a multiple of G/16, so a group's lanes are either all
+// inside the row or all past it (those recompute the row's last piece and store nothing).
+template <int BITS, int G, bool DELTA>
+__global__ __launch_bounds__(256) void quantize_append_kernel(
+    const uint4* __restrict__ x, const uint4* __restrict__ acc, uint8_t* __restrict__ codes,
+    uint16_t* __restrict__ scale, uint16_t* __restrict__ zero, int T, int cap, int d, BatchI32 start)
+{
+    constexpr int LANES = G / 16;
+    constexpr float QMAX = (float)((1 << BITS) - 1);
+    const int t = blockIdx.x, b = blockIdx.y;
+    const long long row_in = (long long)b * T + t;
+    const long long row_out = (long long)b * cap + start.v[b] + t;
+    const int ppr = d >> 4;                               // 16-channel pieces per row
+    const uint4* xr = x + row_in * (d >> 3);
+    const uint4* ar = DELTA ? acc + row_out * (d >> 3) : nullptr;
     uint8_t* rowp = codes + row_out * ((long long)d * BITS / 8);
-    if constexpr (BITS == 8) {
-        uint2 w;
-        w.x = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
-        w.y = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
-        if (live) reinterpret_cast<uint2*>(rowp)[cw] = w;
-    } else if constexpr (BITS == 4) {
-        uint32_t w = 0;
+    uint16_t* srow = scale + row_out * (d / G);
+    uint16_t* zrow = zero + row_out * (d / G);
+
+    for (int p0 = 0; p0 < ppr; p0 += blockDim.x) {
+        const int pi = p0 + (int)threadIdx.x;
+        const bool live = pi < ppr;
+        const int pc = live ? pi : ppr - 1;
+        const uint4 raw0 = xr[2 * pc], raw1 = xr[2 * pc + 1];
+        float v[16];
+        unpack8(raw0, v);
+        unpack8(raw1, v + 8);
+        if constexpr (DELTA) {
+            const uint4 a0 = ar[2 * pc], a1 = ar[2 * pc + 1];
+            float av[16];
+            unpack8(a0, av);
+            unpack8(a1, av + 8);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) w |= q[k] << (4 * k);
-        if (live) reinterpret_cast<uint32_t*>(rowp)[cw] = w;
-    } else if constexpr (BITS == 2) {
-        uint32_t w = 0;
+            for (int k = 0; k < 16; ++k) v[k] -= av[k];
+        }
+        float mn = v[0], mx = v[0];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) w |= q[k] << (2 * k);
-        if (live) reinterpret_cast<uint16_t*>(rowp)[cw] = (uint16_t)w;
-    } else {   // 3 bits: 24 bits per lane, four lanes make three dwords
-        uint32_t w = 0;
+        for (int k = 1; k < 16; k += 2) {                 // v_min3_f32 / v_max3_f32
+            const float lo = k + 1 < 16 ? v[k + 1] : v[k];
+            mn = fminf(fminf(mn, v[k]), lo);
+            mx = fmaxf(fmaxf(mx, v[k]), lo);
+        }
+        group_minmax<LANES>(mn, mx);
+
+        uint32_t zb = f32_to_bf16_rne(mn);
+        zb = (zb & 0x7FFFu) ? zb : 0u;                    // -0 -> +0
+        const float range = mx - mn;
+        const float step = range / QMAX;                  // IEEE divide
+        const uint32_t sb = f32_to_bf16_rne(step);
+        const float zf = bf16_bits_to_f32(zb);
+        const float sf = bf16_bits_to_f32(sb);
+        const GroupRecip r = make_recip(sf);
+
+        uint32_t q[16];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) w |= q[k] << (3 * k);
-        const uint32_t nxt = dpp_u32<DPP_QUAD_NEXT>(w);
-        const int j = threadIdx.x & 3;
-        const uint32_t out = (w >> (8 * j)) | (nxt << (24 - 8 * j));
-        if (live && j < 3) reinterpret_cast<uint32_t*>(rowp)[(cw >> 2) * 3 + j] = out;
+        for (int k = 0; k < 16; ++k) {
+            const float n = v[k] - zf;
+            float y = __builtin_fmaf(n, r.rh, n * r.rl);
+            y = fminf(fmaxf(y, 0.0f), QMAX);
+            q[k] = (uint32_t)__builtin_rintf(y);
+        }
+        if (live && (pi % LANES) == 0) {
+            srow[pi / LANES] = (uint16_t)sb;
+            zrow[pi / LANES] = (uint16_t)zb;
+        }
+
+        if constexpr (BITS == 8) {
+            uint4 w;
+            w.x = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+            w.y = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
+            w.z = q[8] | (q[9] << 8) | (q[10] << 16) | (q[11] << 24);
+            w.w = q[12] | (q[13] << 8) | (q[14] << 16) | (q[15] << 24);
+            if (live) reinterpret_cast<uint4*>(rowp)[pi] = w;
+        } else if constexpr (BITS == 4) {
+            uint2 w = {0u, 0u};
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { w.x |= q[k] << (4 * k); w.y |= q[8 + k] << (4 * k); }
+            if (live) reinterpret_cast<uint2*>(rowp)[pi] = w;
+        } else if constexpr (BITS == 2) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) w |= q[k] << (2 * k);
+            if (live) reinterpret_cast<uint32_t*>(rowp)[pi] = w;
+        } else {   // 3 bits: 48 bits per lane, two lanes make three dwords
+            uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { w0 |= q[k] << (3 * k); w1 |= q[8 + k] << (3 * k); }
+            const uint32_t lo = w0 | (w1 << 24), hi = w1 >> 8;          // bits 0-31, 32-47
+            const uint32_t lo_other = dpp_u32<DPP_QUAD_XOR1>(lo);
+            uint8_t* pair = rowp + 12 * (pi >> 1);
+            if (live) {
+                if ((pi & 1) == 0) {
+                    Dword2 w; w.a = lo; w.b = hi | (lo_other << 16);
+                    *reinterpret_cast<Dword2*>(pair) = w;
+                } else {
+                    reinterpret_cast<uint32_t*>(pair)[2] = (lo >> 16) | (hi << 16);
+                }
+            }
+        }
     }
 }
 
@@ -138,12 +164,11 @@ template <int BITS, int G, bool DELTA>
 static hipError_t launch(const uint16_t* x, const uint16_t* acc, const xq_cache_t* c, int T,
                          const BatchI32& start, hipStream_t s)
 {
-    const long long nchunks = (long long)c->B * T * (c->fmt.d / 8);
-    const int block = 256;
-    const long long grid = (nchunks + block - 1) / block;
-    quantize_append_kernel<BITS, G, DELTA><<<dim3((unsigned)grid), dim3(block), 0, s>>>(
+    const int ppr = c->fmt.d / 16;
+    const int block = ppr >= 256 ? 256 : (ppr + 63) / 64 * 64;
+    quantize_append_kernel<BITS, G, DELTA><<<dim3((unsigned)T, (unsigned)c->B), dim3(block), 0, s>>>(
         reinterpret_cast<const uint4*>(x), reinterpret_cast<const uint4*>(acc), c->codes, c->scale,
-        c->zero, T, c->cap, c->fmt.d, start, nchunks);
+        c->zero, T, c->cap, c->fmt.d, start);
     return hipGetLastError();
 }
 
