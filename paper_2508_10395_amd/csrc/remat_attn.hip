@@ -74,7 +74,6 @@ constexpr int n_code_images(int bits)
 }
 constexpr int lds_scales_off(int bits) { return LDS_CODES_OFF + n_code_images(bits) * code_image_bytes(bits); }
 constexpr int lds_coded_total(int bits) { return lds_scales_off(bits) + 3 * LDS_SCALES_BYTES; }
-constexpr int LDS_DENSE_TOTAL = 2 * SLAB_BYTES;
 
 struct RematParams {
     const uint16_t* q;       // [B][Hq][128]
@@ -605,26 +604,65 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
 }
 
 // =====================================================================================
-// dense source (XQuant-CL accumulator, bf16): token fragments come straight from HBM.  Per
-// k-step a lane loads the 16 bytes of its token's 8 channels; the two half-waves read adjacent
-// pieces, and the fragments of the next slab are loaded early in the current one into a second
-// register set, so that their latency is hidden by the time the slab barrier waits for them.
+// dense source (XQuant-CL accumulator, bf16).  A wave needs, per half slab (4 k-steps = 64
+// channels), 128 contiguous bytes of each of its 32 token rows.  Loading them straight into the
+// MFMA fragment layout touches 32 rows per instruction and keeps the texture unit busy longer
+// than the MFMAs take; instead 4 LDS-DMA instructions fetch 8 rows x 128 B each (8 cache lines
+// per instruction) into a 4 KiB staging area private to the wave, and 4 ds_read_b128 bring the
+// fragments into registers.  Only the wave itself touches its staging area: the hand-over needs
+// s_waitcnt, no barrier.  The 16-byte pieces are placed so that both the DMA's linear LDS
+// write and the fragment read are conflict-free:  piece p of row r of block j sits in slot
+// 8 (r%8) + (p ^ f),  f = ((r%8) >> 1) | ((j & 1) << 2).
+// Per half slab h (32 MFMA slots): slot 16 takes the fragments of half h+1 out of staging, slots
+// 20-23 issue the DMA of half h+2.
 // =====================================================================================
+constexpr int LDS_DENSE_STAGE_OFF = 2 * SLAB_BYTES;
+constexpr int LDS_DENSE_STAGE_BYTES = 4096;            // per wave
+constexpr int LDS_DENSE_TOTAL = LDS_DENSE_STAGE_OFF + 8 * LDS_DENSE_STAGE_BYTES;
+static_assert(LDS_DENSE_TOTAL <= LDS_MAX, "dense kernel LDS");
+
 __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams p)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     TileCtx c;
     if (!locate_tile(p, c)) return;
-    const int lane = c.lane, wave = c.wave, half = c.half;
-    const int dma_turn = wave >> 2;
+    const int lane = c.lane, wave = c.wave, half = c.half, tl = c.tl;
 
     const uint8_t* wsrc = p.wprep + (long long)c.hk * p.head_bytes + wave * 1024;
     const uint32_t dma_voff = (uint32_t)lane * 16u;
-    const uint32_t lds_w = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds + wave * 1024;
+    const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds;
+    const uint32_t lds_w = lds_base + wave * 1024;
     const uint8_t* my_slab = lds + lane * 16;
     const uint8_t* cbase = reinterpret_cast<const uint8_t*>(p.acc) + (long long)c.b * p.cap * p.d * 2;
-    // k-step ks of slab s: channels 128 s + 16 ks + 8 half + [0, 8)
-    const uint32_t coff = (uint32_t)min(c.tok, c.len - 1) * (uint32_t)(p.d * 2) + half * 16;
+    const uint32_t row_bytes = (uint32_t)p.d * 2u;
+    const int n_halves = 2 * p.n_main_slabs;
+
+    // DMA side: lane = (row r8 of the block, slot column); block j covers the wave's tokens 8j .. 8j+7
+    uint32_t xvoff[4];
+    {
+        const int r8 = lane >> 3, sc = lane & 7;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int piece = sc ^ ((r8 >> 1) | ((j & 1) << 2));
+            const int tok = c.tile * TILE_TOKENS + wave * CHUNK_TOKENS + 8 * j + r8;
+            xvoff[j] = (uint32_t)min(tok, c.len - 1) * row_bytes + (uint32_t)piece * 16u;
+        }
+    }
+    const uint32_t stage = lds_base + LDS_DENSE_STAGE_OFF + wave * LDS_DENSE_STAGE_BYTES;
+    // fragment side: this lane's token tl, k-step kk of the half slab -> piece 2 kk + half
+    const uint8_t* my_stage = lds + LDS_DENSE_STAGE_OFF + wave * LDS_DENSE_STAGE_BYTES + (tl >> 3) * 1024 + (tl & 7) * 128;
+    const int fx = ((tl & 7) >> 1) | (((tl >> 3) & 1) << 2);
+    auto issue_x = [&](int h) {                           // token rows of half slab h -> staging
+        const int hc = min(h, n_halves - 1);              // (past the end: a harmless repeat)
+        const uint8_t* src = cbase + (long long)hc * 128;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dma_b128(src, xvoff[j], stage + j * 1024);
+    };
+    auto take_x = [&](uint4 (&dst)[4]) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            dst[kk] = *reinterpret_cast<const uint4*>(my_stage + (((2 * kk + half) ^ fx) * 16));
+    };
 
     f32x16 acc[8];
 #pragma unroll
@@ -633,53 +671,56 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
         for (int i = 0; i < 16; ++i) acc[nb][i] = 0.0f;
 
     uint4 af[8];                         // weight fragments, ring over slots (loaded 7 slots ahead)
-    uint4 bd[8], bdn[8];                 // token fragments of the current / next slab
+    uint4 bd[2][4];                      // token fragments of the two halves of a slab
 
     issue_slab(wsrc, lds_w, dma_voff);
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) bd[ks] = *reinterpret_cast<const uint4*>(cbase + coff + ks * 32);
+    issue_x(0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    take_x(bd[0]);
 #pragma unroll
     for (int sl = 0; sl < 7; ++sl) af[sl] = *reinterpret_cast<const uint4*>(my_slab + sl * 1024);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staging has been read: it may be refilled
+    issue_x(1);
 
     for (int it = 0; it < p.n_main_slabs; ++it) {
         const bool more_main = it + 1 < p.n_main_slabs;
-        const int s_next = more_main ? it + 1 : it;
+        const int s_next = more_main ? it + 1 : it;       // (the last iteration repeats itself into unused buffers)
         const uint32_t wdst = lds_w + (uint32_t)(((it + 1) & 1) * SLAB_BYTES);
         const uint8_t* wnext = wsrc + (long long)s_next * SLAB_BYTES;
         const uint8_t* slab = my_slab + (it & 1) * SLAB_BYTES;
         const uint8_t* slab_next = my_slab + ((it + 1) & 1) * SLAB_BYTES;
-        const uint8_t* xnext = cbase + coff + s_next * 256;
         __builtin_amdgcn_sched_barrier(0);
         static_for<0, 64>([&](auto SIDX) XQ_INLINE_LAMBDA {
             constexpr int sidx = decltype(SIDX)::value;
             constexpr int ks = sidx >> 3, m = sidx & 7;
+            constexpr int hs = sidx & 31, hf = sidx >> 5;            // slot inside the half slab, which half
             acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                __builtin_bit_cast(bf16x8, af[m]), __builtin_bit_cast(bf16x8, bd[ks]), acc[m], 0, 0, 0);
-            // next slab's weights: 8 DMA steps per wave, one every other slot, the two waves of a
-            // SIMD on alternate slots; its token fragments: one load every other slot after that
-            if constexpr ((sidx >> 1) < 8) {
-                if (more_main && (sidx & 1) == dma_turn)
-                    dma_b128(wnext + (sidx >> 1) * 8192, dma_voff, wdst + (sidx >> 1) * 8192);
-            } else if constexpr ((sidx >> 1) < 16) {
-                if (more_main && (sidx & 1) == dma_turn)
-                    bdn[(sidx >> 1) - 8] = *reinterpret_cast<const uint4*>(xnext + ((sidx >> 1) - 8) * 32);
+                __builtin_bit_cast(bf16x8, af[m]), __builtin_bit_cast(bf16x8, bd[hf][ks & 3]), acc[m], 0, 0, 0);
+            // next slab's weights: 4 DMA steps per half slab, one every other slot
+            if constexpr (hs < 8 && (hs & 1) == 0)
+                dma_b128(wnext + (hf * 4 + (hs >> 1)) * 8192, dma_voff, wdst + (hf * 4 + (hs >> 1)) * 8192);
+            // token rows: outstanding behind the DMA of the next half are this half's 4 weight steps
+            if constexpr (hs == 16) {
+                asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                take_x(bd[hf ^ 1]);
             }
-            // the next slab has landed for everyone (its buffer was last read one slab ago)
+            if constexpr (hs == 20) {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                issue_x(2 * it + hf + 2);
+            }
+            // the next slab's weights have landed for everyone (its buffer was last read one slab
+            // ago); the newest 4 DMAs, the token rows just issued, may still be in flight
             if constexpr (ks == SLAB_KSTEPS - 1 && m == 1) {
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
                 __syncthreads();
             }
             if constexpr (sidx + 7 < 64) af[(sidx + 7) & 7] = *reinterpret_cast<const uint4*>(slab + (sidx + 7) * 1024);
             else if (more_main) af[(sidx + 7) & 7] = *reinterpret_cast<const uint4*>(slab_next + (sidx + 7 - 64) * 1024);
             __builtin_amdgcn_sched_barrier(0);
         });
-        if (more_main) {
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) bd[ks] = bdn[ks];
-        }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing may still be writing this workgroup's LDS
     attention_epilogue(p, c, acc);
 }
 
