@@ -476,22 +476,18 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     }
 
     // Multiplies chunk CIDX (of 3,3,3,3,2,2 registers) of one block's accumulator by h.  The empty
-    // asm statements pin the multiplies between the neighbouring scheduling fences: pure
-    // arithmetic is otherwise free to drift during instruction selection.
+    // asm statement consumes the products here, in its slot: pure arithmetic is otherwise free to
+    // drift to the end of the loop body during instruction selection.
     auto rescale_chunk = [&](f32x16& a, auto CIDX, float h) XQ_INLINE_LAMBDA {
         constexpr int cidx = decltype(CIDX)::value;
         constexpr int off = cidx < 4 ? 3 * cidx : 12 + 2 * (cidx - 4);
-        float x0 = a[off], x1 = a[off + 1];
+        float x0 = a[off] * h, x1 = a[off + 1] * h;
         if constexpr (cidx < 4) {
-            float x2 = a[off + 2];
-            asm volatile("" : "+v"(x0), "+v"(x1), "+v"(x2));
-            x0 *= h; x1 *= h; x2 *= h;
-            asm volatile("" : "+v"(x0), "+v"(x1), "+v"(x2));
+            float x2 = a[off + 2] * h;
+            asm volatile("" :: "v"(x0), "v"(x1), "v"(x2));
             a[off + 2] = x2;
         } else {
-            asm volatile("" : "+v"(x0), "+v"(x1));
-            x0 *= h; x1 *= h;
-            asm volatile("" : "+v"(x0), "+v"(x1));
+            asm volatile("" :: "v"(x0), "v"(x1));
         }
         a[off] = x0; a[off + 1] = x1;
     };
