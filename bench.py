@@ -192,7 +192,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": "c2 Llama-2-7B-shaped decode step, one layer: d=4096, 32x128 MHA, batch 8, "
                                "context 4096, X cache 3-bit asym group 128; step = quantize+append 1 token/seq "

@@ -136,7 +136,7 @@ xq_status_t xq_prepare_weights(const xq_attn_t *a, int32_t d, int32_t group, int
  *   len      host [B], 1 <= len[b] <= cap
  *   out      dev [B][n_q_heads][head_dim] fp32
  *   workspace dev, >= xq_remat_attn_workspace_bytes(...) bytes, 16-byte aligned; holds the
- *            per-chunk softmax partials and a token-major copy of the scales; contents are scratch
+ *            per-chunk softmax partials and a tile-ordered copy of the scales; contents are scratch
  * B is taken from xcache->B, or passed in `B` when acc_bf16 is the source.
  * xq_remat_attn_workspace_bytes: max_len = max_b len[b]; d and group are those of the X cache,
  * group = 0 when the accumulator is the source.  Returns 0 for an invalid combination.

@@ -1,8 +1,11 @@
 // Offline weight preparation for the rematerialisation kernel (weights are static;
 // run once per layer).  Re-lays [Wk_h | Wv_h] (Sec. 3.1 / the W_kv concatenation of
 // Sec. 3.3.2 in arxiv 2508.10395) into the slab stream described in
-// remat_layout.hpp and appends the per-group column sums the kernel needs to apply
-// zero-points and the unpacker's "+1" offset exactly.
+// remat_layout.hpp and appends the per-group column sums the kernel needs to apply the
+// zero-points.  For coded sources the stream holds fp16 (the codes are fp16 operands, see
+// unpack.hpp): a bf16 weight times a power of two is exact in fp16 unless it falls below
+// 2^-14 (then it is rounded to the fp16 subnormal grid, an error of at most 2^-25) or above
+// 65504 (clamped; weights that large are outside the supported range).
 #include "common.hpp"
 #include "remat_layout.hpp"
 #include "unpack.hpp"
@@ -13,7 +16,7 @@ struct PrepArgs {
     const uint16_t* Wk;
     const uint16_t* Wv;
     uint8_t* out;
-    float* colsum;   // [2][Hkv][ng][256]: plain sums, then sums of the scaled rows
+    float* colsum;   // [Hkv][ng][256]: per-group sums of the weight rows
     int d, G, bits, Hkv, ncols;
     int n_main_slabs, ng, ng_pad, n_corr_slabs;
     long long head_bytes;
@@ -26,23 +29,13 @@ __device__ __forceinline__ float wval(const PrepArgs& a, int h, int c, int n)
     return bf16_bits_to_f32(W[(long long)c * a.ncols + h * 128 + (n & 127)]);
 }
 
-// code position (0..31 inside its unit) of hidden channel c
-__device__ __forceinline__ int code_pos(const PrepArgs& a, int c) { return (c % (a.G / 2)) & 31; }
-
 __global__ __launch_bounds__(256) void colsum_kernel(PrepArgs a)
 {
     const int n = threadIdx.x;
     const int g = blockIdx.x, h = blockIdx.y;
-    float s = 0.0f, sp = 0.0f;
-    for (int k = 0; k < a.G; ++k) {
-        const int c = g * a.G + k;
-        const float w = wval(a, h, c, n);
-        s += w;
-        sp += ldexpf(w, a.tab.wexp_of_code[code_pos(a, c)]);
-    }
-    const long long idx = ((long long)h * a.ng + g) * 256 + n;
-    a.colsum[idx] = s;
-    a.colsum[(long long)a.Hkv * a.ng * 256 + idx] = sp;
+    float s = 0.0f;
+    for (int k = 0; k < a.G; ++k) s += wval(a, h, g * a.G + k, n);
+    a.colsum[((long long)h * a.ng + g) * 256 + n] = s;
 }
 
 // one thread = one lane's 16 bytes of one fragment; grid (slab, head), block 512 x 8 k-steps... see launch
@@ -72,7 +65,13 @@ __global__ __launch_bounds__(256) void pack_main_kernel(PrepArgs a)
                 c = cs_ * 128 + gi * a.G + half * (a.G / 2) + u * 32 + p;
                 e = a.tab.wexp_of_code[p];
             }
-            v[i] = f32_to_bf16_rne(ldexpf(wval(a, h, c, n), e));   // exact: power-of-two scaling
+            const float wv = ldexpf(wval(a, h, c, n), e);          // exact: power-of-two scaling
+            if (dense) {
+                v[i] = f32_to_bf16_rne(wv);
+            } else {
+                const _Float16 hv = (_Float16)fminf(fmaxf(wv, -65504.0f), 65504.0f);
+                v[i] = (uint32_t)__builtin_bit_cast(uint16_t, hv);
+            }
         }
         uint4 o;
         o.x = v[0] | (v[1] << 16); o.y = v[2] | (v[3] << 16);
@@ -106,8 +105,7 @@ __global__ __launch_bounds__(256) void pack_corr_kernel(PrepArgs a)
             uint32_t bits = 0;
             if (term < N_CORR_TERMS && g < a.ng) {
                 const long long idx = ((long long)h * a.ng + g) * 256 + n;
-                if (term < 2) bits = split_part(a.colsum[idx], term);
-                else bits = split_part(a.colsum[(long long)a.Hkv * a.ng * 256 + idx], term - 2);
+                bits = split_part(a.colsum[idx], term);
             }
             v[i] = bits;
         }

@@ -10,18 +10,18 @@
 // scales, its score, its softmax weight) is a per-lane scalar and is unpacked once.
 //
 // The cached codes are not dequantised to bf16 (that rounding alone would exceed
-// the 2e-3 budget): the codes are dropped into bf16 mantissas (1 + code*2^(o-7),
-// exact) and the MFMA accumulates per quantisation group
-//     P_g = sum_k (1 + c_k 2^(o_k-7)) W'_k.
-// With e_g = 2^b * scale_g the rematerialised value is
-//     K[n][t] = sum_g e_g P_g[n]  +  sum_g ( zero_g S_g[n] - e_g S'_g[n] ).
+// the 2e-3 budget): the code bits are masked into fp16 mantissas under a zero
+// exponent, i.e. they enter the fp16 MFMA as the subnormals c_k 2^(o_k-24), exactly,
+// at one v_and_b32 per pair of codes, and the MFMA accumulates per quantisation group
+//     P_g = sum_k (c_k 2^(o_k-24)) W'_k,      W'_k = W_k 2^(10-o_k-b)  (fp16, exact).
+// With e_g = 2^(b+14) * scale_g the rematerialised value is
+//     K[n][t] = sum_g e_g P_g[n]  +  sum_g zero_g S_g[n],    S_g = sum of the group's weight rows.
 // The first sum is carried in one accumulator by rescaling it with e_{g-1}/e_g at
 // each group boundary (Horner form, one v_mul per register per group, relative
-// error ~2^-23 per group); the second is a rank-(4 d/G) product done by a few extra
-// MFMA k-steps whose token-side operands are the stored zero-points and minus the
-// effective scales (exact in bf16) and whose weight-side operands are bf16 hi/lo
-// splits of the column sums.  A zero stored scale uses e_g = 1 (its codes are all
-// zero, so only the column-sum term matters and it cancels exactly as for any e_g).
+// error ~2^-23 per group); the second is a rank-(3 d/G) product done by a few extra
+// bf16 MFMA k-steps whose token-side operands are the stored zero-points (exact in
+// bf16) and whose weight-side operands are bf16 hi/mid/lo splits of the column sums.
+// A zero stored scale uses e_g = 1 (its codes are all zero).
 //
 // Data movement of the coded kernel: everything the contraction loop consumes
 // arrives by LDS-DMA (global_load_lds): the weight slab, the tile's packed codes of
@@ -58,6 +58,7 @@ __device__ __forceinline__ void static_for(F&& f)
 #define XQ_INLINE_LAMBDA __attribute__((always_inline))
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 // LDS: two weight slabs, then (coded sources) the tile's packed codes of one slab -- two such
@@ -83,7 +84,6 @@ struct RematParams {
     const uint16_t* acc;     // dense source
     const uint8_t* wprep;
     const uint16_t* eT;      // coded source: effective scales [B][tiles][ng (+1 pad)][256], bf16
-    const uint16_t* negE;    // coded source: minus the effective scales, token-major [B][tiles*256][ng], bf16
     float* part_o;           // [B][Hq][chunks_per_seq][128]
     float* part_ml;          // [B][Hq][chunks_per_seq][2]
     int B, cap, d, Hq, Hkv;
@@ -116,10 +116,10 @@ __device__ __forceinline__ void issue_slab(const uint8_t* src, uint32_t lds_dst,
     for (int c = 0; c < 8; ++c) dma_b128(src + c * 8192, voff, lds_dst + c * 8192);
 }
 
-__device__ __forceinline__ bf16x8 as_frag(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+__device__ __forceinline__ f16x8 as_frag(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
 {
     uint4 v; v.x = a; v.y = b; v.z = c; v.w = d;
-    return __builtin_bit_cast(bf16x8, v);
+    return __builtin_bit_cast(f16x8, v);
 }
 
 __device__ __forceinline__ float wave32_max(float v)   // all-reduce over each 32-lane half
@@ -144,13 +144,13 @@ __device__ __forceinline__ float wave32_sum(float v)
 // One k-step of one unit for one token block, dispatching on the (compile-time after
 // unrolling) k-step index inside the unit.
 template <int BITS>
-__device__ __forceinline__ void unpack_kstep(const uint32_t* unit, int j, uint32_t one, uint32_t* out)
+__device__ __forceinline__ void unpack_kstep(const uint32_t* unit, int j, uint32_t* out)
 {
     switch (j & 3) {
-        case 0: UnpackKStep<BITS, 0>::run(unit, one, out); break;
-        case 1: UnpackKStep<BITS, 1>::run(unit, one, out); break;
-        case 2: UnpackKStep<BITS, 2>::run(unit, one, out); break;
-        default: UnpackKStep<BITS, 3>::run(unit, one, out); break;
+        case 0: UnpackKStep<BITS, 0>::run(unit, out); break;
+        case 1: UnpackKStep<BITS, 1>::run(unit, out); break;
+        case 2: UnpackKStep<BITS, 2>::run(unit, out); break;
+        default: UnpackKStep<BITS, 3>::run(unit, out); break;
     }
 }
 
@@ -271,7 +271,6 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     const long long seq_row0 = (long long)c.b * p.cap;
     const uint32_t row_bytes = (uint32_t)(p.d * BITS / 8);
     const uint8_t* cbase = p.codes + seq_row0 * row_bytes;
-    const uint16_t* nbase = p.negE + (long long)c.b * p.tiles_per_seq * TILE_TOKENS * p.ng;   // minus the effective scales
     const uint16_t* zbase = p.zero + seq_row0 * p.ng;
     const uint8_t* ebase = reinterpret_cast<const uint8_t*>(p.eT) +
                            ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.ng + 1) * 512;
@@ -309,8 +308,6 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     uint32_t cur[NDW];                   // packed codes of the current slab
     float E[2 * GPS];                    // effective scales: groups of the previous slab, then of the current one
     float hr_b[NB];                      // Horner factors E[k] / E[k+1] of the boundaries seen this slab
-    uint32_t one = BF16_ONE_PAIR;
-    asm volatile("" : "+v"(one));        // keep the constant in a VGPR (operand of v_and_or_b32)
 
     // effective scales of the slab processed at main iteration `iter` (its buffer is iter & 1)
     auto fetch_scales = [&](int sbuf, float* e) {
@@ -358,8 +355,8 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         }
     };
 
-    // ==== phase 1: the zero-point / offset correction (scale 1), a few k-steps whose token-side
-    // operands are the stored zero-points and minus the effective scales.  Its operands are loaded
+    // ==== phase 1: the zero-point correction (scale 1), a few bf16 k-steps whose token-side
+    // operands are the stored zero-points.  Its operands are loaded
     // first thing, so their latency hides behind the first weight DMA.  The codes and scales of the
     // slab that cyclically precedes the first one arrive meanwhile: the lagging column blocks start
     // inside it (see phase 2).
@@ -367,7 +364,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     auto load_meta = [&](int kk) -> uint4 {
         const int kappa0 = kk * 16 + half * 8;
         const int term = kappa0 / p.ng_pad, g0 = kappa0 % p.ng_pad;
-        const uint16_t* mbase = term < 2 ? zbase : nbase;
+        const uint16_t* mbase = zbase;
         uint4 v = {0u, 0u, 0u, 0u};
         if (kk < p.n_corr_ksteps && term < N_CORR_TERMS) {
             if (vec_meta) {
@@ -455,7 +452,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     // units of 1) are brought to those scales.
 #pragma unroll
     for (int ks = 1; ks < SLAB_KSTEPS; ++ks)
-        unpack_kstep<BITS>(&cur[(ks / KSG) * NDW_G + ((ks % KSG) >> 2) * BITS], ks % KSG, one, ub[ks]);
+        unpack_kstep<BITS>(&cur[(ks / KSG) * NDW_G + ((ks % KSG) >> 2) * BITS], ks % KSG, ub[ks]);
     const int par0 = n_corr_slabs & 1;                 // weight buffer of main iteration 0
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -472,7 +469,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         }
 #pragma unroll
         for (int k = 0; k < NB; ++k) hr_b[k] = E[k] * __builtin_amdgcn_rcpf(E[k + 1]);
-        unpack_kstep<BITS>(&cur[0], 0, one, ub[0]);
+        unpack_kstep<BITS>(&cur[0], 0, ub[0]);
     }
 
     // Multiplies chunk CIDX (of 3,3,3,3,2,2 registers) of one block's accumulator by h.  The empty
@@ -543,8 +540,8 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                 constexpr int sidx = decltype(SIDX)::value;
                 constexpr int ks = sidx >> 3, m = sidx & 7;
                 const uint32_t* b = ub[(ks + 1 + m) & 7];
-                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8, af[m]), as_frag(b[0], b[1], b[2], b[3]), acc[m], 0, 0, 0);
+                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                    __builtin_bit_cast(f16x8, af[m]), as_frag(b[0], b[1], b[2], b[3]), acc[m], 0, 0, 0);
 
                 // DMA of the next slab: 11 steps per wave, one every other slot.  (Issued in bursts they
                 // fill the address FIFO and the issuing wave stalls with its MFMAs behind them.)
@@ -564,10 +561,10 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                 if constexpr (ks + 1 < SLAB_KSTEPS) {
                     if constexpr (m == 2) {
                         constexpr int gi1 = (ks + 1) / KSG, ksg1 = (ks + 1) % KSG;
-                        unpack_kstep<BITS>(&cur[gi1 * NDW_G + (ksg1 >> 2) * BITS], ksg1, one, ub[ks + 1]);
+                        unpack_kstep<BITS>(&cur[gi1 * NDW_G + (ksg1 >> 2) * BITS], ksg1, ub[ks + 1]);
                     }
                 } else if constexpr (m == 7) {               // cur already holds the next slab's codes
-                    if (more_main) unpack_kstep<BITS>(&cur[0], 0, one, ub[0]);
+                    if (more_main) unpack_kstep<BITS>(&cur[0], 0, ub[0]);
                 }
                 // the next slab's scales are in LDS since the previous slab
                 if constexpr (ks == SLAB_KSTEPS - 2 && m == 4) { if (more_main) fetch_scales((it + 1) & 1, e_nxt); }
@@ -720,13 +717,11 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
     attention_epilogue(p, c, acc);
 }
 
-// ---- pre-pass of the coded kernel: effective scales e = 2^bits * scale (1 for a zero scale)
+// ---- pre-pass of the coded kernel: effective scales e = 2^(bits+14) * scale (1 for a zero scale)
 // as bf16, laid out [sequence][tile][group (+1 pad)][256 tokens] so that a tile's scales of
-// one group are contiguous (tokens past len repeat the last row), and -e token-major
-// [sequence][row][group] as the ready-made operand of the zero-scale correction.
+// one group are contiguous (tokens past len repeat the last row).
 __global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __restrict__ scale,
-                                                              uint16_t* __restrict__ eT,
-                                                              uint16_t* __restrict__ negE, int cap, int ng,
+                                                              uint16_t* __restrict__ eT, int cap, int ng,
                                                               int tiles_per_seq, int bits, BatchI32 len)
 {
     const int tile = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
@@ -736,10 +731,8 @@ __global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __
     uint16_t* dst = eT + ((long long)b * tiles_per_seq + tile) * (long long)(ng + 1) * TILE_TOKENS + t;
     for (int g = 0; g < ng; ++g) {
         const uint32_t sb = scale[row * ng + g];
-        const uint32_t e = sb ? sb + ((uint32_t)bits << 7) : 0x3F80u;
+        const uint32_t e = sb ? sb + ((uint32_t)(bits + F16_SUBNORMAL_EXP - F16_MANT_BITS) << 7) : 0x3F80u;
         dst[(long long)g * TILE_TOKENS] = (uint16_t)e;
-        if (tile * TILE_TOKENS + t < L)
-            negE[(((long long)b * tiles_per_seq + tile) * TILE_TOKENS + t) * ng + g] = (uint16_t)(e | 0x8000u);
     }
     dst[(long long)ng * TILE_TOKENS] = 0x3F80u;       // pad group (fetched, never used)
 }
@@ -797,13 +790,11 @@ static hipError_t launch_with_lds(K kernel, int lds_bytes, const RematParams& p,
 
 size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool coded)
 {
-    const size_t cap_rows = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS * TILE_TOKENS;   // negE rows per sequence
     const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
     const size_t chunks = tiles * (TILE_TOKENS / CHUNK_TOKENS);
     size_t bytes = (size_t)B * Hq * chunks * (128 + 2) * sizeof(float);
     if (coded) {
         bytes += (size_t)B * tiles * (size_t)(d / group + 1) * TILE_TOKENS * sizeof(uint16_t);   // eT
-        bytes += (size_t)B * cap_rows * (size_t)(d / group) * sizeof(uint16_t);                  // negE
     }
     return bytes;
 }
@@ -832,15 +823,13 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
     p.part_o = static_cast<float*>(ws);
     p.part_ml = p.part_o + (size_t)B * p.Hq * p.chunks_per_seq * 128;
     uint16_t* eT = reinterpret_cast<uint16_t*>(p.part_ml + (size_t)B * p.Hq * p.chunks_per_seq * 2);
-    uint16_t* negE = eT + (size_t)B * p.tiles_per_seq * (size_t)(L.ng + 1) * TILE_TOKENS;
     p.eT = eT;
-    p.negE = negE;
 
     const int grid = p.Hkv * p.B * p.tiles_per_seq;
     hipError_t e = hipErrorInvalidValue;
     if (xc) {
         scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
-            xc->scale, eT, negE, cap, L.ng, p.tiles_per_seq, bits, len);
+            xc->scale, eT, cap, L.ng, p.tiles_per_seq, bits, len);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

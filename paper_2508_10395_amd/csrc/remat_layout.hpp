@@ -17,11 +17,11 @@
 //                  inside the unit;
 //                  channel = 128 s' + G gi + (G/2) half + 32 u + code_of_slot[j][i],
 //                  value scaled by 2^wexp_of_code (see unpack.hpp).
-// Correction slabs (coded sources only) hold, for contraction index
+// Main slabs hold bf16 for the dense source and fp16 for coded sources.
+// Correction slabs (coded sources only, bf16) hold, for contraction index
 // kappa = 16 kk + 8 half + i, term = kappa / ng_pad, group g = kappa % ng_pad:
-//   term 0,1: bf16 hi, lo parts of S_g[n]  = sum of the group's weight rows
-//   term 2,3: bf16 hi, lo parts of S'_g[n] = sum of the scaled weight rows
-// against which the kernel multiplies the zero-points and minus the scales.
+//   term 0,1,2: bf16 hi, mid, lo parts of S_g[n] = sum of the group's weight rows
+// against which the kernel multiplies the stored zero-points.
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
@@ -30,7 +30,7 @@ namespace xq {
 
 constexpr int SLAB_KSTEPS = 8;
 constexpr int SLAB_BYTES = 65536;
-constexpr int N_CORR_TERMS = 4;
+constexpr int N_CORR_TERMS = 3;
 constexpr int COL_BLOCK_LAG_MAX = 7;  // coded sources: column block nb lags by 7 - nb k-steps
 constexpr int TILE_TOKENS = 256;     // tokens per workgroup
 constexpr int CHUNK_TOKENS = 32;     // tokens per wave = one softmax partial
@@ -56,7 +56,7 @@ inline WPrepLayout make_wprep_layout(int d, int G, int bits, int Hkv)
     }
     L.head_bytes = (size_t)(L.n_main_slabs + L.n_corr_slabs) * SLAB_BYTES;
     L.stream_bytes = L.head_bytes * Hkv;
-    L.colsum_bytes = (size_t)2 * Hkv * L.ng * 256 * sizeof(float);
+    L.colsum_bytes = (size_t)Hkv * L.ng * 256 * sizeof(float);
     L.total_bytes = L.stream_bytes + L.colsum_bytes;
     return L;
 }

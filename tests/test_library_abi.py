@@ -37,7 +37,7 @@ def test_format_queries():
     a = xq.XQAttn(32, 32, 128, 0.1)
     assert xq.xq_remat_attn_workspace_bytes(a, 8, 4096, 4096, 0) == 8 * 32 * 128 * 130 * 4
     assert xq.xq_remat_attn_workspace_bytes(a, 8, 4097, 4096, 0) == 8 * 32 * 136 * 130 * 4
-    assert xq.xq_remat_attn_workspace_bytes(a, 8, 4096, 4096, 128) == 8 * 32 * 128 * 130 * 4 + 8 * 16 * 33 * 512 + 8 * 4096 * 32 * 2
+    assert xq.xq_remat_attn_workspace_bytes(a, 8, 4096, 4096, 128) == 8 * 32 * 128 * 130 * 4 + 8 * 16 * 33 * 512
     assert xq.xq_remat_attn_workspace_bytes(a, 8, 4096, 4096, 32) == 0
     assert xq.xq_prepared_weights_bytes(a, 4096, 128, 3) > 2 * 4096 * 4096 * 2
     assert xq.xq_prepared_weights_bytes(a, 4096, 128, 5) == 0
