@@ -149,6 +149,38 @@ xq_status_t xq_remat_attn_decode(const xq_attn_t *a, const uint16_t *q_bf16,
                                  const void *wprep, const int32_t *len, float *out,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Sec. 3.3.1 (models with grouped-query attention): with the offline decompositions
+ * Wk = Uk Sk Bk^T and Wv = Uv Sv Bv^T (SVD, rank r = n_kv_heads*head_dim), the cache holds the
+ * latent row [x Uk | x Uv] (2r channels) of every token, quantised like any other X cache, and K,
+ * V are rematerialised as (x Uk)(Sk Bk^T) and (x Uv)(Sv Bv^T) with the fused r x r matrices.
+ *
+ * xq_latent_project: the down-projection of M token rows,
+ *   out[m][n] = bf16( sum_c x[m][c] * Ut[n][c] ),   fp32 accumulation, one RNE rounding.
+ *   x_bf16   dev [M][d] bf16
+ *   Ut_bf16  dev [n_lat][d] bf16: U TRANSPOSED, one row per latent channel (for the layout above:
+ *            rows 0..r-1 = columns of Uk, rows r..2r-1 = columns of Uv)
+ *   out_bf16 dev [M][n_lat] bf16, ready for xq_quantize_append with fmt.d = n_lat
+ *   d must be a multiple of 128, n_lat a multiple of 32; M = 0 is a no-op.
+ *
+ * xq_prepare_weights_latent: prepared stream for a latent cache with fmt.d = 2r:
+ *   Wfk, Wfv dev [r][n_kv_heads*head_dim] bf16 row-major = Sk Bk^T and Sv Bv^T
+ *   src_bits 2, 3 or 4; r a multiple of 128; out as for xq_prepare_weights with d = 2r
+ *   (size: xq_prepared_weights_bytes(a, 2r, group, src_bits)).
+ *
+ * xq_remat_attn_decode_latent: as xq_remat_attn_decode with an X cache, for a latent cache and a
+ *   stream from xq_prepare_weights_latent; the first r channels feed only K, the last r only V.
+ *   Workspace size: xq_remat_attn_workspace_bytes(a, B, max_len, 2r, group).
+ */
+xq_status_t xq_latent_project(const uint16_t *x_bf16, const uint16_t *Ut_bf16, int32_t M, int32_t d,
+                              int32_t n_lat, uint16_t *out_bf16, void *stream);
+xq_status_t xq_prepare_weights_latent(const xq_attn_t *a, int32_t r, int32_t group, int32_t src_bits,
+                                      const uint16_t *Wfk, const uint16_t *Wfv, void *out, size_t out_bytes,
+                                      void *stream);
+xq_status_t xq_remat_attn_decode_latent(const xq_attn_t *a, const uint16_t *q_bf16,
+                                        const xq_cache_t *latent, const void *wprep, const int32_t *len,
+                                        float *out, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,6 +27,11 @@
  *                          (textbook attention; two passes, in double).
  *   xqo_remat_attn_pairs   composition of the above for a list of
  *                          (sequence, query-head) pairs; nothing else.
+ *   xqo_project_rows       Sec. 3.3.1 (grouped-query models): down-projection of X
+ *                          into the latent space of an offline SVD, X U, stored
+ *                          as bf16.  (Rematerialising from the latent cache needs
+ *                          nothing new: it is xqo_remat_attn_pairs with the
+ *                          block-diagonal weights [[S_k B_k^T, 0], [0, S_v B_v^T]].)
  *
  * Arithmetic: everything the bit-exact contract covers (min/max, scale, zero,
  * codes, accumulator) is done in IEEE fp32 with explicit fmaf where a fused
@@ -47,7 +52,9 @@
  * cache sizes printed in the paper's tables, identity-quantiser remat == numpy
  * matmul, the cross-layer telescoping identity and depth-independent error
  * bound, attention closed forms (uniform scores, two-token logistic weight,
- * shift/permutation/split invariance) and scipy softmax.  The absolute
+ * shift/permutation/split invariance) and scipy softmax; for the latent path,
+ * numpy matmul in fp64, exactly representable factors whose product must come
+ * back bit for bit, and U S B^T = W closing the loop to plain X W.  The absolute
  * attention outputs on the synthetic benchmark inputs have no printed value in
  * the paper: for those, parity is pinned only through the chain above.
  */
@@ -326,6 +333,41 @@ void xqo_remat_attn_pairs(const uint8_t *packed, const uint16_t *scale,
         xqo_attention(q_bf16 + ((int64_t)b * Hq + hq) * hd, K, V, L, hd,
                       softmax_scale, out + (int64_t)p * hd);
         free(K); free(V); free(xhat);
+    }
+}
+
+/* ------------------------------------------------------- latent (GQA) --- */
+
+/* out[m][n] = bf16( sum_c x[m][c] * Ut[n][c] ), double accumulation, c ascending, one rounding
+ * (double -> float -> bf16 would round twice; the sum is rounded to bf16 directly). */
+static uint16_t f64_to_bf16_rne(double v)
+{
+    /* nearest bf16 to v, ties to even: round the float candidate pair exactly */
+    float f = (float)v;                       /* within half an fp32 ulp of v */
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint32_t lo = u & 0xFFFF0000u;            /* bf16 neighbours of f in magnitude order */
+    uint32_t hi = lo + 0x00010000u;
+    float flo, fhi;
+    memcpy(&flo, &lo, 4);
+    memcpy(&fhi, &hi, 4);
+    double dlo = fabs(v - (double)flo), dhi = fabs((double)fhi - v);
+    if (dlo < dhi) return (uint16_t)(lo >> 16);
+    if (dhi < dlo) return (uint16_t)(hi >> 16);
+    return (uint16_t)(((lo >> 16) & 1u) ? (hi >> 16) : (lo >> 16));
+}
+
+void xqo_project_rows(const uint16_t *x_bf16, const uint16_t *ut_bf16, int64_t M, int d, int n_lat,
+                      uint16_t *out_bf16)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int n = 0; n < n_lat; ++n) {
+            double s = 0.0;
+            for (int c = 0; c < d; ++c)
+                s += (double)bf16_bits_to_float(x_bf16[m * d + c]) * (double)bf16_bits_to_float(ut_bf16[(int64_t)n * d + c]);
+            out_bf16[m * n_lat + n] = f64_to_bf16_rne(s);
+        }
     }
 }
 

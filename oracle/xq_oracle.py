@@ -119,6 +119,20 @@ def cl_accumulate_rows(acc_bf16, codes, scale, zero, G, init):
     return acc_bf16
 
 
+def project_rows(x_bf16, Ut_bf16):
+    """Latent down-projection (Sec. 3.3.1): x [M][d] bf16 bits, Ut [n_lat][d] bf16 bits (U transposed)
+    -> [M][n_lat] bf16 bits of x U, accumulated in double and rounded once."""
+    x = _c(x_bf16, np.uint16)
+    ut = _c(Ut_bf16, np.uint16)
+    d = x.shape[-1]
+    n_lat = ut.shape[0]
+    assert ut.shape[1] == d
+    M = x.size // d
+    out = np.empty((*x.shape[:-1], n_lat), np.uint16)
+    lib().xqo_project_rows(_p(x), _p(ut), C.c_int64(M), C.c_int(d), C.c_int(n_lat), _p(out))
+    return out
+
+
 def remat_head(xhat_f32, W_bf16, col0, hd):
     x = _c(xhat_f32, np.float32)
     W = _c(W_bf16, np.uint16)

@@ -20,6 +20,7 @@ SYMBOLS = [
     "xq_quantize_append", "xq_cl_delta_quantize", "xq_cl_accumulate",
     "xq_prepared_weights_bytes", "xq_prepare_weights",
     "xq_remat_attn_workspace_bytes", "xq_remat_attn_decode",
+    "xq_latent_project", "xq_prepare_weights_latent", "xq_remat_attn_decode_latent",
 ]
 
 
@@ -80,6 +81,16 @@ def load_library():
                                          C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                          C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_size_t,
                                          C.c_void_p]
+    lib.xq_latent_project.restype = C.c_int
+    lib.xq_latent_project.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                      C.c_void_p]
+    lib.xq_prepare_weights_latent.restype = C.c_int
+    lib.xq_prepare_weights_latent.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xq_remat_attn_decode_latent.restype = C.c_int
+    lib.xq_remat_attn_decode_latent.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
+                                                C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_size_t,
+                                                C.c_void_p]
     _LIB = lib
     return lib
 
@@ -230,4 +241,51 @@ def xq_remat_attn_decode(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=Non
     _check(load_library().xq_remat_attn_decode(C.byref(a), _ptr(q_bf16), cptr, _ptr(acc_bf16), B, cap, d,
                                                _ptr(wprep), _i32(lens, B), _ptr(out), _ptr(workspace),
                                                workspace.numel(), _stream()), "xq_remat_attn_decode")
+    return out
+
+
+def xq_latent_project(x_bf16, Ut_bf16, out=None):
+    """x [..., d] bf16 times U (given transposed, [n_lat][d]) -> [..., n_lat] bf16."""
+    assert x_bf16.dtype == torch.bfloat16 and x_bf16.is_contiguous()
+    assert Ut_bf16.dtype == torch.bfloat16 and Ut_bf16.is_contiguous() and Ut_bf16.dim() == 2
+    d = x_bf16.shape[-1]
+    n_lat = Ut_bf16.shape[0]
+    assert Ut_bf16.shape[1] == d
+    M = x_bf16.numel() // d
+    if out is None:
+        out = torch.empty((*x_bf16.shape[:-1], n_lat), dtype=torch.bfloat16, device=x_bf16.device)
+    _check(load_library().xq_latent_project(_ptr(x_bf16), _ptr(Ut_bf16), M, d, n_lat, _ptr(out), _stream()),
+           "xq_latent_project")
+    return out
+
+
+def xq_prepare_weights_latent(attn, r, group, src_bits, Wfk, Wfv, out=None):
+    """Prepared stream for a latent cache [X Uk | X Uv]; Wfk, Wfv [r][Hkv*hd] = S B^T of the two SVDs."""
+    assert Wfk.dtype == torch.bfloat16 and Wfv.dtype == torch.bfloat16
+    assert Wfk.is_contiguous() and Wfv.is_contiguous()
+    nbytes = xq_prepared_weights_bytes(attn, 2 * r, group, src_bits)
+    if nbytes == 0:
+        raise XQError("xq_prepare_weights_latent: unsupported combination")
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=Wfk.device)
+    a = attn.c_struct()
+    _check(load_library().xq_prepare_weights_latent(C.byref(a), r, group, src_bits, _ptr(Wfk), _ptr(Wfv), _ptr(out),
+                                                    out.numel(), _stream()), "xq_prepare_weights_latent")
+    return out
+
+
+def xq_remat_attn_decode_latent(attn, q_bf16, wprep, lens, latent, out=None, workspace=None):
+    """As xq_remat_attn_decode for a latent cache (fmt.d = 2r) and a stream from xq_prepare_weights_latent."""
+    assert q_bf16.dtype == torch.bfloat16 and q_bf16.is_contiguous()
+    lens = [int(v) for v in lens]
+    a = attn.c_struct()
+    cs = latent.c_struct()
+    need = xq_remat_attn_workspace_bytes(attn, latent.B, max(lens) if lens else 1, latent.d, latent.group)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q_bf16.device)
+    if out is None:
+        out = torch.empty((latent.B, attn.n_q_heads, attn.head_dim), dtype=torch.float32, device=q_bf16.device)
+    _check(load_library().xq_remat_attn_decode_latent(C.byref(a), _ptr(q_bf16), C.byref(cs), _ptr(wprep),
+                                                      _i32(lens, latent.B), _ptr(out), _ptr(workspace),
+                                                      workspace.numel(), _stream()), "xq_remat_attn_decode_latent")
     return out

@@ -6,7 +6,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libxquant.so")
-SOURCES = ["api.hip", "quantize.hip", "cl_accumulate.hip", "prepare_weights.hip", "remat_attn.hip"]
+SOURCES = ["api.hip", "quantize.hip", "cl_accumulate.hip", "prepare_weights.hip", "remat_attn.hip",
+           "latent_project.hip"]
 HEADERS = ["common.hpp", "remat_layout.hpp", "unpack.hpp"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -10,11 +10,14 @@ hipError_t run_quantize_append(const xq_cache_t* c, const uint16_t* x, const uin
                                const BatchI32& start, hipStream_t s);
 hipError_t run_cl_accumulate(uint16_t* acc, const xq_cache_t* c, const BatchI32& len, int max_len,
                              bool init, hipStream_t s);
-hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, void* out,
-                               hipStream_t s);
+hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, int split_rows,
+                               void* out, hipStream_t s);
+hipError_t run_latent_project(const uint16_t* x, const uint16_t* ut, int M, int d, int n_lat, uint16_t* out,
+                              hipStream_t s);
 hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
-                                 const BatchI32& len, int max_len, float* out, void* ws, hipStream_t s);
+                                 const BatchI32& len, int max_len, float* out, void* ws, bool split,
+                                 hipStream_t s);
 size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool coded);
 
 static bool fmt_ok(const xq_qfmt_t& f)
@@ -147,7 +150,35 @@ xq_status_t xq_prepare_weights(const xq_attn_t* a, int32_t d, int32_t group, int
     if (!wprep_combo_ok(d, group, src_bits)) return XQ_ERR_UNSUPPORTED;
     const WPrepLayout L = make_wprep_layout(d, src_bits == 16 ? 128 : group, src_bits, a->n_kv_heads);
     if (out_bytes < L.total_bytes) return XQ_ERR_WORKSPACE;
-    hipError_t e = run_prepare_weights(L, Wk, Wv, out, static_cast<hipStream_t>(stream));
+    hipError_t e = run_prepare_weights(L, Wk, Wv, 0, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+xq_status_t xq_prepare_weights_latent(const xq_attn_t* a, int32_t r, int32_t group, int32_t src_bits,
+                                      const uint16_t* Wfk, const uint16_t* Wfv, void* out, size_t out_bytes,
+                                      void* stream)
+{
+    xq_status_t st = check_attn(a);
+    if (st != XQ_OK) return st;
+    if (!Wfk || !Wfv || !out || !aligned16(Wfk) || !aligned16(Wfv) || !aligned16(out)) return XQ_ERR_INVALID_ARG;
+    if (r <= 0) return XQ_ERR_INVALID_ARG;
+    if (src_bits == 16 || r % 128 != 0 || !wprep_combo_ok(2 * r, group, src_bits)) return XQ_ERR_UNSUPPORTED;
+    const WPrepLayout L = make_wprep_layout(2 * r, group, src_bits, a->n_kv_heads);
+    if (out_bytes < L.total_bytes) return XQ_ERR_WORKSPACE;
+    hipError_t e = run_prepare_weights(L, Wfk, Wfv, r, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+xq_status_t xq_latent_project(const uint16_t* x_bf16, const uint16_t* Ut_bf16, int32_t M, int32_t d, int32_t n_lat,
+                              uint16_t* out_bf16, void* stream)
+{
+    if (M < 0 || d <= 0 || n_lat <= 0) return XQ_ERR_INVALID_ARG;
+    if (d % 128 != 0 || n_lat % 32 != 0) return XQ_ERR_UNSUPPORTED;
+    if (M == 0) return XQ_OK;
+    if (M > 65535 * 32) return XQ_ERR_UNSUPPORTED;
+    if (!x_bf16 || !Ut_bf16 || !out_bf16 || !aligned16(x_bf16) || !aligned16(Ut_bf16) || !aligned16(out_bf16))
+        return XQ_ERR_INVALID_ARG;
+    hipError_t e = run_latent_project(x_bf16, Ut_bf16, M, d, n_lat, out_bf16, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 
@@ -158,10 +189,10 @@ size_t xq_remat_attn_workspace_bytes(const xq_attn_t* a, int32_t B, int32_t max_
     return remat_workspace_bytes(B, a->n_q_heads, max_len, d, group ? group : 128, group != 0);
 }
 
-xq_status_t xq_remat_attn_decode(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* xcache,
-                                 const uint16_t* acc_bf16, int32_t B, int32_t cap, int32_t d,
-                                 const void* wprep, const int32_t* len, float* out, void* workspace,
-                                 size_t workspace_bytes, void* stream)
+static xq_status_t remat_attn_common(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* xcache,
+                                     const uint16_t* acc_bf16, int32_t B, int32_t cap, int32_t d,
+                                     const void* wprep, const int32_t* len, float* out, void* workspace,
+                                     size_t workspace_bytes, bool split, void* stream)
 {
     xq_status_t st = check_attn(a);
     if (st != XQ_OK) return st;
@@ -188,8 +219,27 @@ xq_status_t xq_remat_attn_decode(const xq_attn_t* a, const uint16_t* q_bf16, con
     if (workspace_bytes < xq_remat_attn_workspace_bytes(a, B, max_len, d, xcache ? xcache->fmt.group : 0))
         return XQ_ERR_WORKSPACE;
     hipError_t e = run_remat_attn_decode(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, lv, max_len, out,
-                                         workspace, static_cast<hipStream_t>(stream));
+                                         workspace, split, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+xq_status_t xq_remat_attn_decode(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* xcache,
+                                 const uint16_t* acc_bf16, int32_t B, int32_t cap, int32_t d,
+                                 const void* wprep, const int32_t* len, float* out, void* workspace,
+                                 size_t workspace_bytes, void* stream)
+{
+    return remat_attn_common(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, len, out, workspace, workspace_bytes,
+                             false, stream);
+}
+
+xq_status_t xq_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* latent,
+                                        const void* wprep, const int32_t* len, float* out, void* workspace,
+                                        size_t workspace_bytes, void* stream)
+{
+    if (!latent) return XQ_ERR_INVALID_ARG;
+    if (latent->fmt.d % 256 != 0) return XQ_ERR_UNSUPPORTED;      // two halves of whole 128-channel slabs
+    return remat_attn_common(a, q_bf16, latent, nullptr, 0, 0, 0, wprep, len, out, workspace, workspace_bytes,
+                             true, stream);
 }
 
 }  // extern "C"

@@ -18,14 +18,21 @@ struct PrepArgs {
     uint8_t* out;
     float* colsum;   // [Hkv][ng][256]: per-group sums of the weight rows
     int d, G, bits, Hkv, ncols;
+    int split_rows;  // > 0: latent layout, Wk feeds channels [0, split_rows), Wv channels [split_rows, d)
     int n_main_slabs, ng, ng_pad, n_corr_slabs;
     long long head_bytes;
     UnpackTable tab;
 };
 
+// element (channel c, column n of [Wk_h | Wv_h]) of the matrix the stream encodes
 __device__ __forceinline__ float wval(const PrepArgs& a, int h, int c, int n)
 {
-    const uint16_t* W = n < 128 ? a.Wk : a.Wv;
+    const bool kcol = n < 128;
+    if (a.split_rows > 0) {                            // block-diagonal [[Wk, 0], [0, Wv]]
+        if (kcol != (c < a.split_rows)) return 0.0f;
+        if (!kcol) c -= a.split_rows;
+    }
+    const uint16_t* W = kcol ? a.Wk : a.Wv;
     return bf16_bits_to_f32(W[(long long)c * a.ncols + h * 128 + (n & 127)]);
 }
 
@@ -129,10 +136,11 @@ bool unpack_table_for(int bits, UnpackTable* t)
     return t->valid != 0;
 }
 
-hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, void* out,
-                               hipStream_t s)
+hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, int split_rows,
+                               void* out, hipStream_t s)
 {
     PrepArgs a{};
+    a.split_rows = split_rows;
     a.Wk = Wk; a.Wv = Wv;
     a.out = static_cast<uint8_t*>(out);
     a.colsum = reinterpret_cast<float*>(a.out + L.stream_bytes);

@@ -242,7 +242,10 @@ __device__ __forceinline__ void attention_epilogue(const RematParams& p, const T
 // =====================================================================================
 // coded source (XQuant cache, BITS in {2,3,4})
 // =====================================================================================
-template <int BITS, int G>
+// SPLIT: the source is a latent cache [X Uk | X Uv] (Sec. 3.3.1) and the prepared weights are
+// block-diagonal -- the first half of the channels feeds only the K columns, the second half only
+// the V columns.  The MFMAs of the zero blocks are skipped; everything else is unchanged.
+template <int BITS, int G, bool SPLIT>
 __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams p)
 {
     constexpr int KSG = G / 16;                        // k-steps per quantisation group
@@ -533,6 +536,9 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         float hr_bn[NB];                                     // boundary factors of the next iteration
 #pragma unroll
         for (int k = 0; k < NB; ++k) hr_bn[k] = 1.0f;
+        // SPLIT: do this slab's / the previous slab's channels belong to the K half?
+        const bool k_half_cur = 2 * it < p.n_main_slabs;
+        const bool k_half_prev = it >= 1 && 2 * (it - 1) < p.n_main_slabs;
         __builtin_amdgcn_sched_barrier(0);
 
         static_for<0, 64>([&](auto SIDX) XQ_INLINE_LAMBDA {
@@ -540,8 +546,11 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                 constexpr int sidx = decltype(SIDX)::value;
                 constexpr int ks = sidx >> 3, m = sidx & 7;
                 const uint32_t* b = ub[(ks + 1 + m) & 7];
-                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                    __builtin_bit_cast(f16x8, af[m]), as_frag(b[0], b[1], b[2], b[3]), acc[m], 0, 0, 0);
+                // (block m multiplies k-step ks - 7 + m of this slab, or of the previous one if negative)
+                const bool k_half = (ks - 7 + m >= 0) ? k_half_cur : k_half_prev;
+                if (!SPLIT || k_half == (m < 4))
+                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                        __builtin_bit_cast(f16x8, af[m]), as_frag(b[0], b[1], b[2], b[3]), acc[m], 0, 0, 0);
 
                 // DMA of the next slab: 11 steps per wave, one every other slot.  (Issued in bursts they
                 // fill the address FIFO and the issuing wave stalls with its MFMAs behind them.)
@@ -801,7 +810,8 @@ size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool 
 
 hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
-                                 const BatchI32& len, int max_len, float* out, void* ws, hipStream_t s)
+                                 const BatchI32& len, int max_len, float* out, void* ws, bool split,
+                                 hipStream_t s)
 {
     const int bits = xc ? xc->fmt.bits : 16;
     const int G = xc ? xc->fmt.group : 128;
@@ -834,12 +844,18 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
         if (e != hipSuccess) return e;
     }
     switch (bits * 1000 + (bits == 16 ? 0 : G)) {
-        case 2064: e = launch_with_lds(remat_attn_coded_kernel<2, 64>, lds_coded_total(2), p, grid, s); break;
-        case 2128: e = launch_with_lds(remat_attn_coded_kernel<2, 128>, lds_coded_total(2), p, grid, s); break;
-        case 3064: e = launch_with_lds(remat_attn_coded_kernel<3, 64>, lds_coded_total(3), p, grid, s); break;
-        case 3128: e = launch_with_lds(remat_attn_coded_kernel<3, 128>, lds_coded_total(3), p, grid, s); break;
-        case 4064: e = launch_with_lds(remat_attn_coded_kernel<4, 64>, lds_coded_total(4), p, grid, s); break;
-        case 4128: e = launch_with_lds(remat_attn_coded_kernel<4, 128>, lds_coded_total(4), p, grid, s); break;
+        case 2064: e = split ? launch_with_lds(remat_attn_coded_kernel<2, 64, true>, lds_coded_total(2), p, grid, s)
+                         : launch_with_lds(remat_attn_coded_kernel<2, 64, false>, lds_coded_total(2), p, grid, s); break;
+        case 2128: e = split ? launch_with_lds(remat_attn_coded_kernel<2, 128, true>, lds_coded_total(2), p, grid, s)
+                         : launch_with_lds(remat_attn_coded_kernel<2, 128, false>, lds_coded_total(2), p, grid, s); break;
+        case 3064: e = split ? launch_with_lds(remat_attn_coded_kernel<3, 64, true>, lds_coded_total(3), p, grid, s)
+                         : launch_with_lds(remat_attn_coded_kernel<3, 64, false>, lds_coded_total(3), p, grid, s); break;
+        case 3128: e = split ? launch_with_lds(remat_attn_coded_kernel<3, 128, true>, lds_coded_total(3), p, grid, s)
+                         : launch_with_lds(remat_attn_coded_kernel<3, 128, false>, lds_coded_total(3), p, grid, s); break;
+        case 4064: e = split ? launch_with_lds(remat_attn_coded_kernel<4, 64, true>, lds_coded_total(4), p, grid, s)
+                         : launch_with_lds(remat_attn_coded_kernel<4, 64, false>, lds_coded_total(4), p, grid, s); break;
+        case 4128: e = split ? launch_with_lds(remat_attn_coded_kernel<4, 128, true>, lds_coded_total(4), p, grid, s)
+                         : launch_with_lds(remat_attn_coded_kernel<4, 128, false>, lds_coded_total(4), p, grid, s); break;
         case 16000: e = launch_with_lds(remat_attn_dense_kernel, LDS_DENSE_TOTAL, p, grid, s); break;
         default: e = hipErrorInvalidValue;
     }
