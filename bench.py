@@ -172,6 +172,33 @@ def main():
                                               "TFLOP/s": oflops / t_o / 1e9,
                                               "frac_mfma_peak": oflops / t_o / 1e9 / PEAK_BF16_TFLOPS}
             del ocache, owp, ows
+        # the same GQA layer served from the latent cache [X Uk | X Uv] (Sec. 3.3.1): r = 1024, cache width 2048
+        ow = xi.C4
+        r = ow.Hkv * ow.hd
+        oattn = xq.XQAttn(ow.Hq, ow.Hkv, ow.hd, ow.hd ** -0.5)
+        gen = torch.Generator(device=dev).manual_seed(4)
+        lat = torch.randn((ow.B, ow.L, 2 * r), device=dev, generator=gen).to(torch.bfloat16)
+        lcache = xq.alloc_cache(ow.B, ow.L, 2 * r, ow.G, ow.bits)
+        xq.xq_quantize_append(lcache, lat, [0] * ow.B)
+        wfk = (torch.randn((r, r), device=dev, generator=gen) * r ** -0.5).to(torch.bfloat16)
+        wfv = (torch.randn((r, r), device=dev, generator=gen) * r ** -0.5).to(torch.bfloat16)
+        lwp = xq.xq_prepare_weights_latent(oattn, r, ow.G, ow.bits, wfk, wfv)
+        lws = torch.empty(xq.xq_remat_attn_workspace_bytes(oattn, ow.B, ow.L, 2 * r, ow.G), dtype=torch.uint8, device=dev)
+        oq = dev_bf16(xi.gen_q(ow))
+        oout = torch.empty((ow.B, ow.Hq, ow.hd), dtype=torch.float32, device=dev)
+        olens = [ow.L] * ow.B
+        t_l = timed(lambda: xq.xq_remat_attn_decode_latent(oattn, oq, lwp, olens, lcache, out=oout, workspace=lws),
+                    n=5, warm=2)
+        lflops = 2.0 * ow.B * ow.L * r * (2 * r) + 4.0 * ow.B * ow.L * ow.Hq * ow.hd
+        ut = (torch.randn((2 * r, ow.d), device=dev, generator=gen) * ow.d ** -0.5).to(torch.bfloat16)
+        xnew = torch.randn((ow.B, 1, ow.d), device=dev, generator=gen).to(torch.bfloat16)
+        t_p = timed(lambda: xq.xq_latent_project(xnew, ut), n=20)
+        extra["remat_attn_c4_latent"] = {"workload": "c4 layer from the latent cache (r=1024, width 2048, 2-bit, group 64); "
+                                                     "random latent rows and fused matrices (timing only)",
+                                         "ms": t_l, "tokens/s/layer": ow.B * ow.L / (t_l * 1e-3),
+                                         "useful_TFLOP/s": lflops / t_l / 1e9,
+                                         "decode_projection_us": t_p * 1e3}
+        del lcache, lat, lwp, lws
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")

@@ -1,0 +1,140 @@
+"""GPU parity of the latent (grouped-query) path, Sec. 3.3.1 of arxiv 2508.10395:
+xq_latent_project, xq_prepare_weights_latent, xq_remat_attn_decode_latent against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import xq_inputs as xi
+from oracle import xq_oracle as xo
+from tests.util import bits_to_torch, rel_errors, torch_to_bits
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def xq():
+    import paper_2508_10395_amd as m
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    m.load_library()
+    return m
+
+
+def bf(x):
+    return xi.from_bf16_bits(x)
+
+
+def bits(x):
+    return xi.to_bf16_bits(np.asarray(x, np.float32))
+
+
+def _check_projection(got_bits, ref_bits, x_bits, ut_bits):
+    """fp32 accumulation against the oracle's double: the same bf16 number or its neighbour, up to
+    the fp32 accumulation error itself where the sum cancels to something tiny."""
+    g, r = bf(got_bits).astype(np.float64), bf(ref_bits).astype(np.float64)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(r), 1e-30))) - 7)
+    absum = np.abs(bf(x_bits)).astype(np.float64) @ np.abs(bf(ut_bits)).astype(np.float64).T
+    assert np.all(np.abs(g - r) <= ulp * 1.0001 + absum * 2.0 ** -20)
+    assert np.mean(got_bits != ref_bits) < 5e-3
+
+
+@pytest.mark.parametrize("M,d,n_lat", [(1, 256, 64), (16, 512, 256), (33, 384, 96), (300, 256, 512)])
+def test_projection_matches_oracle(xq, M, d, n_lat):
+    rng = np.random.default_rng(M + d)
+    x = bits(rng.standard_normal((M, d)))
+    ut = bits(rng.standard_normal((n_lat, d)) * d ** -0.5)
+    out = torch.full((M, n_lat), 9.0, dtype=torch.bfloat16, device="cuda")
+    xq.xq_latent_project(bits_to_torch(x), bits_to_torch(ut), out=out)
+    torch.cuda.synchronize()
+    _check_projection(torch_to_bits(out), xo.project_rows(x, ut), x, ut)
+
+
+def test_projection_exact_case_and_noop(xq):
+    rng = np.random.default_rng(5)
+    x = rng.integers(-1, 2, size=(40, 256)).astype(np.float32)
+    u = (rng.integers(0, 2, size=(256, 64)) * 2 - 1).astype(np.float32) / 16.0
+    out = xq.xq_latent_project(bits_to_torch(bits(x)), bits_to_torch(bits(u.T)))
+    torch.cuda.synchronize()
+    assert np.array_equal(bf(torch_to_bits(out)).astype(np.float64), x.astype(np.float64) @ u.astype(np.float64))
+    empty = torch.empty((0, 256), dtype=torch.bfloat16, device="cuda")
+    assert xq.xq_latent_project(empty, bits_to_torch(bits(u.T))).shape == (0, 64)
+
+
+def _svd_factors(w, cfg_seed):
+    """Offline step: W [d][Hkv*hd] (bf16 bits) -> U^T [r][d] and S B^T [r][Hkv*hd], both rounded to bf16."""
+    u, s, bt = np.linalg.svd(bf(w).astype(np.float64), full_matrices=False)
+    return bits(u.T), bits(np.diag(s) @ bt)
+
+
+def _run_latent(xq, w, bits_, G, lens, pairs=None):
+    """Project, quantise and attend on the GPU; the oracle attends over the very same latent cache
+    bytes with the block-diagonal fused weights."""
+    r = w.Hkv * w.hd
+    x = xi.gen_x(w)
+    wk, wv = xi.gen_weights(w)
+    q = xi.gen_q(w)
+    utk, wfk = _svd_factors(wk, 1)
+    utv, wfv = _svd_factors(wv, 2)
+    ut = np.concatenate([utk, utv], axis=0)                              # [2r][d]
+    lat = xq.xq_latent_project(bits_to_torch(x), bits_to_torch(ut))     # [B][L][2r]
+    torch.cuda.synchronize()
+    lat_bits = torch_to_bits(lat)
+    sample_rows = np.arange(0, w.L, max(1, w.L // 16))
+    _check_projection(lat_bits[0, sample_rows], xo.project_rows(x[0, sample_rows], ut), x[0, sample_rows], ut)
+    cache = xq.alloc_cache(w.B, w.L, 2 * r, G, bits_)
+    xq.xq_quantize_append(cache, lat, [0] * w.B)
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    wprep = xq.xq_prepare_weights_latent(attn, r, G, bits_, bits_to_torch(wfk), bits_to_torch(wfv))
+    out = xq.xq_remat_attn_decode_latent(attn, bits_to_torch(q), wprep, lens, cache)
+    plain = xq.xq_remat_attn_decode(attn, bits_to_torch(q), wprep, lens, xcache=cache)   # same stream, no skipping
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.array_equal(got, plain.cpu().numpy()), "skipping the zero blocks changed the result"
+    if pairs is None:
+        pairs = [(b, h) for b in range(w.B) for h in range(w.Hq)]
+    zk, zv = np.zeros_like(wfk), np.zeros_like(wfv)
+    ref = xo.remat_attn_pairs(q_bf16=q, Wk=np.concatenate([wfk, zv], axis=0), Wv=np.concatenate([zk, wfv], axis=0),
+                              Hq=w.Hq, Hkv=w.Hkv, hd=w.hd, softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs,
+                              packed=cache.codes.cpu().numpy(), scale=torch_to_bits(cache.scale),
+                              zero=torch_to_bits(cache.zero), G=G, bits=bits_)
+    sel = np.array([got[b, h] for b, h in pairs])
+    normwise, maxwise = rel_errors(sel, ref)
+    assert np.all(np.isfinite(sel)) and normwise.max() <= TOL and maxwise <= TOL, (float(normwise.max()), float(maxwise))
+    return float(normwise.max())
+
+
+@pytest.mark.parametrize("bits_,G", [(2, 64), (3, 128), (4, 128)])
+def test_latent_pipeline_small(xq, bits_, G):
+    w = xi.C4.scaled(B=3, L=420, d=512, Hq=8, Hkv=2, n_outlier=5)      # r = 256, g = 4
+    _run_latent(xq, w, bits_, G, lens=[420, 257, 31])
+
+
+def test_latent_close_to_plain_gqa_at_high_precision(xq):
+    """4-bit latent cache against the same layer served from the 4-bit naive X cache: two different
+    lossy encodings of the same K, V, so the outputs agree only roughly -- a sanity bound."""
+    w = xi.C4.scaled(B=1, L=300, d=512, Hq=8, Hkv=2, n_outlier=0)
+    r = w.Hkv * w.hd
+    x, (wk, wv), q = xi.gen_x(w), xi.gen_weights(w), xi.gen_q(w)
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    cache = xq.alloc_cache(1, w.L, w.d, 128, 4)
+    xq.xq_quantize_append(cache, bits_to_torch(x), [0])
+    plain = xq.xq_remat_attn_decode(attn, bits_to_torch(q), xq.xq_prepare_weights(attn, w.d, 128, 4, bits_to_torch(wk),
+                                    bits_to_torch(wv)), [w.L], xcache=cache).cpu().numpy()
+    utk, wfk = _svd_factors(wk, 1)
+    utv, wfv = _svd_factors(wv, 2)
+    lat = xq.xq_latent_project(bits_to_torch(x), bits_to_torch(np.concatenate([utk, utv], axis=0)))
+    lcache = xq.alloc_cache(1, w.L, 2 * r, 128, 4)
+    xq.xq_quantize_append(lcache, lat, [0])
+    wprep = xq.xq_prepare_weights_latent(attn, r, 128, 4, bits_to_torch(wfk), bits_to_torch(wfv))
+    latent = xq.xq_remat_attn_decode_latent(attn, bits_to_torch(q), wprep, [w.L], lcache).cpu().numpy()
+    normwise, _ = rel_errors(latent.reshape(-1, w.hd), plain.reshape(-1, w.hd))
+    assert normwise.max() < 0.25
+
+
+def test_full_size_llama3_8b_latent_sampled_pairs(xq):
+    """Config 4's shape served from the latent cache (r = 1024, cache width 2048): B=16, L=8192,
+    d=4096, 32 query / 8 KV heads, 2-bit, group 64."""
+    w = xi.C4
+    worst = _run_latent(xq, w, w.bits, w.G, [w.L] * w.B, pairs=xi.sample_pairs(w, 8))
+    print(f"c4 latent sampled pairs: worst norm-wise rel err {worst:.2e}")
