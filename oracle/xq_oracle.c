@@ -27,6 +27,8 @@
  *                          (textbook attention; two passes, in double).
  *   xqo_remat_attn_pairs   composition of the above for a list of
  *                          (sequence, query-head) pairs; nothing else.
+ *   xqo_rope_rows          rotary position embedding of rematerialised keys (half-split
+ *                          pairing, cos/sin table supplied by the caller).
  *   xqo_project_rows       Sec. 3.3.1 (grouped-query models): down-projection of X
  *                          into the latent space of an offline SVD, X U, stored
  *                          as bf16.  (Rematerialising from the latent cache needs
@@ -289,6 +291,32 @@ void xqo_attention(const uint16_t *q_bf16, const double *K, const double *V,
     free(s);
 }
 
+/* ------------------------------------------------------------------ RoPE --- */
+
+/*
+ * Rotary position embedding on rematerialised keys (the models the paper evaluates use it,
+ * and K = X Wk is the key BEFORE the rotation; RoFormer, Su et al., as cited in Sec. 2).
+ * Half-split pairing: element i pairs with i + hd/2.  For row t at position pos0 + t, with
+ * (cos, sin) = table[pos][i]:
+ *     k'[i]        = k[i] cos - k[i + hd/2] sin
+ *     k'[i + hd/2] = k[i + hd/2] cos + k[i] sin
+ * The table (fp32, [n_pos][hd/2][2]) is an input: the frequencies are the model's business.
+ */
+void xqo_rope_rows(double *K, int L, int hd, const float *cos_sin, int pos0)
+{
+    const int h2 = hd / 2;
+    for (int t = 0; t < L; ++t) {
+        const float *cs = cos_sin + (int64_t)(pos0 + t) * h2 * 2;
+        double *k = K + (int64_t)t * hd;
+        for (int i = 0; i < h2; ++i) {
+            const double c = (double)cs[2 * i], sn = (double)cs[2 * i + 1];
+            const double a = k[i], b = k[i + h2];
+            k[i] = a * c - b * sn;
+            k[i + h2] = b * c + a * sn;
+        }
+    }
+}
+
 /* ----------------------------------------------------------- composition --- */
 
 /*
@@ -300,14 +328,14 @@ void xqo_attention(const uint16_t *q_bf16, const double *K, const double *V,
  * Layouts: packed [B][cap][d*bits/8], scale/zero [B][cap][d/G],
  * acc [B][cap][d], q [B][Hq][hd], Wk/Wv [d][Hkv*hd], out [npairs][hd].
  */
-void xqo_remat_attn_pairs(const uint8_t *packed, const uint16_t *scale,
+static void remat_attn_pairs_impl(const uint8_t *packed, const uint16_t *scale,
                           const uint16_t *zero, const uint16_t *acc_bf16,
                           int cap, int d, int G, int bits,
                           const uint16_t *q_bf16, const uint16_t *Wk,
                           const uint16_t *Wv, int Hq, int Hkv, int hd,
                           double softmax_scale, const int32_t *len,
                           const int32_t *pair_b, const int32_t *pair_hq,
-                          int npairs, float *out)
+                          int npairs, const float *rope_cos_sin, const int32_t *pos0, float *out)
 {
     const int ngroups = d / G;
     const int64_t row_bytes = ((int64_t)d * bits) / 8;
@@ -330,10 +358,39 @@ void xqo_remat_attn_pairs(const uint8_t *packed, const uint16_t *scale,
         double *V = (double *)malloc(sizeof(double) * (size_t)L * hd);
         xqo_remat_head(xhat, Wk, L, d, Hkv * hd, hkv * hd, hd, K);
         xqo_remat_head(xhat, Wv, L, d, Hkv * hd, hkv * hd, hd, V);
+        if (rope_cos_sin) xqo_rope_rows(K, L, hd, rope_cos_sin, pos0[b]);
         xqo_attention(q_bf16 + ((int64_t)b * Hq + hq) * hd, K, V, L, hd,
                       softmax_scale, out + (int64_t)p * hd);
         free(K); free(V); free(xhat);
     }
+}
+
+void xqo_remat_attn_pairs(const uint8_t *packed, const uint16_t *scale,
+                          const uint16_t *zero, const uint16_t *acc_bf16,
+                          int cap, int d, int G, int bits,
+                          const uint16_t *q_bf16, const uint16_t *Wk,
+                          const uint16_t *Wv, int Hq, int Hkv, int hd,
+                          double softmax_scale, const int32_t *len,
+                          const int32_t *pair_b, const int32_t *pair_hq,
+                          int npairs, float *out)
+{
+    remat_attn_pairs_impl(packed, scale, zero, acc_bf16, cap, d, G, bits, q_bf16, Wk, Wv, Hq, Hkv, hd,
+                          softmax_scale, len, pair_b, pair_hq, npairs, NULL, NULL, out);
+}
+
+/* the same with the keys rotated (xqo_rope_rows) before the scores; q is taken as given (the caller
+ * rotates it at its own position); pos0[b] = position of cache row 0 of sequence b */
+void xqo_remat_attn_pairs_rope(const uint8_t *packed, const uint16_t *scale,
+                               const uint16_t *zero, const uint16_t *acc_bf16,
+                               int cap, int d, int G, int bits,
+                               const uint16_t *q_bf16, const uint16_t *Wk,
+                               const uint16_t *Wv, int Hq, int Hkv, int hd,
+                               double softmax_scale, const int32_t *len,
+                               const int32_t *pair_b, const int32_t *pair_hq,
+                               int npairs, const float *rope_cos_sin, const int32_t *pos0, float *out)
+{
+    remat_attn_pairs_impl(packed, scale, zero, acc_bf16, cap, d, G, bits, q_bf16, Wk, Wv, Hq, Hkv, hd,
+                          softmax_scale, len, pair_b, pair_hq, npairs, rope_cos_sin, pos0, out);
 }
 
 /* ------------------------------------------------------- latent (GQA) --- */

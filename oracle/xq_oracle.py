@@ -156,11 +156,13 @@ def attention(q_bf16, K, V, softmax_scale):
 
 
 def remat_attn_pairs(*, q_bf16, Wk, Wv, Hq, Hkv, hd, softmax_scale, lens, pairs,
-                     packed=None, scale=None, zero=None, G=0, bits=0, acc_bf16=None):
+                     packed=None, scale=None, zero=None, G=0, bits=0, acc_bf16=None,
+                     rope_cos_sin=None, pos0=None):
     """Attention output [npairs][hd] fp32 for the listed (b, q-head) pairs.
 
     Either (packed, scale, zero, G, bits) -- the X cache, layouts [B][cap][...] --
     or acc_bf16 [B][cap][d] -- the cross-layer accumulator.
+    rope_cos_sin (fp32 [n_pos][hd/2][2]) rotates the keys; pos0[b] = position of cache row 0.
     """
     q = _c(q_bf16, np.uint16)
     Wk = _c(Wk, np.uint16)
@@ -180,9 +182,26 @@ def remat_attn_pairs(*, q_bf16, Wk, Wv, Hq, Hkv, hd, softmax_scale, lens, pairs,
         cap = acc_bf16.shape[1]
         G, bits = d, 16
     out = np.empty((len(pairs), hd), np.float32)
-    lib().xqo_remat_attn_pairs(_p(packed), _p(scale), _p(zero), _p(acc_bf16), C.c_int(cap),
-                               C.c_int(d), C.c_int(G), C.c_int(bits), _p(q), _p(Wk), _p(Wv),
-                               C.c_int(Hq), C.c_int(Hkv), C.c_int(hd),
-                               C.c_double(softmax_scale), _p(lens), _p(pb), _p(ph),
-                               C.c_int(len(pairs)), _p(out))
+    args = [_p(packed), _p(scale), _p(zero), _p(acc_bf16), C.c_int(cap),
+            C.c_int(d), C.c_int(G), C.c_int(bits), _p(q), _p(Wk), _p(Wv),
+            C.c_int(Hq), C.c_int(Hkv), C.c_int(hd),
+            C.c_double(softmax_scale), _p(lens), _p(pb), _p(ph), C.c_int(len(pairs))]
+    if rope_cos_sin is None:
+        lib().xqo_remat_attn_pairs(*args, _p(out))
+    else:
+        tab = _c(rope_cos_sin, np.float32)
+        assert tab.ndim == 3 and tab.shape[1] == hd // 2 and tab.shape[2] == 2
+        p0 = _c(np.zeros(len(lens), np.int32) if pos0 is None else np.asarray(pos0, np.int32), np.int32)
+        assert int(p0.max()) + int(np.max(lens)) <= tab.shape[0]
+        lib().xqo_remat_attn_pairs_rope(*args, _p(tab), _p(p0), _p(out))
     return out
+
+
+def rope_rows(K, cos_sin, pos0=0):
+    """Rotate key rows K [L][hd] (float64, in place on a copy) by the table; returns the copy."""
+    K = np.array(K, np.float64, order="C")
+    tab = _c(cos_sin, np.float32)
+    L, hd = K.shape
+    assert tab.shape[1] == hd // 2 and pos0 + L <= tab.shape[0]
+    lib().xqo_rope_rows(_p(K), C.c_int(L), C.c_int(hd), _p(tab), C.c_int(pos0))
+    return K
