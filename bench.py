@@ -134,6 +134,11 @@ def main():
         t_dense = timed(lambda: xq.xq_remat_attn_decode(attn, q, wprep_dense, lens, acc_bf16=x, out=out, workspace=ws),
                         n=5, warm=1)
         t_app = timed(lambda: xq.xq_quantize_append(cache, x_new, [L - 1] * B), n=20)
+        inv = 10000.0 ** (-torch.arange(hd // 2, dtype=torch.float64) * 2.0 / hd)
+        ang = torch.arange(L, dtype=torch.float64)[:, None] * inv[None, :]
+        rope = torch.stack([torch.cos(ang), torch.sin(ang)], dim=-1).to(torch.float32).to(dev)
+        t_rope = timed(lambda: xq.xq_remat_attn_decode(attn, q, wprep, lens, xcache=cache, out=out, workspace=ws,
+                                                       rope_cos_sin=rope), n=10, warm=2)
         extra = {
             "quantize_bulk": {"workload": "xq_quantize_append T=4096 (whole context), c2 shape", "ms": t_q,
                               "GB/s": q_bytes / t_q / 1e6, "frac_hbm_peak": q_bytes / t_q / 1e6 / PEAK_HBM_GBS},
@@ -142,6 +147,7 @@ def main():
                               "GB/s": acc_bytes / t_acc / 1e6, "frac_hbm_peak": acc_bytes / t_acc / 1e6 / PEAK_HBM_GBS},
             "cl_delta_quantize_bulk": {"ms": t_dq, "GB/s": dq_bytes / t_dq / 1e6,
                                        "frac_hbm_peak": dq_bytes / t_dq / 1e6 / PEAK_HBM_GBS},
+            "remat_attn_with_rope_ms": t_rope,
             "remat_attn_dense_acc": {"workload": "XQuant-CL source (bf16 accumulator), c2 shape", "ms": t_dense,
                                      "TFLOP/s": flops / t_dense / 1e9,
                                      "frac_mfma_peak": flops / t_dense / 1e9 / PEAK_BF16_TFLOPS},

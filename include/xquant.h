@@ -150,6 +150,25 @@ xq_status_t xq_remat_attn_decode(const xq_attn_t *a, const uint16_t *q_bf16,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * xq_remat_attn_decode with rotary position embedding applied to the rematerialised keys (K = X^ Wk
+ * is the key before the rotation; the models the method targets rotate it; RoFormer, cited in
+ * Sec. 2).  Pairing: element i with i + head_dim/2.  For cache row t of sequence b, at position
+ * pos0[b] + t, with (cos, sin) = rope_cos_sin[position][i]:
+ *     k'[i] = k[i] cos - k[i+64] sin,    k'[i+64] = k[i+64] cos + k[i] sin.
+ *   rope_cos_sin   dev [rope_positions][head_dim/2][2] fp32 (cos, sin); the frequencies, and any
+ *                  scaling of them, are the caller's
+ *   pos0           host [B], pos0[b] >= 0 and pos0[b] + len[b] <= rope_positions
+ *   q_bf16         is used as given: the caller rotates the query at its own position
+ * Everything else as xq_remat_attn_decode.
+ */
+xq_status_t xq_remat_attn_decode_rope(const xq_attn_t *a, const uint16_t *q_bf16,
+                                      const xq_cache_t *xcache, const uint16_t *acc_bf16, int32_t B,
+                                      int32_t cap, int32_t d, const void *wprep, const int32_t *len,
+                                      const float *rope_cos_sin, int32_t rope_positions,
+                                      const int32_t *pos0, float *out, void *workspace,
+                                      size_t workspace_bytes, void *stream);
+
+/*
  * Sec. 3.3.1 (models with grouped-query attention): with the offline decompositions
  * Wk = Uk Sk Bk^T and Wv = Uv Sv Bv^T (SVD, rank r = n_kv_heads*head_dim), the cache holds the
  * latent row [x Uk | x Uv] (2r channels) of every token, quantised like any other X cache, and K,

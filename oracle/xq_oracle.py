@@ -192,7 +192,7 @@ def remat_attn_pairs(*, q_bf16, Wk, Wv, Hq, Hkv, hd, softmax_scale, lens, pairs,
         tab = _c(rope_cos_sin, np.float32)
         assert tab.ndim == 3 and tab.shape[1] == hd // 2 and tab.shape[2] == 2
         p0 = _c(np.zeros(len(lens), np.int32) if pos0 is None else np.asarray(pos0, np.int32), np.int32)
-        assert int(p0.max()) + int(np.max(lens)) <= tab.shape[0]
+        assert int((p0.astype(np.int64) + lens).max()) <= tab.shape[0]
         lib().xqo_remat_attn_pairs_rope(*args, _p(tab), _p(p0), _p(out))
     return out
 

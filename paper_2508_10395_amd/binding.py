@@ -21,6 +21,7 @@ SYMBOLS = [
     "xq_prepared_weights_bytes", "xq_prepare_weights",
     "xq_remat_attn_workspace_bytes", "xq_remat_attn_decode",
     "xq_latent_project", "xq_prepare_weights_latent", "xq_remat_attn_decode_latent",
+    "xq_remat_attn_decode_rope",
 ]
 
 
@@ -81,6 +82,11 @@ def load_library():
                                          C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                          C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_size_t,
                                          C.c_void_p]
+    lib.xq_remat_attn_decode_rope.restype = C.c_int
+    lib.xq_remat_attn_decode_rope.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
+                                              C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                              C.POINTER(C.c_int32), C.c_void_p, C.c_int32, C.POINTER(C.c_int32),
+                                              C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.xq_latent_project.restype = C.c_int
     lib.xq_latent_project.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                       C.c_void_p]
@@ -219,8 +225,11 @@ def xq_remat_attn_workspace_bytes(attn, B, max_len, d, group):
     return load_library().xq_remat_attn_workspace_bytes(C.byref(a), B, max_len, d, group)
 
 
-def xq_remat_attn_decode(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=None, out=None, workspace=None):
-    """Attention output fp32 [B][Hq][head_dim] over the first lens[b] cached rows."""
+def xq_remat_attn_decode(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=None, out=None, workspace=None,
+                         rope_cos_sin=None, pos0=None):
+    """Attention output fp32 [B][Hq][head_dim] over the first lens[b] cached rows.  With rope_cos_sin
+    (fp32 [n_pos][head_dim/2][2]) the call is xq_remat_attn_decode_rope: keys rotated, row t of sequence b
+    at position pos0[b] + t."""
     assert q_bf16.dtype == torch.bfloat16 and q_bf16.is_contiguous()
     if xcache is not None:
         B, cap, d = xcache.B, xcache.cap, xcache.d
@@ -238,6 +247,15 @@ def xq_remat_attn_decode(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=Non
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q_bf16.device)
     if out is None:
         out = torch.empty((B, attn.n_q_heads, attn.head_dim), dtype=torch.float32, device=q_bf16.device)
+    if rope_cos_sin is not None:
+        assert rope_cos_sin.dtype == torch.float32 and rope_cos_sin.is_contiguous() and rope_cos_sin.dim() == 3
+        pos0 = [0] * B if pos0 is None else pos0
+        _check(load_library().xq_remat_attn_decode_rope(C.byref(a), _ptr(q_bf16), cptr, _ptr(acc_bf16), B, cap, d,
+                                                        _ptr(wprep), _i32(lens, B), _ptr(rope_cos_sin),
+                                                        rope_cos_sin.shape[0], _i32(pos0, B), _ptr(out),
+                                                        _ptr(workspace), workspace.numel(), _stream()),
+               "xq_remat_attn_decode_rope")
+        return out
     _check(load_library().xq_remat_attn_decode(C.byref(a), _ptr(q_bf16), cptr, _ptr(acc_bf16), B, cap, d,
                                                _ptr(wprep), _i32(lens, B), _ptr(out), _ptr(workspace),
                                                workspace.numel(), _stream()), "xq_remat_attn_decode")

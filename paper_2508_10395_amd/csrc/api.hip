@@ -17,7 +17,7 @@ hipError_t run_latent_project(const uint16_t* x, const uint16_t* ut, int M, int 
 hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
                                  const BatchI32& len, int max_len, float* out, void* ws, bool split,
-                                 hipStream_t s);
+                                 const float* rope, const BatchI32* pos0, hipStream_t s);
 size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool coded);
 
 static bool fmt_ok(const xq_qfmt_t& f)
@@ -192,7 +192,8 @@ size_t xq_remat_attn_workspace_bytes(const xq_attn_t* a, int32_t B, int32_t max_
 static xq_status_t remat_attn_common(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* xcache,
                                      const uint16_t* acc_bf16, int32_t B, int32_t cap, int32_t d,
                                      const void* wprep, const int32_t* len, float* out, void* workspace,
-                                     size_t workspace_bytes, bool split, void* stream)
+                                     size_t workspace_bytes, bool split, const float* rope, int32_t rope_positions,
+                                     const int32_t* pos0, void* stream)
 {
     xq_status_t st = check_attn(a);
     if (st != XQ_OK) return st;
@@ -218,8 +219,16 @@ static xq_status_t remat_attn_common(const xq_attn_t* a, const uint16_t* q_bf16,
     }
     if (workspace_bytes < xq_remat_attn_workspace_bytes(a, B, max_len, d, xcache ? xcache->fmt.group : 0))
         return XQ_ERR_WORKSPACE;
+    BatchI32 pv{};
+    if (rope) {
+        if (!pos0 || !aligned16(rope) || rope_positions < 1) return XQ_ERR_INVALID_ARG;
+        for (int b = 0; b < B; ++b) {                     // every attended row must have a table row
+            if (pos0[b] < 0 || (long long)pos0[b] + len[b] > rope_positions) return XQ_ERR_INVALID_ARG;
+            pv.v[b] = pos0[b];
+        }
+    }
     hipError_t e = run_remat_attn_decode(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, lv, max_len, out,
-                                         workspace, split, static_cast<hipStream_t>(stream));
+                                         workspace, split, rope, &pv, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 
@@ -229,7 +238,18 @@ xq_status_t xq_remat_attn_decode(const xq_attn_t* a, const uint16_t* q_bf16, con
                                  size_t workspace_bytes, void* stream)
 {
     return remat_attn_common(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, len, out, workspace, workspace_bytes,
-                             false, stream);
+                             false, nullptr, 0, nullptr, stream);
+}
+
+xq_status_t xq_remat_attn_decode_rope(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* xcache,
+                                      const uint16_t* acc_bf16, int32_t B, int32_t cap, int32_t d,
+                                      const void* wprep, const int32_t* len, const float* rope_cos_sin,
+                                      int32_t rope_positions, const int32_t* pos0, float* out, void* workspace,
+                                      size_t workspace_bytes, void* stream)
+{
+    if (!rope_cos_sin) return XQ_ERR_INVALID_ARG;
+    return remat_attn_common(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, len, out, workspace, workspace_bytes,
+                             false, rope_cos_sin, rope_positions, pos0, stream);
 }
 
 xq_status_t xq_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* latent,
@@ -239,7 +259,7 @@ xq_status_t xq_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q_bf
     if (!latent) return XQ_ERR_INVALID_ARG;
     if (latent->fmt.d % 256 != 0) return XQ_ERR_UNSUPPORTED;      // two halves of whole 128-channel slabs
     return remat_attn_common(a, q_bf16, latent, nullptr, 0, 0, 0, wprep, len, out, workspace, workspace_bytes,
-                             true, stream);
+                             true, nullptr, 0, nullptr, stream);
 }
 
 }  // extern "C"

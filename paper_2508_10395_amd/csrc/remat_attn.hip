@@ -92,6 +92,8 @@ struct RematParams {
     long long head_bytes;
     float scale_log2e;       // softmax_scale * log2(e)
     BatchI32 len;
+    const float* rope;       // optional [n_pos][64][2] cos, sin: rotate the keys (half-split pairs)
+    BatchI32 pos0;           // with rope: position of cache row 0 of each sequence
 };
 
 // LDS-DMA: every active lane copies 16 bytes from saddr + voff to LDS at lds_dst + 16 * lane.
@@ -196,6 +198,27 @@ __device__ __forceinline__ bool locate_tile(const RematParams& p, TileCtx& c)
 __device__ __forceinline__ void attention_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8])
 {
     if (c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS >= c.len) return;     // chunk entirely past len
+    if (p.rope) {
+        // Rotary embedding of this token's key: column n < 64 pairs with n + 64, i.e. accumulator
+        // element i of block nb with the same element of block nb + 2.  The lane's 4 consecutive
+        // columns 32 nb + 8 i4 + 4 half + [0, 4) need 8 consecutive floats of its position's row.
+        const float* tab = p.rope + (long long)(p.pos0.v[c.b] + min(c.tok, c.len - 1)) * 128;
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const float* cs = tab + 2 * (nb * 32 + i4 * 8 + c.half * 4);
+                const float4 cs0 = *reinterpret_cast<const float4*>(cs);
+                const float4 cs1 = *reinterpret_cast<const float4*>(cs + 4);
+                const float co[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, si[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float a = acc[nb][i4 * 4 + k], b = acc[nb + 2][i4 * 4 + k];
+                    acc[nb][i4 * 4 + k] = __builtin_fmaf(a, co[k], -b * si[k]);
+                    acc[nb + 2][i4 * 4 + k] = __builtin_fmaf(b, co[k], a * si[k]);
+                }
+            }
+    }
     const int gq = p.Hq / p.Hkv;
     const int chunk = c.tile * (TILE_TOKENS / CHUNK_TOKENS) + c.wave;
     for (int j = 0; j < gq; ++j) {
@@ -811,7 +834,7 @@ size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool 
 hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
                                  const BatchI32& len, int max_len, float* out, void* ws, bool split,
-                                 hipStream_t s)
+                                 const float* rope, const BatchI32* pos0, hipStream_t s)
 {
     const int bits = xc ? xc->fmt.bits : 16;
     const int G = xc ? xc->fmt.group : 128;
@@ -830,6 +853,8 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
     p.head_bytes = (long long)L.head_bytes;
     p.scale_log2e = a->softmax_scale * 1.44269504088896340736f;
     p.len = len;
+    p.rope = rope;
+    if (rope) p.pos0 = *pos0;
     p.part_o = static_cast<float*>(ws);
     p.part_ml = p.part_o + (size_t)B * p.Hq * p.chunks_per_seq * 128;
     uint16_t* eT = reinterpret_cast<uint16_t*>(p.part_ml + (size_t)B * p.Hq * p.chunks_per_seq * 2);
