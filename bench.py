@@ -20,6 +20,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, published
+# HBM-side bytes of one launch of the fused kernel on this workload: rocprofv3 FETCH_SIZE + WRITE_SIZE,
+# each scaled by the factor that makes the counter read 256 MiB for a plain 256 MiB device copy
+# (profiles/remat_attn_coded_c2_hbm_traffic.txt; counters cannot be read from inside this process)
+K3_HBM_BYTES_PER_LAUNCH = 2.25e9
 
 
 def parse():
@@ -206,13 +210,7 @@ def main():
                                          "decode_projection_us": t_p * 1e3}
         del lcache, lat, lwp, lws
 
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("remat_attn_kernel_c2_bytes_per_launch")
-        except Exception:
-            traffic = None
+    traffic = K3_HBM_BYTES_PER_LAUNCH
 
     result = {
         "metric": "cached tokens rematerialized+attended/sec/layer",
