@@ -133,6 +133,17 @@ __device__ __forceinline__ float wave32_max(float v)   // all-reduce over each 3
     v = fmaxf(v, __shfl_xor(v, 16));
     return v;
 }
+// sum over each 32-lane half, valid in lanes 16-31 of the half only: the last step adds lane 15 of
+// the lower 16-lane row into the upper row with a DPP row broadcast instead of a cross-row permute
+__device__ __forceinline__ float wave32_sum_upper(float v)
+{
+    v += dpp_f32<DPP_QUAD_XOR1>(v);
+    v += dpp_f32<DPP_QUAD_XOR2>(v);
+    v += dpp_f32<DPP_ROW_HALF_MIRROR>(v);
+    v += dpp_f32<DPP_ROW_MIRROR>(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x142 /* row_bcast:15 */, 0xA, 0xF, false));
+    return v;
+}
 __device__ __forceinline__ float wave32_sum(float v)
 {
     v += dpp_f32<DPP_QUAD_XOR1>(v);
@@ -249,8 +260,8 @@ __device__ __forceinline__ void attention_epilogue(const RematParams& p, const T
                 float o[4];
 #pragma unroll
                 for (int k = 0; k < 4; ++k)   // masked tokens have p = 0 and their rows are clamped copies: finite
-                    o[k] = wave32_sum(pv * acc[4 + nb][i4 * 4 + k]);
-                if (c.tl == 0) {
+                    o[k] = wave32_sum_upper(pv * acc[4 + nb][i4 * 4 + k]);
+                if (c.tl == 16) {
                     float4 w; w.x = o[0]; w.y = o[1]; w.z = o[2]; w.w = o[3];
                     *reinterpret_cast<float4*>(po + nb * 32 + i4 * 8 + c.half * 4) = w;
                 }
