@@ -237,3 +237,29 @@ def test_full_size_cross_layer_stack_first_layers(xq):
         print(f"c3 layer {layer}: worst norm-wise rel err {worst:.2e}")
         if layer < 2:
             x = xi.gen_next_layer_x(w, x, layer + 1)
+
+
+@pytest.mark.parametrize("d", [128, 256])
+@pytest.mark.parametrize("bits,G", [(3, 128), (2, 64), (4, 64)])
+def test_smallest_hidden_sizes(xq, d, bits, G):
+    """d = 128 is a single weight slab (the cyclic walk's predecessor is the slab itself), d = 256 two."""
+    w = xi.C1.scaled(B=2, L=300, d=d, Hq=2, Hkv=2, n_outlier=1)
+    _run_xquant(xq, w, bits, G, lens=[300, 33])
+
+
+def test_maximum_batch(xq):
+    """B = 128 (the largest batch the ABI takes), every sequence a different length."""
+    w = xi.C2.scaled(B=128, L=96, d=256, Hq=2, Hkv=2, n_outlier=2)
+    lens = [1 + (7 * b) % 96 for b in range(128)]
+    _run_xquant(xq, w, 3, 128, lens=lens)
+    acc = xi.gen_x(w)
+    wk, wv = xi.gen_weights(w)
+    q = xi.gen_q(w)
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    wprep = xq.xq_prepare_weights(attn, w.d, 128, 16, bits_to_torch(wk), bits_to_torch(wv))
+    out = xq.xq_remat_attn_decode(attn, bits_to_torch(q), wprep, lens, acc_bf16=bits_to_torch(acc))
+    torch.cuda.synchronize()
+    pairs = [(b, h) for b in range(w.B) for h in range(w.Hq)]
+    ref = xo.remat_attn_pairs(q_bf16=q, Wk=wk, Wv=wv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd,
+                              softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs, acc_bf16=acc)
+    _check(out.cpu().numpy().reshape(-1, w.hd), ref, "dense, B=128")
