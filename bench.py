@@ -193,7 +193,7 @@ def main():
         wfk = (torch.randn((r, r), device=dev, generator=gen) * r ** -0.5).to(torch.bfloat16)
         wfv = (torch.randn((r, r), device=dev, generator=gen) * r ** -0.5).to(torch.bfloat16)
         lwp = xq.xq_prepare_weights_latent(oattn, r, ow.G, ow.bits, wfk, wfv)
-        lws = torch.empty(xq.xq_remat_attn_workspace_bytes(oattn, ow.B, ow.L, 2 * r, ow.G), dtype=torch.uint8, device=dev)
+        lws = torch.empty(xq.xq_remat_attn_latent_workspace_bytes(oattn, ow.B, ow.L, r, ow.G), dtype=torch.uint8, device=dev)
         oq = dev_bf16(xi.gen_q(ow))
         oout = torch.empty((ow.B, ow.Hq, ow.hd), dtype=torch.float32, device=dev)
         olens = [ow.L] * ow.B

@@ -182,15 +182,19 @@ xq_status_t xq_remat_attn_decode_rope(const xq_attn_t *a, const uint16_t *q_bf16
  *   out_bf16 dev [M][n_lat] bf16, ready for xq_quantize_append with fmt.d = n_lat
  *   d must be a multiple of 128, n_lat a multiple of 32; M = 0 is a no-op.
  *
- * xq_prepare_weights_latent: prepared stream for a latent cache with fmt.d = 2r:
+ * xq_prepare_weights_latent: prepared streams for a latent cache with fmt.d = 2r:
  *   Wfk, Wfv dev [r][n_kv_heads*head_dim] bf16 row-major = Sk Bk^T and Sv Bv^T
- *   src_bits 2, 3 or 4; r a multiple of 128; out as for xq_prepare_weights with d = 2r
- *   (size: xq_prepared_weights_bytes(a, 2r, group, src_bits)).
+ *   src_bits 2, 3 or 4; r a multiple of 128; n_kv_heads even;
+ *   out dev, at least xq_prepared_weights_latent_bytes(a, r, group, src_bits) bytes (0 = unsupported).
  *
- * xq_remat_attn_decode_latent: as xq_remat_attn_decode with an X cache, for a latent cache and a
- *   stream from xq_prepare_weights_latent; the first r channels feed only K, the last r only V.
- *   Workspace size: xq_remat_attn_workspace_bytes(a, B, max_len, 2r, group).
+ * xq_remat_attn_decode_latent: decode attention from a latent cache and the streams above: the
+ *   first r channels of a row rematerialise the keys, the last r the values (two passes; the scores
+ *   of pass 1 wait in the workspace).  Arguments as xq_remat_attn_decode with an X cache;
+ *   workspace size: xq_remat_attn_latent_workspace_bytes(a, B, max_len, r, group).
  */
+size_t      xq_prepared_weights_latent_bytes(const xq_attn_t *a, int32_t r, int32_t group, int32_t src_bits);
+size_t      xq_remat_attn_latent_workspace_bytes(const xq_attn_t *a, int32_t B, int32_t max_len, int32_t r,
+                                                 int32_t group);
 xq_status_t xq_latent_project(const uint16_t *x_bf16, const uint16_t *Ut_bf16, int32_t M, int32_t d,
                               int32_t n_lat, uint16_t *out_bf16, void *stream);
 xq_status_t xq_prepare_weights_latent(const xq_attn_t *a, int32_t r, int32_t group, int32_t src_bits,

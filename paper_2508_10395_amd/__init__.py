@@ -8,4 +8,5 @@ from .binding import (  # noqa: F401
     xq_prepared_weights_bytes, xq_prepare_weights,
     xq_remat_attn_workspace_bytes, xq_remat_attn_decode,
     xq_latent_project, xq_prepare_weights_latent, xq_remat_attn_decode_latent,
+    xq_prepared_weights_latent_bytes, xq_remat_attn_latent_workspace_bytes,
 )

@@ -22,6 +22,7 @@ SYMBOLS = [
     "xq_remat_attn_workspace_bytes", "xq_remat_attn_decode",
     "xq_latent_project", "xq_prepare_weights_latent", "xq_remat_attn_decode_latent",
     "xq_remat_attn_decode_rope",
+    "xq_prepared_weights_latent_bytes", "xq_remat_attn_latent_workspace_bytes",
 ]
 
 
@@ -87,6 +88,10 @@ def load_library():
                                               C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                               C.POINTER(C.c_int32), C.c_void_p, C.c_int32, C.POINTER(C.c_int32),
                                               C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xq_prepared_weights_latent_bytes.restype = C.c_size_t
+    lib.xq_prepared_weights_latent_bytes.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32]
+    lib.xq_remat_attn_latent_workspace_bytes.restype = C.c_size_t
+    lib.xq_remat_attn_latent_workspace_bytes.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.xq_latent_project.restype = C.c_int
     lib.xq_latent_project.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                       C.c_void_p]
@@ -262,6 +267,16 @@ def xq_remat_attn_decode(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=Non
     return out
 
 
+def xq_prepared_weights_latent_bytes(attn, r, group, src_bits):
+    a = attn.c_struct()
+    return load_library().xq_prepared_weights_latent_bytes(C.byref(a), r, group, src_bits)
+
+
+def xq_remat_attn_latent_workspace_bytes(attn, B, max_len, r, group):
+    a = attn.c_struct()
+    return load_library().xq_remat_attn_latent_workspace_bytes(C.byref(a), B, max_len, r, group)
+
+
 def xq_latent_project(x_bf16, Ut_bf16, out=None):
     """x [..., d] bf16 times U (given transposed, [n_lat][d]) -> [..., n_lat] bf16."""
     assert x_bf16.dtype == torch.bfloat16 and x_bf16.is_contiguous()
@@ -281,7 +296,7 @@ def xq_prepare_weights_latent(attn, r, group, src_bits, Wfk, Wfv, out=None):
     """Prepared stream for a latent cache [X Uk | X Uv]; Wfk, Wfv [r][Hkv*hd] = S B^T of the two SVDs."""
     assert Wfk.dtype == torch.bfloat16 and Wfv.dtype == torch.bfloat16
     assert Wfk.is_contiguous() and Wfv.is_contiguous()
-    nbytes = xq_prepared_weights_bytes(attn, 2 * r, group, src_bits)
+    nbytes = xq_prepared_weights_latent_bytes(attn, r, group, src_bits)
     if nbytes == 0:
         raise XQError("xq_prepare_weights_latent: unsupported combination")
     if out is None:
@@ -298,7 +313,7 @@ def xq_remat_attn_decode_latent(attn, q_bf16, wprep, lens, latent, out=None, wor
     lens = [int(v) for v in lens]
     a = attn.c_struct()
     cs = latent.c_struct()
-    need = xq_remat_attn_workspace_bytes(attn, latent.B, max(lens) if lens else 1, latent.d, latent.group)
+    need = xq_remat_attn_latent_workspace_bytes(attn, latent.B, max(lens) if lens else 1, latent.d // 2, latent.group)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q_bf16.device)
     if out is None:

@@ -10,14 +10,18 @@ hipError_t run_quantize_append(const xq_cache_t* c, const uint16_t* x, const uin
                                const BatchI32& start, hipStream_t s);
 hipError_t run_cl_accumulate(uint16_t* acc, const xq_cache_t* c, const BatchI32& len, int max_len,
                              bool init, hipStream_t s);
-hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, int split_rows,
-                               void* out, hipStream_t s);
+hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, int ncols,
+                               int head_stride, void* out, hipStream_t s);
 hipError_t run_latent_project(const uint16_t* x, const uint16_t* ut, int M, int d, int n_lat, uint16_t* out,
                               hipStream_t s);
 hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
-                                 const BatchI32& len, int max_len, float* out, void* ws, bool split,
+                                 const BatchI32& len, int max_len, float* out, void* ws,
                                  const float* rope, const BatchI32* pos0, hipStream_t s);
+hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
+                                        const void* wprep, const BatchI32& len, int max_len, float* out, void* ws,
+                                        hipStream_t s);
+size_t remat_latent_workspace_bytes(int B, int Hq, int max_len, int r, int group);
 size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool coded);
 
 static bool fmt_ok(const xq_qfmt_t& f)
@@ -150,8 +154,19 @@ xq_status_t xq_prepare_weights(const xq_attn_t* a, int32_t d, int32_t group, int
     if (!wprep_combo_ok(d, group, src_bits)) return XQ_ERR_UNSUPPORTED;
     const WPrepLayout L = make_wprep_layout(d, src_bits == 16 ? 128 : group, src_bits, a->n_kv_heads);
     if (out_bytes < L.total_bytes) return XQ_ERR_WORKSPACE;
-    hipError_t e = run_prepare_weights(L, Wk, Wv, 0, out, static_cast<hipStream_t>(stream));
+    hipError_t e = run_prepare_weights(L, Wk, Wv, a->n_kv_heads * 128, 128, out, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+static bool latent_combo_ok(const xq_attn_t* a, int r, int group, int src_bits)
+{
+    return r > 0 && r % 128 == 0 && a->n_kv_heads % 2 == 0 && src_bits != 16 && wprep_combo_ok(r, group, src_bits);
+}
+
+size_t xq_prepared_weights_latent_bytes(const xq_attn_t* a, int32_t r, int32_t group, int32_t src_bits)
+{
+    if (check_attn(a) != XQ_OK || !latent_combo_ok(a, r, group, src_bits)) return 0;
+    return 2 * make_wprep_layout(r, group, src_bits, a->n_kv_heads / 2).total_bytes;
 }
 
 xq_status_t xq_prepare_weights_latent(const xq_attn_t* a, int32_t r, int32_t group, int32_t src_bits,
@@ -162,10 +177,15 @@ xq_status_t xq_prepare_weights_latent(const xq_attn_t* a, int32_t r, int32_t gro
     if (st != XQ_OK) return st;
     if (!Wfk || !Wfv || !out || !aligned16(Wfk) || !aligned16(Wfv) || !aligned16(out)) return XQ_ERR_INVALID_ARG;
     if (r <= 0) return XQ_ERR_INVALID_ARG;
-    if (src_bits == 16 || r % 128 != 0 || !wprep_combo_ok(2 * r, group, src_bits)) return XQ_ERR_UNSUPPORTED;
-    const WPrepLayout L = make_wprep_layout(2 * r, group, src_bits, a->n_kv_heads);
-    if (out_bytes < L.total_bytes) return XQ_ERR_WORKSPACE;
-    hipError_t e = run_prepare_weights(L, Wfk, Wfv, r, out, static_cast<hipStream_t>(stream));
+    if (!latent_combo_ok(a, r, group, src_bits)) return XQ_ERR_UNSUPPORTED;
+    // one stream per half; a stream's "head" is a pair of KV heads = 256 adjacent columns of the fused matrix
+    const WPrepLayout L = make_wprep_layout(r, group, src_bits, a->n_kv_heads / 2);
+    if (out_bytes < 2 * L.total_bytes) return XQ_ERR_WORKSPACE;
+    const int ncols = a->n_kv_heads * 128;
+    hipError_t e = run_prepare_weights(L, Wfk, Wfk + 128, ncols, 256, out, static_cast<hipStream_t>(stream));
+    if (e == hipSuccess)
+        e = run_prepare_weights(L, Wfv, Wfv + 128, ncols, 256, static_cast<uint8_t*>(out) + L.total_bytes,
+                                static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 
@@ -192,7 +212,7 @@ size_t xq_remat_attn_workspace_bytes(const xq_attn_t* a, int32_t B, int32_t max_
 static xq_status_t remat_attn_common(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* xcache,
                                      const uint16_t* acc_bf16, int32_t B, int32_t cap, int32_t d,
                                      const void* wprep, const int32_t* len, float* out, void* workspace,
-                                     size_t workspace_bytes, bool split, const float* rope, int32_t rope_positions,
+                                     size_t workspace_bytes, const float* rope, int32_t rope_positions,
                                      const int32_t* pos0, void* stream)
 {
     xq_status_t st = check_attn(a);
@@ -228,7 +248,7 @@ static xq_status_t remat_attn_common(const xq_attn_t* a, const uint16_t* q_bf16,
         }
     }
     hipError_t e = run_remat_attn_decode(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, lv, max_len, out,
-                                         workspace, split, rope, &pv, static_cast<hipStream_t>(stream));
+                                         workspace, rope, &pv, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 
@@ -238,7 +258,7 @@ xq_status_t xq_remat_attn_decode(const xq_attn_t* a, const uint16_t* q_bf16, con
                                  size_t workspace_bytes, void* stream)
 {
     return remat_attn_common(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, len, out, workspace, workspace_bytes,
-                             false, nullptr, 0, nullptr, stream);
+                             nullptr, 0, nullptr, stream);
 }
 
 xq_status_t xq_remat_attn_decode_rope(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* xcache,
@@ -249,17 +269,40 @@ xq_status_t xq_remat_attn_decode_rope(const xq_attn_t* a, const uint16_t* q_bf16
 {
     if (!rope_cos_sin) return XQ_ERR_INVALID_ARG;
     return remat_attn_common(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, len, out, workspace, workspace_bytes,
-                             false, rope_cos_sin, rope_positions, pos0, stream);
+                             rope_cos_sin, rope_positions, pos0, stream);
+}
+
+size_t xq_remat_attn_latent_workspace_bytes(const xq_attn_t* a, int32_t B, int32_t max_len, int32_t r, int32_t group)
+{
+    if (check_attn(a) != XQ_OK || B < 1 || max_len < 1 || r <= 0 || r % 128 != 0) return 0;
+    if (group != 64 && group != 128) return 0;
+    return remat_latent_workspace_bytes(B, a->n_q_heads, max_len, r, group);
 }
 
 xq_status_t xq_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* latent,
                                         const void* wprep, const int32_t* len, float* out, void* workspace,
                                         size_t workspace_bytes, void* stream)
 {
-    if (!latent) return XQ_ERR_INVALID_ARG;
-    if (latent->fmt.d % 256 != 0) return XQ_ERR_UNSUPPORTED;      // two halves of whole 128-channel slabs
-    return remat_attn_common(a, q_bf16, latent, nullptr, 0, 0, 0, wprep, len, out, workspace, workspace_bytes,
-                             true, nullptr, 0, nullptr, stream);
+    xq_status_t st = check_attn(a);
+    if (st != XQ_OK) return st;
+    if (!q_bf16 || !wprep || !len || !out || !workspace) return XQ_ERR_INVALID_ARG;
+    if (!aligned16(q_bf16) || !aligned16(wprep) || !aligned16(out) || !aligned16(workspace)) return XQ_ERR_INVALID_ARG;
+    st = check_cache(latent);
+    if (st != XQ_OK) return st;
+    if (latent->fmt.d % 256 != 0 || !latent_combo_ok(a, latent->fmt.d / 2, latent->fmt.group, latent->fmt.bits))
+        return XQ_ERR_UNSUPPORTED;
+    BatchI32 lv{};
+    int max_len = 0;
+    for (int b = 0; b < latent->B; ++b) {
+        if (len[b] < 1 || len[b] > latent->cap) return XQ_ERR_INVALID_ARG;
+        lv.v[b] = len[b];
+        if (len[b] > max_len) max_len = len[b];
+    }
+    if (workspace_bytes < xq_remat_attn_latent_workspace_bytes(a, latent->B, max_len, latent->fmt.d / 2, latent->fmt.group))
+        return XQ_ERR_WORKSPACE;
+    hipError_t e = run_remat_attn_decode_latent(a, q_bf16, latent, wprep, lv, max_len, out, workspace,
+                                                static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 
 }  // extern "C"

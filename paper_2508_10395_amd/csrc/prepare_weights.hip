@@ -18,7 +18,7 @@ struct PrepArgs {
     uint8_t* out;
     float* colsum;   // [Hkv][ng][256]: per-group sums of the weight rows
     int d, G, bits, Hkv, ncols;
-    int split_rows;  // > 0: latent layout, Wk feeds channels [0, split_rows), Wv channels [split_rows, d)
+    int head_stride; // columns between consecutive heads in Wk / Wv (128; 256 when a "head" is a pair of heads)
     int n_main_slabs, ng, ng_pad, n_corr_slabs;
     long long head_bytes;
     UnpackTable tab;
@@ -27,13 +27,8 @@ struct PrepArgs {
 // element (channel c, column n of [Wk_h | Wv_h]) of the matrix the stream encodes
 __device__ __forceinline__ float wval(const PrepArgs& a, int h, int c, int n)
 {
-    const bool kcol = n < 128;
-    if (a.split_rows > 0) {                            // block-diagonal [[Wk, 0], [0, Wv]]
-        if (kcol != (c < a.split_rows)) return 0.0f;
-        if (!kcol) c -= a.split_rows;
-    }
-    const uint16_t* W = kcol ? a.Wk : a.Wv;
-    return bf16_bits_to_f32(W[(long long)c * a.ncols + h * 128 + (n & 127)]);
+    const uint16_t* W = n < 128 ? a.Wk : a.Wv;
+    return bf16_bits_to_f32(W[(long long)c * a.ncols + h * a.head_stride + (n & 127)]);
 }
 
 __global__ __launch_bounds__(256) void colsum_kernel(PrepArgs a)
@@ -136,15 +131,16 @@ bool unpack_table_for(int bits, UnpackTable* t)
     return t->valid != 0;
 }
 
-hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, int split_rows,
-                               void* out, hipStream_t s)
+// Wk / Wv: [d][ncols] row-major; head h takes columns [h * head_stride, +128) of each
+hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, int ncols,
+                               int head_stride, void* out, hipStream_t s)
 {
     PrepArgs a{};
-    a.split_rows = split_rows;
+    a.head_stride = head_stride;
     a.Wk = Wk; a.Wv = Wv;
     a.out = static_cast<uint8_t*>(out);
     a.colsum = reinterpret_cast<float*>(a.out + L.stream_bytes);
-    a.d = L.d; a.G = L.G; a.bits = L.bits; a.Hkv = L.Hkv; a.ncols = L.Hkv * 128;
+    a.d = L.d; a.G = L.G; a.bits = L.bits; a.Hkv = L.Hkv; a.ncols = ncols;
     a.n_main_slabs = L.n_main_slabs; a.ng = L.ng; a.ng_pad = L.ng_pad; a.n_corr_slabs = L.n_corr_slabs;
     a.head_bytes = (long long)L.head_bytes;
     if (!unpack_table_for(L.bits, &a.tab)) return hipErrorInvalidValue;

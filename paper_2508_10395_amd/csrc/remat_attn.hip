@@ -87,6 +87,9 @@ struct RematParams {
     float* part_o;           // [B][Hq][chunks_per_seq][128]
     float* part_ml;          // [B][Hq][chunks_per_seq][2]
     int B, cap, d, Hq, Hkv;
+    int row_d, ng_row;       // coded source: channels / groups per cache row (>= d, ng when a sub-range is contracted)
+    int grid_heads;          // heads (or head pairs) the grid is laid over
+    float* scores;           // latent passes: q.K * scale * log2(e), [B][Hq][tiles_per_seq * 256]
     int tiles_per_seq, chunks_per_seq;
     int n_main_slabs, n_corr_ksteps, ng, ng_pad;
     long long head_bytes;
@@ -184,7 +187,7 @@ __device__ __forceinline__ bool locate_tile(const RematParams& p, TileCtx& c)
     // resident on one XCD (blockIdx % 8) stream the same head's slabs through its L2
     const int NT = p.B * p.tiles_per_seq;
     int tile_lin;
-    if ((p.Hkv & 7) == 0) {
+    if ((p.grid_heads & 7) == 0) {
         const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
         c.hk = xcd + 8 * (j / NT);
         tile_lin = j % NT;
@@ -273,13 +276,85 @@ __device__ __forceinline__ void attention_epilogue(const RematParams& p, const T
     }
 }
 
+// ---- latent cache (Sec. 3.3.1), pass 1: the wave holds the keys of two KV heads of its 32 tokens
+// (blocks 0-3: head 2 pair, blocks 4-7: head 2 pair + 1) and stores the scaled scores of their
+// query heads; pass 2 turns them into softmax partials against the values.
+__device__ __forceinline__ void scores_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8])
+{
+    if (c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS >= c.len) return;
+    const int gq = p.Hq / p.Hkv;
+    const long long srow = (long long)p.tiles_per_seq * TILE_TOKENS;
+    static_for<0, 2>([&](auto HH) XQ_INLINE_LAMBDA {       // (compile-time: the accumulator must stay in registers)
+        constexpr int hh = decltype(HH)::value;
+        for (int j = 0; j < gq; ++j) {
+            const int hq = (2 * c.hk + hh) * gq + j;
+            const uint16_t* qv = p.q + ((long long)c.b * p.Hq + hq) * 128;
+            float dot = 0.0f;
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const uint2 qq = *reinterpret_cast<const uint2*>(qv + nb * 32 + i4 * 8 + c.half * 4);
+                    const f32x16& a = acc[4 * hh + nb];
+                    dot = __builtin_fmaf(bf16_lo_to_f32(qq.x), a[i4 * 4 + 0], dot);
+                    dot = __builtin_fmaf(bf16_hi_to_f32(qq.x), a[i4 * 4 + 1], dot);
+                    dot = __builtin_fmaf(bf16_lo_to_f32(qq.y), a[i4 * 4 + 2], dot);
+                    dot = __builtin_fmaf(bf16_hi_to_f32(qq.y), a[i4 * 4 + 3], dot);
+                }
+            const float sc = (dot + __shfl_xor(dot, 32)) * p.scale_log2e;
+            if (c.half == 0) p.scores[((long long)c.b * p.Hq + hq) * srow + c.tok] = sc;
+        }
+    });
+}
+
+// pass 2: blocks 0-3 / 4-7 hold the values of the two KV heads; one partial (m, l, o[128]) per query head
+__device__ __forceinline__ void weighted_sum_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8])
+{
+    if (c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS >= c.len) return;
+    const int gq = p.Hq / p.Hkv;
+    const int chunk = c.tile * (TILE_TOKENS / CHUNK_TOKENS) + c.wave;
+    const long long srow = (long long)p.tiles_per_seq * TILE_TOKENS;
+    static_for<0, 2>([&](auto HH) XQ_INLINE_LAMBDA {
+        constexpr int hh = decltype(HH)::value;
+        for (int j = 0; j < gq; ++j) {
+            const int hq = (2 * c.hk + hh) * gq + j;
+            float sc = p.scores[((long long)c.b * p.Hq + hq) * srow + min(c.tok, c.len - 1)];
+            sc = c.tok < c.len ? sc : -INFINITY;
+            const float m = wave32_max(sc);
+            const float pv = __builtin_amdgcn_exp2f(sc - m);
+            const float l = wave32_sum(pv);
+            const long long pidx = ((long long)c.b * p.Hq + hq) * p.chunks_per_seq + chunk;
+            float* po = p.part_o + pidx * 128;
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const f32x16& a = acc[4 * hh + nb];
+                    float o[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) o[k] = wave32_sum_upper(pv * a[i4 * 4 + k]);
+                    if (c.tl == 16) {
+                        float4 w; w.x = o[0]; w.y = o[1]; w.z = o[2]; w.w = o[3];
+                        *reinterpret_cast<float4*>(po + nb * 32 + i4 * 8 + c.half * 4) = w;
+                    }
+                }
+            if (c.lane == 0) {
+                p.part_ml[pidx * 2] = m;
+                p.part_ml[pidx * 2 + 1] = l;
+            }
+        }
+    });
+}
+
+constexpr int MODE_ATTENTION = 0, MODE_SCORES = 1, MODE_WEIGHTED_SUM = 2;
+
 // =====================================================================================
 // coded source (XQuant cache, BITS in {2,3,4})
 // =====================================================================================
-// SPLIT: the source is a latent cache [X Uk | X Uv] (Sec. 3.3.1) and the prepared weights are
-// block-diagonal -- the first half of the channels feeds only the K columns, the second half only
-// the V columns.  The MFMAs of the zero blocks are skipped; everything else is unchanged.
-template <int BITS, int G, bool SPLIT>
+// MODE selects what happens to the 256 rematerialised columns of the wave's 32 tokens: decode
+// attention ([K_h | V_h]), or one of the two passes over a latent cache, where the columns are the
+// keys (pass 1) or the values (pass 2) of a PAIR of KV heads.
+template <int BITS, int G, int MODE>
 __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams p)
 {
     constexpr int KSG = G / 16;                        // k-steps per quantisation group
@@ -306,12 +381,12 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
 
     // ---- token-side sources
     const long long seq_row0 = (long long)c.b * p.cap;
-    const uint32_t row_bytes = (uint32_t)(p.d * BITS / 8);
+    const uint32_t row_bytes = (uint32_t)(p.row_d * BITS / 8);
     const uint8_t* cbase = p.codes + seq_row0 * row_bytes;
-    const uint16_t* zbase = p.zero + seq_row0 * p.ng;
+    const uint16_t* zbase = p.zero + seq_row0 * p.ng_row;
     const uint8_t* ebase = reinterpret_cast<const uint8_t*>(p.eT) +
                            ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.ng + 1) * 512;
-    const uint32_t moff = (uint32_t)min(c.tok, c.len - 1) * (uint32_t)p.ng;
+    const uint32_t moff = (uint32_t)min(c.tok, c.len - 1) * (uint32_t)p.ng_row;
 
     // code DMA: 16-byte piece pc of the tile's slab image = (row pc / BITS, part pc % BITS);
     // wave instruction i covers pieces [64 i, 64 i + 64); this wave issues i = wave and wave + 8
@@ -397,7 +472,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     // first thing, so their latency hides behind the first weight DMA.  The codes and scales of the
     // slab that cyclically precedes the first one arrive meanwhile: the lagging column blocks start
     // inside it (see phase 2).
-    const bool vec_meta = (p.ng & 7) == 0;
+    const bool vec_meta = (p.ng & 7) == 0 && (p.ng_row & 7) == 0 && ((size_t)zbase & 15) == 0;
     auto load_meta = [&](int kk) -> uint4 {
         const int kappa0 = kk * 16 + half * 8;
         const int term = kappa0 / p.ng_pad, g0 = kappa0 % p.ng_pad;
@@ -570,9 +645,6 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         float hr_bn[NB];                                     // boundary factors of the next iteration
 #pragma unroll
         for (int k = 0; k < NB; ++k) hr_bn[k] = 1.0f;
-        // SPLIT: do this slab's / the previous slab's channels belong to the K half?
-        const bool k_half_cur = 2 * it < p.n_main_slabs;
-        const bool k_half_prev = it >= 1 && 2 * (it - 1) < p.n_main_slabs;
         __builtin_amdgcn_sched_barrier(0);
 
         static_for<0, 64>([&](auto SIDX) XQ_INLINE_LAMBDA {
@@ -580,11 +652,8 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                 constexpr int sidx = decltype(SIDX)::value;
                 constexpr int ks = sidx >> 3, m = sidx & 7;
                 const uint32_t* b = ub[(ks + 1 + m) & 7];
-                // (block m multiplies k-step ks - 7 + m of this slab, or of the previous one if negative)
-                const bool k_half = (ks - 7 + m >= 0) ? k_half_cur : k_half_prev;
-                if (!SPLIT || k_half == (m < 4))
-                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                        __builtin_bit_cast(f16x8, af[m]), as_frag(b[0], b[1], b[2], b[3]), acc[m], 0, 0, 0);
+                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                    __builtin_bit_cast(f16x8, af[m]), as_frag(b[0], b[1], b[2], b[3]), acc[m], 0, 0, 0);
 
                 // DMA of the next slab: 11 steps per wave, one every other slot.  (Issued in bursts they
                 // fill the address FIFO and the issuing wave stalls with its MFMAs behind them.)
@@ -636,7 +705,9 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     // every block ends in the slab it started in; leave its group's scale: the accumulator is K | V
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] *= E[GPS + j / KSG];
-    attention_epilogue(p, c, acc);
+    if constexpr (MODE == MODE_SCORES) scores_epilogue(p, c, acc);
+    else if constexpr (MODE == MODE_WEIGHTED_SUM) weighted_sum_epilogue(p, c, acc);
+    else attention_epilogue(p, c, acc);
 }
 
 // =====================================================================================
@@ -765,7 +836,7 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
 // one group are contiguous (tokens past len repeat the last row).
 __global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __restrict__ scale,
                                                               uint16_t* __restrict__ eT, int cap, int ng,
-                                                              int tiles_per_seq, int bits, BatchI32 len)
+                                                              int ng_row, int tiles_per_seq, int bits, BatchI32 len)
 {
     const int tile = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
     const int L = len.v[b];
@@ -773,7 +844,7 @@ __global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __
     const long long row = (long long)b * cap + min(tile * TILE_TOKENS + t, L - 1);
     uint16_t* dst = eT + ((long long)b * tiles_per_seq + tile) * (long long)(ng + 1) * TILE_TOKENS + t;
     for (int g = 0; g < ng; ++g) {
-        const uint32_t sb = scale[row * ng + g];
+        const uint32_t sb = scale[row * ng_row + g];
         const uint32_t e = sb ? sb + ((uint32_t)(bits + F16_SUBNORMAL_EXP - F16_MANT_BITS) << 7) : 0x3F80u;
         dst[(long long)g * TILE_TOKENS] = (uint16_t)e;
     }
@@ -842,32 +913,63 @@ size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool 
     return bytes;
 }
 
+// latent cache of rank r: partials, effective scales of the K half and of the V half, scores
+size_t remat_latent_workspace_bytes(int B, int Hq, int max_len, int r, int group)
+{
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    return remat_workspace_bytes(B, Hq, max_len, r, group, true) +
+           (size_t)B * tiles * (size_t)(r / group + 1) * TILE_TOKENS * sizeof(uint16_t) +
+           (size_t)B * Hq * tiles * TILE_TOKENS * sizeof(float);
+}
+
+template <int MODE>
+static hipError_t launch_coded(int bits, int G, const RematParams& p, int grid, hipStream_t s)
+{
+    switch (bits * 1000 + G) {
+        case 2064: return launch_with_lds(remat_attn_coded_kernel<2, 64, MODE>, lds_coded_total(2), p, grid, s);
+        case 2128: return launch_with_lds(remat_attn_coded_kernel<2, 128, MODE>, lds_coded_total(2), p, grid, s);
+        case 3064: return launch_with_lds(remat_attn_coded_kernel<3, 64, MODE>, lds_coded_total(3), p, grid, s);
+        case 3128: return launch_with_lds(remat_attn_coded_kernel<3, 128, MODE>, lds_coded_total(3), p, grid, s);
+        case 4064: return launch_with_lds(remat_attn_coded_kernel<4, 64, MODE>, lds_coded_total(4), p, grid, s);
+        case 4128: return launch_with_lds(remat_attn_coded_kernel<4, 128, MODE>, lds_coded_total(4), p, grid, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+static void fill_common(RematParams& p, const xq_attn_t* a, const uint16_t* q, int B, int cap, const BatchI32& len,
+                        int max_len, void* ws)
+{
+    p.q = q;
+    p.B = B; p.cap = cap; p.Hq = a->n_q_heads; p.Hkv = a->n_kv_heads;
+    p.tiles_per_seq = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    p.chunks_per_seq = p.tiles_per_seq * (TILE_TOKENS / CHUNK_TOKENS);
+    p.scale_log2e = a->softmax_scale * 1.44269504088896340736f;
+    p.len = len;
+    p.part_o = static_cast<float*>(ws);
+    p.part_ml = p.part_o + (size_t)B * p.Hq * p.chunks_per_seq * 128;
+}
+
 hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
-                                 const BatchI32& len, int max_len, float* out, void* ws, bool split,
+                                 const BatchI32& len, int max_len, float* out, void* ws,
                                  const float* rope, const BatchI32* pos0, hipStream_t s)
 {
     const int bits = xc ? xc->fmt.bits : 16;
     const int G = xc ? xc->fmt.group : 128;
     const WPrepLayout L = make_wprep_layout(d, G, bits, a->n_kv_heads);
     RematParams p{};
-    p.q = q;
+    fill_common(p, a, q, B, cap, len, max_len, ws);
     p.codes = xc ? xc->codes : nullptr;
     p.scale = xc ? xc->scale : nullptr;
     p.zero = xc ? xc->zero : nullptr;
     p.acc = acc;
     p.wprep = static_cast<const uint8_t*>(wprep);
-    p.B = B; p.cap = cap; p.d = d; p.Hq = a->n_q_heads; p.Hkv = a->n_kv_heads;
-    p.tiles_per_seq = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
-    p.chunks_per_seq = p.tiles_per_seq * (TILE_TOKENS / CHUNK_TOKENS);
+    p.d = d; p.row_d = d; p.grid_heads = p.Hkv;
     p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
+    p.ng_row = L.ng;
     p.head_bytes = (long long)L.head_bytes;
-    p.scale_log2e = a->softmax_scale * 1.44269504088896340736f;
-    p.len = len;
     p.rope = rope;
     if (rope) p.pos0 = *pos0;
-    p.part_o = static_cast<float*>(ws);
-    p.part_ml = p.part_o + (size_t)B * p.Hq * p.chunks_per_seq * 128;
     uint16_t* eT = reinterpret_cast<uint16_t*>(p.part_ml + (size_t)B * p.Hq * p.chunks_per_seq * 2);
     p.eT = eT;
 
@@ -875,26 +977,56 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
     hipError_t e = hipErrorInvalidValue;
     if (xc) {
         scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
-            xc->scale, eT, cap, L.ng, p.tiles_per_seq, bits, len);
+            xc->scale, eT, cap, L.ng, L.ng, p.tiles_per_seq, bits, len);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
+        e = launch_coded<MODE_ATTENTION>(bits, G, p, grid, s);
+    } else {
+        e = launch_with_lds(remat_attn_dense_kernel, LDS_DENSE_TOTAL, p, grid, s);
     }
-    switch (bits * 1000 + (bits == 16 ? 0 : G)) {
-        case 2064: e = split ? launch_with_lds(remat_attn_coded_kernel<2, 64, true>, lds_coded_total(2), p, grid, s)
-                         : launch_with_lds(remat_attn_coded_kernel<2, 64, false>, lds_coded_total(2), p, grid, s); break;
-        case 2128: e = split ? launch_with_lds(remat_attn_coded_kernel<2, 128, true>, lds_coded_total(2), p, grid, s)
-                         : launch_with_lds(remat_attn_coded_kernel<2, 128, false>, lds_coded_total(2), p, grid, s); break;
-        case 3064: e = split ? launch_with_lds(remat_attn_coded_kernel<3, 64, true>, lds_coded_total(3), p, grid, s)
-                         : launch_with_lds(remat_attn_coded_kernel<3, 64, false>, lds_coded_total(3), p, grid, s); break;
-        case 3128: e = split ? launch_with_lds(remat_attn_coded_kernel<3, 128, true>, lds_coded_total(3), p, grid, s)
-                         : launch_with_lds(remat_attn_coded_kernel<3, 128, false>, lds_coded_total(3), p, grid, s); break;
-        case 4064: e = split ? launch_with_lds(remat_attn_coded_kernel<4, 64, true>, lds_coded_total(4), p, grid, s)
-                         : launch_with_lds(remat_attn_coded_kernel<4, 64, false>, lds_coded_total(4), p, grid, s); break;
-        case 4128: e = split ? launch_with_lds(remat_attn_coded_kernel<4, 128, true>, lds_coded_total(4), p, grid, s)
-                         : launch_with_lds(remat_attn_coded_kernel<4, 128, false>, lds_coded_total(4), p, grid, s); break;
-        case 16000: e = launch_with_lds(remat_attn_dense_kernel, LDS_DENSE_TOTAL, p, grid, s); break;
-        default: e = hipErrorInvalidValue;
-    }
+    if (e != hipSuccess) return e;
+    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len);
+    return hipGetLastError();
+}
+
+// Latent cache [X Uk | X Uv] of rank r (Sec. 3.3.1): two passes of the same contraction kernel over
+// the two halves of the cache rows, each with all 256 columns in use -- pass 1 rematerialises the
+// keys of a pair of KV heads from the first r channels and stores the scaled scores, pass 2 the
+// values of the pair from the last r channels and turns scores into softmax partials.
+hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
+                                        const void* wprep, const BatchI32& len, int max_len, float* out, void* ws,
+                                        hipStream_t s)
+{
+    const int bits = xc->fmt.bits, G = xc->fmt.group, r = xc->fmt.d / 2, B = xc->B, cap = xc->cap;
+    const int pairs = a->n_kv_heads / 2;
+    const WPrepLayout L = make_wprep_layout(r, G, bits, pairs);          // one stream per half, "head" = pair
+    RematParams p{};
+    fill_common(p, a, q, B, cap, len, max_len, ws);
+    p.d = r; p.row_d = 2 * r; p.grid_heads = pairs;
+    p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
+    p.ng_row = 2 * L.ng;
+    p.head_bytes = (long long)L.head_bytes;
+    const size_t et_elems = (size_t)B * p.tiles_per_seq * (size_t)(L.ng + 1) * TILE_TOKENS;
+    uint16_t* eT_k = reinterpret_cast<uint16_t*>(p.part_ml + (size_t)B * p.Hq * p.chunks_per_seq * 2);
+    uint16_t* eT_v = eT_k + et_elems;
+    p.scores = reinterpret_cast<float*>(eT_v + et_elems);
+    const int grid = pairs * B * p.tiles_per_seq;
+
+    scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
+        xc->scale, eT_k, cap, L.ng, 2 * L.ng, p.tiles_per_seq, bits, len);
+    scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
+        xc->scale + L.ng, eT_v, cap, L.ng, 2 * L.ng, p.tiles_per_seq, bits, len);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // pass 1: keys
+    p.codes = xc->codes; p.scale = xc->scale; p.zero = xc->zero; p.eT = eT_k;
+    p.wprep = static_cast<const uint8_t*>(wprep);
+    e = launch_coded<MODE_SCORES>(bits, G, p, grid, s);
+    if (e != hipSuccess) return e;
+    // pass 2: values
+    p.codes = xc->codes + (size_t)r * bits / 8; p.scale = xc->scale + L.ng; p.zero = xc->zero + L.ng; p.eT = eT_v;
+    p.wprep = static_cast<const uint8_t*>(wprep) + L.total_bytes;
+    e = launch_coded<MODE_WEIGHTED_SUM>(bits, G, p, grid, s);
     if (e != hipSuccess) return e;
     combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len);
     return hipGetLastError();

@@ -87,10 +87,8 @@ def _run_latent(xq, w, bits_, G, lens, pairs=None):
     attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
     wprep = xq.xq_prepare_weights_latent(attn, r, G, bits_, bits_to_torch(wfk), bits_to_torch(wfv))
     out = xq.xq_remat_attn_decode_latent(attn, bits_to_torch(q), wprep, lens, cache)
-    plain = xq.xq_remat_attn_decode(attn, bits_to_torch(q), wprep, lens, xcache=cache)   # same stream, no skipping
     torch.cuda.synchronize()
     got = out.cpu().numpy()
-    assert np.array_equal(got, plain.cpu().numpy()), "skipping the zero blocks changed the result"
     if pairs is None:
         pairs = [(b, h) for b in range(w.B) for h in range(w.Hq)]
     zk, zv = np.zeros_like(wfk), np.zeros_like(wfv)
