@@ -142,7 +142,7 @@ def main():
         ang = torch.arange(L, dtype=torch.float64)[:, None] * inv[None, :]
         rope = torch.stack([torch.cos(ang), torch.sin(ang)], dim=-1).to(torch.float32).to(dev)
         t_rope = timed(lambda: xq.xq_remat_attn_decode(attn, q, wprep, lens, xcache=cache, out=out, workspace=ws,
-                                                       rope_cos_sin=rope), n=10, warm=2)
+                                                       rope_cos_sin=rope), n=10, warm=5)
         extra = {
             "quantize_bulk": {"workload": "xq_quantize_append T=4096 (whole context), c2 shape", "ms": t_q,
                               "GB/s": q_bytes / t_q / 1e6, "frac_hbm_peak": q_bytes / t_q / 1e6 / PEAK_HBM_GBS},
