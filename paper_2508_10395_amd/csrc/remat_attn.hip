@@ -4,8 +4,9 @@
 // One workgroup (8 waves) owns a tile of 256 cached tokens of one (sequence, KV
 // head).  Wave w handles tokens [32 w, 32 w + 32) of the tile and all 256 columns of
 // [Wk_h | Wv_h]: eight 32 x 32 fp32 accumulator blocks = 128 VGPRs, computed as
-// D[n][t] = sum_c W[c][n] * x^[t][c] with v_mfma_f32_32x32x16_bf16, weights as the A
-// operand (streamed HBM -> LDS as prepared 64 KiB slabs, double buffered) and tokens
+// D[n][t] = sum_c W[c][n] * x^[t][c] with v_mfma_f32_32x32x16_f16 (coded sources) or
+// _bf16 (the XQuant-CL accumulator), weights as the A operand (streamed HBM -> LDS
+// as prepared 64 KiB slabs, double buffered) and tokens
 // along the lanes of the B operand, so that everything per token (its codes, its
 // scales, its score, its softmax weight) is a per-lane scalar and is unpacked once.
 //
