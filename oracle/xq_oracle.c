@@ -34,6 +34,11 @@
  *                          as bf16.  (Rematerialising from the latent cache needs
  *                          nothing new: it is xqo_remat_attn_pairs with the
  *                          block-diagonal weights [[S_k B_k^T, 0], [0, S_v B_v^T]].)
+ *   xqo_project_delta_rows Sec. 3.3.2 (cross-layer deltas of grouped-query models):
+ *                          (X_i - X^_{i-1}) U_kv, stored as bf16.
+ *   xqo_cl_accumulate_latent_rows
+ *                          Sec. 3.3.2: X^_i = X^_{i-1} + dequant(cached latent delta) U_kv^T,
+ *                          the up-projection back into the accumulator.
  *
  * Arithmetic: everything the bit-exact contract covers (min/max, scale, zero,
  * codes, accumulator) is done in IEEE fp32 with explicit fmaf where a fused
@@ -425,6 +430,56 @@ void xqo_project_rows(const uint16_t *x_bf16, const uint16_t *ut_bf16, int64_t M
                 s += (double)bf16_bits_to_float(x_bf16[m * d + c]) * (double)bf16_bits_to_float(ut_bf16[(int64_t)n * d + c]);
             out_bf16[m * n_lat + n] = f64_to_bf16_rne(s);
         }
+    }
+}
+
+/*
+ * Sec. 3.3.2: the latent delta of a grouped-query model, (x - a) U_kv, where x is the true
+ * layer input and a the accumulator row X^_{i-1}; the difference and the sum are exact in
+ * double, one RNE rounding to bf16.  ut is U_kv transposed, [n_lat][d].
+ */
+void xqo_project_delta_rows(const uint16_t *x_bf16, const uint16_t *a_bf16, const uint16_t *ut_bf16,
+                            int64_t M, int d, int n_lat, uint16_t *out_bf16)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int n = 0; n < n_lat; ++n) {
+            double s = 0.0;
+            for (int c = 0; c < d; ++c) {
+                double delta = (double)bf16_bits_to_float(x_bf16[m * d + c]) - (double)bf16_bits_to_float(a_bf16[m * d + c]);
+                s += delta * (double)bf16_bits_to_float(ut_bf16[(int64_t)n * d + c]);
+            }
+            out_bf16[m * n_lat + n] = f64_to_bf16_rne(s);
+        }
+    }
+}
+
+/*
+ * Sec. 3.3.2: merge a cached latent delta into the accumulator,
+ *     acc[r][n] = bf16( acc[r][n] + sum_c dq[r][c] * U_kv[n][c] ),   n < d,
+ * with dq = fma(code, scale, zero) in fp32 as everywhere else, the sum over the n_lat latent
+ * channels in double (c ascending), the addition in double and one RNE rounding to bf16.
+ * ut is U_kv transposed, [n_lat][d], so that U_kv[n][c] = ut[c][n].
+ */
+void xqo_cl_accumulate_latent_rows(uint16_t *acc_bf16, const uint8_t *codes, const uint16_t *scale,
+                                   const uint16_t *zero, const uint16_t *ut_bf16, int64_t rows, int d,
+                                   int n_lat, int G)
+{
+    const int ngroups = n_lat / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        double *up = (double *)calloc((size_t)d, sizeof(double));
+        for (int c = 0; c < n_lat; ++c) {
+            int g = c / G;
+            float sf = bf16_bits_to_float(scale[r * ngroups + g]);
+            float zf = bf16_bits_to_float(zero[r * ngroups + g]);
+            double dq = (double)fmaf((float)codes[r * (int64_t)n_lat + c], sf, zf);
+            const uint16_t *urow = ut_bf16 + (int64_t)c * d;
+            for (int n = 0; n < d; ++n) up[n] += dq * (double)bf16_bits_to_float(urow[n]);
+        }
+        for (int n = 0; n < d; ++n)
+            acc_bf16[r * (int64_t)d + n] = f64_to_bf16_rne((double)bf16_bits_to_float(acc_bf16[r * (int64_t)d + n]) + up[n]);
+        free(up);
     }
 }
 

@@ -133,6 +133,39 @@ def project_rows(x_bf16, Ut_bf16):
     return out
 
 
+def project_delta_rows(x_bf16, acc_bf16, Ut_bf16):
+    """Latent cross-layer delta (Sec. 3.3.2): (x - acc) U_kv for rows x, acc [M][d] bf16 bits and
+    Ut = U_kv transposed [n_lat][d] bf16 bits -> [M][n_lat] bf16 bits."""
+    x = _c(x_bf16, np.uint16)
+    a = _c(acc_bf16, np.uint16)
+    ut = _c(Ut_bf16, np.uint16)
+    assert x.shape == a.shape
+    d = x.shape[-1]
+    n_lat = ut.shape[0]
+    assert ut.shape[1] == d
+    M = x.size // d
+    out = np.empty((*x.shape[:-1], n_lat), np.uint16)
+    lib().xqo_project_delta_rows(_p(x), _p(a), _p(ut), C.c_int64(M), C.c_int(d), C.c_int(n_lat), _p(out))
+    return out
+
+
+def cl_accumulate_latent_rows(acc_bf16, codes, scale, zero, Ut_bf16, G):
+    """Sec. 3.3.2, in place on acc_bf16 [rows][d] (uint16, C-contiguous):
+    acc += dequant(codes [rows][n_lat]) @ Ut, Ut = U_kv transposed [n_lat][d]."""
+    assert acc_bf16.dtype == np.uint16 and acc_bf16.flags.c_contiguous
+    codes = _c(codes, np.uint8)
+    scale = _c(scale, np.uint16)
+    zero = _c(zero, np.uint16)
+    ut = _c(Ut_bf16, np.uint16)
+    n_lat, d = ut.shape
+    assert codes.shape[-1] == n_lat and acc_bf16.shape[-1] == d
+    rows = codes.size // n_lat
+    assert acc_bf16.size == rows * d
+    lib().xqo_cl_accumulate_latent_rows(_p(acc_bf16), _p(codes), _p(scale), _p(zero), _p(ut),
+                                        C.c_int64(rows), C.c_int(d), C.c_int(n_lat), C.c_int(G))
+    return acc_bf16
+
+
 def remat_head(xhat_f32, W_bf16, col0, hd):
     x = _c(xhat_f32, np.float32)
     W = _c(W_bf16, np.uint16)
