@@ -204,6 +204,48 @@ xq_status_t xq_remat_attn_decode_latent(const xq_attn_t *a, const uint16_t *q_bf
                                         const xq_cache_t *latent, const void *wprep, const int32_t *len,
                                         float *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Sec. 3.3.2 (XQuant-CL for grouped-query models): with the offline SVD [Wk | Wv] = U_kv S B^T
+ * (n_lat = 2 * n_kv_heads * head_dim latent channels), layer i caches the quantised latent delta
+ * (X_i - X^_{i-1}) U_kv and merges it into the accumulator through U_kv^T:
+ *     X^_i = X^_{i-1} + dequant(cached delta) U_kv^T;
+ * K and V then come from xq_remat_attn_decode on the accumulator (xcache = NULL) with Wk, Wv.
+ * Ut_bf16 is U_kv TRANSPOSED, dev [n_lat][d] bf16 row-major, in all three calls.
+ *
+ * xq_cl_latent_delta_project: the latent delta of T new tokens per sequence,
+ *   out[b][t][n] = bf16( sum_c (x[b][t][c] - acc[b][start[b]+t][c]) * Ut[n][c] ),
+ *   difference and accumulation in fp32, one RNE rounding; ready for xq_quantize_append with
+ *   fmt.d = n_lat.
+ *   x_bf16 dev [B][T][d]; acc_bf16 dev [B][cap][d]; start host [B], 0 <= start[b], start[b]+T <= cap;
+ *   out_bf16 dev [B][T][n_lat].  d multiple of 128, n_lat multiple of 32.  T = 0 is a no-op.
+ *
+ * xq_prepare_upproject: offline re-layout of Ut for xq_cl_accumulate_latent (src_bits 2, 3, 4 of
+ *   the delta cache; d multiple of 256, n_lat multiple of 128); out dev, at least
+ *   xq_prepared_upproject_bytes(d, n_lat, group, src_bits) bytes (0 = unsupported).
+ *
+ * xq_cl_accumulate_latent: for rows t < len[b] of every sequence and all d hidden channels n,
+ *     acc[b][t][n] = bf16( acc[b][t][n] + sum_c fma(code[c], scale, zero) * Ut[c][n] ),
+ *   the sum on the matrix cores with fp32 accumulation, fp32 add, one RNE rounding.  The stored
+ *   bf16 can differ from the exactly rounded one by one unit in the last place where the exact
+ *   sum lies within the fp32 accumulation error of a rounding boundary.
+ *   acc_bf16  dev [B][cap][d] (B, cap from delta), updated in place
+ *   delta     cache with fmt.d = n_lat
+ *   len       host [B], 0 <= len[b] <= cap
+ *   workspace dev, xq_cl_accumulate_latent_workspace_bytes(B, max len, n_lat, group) bytes
+ */
+xq_status_t xq_cl_latent_delta_project(const uint16_t *x_bf16, const uint16_t *acc_bf16,
+                                       const uint16_t *Ut_bf16, int32_t B, int32_t T, int32_t cap,
+                                       const int32_t *start, int32_t d, int32_t n_lat,
+                                       uint16_t *out_bf16, void *stream);
+size_t      xq_prepared_upproject_bytes(int32_t d, int32_t n_lat, int32_t group, int32_t src_bits);
+xq_status_t xq_prepare_upproject(int32_t d, int32_t n_lat, int32_t group, int32_t src_bits,
+                                 const uint16_t *Ut_bf16, void *out, size_t out_bytes, void *stream);
+size_t      xq_cl_accumulate_latent_workspace_bytes(int32_t B, int32_t max_len, int32_t n_lat,
+                                                    int32_t group);
+xq_status_t xq_cl_accumulate_latent(uint16_t *acc_bf16, const xq_cache_t *delta, int32_t d,
+                                    const void *uprep, const int32_t *len, void *workspace,
+                                    size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

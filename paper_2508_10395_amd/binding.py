@@ -23,6 +23,8 @@ SYMBOLS = [
     "xq_latent_project", "xq_prepare_weights_latent", "xq_remat_attn_decode_latent",
     "xq_remat_attn_decode_rope",
     "xq_prepared_weights_latent_bytes", "xq_remat_attn_latent_workspace_bytes",
+    "xq_cl_latent_delta_project", "xq_prepared_upproject_bytes", "xq_prepare_upproject",
+    "xq_cl_accumulate_latent_workspace_bytes", "xq_cl_accumulate_latent",
 ]
 
 
@@ -102,6 +104,19 @@ def load_library():
     lib.xq_remat_attn_decode_latent.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
                                                 C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_size_t,
                                                 C.c_void_p]
+    lib.xq_cl_latent_delta_project.restype = C.c_int
+    lib.xq_cl_latent_delta_project.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                               C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.xq_prepared_upproject_bytes.restype = C.c_size_t
+    lib.xq_prepared_upproject_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    lib.xq_prepare_upproject.restype = C.c_int
+    lib.xq_prepare_upproject.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                         C.c_size_t, C.c_void_p]
+    lib.xq_cl_accumulate_latent_workspace_bytes.restype = C.c_size_t
+    lib.xq_cl_accumulate_latent_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    lib.xq_cl_accumulate_latent.restype = C.c_int
+    lib.xq_cl_accumulate_latent.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_int32, C.c_void_p,
+                                            C.POINTER(C.c_int32), C.c_void_p, C.c_size_t, C.c_void_p]
     _LIB = lib
     return lib
 
@@ -322,3 +337,56 @@ def xq_remat_attn_decode_latent(attn, q_bf16, wprep, lens, latent, out=None, wor
                                                       _i32(lens, latent.B), _ptr(out), _ptr(workspace),
                                                       workspace.numel(), _stream()), "xq_remat_attn_decode_latent")
     return out
+
+
+def xq_cl_latent_delta_project(x_bf16, acc_bf16, Ut_bf16, start, out=None):
+    """(x - acc rows start[b]+t) U_kv for x [B][T][d], acc [B][cap][d], Ut = U_kv transposed [n_lat][d]
+    -> [B][T][n_lat] bf16."""
+    for t in (x_bf16, acc_bf16, Ut_bf16):
+        assert t.dtype == torch.bfloat16 and t.is_contiguous()
+    B, T, d = x_bf16.shape
+    assert acc_bf16.dim() == 3 and acc_bf16.shape[0] == B and acc_bf16.shape[2] == d
+    n_lat = Ut_bf16.shape[0]
+    assert Ut_bf16.shape[1] == d
+    if out is None:
+        out = torch.empty((B, T, n_lat), dtype=torch.bfloat16, device=x_bf16.device)
+    _check(load_library().xq_cl_latent_delta_project(_ptr(x_bf16), _ptr(acc_bf16), _ptr(Ut_bf16), B, T,
+                                                     acc_bf16.shape[1], _i32(start, B), d, n_lat, _ptr(out),
+                                                     _stream()), "xq_cl_latent_delta_project")
+    return out
+
+
+def xq_prepared_upproject_bytes(d, n_lat, group, src_bits):
+    return load_library().xq_prepared_upproject_bytes(d, n_lat, group, src_bits)
+
+
+def xq_prepare_upproject(d, group, src_bits, Ut_bf16, out=None):
+    """Prepared stream of U_kv^T (Ut [n_lat][d] bf16) for xq_cl_accumulate_latent."""
+    assert Ut_bf16.dtype == torch.bfloat16 and Ut_bf16.is_contiguous() and Ut_bf16.shape[1] == d
+    n_lat = Ut_bf16.shape[0]
+    nbytes = xq_prepared_upproject_bytes(d, n_lat, group, src_bits)
+    if nbytes == 0:
+        raise XQError("xq_prepare_upproject: unsupported combination")
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=Ut_bf16.device)
+    _check(load_library().xq_prepare_upproject(d, n_lat, group, src_bits, _ptr(Ut_bf16), _ptr(out), out.numel(),
+                                               _stream()), "xq_prepare_upproject")
+    return out
+
+
+def xq_cl_accumulate_latent_workspace_bytes(B, max_len, n_lat, group):
+    return load_library().xq_cl_accumulate_latent_workspace_bytes(B, max_len, n_lat, group)
+
+
+def xq_cl_accumulate_latent(acc_bf16, delta, uprep, lens, workspace=None):
+    """acc [B][cap][d] += dequant(delta cache, fmt.d = n_lat) U_kv^T on rows t < lens[b], in place."""
+    assert acc_bf16.dtype == torch.bfloat16 and acc_bf16.is_contiguous() and acc_bf16.dim() == 3
+    assert acc_bf16.shape[0] == delta.B and acc_bf16.shape[1] == delta.cap
+    lens = [int(v) for v in lens]
+    cs = delta.c_struct()
+    need = xq_cl_accumulate_latent_workspace_bytes(delta.B, max(max(lens), 1) if lens else 1, delta.d, delta.group)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=acc_bf16.device)
+    _check(load_library().xq_cl_accumulate_latent(_ptr(acc_bf16), C.byref(cs), acc_bf16.shape[2], _ptr(uprep),
+                                                  _i32(lens, delta.B), _ptr(workspace), workspace.numel(),
+                                                  _stream()), "xq_cl_accumulate_latent")

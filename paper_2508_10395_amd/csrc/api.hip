@@ -22,6 +22,11 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
                                         const void* wprep, const BatchI32& len, int max_len, float* out, void* ws,
                                         hipStream_t s);
 size_t remat_latent_workspace_bytes(int B, int Hq, int max_len, int r, int group);
+hipError_t run_latent_delta_project(const uint16_t* x, const uint16_t* acc, const uint16_t* ut, int B, int T, int cap,
+                                    const BatchI32& start, int d, int n_lat, uint16_t* out, hipStream_t s);
+size_t upproject_workspace_bytes(int B, int max_len, int n_lat, int group);
+hipError_t run_cl_accumulate_latent(uint16_t* acc, const xq_cache_t* xc, int d, const void* uprep,
+                                    const BatchI32& len, int max_len, void* ws, hipStream_t s);
 size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool coded);
 
 static bool fmt_ok(const xq_qfmt_t& f)
@@ -302,6 +307,79 @@ xq_status_t xq_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q_bf
         return XQ_ERR_WORKSPACE;
     hipError_t e = run_remat_attn_decode_latent(a, q_bf16, latent, wprep, lv, max_len, out, workspace,
                                                 static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+static bool upproject_combo_ok(int d, int n_lat, int group, int src_bits)
+{
+    return d > 0 && d % 256 == 0 && src_bits != 16 && wprep_combo_ok(n_lat, group, src_bits);
+}
+
+xq_status_t xq_cl_latent_delta_project(const uint16_t* x_bf16, const uint16_t* acc_bf16, const uint16_t* Ut_bf16,
+                                       int32_t B, int32_t T, int32_t cap, const int32_t* start, int32_t d,
+                                       int32_t n_lat, uint16_t* out_bf16, void* stream)
+{
+    if (B < 1 || T < 0 || cap < 1 || d <= 0 || n_lat <= 0 || !start) return XQ_ERR_INVALID_ARG;
+    if (B > XQ_MAX_BATCH || d % 128 != 0 || n_lat % 32 != 0) return XQ_ERR_UNSUPPORTED;
+    BatchI32 sv{};
+    for (int b = 0; b < B; ++b) {
+        if (start[b] < 0 || (long long)start[b] + T > cap) return XQ_ERR_INVALID_ARG;
+        sv.v[b] = start[b];
+    }
+    if (T == 0) return XQ_OK;
+    if ((long long)B * T > 65535LL * 32) return XQ_ERR_UNSUPPORTED;
+    if (!x_bf16 || !acc_bf16 || !Ut_bf16 || !out_bf16 || !aligned16(x_bf16) || !aligned16(acc_bf16) ||
+        !aligned16(Ut_bf16) || !aligned16(out_bf16))
+        return XQ_ERR_INVALID_ARG;
+    hipError_t e = run_latent_delta_project(x_bf16, acc_bf16, Ut_bf16, B, T, cap, sv, d, n_lat, out_bf16,
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+size_t xq_prepared_upproject_bytes(int32_t d, int32_t n_lat, int32_t group, int32_t src_bits)
+{
+    if (!upproject_combo_ok(d, n_lat, group, src_bits)) return 0;
+    return make_wprep_layout(n_lat, group, src_bits, d / 256).total_bytes;
+}
+
+xq_status_t xq_prepare_upproject(int32_t d, int32_t n_lat, int32_t group, int32_t src_bits, const uint16_t* Ut_bf16,
+                                 void* out, size_t out_bytes, void* stream)
+{
+    if (!Ut_bf16 || !out || !aligned16(Ut_bf16) || !aligned16(out) || d <= 0 || n_lat <= 0) return XQ_ERR_INVALID_ARG;
+    if (!upproject_combo_ok(d, n_lat, group, src_bits)) return XQ_ERR_UNSUPPORTED;
+    // the contraction runs over the latent channels; a "head" is 256 adjacent hidden channels
+    const WPrepLayout L = make_wprep_layout(n_lat, group, src_bits, d / 256);
+    if (out_bytes < L.total_bytes) return XQ_ERR_WORKSPACE;
+    hipError_t e = run_prepare_weights(L, Ut_bf16, Ut_bf16 + 128, d, 256, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+size_t xq_cl_accumulate_latent_workspace_bytes(int32_t B, int32_t max_len, int32_t n_lat, int32_t group)
+{
+    if (B < 1 || max_len < 1 || n_lat <= 0 || (group != 64 && group != 128) || n_lat % 128 != 0) return 0;
+    return upproject_workspace_bytes(B, max_len, n_lat, group);
+}
+
+xq_status_t xq_cl_accumulate_latent(uint16_t* acc_bf16, const xq_cache_t* delta, int32_t d, const void* uprep,
+                                    const int32_t* len, void* workspace, size_t workspace_bytes, void* stream)
+{
+    xq_status_t st = check_cache(delta);
+    if (st != XQ_OK) return st;
+    if (!acc_bf16 || !uprep || !len || !aligned16(acc_bf16) || !aligned16(uprep) || d <= 0) return XQ_ERR_INVALID_ARG;
+    if (!upproject_combo_ok(d, delta->fmt.d, delta->fmt.group, delta->fmt.bits)) return XQ_ERR_UNSUPPORTED;
+    BatchI32 lv{};
+    int max_len = 0;
+    for (int b = 0; b < delta->B; ++b) {
+        if (len[b] < 0 || len[b] > delta->cap) return XQ_ERR_INVALID_ARG;
+        lv.v[b] = len[b];
+        if (len[b] > max_len) max_len = len[b];
+    }
+    if (max_len == 0) return XQ_OK;
+    if (!workspace || !aligned16(workspace)) return XQ_ERR_INVALID_ARG;
+    if (workspace_bytes < upproject_workspace_bytes(delta->B, max_len, delta->fmt.d, delta->fmt.group))
+        return XQ_ERR_WORKSPACE;
+    hipError_t e = run_cl_accumulate_latent(acc_bf16, delta, d, uprep, lv, max_len, workspace,
+                                            static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 

@@ -96,6 +96,8 @@ struct RematParams {
     long long head_bytes;
     float scale_log2e;       // softmax_scale * log2(e)
     BatchI32 len;
+    uint16_t* acc_out;       // up-projection mode: accumulator [B][cap][d_out] bf16, updated in place
+    int d_out;
     const float* rope;       // optional [n_pos][64][2] cos, sin: rotate the keys (half-split pairs)
     BatchI32 pos0;           // with rope: position of cache row 0 of each sequence
 };
@@ -347,7 +349,31 @@ __device__ __forceinline__ void weighted_sum_epilogue(const RematParams& p, cons
     });
 }
 
-constexpr int MODE_ATTENTION = 0, MODE_SCORES = 1, MODE_WEIGHTED_SUM = 2;
+// ---- cross-layer accumulator of grouped-query models (Sec. 3.3.2): the contraction is the
+// up-projection of a cached latent delta through U_kv^T, "head" hk = 256 adjacent hidden channels.
+// The wave adds its 32 tokens x 256 channels to the bf16 accumulator rows (fp32 add, one RNE
+// rounding).  A lane owns 4 adjacent channels per (block, i4): 8-byte read-modify-write, and the
+// two halves of the wave make that 16 contiguous bytes per token.
+__device__ __forceinline__ void accumulate_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8])
+{
+    if (c.tok >= c.len) return;
+    uint16_t* row = p.acc_out + ((long long)c.b * p.cap + c.tok) * p.d_out + c.hk * 256 + c.half * 4;
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            uint2* ptr = reinterpret_cast<uint2*>(row + nb * 32 + i4 * 8);
+            const uint2 old = *ptr;
+            uint2 upd;
+            upd.x = f32_to_bf16_rne(bf16_lo_to_f32(old.x) + acc[nb][i4 * 4 + 0]) |
+                    (f32_to_bf16_rne(bf16_hi_to_f32(old.x) + acc[nb][i4 * 4 + 1]) << 16);
+            upd.y = f32_to_bf16_rne(bf16_lo_to_f32(old.y) + acc[nb][i4 * 4 + 2]) |
+                    (f32_to_bf16_rne(bf16_hi_to_f32(old.y) + acc[nb][i4 * 4 + 3]) << 16);
+            *ptr = upd;
+        }
+}
+
+constexpr int MODE_ATTENTION = 0, MODE_SCORES = 1, MODE_WEIGHTED_SUM = 2, MODE_ACCUMULATE = 3;
 
 // =====================================================================================
 // coded source (XQuant cache, BITS in {2,3,4})
@@ -708,6 +734,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     for (int j = 0; j < 8; ++j) acc[j] *= E[GPS + j / KSG];
     if constexpr (MODE == MODE_SCORES) scores_epilogue(p, c, acc);
     else if constexpr (MODE == MODE_WEIGHTED_SUM) weighted_sum_epilogue(p, c, acc);
+    else if constexpr (MODE == MODE_ACCUMULATE) accumulate_epilogue(p, c, acc);
     else attention_epilogue(p, c, acc);
 }
 
@@ -1031,6 +1058,41 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
     if (e != hipSuccess) return e;
     combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len);
     return hipGetLastError();
+}
+
+// Sec. 3.3.2: acc[b][t][:] += dequant(latent delta cache row) U_kv^T for t < len[b], with the
+// contraction kernel laid over d / 256 column blocks of the hidden size.  ws holds the effective
+// scales only.
+size_t upproject_workspace_bytes(int B, int max_len, int n_lat, int group)
+{
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    return (size_t)B * tiles * (size_t)(n_lat / group + 1) * TILE_TOKENS * sizeof(uint16_t);
+}
+
+hipError_t run_cl_accumulate_latent(uint16_t* acc, const xq_cache_t* xc, int d, const void* uprep,
+                                    const BatchI32& len, int max_len, void* ws, hipStream_t s)
+{
+    const int bits = xc->fmt.bits, G = xc->fmt.group, n_lat = xc->fmt.d, B = xc->B;
+    const int blocks = d / 256;
+    const WPrepLayout L = make_wprep_layout(n_lat, G, bits, blocks);
+    RematParams p{};
+    p.B = B; p.cap = xc->cap; p.Hq = p.Hkv = blocks; p.grid_heads = blocks;
+    p.tiles_per_seq = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    p.chunks_per_seq = p.tiles_per_seq * (TILE_TOKENS / CHUNK_TOKENS);
+    p.len = len;
+    p.codes = xc->codes; p.scale = xc->scale; p.zero = xc->zero;
+    p.wprep = static_cast<const uint8_t*>(uprep);
+    p.d = n_lat; p.row_d = n_lat;
+    p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
+    p.ng_row = L.ng;
+    p.head_bytes = (long long)L.head_bytes;
+    p.eT = static_cast<uint16_t*>(ws);
+    p.acc_out = acc; p.d_out = d;
+    scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
+        xc->scale, static_cast<uint16_t*>(ws), xc->cap, L.ng, L.ng, p.tiles_per_seq, bits, len);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_coded<MODE_ACCUMULATE>(bits, G, p, blocks * B * p.tiles_per_seq, s);
 }
 
 }  // namespace xq
