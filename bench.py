@@ -209,6 +209,33 @@ def main():
                                          "useful_TFLOP/s": lflops / t_l / 1e9,
                                          "decode_projection_us": t_p * 1e3}
         del lcache, lat, lwp, lws
+        # the cross-layer step of the same GQA layer (Sec. 3.3.2): latent delta of the new token, quantise,
+        # up-project every cached delta into the accumulator, attend from the accumulator with [Wk | Wv]
+        n_lat = 2 * r
+        dcache = xq.alloc_cache(ow.B, ow.L, n_lat, ow.G, ow.bits)
+        dl = (torch.randn((ow.B, ow.L, n_lat), device=dev, generator=gen) * 0.3).to(torch.bfloat16)
+        xq.xq_quantize_append(dcache, dl, [0] * ow.B)
+        del dl
+        uprep = xq.xq_prepare_upproject(ow.d, ow.G, ow.bits, ut)
+        oacc = torch.randn((ow.B, ow.L, ow.d), device=dev, generator=gen).to(torch.bfloat16)
+        uws = torch.empty(xq.xq_cl_accumulate_latent_workspace_bytes(ow.B, ow.L, n_lat, ow.G), dtype=torch.uint8,
+                          device=dev)
+        t_u = timed(lambda: xq.xq_cl_accumulate_latent(oacc, dcache, uprep, olens, workspace=uws), n=5, warm=5)
+        dlat = torch.empty((ow.B, 1, n_lat), dtype=torch.bfloat16, device=dev)
+        t_d = timed(lambda: xq.xq_cl_latent_delta_project(xnew, oacc, ut, [ow.L - 1] * ow.B, out=dlat), n=20)
+        owk, owv = xi.gen_weights(ow)
+        dwp = xq.xq_prepare_weights(oattn, ow.d, 0, 16, dev_bf16(owk), dev_bf16(owv))
+        dws = torch.empty(xq.xq_remat_attn_workspace_bytes(oattn, ow.B, ow.L, ow.d, 0), dtype=torch.uint8, device=dev)
+        t_a = timed(lambda: xq.xq_remat_attn_decode(oattn, oq, dwp, olens, acc_bf16=oacc, out=oout, workspace=dws),
+                    n=5, warm=2)
+        uflops = 2.0 * ow.B * ow.L * n_lat * ow.d
+        extra["cl_gqa_c4"] = {"workload": "c4 shape, cross-layer step of a GQA layer (latent width 2048, 2-bit, group 64); "
+                                          "random latent deltas and U_kv (timing only)",
+                              "accumulate_latent_ms": t_u, "accumulate_latent_TFLOP/s": uflops / t_u / 1e9,
+                              "accumulate_latent_frac_mfma_peak": uflops / t_u / 1e9 / PEAK_BF16_TFLOPS,
+                              "delta_projection_us": t_d * 1e3,
+                              "remat_attn_from_accumulator_ms": t_a}
+        del dcache, oacc, uprep, uws, dwp, dws
 
     traffic = K3_HBM_BYTES_PER_LAUNCH
 

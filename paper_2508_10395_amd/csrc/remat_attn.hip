@@ -352,25 +352,59 @@ __device__ __forceinline__ void weighted_sum_epilogue(const RematParams& p, cons
 // ---- cross-layer accumulator of grouped-query models (Sec. 3.3.2): the contraction is the
 // up-projection of a cached latent delta through U_kv^T, "head" hk = 256 adjacent hidden channels.
 // The wave adds its 32 tokens x 256 channels to the bf16 accumulator rows (fp32 add, one RNE
-// rounding).  A lane owns 4 adjacent channels per (block, i4): 8-byte read-modify-write, and the
-// two halves of the wave make that 16 contiguous bytes per token.
-__device__ __forceinline__ void accumulate_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8])
+// rounding).  In the accumulator layout a lane owns 4 adjacent channels of one token, which would
+// touch 32 rows with 16 bytes each per memory instruction; so 64 channels at a time are turned
+// through a wave-private piece of LDS (the weight slabs are dead by now: the last workgroup
+// barrier of the contraction loop comes after the last read of them) into rows of 8 lanes x 16
+// bytes, and every read-modify-write instruction covers 8 full 128-byte lines.
+constexpr int STAGE_ROW_BYTES = 64 * 4 + 16;       // 64 fp32 + 16: rows start 4 banks apart
+static_assert(8 * CHUNK_TOKENS * STAGE_ROW_BYTES <= 2 * SLAB_BYTES, "staging fits the slab buffers");
+
+__device__ __forceinline__ void accumulate_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8],
+                                                    uint8_t* lds)
 {
-    if (c.tok >= c.len) return;
-    uint16_t* row = p.acc_out + ((long long)c.b * p.cap + c.tok) * p.d_out + c.hk * 256 + c.half * 4;
+    const int tok0 = c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS;
+    if (tok0 >= c.len) return;                                             // wave-uniform
+    uint8_t* stage = lds + c.wave * (CHUNK_TOKENS * STAGE_ROW_BYTES);
+    const int r0 = c.lane >> 3, c8 = c.lane & 7;                           // row in a group of 8; 8-channel piece
+    uint16_t* gbase = p.acc_out + ((long long)c.b * p.cap + tok0) * p.d_out + c.hk * 256 + c8 * 8;
+    // all 16 old pieces first, so that their latency is paid once (rows past len: a clamped copy, not stored)
+    uint4 old[4][4];
 #pragma unroll
-    for (int nb = 0; nb < 8; ++nb)
+    for (int pb = 0; pb < 4; ++pb)
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-            uint2* ptr = reinterpret_cast<uint2*>(row + nb * 32 + i4 * 8);
-            const uint2 old = *ptr;
-            uint2 upd;
-            upd.x = f32_to_bf16_rne(bf16_lo_to_f32(old.x) + acc[nb][i4 * 4 + 0]) |
-                    (f32_to_bf16_rne(bf16_hi_to_f32(old.x) + acc[nb][i4 * 4 + 1]) << 16);
-            upd.y = f32_to_bf16_rne(bf16_lo_to_f32(old.y) + acc[nb][i4 * 4 + 2]) |
-                    (f32_to_bf16_rne(bf16_hi_to_f32(old.y) + acc[nb][i4 * 4 + 3]) << 16);
-            *ptr = upd;
+        for (int k = 0; k < 4; ++k) {
+            const int r = min(r0 + 8 * k, c.len - 1 - tok0);
+            old[pb][k] = *reinterpret_cast<const uint4*>(gbase + (long long)r * p.d_out + pb * 64);
         }
+    static_for<0, 4>([&](auto PB) XQ_INLINE_LAMBDA {
+        constexpr int pb = decltype(PB)::value;
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const f32x16& a = acc[2 * pb + q];
+                float4 v; v.x = a[i4 * 4 + 0]; v.y = a[i4 * 4 + 1]; v.z = a[i4 * 4 + 2]; v.w = a[i4 * 4 + 3];
+                *reinterpret_cast<float4*>(stage + c.tl * STAGE_ROW_BYTES + (q * 32 + i4 * 8 + c.half * 4) * 4) = v;
+            }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int r = r0 + 8 * k;
+            const float4 lo = *reinterpret_cast<const float4*>(stage + r * STAGE_ROW_BYTES + c8 * 32);
+            const float4 hi = *reinterpret_cast<const float4*>(stage + r * STAGE_ROW_BYTES + c8 * 32 + 16);
+            if (tok0 + r < c.len) {
+                const uint4 o = old[pb][k];
+                uint4 upd;
+                upd.x = f32_to_bf16_rne(bf16_lo_to_f32(o.x) + lo.x) | (f32_to_bf16_rne(bf16_hi_to_f32(o.x) + lo.y) << 16);
+                upd.y = f32_to_bf16_rne(bf16_lo_to_f32(o.y) + lo.z) | (f32_to_bf16_rne(bf16_hi_to_f32(o.y) + lo.w) << 16);
+                upd.z = f32_to_bf16_rne(bf16_lo_to_f32(o.z) + hi.x) | (f32_to_bf16_rne(bf16_hi_to_f32(o.z) + hi.y) << 16);
+                upd.w = f32_to_bf16_rne(bf16_lo_to_f32(o.w) + hi.z) | (f32_to_bf16_rne(bf16_hi_to_f32(o.w) + hi.w) << 16);
+                *reinterpret_cast<uint4*>(gbase + (long long)r * p.d_out + pb * 64) = upd;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    });
 }
 
 constexpr int MODE_ATTENTION = 0, MODE_SCORES = 1, MODE_WEIGHTED_SUM = 2, MODE_ACCUMULATE = 3;
@@ -734,7 +768,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     for (int j = 0; j < 8; ++j) acc[j] *= E[GPS + j / KSG];
     if constexpr (MODE == MODE_SCORES) scores_epilogue(p, c, acc);
     else if constexpr (MODE == MODE_WEIGHTED_SUM) weighted_sum_epilogue(p, c, acc);
-    else if constexpr (MODE == MODE_ACCUMULATE) accumulate_epilogue(p, c, acc);
+    else if constexpr (MODE == MODE_ACCUMULATE) accumulate_epilogue(p, c, acc, lds);
     else attention_epilogue(p, c, acc);
 }
 
