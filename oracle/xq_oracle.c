@@ -34,6 +34,9 @@
  *                          as bf16.  (Rematerialising from the latent cache needs
  *                          nothing new: it is xqo_remat_attn_pairs with the
  *                          block-diagonal weights [[S_k B_k^T, 0], [0, S_v B_v^T]].)
+ *   (causal attention of several new tokens per sequence -- chunked prefill -- is, per
+ *   query, xqo_remat_attn_pairs over the prefix ending at the query's own row; the Python
+ *   wrapper prefill_attn_triples does exactly that and adds no arithmetic.)
  *   xqo_project_delta_rows Sec. 3.3.2 (cross-layer deltas of grouped-query models):
  *                          (X_i - X^_{i-1}) U_kv, stored as bf16.
  *   xqo_cl_accumulate_latent_rows

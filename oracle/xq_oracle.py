@@ -230,6 +230,28 @@ def remat_attn_pairs(*, q_bf16, Wk, Wv, Hq, Hkv, hd, softmax_scale, lens, pairs,
     return out
 
 
+def prefill_attn_triples(*, q_bf16, lens, triples, **kw):
+    """Causal attention of the T newest tokens of every sequence (chunked prefill; T = 1 is the
+    decode step): q_bf16 [B][T][Hq][hd]; query t of sequence b sits at cache row lens[b] - T + t
+    and attends rows 0 .. that row.  By definition this is the decode attention of that query
+    over the prefix that ends at its own row, so each listed (b, t, q-head) triple is one call
+    of remat_attn_pairs with the prefix length -- nothing else is computed here.
+    Returns [ntriples][hd] fp32 in the order of `triples`; other arguments as remat_attn_pairs."""
+    q = _c(q_bf16, np.uint16)
+    B, T = q.shape[0], q.shape[1]
+    lens = np.asarray(lens, np.int64)
+    assert lens.shape == (B,) and np.all(lens >= T)
+    out = None
+    for t in sorted({tr[1] for tr in triples}):
+        idx = [i for i, tr in enumerate(triples) if tr[1] == t]
+        res = remat_attn_pairs(q_bf16=np.ascontiguousarray(q[:, t]), lens=(lens - T + t + 1).astype(np.int32),
+                               pairs=[(triples[i][0], triples[i][2]) for i in idx], **kw)
+        if out is None:
+            out = np.empty((len(triples), res.shape[1]), np.float32)
+        out[idx] = res
+    return out
+
+
 def rope_rows(K, cos_sin, pos0=0):
     """Rotate key rows K [L][hd] (float64, in place on a copy) by the table; returns the copy."""
     K = np.array(K, np.float64, order="C")
