@@ -169,6 +169,29 @@ xq_status_t xq_remat_attn_decode_rope(const xq_attn_t *a, const uint16_t *q_bf16
                                       size_t workspace_bytes, void *stream);
 
 /*
+ * Causal attention of the T newest tokens of every sequence (chunked prefill; the method
+ * rematerialises K, V for any query that attends to the cache, Sec. 3.1, and App. A treats T > 1
+ * new tokens).  The T queries' own rows are already in the cache (xq_quantize_append first):
+ * query t of sequence b sits at cache row len[b] - T + t and attends rows 0 .. that row.
+ *   q_bf16   dev [B][T][n_q_heads][head_dim] bf16
+ *   len      host [B], T <= len[b] <= cap: valid cache rows including the T new ones
+ *   rope_cos_sin, rope_positions, pos0: as xq_remat_attn_decode_rope, or NULL, 0, NULL for no rotation
+ *   out      dev [B][T][n_q_heads][head_dim] fp32
+ *   workspace dev, xq_remat_attn_prefill_workspace_bytes(a, B, T, max len, d, group) bytes
+ *             (group = 0 for the accumulator source); B*T <= 65535.
+ * Everything else as xq_remat_attn_decode.  Scores and the weighted sum run on the matrix cores
+ * with K, V and the softmax weights split into bf16 hi + lo parts (relative error 2^-16).
+ */
+size_t      xq_remat_attn_prefill_workspace_bytes(const xq_attn_t *a, int32_t B, int32_t T,
+                                                  int32_t max_len, int32_t d, int32_t group);
+xq_status_t xq_remat_attn_prefill(const xq_attn_t *a, const uint16_t *q_bf16, int32_t T,
+                                  const xq_cache_t *xcache, const uint16_t *acc_bf16, int32_t B,
+                                  int32_t cap, int32_t d, const void *wprep, const int32_t *len,
+                                  const float *rope_cos_sin, int32_t rope_positions,
+                                  const int32_t *pos0, float *out, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
+/*
  * Sec. 3.3.1 (models with grouped-query attention): with the offline decompositions
  * Wk = Uk Sk Bk^T and Wv = Uv Sv Bv^T (SVD, rank r = n_kv_heads*head_dim), the cache holds the
  * latent row [x Uk | x Uv] (2r channels) of every token, quantised like any other X cache, and K,

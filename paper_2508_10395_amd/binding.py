@@ -25,6 +25,7 @@ SYMBOLS = [
     "xq_prepared_weights_latent_bytes", "xq_remat_attn_latent_workspace_bytes",
     "xq_cl_latent_delta_project", "xq_prepared_upproject_bytes", "xq_prepare_upproject",
     "xq_cl_accumulate_latent_workspace_bytes", "xq_cl_accumulate_latent",
+    "xq_remat_attn_prefill_workspace_bytes", "xq_remat_attn_prefill",
 ]
 
 
@@ -117,6 +118,14 @@ def load_library():
     lib.xq_cl_accumulate_latent.restype = C.c_int
     lib.xq_cl_accumulate_latent.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_int32, C.c_void_p,
                                             C.POINTER(C.c_int32), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xq_remat_attn_prefill_workspace_bytes.restype = C.c_size_t
+    lib.xq_remat_attn_prefill_workspace_bytes.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                                          C.c_int32]
+    lib.xq_remat_attn_prefill.restype = C.c_int
+    lib.xq_remat_attn_prefill.argtypes = [C.POINTER(_Attn), C.c_void_p, C.c_int32, C.POINTER(_Cache), C.c_void_p,
+                                          C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_int32),
+                                          C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p, C.c_void_p,
+                                          C.c_size_t, C.c_void_p]
     _LIB = lib
     return lib
 
@@ -390,3 +399,42 @@ def xq_cl_accumulate_latent(acc_bf16, delta, uprep, lens, workspace=None):
     _check(load_library().xq_cl_accumulate_latent(_ptr(acc_bf16), C.byref(cs), acc_bf16.shape[2], _ptr(uprep),
                                                   _i32(lens, delta.B), _ptr(workspace), workspace.numel(),
                                                   _stream()), "xq_cl_accumulate_latent")
+
+
+def xq_remat_attn_prefill_workspace_bytes(attn, B, T, max_len, d, group):
+    a = attn.c_struct()
+    return load_library().xq_remat_attn_prefill_workspace_bytes(C.byref(a), B, T, max_len, d, group)
+
+
+def xq_remat_attn_prefill(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=None, out=None, workspace=None,
+                          rope_cos_sin=None, pos0=None):
+    """Causal attention of the T newest cache rows of every sequence: q [B][T][Hq][head_dim] bf16 ->
+    fp32 [B][T][Hq][head_dim]; lens[b] counts the valid rows including the T new ones."""
+    assert q_bf16.dtype == torch.bfloat16 and q_bf16.is_contiguous() and q_bf16.dim() == 4
+    T = q_bf16.shape[1]
+    if xcache is not None:
+        B, cap, d = xcache.B, xcache.cap, xcache.d
+        cs = xcache.c_struct()
+        cptr = C.byref(cs)
+    else:
+        assert acc_bf16.dtype == torch.bfloat16 and acc_bf16.is_contiguous() and acc_bf16.dim() == 3
+        B, cap, d = acc_bf16.shape
+        cptr = None
+    lens = [int(v) for v in lens]
+    a = attn.c_struct()
+    need = xq_remat_attn_prefill_workspace_bytes(attn, B, T, max(lens) if lens else 1, d,
+                                                 xcache.group if xcache is not None else 0)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q_bf16.device)
+    if out is None:
+        out = torch.empty((B, T, attn.n_q_heads, attn.head_dim), dtype=torch.float32, device=q_bf16.device)
+    rope_ptr, n_pos, p0 = None, 0, None
+    if rope_cos_sin is not None:
+        assert rope_cos_sin.dtype == torch.float32 and rope_cos_sin.is_contiguous() and rope_cos_sin.dim() == 3
+        rope_ptr, n_pos = _ptr(rope_cos_sin), rope_cos_sin.shape[0]
+        p0 = _i32([0] * B if pos0 is None else pos0, B)
+    _check(load_library().xq_remat_attn_prefill(C.byref(a), _ptr(q_bf16), T, cptr, _ptr(acc_bf16), B, cap, d,
+                                                _ptr(wprep), _i32(lens, B), rope_ptr, n_pos, p0, _ptr(out),
+                                                _ptr(workspace), workspace.numel(), _stream()),
+           "xq_remat_attn_prefill")
+    return out

@@ -24,6 +24,11 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
 size_t remat_latent_workspace_bytes(int B, int Hq, int max_len, int r, int group);
 hipError_t run_latent_delta_project(const uint16_t* x, const uint16_t* acc, const uint16_t* ut, int B, int T, int cap,
                                     const BatchI32& start, int d, int n_lat, uint16_t* out, hipStream_t s);
+size_t remat_prefill_workspace_bytes(int B, int T, int Hq, int max_len, int d, int group, bool coded);
+hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, const xq_cache_t* xc,
+                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
+                                  const BatchI32& len, int max_len, float* out, void* ws,
+                                  const float* rope, const BatchI32* pos0, hipStream_t s);
 size_t upproject_workspace_bytes(int B, int max_len, int n_lat, int group);
 hipError_t run_cl_accumulate_latent(uint16_t* acc, const xq_cache_t* xc, int d, const void* uprep,
                                     const BatchI32& len, int max_len, void* ws, hipStream_t s);
@@ -214,13 +219,23 @@ size_t xq_remat_attn_workspace_bytes(const xq_attn_t* a, int32_t B, int32_t max_
     return remat_workspace_bytes(B, a->n_q_heads, max_len, d, group ? group : 128, group != 0);
 }
 
+size_t xq_remat_attn_prefill_workspace_bytes(const xq_attn_t* a, int32_t B, int32_t T, int32_t max_len, int32_t d,
+                                             int32_t group)
+{
+    if (check_attn(a) != XQ_OK || B < 1 || T < 1 || max_len < 1 || d <= 0 || d % 128 != 0) return 0;
+    if (group != 0 && group != 64 && group != 128) return 0;
+    return remat_prefill_workspace_bytes(B, T, a->n_q_heads, max_len, d, group ? group : 128, group != 0);
+}
+
 static xq_status_t remat_attn_common(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* xcache,
                                      const uint16_t* acc_bf16, int32_t B, int32_t cap, int32_t d,
                                      const void* wprep, const int32_t* len, float* out, void* workspace,
                                      size_t workspace_bytes, const float* rope, int32_t rope_positions,
-                                     const int32_t* pos0, void* stream)
+                                     const int32_t* pos0, void* stream, int32_t T = 0)
 {
+    // T = 0: one decode query per sequence; T >= 1: the T newest rows are queries (causal)
     xq_status_t st = check_attn(a);
+    if (T < 0) return XQ_ERR_INVALID_ARG;
     if (st != XQ_OK) return st;
     if ((xcache != nullptr) == (acc_bf16 != nullptr)) return XQ_ERR_INVALID_ARG;
     if (!q_bf16 || !wprep || !len || !out || !workspace) return XQ_ERR_INVALID_ARG;
@@ -238,12 +253,15 @@ static xq_status_t remat_attn_common(const xq_attn_t* a, const uint16_t* q_bf16,
     BatchI32 lv{};
     int max_len = 0;
     for (int b = 0; b < B; ++b) {
-        if (len[b] < 1 || len[b] > cap) return XQ_ERR_INVALID_ARG;
+        if (len[b] < 1 || len[b] > cap || len[b] < T) return XQ_ERR_INVALID_ARG;
         lv.v[b] = len[b];
         if (len[b] > max_len) max_len = len[b];
     }
-    if (workspace_bytes < xq_remat_attn_workspace_bytes(a, B, max_len, d, xcache ? xcache->fmt.group : 0))
-        return XQ_ERR_WORKSPACE;
+    if (T > 0 && (long long)B * T > 65535) return XQ_ERR_UNSUPPORTED;
+    const size_t need = T > 0 ? xq_remat_attn_prefill_workspace_bytes(a, B, T, max_len, d, xcache ? xcache->fmt.group : 0)
+                              : xq_remat_attn_workspace_bytes(a, B, max_len, d, xcache ? xcache->fmt.group : 0);
+    if (need == 0) return XQ_ERR_UNSUPPORTED;
+    if (workspace_bytes < need) return XQ_ERR_WORKSPACE;
     BatchI32 pv{};
     if (rope) {
         if (!pos0 || !aligned16(rope) || rope_positions < 1) return XQ_ERR_INVALID_ARG;
@@ -252,8 +270,10 @@ static xq_status_t remat_attn_common(const xq_attn_t* a, const uint16_t* q_bf16,
             pv.v[b] = pos0[b];
         }
     }
-    hipError_t e = run_remat_attn_decode(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, lv, max_len, out,
-                                         workspace, rope, &pv, static_cast<hipStream_t>(stream));
+    hipError_t e = T > 0 ? run_remat_attn_prefill(a, q_bf16, T, xcache, acc_bf16, B, cap, d, wprep, lv, max_len, out,
+                                                  workspace, rope, &pv, static_cast<hipStream_t>(stream))
+                         : run_remat_attn_decode(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, lv, max_len, out,
+                                                 workspace, rope, &pv, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 
@@ -308,6 +328,17 @@ xq_status_t xq_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q_bf
     hipError_t e = run_remat_attn_decode_latent(a, q_bf16, latent, wprep, lv, max_len, out, workspace,
                                                 static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+xq_status_t xq_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q_bf16, int32_t T, const xq_cache_t* xcache,
+                                  const uint16_t* acc_bf16, int32_t B, int32_t cap, int32_t d, const void* wprep,
+                                  const int32_t* len, const float* rope_cos_sin, int32_t rope_positions,
+                                  const int32_t* pos0, float* out, void* workspace, size_t workspace_bytes,
+                                  void* stream)
+{
+    if (T < 1) return XQ_ERR_INVALID_ARG;
+    return remat_attn_common(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, len, out, workspace, workspace_bytes,
+                             rope_cos_sin, rope_positions, pos0, stream, T);
 }
 
 static bool upproject_combo_ok(int d, int n_lat, int group, int src_bits)

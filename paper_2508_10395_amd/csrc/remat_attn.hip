@@ -78,7 +78,8 @@ constexpr int lds_scales_off(int bits) { return LDS_CODES_OFF + n_code_images(bi
 constexpr int lds_coded_total(int bits) { return lds_scales_off(bits) + 3 * LDS_SCALES_BYTES; }
 
 struct RematParams {
-    const uint16_t* q;       // [B][Hq][128]
+    const uint16_t* q;       // [B][Hq][128]; prefill: [B][Tq][Hq][128]
+    int Tq;                  // prefill: new tokens (queries) per sequence; partials are then [B][Tq][Hq][chunks]
     const uint8_t* codes;    // coded source
     const uint16_t* scale;
     const uint16_t* zero;
@@ -208,6 +209,29 @@ __device__ __forceinline__ bool locate_tile(const RematParams& p, TileCtx& c)
     return c.tile * TILE_TOKENS < c.len;
 }
 
+// Rotary embedding of this lane's key: column n < 64 pairs with n + 64, i.e. accumulator element i
+// of block nb with the same element of block nb + 2.  The lane's 4 consecutive columns
+// 32 nb + 8 i4 + 4 half + [0, 4) need 8 consecutive floats of its position's row of the table.
+__device__ __forceinline__ void rope_rotate(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8])
+{
+    const float* tab = p.rope + (long long)(p.pos0.v[c.b] + min(c.tok, c.len - 1)) * 128;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            const float* cs = tab + 2 * (nb * 32 + i4 * 8 + c.half * 4);
+            const float4 cs0 = *reinterpret_cast<const float4*>(cs);
+            const float4 cs1 = *reinterpret_cast<const float4*>(cs + 4);
+            const float co[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, si[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float a = acc[nb][i4 * 4 + k], b = acc[nb + 2][i4 * 4 + k];
+                acc[nb][i4 * 4 + k] = __builtin_fmaf(a, co[k], -b * si[k]);
+                acc[nb + 2][i4 * 4 + k] = __builtin_fmaf(b, co[k], a * si[k]);
+            }
+        }
+}
+
 // ---- attention on the rematerialised chunk: each wave holds K (blocks 0-3) and V (blocks 4-7)
 // of its 32 tokens.  Accumulator element i of column block nb <-> column 32 (nb%4) + 8 (i/4) +
 // 4 half + i%4 of K or V, token = lane % 32.  No LDS and no barrier: scores, softmax weights and
@@ -215,27 +239,7 @@ __device__ __forceinline__ bool locate_tile(const RematParams& p, TileCtx& c)
 __device__ __forceinline__ void attention_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8])
 {
     if (c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS >= c.len) return;     // chunk entirely past len
-    if (p.rope) {
-        // Rotary embedding of this token's key: column n < 64 pairs with n + 64, i.e. accumulator
-        // element i of block nb with the same element of block nb + 2.  The lane's 4 consecutive
-        // columns 32 nb + 8 i4 + 4 half + [0, 4) need 8 consecutive floats of its position's row.
-        const float* tab = p.rope + (long long)(p.pos0.v[c.b] + min(c.tok, c.len - 1)) * 128;
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const float* cs = tab + 2 * (nb * 32 + i4 * 8 + c.half * 4);
-                const float4 cs0 = *reinterpret_cast<const float4*>(cs);
-                const float4 cs1 = *reinterpret_cast<const float4*>(cs + 4);
-                const float co[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, si[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float a = acc[nb][i4 * 4 + k], b = acc[nb + 2][i4 * 4 + k];
-                    acc[nb][i4 * 4 + k] = __builtin_fmaf(a, co[k], -b * si[k]);
-                    acc[nb + 2][i4 * 4 + k] = __builtin_fmaf(b, co[k], a * si[k]);
-                }
-            }
-    }
+    if (p.rope) rope_rotate(p, c, acc);
     const int gq = p.Hq / p.Hkv;
     const int chunk = c.tile * (TILE_TOKENS / CHUNK_TOKENS) + c.wave;
     for (int j = 0; j < gq; ++j) {
@@ -273,6 +277,155 @@ __device__ __forceinline__ void attention_epilogue(const RematParams& p, const T
                 }
             }
         if (c.lane == 0) {
+            p.part_ml[pidx * 2] = m;
+            p.part_ml[pidx * 2 + 1] = l;
+        }
+    }
+}
+
+// ---- several queries per sequence (chunked prefill, causal): the T newest cache rows of a sequence
+// are the queries' own tokens; query t sits at row len - T + t and sees rows 0 .. that row.
+// Scores and the weighted sum go through the matrix cores, 32 (query, head) rows at a time:
+//   S^T[token][query] = K Q^T : A = the wave's K rows straight from the accumulator (a lane's 8
+//       registers of one 16-column k-step are 8 contraction indices in a fixed permuted order that
+//       the Q fragment loads mirror), split into bf16 hi + lo (two MFMAs per k-step);
+//   the result has lane = query, registers = 16 of the 32 tokens (the other lane half holds the
+//       other 16): mask, max, exp2 and sum are per-lane loops plus one exchange between halves;
+//   O[query][n] = P V : A = the softmax weights as they sit in those registers (hi + lo), B = V
+//       read column-wise, for which V is transposed once per tile through the wave's own piece of
+//       LDS (bf16 hi and lo images, [n][32 tokens], rows 72 bytes apart: conflict-free 8-byte
+//       reads); hi*hi + lo*hi + hi*lo, the lo*lo term (2^-16 relative) is dropped.
+// One partial (m, l, o[128]) per (query, head, 32-token chunk), merged by the same combine kernel.
+constexpr int VT_ROW_BYTES = 72;
+constexpr int VT_IMAGE_BYTES = 128 * VT_ROW_BYTES;
+constexpr int VT_WAVE_BYTES = 2 * VT_IMAGE_BYTES;
+static_assert(8 * VT_WAVE_BYTES <= lds_coded_total(2), "transposed V fits the smallest LDS allocation");
+
+__device__ __forceinline__ void split_bf16x8(const float (&v)[8], uint4& hi, uint4& lo)
+{
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t h0 = f32_to_bf16_rne(v[2 * i]), h1 = f32_to_bf16_rne(v[2 * i + 1]);
+        h[i] = h0 | (h1 << 16);
+        l[i] = f32_to_bf16_rne(v[2 * i] - bf16_bits_to_f32(h0)) | (f32_to_bf16_rne(v[2 * i + 1] - bf16_bits_to_f32(h1)) << 16);
+    }
+    hi = make_uint4(h[0], h[1], h[2], h[3]);
+    lo = make_uint4(l[0], l[1], l[2], l[3]);
+}
+
+__device__ __forceinline__ f32x16 mfma_bf16(const uint4& a, const uint4& b, const f32x16& c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ void prefill_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8], uint8_t* lds)
+{
+    const int tok0 = c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS;
+    if (tok0 >= c.len) return;                                             // wave-uniform
+    if (p.rope) rope_rotate(p, c, acc);
+    uint8_t* vt = lds + c.wave * VT_WAVE_BYTES;
+    // V^T images: element i of block 4 + nb is V[token tl][n], n = 32 nb + 8 (i/4) + 4 half + i%4
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int n = nb * 32 + (i >> 2) * 8 + c.half * 4 + (i & 3);
+            const float v = acc[4 + nb][i];
+            const uint32_t h = f32_to_bf16_rne(v);
+            *reinterpret_cast<uint16_t*>(vt + n * VT_ROW_BYTES + c.tl * 2) = (uint16_t)h;
+            *reinterpret_cast<uint16_t*>(vt + VT_IMAGE_BYTES + n * VT_ROW_BYTES + c.tl * 2) =
+                (uint16_t)f32_to_bf16_rne(v - bf16_bits_to_f32(h));
+        }
+    // K fragments: k-step ks covers columns [16 ks, 16 ks + 16); this lane's 8 of them are
+    // 16 ks + 4 half + [0, 4) and 16 ks + 8 + 4 half + [0, 4)
+    uint4 khi[8], klo[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = acc[ks >> 1][(ks & 1) * 8 + k];
+        split_bf16x8(v, khi[ks], klo[ks]);
+    }
+    __builtin_amdgcn_wave_barrier();
+
+    const int gq = p.Hq / p.Hkv, NQ = p.Tq * gq;
+    const int chunk = c.tile * (TILE_TOKENS / CHUNK_TOKENS) + c.wave;
+    const int jq = c.tl;
+    for (int q0 = 0; q0 < NQ; q0 += 32) {
+        // this lane's query row of the group (rows past NQ repeat the last one and are not stored)
+        const int qi = min(q0 + jq, NQ - 1);
+        const int tq = qi / gq, hq = c.hk * gq + (qi - tq * gq);
+        const long long qrow = ((long long)c.b * p.Tq + tq) * p.Hq + hq;
+        const uint16_t* qv = p.q + qrow * 128 + c.half * 4;
+        f32x16 S;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) S[i] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const uint2 a = *reinterpret_cast<const uint2*>(qv + 16 * ks);
+            const uint2 b = *reinterpret_cast<const uint2*>(qv + 16 * ks + 8);
+            const uint4 qf = make_uint4(a.x, a.y, b.x, b.y);
+            S = mfma_bf16(khi[ks], qf, S);
+            S = mfma_bf16(klo[ks], qf, S);
+        }
+        // register r <-> token tok0 + 8 (r/4) + 4 half + r%4; visible up to the query's own row
+        const int limit = c.len - p.Tq + tq - tok0;
+        float m = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int rel = (r >> 2) * 8 + c.half * 4 + (r & 3);
+            S[r] = rel <= limit ? S[r] * p.scale_log2e : -INFINITY;
+            m = fmaxf(m, S[r]);
+        }
+        m = fmaxf(m, __shfl_xor(m, 32));
+        const float mu = m == -INFINITY ? 0.0f : m;                        // nothing visible: all weights 0
+        float pr[16], l = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            pr[r] = __builtin_amdgcn_exp2f(S[r] - mu);
+            l += pr[r];
+        }
+        l += __shfl_xor(l, 32);
+        uint4 phi[2], plo[2];
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+            float v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = pr[k2 * 8 + k];
+            split_bf16x8(v, phi[k2], plo[k2]);
+        }
+        f32x16 O[4];
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[nb][i] = 0.0f;
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2) {
+                // column n = 32 nb + jq of V, tokens 16 k2 + 4 half + [0, 4) and 16 k2 + 8 + 4 half + [0, 4)
+                const uint8_t* vp = vt + (nb * 32 + jq) * VT_ROW_BYTES + (16 * k2 + 4 * c.half) * 2;
+                const uint2 h0 = *reinterpret_cast<const uint2*>(vp), h1 = *reinterpret_cast<const uint2*>(vp + 16);
+                const uint2 l0 = *reinterpret_cast<const uint2*>(vp + VT_IMAGE_BYTES);
+                const uint2 l1 = *reinterpret_cast<const uint2*>(vp + VT_IMAGE_BYTES + 16);
+                const uint4 vh = make_uint4(h0.x, h0.y, h1.x, h1.y), vl = make_uint4(l0.x, l0.y, l1.x, l1.y);
+                O[nb] = mfma_bf16(plo[k2], vh, O[nb]);
+                O[nb] = mfma_bf16(phi[k2], vl, O[nb]);
+                O[nb] = mfma_bf16(phi[k2], vh, O[nb]);
+            }
+        }
+        // O: lane = column 32 nb + jq, register r <-> query q0 + 8 (r/4) + 4 half + r%4
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int qr = q0 + (r >> 2) * 8 + c.half * 4 + (r & 3);
+            if (qr < NQ) {
+                const int tr = qr / gq, hr = c.hk * gq + (qr - tr * gq);
+                float* po = p.part_o + ((((long long)c.b * p.Tq + tr) * p.Hq + hr) * p.chunks_per_seq + chunk) * 128 + jq;
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) po[nb * 32] = O[nb][r];
+            }
+        }
+        if (c.half == 0 && q0 + jq < NQ) {
+            const long long pidx = qrow * p.chunks_per_seq + chunk;
             p.part_ml[pidx * 2] = m;
             p.part_ml[pidx * 2 + 1] = l;
         }
@@ -407,7 +560,7 @@ __device__ __forceinline__ void accumulate_epilogue(const RematParams& p, const 
     });
 }
 
-constexpr int MODE_ATTENTION = 0, MODE_SCORES = 1, MODE_WEIGHTED_SUM = 2, MODE_ACCUMULATE = 3;
+constexpr int MODE_ATTENTION = 0, MODE_SCORES = 1, MODE_WEIGHTED_SUM = 2, MODE_ACCUMULATE = 3, MODE_PREFILL = 4;
 
 // =====================================================================================
 // coded source (XQuant cache, BITS in {2,3,4})
@@ -769,6 +922,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     if constexpr (MODE == MODE_SCORES) scores_epilogue(p, c, acc);
     else if constexpr (MODE == MODE_WEIGHTED_SUM) weighted_sum_epilogue(p, c, acc);
     else if constexpr (MODE == MODE_ACCUMULATE) accumulate_epilogue(p, c, acc, lds);
+    else if constexpr (MODE == MODE_PREFILL) prefill_epilogue(p, c, acc, lds);
     else attention_epilogue(p, c, acc);
 }
 
@@ -790,6 +944,7 @@ constexpr int LDS_DENSE_STAGE_BYTES = 4096;            // per wave
 constexpr int LDS_DENSE_TOTAL = LDS_DENSE_STAGE_OFF + 8 * LDS_DENSE_STAGE_BYTES;
 static_assert(LDS_DENSE_TOTAL <= LDS_MAX, "dense kernel LDS");
 
+template <bool PREFILL>
 __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams p)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -890,7 +1045,12 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
         });
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing may still be writing this workgroup's LDS
-    attention_epilogue(p, c, acc);
+    if constexpr (PREFILL) {
+        __syncthreads();                                  // ... including the other waves' staging copies
+        prefill_epilogue(p, c, acc, lds);
+    } else {
+        attention_epilogue(p, c, acc);
+    }
 }
 
 // ---- pre-pass of the coded kernel: effective scales e = 2^(bits+14) * scale (1 for a zero scale)
@@ -921,13 +1081,14 @@ constexpr int COMBINE_GROUPS = 8;
 __global__ __launch_bounds__(128 * COMBINE_GROUPS) void combine_kernel(const float* __restrict__ part_o,
                                                                        const float* __restrict__ part_ml,
                                                                        float* __restrict__ out, int Hq,
-                                                                       int chunks_per_seq, BatchI32 len)
+                                                                       int chunks_per_seq, BatchI32 len, int rows_per_seq)
 {
     __shared__ float sm[COMBINE_GROUPS];
     __shared__ float sl[COMBINE_GROUPS];
     __shared__ float so[COMBINE_GROUPS][128];
     const int h = blockIdx.x, b = blockIdx.y, n = threadIdx.x & 127, grp = threadIdx.x >> 7;
-    const int nchunks = (len.v[b] + CHUNK_TOKENS - 1) / CHUNK_TOKENS;
+    // b runs over sequences x rows_per_seq (the queries of a prefill chunk; 1 at decode)
+    const int nchunks = (len.v[b / rows_per_seq] + CHUNK_TOKENS - 1) / CHUNK_TOKENS;
     const long long base = ((long long)b * Hq + h) * chunks_per_seq;
     float m_g = -INFINITY;
     for (int c = grp; c < nchunks; c += COMBINE_GROUPS) m_g = fmaxf(m_g, part_ml[(base + c) * 2]);
@@ -1044,10 +1205,68 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
         if (e != hipSuccess) return e;
         e = launch_coded<MODE_ATTENTION>(bits, G, p, grid, s);
     } else {
-        e = launch_with_lds(remat_attn_dense_kernel, LDS_DENSE_TOTAL, p, grid, s);
+        e = launch_with_lds(remat_attn_dense_kernel<false>, LDS_DENSE_TOTAL, p, grid, s);
     }
     if (e != hipSuccess) return e;
-    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len);
+    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len, 1);
+    return hipGetLastError();
+}
+
+// Causal attention of the T newest tokens of every sequence (chunked prefill): the decode launch
+// with T query rows per sequence in the partial buffers and the matrix-core epilogue.
+size_t remat_prefill_workspace_bytes(int B, int T, int Hq, int max_len, int d, int group, bool coded)
+{
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    const size_t chunks = tiles * (TILE_TOKENS / CHUNK_TOKENS);
+    size_t bytes = (size_t)B * T * Hq * chunks * (128 + 2) * sizeof(float);
+    if (coded) bytes += (size_t)B * tiles * (size_t)(d / group + 1) * TILE_TOKENS * sizeof(uint16_t);
+    return bytes;
+}
+
+hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, const xq_cache_t* xc,
+                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
+                                  const BatchI32& len, int max_len, float* out, void* ws,
+                                  const float* rope, const BatchI32* pos0, hipStream_t s)
+{
+    const int bits = xc ? xc->fmt.bits : 16;
+    const int G = xc ? xc->fmt.group : 128;
+    const WPrepLayout L = make_wprep_layout(d, G, bits, a->n_kv_heads);
+    RematParams p{};
+    p.q = q; p.Tq = T;
+    p.B = B; p.cap = cap; p.Hq = a->n_q_heads; p.Hkv = a->n_kv_heads;
+    p.tiles_per_seq = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    p.chunks_per_seq = p.tiles_per_seq * (TILE_TOKENS / CHUNK_TOKENS);
+    p.scale_log2e = a->softmax_scale * 1.44269504088896340736f;
+    p.len = len;
+    const size_t rows = (size_t)B * T * p.Hq * p.chunks_per_seq;
+    p.part_o = static_cast<float*>(ws);
+    p.part_ml = p.part_o + rows * 128;
+    p.eT = reinterpret_cast<uint16_t*>(p.part_ml + rows * 2);
+    p.codes = xc ? xc->codes : nullptr;
+    p.scale = xc ? xc->scale : nullptr;
+    p.zero = xc ? xc->zero : nullptr;
+    p.acc = acc;
+    p.wprep = static_cast<const uint8_t*>(wprep);
+    p.d = d; p.row_d = d; p.grid_heads = p.Hkv;
+    p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
+    p.ng_row = L.ng;
+    p.head_bytes = (long long)L.head_bytes;
+    p.rope = rope;
+    if (rope) p.pos0 = *pos0;
+    const int grid = p.Hkv * p.B * p.tiles_per_seq;
+    hipError_t e;
+    if (xc) {
+        scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
+            xc->scale, const_cast<uint16_t*>(p.eT), cap, L.ng, L.ng, p.tiles_per_seq, bits, len);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        e = launch_coded<MODE_PREFILL>(bits, G, p, grid, s);
+    } else {
+        e = launch_with_lds(remat_attn_dense_kernel<true>, LDS_DENSE_TOTAL, p, grid, s);
+    }
+    if (e != hipSuccess) return e;
+    combine_kernel<<<dim3(p.Hq, p.B * T), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq,
+                                                                            p.chunks_per_seq, p.len, T);
     return hipGetLastError();
 }
 
@@ -1090,7 +1309,7 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
     p.wprep = static_cast<const uint8_t*>(wprep) + L.total_bytes;
     e = launch_coded<MODE_WEIGHTED_SUM>(bits, G, p, grid, s);
     if (e != hipSuccess) return e;
-    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len);
+    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len, 1);
     return hipGetLastError();
 }
 
