@@ -143,7 +143,18 @@ def main():
         rope = torch.stack([torch.cos(ang), torch.sin(ang)], dim=-1).to(torch.float32).to(dev)
         t_rope = timed(lambda: xq.xq_remat_attn_decode(attn, q, wprep, lens, xcache=cache, out=out, workspace=ws,
                                                        rope_cos_sin=rope), n=10, warm=5)
+        # a chunk of 32 new tokens per sequence attending causally to the same cache (chunked prefill)
+        Tq = 32
+        gen_q = torch.Generator(device=dev).manual_seed(32)
+        q_chunk = torch.randn((w.B, Tq, w.Hq, w.hd), device=dev, generator=gen_q).to(torch.bfloat16)
+        ws_chunk = torch.empty(xq.xq_remat_attn_prefill_workspace_bytes(attn, w.B, Tq, w.L, w.d, w.G), dtype=torch.uint8,
+                               device=dev)
+        out_chunk = torch.empty((w.B, Tq, w.Hq, w.hd), dtype=torch.float32, device=dev)
+        t_chunk = timed(lambda: xq.xq_remat_attn_prefill(attn, q_chunk, wprep, lens, xcache=cache, out=out_chunk,
+                                                         workspace=ws_chunk), n=10, warm=5)
+        del ws_chunk, out_chunk
         extra = {
+            "remat_attn_prefill_chunk32_ms": t_chunk,
             "quantize_bulk": {"workload": "xq_quantize_append T=4096 (whole context), c2 shape", "ms": t_q,
                               "GB/s": q_bytes / t_q / 1e6, "frac_hbm_peak": q_bytes / t_q / 1e6 / PEAK_HBM_GBS},
             "quantize_decode_append_us": t_app * 1e3,
