@@ -293,13 +293,22 @@ __device__ __forceinline__ void attention_epilogue(const RematParams& p, const T
 //       other 16): mask, max, exp2 and sum are per-lane loops plus one exchange between halves;
 //   O[query][n] = P V : A = the softmax weights as they sit in those registers (hi + lo), B = V
 //       read column-wise, for which V is transposed once per tile through the wave's own piece of
-//       LDS (bf16 hi and lo images, [n][32 tokens], rows 72 bytes apart: conflict-free 8-byte
-//       reads); hi*hi + lo*hi + hi*lo, the lo*lo term (2^-16 relative) is dropped.
-// One partial (m, l, o[128]) per (query, head, 32-token chunk), merged by the same combine kernel.
-constexpr int VT_ROW_BYTES = 72;
-constexpr int VT_IMAGE_BYTES = 128 * VT_ROW_BYTES;
+//       LDS (bf16 hi and lo images [n][32 tokens], 64-byte rows whose 8-byte pieces are XOR-swizzled
+//       by the row: conflict-free fragment reads); hi*hi + lo*hi + hi*lo, the lo*lo term (2^-16
+//       relative) is dropped.
+// The eight waves' results are then merged inside the workgroup (maxima and sums exchanged
+// through LDS, the rescaled O blocks summed in fixed wave order through a 32 KB staging area), so
+// that one partial (m, l, o[128]) per (query, head, 256-token tile) goes to memory; the same
+// combine kernel merges the tiles.  LDS: 8 x 16 KB of V images, then the staging area.
+constexpr int VT_IMAGE_BYTES = 128 * 64;
 constexpr int VT_WAVE_BYTES = 2 * VT_IMAGE_BYTES;
-static_assert(8 * VT_WAVE_BYTES <= lds_coded_total(2), "transposed V fits the smallest LDS allocation");
+constexpr int PF_STAGE_OFF = 8 * VT_WAVE_BYTES;
+constexpr int PF_STAGE_BYTES = 8 * 16 * 64 * 4;        // [wave][register][lane] fp32 of one 32-column block
+constexpr int LDS_PREFILL_TOTAL = PF_STAGE_OFF + PF_STAGE_BYTES;
+static_assert(LDS_PREFILL_TOTAL <= LDS_MAX, "prefill epilogue LDS");
+
+// byte offset of the 8-byte piece (4 tokens) `piece` of row n inside a V image
+__device__ __forceinline__ int vt_offset(int n, int piece) { return n * 64 + ((piece ^ ((n >> 2) & 7)) << 3); }
 
 __device__ __forceinline__ void split_bf16x8(const float (&v)[8], uint4& hi, uint4& lo)
 {
@@ -319,115 +328,156 @@ __device__ __forceinline__ f32x16 mfma_bf16(const uint4& a, const uint4& b, cons
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// Called by all eight waves of the workgroup (it contains workgroup barriers); the LDS must not be
+// read or written by anything else any more.
 __device__ __forceinline__ void prefill_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8], uint8_t* lds)
 {
     const int tok0 = c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS;
-    if (tok0 >= c.len) return;                                             // wave-uniform
-    if (p.rope) rope_rotate(p, c, acc);
+    const bool active = tok0 < c.len;                                      // wave-uniform: chunk not entirely past len
     uint8_t* vt = lds + c.wave * VT_WAVE_BYTES;
-    // V^T images: element i of block 4 + nb is V[token tl][n], n = 32 nb + 8 (i/4) + 4 half + i%4
-#pragma unroll
-    for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int n = nb * 32 + (i >> 2) * 8 + c.half * 4 + (i & 3);
-            const float v = acc[4 + nb][i];
-            const uint32_t h = f32_to_bf16_rne(v);
-            *reinterpret_cast<uint16_t*>(vt + n * VT_ROW_BYTES + c.tl * 2) = (uint16_t)h;
-            *reinterpret_cast<uint16_t*>(vt + VT_IMAGE_BYTES + n * VT_ROW_BYTES + c.tl * 2) =
-                (uint16_t)f32_to_bf16_rne(v - bf16_bits_to_f32(h));
-        }
-    // K fragments: k-step ks covers columns [16 ks, 16 ks + 16); this lane's 8 of them are
-    // 16 ks + 4 half + [0, 4) and 16 ks + 8 + 4 half + [0, 4)
     uint4 khi[8], klo[8];
+    if (active) {
+        if (p.rope) rope_rotate(p, c, acc);
+        // V^T images: element i of block 4 + nb is V[token tl][n], n = 32 nb + 8 (i/4) + 4 half + i%4
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        float v[8];
+        for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = acc[ks >> 1][(ks & 1) * 8 + k];
-        split_bf16x8(v, khi[ks], klo[ks]);
+            for (int i = 0; i < 16; ++i) {
+                const int n = nb * 32 + (i >> 2) * 8 + c.half * 4 + (i & 3);
+                const float v = acc[4 + nb][i];
+                const uint32_t h = f32_to_bf16_rne(v);
+                uint8_t* dst = vt + vt_offset(n, c.tl >> 2) + (c.tl & 3) * 2;
+                *reinterpret_cast<uint16_t*>(dst) = (uint16_t)h;
+                *reinterpret_cast<uint16_t*>(dst + VT_IMAGE_BYTES) = (uint16_t)f32_to_bf16_rne(v - bf16_bits_to_f32(h));
+            }
+        // K fragments: k-step ks covers columns [16 ks, 16 ks + 16); this lane's 8 of them are
+        // 16 ks + 4 half + [0, 4) and 16 ks + 8 + 4 half + [0, 4)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            float v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = acc[ks >> 1][(ks & 1) * 8 + k];
+            split_bf16x8(v, khi[ks], klo[ks]);
+        }
     }
     __builtin_amdgcn_wave_barrier();
 
     const int gq = p.Hq / p.Hkv, NQ = p.Tq * gq;
-    const int chunk = c.tile * (TILE_TOKENS / CHUNK_TOKENS) + c.wave;
     const int jq = c.tl;
+    float* mbuf = reinterpret_cast<float*>(lds + PF_STAGE_OFF);            // [wave][32 queries]
+    float* lbuf = mbuf + 8 * 32;
+    float* stage = reinterpret_cast<float*>(lds + PF_STAGE_OFF);           // [wave][16][64]
     for (int q0 = 0; q0 < NQ; q0 += 32) {
         // this lane's query row of the group (rows past NQ repeat the last one and are not stored)
         const int qi = min(q0 + jq, NQ - 1);
         const int tq = qi / gq, hq = c.hk * gq + (qi - tq * gq);
         const long long qrow = ((long long)c.b * p.Tq + tq) * p.Hq + hq;
-        const uint16_t* qv = p.q + qrow * 128 + c.half * 4;
-        f32x16 S;
+        float m = -INFINITY, l = 0.0f;
+        float pr[16];
+        if (active) {
+            const uint16_t* qv = p.q + qrow * 128 + c.half * 4;
+            f32x16 S;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) S[i] = 0.0f;
+            for (int i = 0; i < 16; ++i) S[i] = 0.0f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const uint2 a = *reinterpret_cast<const uint2*>(qv + 16 * ks);
-            const uint2 b = *reinterpret_cast<const uint2*>(qv + 16 * ks + 8);
-            const uint4 qf = make_uint4(a.x, a.y, b.x, b.y);
-            S = mfma_bf16(khi[ks], qf, S);
-            S = mfma_bf16(klo[ks], qf, S);
+            for (int ks = 0; ks < 8; ++ks) {
+                const uint2 a = *reinterpret_cast<const uint2*>(qv + 16 * ks);
+                const uint2 b = *reinterpret_cast<const uint2*>(qv + 16 * ks + 8);
+                const uint4 qf = make_uint4(a.x, a.y, b.x, b.y);
+                S = mfma_bf16(khi[ks], qf, S);
+                S = mfma_bf16(klo[ks], qf, S);
+            }
+            // register r <-> token tok0 + 8 (r/4) + 4 half + r%4; visible up to the query's own row
+            const int limit = c.len - p.Tq + tq - tok0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rel = (r >> 2) * 8 + c.half * 4 + (r & 3);
+                S[r] = rel <= limit ? S[r] * p.scale_log2e : -INFINITY;
+                m = fmaxf(m, S[r]);
+            }
+            m = fmaxf(m, __shfl_xor(m, 32));
+            const float mu = m == -INFINITY ? 0.0f : m;                    // nothing visible: all weights 0
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                pr[r] = __builtin_amdgcn_exp2f(S[r] - mu);
+                l += pr[r];
+            }
+            l += __shfl_xor(l, 32);
         }
-        // register r <-> token tok0 + 8 (r/4) + 4 half + r%4; visible up to the query's own row
-        const int limit = c.len - p.Tq + tq - tok0;
-        float m = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int rel = (r >> 2) * 8 + c.half * 4 + (r & 3);
-            S[r] = rel <= limit ? S[r] * p.scale_log2e : -INFINITY;
-            m = fmaxf(m, S[r]);
+        // maxima and sums of the eight chunks -> the tile's maximum M, this wave's factor 2^(m - M)
+        if (c.half == 0) {
+            mbuf[c.wave * 32 + jq] = m;
+            lbuf[c.wave * 32 + jq] = l;
         }
-        m = fmaxf(m, __shfl_xor(m, 32));
-        const float mu = m == -INFINITY ? 0.0f : m;                        // nothing visible: all weights 0
-        float pr[16], l = 0.0f;
+        __syncthreads();
+        float M = -INFINITY;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            pr[r] = __builtin_amdgcn_exp2f(S[r] - mu);
-            l += pr[r];
+        for (int w = 0; w < 8; ++w) M = fmaxf(M, mbuf[w * 32 + jq]);
+        const float Mu = M == -INFINITY ? 0.0f : M;
+        float Lt = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) Lt = __builtin_fmaf(lbuf[w * 32 + jq], __builtin_amdgcn_exp2f(mbuf[w * 32 + jq] - Mu), Lt);
+        const float f = __builtin_amdgcn_exp2f(m - Mu);                    // per lane-query
+        __syncthreads();                                                   // mbuf / lbuf are reused as staging
+        if (c.wave == 0 && c.half == 0 && q0 + jq < NQ) {
+            const long long pidx = qrow * p.chunks_per_seq + c.tile;
+            p.part_ml[pidx * 2] = M;
+            p.part_ml[pidx * 2 + 1] = Lt;
         }
-        l += __shfl_xor(l, 32);
         uint4 phi[2], plo[2];
-#pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2) {
-            float v[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = pr[k2 * 8 + k];
-            split_bf16x8(v, phi[k2], plo[k2]);
-        }
-        f32x16 O[4];
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) O[nb][i] = 0.0f;
+        float fr[16];                                                      // the factor of register r's query
+        if (active) {
 #pragma unroll
             for (int k2 = 0; k2 < 2; ++k2) {
-                // column n = 32 nb + jq of V, tokens 16 k2 + 4 half + [0, 4) and 16 k2 + 8 + 4 half + [0, 4)
-                const uint8_t* vp = vt + (nb * 32 + jq) * VT_ROW_BYTES + (16 * k2 + 4 * c.half) * 2;
-                const uint2 h0 = *reinterpret_cast<const uint2*>(vp), h1 = *reinterpret_cast<const uint2*>(vp + 16);
-                const uint2 l0 = *reinterpret_cast<const uint2*>(vp + VT_IMAGE_BYTES);
-                const uint2 l1 = *reinterpret_cast<const uint2*>(vp + VT_IMAGE_BYTES + 16);
-                const uint4 vh = make_uint4(h0.x, h0.y, h1.x, h1.y), vl = make_uint4(l0.x, l0.y, l1.x, l1.y);
-                O[nb] = mfma_bf16(plo[k2], vh, O[nb]);
-                O[nb] = mfma_bf16(phi[k2], vl, O[nb]);
-                O[nb] = mfma_bf16(phi[k2], vh, O[nb]);
-            }
-        }
-        // O: lane = column 32 nb + jq, register r <-> query q0 + 8 (r/4) + 4 half + r%4
+                float v[8];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int qr = q0 + (r >> 2) * 8 + c.half * 4 + (r & 3);
-            if (qr < NQ) {
-                const int tr = qr / gq, hr = c.hk * gq + (qr - tr * gq);
-                float* po = p.part_o + ((((long long)c.b * p.Tq + tr) * p.Hq + hr) * p.chunks_per_seq + chunk) * 128 + jq;
-#pragma unroll
-                for (int nb = 0; nb < 4; ++nb) po[nb * 32] = O[nb][r];
+                for (int k = 0; k < 8; ++k) v[k] = pr[k2 * 8 + k];
+                split_bf16x8(v, phi[k2], plo[k2]);
             }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) fr[r] = __shfl(f, (r >> 2) * 8 + c.half * 4 + (r & 3));
         }
-        if (c.half == 0 && q0 + jq < NQ) {
-            const long long pidx = qrow * p.chunks_per_seq + chunk;
-            p.part_ml[pidx * 2] = m;
-            p.part_ml[pidx * 2 + 1] = l;
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            f32x16 O;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[i] = 0.0f;
+            if (active) {
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) {
+                    // column n = 32 nb + jq of V, tokens 16 k2 + 4 half + [0, 4) and 16 k2 + 8 + 4 half + [0, 4)
+                    const int n = nb * 32 + jq;
+                    const uint8_t* v0 = vt + vt_offset(n, 4 * k2 + c.half);
+                    const uint8_t* v1 = vt + vt_offset(n, 4 * k2 + c.half + 2);
+                    const uint2 h0 = *reinterpret_cast<const uint2*>(v0), h1 = *reinterpret_cast<const uint2*>(v1);
+                    const uint2 l0 = *reinterpret_cast<const uint2*>(v0 + VT_IMAGE_BYTES);
+                    const uint2 l1 = *reinterpret_cast<const uint2*>(v1 + VT_IMAGE_BYTES);
+                    const uint4 vh = make_uint4(h0.x, h0.y, h1.x, h1.y), vl = make_uint4(l0.x, l0.y, l1.x, l1.y);
+                    O = mfma_bf16(plo[k2], vh, O);
+                    O = mfma_bf16(phi[k2], vl, O);
+                    O = mfma_bf16(phi[k2], vh, O);
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) O[r] *= fr[r];
+            }
+            // O: lane = column 32 nb + jq, register r <-> query q0 + 8 (r/4) + 4 half + r%4.
+            // Sum over the waves in fixed order; wave w reduces and stores registers 2 w, 2 w + 1.
+#pragma unroll
+            for (int r = 0; r < 16; ++r) stage[(c.wave * 16 + r) * 64 + c.lane] = O[r];
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int r = 2 * c.wave + k;
+                float sum = stage[r * 64 + c.lane];
+#pragma unroll
+                for (int w = 1; w < 8; ++w) sum += stage[(w * 16 + r) * 64 + c.lane];
+                const int qr = q0 + (r >> 2) * 8 + c.half * 4 + (r & 3);
+                if (qr < NQ) {
+                    const int tr = qr / gq, hr = c.hk * gq + (qr - tr * gq);
+                    p.part_o[((((long long)c.b * p.Tq + tr) * p.Hq + hr) * p.chunks_per_seq + c.tile) * 128 + nb * 32 + jq] = sum;
+                }
+            }
+            __syncthreads();
         }
     }
 }
@@ -1081,14 +1131,15 @@ constexpr int COMBINE_GROUPS = 8;
 __global__ __launch_bounds__(128 * COMBINE_GROUPS) void combine_kernel(const float* __restrict__ part_o,
                                                                        const float* __restrict__ part_ml,
                                                                        float* __restrict__ out, int Hq,
-                                                                       int chunks_per_seq, BatchI32 len, int rows_per_seq)
+                                                                       int chunks_per_seq, BatchI32 len, int rows_per_seq,
+                                                                       int chunk_tokens)
 {
     __shared__ float sm[COMBINE_GROUPS];
     __shared__ float sl[COMBINE_GROUPS];
     __shared__ float so[COMBINE_GROUPS][128];
     const int h = blockIdx.x, b = blockIdx.y, n = threadIdx.x & 127, grp = threadIdx.x >> 7;
     // b runs over sequences x rows_per_seq (the queries of a prefill chunk; 1 at decode)
-    const int nchunks = (len.v[b / rows_per_seq] + CHUNK_TOKENS - 1) / CHUNK_TOKENS;
+    const int nchunks = (len.v[b / rows_per_seq] + chunk_tokens - 1) / chunk_tokens;
     const long long base = ((long long)b * Hq + h) * chunks_per_seq;
     float m_g = -INFINITY;
     for (int c = grp; c < nchunks; c += COMBINE_GROUPS) m_g = fmaxf(m_g, part_ml[(base + c) * 2]);
@@ -1145,16 +1196,23 @@ size_t remat_latent_workspace_bytes(int B, int Hq, int max_len, int r, int group
            (size_t)B * Hq * tiles * TILE_TOKENS * sizeof(float);
 }
 
+// the prefill epilogue lays its own images over the whole LDS once the contraction is done
+template <int MODE>
+constexpr int lds_for_mode(int bits)
+{
+    return MODE == MODE_PREFILL && LDS_PREFILL_TOTAL > lds_coded_total(bits) ? LDS_PREFILL_TOTAL : lds_coded_total(bits);
+}
+
 template <int MODE>
 static hipError_t launch_coded(int bits, int G, const RematParams& p, int grid, hipStream_t s)
 {
     switch (bits * 1000 + G) {
-        case 2064: return launch_with_lds(remat_attn_coded_kernel<2, 64, MODE>, lds_coded_total(2), p, grid, s);
-        case 2128: return launch_with_lds(remat_attn_coded_kernel<2, 128, MODE>, lds_coded_total(2), p, grid, s);
-        case 3064: return launch_with_lds(remat_attn_coded_kernel<3, 64, MODE>, lds_coded_total(3), p, grid, s);
-        case 3128: return launch_with_lds(remat_attn_coded_kernel<3, 128, MODE>, lds_coded_total(3), p, grid, s);
-        case 4064: return launch_with_lds(remat_attn_coded_kernel<4, 64, MODE>, lds_coded_total(4), p, grid, s);
-        case 4128: return launch_with_lds(remat_attn_coded_kernel<4, 128, MODE>, lds_coded_total(4), p, grid, s);
+        case 2064: return launch_with_lds(remat_attn_coded_kernel<2, 64, MODE>, lds_for_mode<MODE>(2), p, grid, s);
+        case 2128: return launch_with_lds(remat_attn_coded_kernel<2, 128, MODE>, lds_for_mode<MODE>(2), p, grid, s);
+        case 3064: return launch_with_lds(remat_attn_coded_kernel<3, 64, MODE>, lds_for_mode<MODE>(3), p, grid, s);
+        case 3128: return launch_with_lds(remat_attn_coded_kernel<3, 128, MODE>, lds_for_mode<MODE>(3), p, grid, s);
+        case 4064: return launch_with_lds(remat_attn_coded_kernel<4, 64, MODE>, lds_for_mode<MODE>(4), p, grid, s);
+        case 4128: return launch_with_lds(remat_attn_coded_kernel<4, 128, MODE>, lds_for_mode<MODE>(4), p, grid, s);
     }
     return hipErrorInvalidValue;
 }
@@ -1172,11 +1230,22 @@ static void fill_common(RematParams& p, const xq_attn_t* a, const uint16_t* q, i
     p.part_ml = p.part_o + (size_t)B * p.Hq * p.chunks_per_seq * 128;
 }
 
+hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, const xq_cache_t* xc,
+                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
+                                  const BatchI32& len, int max_len, float* out, void* ws,
+                                  const float* rope, const BatchI32* pos0, hipStream_t s);
+
+// query heads per KV head from which the decode step goes through the matrix-core epilogue (the
+// per-query-head vector epilogue runs that many times per tile; measured break-even is about 4)
+constexpr int DECODE_MFMA_EPILOGUE_MIN_GROUP = 4;
+
 hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
                                  const BatchI32& len, int max_len, float* out, void* ws,
                                  const float* rope, const BatchI32* pos0, hipStream_t s)
 {
+    if (a->n_q_heads / a->n_kv_heads >= DECODE_MFMA_EPILOGUE_MIN_GROUP)     // same layouts and workspace at T = 1
+        return run_remat_attn_prefill(a, q, 1, xc, acc, B, cap, d, wprep, len, max_len, out, ws, rope, pos0, s);
     const int bits = xc ? xc->fmt.bits : 16;
     const int G = xc ? xc->fmt.group : 128;
     const WPrepLayout L = make_wprep_layout(d, G, bits, a->n_kv_heads);
@@ -1208,7 +1277,7 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
         e = launch_with_lds(remat_attn_dense_kernel<false>, LDS_DENSE_TOTAL, p, grid, s);
     }
     if (e != hipSuccess) return e;
-    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len, 1);
+    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len, 1, CHUNK_TOKENS);
     return hipGetLastError();
 }
 
@@ -1217,8 +1286,7 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
 size_t remat_prefill_workspace_bytes(int B, int T, int Hq, int max_len, int d, int group, bool coded)
 {
     const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
-    const size_t chunks = tiles * (TILE_TOKENS / CHUNK_TOKENS);
-    size_t bytes = (size_t)B * T * Hq * chunks * (128 + 2) * sizeof(float);
+    size_t bytes = ((size_t)B * T * Hq * tiles + 7) / 8 * 8 * (128 + 2) * sizeof(float);    // one partial per tile
     if (coded) bytes += (size_t)B * tiles * (size_t)(d / group + 1) * TILE_TOKENS * sizeof(uint16_t);
     return bytes;
 }
@@ -1235,10 +1303,10 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
     p.q = q; p.Tq = T;
     p.B = B; p.cap = cap; p.Hq = a->n_q_heads; p.Hkv = a->n_kv_heads;
     p.tiles_per_seq = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
-    p.chunks_per_seq = p.tiles_per_seq * (TILE_TOKENS / CHUNK_TOKENS);
+    p.chunks_per_seq = p.tiles_per_seq;                  // the epilogue merges a tile's chunks: one partial per tile
     p.scale_log2e = a->softmax_scale * 1.44269504088896340736f;
     p.len = len;
-    const size_t rows = (size_t)B * T * p.Hq * p.chunks_per_seq;
+    const size_t rows = ((size_t)B * T * p.Hq * p.tiles_per_seq + 7) / 8 * 8;   // (keeps the scale copy 16-byte aligned)
     p.part_o = static_cast<float*>(ws);
     p.part_ml = p.part_o + rows * 128;
     p.eT = reinterpret_cast<uint16_t*>(p.part_ml + rows * 2);
@@ -1266,7 +1334,7 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
     }
     if (e != hipSuccess) return e;
     combine_kernel<<<dim3(p.Hq, p.B * T), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq,
-                                                                            p.chunks_per_seq, p.len, T);
+                                                                            p.chunks_per_seq, p.len, T, TILE_TOKENS);
     return hipGetLastError();
 }
 
@@ -1309,7 +1377,7 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
     p.wprep = static_cast<const uint8_t*>(wprep) + L.total_bytes;
     e = launch_coded<MODE_WEIGHTED_SUM>(bits, G, p, grid, s);
     if (e != hipSuccess) return e;
-    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len, 1);
+    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len, 1, CHUNK_TOKENS);
     return hipGetLastError();
 }
 
