@@ -100,6 +100,66 @@ def test_argument_errors_are_reported_before_any_launch():
     assert call(out=None) == INVALID
 
 
+def test_argument_errors_of_the_widened_entry_points():
+    """Latent cache, cross-layer GQA and prefill entry points: every host-side check fires before a launch."""
+    lib = xq.load_library()
+    x = C.c_void_p(32)
+    st = C.c_void_p(0)
+    one = (C.c_int32 * 1)(0)
+    INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
+    a = B._Attn(4, 2, 128, 0.1)
+    # prefill: T rows must exist, B*T bounded, workspace checked, size query
+    cache = _cache()
+    pre = lambda T, ln, wsb=1 << 30, xc=cache: lib.xq_remat_attn_prefill(
+        C.byref(a), x, T, C.byref(xc), None, 1, 8, 256, x, (C.c_int32 * 1)(ln), None, 0, None, x, x, wsb, st)
+    assert pre(0, 8) == INVALID
+    assert pre(5, 4) == INVALID                         # fewer rows than queries
+    assert pre(2, 9) == INVALID                         # longer than the cache
+    assert pre(2, 8, wsb=64) == WORKSPACE
+    assert pre(2, 8, xc=_cache(bits=8)) == UNSUPPORTED
+    assert lib.xq_remat_attn_prefill(C.byref(a), x, 2, C.byref(cache), None, 1, 8, 256, x, (C.c_int32 * 1)(8), x, 4,
+                                     None, x, x, 1 << 30, st) == INVALID        # table without positions
+    at = xq.XQAttn(4, 2, 128, 0.1)
+    assert xq.xq_remat_attn_prefill_workspace_bytes(at, 2, 3, 257, 256, 0) == 2 * 3 * 4 * 2 * 130 * 4
+    assert xq.xq_remat_attn_prefill_workspace_bytes(at, 2, 0, 257, 256, 0) == 0
+    # latent projection and its cross-layer variant
+    assert lib.xq_latent_project(x, x, 4, 200, 64, x, st) == UNSUPPORTED
+    assert lib.xq_latent_project(x, x, -1, 256, 64, x, st) == INVALID
+    assert lib.xq_latent_project(None, x, 0, 256, 64, x, st) == 0               # no rows: nothing is read
+    dp = lambda **kw: lib.xq_cl_latent_delta_project(*[dict(dict(x=x, acc=x, ut=x, B=1, T=1, cap=8, start=one, d=256,
+                                                                 n=64, out=x, st=st), **kw)[k]
+                                                       for k in ("x", "acc", "ut", "B", "T", "cap", "start", "d", "n", "out", "st")])
+    assert dp(acc=None) == INVALID
+    assert dp(start=(C.c_int32 * 1)(8)) == INVALID      # start + T > cap
+    assert dp(d=200) == UNSUPPORTED
+    assert dp(n=48) == UNSUPPORTED
+    assert dp(T=0, x=None) == 0
+    # up-projection stream and accumulate
+    assert xq.xq_prepared_upproject_bytes(4096, 2048, 64, 2) > 2048 * 4096 * 2
+    assert xq.xq_prepared_upproject_bytes(4096 + 128, 2048, 64, 2) == 0         # d not a multiple of 256
+    assert xq.xq_prepared_upproject_bytes(4096, 2048, 64, 16) == 0
+    assert lib.xq_prepare_upproject(512, 256, 128, 3, x, x, 16, st) == WORKSPACE
+    assert lib.xq_prepare_upproject(512, 256, 128, 3, None, x, 1 << 30, st) == INVALID
+    lat = _cache(d=256, group=128, bits=3)
+    acc_lat = lambda ln, d=512, ws=x, wsb=1 << 30: lib.xq_cl_accumulate_latent(x, C.byref(lat), d, x, (C.c_int32 * 1)(ln),
+                                                                                ws, wsb, st)
+    assert acc_lat(9) == INVALID
+    assert acc_lat(0) == 0                              # nothing to do
+    assert acc_lat(8, d=384) == UNSUPPORTED
+    assert acc_lat(8, wsb=16) == WORKSPACE
+    assert acc_lat(8, ws=None) == INVALID
+    assert xq.xq_cl_accumulate_latent_workspace_bytes(2, 300, 256, 128) == 2 * 2 * 3 * 256 * 2
+    # latent attention
+    la = B._Attn(4, 2, 128, 0.1)
+    lc = _cache(d=512, group=128, bits=3)
+    lat_call = lambda attn=la, c=lc, ln=8, wsb=1 << 30: lib.xq_remat_attn_decode_latent(
+        C.byref(attn), x, C.byref(c), x, (C.c_int32 * 1)(ln), x, x, wsb, st)
+    assert lat_call(ln=0) == INVALID
+    assert lat_call(wsb=16) == WORKSPACE
+    assert lat_call(attn=B._Attn(3, 3, 128, 0.1), c=_cache(d=768, group=128, bits=3)) == UNSUPPORTED   # odd number of KV heads
+    assert lat_call(c=_cache(d=384, group=128, bits=3)) == UNSUPPORTED          # latent width not a multiple of 256
+
+
 def test_binding_has_no_cpu_fallback():
     src = open(os.path.join(ROOT, "paper_2508_10395_amd", "binding.py")).read()
     assert "oracle" not in src
