@@ -44,6 +44,20 @@ __device__ __forceinline__ void group_minmax(float& mn, float& mx)
     }
 }
 
+// Rounding and packing without a convert per element: for 0 <= y < 2^22, y + 2^23 (one fp32 add,
+// round-to-nearest-even) is the float whose bit pattern is 0x4B000000 + rint(y); clamping that
+// float to [2^23, 2^23 + qmax] clamps the code (the bounds are integers, so rounding first and
+// clamping second gives the same code).  The packed word is then a sum of shifted bit patterns,
+// and the shifted constants are taken out once per word (arithmetic modulo 2^32).
+constexpr float ROUND_MAGIC = 8388608.0f;
+constexpr uint32_t ROUND_MAGIC_BITS = 0x4B000000u;
+constexpr uint32_t magic_sum(int n, int bits)
+{
+    uint32_t c = 0;
+    for (int k = 0; k < n; ++k) c += ROUND_MAGIC_BITS << (bits * k);
+    return c;
+}
+
 struct __attribute__((packed, aligned(4))) Dword2 {
     uint32_t a, b;
 };
@@ -111,13 +125,12 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(
         const float sf = bf16_bits_to_f32(sb);
         const GroupRecip r = make_recip(sf);
 
-        uint32_t q[16];
+        uint32_t q[16];                                   // 0x4B000000 + code
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             const float n = v[k] - zf;
-            float y = __builtin_fmaf(n, r.rh, n * r.rl);
-            y = fminf(fmaxf(y, 0.0f), QMAX);
-            q[k] = (uint32_t)__builtin_rintf(y);
+            const float y = __builtin_fmaf(n, r.rh, n * r.rl);
+            q[k] = __float_as_uint(__builtin_amdgcn_fmed3f(y + ROUND_MAGIC, ROUND_MAGIC, ROUND_MAGIC + QMAX));
         }
         if (live && (pi % LANES) == 0) {
             srow[pi / LANES] = (uint16_t)sb;
@@ -125,26 +138,29 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(
         }
 
         if constexpr (BITS == 8) {
+            constexpr uint32_t C = magic_sum(4, 8);
             uint4 w;
-            w.x = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
-            w.y = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
-            w.z = q[8] | (q[9] << 8) | (q[10] << 16) | (q[11] << 24);
-            w.w = q[12] | (q[13] << 8) | (q[14] << 16) | (q[15] << 24);
+            w.x = q[0] + (q[1] << 8) + (q[2] << 16) + (q[3] << 24) - C;
+            w.y = q[4] + (q[5] << 8) + (q[6] << 16) + (q[7] << 24) - C;
+            w.z = q[8] + (q[9] << 8) + (q[10] << 16) + (q[11] << 24) - C;
+            w.w = q[12] + (q[13] << 8) + (q[14] << 16) + (q[15] << 24) - C;
             if (live) reinterpret_cast<uint4*>(rowp)[pi] = w;
         } else if constexpr (BITS == 4) {
-            uint2 w = {0u, 0u};
+            constexpr uint32_t C = magic_sum(8, 4);
+            uint2 w = {0u - C, 0u - C};
 #pragma unroll
-            for (int k = 0; k < 8; ++k) { w.x |= q[k] << (4 * k); w.y |= q[8 + k] << (4 * k); }
+            for (int k = 0; k < 8; ++k) { w.x += q[k] << (4 * k); w.y += q[8 + k] << (4 * k); }
             if (live) reinterpret_cast<uint2*>(rowp)[pi] = w;
         } else if constexpr (BITS == 2) {
-            uint32_t w = 0;
+            uint32_t w = 0u - magic_sum(16, 2);
 #pragma unroll
-            for (int k = 0; k < 16; ++k) w |= q[k] << (2 * k);
+            for (int k = 0; k < 16; ++k) w += q[k] << (2 * k);
             if (live) reinterpret_cast<uint32_t*>(rowp)[pi] = w;
         } else {   // 3 bits: 48 bits per lane, two lanes make three dwords
-            uint32_t w0 = 0, w1 = 0;
+            constexpr uint32_t C = magic_sum(8, 3);
+            uint32_t w0 = 0u - C, w1 = 0u - C;                           // 24 bits of codes each
 #pragma unroll
-            for (int k = 0; k < 8; ++k) { w0 |= q[k] << (3 * k); w1 |= q[8 + k] << (3 * k); }
+            for (int k = 0; k < 8; ++k) { w0 += q[k] << (3 * k); w1 += q[8 + k] << (3 * k); }
             const uint32_t lo = w0 | (w1 << 24), hi = w1 >> 8;          // bits 0-31, 32-47
             const uint32_t lo_other = dpp_u32<DPP_QUAD_XOR1>(lo);
             uint8_t* pair = rowp + 12 * (pi >> 1);
