@@ -79,14 +79,13 @@ constexpr int lds_coded_total(int bits) { return lds_scales_off(bits) + 3 * LDS_
 
 struct RematParams {
     const uint16_t* q;       // [B][Hq][128]; prefill: [B][Tq][Hq][128]
-    int Tq;                  // prefill: new tokens (queries) per sequence; partials are then [B][Tq][Hq][chunks]
-    const uint8_t* codes;    // coded source
-    const uint16_t* scale;
+    int Tq;                  // prefill: new tokens (queries) per sequence
+    const uint8_t* codes;    // coded source (its scales reach the kernel through eT)
     const uint16_t* zero;
     const uint16_t* acc;     // dense source
     const uint8_t* wprep;
     const uint16_t* eT;      // coded source: effective scales [B][tiles][ng (+1 pad)][256], bf16
-    float* part_o;           // [B][Hq][chunks_per_seq][128]
+    float* part_o;           // [B][Hq][chunks_per_seq][128]  (prefill: [B][Tq][Hq][tiles_per_seq][128])
     float* part_ml;          // [B][Hq][chunks_per_seq][2]
     int B, cap, d, Hq, Hkv;
     int row_d, ng_row;       // coded source: channels / groups per cache row (>= d, ng when a sub-range is contracted)
@@ -616,8 +615,11 @@ constexpr int MODE_ATTENTION = 0, MODE_SCORES = 1, MODE_WEIGHTED_SUM = 2, MODE_A
 // coded source (XQuant cache, BITS in {2,3,4})
 // =====================================================================================
 // MODE selects what happens to the 256 rematerialised columns of the wave's 32 tokens: decode
-// attention ([K_h | V_h]), or one of the two passes over a latent cache, where the columns are the
-// keys (pass 1) or the values (pass 2) of a PAIR of KV heads.
+// attention ([K_h | V_h]) with the per-query-head vector epilogue; one of the two passes over a
+// latent cache, where the columns are the keys (pass 1) or the values (pass 2) of a PAIR of KV
+// heads; the up-projection of cross-layer latent deltas into the bf16 accumulator (the columns are
+// 256 hidden channels); or attention for many (query, head) rows per KV head through the
+// matrix-core epilogue (prefill chunks, and decode when a KV head serves several query heads).
 template <int BITS, int G, int MODE>
 __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams p)
 {
@@ -1252,7 +1254,6 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
     RematParams p{};
     fill_common(p, a, q, B, cap, len, max_len, ws);
     p.codes = xc ? xc->codes : nullptr;
-    p.scale = xc ? xc->scale : nullptr;
     p.zero = xc ? xc->zero : nullptr;
     p.acc = acc;
     p.wprep = static_cast<const uint8_t*>(wprep);
@@ -1311,7 +1312,6 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
     p.part_ml = p.part_o + rows * 128;
     p.eT = reinterpret_cast<uint16_t*>(p.part_ml + rows * 2);
     p.codes = xc ? xc->codes : nullptr;
-    p.scale = xc ? xc->scale : nullptr;
     p.zero = xc ? xc->zero : nullptr;
     p.acc = acc;
     p.wprep = static_cast<const uint8_t*>(wprep);
@@ -1368,12 +1368,12 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // pass 1: keys
-    p.codes = xc->codes; p.scale = xc->scale; p.zero = xc->zero; p.eT = eT_k;
+    p.codes = xc->codes; p.zero = xc->zero; p.eT = eT_k;
     p.wprep = static_cast<const uint8_t*>(wprep);
     e = launch_coded<MODE_SCORES>(bits, G, p, grid, s);
     if (e != hipSuccess) return e;
     // pass 2: values
-    p.codes = xc->codes + (size_t)r * bits / 8; p.scale = xc->scale + L.ng; p.zero = xc->zero + L.ng; p.eT = eT_v;
+    p.codes = xc->codes + (size_t)r * bits / 8; p.zero = xc->zero + L.ng; p.eT = eT_v;
     p.wprep = static_cast<const uint8_t*>(wprep) + L.total_bytes;
     e = launch_coded<MODE_WEIGHTED_SUM>(bits, G, p, grid, s);
     if (e != hipSuccess) return e;
@@ -1401,7 +1401,7 @@ hipError_t run_cl_accumulate_latent(uint16_t* acc, const xq_cache_t* xc, int d, 
     p.tiles_per_seq = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
     p.chunks_per_seq = p.tiles_per_seq * (TILE_TOKENS / CHUNK_TOKENS);
     p.len = len;
-    p.codes = xc->codes; p.scale = xc->scale; p.zero = xc->zero;
+    p.codes = xc->codes; p.zero = xc->zero;
     p.wprep = static_cast<const uint8_t*>(uprep);
     p.d = n_lat; p.row_d = n_lat;
     p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
