@@ -23,6 +23,17 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Two fp32 -> one dword of two bf16 (a in the low half), round-to-nearest-even, as a single
+// v_cvt_pk_bf16_f32.  Used where results are compared by tolerance; the bit-exact paths keep the
+// integer form above.
+typedef __bf16 xq_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float xq_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2_rne(float a, float b)
+{
+    const xq_f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, xq_bf16x2));
+}
+
 // DPP lane exchange inside a row of 16 lanes.
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v)

@@ -68,9 +68,8 @@ __global__ __launch_bounds__(512) void latent_project_kernel(const uint16_t* __r
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float d0 = xf[2 * i] - sf[2 * i], d1 = xf[2 * i + 1] - sf[2 * i + 1];
-                const uint32_t h0 = f32_to_bf16_rne(d0), h1 = f32_to_bf16_rne(d1);
-                hi[i] = h0 | (h1 << 16);
-                lo[i] = f32_to_bf16_rne(d0 - bf16_bits_to_f32(h0)) | (f32_to_bf16_rne(d1 - bf16_bits_to_f32(h1)) << 16);
+                hi[i] = pack_bf16x2_rne(d0, d1);
+                lo[i] = pack_bf16x2_rne(d0 - bf16_lo_to_f32(hi[i]), d1 - bf16_hi_to_f32(hi[i]));
             }
             const uint4 vh = make_uint4(hi[0], hi[1], hi[2], hi[3]), vl = make_uint4(lo[0], lo[1], lo[2], lo[3]);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vl), __builtin_bit_cast(bf16x8, b),

@@ -314,9 +314,8 @@ __device__ __forceinline__ void split_bf16x8(const float (&v)[8], uint4& hi, uin
     uint32_t h[4], l[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const uint32_t h0 = f32_to_bf16_rne(v[2 * i]), h1 = f32_to_bf16_rne(v[2 * i + 1]);
-        h[i] = h0 | (h1 << 16);
-        l[i] = f32_to_bf16_rne(v[2 * i] - bf16_bits_to_f32(h0)) | (f32_to_bf16_rne(v[2 * i + 1] - bf16_bits_to_f32(h1)) << 16);
+        h[i] = pack_bf16x2_rne(v[2 * i], v[2 * i + 1]);
+        l[i] = pack_bf16x2_rne(v[2 * i] - bf16_lo_to_f32(h[i]), v[2 * i + 1] - bf16_hi_to_f32(h[i]));
     }
     hi = make_uint4(h[0], h[1], h[2], h[3]);
     lo = make_uint4(l[0], l[1], l[2], l[3]);
@@ -344,10 +343,10 @@ __device__ __forceinline__ void prefill_epilogue(const RematParams& p, const Til
             for (int i = 0; i < 16; ++i) {
                 const int n = nb * 32 + (i >> 2) * 8 + c.half * 4 + (i & 3);
                 const float v = acc[4 + nb][i];
-                const uint32_t h = f32_to_bf16_rne(v);
+                const uint32_t h = pack_bf16x2_rne(v, 0.0f);
                 uint8_t* dst = vt + vt_offset(n, c.tl >> 2) + (c.tl & 3) * 2;
                 *reinterpret_cast<uint16_t*>(dst) = (uint16_t)h;
-                *reinterpret_cast<uint16_t*>(dst + VT_IMAGE_BYTES) = (uint16_t)f32_to_bf16_rne(v - bf16_bits_to_f32(h));
+                *reinterpret_cast<uint16_t*>(dst + VT_IMAGE_BYTES) = (uint16_t)pack_bf16x2_rne(v - bf16_lo_to_f32(h), 0.0f);
             }
         // K fragments: k-step ks covers columns [16 ks, 16 ks + 16); this lane's 8 of them are
         // 16 ks + 4 half + [0, 4) and 16 ks + 8 + 4 half + [0, 4)
@@ -598,10 +597,10 @@ __device__ __forceinline__ void accumulate_epilogue(const RematParams& p, const 
             if (tok0 + r < c.len) {
                 const uint4 o = old[pb][k];
                 uint4 upd;
-                upd.x = f32_to_bf16_rne(bf16_lo_to_f32(o.x) + lo.x) | (f32_to_bf16_rne(bf16_hi_to_f32(o.x) + lo.y) << 16);
-                upd.y = f32_to_bf16_rne(bf16_lo_to_f32(o.y) + lo.z) | (f32_to_bf16_rne(bf16_hi_to_f32(o.y) + lo.w) << 16);
-                upd.z = f32_to_bf16_rne(bf16_lo_to_f32(o.z) + hi.x) | (f32_to_bf16_rne(bf16_hi_to_f32(o.z) + hi.y) << 16);
-                upd.w = f32_to_bf16_rne(bf16_lo_to_f32(o.w) + hi.z) | (f32_to_bf16_rne(bf16_hi_to_f32(o.w) + hi.w) << 16);
+                upd.x = pack_bf16x2_rne(bf16_lo_to_f32(o.x) + lo.x, bf16_hi_to_f32(o.x) + lo.y);
+                upd.y = pack_bf16x2_rne(bf16_lo_to_f32(o.y) + lo.z, bf16_hi_to_f32(o.y) + lo.w);
+                upd.z = pack_bf16x2_rne(bf16_lo_to_f32(o.z) + hi.x, bf16_hi_to_f32(o.z) + hi.y);
+                upd.w = pack_bf16x2_rne(bf16_lo_to_f32(o.w) + hi.z, bf16_hi_to_f32(o.w) + hi.w);
                 *reinterpret_cast<uint4*>(gbase + (long long)r * p.d_out + pb * 64) = upd;
             }
         }
