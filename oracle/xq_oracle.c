@@ -15,6 +15,9 @@
  *                          channels, one scale and one zero-point per group,
  *                          16 bits each (the normalised cache sizes printed in
  *                          Tables 1 and 4 fix 32 metadata bits per group).
+ *   xqo_quantize_blocks_per_channel / xqo_dequantize_blocks_per_channel
+ *                          the same quantiser with groups along the token axis (one
+ *                          channel over a block of G tokens), Sec. 3.3.1.
  *   xqo_pack_rows /        storage format of the codes: one little-endian bit
  *   xqo_unpack_rows        string per token row (the paper is silent on it).
  *   xqo_dequantize_rows    x^ = code * scale + zero.
@@ -149,6 +152,63 @@ void xqo_quantize_rows(const float *x, int64_t rows, int d, int G, int bits,
                 qg[i] = (uint8_t)rq;
             }
         }
+    }
+}
+
+/*
+ * Per-channel quantisation (Sec. 3.3.1: the setting the paper finds best for X U_k; groups
+ * run along the token axis as in KIVI, cited there): a group is one channel over a block of
+ * G consecutive tokens.  x: [nblocks*G][d] fp32; codes: [nblocks*G][d]; scale, zero:
+ * [nblocks][d] bf16 bit patterns.  The arithmetic of a group is that of xqo_quantize_rows.
+ * (Tokens that do not fill a block stay unquantised: the caller's residual window.)
+ */
+void xqo_quantize_blocks_per_channel(const float *x, int64_t nblocks, int d, int G, int bits,
+                                     uint8_t *codes, uint16_t *scale, uint16_t *zero)
+{
+    const float qmax = (float)((1 << bits) - 1);
+#pragma omp parallel for schedule(static)
+    for (int64_t blk = 0; blk < nblocks; ++blk) {
+        for (int c = 0; c < d; ++c) {
+            const float *x0 = x + blk * (int64_t)G * d + c;           /* token i of the block: x0[i*d] */
+            float mn = x0[0], mx = x0[0];
+            for (int i = 1; i < G; ++i) {
+                float v = x0[(int64_t)i * d];
+                if (v < mn) mn = v;
+                if (v > mx) mx = v;
+            }
+            uint16_t zb = float_to_bf16_bits_rne(mn);
+            if ((zb & 0x7FFFu) == 0) zb = 0;
+            float range = mx - mn;
+            float step = range / qmax;
+            uint16_t sb = float_to_bf16_bits_rne(step);
+            const float zf = bf16_bits_to_float(zb);
+            const float sf = bf16_bits_to_float(sb);
+            scale[blk * d + c] = sb;
+            zero[blk * d + c] = zb;
+            for (int i = 0; i < G; ++i) {
+                uint8_t *q = codes + (blk * G + i) * (int64_t)d + c;
+                if (sf == 0.0f) { *q = 0; continue; }
+                float num = x0[(int64_t)i * d] - zf;
+                float quo = num / sf;
+                float rq = rintf(quo);
+                if (rq < 0.0f) rq = 0.0f;
+                if (rq > qmax) rq = qmax;
+                *q = (uint8_t)rq;
+            }
+        }
+    }
+}
+
+/* x^[t][c] = fma(code[t][c], scale[t/G][c], zero[t/G][c]) in fp32, for rows = nblocks*G tokens */
+void xqo_dequantize_blocks_per_channel(const uint8_t *codes, const uint16_t *scale, const uint16_t *zero,
+                                       int64_t nblocks, int d, int G, float *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < nblocks * G; ++t) {
+        const int64_t blk = t / G;
+        for (int c = 0; c < d; ++c)
+            out[t * d + c] = fmaf((float)codes[t * d + c], bf16_bits_to_float(scale[blk * d + c]),
+                                  bf16_bits_to_float(zero[blk * d + c]));
     }
 }
 

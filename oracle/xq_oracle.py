@@ -64,6 +64,34 @@ def quantize_rows(x_f32, G, bits):
     return codes, scale, zero
 
 
+def quantize_blocks_per_channel(x_f32, G, bits):
+    """Per-channel groups of G consecutive tokens: x [..., nblk*G, d] fp32 -> codes uint8 same shape,
+    scale / zero bf16 bits [..., nblk, d]."""
+    x = _c(x_f32, np.float32)
+    rows, d = x.shape[-2], x.shape[-1]
+    assert rows % G == 0
+    lead = int(np.prod(x.shape[:-2], dtype=np.int64))
+    nblk = lead * (rows // G)
+    codes = np.empty(x.shape, np.uint8)
+    scale = np.empty(x.shape[:-2] + (rows // G, d), np.uint16)
+    zero = np.empty_like(scale)
+    lib().xqo_quantize_blocks_per_channel(_p(x), C.c_int64(nblk), C.c_int(d), C.c_int(G), C.c_int(bits),
+                                          _p(codes), _p(scale), _p(zero))
+    return codes, scale, zero
+
+
+def dequantize_blocks_per_channel(codes, scale, zero, G):
+    codes = _c(codes, np.uint8)
+    scale = _c(scale, np.uint16)
+    zero = _c(zero, np.uint16)
+    rows, d = codes.shape[-2], codes.shape[-1]
+    lead = int(np.prod(codes.shape[:-2], dtype=np.int64))
+    out = np.empty(codes.shape, np.float32)
+    lib().xqo_dequantize_blocks_per_channel(_p(codes), _p(scale), _p(zero), C.c_int64(lead * (rows // G)), C.c_int(d),
+                                            C.c_int(G), _p(out))
+    return out
+
+
 def pack_rows(codes, bits):
     codes = _c(codes, np.uint8)
     d = codes.shape[-1]
@@ -227,6 +255,37 @@ def remat_attn_pairs(*, q_bf16, Wk, Wv, Hq, Hkv, hd, softmax_scale, lens, pairs,
         p0 = _c(np.zeros(len(lens), np.int32) if pos0 is None else np.asarray(pos0, np.int32), np.int32)
         assert int((p0.astype(np.int64) + lens).max()) <= tab.shape[0]
         lib().xqo_remat_attn_pairs_rope(*args, _p(tab), _p(p0), _p(out))
+    return out
+
+
+def remat_attn_pairs_per_channel(*, q_bf16, Wk, Wv, Hq, Hkv, hd, softmax_scale, lens, pairs,
+                                 packed, scale, zero, G, bits, tail_bf16):
+    """Decode attention from a per-channel cache with a residual window (Sec. 3.3.1): of the lens[b]
+    tokens of sequence b the first floor(lens[b]/G)*G are read from the cache (packed [B][cap][d*bits/8],
+    scale / zero [B][cap/G][d]) and the remaining lens[b] % G from rows 0.. of tail_bf16 [B][G][d], which
+    holds them unquantised.  Composition of pinned pieces only: unpack, per-channel dequantise,
+    xqo_remat_head, xqo_attention.  Returns [npairs][hd] fp32."""
+    q = _c(q_bf16, np.uint16)
+    packed = _c(packed, np.uint8)
+    tail = _c(tail_bf16, np.uint16)
+    d = Wk.shape[0]
+    g = Hq // Hkv
+    out = np.empty((len(pairs), hd), np.float32)
+    xhat_cache = {}
+    for i, (b, hq) in enumerate(pairs):
+        if b not in xhat_cache:
+            n = int(lens[b])
+            nblk, rem = n // G, n % G
+            coded = np.empty((0, d), np.float32)
+            if nblk:
+                codes = unpack_rows(packed[b, :nblk * G], d, bits)
+                coded = dequantize_blocks_per_channel(codes, scale[b, :nblk], zero[b, :nblk], G)
+            xhat_cache[b] = np.concatenate([coded, bf16_to_f32(tail[b, :rem])], axis=0)
+        xhat = xhat_cache[b]
+        hk = hq // g
+        K = remat_head(xhat, Wk, hk * hd, hd)
+        V = remat_head(xhat, Wv, hk * hd, hd)
+        out[i] = attention(q[b, hq], K, V, softmax_scale)
     return out
 
 

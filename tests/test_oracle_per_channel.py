@@ -1,0 +1,109 @@
+"""Pins for the oracle's per-channel quantiser (groups of G consecutive tokens per channel,
+Sec. 3.3.1 of arxiv 2508.10395: the paper's best setting for X U_k)."""
+import numpy as np
+
+import xq_inputs as xi
+from oracle import xq_oracle as xo
+
+
+def bf(x):
+    return xi.from_bf16_bits(x)
+
+
+def _x(seed, rows, d):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((rows, d)).astype(np.float32)
+    x[:, 3] *= 40.0                                   # an outlier channel: per-channel groups isolate it
+    return bf(xi.to_bf16_bits(x))
+
+
+def test_per_channel_is_the_per_token_quantiser_on_the_transposed_block():
+    """A group is the same arithmetic whichever axis it runs along: block^T quantised per token
+    with one group per row (the pinned quantiser) must give the same codes, scales, zero-points."""
+    G, d = 64, 96
+    for bits in (2, 3, 4):
+        x = _x(bits, 3 * G, d)
+        codes, scale, zero = xo.quantize_blocks_per_channel(x, G, bits)
+        for blk in range(3):
+            xt = np.ascontiguousarray(x[blk * G:(blk + 1) * G].T)                # [d][G]
+            c2, s2, z2 = xo.quantize_rows(xt, G, bits)
+            assert np.array_equal(codes[blk * G:(blk + 1) * G], c2.T)
+            assert np.array_equal(scale[blk], s2[:, 0]) and np.array_equal(zero[blk], z2[:, 0])
+
+
+def test_exact_grid_and_dequantisation():
+    """Channel c of block b holds min + k*step exactly (representable values): codes are k, and the
+    dequantised block is the input bit for bit."""
+    G, d, bits = 32, 8, 3
+    k = np.random.default_rng(0).integers(0, 8, size=(2 * G, d))
+    k[0], k[1] = 0, 7                                                            # every channel spans the range
+    k[G], k[G + 1] = 0, 7
+    step = 2.0 ** -np.arange(d)                                                  # bf16-exact steps
+    mn = -np.arange(d, dtype=np.float64)
+    x = (mn + k * step).astype(np.float32)
+    codes, scale, zero = xo.quantize_blocks_per_channel(x, G, bits)
+    assert np.array_equal(codes, k.astype(np.uint8))
+    assert np.array_equal(bf(scale)[0], step.astype(np.float32)) and np.array_equal(bf(zero)[1], mn.astype(np.float32))
+    assert np.array_equal(xo.dequantize_blocks_per_channel(codes, scale, zero, G), x)
+
+
+def test_round_trip_bound_and_outlier_isolation():
+    G, d, bits = 128, 64, 4
+    x = _x(9, 2 * G, d)
+    codes, scale, zero = xo.quantize_blocks_per_channel(x, G, bits)
+    xh = xo.dequantize_blocks_per_channel(codes, scale, zero, G)
+    s = np.repeat(bf(scale).astype(np.float64), G, axis=0)
+    z = np.repeat(bf(zero).astype(np.float64), G, axis=0)
+    # half a step, plus what rounding the zero-point and the step to bf16 moves the grid by
+    qmax = 2 ** bits - 1
+    assert np.all(np.abs(xh - x) <= 0.5 * s + np.abs(z) * 2.0 ** -8 + qmax * s * 2.0 ** -8 + 1e-30)
+    # the outlier channel does not spoil its neighbours (it would under per-token groups)
+    err_pc = np.abs(xh - x)[:, :3].mean()
+    ct, st, zt = xo.quantize_rows(x, 64, bits)
+    err_pt = np.abs(xo.dequantize_rows(ct, st, zt, 64) - x)[:, :3].mean()
+    assert err_pc < 0.25 * err_pt
+
+
+def test_dequantisation_is_one_fma_per_element():
+    G, d, bits = 16, 5, 2
+    rng = np.random.default_rng(4)
+    codes = rng.integers(0, 4, size=(G, d)).astype(np.uint8)
+    scale = xi.to_bf16_bits(rng.random((1, d)).astype(np.float32) + 0.1)
+    zero = xi.to_bf16_bits(rng.standard_normal((1, d)).astype(np.float32))
+    got = xo.dequantize_blocks_per_channel(codes, scale, zero, G)
+    exact = codes.astype(np.float64) * bf(scale).astype(np.float64) + bf(zero).astype(np.float64)   # exact in fp64
+    assert np.array_equal(got, exact.astype(np.float32))                        # one rounding
+
+
+def test_attention_from_per_channel_cache_and_residual_window_equals_brute_force():
+    from scipy.special import softmax
+    rng = np.random.default_rng(12)
+    B, L, d, G, bits, Hq, Hkv, hd = 2, 3 * 32 + 9, 256, 32, 4, 4, 2, 128
+    x = xi.to_bf16_bits(rng.standard_normal((B, L, d)).astype(np.float32))
+    wk = xi.to_bf16_bits((rng.standard_normal((d, Hkv * hd)) * d ** -0.5).astype(np.float32))
+    wv = xi.to_bf16_bits((rng.standard_normal((d, Hkv * hd)) * d ** -0.5).astype(np.float32))
+    q = xi.to_bf16_bits(rng.standard_normal((B, Hq, hd)).astype(np.float32))
+    lens = [L, 2 * 32]                                   # one sequence with a window of 9, one with none
+    cap = 4 * 32
+    codes = np.zeros((B, cap, d), np.uint8)
+    scale = np.zeros((B, cap // G, d), np.uint16)
+    zero = np.zeros_like(scale)
+    tail = np.zeros((B, G, d), np.uint16)
+    xhat = []
+    for b in range(B):
+        nblk, rem = lens[b] // G, lens[b] % G
+        c, s, z = xo.quantize_blocks_per_channel(bf(x[b, :nblk * G]), G, bits)
+        codes[b, :nblk * G], scale[b, :nblk], zero[b, :nblk] = c, s, z
+        tail[b, :rem] = x[b, nblk * G:lens[b]]
+        xhat.append(np.concatenate([xo.dequantize_blocks_per_channel(c, s, z, G), bf(x[b, nblk * G:lens[b]])]))
+    pairs = [(b, h) for b in range(B) for h in range(Hq)]
+    got = xo.remat_attn_pairs_per_channel(q_bf16=q, Wk=wk, Wv=wv, Hq=Hq, Hkv=Hkv, hd=hd, softmax_scale=hd ** -0.5,
+                                          lens=lens, pairs=pairs, packed=xo.pack_rows(codes, bits), scale=scale,
+                                          zero=zero, G=G, bits=bits, tail_bf16=tail)
+    for i, (b, hq) in enumerate(pairs):
+        hk = hq // (Hq // Hkv)
+        X = xhat[b].astype(np.float64)
+        K = X @ bf(wk)[:, hk * hd:(hk + 1) * hd].astype(np.float64)
+        V = X @ bf(wv)[:, hk * hd:(hk + 1) * hd].astype(np.float64)
+        ref = softmax(K @ bf(q)[b, hq].astype(np.float64) * hd ** -0.5) @ V
+        assert np.allclose(got[i], ref, rtol=1e-5, atol=1e-6)
