@@ -269,6 +269,26 @@ xq_status_t xq_cl_accumulate_latent(uint16_t *acc_bf16, const xq_cache_t *delta,
                                     const void *uprep, const int32_t *len, void *workspace,
                                     size_t workspace_bytes, void *stream);
 
+/*
+ * Per-channel quantisation (Sec. 3.3.1: the paper's best setting for X U_k; groups along the
+ * token axis with an unquantised residual window, as in KIVI cited there).  A per-channel cache
+ * uses xq_cache_t with
+ *   codes  dev [B][cap][d*bits/8]   rows packed exactly as in a per-token cache
+ *   scale  dev [B][cap/group][d] bf16,  zero likewise: one pair per (block of `group` tokens, channel)
+ *   fmt.group = tokens per block (64 or 128), cap a multiple of it, d a multiple of 128.
+ * Only complete blocks are quantised; the newest len % group tokens of a sequence stay in a bf16
+ * residual window that the caller keeps ([B][group][d]) and hands to the attention call.
+ *
+ * xq_quantize_blocks_per_channel: quantise nblk complete blocks per sequence,
+ *   x_bf16  dev [B][nblk*group][d] bf16
+ *   block0  host [B]: sequence b's blocks block0[b] .. block0[b]+nblk-1 are written
+ *           (block0[b] >= 0, (block0[b]+nblk)*group <= cap)
+ * with the arithmetic of xq_quantize_append per group (min/max, bf16 zero-point and scale, codes
+ * from the stored pair).  nblk = 0 is a no-op.
+ */
+xq_status_t xq_quantize_blocks_per_channel(const xq_cache_t *cache, const uint16_t *x_bf16,
+                                           int32_t nblk, const int32_t *block0, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

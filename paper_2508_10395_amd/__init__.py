@@ -12,4 +12,5 @@ from .binding import (  # noqa: F401
     xq_cl_latent_delta_project, xq_prepared_upproject_bytes, xq_prepare_upproject,
     xq_cl_accumulate_latent_workspace_bytes, xq_cl_accumulate_latent,
     xq_remat_attn_prefill_workspace_bytes, xq_remat_attn_prefill,
+    alloc_cache_per_channel, xq_quantize_blocks_per_channel,
 )

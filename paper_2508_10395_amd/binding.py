@@ -26,6 +26,7 @@ SYMBOLS = [
     "xq_cl_latent_delta_project", "xq_prepared_upproject_bytes", "xq_prepare_upproject",
     "xq_cl_accumulate_latent_workspace_bytes", "xq_cl_accumulate_latent",
     "xq_remat_attn_prefill_workspace_bytes", "xq_remat_attn_prefill",
+    "xq_quantize_blocks_per_channel",
 ]
 
 
@@ -126,6 +127,9 @@ def load_library():
                                           C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_int32),
                                           C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p, C.c_void_p,
                                           C.c_size_t, C.c_void_p]
+    lib.xq_quantize_blocks_per_channel.restype = C.c_int
+    lib.xq_quantize_blocks_per_channel.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_int32, C.POINTER(C.c_int32),
+                                                   C.c_void_p]
     _LIB = lib
     return lib
 
@@ -438,3 +442,22 @@ def xq_remat_attn_prefill(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=No
                                                 _ptr(workspace), workspace.numel(), _stream()),
            "xq_remat_attn_prefill")
     return out
+
+
+def alloc_cache_per_channel(B, cap, d, group, bits, device="cuda"):
+    """Per-channel cache: codes as alloc_cache, scale / zero [B][cap/group][d]."""
+    assert cap % group == 0
+    return XQCache(torch.zeros((B, cap, d * bits // 8), dtype=torch.uint8, device=device),
+                   torch.zeros((B, cap // group, d), dtype=torch.bfloat16, device=device),
+                   torch.zeros((B, cap // group, d), dtype=torch.bfloat16, device=device),
+                   B, cap, d, group, bits)
+
+
+def xq_quantize_blocks_per_channel(cache, x_bf16, block0):
+    """x [B][nblk*group][d] bf16 -> blocks block0[b] .. of the per-channel cache."""
+    assert x_bf16.dtype == torch.bfloat16 and x_bf16.is_contiguous() and x_bf16.dim() == 3
+    assert x_bf16.shape[0] == cache.B and x_bf16.shape[2] == cache.d and x_bf16.shape[1] % cache.group == 0
+    cs = cache.c_struct()
+    _check(load_library().xq_quantize_blocks_per_channel(C.byref(cs), _ptr(x_bf16), x_bf16.shape[1] // cache.group,
+                                                         _i32(block0, cache.B), _stream()),
+           "xq_quantize_blocks_per_channel")

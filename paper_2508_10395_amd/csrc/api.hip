@@ -24,6 +24,8 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
 size_t remat_latent_workspace_bytes(int B, int Hq, int max_len, int r, int group);
 hipError_t run_latent_delta_project(const uint16_t* x, const uint16_t* acc, const uint16_t* ut, int B, int T, int cap,
                                     const BatchI32& start, int d, int n_lat, uint16_t* out, hipStream_t s);
+hipError_t run_quantize_blocks_per_channel(const xq_cache_t* c, const uint16_t* x, int nblk, const BatchI32& block0,
+                                           hipStream_t s);
 size_t remat_prefill_workspace_bytes(int B, int T, int Hq, int max_len, int d, int group, bool coded);
 hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, const xq_cache_t* xc,
                                   const uint16_t* acc, int B, int cap, int d, const void* wprep,
@@ -339,6 +341,38 @@ xq_status_t xq_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q_bf16, in
     if (T < 1) return XQ_ERR_INVALID_ARG;
     return remat_attn_common(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, len, out, workspace, workspace_bytes,
                              rope_cos_sin, rope_positions, pos0, stream, T);
+}
+
+// per-channel cache: the struct of a per-token cache with scale / zero [B][cap/group][d]
+static xq_status_t check_cache_per_channel(const xq_cache_t* c)
+{
+    if (!c || !c->codes || !c->scale || !c->zero) return XQ_ERR_INVALID_ARG;
+    if (c->B < 1 || c->cap < 1 || c->fmt.d <= 0 || c->fmt.group <= 0) return XQ_ERR_INVALID_ARG;
+    if (c->B > XQ_MAX_BATCH) return XQ_ERR_UNSUPPORTED;
+    if (c->fmt.group != 64 && c->fmt.group != 128) return XQ_ERR_UNSUPPORTED;
+    if (c->fmt.bits != 2 && c->fmt.bits != 3 && c->fmt.bits != 4 && c->fmt.bits != 8) return XQ_ERR_UNSUPPORTED;
+    if (c->fmt.d % 128 != 0) return XQ_ERR_UNSUPPORTED;
+    if (c->cap % c->fmt.group != 0) return XQ_ERR_INVALID_ARG;
+    if (!aligned16(c->codes) || !aligned16(c->scale) || !aligned16(c->zero)) return XQ_ERR_INVALID_ARG;
+    return XQ_OK;
+}
+
+xq_status_t xq_quantize_blocks_per_channel(const xq_cache_t* cache, const uint16_t* x_bf16, int32_t nblk,
+                                           const int32_t* block0, void* stream)
+{
+    xq_status_t st = check_cache_per_channel(cache);
+    if (st != XQ_OK) return st;
+    if (!block0 || nblk < 0) return XQ_ERR_INVALID_ARG;
+    BatchI32 bv{};
+    for (int b = 0; b < cache->B; ++b) {
+        if (block0[b] < 0 || ((long long)block0[b] + nblk) * cache->fmt.group > cache->cap) return XQ_ERR_INVALID_ARG;
+        bv.v[b] = block0[b];
+    }
+    if (nblk == 0) return XQ_OK;
+    if (nblk > 65535) return XQ_ERR_UNSUPPORTED;
+    if (!x_bf16 || !aligned16(x_bf16)) return XQ_ERR_INVALID_ARG;
+    hipError_t e = run_quantize_blocks_per_channel(cache, x_bf16, nblk, bv, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 
 static bool upproject_combo_ok(int d, int n_lat, int group, int src_bits)

@@ -70,6 +70,49 @@ __device__ __forceinline__ void unpack8(const uint4& raw, float* v)
     v[6] = bf16_lo_to_f32(raw.w); v[7] = bf16_hi_to_f32(raw.w);
 }
 
+// Packs the 16 codes of one lane (bit patterns 0x4B000000 + code) into the row's little-endian bit
+// string and stores them: lane `pi` owns bits [16 pi BITS, 16 (pi + 1) BITS) of the row at rowp.
+template <int BITS>
+__device__ __forceinline__ void pack_store16(const uint32_t (&q)[16], uint8_t* rowp, int pi, bool live)
+{
+    if constexpr (BITS == 8) {
+        constexpr uint32_t C = magic_sum(4, 8);
+        uint4 w;
+        w.x = q[0] + (q[1] << 8) + (q[2] << 16) + (q[3] << 24) - C;
+        w.y = q[4] + (q[5] << 8) + (q[6] << 16) + (q[7] << 24) - C;
+        w.z = q[8] + (q[9] << 8) + (q[10] << 16) + (q[11] << 24) - C;
+        w.w = q[12] + (q[13] << 8) + (q[14] << 16) + (q[15] << 24) - C;
+        if (live) reinterpret_cast<uint4*>(rowp)[pi] = w;
+    } else if constexpr (BITS == 4) {
+        constexpr uint32_t C = magic_sum(8, 4);
+        uint2 w = {0u - C, 0u - C};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { w.x += q[k] << (4 * k); w.y += q[8 + k] << (4 * k); }
+        if (live) reinterpret_cast<uint2*>(rowp)[pi] = w;
+    } else if constexpr (BITS == 2) {
+        uint32_t w = 0u - magic_sum(16, 2);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) w += q[k] << (2 * k);
+        if (live) reinterpret_cast<uint32_t*>(rowp)[pi] = w;
+    } else {   // 3 bits: 48 bits per lane, two lanes make three dwords
+        constexpr uint32_t C = magic_sum(8, 3);
+        uint32_t w0 = 0u - C, w1 = 0u - C;                           // 24 bits of codes each
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { w0 += q[k] << (3 * k); w1 += q[8 + k] << (3 * k); }
+        const uint32_t lo = w0 | (w1 << 24), hi = w1 >> 8;          // bits 0-31, 32-47
+        const uint32_t lo_other = dpp_u32<DPP_QUAD_XOR1>(lo);
+        uint8_t* pair = rowp + 12 * (pi >> 1);
+        if (live) {
+            if ((pi & 1) == 0) {
+                Dword2 w; w.a = lo; w.b = hi | (lo_other << 16);
+                *reinterpret_cast<Dword2*>(pair) = w;
+            } else {
+                reinterpret_cast<uint32_t*>(pair)[2] = (lo >> 16) | (hi << 16);
+            }
+        }
+    }
+}
+
 // Workgroup (t, b) quantises input row b*T + t into cache row b*cap + start[b] + t; a thread
 // takes 16 consecutive channels at a time.  In DELTA mode the value quantised is
 // x - acc[b][start[b]+t] (fp32).  d/16 is a multiple of G/16, so a group's lanes are either all
@@ -137,42 +180,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(
             zrow[pi / LANES] = (uint16_t)zb;
         }
 
-        if constexpr (BITS == 8) {
-            constexpr uint32_t C = magic_sum(4, 8);
-            uint4 w;
-            w.x = q[0] + (q[1] << 8) + (q[2] << 16) + (q[3] << 24) - C;
-            w.y = q[4] + (q[5] << 8) + (q[6] << 16) + (q[7] << 24) - C;
-            w.z = q[8] + (q[9] << 8) + (q[10] << 16) + (q[11] << 24) - C;
-            w.w = q[12] + (q[13] << 8) + (q[14] << 16) + (q[15] << 24) - C;
-            if (live) reinterpret_cast<uint4*>(rowp)[pi] = w;
-        } else if constexpr (BITS == 4) {
-            constexpr uint32_t C = magic_sum(8, 4);
-            uint2 w = {0u - C, 0u - C};
-#pragma unroll
-            for (int k = 0; k < 8; ++k) { w.x += q[k] << (4 * k); w.y += q[8 + k] << (4 * k); }
-            if (live) reinterpret_cast<uint2*>(rowp)[pi] = w;
-        } else if constexpr (BITS == 2) {
-            uint32_t w = 0u - magic_sum(16, 2);
-#pragma unroll
-            for (int k = 0; k < 16; ++k) w += q[k] << (2 * k);
-            if (live) reinterpret_cast<uint32_t*>(rowp)[pi] = w;
-        } else {   // 3 bits: 48 bits per lane, two lanes make three dwords
-            constexpr uint32_t C = magic_sum(8, 3);
-            uint32_t w0 = 0u - C, w1 = 0u - C;                           // 24 bits of codes each
-#pragma unroll
-            for (int k = 0; k < 8; ++k) { w0 += q[k] << (3 * k); w1 += q[8 + k] << (3 * k); }
-            const uint32_t lo = w0 | (w1 << 24), hi = w1 >> 8;          // bits 0-31, 32-47
-            const uint32_t lo_other = dpp_u32<DPP_QUAD_XOR1>(lo);
-            uint8_t* pair = rowp + 12 * (pi >> 1);
-            if (live) {
-                if ((pi & 1) == 0) {
-                    Dword2 w; w.a = lo; w.b = hi | (lo_other << 16);
-                    *reinterpret_cast<Dword2*>(pair) = w;
-                } else {
-                    reinterpret_cast<uint32_t*>(pair)[2] = (lo >> 16) | (hi << 16);
-                }
-            }
-        }
+        pack_store16<BITS>(q, rowp, pi, live);
     }
 }
 
@@ -210,6 +218,100 @@ hipError_t run_quantize_append(const xq_cache_t* c, const uint16_t* x, const uin
                                const BatchI32& start, hipStream_t s)
 {
     return acc ? dispatch<true>(x, acc, c, T, start, s) : dispatch<false>(x, nullptr, c, T, start, s);
+}
+
+// ---- per-channel groups (Sec. 3.3.1): a group is one channel over a block of G consecutive tokens.
+// Workgroup = (1024-channel slab, block, sequence), 4 waves; a lane owns 16 consecutive channels,
+// the waves split the block's rows.  Pass 1 reduces min/max per channel (rows in registers, waves
+// through LDS); pass 2 re-reads the rows (1 MB per block: L2) and encodes them with the per-channel
+// scale and zero-point, packing each row exactly as the per-token kernel does.
+template <int BITS>
+__global__ __launch_bounds__(256) void quantize_blocks_per_channel_kernel(
+    const uint4* __restrict__ x, uint8_t* __restrict__ codes, uint16_t* __restrict__ scale,
+    uint16_t* __restrict__ zero, int nblk, int G, int cap, int d, BatchI32 block0)
+{
+    __shared__ float smn[4][64][17], smx[4][64][17];
+    constexpr float QMAX = (float)((1 << BITS) - 1);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int blk = blockIdx.y, b = blockIdx.z;
+    const int ppr = d >> 4;
+    const int pi = blockIdx.x * 64 + lane;
+    const bool live = pi < ppr;
+    const int pc = live ? pi : ppr - 1;
+    const long long row_in0 = ((long long)b * nblk + blk) * G;              // first input row of the block
+    const long long blk_out = (long long)b * (cap / G) + block0.v[b] + blk;    // block index in the cache
+    const long long row_out0 = (long long)b * cap + (long long)(block0.v[b] + blk) * G;
+    const long long row_bytes = (long long)d * BITS / 8;
+
+    float mn[16], mx[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) { mn[k] = INFINITY; mx[k] = -INFINITY; }
+    for (int r = wave; r < G; r += 4) {
+        const uint4* xr = x + (row_in0 + r) * (d >> 3);
+        float v[16];
+        unpack8(xr[2 * pc], v);
+        unpack8(xr[2 * pc + 1], v + 8);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) { mn[k] = fminf(mn[k], v[k]); mx[k] = fmaxf(mx[k], v[k]); }
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) { smn[wave][lane][k] = mn[k]; smx[wave][lane][k] = mx[k]; }
+    __syncthreads();
+    float zf[16], rh[16], rl[16];
+    uint32_t zb[16], sb[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        float a = smn[0][lane][k], c = smx[0][lane][k];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) { a = fminf(a, smn[w][lane][k]); c = fmaxf(c, smx[w][lane][k]); }
+        uint32_t z = f32_to_bf16_rne(a);
+        z = (z & 0x7FFFu) ? z : 0u;                       // -0 -> +0
+        const float step = (c - a) / QMAX;                // IEEE divide
+        const uint32_t sbits = f32_to_bf16_rne(step);
+        const GroupRecip rr = make_recip(bf16_bits_to_f32(sbits));
+        zb[k] = z; sb[k] = sbits;
+        zf[k] = bf16_bits_to_f32(z); rh[k] = rr.rh; rl[k] = rr.rl;
+    }
+    if (wave == 0 && live) {
+        uint4 s0, s1, z0, z1;
+        s0.x = sb[0] | (sb[1] << 16); s0.y = sb[2] | (sb[3] << 16); s0.z = sb[4] | (sb[5] << 16); s0.w = sb[6] | (sb[7] << 16);
+        s1.x = sb[8] | (sb[9] << 16); s1.y = sb[10] | (sb[11] << 16); s1.z = sb[12] | (sb[13] << 16); s1.w = sb[14] | (sb[15] << 16);
+        z0.x = zb[0] | (zb[1] << 16); z0.y = zb[2] | (zb[3] << 16); z0.z = zb[4] | (zb[5] << 16); z0.w = zb[6] | (zb[7] << 16);
+        z1.x = zb[8] | (zb[9] << 16); z1.y = zb[10] | (zb[11] << 16); z1.z = zb[12] | (zb[13] << 16); z1.w = zb[14] | (zb[15] << 16);
+        uint4* sp = reinterpret_cast<uint4*>(scale + blk_out * d) + 2 * pi;
+        uint4* zp = reinterpret_cast<uint4*>(zero + blk_out * d) + 2 * pi;
+        sp[0] = s0; sp[1] = s1; zp[0] = z0; zp[1] = z1;
+    }
+    for (int r = wave; r < G; r += 4) {
+        const uint4* xr = x + (row_in0 + r) * (d >> 3);
+        float v[16];
+        unpack8(xr[2 * pc], v);
+        unpack8(xr[2 * pc + 1], v + 8);
+        uint32_t q[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const float n = v[k] - zf[k];
+            const float y = __builtin_fmaf(n, rh[k], n * rl[k]);
+            q[k] = __float_as_uint(__builtin_amdgcn_fmed3f(y + ROUND_MAGIC, ROUND_MAGIC, ROUND_MAGIC + QMAX));
+        }
+        pack_store16<BITS>(q, codes + (row_out0 + r) * row_bytes, pi, live);
+    }
+}
+
+hipError_t run_quantize_blocks_per_channel(const xq_cache_t* c, const uint16_t* x, int nblk, const BatchI32& block0,
+                                           hipStream_t s)
+{
+    const int d = c->fmt.d, G = c->fmt.group;
+    const dim3 grid((unsigned)((d / 16 + 63) / 64), (unsigned)nblk, (unsigned)c->B);
+    const uint4* xp = reinterpret_cast<const uint4*>(x);
+    switch (c->fmt.bits) {
+        case 2: quantize_blocks_per_channel_kernel<2><<<grid, dim3(256), 0, s>>>(xp, c->codes, c->scale, c->zero, nblk, G, c->cap, d, block0); break;
+        case 3: quantize_blocks_per_channel_kernel<3><<<grid, dim3(256), 0, s>>>(xp, c->codes, c->scale, c->zero, nblk, G, c->cap, d, block0); break;
+        case 4: quantize_blocks_per_channel_kernel<4><<<grid, dim3(256), 0, s>>>(xp, c->codes, c->scale, c->zero, nblk, G, c->cap, d, block0); break;
+        case 8: quantize_blocks_per_channel_kernel<8><<<grid, dim3(256), 0, s>>>(xp, c->codes, c->scale, c->zero, nblk, G, c->cap, d, block0); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
 }
 
 }  // namespace xq
