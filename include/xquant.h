@@ -289,6 +289,27 @@ xq_status_t xq_cl_accumulate_latent(uint16_t *acc_bf16, const xq_cache_t *delta,
 xq_status_t xq_quantize_blocks_per_channel(const xq_cache_t *cache, const uint16_t *x_bf16,
                                            int32_t nblk, const int32_t *block0, void *stream);
 
+/*
+ * xq_remat_attn_decode_per_channel: decode attention (as xq_remat_attn_decode) over len[b] tokens of
+ * which the first floor(len[b]/group)*group are read from the per-channel cache (bits 2, 3 or 4) and
+ * the remaining len[b] % group from rows 0.. of the residual window.
+ *   tail_bf16    dev [B][group][d] bf16: the window (rows past len[b] % group are not read)
+ *   len          host [B], len[b] >= 1, floor(len[b]/group)*group <= cap
+ *   wprep_coded  xq_prepare_weights(a, d, 128, bits, Wk, Wv): stream for the coded blocks
+ *   wprep_dense  xq_prepare_weights(a, d, 0, 16, Wk, Wv): stream for the window and for the
+ *                zero-point term (the zero-points of a block times [Wk | Wv], one row per block)
+ *   workspace    dev, xq_remat_attn_per_channel_workspace_bytes(a, B, max len, d, group) bytes
+ * The per-channel scales enter the contraction on the token operand (one packed fp16 multiply per
+ * operand dword): exact for 2- and 3-bit codes, rounded at 2^-12 relative for 4-bit codes.
+ */
+size_t      xq_remat_attn_per_channel_workspace_bytes(const xq_attn_t *a, int32_t B, int32_t max_len,
+                                                      int32_t d, int32_t group);
+xq_status_t xq_remat_attn_decode_per_channel(const xq_attn_t *a, const uint16_t *q_bf16,
+                                             const xq_cache_t *cache, const uint16_t *tail_bf16,
+                                             const int32_t *len, const void *wprep_coded,
+                                             const void *wprep_dense, float *out, void *workspace,
+                                             size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -13,4 +13,5 @@ from .binding import (  # noqa: F401
     xq_cl_accumulate_latent_workspace_bytes, xq_cl_accumulate_latent,
     xq_remat_attn_prefill_workspace_bytes, xq_remat_attn_prefill,
     alloc_cache_per_channel, xq_quantize_blocks_per_channel,
+    xq_remat_attn_per_channel_workspace_bytes, xq_remat_attn_decode_per_channel,
 )

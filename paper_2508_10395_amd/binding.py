@@ -27,6 +27,7 @@ SYMBOLS = [
     "xq_cl_accumulate_latent_workspace_bytes", "xq_cl_accumulate_latent",
     "xq_remat_attn_prefill_workspace_bytes", "xq_remat_attn_prefill",
     "xq_quantize_blocks_per_channel",
+    "xq_remat_attn_per_channel_workspace_bytes", "xq_remat_attn_decode_per_channel",
 ]
 
 
@@ -130,6 +131,12 @@ def load_library():
     lib.xq_quantize_blocks_per_channel.restype = C.c_int
     lib.xq_quantize_blocks_per_channel.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_int32, C.POINTER(C.c_int32),
                                                    C.c_void_p]
+    lib.xq_remat_attn_per_channel_workspace_bytes.restype = C.c_size_t
+    lib.xq_remat_attn_per_channel_workspace_bytes.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    lib.xq_remat_attn_decode_per_channel.restype = C.c_int
+    lib.xq_remat_attn_decode_per_channel.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
+                                                     C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_void_p,
+                                                     C.c_void_p, C.c_size_t, C.c_void_p]
     _LIB = lib
     return lib
 
@@ -461,3 +468,29 @@ def xq_quantize_blocks_per_channel(cache, x_bf16, block0):
     _check(load_library().xq_quantize_blocks_per_channel(C.byref(cs), _ptr(x_bf16), x_bf16.shape[1] // cache.group,
                                                          _i32(block0, cache.B), _stream()),
            "xq_quantize_blocks_per_channel")
+
+
+def xq_remat_attn_per_channel_workspace_bytes(attn, B, max_len, d, group):
+    a = attn.c_struct()
+    return load_library().xq_remat_attn_per_channel_workspace_bytes(C.byref(a), B, max_len, d, group)
+
+
+def xq_remat_attn_decode_per_channel(attn, q_bf16, cache, tail_bf16, lens, wprep_coded, wprep_dense, out=None,
+                                     workspace=None):
+    """Decode attention from a per-channel cache plus the bf16 residual window [B][group][d]."""
+    assert q_bf16.dtype == torch.bfloat16 and q_bf16.is_contiguous()
+    assert tail_bf16.dtype == torch.bfloat16 and tail_bf16.is_contiguous()
+    assert tuple(tail_bf16.shape) == (cache.B, cache.group, cache.d)
+    lens = [int(v) for v in lens]
+    a = attn.c_struct()
+    cs = cache.c_struct()
+    need = xq_remat_attn_per_channel_workspace_bytes(attn, cache.B, max(lens) if lens else 1, cache.d, cache.group)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q_bf16.device)
+    if out is None:
+        out = torch.empty((cache.B, attn.n_q_heads, attn.head_dim), dtype=torch.float32, device=q_bf16.device)
+    _check(load_library().xq_remat_attn_decode_per_channel(C.byref(a), _ptr(q_bf16), C.byref(cs), _ptr(tail_bf16),
+                                                           _i32(lens, cache.B), _ptr(wprep_coded), _ptr(wprep_dense),
+                                                           _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
+           "xq_remat_attn_decode_per_channel")
+    return out

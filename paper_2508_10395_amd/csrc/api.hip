@@ -26,6 +26,10 @@ hipError_t run_latent_delta_project(const uint16_t* x, const uint16_t* acc, cons
                                     const BatchI32& start, int d, int n_lat, uint16_t* out, hipStream_t s);
 hipError_t run_quantize_blocks_per_channel(const xq_cache_t* c, const uint16_t* x, int nblk, const BatchI32& block0,
                                            hipStream_t s);
+size_t remat_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int d, int block);
+hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc, const uint16_t* tail,
+                                    const void* wprep_coded, const void* wprep_dense, const BatchI32& len, int max_len,
+                                    float* out, void* ws, hipStream_t s);
 size_t remat_prefill_workspace_bytes(int B, int T, int Hq, int max_len, int d, int group, bool coded);
 hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, const xq_cache_t* xc,
                                   const uint16_t* acc, int B, int cap, int d, const void* wprep,
@@ -372,6 +376,42 @@ xq_status_t xq_quantize_blocks_per_channel(const xq_cache_t* cache, const uint16
     if (nblk > 65535) return XQ_ERR_UNSUPPORTED;
     if (!x_bf16 || !aligned16(x_bf16)) return XQ_ERR_INVALID_ARG;
     hipError_t e = run_quantize_blocks_per_channel(cache, x_bf16, nblk, bv, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+size_t xq_remat_attn_per_channel_workspace_bytes(const xq_attn_t* a, int32_t B, int32_t max_len, int32_t d, int32_t group)
+{
+    if (check_attn(a) != XQ_OK || B < 1 || max_len < 1 || d <= 0 || d % 128 != 0) return 0;
+    if (group != 64 && group != 128) return 0;
+    return remat_pc_workspace_bytes(B, a->n_q_heads, a->n_kv_heads, max_len, d, group);
+}
+
+xq_status_t xq_remat_attn_decode_per_channel(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* cache,
+                                             const uint16_t* tail_bf16, const int32_t* len, const void* wprep_coded,
+                                             const void* wprep_dense, float* out, void* workspace,
+                                             size_t workspace_bytes, void* stream)
+{
+    xq_status_t st = check_attn(a);
+    if (st != XQ_OK) return st;
+    st = check_cache_per_channel(cache);
+    if (st != XQ_OK) return st;
+    if (cache->fmt.bits == 8) return XQ_ERR_UNSUPPORTED;
+    if (!q_bf16 || !tail_bf16 || !len || !wprep_coded || !wprep_dense || !out || !workspace) return XQ_ERR_INVALID_ARG;
+    if (!aligned16(q_bf16) || !aligned16(tail_bf16) || !aligned16(wprep_coded) || !aligned16(wprep_dense) ||
+        !aligned16(out) || !aligned16(workspace))
+        return XQ_ERR_INVALID_ARG;
+    BatchI32 lv{};
+    int max_len = 0;
+    for (int b = 0; b < cache->B; ++b) {
+        // the blocks must fit the cache; the window holds at most group - 1 tokens by construction
+        if (len[b] < 1 || (len[b] / cache->fmt.group) * cache->fmt.group > cache->cap) return XQ_ERR_INVALID_ARG;
+        lv.v[b] = len[b];
+        if (len[b] > max_len) max_len = len[b];
+    }
+    if (workspace_bytes < xq_remat_attn_per_channel_workspace_bytes(a, cache->B, max_len, cache->fmt.d, cache->fmt.group))
+        return XQ_ERR_WORKSPACE;
+    hipError_t e = run_remat_attn_decode_pc(a, q_bf16, cache, tail_bf16, wprep_coded, wprep_dense, lv, max_len, out,
+                                            workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 

@@ -98,6 +98,12 @@ struct RematParams {
     BatchI32 len;
     uint16_t* acc_out;       // up-projection mode: accumulator [B][cap][d_out] bf16, updated in place
     int d_out;
+    BatchI32 chunk0;         // first partial-chunk index of each sequence in this launch (0 unless a launch continues another)
+    // per-channel source (groups along the token axis): factor images, per-block scale and z W rows
+    const float* pc_fscale;  // [B][pc_blocks_cap]: 2^(E_blk + bits - 1)
+    const float* pc_zw;      // [B][pc_blocks_cap][Hkv][256] fp32: zero-points of the block times [Wk_h | Wv_h]
+    float* kv_out;           // dense store mode: [B][pc_blocks_cap][Hkv][256] fp32 rows of [K_h | V_h]
+    int pc_block, pc_blocks_cap;   // tokens per block (64 or 128), blocks per sequence in the arrays above
     const float* rope;       // optional [n_pos][64][2] cos, sin: rotate the keys (half-split pairs)
     BatchI32 pos0;           // with rope: position of cache row 0 of each sequence
 };
@@ -240,7 +246,7 @@ __device__ __forceinline__ void attention_epilogue(const RematParams& p, const T
     if (c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS >= c.len) return;     // chunk entirely past len
     if (p.rope) rope_rotate(p, c, acc);
     const int gq = p.Hq / p.Hkv;
-    const int chunk = c.tile * (TILE_TOKENS / CHUNK_TOKENS) + c.wave;
+    const int chunk = p.chunk0.v[c.b] + c.tile * (TILE_TOKENS / CHUNK_TOKENS) + c.wave;
     for (int j = 0; j < gq; ++j) {
         const int hq = c.hk * gq + j;
         const uint16_t* qv = p.q + ((long long)c.b * p.Hq + hq) * 128;
@@ -608,7 +614,15 @@ __device__ __forceinline__ void accumulate_epilogue(const RematParams& p, const 
     });
 }
 
-constexpr int MODE_ATTENTION = 0, MODE_SCORES = 1, MODE_WEIGHTED_SUM = 2, MODE_ACCUMULATE = 3, MODE_PREFILL = 4;
+constexpr int MODE_ATTENTION = 0, MODE_SCORES = 1, MODE_WEIGHTED_SUM = 2, MODE_ACCUMULATE = 3, MODE_PREFILL = 4,
+              MODE_ATTENTION_PC = 5;
+
+// packed fp16 multiply of two operand dwords (v_pk_mul_f16; fp16 subnormals are honoured)
+typedef _Float16 xq_f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_mul_f16(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(xq_f16x2, a) * __builtin_bit_cast(xq_f16x2, b));
+}
 
 // =====================================================================================
 // coded source (XQuant cache, BITS in {2,3,4})
@@ -619,6 +633,17 @@ constexpr int MODE_ATTENTION = 0, MODE_SCORES = 1, MODE_WEIGHTED_SUM = 2, MODE_A
 // heads; the up-projection of cross-layer latent deltas into the bf16 accumulator (the columns are
 // 256 hidden channels); or attention for many (query, head) rows per KV head through the
 // matrix-core epilogue (prefill chunks, and decode when a KV head serves several query heads).
+//
+// MODE_ATTENTION_PC reads a per-channel cache (Sec. 3.3.1: one scale and zero-point per channel and
+// block of 64 or 128 tokens).  The scale now varies along the contraction, so it moves to the token
+// operand: each unpacked operand dword is multiplied (packed fp16) by the block's factors
+// scale * 2^(15 - E_blk) of its two channels -- an 8-bit significand times a code of at most 3 bits
+// is exact in fp16 (4-bit codes round at 2^-12), and one exponent per block suffices because fp16
+// subnormals keep an absolute precision of 2^-24 against the block's largest scale.  All tokens of
+// a wave lie in one block, so the factors come from a small LDS image (one per slab, three
+// rotating buffers) by broadcast reads.  There is no Horner rescale and no correction phase; the
+// zero-point term z_blk [Wk_h | Wv_h] is the same for every token of a block, comes from a
+// pre-pass and is added in the epilogue together with the block's power of two.
 template <int BITS, int G, int MODE>
 __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams p)
 {
@@ -631,6 +656,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     constexpr int IMG_BYTES = code_image_bytes(BITS);
     constexpr int NIMG = n_code_images(BITS);
     constexpr int LDS_SCALES_OFF = lds_scales_off(BITS);
+    constexpr bool PC = MODE == MODE_ATTENTION_PC;     // per-channel source: factors on the token operand
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     TileCtx c;
@@ -649,8 +675,11 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     const uint32_t row_bytes = (uint32_t)(p.row_d * BITS / 8);
     const uint8_t* cbase = p.codes + seq_row0 * row_bytes;
     const uint16_t* zbase = p.zero + seq_row0 * p.ng_row;
+    // per-token source: effective scales, GPS * 512 bytes per slab; per-channel: one 1 KiB factor image per slab
+    const int e_slab_bytes = PC ? LDS_SCALES_BYTES : GPS * 512;
     const uint8_t* ebase = reinterpret_cast<const uint8_t*>(p.eT) +
-                           ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.ng + 1) * 512;
+                           (PC ? ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.n_main_slabs + 1) * LDS_SCALES_BYTES
+                               : ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.ng + 1) * 512);
     const uint32_t moff = (uint32_t)min(c.tok, c.len - 1) * (uint32_t)p.ng_row;
 
     // code DMA: 16-byte piece pc of the tile's slab image = (row pc / BITS, part pc % BITS);
@@ -716,6 +745,16 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
             }
         }
     };
+    // per-channel source: multiply the operand dwords of k-step ks by the block's factors of their channels
+    // (image of the slab in scale buffer sbuf: [block of the tile][k-step][lane half][8 fp16], broadcast read)
+    const uint8_t* my_factors = lds + LDS_SCALES_OFF + (PC ? ((wave * CHUNK_TOKENS) / p.pc_block) * 256 + half * 16 : 0);
+    auto scale_frag = [&](uint32_t* frag, int sbuf, int ks) {
+        const uint4 f = *reinterpret_cast<const uint4*>(my_factors + sbuf * LDS_SCALES_BYTES + ks * 32);
+        frag[0] = pk_mul_f16(frag[0], f.x);
+        frag[1] = pk_mul_f16(frag[1], f.y);
+        frag[2] = pk_mul_f16(frag[2], f.z);
+        frag[3] = pk_mul_f16(frag[3], f.w);
+    };
     // one piece of the DMA that brings in main slab `slab` (weights to `wdst`): steps 0,1 this wave's
     // code pieces (to code image `img`), 2 scales (wave 7; of slab `slab2`, into scale buffer `sbuf`),
     // 3..10 the weight chunks
@@ -726,7 +765,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                          lds_base + LDS_CODES_OFF + (uint32_t)(img * IMG_BYTES) + (wave + 8 * step) * 1024);
         } else if (step == 2) {
             if (with_scales2 && wave == 7)
-                dma_b128(ebase + (long long)slab2 * GPS * 512, dma_voff, lds_base + LDS_SCALES_OFF + (uint32_t)(sbuf * LDS_SCALES_BYTES));
+                dma_b128(ebase + (long long)slab2 * e_slab_bytes, dma_voff, lds_base + LDS_SCALES_OFF + (uint32_t)(sbuf * LDS_SCALES_BYTES));
         } else {
             dma_b128(wsrc + (long long)slab * SLAB_BYTES + (step - 3) * 8192, dma_voff, wdst + (step - 3) * 8192);
         }
@@ -772,8 +811,10 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         dma_step(1, 0, 0, 0, false, 0, 0);
     }
     uint4 mfr[SLAB_KSTEPS];
+    if constexpr (!PC) {
 #pragma unroll
-    for (int ks = 0; ks < SLAB_KSTEPS; ++ks) mfr[ks] = load_meta(ks);
+        for (int ks = 0; ks < SLAB_KSTEPS; ++ks) mfr[ks] = load_meta(ks);
+    }
     for (int cs = 0; cs < n_corr_slabs; ++cs) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
@@ -782,7 +823,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         else issue_slab(wsrc, wdst, dma_voff);                                                   // the first main slab
         if (cs == 0) {
             fetch_tokens(NIMG - 1);
-            fetch_scales(2, &E[0]);
+            if constexpr (!PC) fetch_scales(2, &E[0]);
         }
         const uint8_t* slab = my_slab + (cs & 1) * SLAB_BYTES;
         const int nks = min(SLAB_KSTEPS, p.n_corr_ksteps - cs * SLAB_KSTEPS);
@@ -790,7 +831,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         for (int nb = 0; nb < 8; ++nb) af[nb] = *reinterpret_cast<const uint4*>(slab + nb * 1024);
 #pragma unroll
         for (int ks = 0; ks < SLAB_KSTEPS; ++ks) {
-            if (ks < nks) {
+            if (!PC && ks < nks) {                    // (per-channel source: the zero-point term comes from a pre-pass)
 #pragma unroll
                 for (int nb = 0; nb < 8; ++nb) {
                     acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[nb]),
@@ -810,9 +851,11 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                 }
             }
         }
-        if (cs + 1 < n_corr_slabs) {
+        if constexpr (!PC) {
+            if (cs + 1 < n_corr_slabs) {
 #pragma unroll
-            for (int ks = 0; ks < SLAB_KSTEPS; ++ks) mfr[ks] = load_meta((cs + 1) * SLAB_KSTEPS + ks);
+                for (int ks = 0; ks < SLAB_KSTEPS; ++ks) mfr[ks] = load_meta((cs + 1) * SLAB_KSTEPS + ks);
+            }
         }
     }
 
@@ -828,25 +871,30 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     // scales E[0..GPS) the lagging blocks start from; the accumulators (holding the correction in
     // units of 1) are brought to those scales.
 #pragma unroll
-    for (int ks = 1; ks < SLAB_KSTEPS; ++ks)
+    for (int ks = 1; ks < SLAB_KSTEPS; ++ks) {
         unpack_kstep<BITS>(&cur[(ks / KSG) * NDW_G + ((ks % KSG) >> 2) * BITS], ks % KSG, ub[ks]);
+        if constexpr (PC) scale_frag(ub[ks], 2, ks);       // (the predecessor slab's factors wait in buffer 2)
+    }
     const int par0 = n_corr_slabs & 1;                 // weight buffer of main iteration 0
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     fetch_tokens(0);
-    fetch_scales(0, &E[GPS]);
+    if constexpr (!PC) fetch_scales(0, &E[GPS]);
     {
         const uint8_t* slab0 = my_slab + par0 * SLAB_BYTES;
 #pragma unroll
         for (int sl = 0; sl < 7; ++sl) af[sl] = *reinterpret_cast<const uint4*>(slab0 + sl * 1024);
+        if constexpr (!PC) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float r0 = __builtin_amdgcn_rcpf(E[floordiv_c(j - 8, KSG) + GPS]);
-            acc[j] *= r0;
+            for (int j = 0; j < 8; ++j) {
+                const float r0 = __builtin_amdgcn_rcpf(E[floordiv_c(j - 8, KSG) + GPS]);
+                acc[j] *= r0;
+            }
+#pragma unroll
+            for (int k = 0; k < NB; ++k) hr_b[k] = E[k] * __builtin_amdgcn_rcpf(E[k + 1]);
         }
-#pragma unroll
-        for (int k = 0; k < NB; ++k) hr_b[k] = E[k] * __builtin_amdgcn_rcpf(E[k + 1]);
         unpack_kstep<BITS>(&cur[0], 0, ub[0]);
+        if constexpr (PC) scale_frag(ub[0], 0, 0);
     }
 
     // Multiplies chunk CIDX (of 3,3,3,3,2,2 registers) of one block's accumulator by h.  The empty
@@ -885,7 +933,8 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         });
     };
     // boundaries in the first slots of iteration 0 whose chunks belong to "the slab before"
-    static_for<58, 64>([&](auto SIDX) XQ_INLINE_LAMBDA { horner_slot(SIDX, hr_b, hr_b, std::false_type{}, true); });
+    if constexpr (!PC)
+        static_for<58, 64>([&](auto SIDX) XQ_INLINE_LAMBDA { horner_slot(SIDX, hr_b, hr_b, std::false_type{}, true); });
 
     // A tick is 8 slots of one MFMA each (slot = column block); the VALU/LDS/DMA work that feeds
     // later slots is spread over the slots and pinned there with scheduling fences so that it runs
@@ -906,6 +955,10 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         const uint32_t wdst = lds_w + (uint32_t)(((it + 1 + par0) & 1) * SLAB_BYTES);
         const uint8_t* slab = my_slab + ((it + par0) & 1) * SLAB_BYTES;
         const uint8_t* slab_next = my_slab + ((it + 1 + par0) & 1) * SLAB_BYTES;
+        // scale buffers: per-token source, slab s in buffer s & 1 (its scales are taken into registers one slab
+        // ahead); per-channel source, slab s in buffer s % 3 (its factors are read all through its own iteration)
+        const int sb_dma = PC ? (it + 2) % 3 : (it & 1);
+        const int sb_cur = it % 3, sb_nxt = (it + 1) % 3;
         float e_nxt[GPS];                                    // scales of the next slab (landed one slab ago)
         float hr_bn[NB];                                     // boundary factors of the next iteration
 #pragma unroll
@@ -923,7 +976,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                 // DMA of the next slab: 11 steps per wave, one every other slot.  (Issued in bursts they
                 // fill the address FIFO and the issuing wave stalls with its MFMAs behind them.)
                 if constexpr ((sidx >> 1) < 11 && (sidx & 1) == 0)
-                    dma_step(sidx >> 1, s_next, img_next, s_next2, true, it & 1, wdst);
+                    dma_step(sidx >> 1, s_next, img_next, s_next2, true, sb_dma, wdst);
                 // the old codes are no longer needed: wait until the next slab has landed for everyone,
                 // then take the next slab's codes
                 if constexpr (ks == SLAB_KSTEPS - 1 && m == 1) {
@@ -939,13 +992,17 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                     if constexpr (m == 2) {
                         constexpr int gi1 = (ks + 1) / KSG, ksg1 = (ks + 1) % KSG;
                         unpack_kstep<BITS>(&cur[gi1 * NDW_G + (ksg1 >> 2) * BITS], ksg1, ub[ks + 1]);
+                        if constexpr (PC) scale_frag(ub[ks + 1], sb_cur, ks + 1);
                     }
                 } else if constexpr (m == 7) {               // cur already holds the next slab's codes
-                    if (more_main) unpack_kstep<BITS>(&cur[0], 0, ub[0]);
+                    if (more_main) {
+                        unpack_kstep<BITS>(&cur[0], 0, ub[0]);
+                        if constexpr (PC) scale_frag(ub[0], sb_nxt, 0);
+                    }
                 }
                 // the next slab's scales are in LDS since the previous slab
-                if constexpr (ks == SLAB_KSTEPS - 2 && m == 4) { if (more_main) fetch_scales((it + 1) & 1, e_nxt); }
-                if constexpr (ks == SLAB_KSTEPS - 1 && m == 3) {
+                if constexpr (!PC && ks == SLAB_KSTEPS - 2 && m == 4) { if (more_main) fetch_scales((it + 1) & 1, e_nxt); }
+                if constexpr (!PC && ks == SLAB_KSTEPS - 1 && m == 3) {
                     if (more_main) {
                         static_for<0, NB>([&](auto K) XQ_INLINE_LAMBDA {
                             constexpr int k = decltype(K)::value;
@@ -956,20 +1013,40 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                         });
                     }
                 }
-                horner_slot(SIDX, hr_b, hr_bn, std::true_type{}, more_main);
+                if constexpr (!PC) horner_slot(SIDX, hr_b, hr_bn, std::true_type{}, more_main);
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
-        if (more_main) {
+        if constexpr (!PC) {
+            if (more_main) {
 #pragma unroll
-            for (int gi = 0; gi < GPS; ++gi) { E[gi] = E[gi + GPS]; E[gi + GPS] = e_nxt[gi]; }
+                for (int gi = 0; gi < GPS; ++gi) { E[gi] = E[gi + GPS]; E[gi + GPS] = e_nxt[gi]; }
 #pragma unroll
-            for (int k = 0; k < NB; ++k) hr_b[k] = hr_bn[k];
+                for (int k = 0; k < NB; ++k) hr_b[k] = hr_bn[k];
+            }
         }
     }
-    // every block ends in the slab it started in; leave its group's scale: the accumulator is K | V
+    if constexpr (PC) {
+        // K | V = accumulator * 2^(E_blk + bits - 1) + z_blk [Wk_h | Wv_h]; waves past len take the last block's
+        const int blk = min((c.tile * TILE_TOKENS + wave * CHUNK_TOKENS) / p.pc_block, (c.len - 1) / p.pc_block);
+        const long long brow = (long long)c.b * p.pc_blocks_cap + blk;
+        const float fs = p.pc_fscale[brow];
+        const float* zw = p.pc_zw + (brow * p.Hkv + c.hk) * 256 + half * 4;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] *= E[GPS + j / KSG];
+        for (int nb = 0; nb < 8; ++nb)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const float4 z = *reinterpret_cast<const float4*>(zw + nb * 32 + i4 * 8);
+                acc[nb][i4 * 4 + 0] = __builtin_fmaf(acc[nb][i4 * 4 + 0], fs, z.x);
+                acc[nb][i4 * 4 + 1] = __builtin_fmaf(acc[nb][i4 * 4 + 1], fs, z.y);
+                acc[nb][i4 * 4 + 2] = __builtin_fmaf(acc[nb][i4 * 4 + 2], fs, z.z);
+                acc[nb][i4 * 4 + 3] = __builtin_fmaf(acc[nb][i4 * 4 + 3], fs, z.w);
+            }
+    } else {
+        // every block ends in the slab it started in; leave its group's scale: the accumulator is K | V
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] *= E[GPS + j / KSG];
+    }
     if constexpr (MODE == MODE_SCORES) scores_epilogue(p, c, acc);
     else if constexpr (MODE == MODE_WEIGHTED_SUM) weighted_sum_epilogue(p, c, acc);
     else if constexpr (MODE == MODE_ACCUMULATE) accumulate_epilogue(p, c, acc, lds);
@@ -995,7 +1072,10 @@ constexpr int LDS_DENSE_STAGE_BYTES = 4096;            // per wave
 constexpr int LDS_DENSE_TOTAL = LDS_DENSE_STAGE_OFF + 8 * LDS_DENSE_STAGE_BYTES;
 static_assert(LDS_DENSE_TOTAL <= LDS_MAX, "dense kernel LDS");
 
-template <bool PREFILL>
+// DMODE: 0 decode attention, 1 matrix-core epilogue (prefill), 2 store the rematerialised rows
+// [K_h | V_h] as fp32 (used for the zero-point term of a per-channel cache)
+constexpr int DENSE_ATTENTION = 0, DENSE_PREFILL = 1, DENSE_STORE = 2;
+template <int DMODE>
 __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams p)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -1096,9 +1176,20 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
         });
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing may still be writing this workgroup's LDS
-    if constexpr (PREFILL) {
+    if constexpr (DMODE == DENSE_PREFILL) {
         __syncthreads();                                  // ... including the other waves' staging copies
         prefill_epilogue(p, c, acc, lds);
+    } else if constexpr (DMODE == DENSE_STORE) {
+        if (c.tok < c.len) {
+            float* row = p.kv_out + (((long long)c.b * p.pc_blocks_cap + c.tok) * p.Hkv + c.hk) * 256 + c.half * 4;
+#pragma unroll
+            for (int nb = 0; nb < 8; ++nb)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    float4 v; v.x = acc[nb][i4 * 4]; v.y = acc[nb][i4 * 4 + 1]; v.z = acc[nb][i4 * 4 + 2]; v.w = acc[nb][i4 * 4 + 3];
+                    *reinterpret_cast<float4*>(row + nb * 32 + i4 * 8) = v;
+                }
+        }
     } else {
         attention_epilogue(p, c, acc);
     }
@@ -1274,7 +1365,7 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
         if (e != hipSuccess) return e;
         e = launch_coded<MODE_ATTENTION>(bits, G, p, grid, s);
     } else {
-        e = launch_with_lds(remat_attn_dense_kernel<false>, LDS_DENSE_TOTAL, p, grid, s);
+        e = launch_with_lds(remat_attn_dense_kernel<DENSE_ATTENTION>, LDS_DENSE_TOTAL, p, grid, s);
     }
     if (e != hipSuccess) return e;
     combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len, 1, CHUNK_TOKENS);
@@ -1329,7 +1420,7 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
         if (e != hipSuccess) return e;
         e = launch_coded<MODE_PREFILL>(bits, G, p, grid, s);
     } else {
-        e = launch_with_lds(remat_attn_dense_kernel<true>, LDS_DENSE_TOTAL, p, grid, s);
+        e = launch_with_lds(remat_attn_dense_kernel<DENSE_PREFILL>, LDS_DENSE_TOTAL, p, grid, s);
     }
     if (e != hipSuccess) return e;
     combine_kernel<<<dim3(p.Hq, p.B * T), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq,
@@ -1413,6 +1504,165 @@ hipError_t run_cl_accumulate_latent(uint16_t* acc, const xq_cache_t* xc, int d, 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_coded<MODE_ACCUMULATE>(bits, G, p, blocks * B * p.tiles_per_seq, s);
+}
+
+// ---- per-channel cache (Sec. 3.3.1) ----------------------------------------------------------
+// Pre-pass 1: per block, E = exponent with max_c scale < 2^E, and the block's final factor
+// 2^(E + bits - 1) (the operand factors are scale * 2^(15 - E), the prepared weights carry 2^(-14 - bits)
+// relative to the code bits).  One workgroup per (block, sequence).
+__global__ __launch_bounds__(256) void pc_block_exponent_kernel(const uint16_t* __restrict__ scale, float* __restrict__ fscale,
+                                                                int* __restrict__ eblk, int d, int blocks_cap,
+                                                                int blocks_ws, int bits, BatchI32 nblk)
+{
+    __shared__ uint32_t red[256];
+    const int blk = blockIdx.x, b = blockIdx.y;
+    if (blk >= nblk.v[b]) return;
+    const uint16_t* row = scale + ((long long)b * blocks_cap + blk) * d;
+    uint32_t mx = 0;
+    for (int c = threadIdx.x; c < d; c += 256) mx = max(mx, (uint32_t)row[c]);    // non-negative bf16: ordered as integers
+    red[threadIdx.x] = mx;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+        if ((int)threadIdx.x < st) red[threadIdx.x] = max(red[threadIdx.x], red[threadIdx.x + st]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const int e8 = (int)(red[0] >> 7);                                          // biased exponent of the largest scale
+        const int E = red[0] ? e8 - 126 : 0;                                        // largest scale < 2^E
+        eblk[(long long)b * blocks_ws + blk] = E;                                   // (workspace rows per sequence)
+        fscale[(long long)b * blocks_ws + blk] = ldexpf(1.0f, E + bits - 1);
+    }
+}
+
+// Pre-pass 2: the factor images, [sequence][tile][slab (+1 pad)][block of the tile][k-step][lane half][8] fp16, in
+// the order the unpacked operand dwords hold their channels (the unpack table gives the code of each slot).
+// Blocks past the sequence's last one repeat it (their tokens are masked, but must stay finite).
+struct PcImageArgs {
+    const uint16_t* scale;
+    const int* eblk;
+    uint16_t* img;
+    int d, blocks_cap, blocks_ws, block, tiles_per_seq, n_slabs, G;   // blocks per sequence in the cache / in eblk
+    BatchI32 nblk;
+    UnpackTable tab;
+};
+__global__ __launch_bounds__(256) void pc_factor_image_kernel(PcImageArgs a)
+{
+    const int slab = blockIdx.x, tile = blockIdx.y, b = blockIdx.z;
+    const int bpt = TILE_TOKENS / a.block;                       // blocks per tile
+    if (tile * bpt >= a.nblk.v[b]) return;
+    uint16_t* out = a.img + (((long long)b * a.tiles_per_seq + tile) * (a.n_slabs + 1) + slab) * (LDS_SCALES_BYTES / 2);
+    const int ksg_n = a.G / 16;
+    for (int e = threadIdx.x; e < bpt * 128; e += 256) {
+        const int i = e & 7, half = (e >> 3) & 1, ks = (e >> 4) & 7, bt = e >> 7;
+        const int blk = min(tile * bpt + bt, a.nblk.v[b] - 1);
+        const int gi = ks / ksg_n, ksg = ks % ksg_n;
+        const int c = slab * 128 + gi * a.G + half * (a.G / 2) + (ksg >> 2) * 32 + a.tab.code_of_slot[ksg & 3][i];
+        const float sc = bf16_bits_to_f32(a.scale[((long long)b * a.blocks_cap + blk) * a.d + c]);
+        const float f = ldexpf(sc, 15 - a.eblk[(long long)b * a.blocks_ws + blk]);
+        out[e] = __builtin_bit_cast(uint16_t, (_Float16)f);
+    }
+}
+
+bool unpack_table_for(int bits, UnpackTable* t);
+
+size_t remat_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int d, int block)
+{
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    const size_t chunks = (tiles + 1) * (TILE_TOKENS / CHUNK_TOKENS);
+    const size_t blocks = (size_t)max_len / block + 1;
+    return (size_t)B * Hq * chunks * (128 + 2) * sizeof(float)                    // partials
+         + (size_t)B * tiles * (size_t)(d / 128 + 1) * LDS_SCALES_BYTES           // factor images
+         + (size_t)B * blocks * (size_t)Hkv * 256 * sizeof(float)                 // z W rows
+         + (size_t)B * blocks * 2 * sizeof(float) + 256;                          // block factors and exponents
+}
+
+// Decode attention from a per-channel cache plus the bf16 residual window of the newest len % block tokens.
+hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc, const uint16_t* tail,
+                                    const void* wprep_coded, const void* wprep_dense, const BatchI32& len, int max_len,
+                                    float* out, void* ws, hipStream_t s)
+{
+    const int bits = xc->fmt.bits, blockT = xc->fmt.group, d = xc->fmt.d, B = xc->B, cap = xc->cap;
+    const int blocks_cap = cap / blockT;
+    const WPrepLayout Lc = make_wprep_layout(d, 128, bits, a->n_kv_heads);
+    const WPrepLayout Ld = make_wprep_layout(d, 128, 16, a->n_kv_heads);
+    UnpackTable tab;
+    if (!unpack_table_for(bits, &tab)) return hipErrorInvalidValue;
+    BatchI32 nblk{}, len_coded{}, len_tail{}, chunk0{};
+    int max_coded = 0, max_nblk = 0, any_tail = 0;
+    for (int b = 0; b < B; ++b) {
+        nblk.v[b] = len.v[b] / blockT;
+        len_coded.v[b] = nblk.v[b] * blockT;
+        len_tail.v[b] = len.v[b] - len_coded.v[b];
+        chunk0.v[b] = len_coded.v[b] / CHUNK_TOKENS;
+        max_coded = len_coded.v[b] > max_coded ? len_coded.v[b] : max_coded;
+        max_nblk = nblk.v[b] > max_nblk ? nblk.v[b] : max_nblk;
+        any_tail |= len_tail.v[b];
+    }
+    const int tiles_all = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    const int tiles_coded = (max_coded + TILE_TOKENS - 1) / TILE_TOKENS;
+    const int chunks_stride = (tiles_all + 1) * (TILE_TOKENS / CHUNK_TOKENS);
+    // workspace carve-up (sizes as in remat_pc_workspace_bytes)
+    float* part_o = static_cast<float*>(ws);
+    float* part_ml = part_o + (size_t)B * a->n_q_heads * chunks_stride * 128;
+    uint8_t* img = reinterpret_cast<uint8_t*>(part_ml + (size_t)B * a->n_q_heads * chunks_stride * 2);
+    float* zw = reinterpret_cast<float*>(img + (size_t)B * tiles_all * (size_t)(d / 128 + 1) * LDS_SCALES_BYTES);
+    const size_t blocks_ws = (size_t)max_len / blockT + 1;
+    float* fscale = zw + (size_t)B * blocks_ws * a->n_kv_heads * 256;
+    int* eblk = reinterpret_cast<int*>(fscale + (size_t)B * blocks_ws);
+
+    RematParams p{};
+    p.q = q;
+    p.B = B; p.Hq = a->n_q_heads; p.Hkv = a->n_kv_heads; p.grid_heads = p.Hkv;
+    p.scale_log2e = a->softmax_scale * 1.44269504088896340736f;
+    p.part_o = part_o; p.part_ml = part_ml; p.chunks_per_seq = chunks_stride;
+    p.d = d; p.row_d = d;
+    hipError_t e = hipSuccess;
+    if (max_nblk > 0) {
+        // block exponents, factor images
+        pc_block_exponent_kernel<<<dim3(max_nblk, B), dim3(256), 0, s>>>(xc->scale, fscale, eblk, d, blocks_cap, (int)blocks_ws, bits, nblk);
+        PcImageArgs ia{xc->scale, eblk, reinterpret_cast<uint16_t*>(img), d, blocks_cap, (int)blocks_ws, blockT, tiles_coded, Lc.n_main_slabs, 128,
+                       nblk, tab};
+        pc_factor_image_kernel<<<dim3(Lc.n_main_slabs, tiles_coded, B), dim3(256), 0, s>>>(ia);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        // z_blk [Wk | Wv]: the dense contraction over the zero-point rows, stored
+        RematParams z = p;
+        z.acc = xc->zero; z.cap = blocks_cap; z.len = nblk;                  // source rows: one per block
+        z.tiles_per_seq = (max_nblk + TILE_TOKENS - 1) / TILE_TOKENS;
+        z.wprep = static_cast<const uint8_t*>(wprep_dense);
+        z.n_main_slabs = Ld.n_main_slabs; z.head_bytes = (long long)Ld.head_bytes;
+        z.kv_out = zw; z.pc_blocks_cap = (int)blocks_ws;                     // destination rows per sequence
+        e = launch_with_lds(remat_attn_dense_kernel<DENSE_STORE>, LDS_DENSE_TOTAL, z, p.Hkv * B * z.tiles_per_seq, s);
+        if (e != hipSuccess) return e;
+        // the coded blocks
+        RematParams m = p;
+        m.codes = xc->codes; m.eT = reinterpret_cast<const uint16_t*>(img);
+        m.cap = cap; m.len = len_coded; m.tiles_per_seq = tiles_coded;
+        m.wprep = static_cast<const uint8_t*>(wprep_coded);
+        m.n_main_slabs = Lc.n_main_slabs; m.n_corr_ksteps = Lc.n_corr_ksteps; m.ng = Lc.ng; m.ng_pad = Lc.ng_pad; m.ng_row = Lc.ng;
+        m.head_bytes = (long long)Lc.head_bytes;
+        m.pc_fscale = fscale; m.pc_zw = zw; m.pc_block = blockT; m.pc_blocks_cap = (int)blocks_ws;
+        const int grid = p.Hkv * B * tiles_coded;
+        switch (bits) {
+            case 2: e = launch_with_lds(remat_attn_coded_kernel<2, 128, MODE_ATTENTION_PC>, lds_coded_total(2), m, grid, s); break;
+            case 3: e = launch_with_lds(remat_attn_coded_kernel<3, 128, MODE_ATTENTION_PC>, lds_coded_total(3), m, grid, s); break;
+            case 4: e = launch_with_lds(remat_attn_coded_kernel<4, 128, MODE_ATTENTION_PC>, lds_coded_total(4), m, grid, s); break;
+            default: e = hipErrorInvalidValue;
+        }
+        if (e != hipSuccess) return e;
+    }
+    if (any_tail) {
+        // the residual window: bf16 rows, dense-source kernel, partial chunks placed after the coded ones
+        RematParams t = p;
+        t.acc = tail; t.cap = blockT; t.len = len_tail; t.tiles_per_seq = 1; t.chunk0 = chunk0;
+        t.wprep = static_cast<const uint8_t*>(wprep_dense);
+        t.n_main_slabs = Ld.n_main_slabs; t.head_bytes = (long long)Ld.head_bytes;
+        e = launch_with_lds(remat_attn_dense_kernel<DENSE_ATTENTION>, LDS_DENSE_TOTAL, t, p.Hkv * B, s);
+        if (e != hipSuccess) return e;
+    }
+    combine_kernel<<<dim3(p.Hq, B), dim3(128 * COMBINE_GROUPS), 0, s>>>(part_o, part_ml, out, p.Hq, chunks_stride, len, 1,
+                                                                      CHUNK_TOKENS);
+    return hipGetLastError();
 }
 
 }  // namespace xq

@@ -67,3 +67,72 @@ def test_block_quantiser_noop_and_errors(xq):
     with pytest.raises(xq.XQError):
         xq.xq_quantize_blocks_per_channel(xq.alloc_cache_per_channel(2, 256, 192, 64, 3),
                                           torch.zeros((2, 64, 192), dtype=torch.bfloat16, device="cuda"), [0, 0])
+
+
+def _attend(xq, w, bits, G, lens, pairs=None, scale_spread=1.0):
+    """Quantise the complete blocks per channel on the GPU, keep the rest in the bf16 window, attend; the
+    oracle attends over the very same cache bytes and window."""
+    x, (wk, wv), q = xi.gen_x(w), xi.gen_weights(w), xi.gen_q(w)
+    if scale_spread != 1.0:                              # channels whose scales differ by many powers of two
+        xf = bf(x).astype(np.float32)
+        xf *= (scale_spread ** np.linspace(-1.0, 1.0, w.d)).astype(np.float32)[None, None, :]
+        x = xi.to_bf16_bits(xf)
+    cap = (w.L + G - 1) // G * G
+    cache = xq.alloc_cache_per_channel(w.B, cap, w.d, G, bits)
+    tail = torch.zeros((w.B, G, w.d), dtype=torch.bfloat16, device="cuda")
+    xt = bits_to_torch(x)
+    for b in range(w.B):
+        nblk, rem = lens[b] // G, lens[b] % G
+        if nblk:
+            sub = xq.XQCache(cache.codes[b:b + 1], cache.scale[b:b + 1], cache.zero[b:b + 1], 1, cap, w.d, G, bits)
+            xq.xq_quantize_blocks_per_channel(sub, xt[b:b + 1, :nblk * G].contiguous(), [0])
+        tail[b, :rem] = xt[b, nblk * G:lens[b]]
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    wpc = xq.xq_prepare_weights(attn, w.d, 128, bits, bits_to_torch(wk), bits_to_torch(wv))
+    wpd = xq.xq_prepare_weights(attn, w.d, 0, 16, bits_to_torch(wk), bits_to_torch(wv))
+    out = xq.xq_remat_attn_decode_per_channel(attn, bits_to_torch(q), cache, tail, lens, wpc, wpd)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    if pairs is None:
+        pairs = [(b, h) for b in range(w.B) for h in range(w.Hq)]
+    ref = xo.remat_attn_pairs_per_channel(q_bf16=q, Wk=wk, Wv=wv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd, softmax_scale=w.hd ** -0.5,
+                                          lens=lens, pairs=pairs, packed=cache.codes.cpu().numpy(),
+                                          scale=torch_to_bits(cache.scale), zero=torch_to_bits(cache.zero), G=G, bits=bits,
+                                          tail_bf16=torch_to_bits(tail))
+    sel = np.array([got[b, h] for b, h in pairs])
+    normwise, maxwise = rel_errors(sel, ref)
+    assert np.all(np.isfinite(got)), w.name
+    assert normwise.max() <= TOL and maxwise <= TOL, (w.name, bits, G, float(normwise.max()), float(maxwise))
+    return float(normwise.max())
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("G", [64, 128])
+def test_attention_blocks_and_window(xq, bits, G):
+    """Several tiles, a sequence ending on a block boundary (empty window), one inside the first block
+    (window only), one with a partial last tile."""
+    w = xi.C2.scaled(B=4, L=700, d=512, Hq=4, Hkv=4, n_outlier=5)
+    _attend(xq, w, bits, G, lens=[700, 512, G - 3, 300])
+
+
+def test_attention_gqa_and_wide_scale_range(xq):
+    w = xi.C4.scaled(B=2, L=400, d=768, Hq=8, Hkv=2)
+    _attend(xq, w, 2, 64, lens=[400, 130])
+    # per-channel scales spread over 2^-10 .. 2^10 within a block: one exponent per block must do
+    w2 = xi.C2.scaled(B=2, L=300, d=512, Hq=4, Hkv=4, n_outlier=0)
+    _attend(xq, w2, 3, 128, lens=[300, 257], scale_spread=1024.0)
+
+
+def test_attention_single_slab_and_window_only(xq):
+    w = xi.C2.scaled(B=2, L=200, d=128, Hq=2, Hkv=2, n_outlier=1)
+    _attend(xq, w, 3, 128, lens=[200, 100])
+    _attend(xq, w, 4, 64, lens=[63, 1])                  # no complete block anywhere: the window alone
+
+
+def test_full_size_llama2_7b_per_channel_sampled_pairs(xq):
+    """Config 2's shape with per-channel groups of 128 tokens, 3-bit, and a window of 77 tokens."""
+    w = xi.C2
+    lens = [w.L - 51] * w.B                              # 31 blocks + 77 window tokens
+    lens[1] = w.L
+    worst = _attend(xq, w, 3, 128, lens, pairs=xi.sample_pairs(w, 8))
+    print(f"c2 per-channel sampled pairs: worst norm-wise rel err {worst:.2e}")
