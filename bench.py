@@ -153,7 +153,26 @@ def main():
         t_chunk = timed(lambda: xq.xq_remat_attn_prefill(attn, q_chunk, wprep, lens, xcache=cache, out=out_chunk,
                                                          workspace=ws_chunk), n=10, warm=5)
         del ws_chunk, out_chunk
+        # the same layer from a per-channel cache (groups of 128 tokens per channel, Sec. 3.3.1) with 77 tokens in
+        # the bf16 residual window, and the block quantiser that fills it
+        pc_cache = xq.alloc_cache_per_channel(w.B, w.L, w.d, 128, w.bits)
+        t_pcq = timed(lambda: xq.xq_quantize_blocks_per_channel(pc_cache, x, [0] * w.B), n=10)
+        pcq_bytes = w.B * w.L * w.d * (2 + w.bits / 8.0)
+        pc_tail = x[:, L - 128:].contiguous()
+        wprep_pc = xq.xq_prepare_weights(attn, w.d, 128, w.bits, dev_bf16(wk_bits), dev_bf16(wv_bits))
+        ws_pc = torch.empty(xq.xq_remat_attn_per_channel_workspace_bytes(attn, w.B, w.L, w.d, 128), dtype=torch.uint8,
+                            device=dev)
+        pc_lens = [w.L - 51] * w.B
+        t_pc = timed(lambda: xq.xq_remat_attn_decode_per_channel(attn, q, pc_cache, pc_tail, pc_lens, wprep_pc, wprep_dense,
+                                                                 out=out, workspace=ws_pc), n=10, warm=5)
+        del pc_cache, ws_pc, wprep_pc, pc_tail
         extra = {
+            "remat_attn_per_channel": {"workload": "c2 shape, per-channel groups of 128 tokens, 3-bit, 31 blocks + 77 window "
+                                                   "tokens per sequence; includes the per-step pre-passes", "ms": t_pc,
+                                       "tokens/s/layer": w.B * (w.L - 51) / (t_pc * 1e-3)},
+            "quantize_blocks_per_channel": {"workload": "xq_quantize_blocks_per_channel, 32 blocks of 128 tokens per sequence",
+                                            "ms": t_pcq, "GB/s": pcq_bytes / t_pcq / 1e6,
+                                            "frac_hbm_peak": pcq_bytes / t_pcq / 1e6 / PEAK_HBM_GBS},
             "remat_attn_prefill_chunk32_ms": t_chunk,
             "quantize_bulk": {"workload": "xq_quantize_append T=4096 (whole context), c2 shape", "ms": t_q,
                               "GB/s": q_bytes / t_q / 1e6, "frac_hbm_peak": q_bytes / t_q / 1e6 / PEAK_HBM_GBS},

@@ -67,7 +67,8 @@
  * bound, attention closed forms (uniform scores, two-token logistic weight,
  * shift/permutation/split invariance) and scipy softmax; for the latent path,
  * numpy matmul in fp64, exactly representable factors whose product must come
- * back bit for bit, and U S B^T = W closing the loop to plain X W.  The absolute
+ * back bit for bit, and U S B^T = W closing the loop to plain X W; for the per-channel
+ * quantiser, the transposed block through the per-token quantiser.  The absolute
  * attention outputs on the synthetic benchmark inputs have no printed value in
  * the paper: for those, parity is pinned only through the chain above.
  */

@@ -246,13 +246,23 @@ __global__ __launch_bounds__(256) void quantize_blocks_per_channel_kernel(
     float mn[16], mx[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) { mn[k] = INFINITY; mx[k] = -INFINITY; }
-    for (int r = wave; r < G; r += 4) {
-        const uint4* xr = x + (row_in0 + r) * (d >> 3);
-        float v[16];
-        unpack8(xr[2 * pc], v);
-        unpack8(xr[2 * pc + 1], v + 8);
+    // (G / 4 rows per wave, G a multiple of 16: four rows' loads are in flight at a time)
+    for (int r0 = wave; r0 < G; r0 += 16) {
+        uint4 raw[4][2];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) { mn[k] = fminf(mn[k], v[k]); mx[k] = fmaxf(mx[k], v[k]); }
+        for (int u = 0; u < 4; ++u) {
+            const uint4* xr = x + (row_in0 + r0 + 4 * u) * (d >> 3);
+            raw[u][0] = xr[2 * pc];
+            raw[u][1] = xr[2 * pc + 1];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float v[16];
+            unpack8(raw[u][0], v);
+            unpack8(raw[u][1], v + 8);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) { mn[k] = fminf(mn[k], v[k]); mx[k] = fmaxf(mx[k], v[k]); }
+        }
     }
 #pragma unroll
     for (int k = 0; k < 16; ++k) { smn[wave][lane][k] = mn[k]; smx[wave][lane][k] = mx[k]; }
@@ -282,19 +292,28 @@ __global__ __launch_bounds__(256) void quantize_blocks_per_channel_kernel(
         uint4* zp = reinterpret_cast<uint4*>(zero + blk_out * d) + 2 * pi;
         sp[0] = s0; sp[1] = s1; zp[0] = z0; zp[1] = z1;
     }
-    for (int r = wave; r < G; r += 4) {
-        const uint4* xr = x + (row_in0 + r) * (d >> 3);
-        float v[16];
-        unpack8(xr[2 * pc], v);
-        unpack8(xr[2 * pc + 1], v + 8);
-        uint32_t q[16];
+    for (int r0 = wave; r0 < G; r0 += 16) {
+        uint4 raw[4][2];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const float n = v[k] - zf[k];
-            const float y = __builtin_fmaf(n, rh[k], n * rl[k]);
-            q[k] = __float_as_uint(__builtin_amdgcn_fmed3f(y + ROUND_MAGIC, ROUND_MAGIC, ROUND_MAGIC + QMAX));
+        for (int u = 0; u < 4; ++u) {
+            const uint4* xr = x + (row_in0 + r0 + 4 * u) * (d >> 3);
+            raw[u][0] = xr[2 * pc];
+            raw[u][1] = xr[2 * pc + 1];
         }
-        pack_store16<BITS>(q, codes + (row_out0 + r) * row_bytes, pi, live);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float v[16];
+            unpack8(raw[u][0], v);
+            unpack8(raw[u][1], v + 8);
+            uint32_t q[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const float n = v[k] - zf[k];
+                const float y = __builtin_fmaf(n, rh[k], n * rl[k]);
+                q[k] = __float_as_uint(__builtin_amdgcn_fmed3f(y + ROUND_MAGIC, ROUND_MAGIC, ROUND_MAGIC + QMAX));
+            }
+            pack_store16<BITS>(q, codes + (row_out0 + r0 + 4 * u) * row_bytes, pi, live);
+        }
     }
 }
 

@@ -158,6 +158,24 @@ def test_argument_errors_of_the_widened_entry_points():
     assert lat_call(wsb=16) == WORKSPACE
     assert lat_call(attn=B._Attn(3, 3, 128, 0.1), c=_cache(d=768, group=128, bits=3)) == UNSUPPORTED   # odd number of KV heads
     assert lat_call(c=_cache(d=384, group=128, bits=3)) == UNSUPPORTED          # latent width not a multiple of 256
+    # per-channel cache: block quantiser and attention
+    pc = lambda **kw: _cache(**dict(dict(cap=256, d=256, group=128, bits=3), **kw))
+    qb = lambda c, nblk=1, b0=0, xx=x: lib.xq_quantize_blocks_per_channel(C.byref(c), xx, nblk, (C.c_int32 * 1)(b0), st)
+    assert qb(pc(), nblk=0) == 0
+    assert qb(pc(), nblk=1, b0=2) == INVALID                                    # past the capacity
+    assert qb(pc(), xx=None) == INVALID
+    assert qb(pc(cap=200)) == INVALID                                           # capacity not a whole number of blocks
+    assert qb(pc(group=32)) == UNSUPPORTED
+    assert qb(pc(d=192)) == UNSUPPORTED
+    pa = lambda c=None, ln=130, tail=x, wsb=1 << 30: lib.xq_remat_attn_decode_per_channel(
+        C.byref(la), x, C.byref(c if c is not None else pc()), tail, (C.c_int32 * 1)(ln), x, x, x, x, wsb, st)
+    assert pa(ln=0) == INVALID
+    assert pa(ln=400) == INVALID                                                # three blocks do not fit a cache of two
+    assert pa(tail=None) == INVALID
+    assert pa(wsb=64) == WORKSPACE
+    assert pa(c=pc(bits=8)) == UNSUPPORTED
+    assert xq.xq_remat_attn_per_channel_workspace_bytes(xq.XQAttn(4, 2, 128, 0.1), 1, 300, 256, 32) == 0
+    assert xq.xq_remat_attn_per_channel_workspace_bytes(xq.XQAttn(4, 2, 128, 0.1), 1, 300, 256, 128) > 0
 
 
 def test_binding_has_no_cpu_fallback():
