@@ -221,116 +221,114 @@ hipError_t run_quantize_append(const xq_cache_t* c, const uint16_t* x, const uin
 }
 
 // ---- per-channel groups (Sec. 3.3.1): a group is one channel over a block of G consecutive tokens.
-// Workgroup = (1024-channel slab, block, sequence), 4 waves; a lane owns 16 consecutive channels,
-// the waves split the block's rows.  Pass 1 reduces min/max per channel (rows in registers, waves
-// through LDS); pass 2 re-reads the rows (1 MB per block: L2) and encodes them with the per-channel
-// scale and zero-point, packing each row exactly as the per-token kernel does.
-template <int BITS>
+// One pass over HBM: a wave owns 64 rows x 128 channels of a block, a lane two adjacent channels,
+// and keeps its column of the piece -- one dword per row -- in 64 registers.  Min/max need no
+// exchange inside the wave; for G = 128 the two waves that share a piece swap theirs through LDS
+// (one barrier).  Zero-point, scale and the codes are then computed per lane; only the packing
+// needs 16 consecutive channels per lane, so the codes go through the wave's own 8 KiB of LDS as
+// bytes ([row][128]) and come back as 8 rows x 8 units of 16 codes per instruction, packed and
+// stored exactly as in the per-token kernel.
+template <int BITS, int G>
 __global__ __launch_bounds__(256) void quantize_blocks_per_channel_kernel(
-    const uint4* __restrict__ x, uint8_t* __restrict__ codes, uint16_t* __restrict__ scale,
-    uint16_t* __restrict__ zero, int nblk, int G, int cap, int d, BatchI32 block0)
+    const uint32_t* __restrict__ x, uint8_t* __restrict__ codes, uint16_t* __restrict__ scale,
+    uint16_t* __restrict__ zero, int nblk, int cap, int d, BatchI32 block0)
 {
-    __shared__ float smn[4][64][17], smx[4][64][17];
+    constexpr int RW = 64;                       // rows per wave
+    constexpr int RSPLIT = G / RW;               // waves per piece (1 or 2)
+    static_assert(G == 64 || G == 128, "block size");
+    __shared__ __attribute__((aligned(16))) uint8_t stage[4][RW * 128];
+    __shared__ float xch[4][4][64];
     constexpr float QMAX = (float)((1 << BITS) - 1);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int piece = blockIdx.x * (4 / RSPLIT) + wave / RSPLIT;              // 128-channel piece of the row
+    const int rhalf = wave % RSPLIT;                                          // which 64 rows of the block
+    const bool active = piece * 128 < d;
+    const int pc = active ? piece : 0;
     const int blk = blockIdx.y, b = blockIdx.z;
-    const int ppr = d >> 4;
-    const int pi = blockIdx.x * 64 + lane;
-    const bool live = pi < ppr;
-    const int pc = live ? pi : ppr - 1;
-    const long long row_in0 = ((long long)b * nblk + blk) * G;              // first input row of the block
-    const long long blk_out = (long long)b * (cap / G) + block0.v[b] + blk;    // block index in the cache
-    const long long row_out0 = (long long)b * cap + (long long)(block0.v[b] + blk) * G;
+    const long long row_in0 = ((long long)b * nblk + blk) * G + rhalf * RW;
+    const long long blk_out = (long long)b * (cap / G) + block0.v[b] + blk;
+    const long long row_out0 = (long long)b * cap + (long long)(block0.v[b] + blk) * G + rhalf * RW;
     const long long row_bytes = (long long)d * BITS / 8;
+    const int dw_per_row = d >> 1;
 
-    float mn[16], mx[16];
+    uint32_t raw[RW];
+    const uint32_t* src = x + row_in0 * dw_per_row + pc * 64 + lane;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) { mn[k] = INFINITY; mx[k] = -INFINITY; }
-    // (G / 4 rows per wave, G a multiple of 16: four rows' loads are in flight at a time)
-    for (int r0 = wave; r0 < G; r0 += 16) {
-        uint4 raw[4][2];
+    for (int r = 0; r < RW; ++r) raw[r] = src[(long long)r * dw_per_row];
+    float mn0 = bf16_lo_to_f32(raw[0]), mx0 = mn0, mn1 = bf16_hi_to_f32(raw[0]), mx1 = mn1;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint4* xr = x + (row_in0 + r0 + 4 * u) * (d >> 3);
-            raw[u][0] = xr[2 * pc];
-            raw[u][1] = xr[2 * pc + 1];
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            float v[16];
-            unpack8(raw[u][0], v);
-            unpack8(raw[u][1], v + 8);
-#pragma unroll
-            for (int k = 0; k < 16; ++k) { mn[k] = fminf(mn[k], v[k]); mx[k] = fmaxf(mx[k], v[k]); }
-        }
+    for (int r = 1; r < RW; r += 2) {
+        const float a0 = bf16_lo_to_f32(raw[r]), a1 = bf16_hi_to_f32(raw[r]);
+        const float b0 = r + 1 < RW ? bf16_lo_to_f32(raw[r + 1]) : a0, b1 = r + 1 < RW ? bf16_hi_to_f32(raw[r + 1]) : a1;
+        mn0 = fminf(fminf(mn0, a0), b0); mx0 = fmaxf(fmaxf(mx0, a0), b0);
+        mn1 = fminf(fminf(mn1, a1), b1); mx1 = fmaxf(fmaxf(mx1, a1), b1);
     }
-#pragma unroll
-    for (int k = 0; k < 16; ++k) { smn[wave][lane][k] = mn[k]; smx[wave][lane][k] = mx[k]; }
-    __syncthreads();
-    float zf[16], rh[16], rl[16];
-    uint32_t zb[16], sb[16];
-#pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        float a = smn[0][lane][k], c = smx[0][lane][k];
-#pragma unroll
-        for (int w = 1; w < 4; ++w) { a = fminf(a, smn[w][lane][k]); c = fmaxf(c, smx[w][lane][k]); }
-        uint32_t z = f32_to_bf16_rne(a);
-        z = (z & 0x7FFFu) ? z : 0u;                       // -0 -> +0
-        const float step = (c - a) / QMAX;                // IEEE divide
-        const uint32_t sbits = f32_to_bf16_rne(step);
-        const GroupRecip rr = make_recip(bf16_bits_to_f32(sbits));
-        zb[k] = z; sb[k] = sbits;
-        zf[k] = bf16_bits_to_f32(z); rh[k] = rr.rh; rl[k] = rr.rl;
+    if constexpr (RSPLIT == 2) {
+        xch[wave][0][lane] = mn0; xch[wave][1][lane] = mx0; xch[wave][2][lane] = mn1; xch[wave][3][lane] = mx1;
+        __syncthreads();
+        mn0 = fminf(mn0, xch[wave ^ 1][0][lane]); mx0 = fmaxf(mx0, xch[wave ^ 1][1][lane]);
+        mn1 = fminf(mn1, xch[wave ^ 1][2][lane]); mx1 = fmaxf(mx1, xch[wave ^ 1][3][lane]);
     }
-    if (wave == 0 && live) {
-        uint4 s0, s1, z0, z1;
-        s0.x = sb[0] | (sb[1] << 16); s0.y = sb[2] | (sb[3] << 16); s0.z = sb[4] | (sb[5] << 16); s0.w = sb[6] | (sb[7] << 16);
-        s1.x = sb[8] | (sb[9] << 16); s1.y = sb[10] | (sb[11] << 16); s1.z = sb[12] | (sb[13] << 16); s1.w = sb[14] | (sb[15] << 16);
-        z0.x = zb[0] | (zb[1] << 16); z0.y = zb[2] | (zb[3] << 16); z0.z = zb[4] | (zb[5] << 16); z0.w = zb[6] | (zb[7] << 16);
-        z1.x = zb[8] | (zb[9] << 16); z1.y = zb[10] | (zb[11] << 16); z1.z = zb[12] | (zb[13] << 16); z1.w = zb[14] | (zb[15] << 16);
-        uint4* sp = reinterpret_cast<uint4*>(scale + blk_out * d) + 2 * pi;
-        uint4* zp = reinterpret_cast<uint4*>(zero + blk_out * d) + 2 * pi;
-        sp[0] = s0; sp[1] = s1; zp[0] = z0; zp[1] = z1;
+    if (!active) return;                                                      // (after the only barrier)
+    uint32_t z0 = f32_to_bf16_rne(mn0), z1 = f32_to_bf16_rne(mn1);
+    z0 = (z0 & 0x7FFFu) ? z0 : 0u;                                            // -0 -> +0
+    z1 = (z1 & 0x7FFFu) ? z1 : 0u;
+    const uint32_t s0 = f32_to_bf16_rne((mx0 - mn0) / QMAX), s1 = f32_to_bf16_rne((mx1 - mn1) / QMAX);   // IEEE divides
+    const float zf0 = bf16_bits_to_f32(z0), zf1 = bf16_bits_to_f32(z1);
+    const GroupRecip r0 = make_recip(bf16_bits_to_f32(s0)), r1 = make_recip(bf16_bits_to_f32(s1));
+    if (rhalf == 0) {
+        reinterpret_cast<uint32_t*>(scale + blk_out * d)[piece * 64 + lane] = s0 | (s1 << 16);
+        reinterpret_cast<uint32_t*>(zero + blk_out * d)[piece * 64 + lane] = z0 | (z1 << 16);
     }
-    for (int r0 = wave; r0 < G; r0 += 16) {
-        uint4 raw[4][2];
+
+    uint8_t* mine = stage[wave];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint4* xr = x + (row_in0 + r0 + 4 * u) * (d >> 3);
-            raw[u][0] = xr[2 * pc];
-            raw[u][1] = xr[2 * pc + 1];
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            float v[16];
-            unpack8(raw[u][0], v);
-            unpack8(raw[u][1], v + 8);
-            uint32_t q[16];
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const float n = v[k] - zf[k];
-                const float y = __builtin_fmaf(n, rh[k], n * rl[k]);
-                q[k] = __float_as_uint(__builtin_amdgcn_fmed3f(y + ROUND_MAGIC, ROUND_MAGIC, ROUND_MAGIC + QMAX));
-            }
-            pack_store16<BITS>(q, codes + (row_out0 + r0 + 4 * u) * row_bytes, pi, live);
-        }
+    for (int r = 0; r < RW; ++r) {
+        const float n0 = bf16_lo_to_f32(raw[r]) - zf0, n1 = bf16_hi_to_f32(raw[r]) - zf1;
+        const float y0 = __builtin_fmaf(n0, r0.rh, n0 * r0.rl), y1 = __builtin_fmaf(n1, r1.rh, n1 * r1.rl);
+        const uint32_t q0 = __float_as_uint(__builtin_amdgcn_fmed3f(y0 + ROUND_MAGIC, ROUND_MAGIC, ROUND_MAGIC + QMAX));
+        const uint32_t q1 = __float_as_uint(__builtin_amdgcn_fmed3f(y1 + ROUND_MAGIC, ROUND_MAGIC, ROUND_MAGIC + QMAX));
+        reinterpret_cast<uint16_t*>(mine + r * 128)[lane] = (uint16_t)((q0 & 0xFFu) | (q1 << 8));
     }
+    __builtin_amdgcn_wave_barrier();
+    // packing: lane = (row r8 + lane / 8, unit lane % 8 of 16 codes)
+    const int unit = lane & 7, sub = lane >> 3;
+#pragma unroll 2
+    for (int r8 = 0; r8 < RW; r8 += 8) {
+        const int r = r8 + sub;
+        const uint4 cw = *reinterpret_cast<const uint4*>(mine + r * 128 + unit * 16);
+        const uint32_t w4[4] = {cw.x, cw.y, cw.z, cw.w};
+        uint32_t q[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) q[k] = ((w4[k >> 2] >> (8 * (k & 3))) & 0xFFu) | ROUND_MAGIC_BITS;
+        pack_store16<BITS>(q, codes + (row_out0 + r) * row_bytes, piece * 8 + unit, true);
+    }
+}
+
+template <int BITS>
+static hipError_t launch_blocks_pc(const xq_cache_t* c, const uint16_t* x, int nblk, const BatchI32& block0, hipStream_t s)
+{
+    const int d = c->fmt.d;
+    const int ppw = c->fmt.group == 64 ? 4 : 2;                       // 128-channel pieces per workgroup
+    const dim3 grid((unsigned)((d / 128 + ppw - 1) / ppw), (unsigned)nblk, (unsigned)c->B);
+    const uint32_t* xp = reinterpret_cast<const uint32_t*>(x);
+    if (c->fmt.group == 64)
+        quantize_blocks_per_channel_kernel<BITS, 64><<<grid, dim3(256), 0, s>>>(xp, c->codes, c->scale, c->zero, nblk, c->cap, d, block0);
+    else
+        quantize_blocks_per_channel_kernel<BITS, 128><<<grid, dim3(256), 0, s>>>(xp, c->codes, c->scale, c->zero, nblk, c->cap, d, block0);
+    return hipGetLastError();
 }
 
 hipError_t run_quantize_blocks_per_channel(const xq_cache_t* c, const uint16_t* x, int nblk, const BatchI32& block0,
                                            hipStream_t s)
 {
-    const int d = c->fmt.d, G = c->fmt.group;
-    const dim3 grid((unsigned)((d / 16 + 63) / 64), (unsigned)nblk, (unsigned)c->B);
-    const uint4* xp = reinterpret_cast<const uint4*>(x);
     switch (c->fmt.bits) {
-        case 2: quantize_blocks_per_channel_kernel<2><<<grid, dim3(256), 0, s>>>(xp, c->codes, c->scale, c->zero, nblk, G, c->cap, d, block0); break;
-        case 3: quantize_blocks_per_channel_kernel<3><<<grid, dim3(256), 0, s>>>(xp, c->codes, c->scale, c->zero, nblk, G, c->cap, d, block0); break;
-        case 4: quantize_blocks_per_channel_kernel<4><<<grid, dim3(256), 0, s>>>(xp, c->codes, c->scale, c->zero, nblk, G, c->cap, d, block0); break;
-        case 8: quantize_blocks_per_channel_kernel<8><<<grid, dim3(256), 0, s>>>(xp, c->codes, c->scale, c->zero, nblk, G, c->cap, d, block0); break;
-        default: return hipErrorInvalidValue;
+        case 2: return launch_blocks_pc<2>(c, x, nblk, block0, s);
+        case 3: return launch_blocks_pc<3>(c, x, nblk, block0, s);
+        case 4: return launch_blocks_pc<4>(c, x, nblk, block0, s);
+        case 8: return launch_blocks_pc<8>(c, x, nblk, block0, s);
     }
-    return hipGetLastError();
+    return hipErrorInvalidValue;
 }
 
 }  // namespace xq
