@@ -300,7 +300,8 @@ xq_status_t xq_quantize_blocks_per_channel(const xq_cache_t *cache, const uint16
  *                zero-point term (the zero-points of a block times [Wk | Wv], one row per block)
  *   workspace    dev, xq_remat_attn_per_channel_workspace_bytes(a, B, max len, d, group) bytes
  * The per-channel scales enter the contraction on the token operand (one packed fp16 multiply per
- * operand dword): exact for 2- and 3-bit codes, rounded at 2^-12 relative for 4-bit codes.
+ * operand dword), exactly: an 8-bit significand times a 2- or 3-bit code fits fp16, and 4-bit codes
+ * enter as code - 8 (the block-constant remainder joins the zero-point term).
  */
 size_t      xq_remat_attn_per_channel_workspace_bytes(const xq_attn_t *a, int32_t B, int32_t max_len,
                                                       int32_t d, int32_t group);
@@ -309,6 +310,36 @@ xq_status_t xq_remat_attn_decode_per_channel(const xq_attn_t *a, const uint16_t 
                                              const int32_t *len, const void *wprep_coded,
                                              const void *wprep_dense, float *out, void *workspace,
                                              size_t workspace_bytes, void *stream);
+
+/*
+ * The setting Sec. 3.3.1 finds best for grouped-query models: X Uk quantised per channel (with its
+ * residual window), X Uv per token, each in a cache of its own of width r = n_kv_heads*head_dim.
+ *
+ * xq_prepare_weights_pairs: prepared stream of ONE fused latent matrix Wf = S B^T, dev [r][n_kv_heads*head_dim]
+ *   bf16, whose "head" is a pair of KV heads (as each half of xq_prepare_weights_latent); src_bits 2, 3, 4
+ *   (with group 64 or 128) or 16 (group ignored); out dev, xq_prepared_weights_pairs_bytes(...) bytes.
+ *
+ * xq_remat_attn_decode_latent_per_channel: decode attention over len[b] tokens,
+ *   kcache      per-channel cache of X Uk (fmt.d = r): its floor(len[b]/group) complete blocks are read
+ *   ktail_bf16  dev [B][kcache group][r] bf16: the window, rows 0 .. len[b] % group - 1
+ *   vcache      per-token cache of X Uv (fmt.d = r), rows 0 .. len[b]-1
+ *   wk_coded    xq_prepare_weights_pairs(a, r, 128, kcache bits, Sk Bk^T)
+ *   wk_dense    xq_prepare_weights_pairs(a, r, 0, 16, Sk Bk^T)
+ *   wv_coded    xq_prepare_weights_pairs(a, r, vcache group, vcache bits, Sv Bv^T)
+ *   workspace   xq_remat_attn_latent_per_channel_workspace_bytes(a, B, max len, r, kcache group, vcache group)
+ * Two passes as xq_remat_attn_decode_latent; pass 1 takes the keys as xq_remat_attn_decode_per_channel does.
+ */
+size_t      xq_prepared_weights_pairs_bytes(const xq_attn_t *a, int32_t r, int32_t group, int32_t src_bits);
+xq_status_t xq_prepare_weights_pairs(const xq_attn_t *a, int32_t r, int32_t group, int32_t src_bits,
+                                     const uint16_t *Wf, void *out, size_t out_bytes, void *stream);
+size_t      xq_remat_attn_latent_per_channel_workspace_bytes(const xq_attn_t *a, int32_t B, int32_t max_len,
+                                                             int32_t r, int32_t k_group, int32_t v_group);
+xq_status_t xq_remat_attn_decode_latent_per_channel(const xq_attn_t *a, const uint16_t *q_bf16,
+                                                    const xq_cache_t *kcache, const uint16_t *ktail_bf16,
+                                                    const xq_cache_t *vcache, const void *wk_coded,
+                                                    const void *wk_dense, const void *wv_coded,
+                                                    const int32_t *len, float *out, void *workspace,
+                                                    size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -289,6 +289,36 @@ def remat_attn_pairs_per_channel(*, q_bf16, Wk, Wv, Hq, Hkv, hd, softmax_scale, 
     return out
 
 
+def latent_attn_pairs_per_channel(*, q_bf16, Wfk, Wfv, Hq, Hkv, hd, softmax_scale, lens, pairs,
+                                  k_packed, k_scale, k_zero, k_G, k_bits, k_tail_bf16,
+                                  v_packed, v_scale, v_zero, v_G, v_bits):
+    """Sec. 3.3.1's setting for grouped-query models: keys from a per-channel cache of X Uk (complete blocks
+    of k_G tokens, the rest in the bf16 window k_tail) through Wfk = Sk Bk^T, values from a per-token cache
+    of X Uv through Wfv = Sv Bv^T.  Composition of pinned pieces only.  Returns [npairs][hd] fp32."""
+    q = _c(q_bf16, np.uint16)
+    r = Wfk.shape[0]
+    g = Hq // Hkv
+    out = np.empty((len(pairs), hd), np.float32)
+    cache = {}
+    for i, (b, hq) in enumerate(pairs):
+        if b not in cache:
+            n = int(lens[b])
+            nblk, rem = n // k_G, n % k_G
+            coded = np.empty((0, r), np.float32)
+            if nblk:
+                coded = dequantize_blocks_per_channel(unpack_rows(_c(k_packed, np.uint8)[b, :nblk * k_G], r, k_bits),
+                                                      k_scale[b, :nblk], k_zero[b, :nblk], k_G)
+            xk = np.concatenate([coded, bf16_to_f32(_c(k_tail_bf16, np.uint16)[b, :rem])], axis=0)
+            xv = dequantize_rows(unpack_rows(_c(v_packed, np.uint8)[b, :n], r, v_bits), v_scale[b, :n], v_zero[b, :n], v_G)
+            cache[b] = (xk, xv)
+        xk, xv = cache[b]
+        hk = hq // g
+        K = remat_head(xk, Wfk, hk * hd, hd)
+        V = remat_head(xv, Wfv, hk * hd, hd)
+        out[i] = attention(q[b, hq], K, V, softmax_scale)
+    return out
+
+
 def prefill_attn_triples(*, q_bf16, lens, triples, **kw):
     """Causal attention of the T newest tokens of every sequence (chunked prefill; T = 1 is the
     decode step): q_bf16 [B][T][Hq][hd]; query t of sequence b sits at cache row lens[b] - T + t

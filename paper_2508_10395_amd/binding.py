@@ -28,6 +28,8 @@ SYMBOLS = [
     "xq_remat_attn_prefill_workspace_bytes", "xq_remat_attn_prefill",
     "xq_quantize_blocks_per_channel",
     "xq_remat_attn_per_channel_workspace_bytes", "xq_remat_attn_decode_per_channel",
+    "xq_prepared_weights_pairs_bytes", "xq_prepare_weights_pairs",
+    "xq_remat_attn_latent_per_channel_workspace_bytes", "xq_remat_attn_decode_latent_per_channel",
 ]
 
 
@@ -137,6 +139,19 @@ def load_library():
     lib.xq_remat_attn_decode_per_channel.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
                                                      C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_void_p,
                                                      C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xq_prepared_weights_pairs_bytes.restype = C.c_size_t
+    lib.xq_prepared_weights_pairs_bytes.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32]
+    lib.xq_prepare_weights_pairs.restype = C.c_int
+    lib.xq_prepare_weights_pairs.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                             C.c_size_t, C.c_void_p]
+    lib.xq_remat_attn_latent_per_channel_workspace_bytes.restype = C.c_size_t
+    lib.xq_remat_attn_latent_per_channel_workspace_bytes.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32,
+                                                                     C.c_int32, C.c_int32]
+    lib.xq_remat_attn_decode_latent_per_channel.restype = C.c_int
+    lib.xq_remat_attn_decode_latent_per_channel.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
+                                                            C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p,
+                                                            C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_size_t,
+                                                            C.c_void_p]
     _LIB = lib
     return lib
 
@@ -493,4 +508,50 @@ def xq_remat_attn_decode_per_channel(attn, q_bf16, cache, tail_bf16, lens, wprep
                                                            _i32(lens, cache.B), _ptr(wprep_coded), _ptr(wprep_dense),
                                                            _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
            "xq_remat_attn_decode_per_channel")
+    return out
+
+
+def xq_prepared_weights_pairs_bytes(attn, r, group, src_bits):
+    a = attn.c_struct()
+    return load_library().xq_prepared_weights_pairs_bytes(C.byref(a), r, group, src_bits)
+
+
+def xq_prepare_weights_pairs(attn, r, group, src_bits, Wf, out=None):
+    """Prepared stream of one fused latent matrix Wf [r][Hkv*hd] bf16 with a pair of KV heads per "head"."""
+    assert Wf.dtype == torch.bfloat16 and Wf.is_contiguous()
+    nbytes = xq_prepared_weights_pairs_bytes(attn, r, group, src_bits)
+    if nbytes == 0:
+        raise XQError("xq_prepare_weights_pairs: unsupported combination")
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=Wf.device)
+    a = attn.c_struct()
+    _check(load_library().xq_prepare_weights_pairs(C.byref(a), r, group, src_bits, _ptr(Wf), _ptr(out), out.numel(),
+                                                   _stream()), "xq_prepare_weights_pairs")
+    return out
+
+
+def xq_remat_attn_latent_per_channel_workspace_bytes(attn, B, max_len, r, k_group, v_group):
+    a = attn.c_struct()
+    return load_library().xq_remat_attn_latent_per_channel_workspace_bytes(C.byref(a), B, max_len, r, k_group, v_group)
+
+
+def xq_remat_attn_decode_latent_per_channel(attn, q_bf16, kcache, ktail_bf16, vcache, wk_coded, wk_dense, wv_coded, lens,
+                                            out=None, workspace=None):
+    """Decode attention from a per-channel X Uk cache (+ bf16 window) and a per-token X Uv cache (Sec. 3.3.1)."""
+    assert q_bf16.dtype == torch.bfloat16 and q_bf16.is_contiguous()
+    assert ktail_bf16.dtype == torch.bfloat16 and ktail_bf16.is_contiguous()
+    assert tuple(ktail_bf16.shape) == (kcache.B, kcache.group, kcache.d)
+    lens = [int(v) for v in lens]
+    a = attn.c_struct()
+    ks, vs = kcache.c_struct(), vcache.c_struct()
+    need = xq_remat_attn_latent_per_channel_workspace_bytes(attn, kcache.B, max(lens) if lens else 1, kcache.d,
+                                                            kcache.group, vcache.group)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q_bf16.device)
+    if out is None:
+        out = torch.empty((kcache.B, attn.n_q_heads, attn.head_dim), dtype=torch.float32, device=q_bf16.device)
+    _check(load_library().xq_remat_attn_decode_latent_per_channel(
+        C.byref(a), _ptr(q_bf16), C.byref(ks), _ptr(ktail_bf16), C.byref(vs), _ptr(wk_coded), _ptr(wk_dense),
+        _ptr(wv_coded), _i32(lens, kcache.B), _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
+        "xq_remat_attn_decode_latent_per_channel")
     return out

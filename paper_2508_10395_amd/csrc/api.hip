@@ -30,6 +30,11 @@ size_t remat_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int d, int 
 hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc, const uint16_t* tail,
                                     const void* wprep_coded, const void* wprep_dense, const BatchI32& len, int max_len,
                                     float* out, void* ws, hipStream_t s);
+size_t remat_latent_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int r, int block, int v_group);
+hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* kc,
+                                           const uint16_t* ktail, const xq_cache_t* vc, const void* wk_coded,
+                                           const void* wk_dense, const void* wv_coded, const BatchI32& len, int max_len,
+                                           float* out, void* ws, hipStream_t s);
 size_t remat_prefill_workspace_bytes(int B, int T, int Hq, int max_len, int d, int group, bool coded);
 hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, const xq_cache_t* xc,
                                   const uint16_t* acc, int B, int cap, int d, const void* wprep,
@@ -412,6 +417,74 @@ xq_status_t xq_remat_attn_decode_per_channel(const xq_attn_t* a, const uint16_t*
         return XQ_ERR_WORKSPACE;
     hipError_t e = run_remat_attn_decode_pc(a, q_bf16, cache, tail_bf16, wprep_coded, wprep_dense, lv, max_len, out,
                                             workspace, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+// one fused latent matrix (Sec. 3.3.1) as a prepared stream whose "head" is a pair of KV heads
+static bool pairs_combo_ok(const xq_attn_t* a, int r, int group, int src_bits)
+{
+    return r > 0 && r % 128 == 0 && a->n_kv_heads % 2 == 0 && wprep_combo_ok(r, group, src_bits);
+}
+
+size_t xq_prepared_weights_pairs_bytes(const xq_attn_t* a, int32_t r, int32_t group, int32_t src_bits)
+{
+    if (check_attn(a) != XQ_OK || !pairs_combo_ok(a, r, group, src_bits)) return 0;
+    return make_wprep_layout(r, src_bits == 16 ? 128 : group, src_bits, a->n_kv_heads / 2).total_bytes;
+}
+
+xq_status_t xq_prepare_weights_pairs(const xq_attn_t* a, int32_t r, int32_t group, int32_t src_bits, const uint16_t* Wf,
+                                     void* out, size_t out_bytes, void* stream)
+{
+    xq_status_t st = check_attn(a);
+    if (st != XQ_OK) return st;
+    if (!Wf || !out || !aligned16(Wf) || !aligned16(out) || r <= 0) return XQ_ERR_INVALID_ARG;
+    if (!pairs_combo_ok(a, r, group, src_bits)) return XQ_ERR_UNSUPPORTED;
+    const WPrepLayout L = make_wprep_layout(r, src_bits == 16 ? 128 : group, src_bits, a->n_kv_heads / 2);
+    if (out_bytes < L.total_bytes) return XQ_ERR_WORKSPACE;
+    hipError_t e = run_prepare_weights(L, Wf, Wf + 128, a->n_kv_heads * 128, 256, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+size_t xq_remat_attn_latent_per_channel_workspace_bytes(const xq_attn_t* a, int32_t B, int32_t max_len, int32_t r,
+                                                        int32_t k_group, int32_t v_group)
+{
+    if (check_attn(a) != XQ_OK || B < 1 || max_len < 1 || r <= 0 || r % 128 != 0 || a->n_kv_heads % 2 != 0) return 0;
+    if ((k_group != 64 && k_group != 128) || (v_group != 64 && v_group != 128)) return 0;
+    return remat_latent_pc_workspace_bytes(B, a->n_q_heads, a->n_kv_heads, max_len, r, k_group, v_group);
+}
+
+xq_status_t xq_remat_attn_decode_latent_per_channel(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* kcache,
+                                                    const uint16_t* ktail_bf16, const xq_cache_t* vcache,
+                                                    const void* wk_coded, const void* wk_dense, const void* wv_coded,
+                                                    const int32_t* len, float* out, void* workspace, size_t workspace_bytes,
+                                                    void* stream)
+{
+    xq_status_t st = check_attn(a);
+    if (st != XQ_OK) return st;
+    st = check_cache_per_channel(kcache);
+    if (st != XQ_OK) return st;
+    st = check_cache(vcache);
+    if (st != XQ_OK) return st;
+    if (kcache->fmt.bits == 8 || vcache->fmt.bits == 8 || a->n_kv_heads % 2 != 0) return XQ_ERR_UNSUPPORTED;
+    if (vcache->fmt.d != kcache->fmt.d || vcache->B != kcache->B) return XQ_ERR_INVALID_ARG;
+    if (!pairs_combo_ok(a, vcache->fmt.d, vcache->fmt.group, vcache->fmt.bits)) return XQ_ERR_UNSUPPORTED;
+    if (!q_bf16 || !ktail_bf16 || !len || !wk_coded || !wk_dense || !wv_coded || !out || !workspace) return XQ_ERR_INVALID_ARG;
+    if (!aligned16(q_bf16) || !aligned16(ktail_bf16) || !aligned16(wk_coded) || !aligned16(wk_dense) || !aligned16(wv_coded) ||
+        !aligned16(out) || !aligned16(workspace))
+        return XQ_ERR_INVALID_ARG;
+    BatchI32 lv{};
+    int max_len = 0;
+    for (int b = 0; b < kcache->B; ++b) {
+        if (len[b] < 1 || len[b] > vcache->cap || (len[b] / kcache->fmt.group) * kcache->fmt.group > kcache->cap)
+            return XQ_ERR_INVALID_ARG;
+        lv.v[b] = len[b];
+        if (len[b] > max_len) max_len = len[b];
+    }
+    if (workspace_bytes < xq_remat_attn_latent_per_channel_workspace_bytes(a, kcache->B, max_len, kcache->fmt.d,
+                                                                           kcache->fmt.group, vcache->fmt.group))
+        return XQ_ERR_WORKSPACE;
+    hipError_t e = run_remat_attn_decode_latent_pc(a, q_bf16, kcache, ktail_bf16, vcache, wk_coded, wk_dense, wv_coded, lv,
+                                                   max_len, out, workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 

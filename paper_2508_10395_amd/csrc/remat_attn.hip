@@ -90,7 +90,9 @@ struct RematParams {
     int B, cap, d, Hq, Hkv;
     int row_d, ng_row;       // coded source: channels / groups per cache row (>= d, ng when a sub-range is contracted)
     int grid_heads;          // heads (or head pairs) the grid is laid over
-    float* scores;           // latent passes: q.K * scale * log2(e), [B][Hq][tiles_per_seq * 256]
+    float* scores;           // latent passes: q.K * scale * log2(e), [B][Hq][score_stride]
+    int score_stride;        // floats per (sequence, query head) in scores
+    BatchI32 tok0;           // pass 1: token index of this launch's row 0 in scores (0 unless a launch continues another)
     int tiles_per_seq, chunks_per_seq;
     int n_main_slabs, n_corr_ksteps, ng, ng_pad;
     long long head_bytes;
@@ -101,8 +103,11 @@ struct RematParams {
     BatchI32 chunk0;         // first partial-chunk index of each sequence in this launch (0 unless a launch continues another)
     // per-channel source (groups along the token axis): factor images, per-block scale and z W rows
     const float* pc_fscale;  // [B][pc_blocks_cap]: 2^(E_blk + bits - 1)
-    const float* pc_zw;      // [B][pc_blocks_cap][Hkv][256] fp32: zero-points of the block times [Wk_h | Wv_h]
-    float* kv_out;           // dense store mode: [B][pc_blocks_cap][Hkv][256] fp32 rows of [K_h | V_h]
+    const float* pc_zw;      // [B][pc_blocks_cap][grid_heads][256] fp32: zero-points of the block times the head's 256 columns
+                             //   (4-bit codes: plus 8 times the scales of the block times those columns)
+    float store_scale;       // dense store mode: kv_out = (store_add ? kv_out : 0) + store_scale * row
+    int store_add;
+    float* kv_out;           // dense store mode: [B][pc_blocks_cap][grid_heads][256] fp32 rematerialised rows
     int pc_block, pc_blocks_cap;   // tokens per block (64 or 128), blocks per sequence in the arrays above
     const float* rope;       // optional [n_pos][64][2] cos, sin: rotate the keys (half-split pairs)
     BatchI32 pos0;           // with rope: position of cache row 0 of each sequence
@@ -493,7 +498,8 @@ __device__ __forceinline__ void scores_epilogue(const RematParams& p, const Tile
 {
     if (c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS >= c.len) return;
     const int gq = p.Hq / p.Hkv;
-    const long long srow = (long long)p.tiles_per_seq * TILE_TOKENS;
+    const long long srow = p.score_stride;
+    const int tok_out = p.tok0.v[c.b] + c.tok;
     static_for<0, 2>([&](auto HH) XQ_INLINE_LAMBDA {       // (compile-time: the accumulator must stay in registers)
         constexpr int hh = decltype(HH)::value;
         for (int j = 0; j < gq; ++j) {
@@ -512,7 +518,7 @@ __device__ __forceinline__ void scores_epilogue(const RematParams& p, const Tile
                     dot = __builtin_fmaf(bf16_hi_to_f32(qq.y), a[i4 * 4 + 3], dot);
                 }
             const float sc = (dot + __shfl_xor(dot, 32)) * p.scale_log2e;
-            if (c.half == 0) p.scores[((long long)c.b * p.Hq + hq) * srow + c.tok] = sc;
+            if (c.half == 0 && c.tok < c.len) p.scores[((long long)c.b * p.Hq + hq) * srow + tok_out] = sc;
         }
     });
 }
@@ -523,7 +529,7 @@ __device__ __forceinline__ void weighted_sum_epilogue(const RematParams& p, cons
     if (c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS >= c.len) return;
     const int gq = p.Hq / p.Hkv;
     const int chunk = c.tile * (TILE_TOKENS / CHUNK_TOKENS) + c.wave;
-    const long long srow = (long long)p.tiles_per_seq * TILE_TOKENS;
+    const long long srow = p.score_stride;
     static_for<0, 2>([&](auto HH) XQ_INLINE_LAMBDA {
         constexpr int hh = decltype(HH)::value;
         for (int j = 0; j < gq; ++j) {
@@ -615,13 +621,17 @@ __device__ __forceinline__ void accumulate_epilogue(const RematParams& p, const 
 }
 
 constexpr int MODE_ATTENTION = 0, MODE_SCORES = 1, MODE_WEIGHTED_SUM = 2, MODE_ACCUMULATE = 3, MODE_PREFILL = 4,
-              MODE_ATTENTION_PC = 5;
+              MODE_ATTENTION_PC = 5, MODE_SCORES_PC = 6;
 
 // packed fp16 multiply of two operand dwords (v_pk_mul_f16; fp16 subnormals are honoured)
 typedef _Float16 xq_f16x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pk_mul_f16(uint32_t a, uint32_t b)
 {
     return __builtin_bit_cast(uint32_t, __builtin_bit_cast(xq_f16x2, a) * __builtin_bit_cast(xq_f16x2, b));
+}
+__device__ __forceinline__ uint32_t pk_add_f16(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(xq_f16x2, a) + __builtin_bit_cast(xq_f16x2, b));
 }
 
 // =====================================================================================
@@ -638,7 +648,8 @@ __device__ __forceinline__ uint32_t pk_mul_f16(uint32_t a, uint32_t b)
 // block of 64 or 128 tokens).  The scale now varies along the contraction, so it moves to the token
 // operand: each unpacked operand dword is multiplied (packed fp16) by the block's factors
 // scale * 2^(15 - E_blk) of its two channels -- an 8-bit significand times a code of at most 3 bits
-// is exact in fp16 (4-bit codes round at 2^-12), and one exponent per block suffices because fp16
+// is exact in fp16 (4-bit codes enter as code - 8, which makes their products exact too: the
+// block-constant 8 * scale term joins the zero-point term), and one exponent per block suffices because fp16
 // subnormals keep an absolute precision of 2^-24 against the block's largest scale.  All tokens of
 // a wave lie in one block, so the factors come from a small LDS image (one per slab, three
 // rotating buffers) by broadcast reads.  There is no Horner rescale and no correction phase; the
@@ -656,7 +667,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     constexpr int IMG_BYTES = code_image_bytes(BITS);
     constexpr int NIMG = n_code_images(BITS);
     constexpr int LDS_SCALES_OFF = lds_scales_off(BITS);
-    constexpr bool PC = MODE == MODE_ATTENTION_PC;     // per-channel source: factors on the token operand
+    constexpr bool PC = MODE == MODE_ATTENTION_PC || MODE == MODE_SCORES_PC;   // per-channel source: factors on the token operand
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     TileCtx c;
@@ -750,6 +761,15 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     const uint8_t* my_factors = lds + LDS_SCALES_OFF + (PC ? ((wave * CHUNK_TOKENS) / p.pc_block) * 256 + half * 16 : 0);
     auto scale_frag = [&](uint32_t* frag, int sbuf, int ks) {
         const uint4 f = *reinterpret_cast<const uint4*>(my_factors + sbuf * LDS_SCALES_BYTES + ks * 32);
+        if constexpr (BITS == 4) {
+            // a 4-bit code times an 8-bit significand needs 12 bits; (code - 8) times it needs 11 and is exact in
+            // fp16.  All 4-bit fields sit at mantissa offset 6, so 8 is the subnormal 2^-15 in both halves; the
+            // 8 * scale * W that this takes out is the same for every token of the block and comes back with
+            // the zero-point term.
+            constexpr uint32_t MINUS_EIGHT = 0x82008200u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) frag[i] = pk_add_f16(frag[i], MINUS_EIGHT);
+        }
         frag[0] = pk_mul_f16(frag[0], f.x);
         frag[1] = pk_mul_f16(frag[1], f.y);
         frag[2] = pk_mul_f16(frag[2], f.z);
@@ -1031,7 +1051,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         const int blk = min((c.tile * TILE_TOKENS + wave * CHUNK_TOKENS) / p.pc_block, (c.len - 1) / p.pc_block);
         const long long brow = (long long)c.b * p.pc_blocks_cap + blk;
         const float fs = p.pc_fscale[brow];
-        const float* zw = p.pc_zw + (brow * p.Hkv + c.hk) * 256 + half * 4;
+        const float* zw = p.pc_zw + (brow * p.grid_heads + c.hk) * 256 + half * 4;
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb)
 #pragma unroll
@@ -1047,7 +1067,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] *= E[GPS + j / KSG];
     }
-    if constexpr (MODE == MODE_SCORES) scores_epilogue(p, c, acc);
+    if constexpr (MODE == MODE_SCORES || MODE == MODE_SCORES_PC) scores_epilogue(p, c, acc);
     else if constexpr (MODE == MODE_WEIGHTED_SUM) weighted_sum_epilogue(p, c, acc);
     else if constexpr (MODE == MODE_ACCUMULATE) accumulate_epilogue(p, c, acc, lds);
     else if constexpr (MODE == MODE_PREFILL) prefill_epilogue(p, c, acc, lds);
@@ -1073,8 +1093,9 @@ constexpr int LDS_DENSE_TOTAL = LDS_DENSE_STAGE_OFF + 8 * LDS_DENSE_STAGE_BYTES;
 static_assert(LDS_DENSE_TOTAL <= LDS_MAX, "dense kernel LDS");
 
 // DMODE: 0 decode attention, 1 matrix-core epilogue (prefill), 2 store the rematerialised rows
-// [K_h | V_h] as fp32 (used for the zero-point term of a per-channel cache)
-constexpr int DENSE_ATTENTION = 0, DENSE_PREFILL = 1, DENSE_STORE = 2;
+// as fp32 (used for the zero-point term of a per-channel cache), 3 pass 1 of the latent path (scores of a
+// pair of KV heads) for the rows of a residual window
+constexpr int DENSE_ATTENTION = 0, DENSE_PREFILL = 1, DENSE_STORE = 2, DENSE_SCORES = 3;
 template <int DMODE>
 __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams p)
 {
@@ -1181,15 +1202,22 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
         prefill_epilogue(p, c, acc, lds);
     } else if constexpr (DMODE == DENSE_STORE) {
         if (c.tok < c.len) {
-            float* row = p.kv_out + (((long long)c.b * p.pc_blocks_cap + c.tok) * p.Hkv + c.hk) * 256 + c.half * 4;
+            float* row = p.kv_out + (((long long)c.b * p.pc_blocks_cap + c.tok) * p.grid_heads + c.hk) * 256 + c.half * 4;
 #pragma unroll
             for (int nb = 0; nb < 8; ++nb)
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4) {
-                    float4 v; v.x = acc[nb][i4 * 4]; v.y = acc[nb][i4 * 4 + 1]; v.z = acc[nb][i4 * 4 + 2]; v.w = acc[nb][i4 * 4 + 3];
+                    float4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (p.store_add) v = *reinterpret_cast<const float4*>(row + nb * 32 + i4 * 8);
+                    v.x = __builtin_fmaf(p.store_scale, acc[nb][i4 * 4], v.x);
+                    v.y = __builtin_fmaf(p.store_scale, acc[nb][i4 * 4 + 1], v.y);
+                    v.z = __builtin_fmaf(p.store_scale, acc[nb][i4 * 4 + 2], v.z);
+                    v.w = __builtin_fmaf(p.store_scale, acc[nb][i4 * 4 + 3], v.w);
                     *reinterpret_cast<float4*>(row + nb * 32 + i4 * 8) = v;
                 }
         }
+    } else if constexpr (DMODE == DENSE_SCORES) {
+        scores_epilogue(p, c, acc);
     } else {
         attention_epilogue(p, c, acc);
     }
@@ -1449,6 +1477,7 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
     uint16_t* eT_k = reinterpret_cast<uint16_t*>(p.part_ml + (size_t)B * p.Hq * p.chunks_per_seq * 2);
     uint16_t* eT_v = eT_k + et_elems;
     p.scores = reinterpret_cast<float*>(eT_v + et_elems);
+    p.score_stride = p.tiles_per_seq * TILE_TOKENS;
     const int grid = pairs * B * p.tiles_per_seq;
 
     scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
@@ -1632,7 +1661,12 @@ hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const
         z.wprep = static_cast<const uint8_t*>(wprep_dense);
         z.n_main_slabs = Ld.n_main_slabs; z.head_bytes = (long long)Ld.head_bytes;
         z.kv_out = zw; z.pc_blocks_cap = (int)blocks_ws;                     // destination rows per sequence
+        z.store_scale = 1.0f; z.store_add = 0;
         e = launch_with_lds(remat_attn_dense_kernel<DENSE_STORE>, LDS_DENSE_TOTAL, z, p.Hkv * B * z.tiles_per_seq, s);
+        if (e == hipSuccess && bits == 4) {                                  // + 8 s_blk [Wk | Wv]: the codes enter as code - 8
+            z.acc = xc->scale; z.store_scale = 8.0f; z.store_add = 1;
+            e = launch_with_lds(remat_attn_dense_kernel<DENSE_STORE>, LDS_DENSE_TOTAL, z, p.Hkv * B * z.tiles_per_seq, s);
+        }
         if (e != hipSuccess) return e;
         // the coded blocks
         RematParams m = p;
@@ -1662,6 +1696,130 @@ hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const
     }
     combine_kernel<<<dim3(p.Hq, B), dim3(128 * COMBINE_GROUPS), 0, s>>>(part_o, part_ml, out, p.Hq, chunks_stride, len, 1,
                                                                       CHUNK_TOKENS);
+    return hipGetLastError();
+}
+
+// ---- the paper's setting for grouped-query models (Sec. 3.3.1): X Uk per channel with a residual
+// window, X Uv per token.  Two passes as in run_remat_attn_decode_latent: pass 1 rematerialises the keys of a
+// head pair from the per-channel K cache (coded blocks, then the window rows through the dense kernel) and
+// stores the scaled scores; pass 2 is the unchanged value pass over the per-token V cache.
+size_t remat_latent_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int r, int block, int v_group)
+{
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    const size_t chunks = tiles * (TILE_TOKENS / CHUNK_TOKENS);
+    const size_t blocks = (size_t)max_len / block + 1;
+    return (size_t)B * Hq * chunks * (128 + 2) * sizeof(float)                          // partials
+         + (size_t)B * Hq * (tiles + 1) * TILE_TOKENS * sizeof(float)                   // scores
+         + (size_t)B * tiles * (size_t)(r / 128 + 1) * LDS_SCALES_BYTES                 // K factor images
+         + (size_t)B * blocks * (size_t)(Hkv / 2) * 256 * sizeof(float)                 // z W rows of the head pairs
+         + (size_t)B * tiles * (size_t)(r / v_group + 1) * TILE_TOKENS * sizeof(uint16_t)    // V effective scales
+         + (size_t)B * blocks * 2 * sizeof(float) + 256;                                // block factors and exponents
+}
+
+hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* kc,
+                                           const uint16_t* ktail, const xq_cache_t* vc, const void* wk_coded,
+                                           const void* wk_dense, const void* wv_coded, const BatchI32& len, int max_len,
+                                           float* out, void* ws, hipStream_t s)
+{
+    const int kbits = kc->fmt.bits, blockT = kc->fmt.group, r = kc->fmt.d, B = kc->B;
+    const int vbits = vc->fmt.bits, vG = vc->fmt.group;
+    const int pairs = a->n_kv_heads / 2;
+    const int blocks_cap = kc->cap / blockT;
+    const WPrepLayout Lk = make_wprep_layout(r, 128, kbits, pairs);
+    const WPrepLayout Ld = make_wprep_layout(r, 128, 16, pairs);
+    const WPrepLayout Lv = make_wprep_layout(r, vG, vbits, pairs);
+    UnpackTable tab;
+    if (!unpack_table_for(kbits, &tab)) return hipErrorInvalidValue;
+    BatchI32 nblk{}, len_coded{}, len_tail{};
+    int max_coded = 0, max_nblk = 0, any_tail = 0;
+    for (int b = 0; b < B; ++b) {
+        nblk.v[b] = len.v[b] / blockT;
+        len_coded.v[b] = nblk.v[b] * blockT;
+        len_tail.v[b] = len.v[b] - len_coded.v[b];
+        max_coded = len_coded.v[b] > max_coded ? len_coded.v[b] : max_coded;
+        max_nblk = nblk.v[b] > max_nblk ? nblk.v[b] : max_nblk;
+        any_tail |= len_tail.v[b];
+    }
+    const int tiles_all = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    const int tiles_coded = (max_coded + TILE_TOKENS - 1) / TILE_TOKENS;
+    const int chunks = tiles_all * (TILE_TOKENS / CHUNK_TOKENS);
+    const size_t blocks_ws = (size_t)max_len / blockT + 1;
+    // workspace carve-up (sizes as in remat_latent_pc_workspace_bytes)
+    float* part_o = static_cast<float*>(ws);
+    float* part_ml = part_o + (size_t)B * a->n_q_heads * chunks * 128;
+    float* scores = part_ml + (size_t)B * a->n_q_heads * chunks * 2;
+    const int score_stride = (tiles_all + 1) * TILE_TOKENS;
+    uint8_t* img = reinterpret_cast<uint8_t*>(scores + (size_t)B * a->n_q_heads * score_stride);
+    float* zw = reinterpret_cast<float*>(img + (size_t)B * tiles_all * (size_t)(r / 128 + 1) * LDS_SCALES_BYTES);
+    uint16_t* eT_v = reinterpret_cast<uint16_t*>(zw + (size_t)B * blocks_ws * pairs * 256);      // (16-byte aligned: a DMA source)
+    float* fscale = reinterpret_cast<float*>(eT_v + (size_t)B * tiles_all * (size_t)(r / vG + 1) * TILE_TOKENS);
+    int* eblk = reinterpret_cast<int*>(fscale + (size_t)B * blocks_ws);
+
+    RematParams p{};
+    p.q = q;
+    p.B = B; p.Hq = a->n_q_heads; p.Hkv = a->n_kv_heads; p.grid_heads = pairs;
+    p.scale_log2e = a->softmax_scale * 1.44269504088896340736f;
+    p.part_o = part_o; p.part_ml = part_ml; p.chunks_per_seq = chunks;
+    p.scores = scores; p.score_stride = score_stride;
+    p.d = r; p.row_d = r;
+    hipError_t e = hipSuccess;
+    if (max_nblk > 0) {
+        pc_block_exponent_kernel<<<dim3(max_nblk, B), dim3(256), 0, s>>>(kc->scale, fscale, eblk, r, blocks_cap, (int)blocks_ws, kbits, nblk);
+        PcImageArgs ia{kc->scale, eblk, reinterpret_cast<uint16_t*>(img), r, blocks_cap, (int)blocks_ws, blockT, tiles_coded,
+                       Lk.n_main_slabs, 128, nblk, tab};
+        pc_factor_image_kernel<<<dim3(Lk.n_main_slabs, tiles_coded, B), dim3(256), 0, s>>>(ia);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        RematParams z = p;                                                   // z_blk (Sk Bk^T) of every head pair
+        z.acc = kc->zero; z.cap = blocks_cap; z.len = nblk;
+        z.tiles_per_seq = (max_nblk + TILE_TOKENS - 1) / TILE_TOKENS;
+        z.wprep = static_cast<const uint8_t*>(wk_dense);
+        z.n_main_slabs = Ld.n_main_slabs; z.head_bytes = (long long)Ld.head_bytes;
+        z.kv_out = zw; z.pc_blocks_cap = (int)blocks_ws;
+        z.store_scale = 1.0f; z.store_add = 0;
+        e = launch_with_lds(remat_attn_dense_kernel<DENSE_STORE>, LDS_DENSE_TOTAL, z, pairs * B * z.tiles_per_seq, s);
+        if (e == hipSuccess && kbits == 4) {                                 // + 8 s_blk (Sk Bk^T): the codes enter as code - 8
+            z.acc = kc->scale; z.store_scale = 8.0f; z.store_add = 1;
+            e = launch_with_lds(remat_attn_dense_kernel<DENSE_STORE>, LDS_DENSE_TOTAL, z, pairs * B * z.tiles_per_seq, s);
+        }
+        if (e != hipSuccess) return e;
+        RematParams m = p;                                                   // pass 1, coded blocks
+        m.codes = kc->codes; m.eT = reinterpret_cast<const uint16_t*>(img);
+        m.cap = kc->cap; m.len = len_coded; m.tiles_per_seq = tiles_coded;
+        m.wprep = static_cast<const uint8_t*>(wk_coded);
+        m.n_main_slabs = Lk.n_main_slabs; m.n_corr_ksteps = Lk.n_corr_ksteps; m.ng = Lk.ng; m.ng_pad = Lk.ng_pad; m.ng_row = Lk.ng;
+        m.head_bytes = (long long)Lk.head_bytes;
+        m.pc_fscale = fscale; m.pc_zw = zw; m.pc_block = blockT; m.pc_blocks_cap = (int)blocks_ws;
+        const int grid = pairs * B * tiles_coded;
+        switch (kbits) {
+            case 2: e = launch_with_lds(remat_attn_coded_kernel<2, 128, MODE_SCORES_PC>, lds_coded_total(2), m, grid, s); break;
+            case 3: e = launch_with_lds(remat_attn_coded_kernel<3, 128, MODE_SCORES_PC>, lds_coded_total(3), m, grid, s); break;
+            case 4: e = launch_with_lds(remat_attn_coded_kernel<4, 128, MODE_SCORES_PC>, lds_coded_total(4), m, grid, s); break;
+            default: e = hipErrorInvalidValue;
+        }
+        if (e != hipSuccess) return e;
+    }
+    if (any_tail) {                                                          // pass 1, window rows
+        RematParams t = p;
+        t.acc = ktail; t.cap = blockT; t.len = len_tail; t.tiles_per_seq = 1; t.tok0 = len_coded;
+        t.wprep = static_cast<const uint8_t*>(wk_dense);
+        t.n_main_slabs = Ld.n_main_slabs; t.head_bytes = (long long)Ld.head_bytes;
+        e = launch_with_lds(remat_attn_dense_kernel<DENSE_SCORES>, LDS_DENSE_TOTAL, t, pairs * B, s);
+        if (e != hipSuccess) return e;
+    }
+    // pass 2: values from the per-token cache
+    scale_transpose_kernel<<<dim3(tiles_all, B), dim3(TILE_TOKENS), 0, s>>>(vc->scale, eT_v, vc->cap, Lv.ng, Lv.ng, tiles_all, vbits, len);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    RematParams v = p;
+    v.codes = vc->codes; v.zero = vc->zero; v.eT = eT_v;
+    v.cap = vc->cap; v.len = len; v.tiles_per_seq = tiles_all;
+    v.wprep = static_cast<const uint8_t*>(wv_coded);
+    v.n_main_slabs = Lv.n_main_slabs; v.n_corr_ksteps = Lv.n_corr_ksteps; v.ng = Lv.ng; v.ng_pad = Lv.ng_pad; v.ng_row = Lv.ng;
+    v.head_bytes = (long long)Lv.head_bytes;
+    e = launch_coded<MODE_WEIGHTED_SUM>(vbits, vG, v, pairs * B * tiles_all, s);
+    if (e != hipSuccess) return e;
+    combine_kernel<<<dim3(p.Hq, B), dim3(128 * COMBINE_GROUPS), 0, s>>>(part_o, part_ml, out, p.Hq, chunks, len, 1, CHUNK_TOKENS);
     return hipGetLastError();
 }
 

@@ -136,3 +136,65 @@ def test_full_size_llama2_7b_per_channel_sampled_pairs(xq):
     lens[1] = w.L
     worst = _attend(xq, w, 3, 128, lens, pairs=xi.sample_pairs(w, 8))
     print(f"c2 per-channel sampled pairs: worst norm-wise rel err {worst:.2e}")
+
+
+def _latent_pc(xq, w, kbits, kG, vbits, vG, lens, pairs=None):
+    """Latent rows X Uk, X Uv (synthetic, with the outlier channel of X Uk), keys per channel with a window,
+    values per token; the oracle attends over the same bytes."""
+    r = w.Hkv * w.hd
+    rng = np.random.default_rng(w.cfg_id * 7 + kbits)
+    lk = rng.standard_normal((w.B, w.L, r)).astype(np.float32)
+    lk[..., 0] *= 25.0
+    lk = xi.to_bf16_bits(lk)
+    lv = xi.to_bf16_bits(rng.standard_normal((w.B, w.L, r)).astype(np.float32))
+    wfk = xi.to_bf16_bits((rng.standard_normal((r, r)) * r ** -0.5).astype(np.float32))
+    wfv = xi.to_bf16_bits((rng.standard_normal((r, r)) * r ** -0.5).astype(np.float32))
+    q = xi.gen_q(w)
+    capk = (w.L + kG - 1) // kG * kG
+    kc = xq.alloc_cache_per_channel(w.B, capk, r, kG, kbits)
+    ktail = torch.zeros((w.B, kG, r), dtype=torch.bfloat16, device="cuda")
+    lkt = bits_to_torch(lk)
+    for b in range(w.B):
+        nblk, rem = lens[b] // kG, lens[b] % kG
+        if nblk:
+            sub = xq.XQCache(kc.codes[b:b + 1], kc.scale[b:b + 1], kc.zero[b:b + 1], 1, capk, r, kG, kbits)
+            xq.xq_quantize_blocks_per_channel(sub, lkt[b:b + 1, :nblk * kG].contiguous(), [0])
+        ktail[b, :rem] = lkt[b, nblk * kG:lens[b]]
+    vc = xq.alloc_cache(w.B, w.L, r, vG, vbits)
+    xq.xq_quantize_append(vc, bits_to_torch(lv), [0] * w.B)
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    wkc = xq.xq_prepare_weights_pairs(attn, r, 128, kbits, bits_to_torch(wfk))
+    wkd = xq.xq_prepare_weights_pairs(attn, r, 0, 16, bits_to_torch(wfk))
+    wvc = xq.xq_prepare_weights_pairs(attn, r, vG, vbits, bits_to_torch(wfv))
+    out = xq.xq_remat_attn_decode_latent_per_channel(attn, bits_to_torch(q), kc, ktail, vc, wkc, wkd, wvc, lens)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    if pairs is None:
+        pairs = [(b, h) for b in range(w.B) for h in range(w.Hq)]
+    ref = xo.latent_attn_pairs_per_channel(q_bf16=q, Wfk=wfk, Wfv=wfv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd,
+                                           softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs,
+                                           k_packed=kc.codes.cpu().numpy(), k_scale=torch_to_bits(kc.scale),
+                                           k_zero=torch_to_bits(kc.zero), k_G=kG, k_bits=kbits,
+                                           k_tail_bf16=torch_to_bits(ktail), v_packed=vc.codes.cpu().numpy(),
+                                           v_scale=torch_to_bits(vc.scale), v_zero=torch_to_bits(vc.zero), v_G=vG, v_bits=vbits)
+    sel = np.array([got[b, h] for b, h in pairs])
+    normwise, maxwise = rel_errors(sel, ref)
+    assert np.all(np.isfinite(got)), w.name
+    assert normwise.max() <= TOL and maxwise <= TOL, (w.name, float(normwise.max()), float(maxwise))
+    return float(normwise.max())
+
+
+@pytest.mark.parametrize("kbits,kG,vbits,vG", [(2, 64, 2, 64), (3, 128, 3, 128), (4, 128, 2, 64)])
+def test_latent_with_per_channel_keys(xq, kbits, kG, vbits, vG):
+    w = xi.C4.scaled(B=3, L=420, d=512, Hq=8, Hkv=2, n_outlier=5)          # r = 256, 4 query heads per KV head
+    _latent_pc(xq, w, kbits, kG, vbits, vG, lens=[420, 256, 31])
+
+
+def test_full_size_llama3_8b_latent_per_channel_sampled_pairs(xq):
+    """Config 4's shape from the paper's GQA setting: r = 1024, keys per channel in blocks of 128 (2-bit) with a
+    window of 100 tokens, values per token (2-bit, group 64)."""
+    w = xi.C4
+    lens = [w.L - 28] * w.B
+    lens[3] = w.L
+    worst = _latent_pc(xq, w, 2, 128, 2, 64, lens, pairs=xi.sample_pairs(w, 8))
+    print(f"c4 latent with per-channel keys, sampled pairs: worst norm-wise rel err {worst:.2e}")

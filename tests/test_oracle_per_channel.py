@@ -107,3 +107,40 @@ def test_attention_from_per_channel_cache_and_residual_window_equals_brute_force
         V = X @ bf(wv)[:, hk * hd:(hk + 1) * hd].astype(np.float64)
         ref = softmax(K @ bf(q)[b, hq].astype(np.float64) * hd ** -0.5) @ V
         assert np.allclose(got[i], ref, rtol=1e-5, atol=1e-6)
+
+
+def test_latent_attention_with_per_channel_keys_equals_brute_force():
+    from scipy.special import softmax
+    rng = np.random.default_rng(31)
+    B, L, r, Gk, Gv, kb, vb, Hq, Hkv, hd = 2, 70, 256, 32, 64, 3, 4, 4, 2, 128
+    lk = xi.to_bf16_bits(rng.standard_normal((B, L, r)).astype(np.float32))       # X Uk rows
+    lv = xi.to_bf16_bits(rng.standard_normal((B, L, r)).astype(np.float32))       # X Uv rows
+    wfk = xi.to_bf16_bits((rng.standard_normal((r, Hkv * hd)) * r ** -0.5).astype(np.float32))
+    wfv = xi.to_bf16_bits((rng.standard_normal((r, Hkv * hd)) * r ** -0.5).astype(np.float32))
+    q = xi.to_bf16_bits(rng.standard_normal((B, Hq, hd)).astype(np.float32))
+    lens = [70, 64]
+    cap = 96
+    kcodes = np.zeros((B, cap, r), np.uint8)
+    kscale = np.zeros((B, cap // Gk, r), np.uint16)
+    kzero = np.zeros_like(kscale)
+    ktail = np.zeros((B, Gk, r), np.uint16)
+    xk = []
+    for b in range(B):
+        nblk, rem = lens[b] // Gk, lens[b] % Gk
+        c, s, z = xo.quantize_blocks_per_channel(bf(lk[b, :nblk * Gk]), Gk, kb)
+        kcodes[b, :nblk * Gk], kscale[b, :nblk], kzero[b, :nblk] = c, s, z
+        ktail[b, :rem] = lk[b, nblk * Gk:lens[b]]
+        xk.append(np.concatenate([xo.dequantize_blocks_per_channel(c, s, z, Gk), bf(lk[b, nblk * Gk:lens[b]])]))
+    vc, vs, vz = xo.quantize_rows(bf(lv), Gv, vb)
+    xv = xo.dequantize_rows(vc, vs, vz, Gv)
+    pairs = [(b, h) for b in range(B) for h in range(Hq)]
+    got = xo.latent_attn_pairs_per_channel(q_bf16=q, Wfk=wfk, Wfv=wfv, Hq=Hq, Hkv=Hkv, hd=hd, softmax_scale=hd ** -0.5,
+                                           lens=lens, pairs=pairs, k_packed=xo.pack_rows(kcodes, kb), k_scale=kscale,
+                                           k_zero=kzero, k_G=Gk, k_bits=kb, k_tail_bf16=ktail,
+                                           v_packed=xo.pack_rows(vc, vb), v_scale=vs, v_zero=vz, v_G=Gv, v_bits=vb)
+    for i, (b, hq) in enumerate(pairs):
+        hk = hq // (Hq // Hkv)
+        K = xk[b].astype(np.float64) @ bf(wfk)[:, hk * hd:(hk + 1) * hd].astype(np.float64)
+        V = xv[b, :lens[b]].astype(np.float64) @ bf(wfv)[:, hk * hd:(hk + 1) * hd].astype(np.float64)
+        ref = softmax(K @ bf(q)[b, hq].astype(np.float64) * hd ** -0.5) @ V
+        assert np.allclose(got[i], ref, rtol=1e-5, atol=1e-6)
