@@ -176,6 +176,23 @@ def test_argument_errors_of_the_widened_entry_points():
     assert pa(c=pc(bits=8)) == UNSUPPORTED
     assert xq.xq_remat_attn_per_channel_workspace_bytes(xq.XQAttn(4, 2, 128, 0.1), 1, 300, 256, 32) == 0
     assert xq.xq_remat_attn_per_channel_workspace_bytes(xq.XQAttn(4, 2, 128, 0.1), 1, 300, 256, 128) > 0
+    # latent keys per channel, latent values per token
+    at2 = xq.XQAttn(4, 2, 128, 0.1)
+    assert xq.xq_prepared_weights_pairs_bytes(at2, 256, 128, 3) > 256 * 256 * 2
+    assert xq.xq_prepared_weights_pairs_bytes(at2, 256, 0, 16) == 256 * 256 * 2                 # the dense stream: no correction slabs
+    assert xq.xq_prepared_weights_pairs_bytes(xq.XQAttn(3, 3, 128, 0.1), 384, 128, 3) == 0     # odd number of KV heads
+    assert lib.xq_prepare_weights_pairs(C.byref(la), 256, 128, 3, x, x, 16, st) == WORKSPACE
+    assert lib.xq_prepare_weights_pairs(C.byref(la), 256, 128, 3, None, x, 1 << 30, st) == INVALID
+    kc, vc = pc(d=256), _cache(cap=256, d=256, group=64, bits=2)
+    lp = lambda k=kc, v=vc, ln=130, wsb=1 << 30: lib.xq_remat_attn_decode_latent_per_channel(
+        C.byref(la), x, C.byref(k), x, C.byref(v), x, x, x, (C.c_int32 * 1)(ln), x, x, wsb, st)
+    assert lp(ln=0) == INVALID
+    assert lp(ln=300) == INVALID                                                # longer than the value cache
+    assert lp(v=_cache(cap=256, d=512, group=64, bits=2)) == INVALID            # widths differ
+    assert lp(wsb=64) == WORKSPACE
+    assert lp(k=pc(d=256, bits=8)) == UNSUPPORTED
+    assert xq.xq_remat_attn_latent_per_channel_workspace_bytes(at2, 1, 300, 256, 128, 64) > 0
+    assert xq.xq_remat_attn_latent_per_channel_workspace_bytes(at2, 1, 300, 256, 128, 32) == 0
 
 
 def test_binding_has_no_cpu_fallback():
