@@ -238,6 +238,25 @@ def main():
                                          "ms": t_l, "tokens/s/layer": ow.B * ow.L / (t_l * 1e-3),
                                          "useful_TFLOP/s": lflops / t_l / 1e9,
                                          "decode_projection_us": t_p * 1e3}
+        # the paper's setting for this layer: X Uk per channel (blocks of 128 tokens, 100 of the newest in the bf16
+        # window), X Uv per token
+        kc = xq.alloc_cache_per_channel(ow.B, ow.L, r, 128, ow.bits)
+        xq.xq_quantize_blocks_per_channel(kc, lat[..., :r].contiguous(), [0] * ow.B)
+        vc = xq.alloc_cache(ow.B, ow.L, r, ow.G, ow.bits)
+        xq.xq_quantize_append(vc, lat[..., r:].contiguous(), [0] * ow.B)
+        ktail = lat[:, ow.L - 128:, :r].contiguous()
+        wkc = xq.xq_prepare_weights_pairs(oattn, r, 128, ow.bits, wfk)
+        wkd = xq.xq_prepare_weights_pairs(oattn, r, 0, 16, wfk)
+        wvc = xq.xq_prepare_weights_pairs(oattn, r, ow.G, ow.bits, wfv)
+        pws = torch.empty(xq.xq_remat_attn_latent_per_channel_workspace_bytes(oattn, ow.B, ow.L, r, 128, ow.G),
+                          dtype=torch.uint8, device=dev)
+        plens = [ow.L - 28] * ow.B
+        t_lp = timed(lambda: xq.xq_remat_attn_decode_latent_per_channel(oattn, oq, kc, ktail, vc, wkc, wkd, wvc, plens,
+                                                                        out=oout, workspace=pws), n=5, warm=3)
+        extra["remat_attn_c4_latent_keys_per_channel"] = {
+            "workload": "c4 layer, X Uk per channel (2-bit, blocks of 128, 100 window tokens), X Uv per token (2-bit, group 64)",
+            "ms": t_lp, "tokens/s/layer": ow.B * (ow.L - 28) / (t_lp * 1e-3)}
+        del kc, vc, ktail, wkc, wkd, wvc, pws
         del lcache, lat, lwp, lws
         # the cross-layer step of the same GQA layer (Sec. 3.3.2): latent delta of the new token, quantise,
         # up-project every cached delta into the accumulator, attend from the accumulator with [Wk | Wv]
