@@ -1,0 +1,544 @@
+// Host side of the rematerialisation kernels: workspace sizes, kernel parameters, launches.  Included at the
+// end of remat_attn.hip (the kernels are templates of that translation unit).
+#pragma once
+
+namespace xq {
+
+template <typename K>
+static hipError_t launch_with_lds(K kernel, int lds_bytes, const RematParams& p, int grid, hipStream_t s)
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return e;
+    kernel<<<dim3(grid), dim3(512), lds_bytes, s>>>(p);
+    return hipGetLastError();
+}
+
+size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool coded)
+{
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    const size_t chunks = tiles * (TILE_TOKENS / CHUNK_TOKENS);
+    size_t bytes = (size_t)B * Hq * chunks * (128 + 2) * sizeof(float);
+    if (coded) {
+        bytes += (size_t)B * tiles * (size_t)(d / group + 1) * TILE_TOKENS * sizeof(uint16_t);   // eT
+    }
+    return bytes;
+}
+
+// latent cache of rank r: partials, effective scales of the K half and of the V half, scores
+size_t remat_latent_workspace_bytes(int B, int Hq, int max_len, int r, int group)
+{
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    return remat_workspace_bytes(B, Hq, max_len, r, group, true) +
+           (size_t)B * tiles * (size_t)(r / group + 1) * TILE_TOKENS * sizeof(uint16_t) +
+           (size_t)B * Hq * tiles * TILE_TOKENS * sizeof(float);
+}
+
+// the prefill epilogue lays its own images over the whole LDS once the contraction is done
+template <int MODE>
+constexpr int lds_for_mode(int bits)
+{
+    return MODE == MODE_PREFILL && LDS_PREFILL_TOTAL > lds_coded_total(bits) ? LDS_PREFILL_TOTAL : lds_coded_total(bits);
+}
+
+template <int MODE>
+static hipError_t launch_coded(int bits, int G, const RematParams& p, int grid, hipStream_t s)
+{
+    switch (bits * 1000 + G) {
+        case 2064: return launch_with_lds(remat_attn_coded_kernel<2, 64, MODE>, lds_for_mode<MODE>(2), p, grid, s);
+        case 2128: return launch_with_lds(remat_attn_coded_kernel<2, 128, MODE>, lds_for_mode<MODE>(2), p, grid, s);
+        case 3064: return launch_with_lds(remat_attn_coded_kernel<3, 64, MODE>, lds_for_mode<MODE>(3), p, grid, s);
+        case 3128: return launch_with_lds(remat_attn_coded_kernel<3, 128, MODE>, lds_for_mode<MODE>(3), p, grid, s);
+        case 4064: return launch_with_lds(remat_attn_coded_kernel<4, 64, MODE>, lds_for_mode<MODE>(4), p, grid, s);
+        case 4128: return launch_with_lds(remat_attn_coded_kernel<4, 128, MODE>, lds_for_mode<MODE>(4), p, grid, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+static void fill_common(RematParams& p, const xq_attn_t* a, const uint16_t* q, int B, int cap, const BatchI32& len,
+                        int max_len, void* ws)
+{
+    p.q = q;
+    p.B = B; p.cap = cap; p.Hq = a->n_q_heads; p.Hkv = a->n_kv_heads;
+    p.tiles_per_seq = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    p.chunks_per_seq = p.tiles_per_seq * (TILE_TOKENS / CHUNK_TOKENS);
+    p.scale_log2e = a->softmax_scale * 1.44269504088896340736f;
+    p.len = len;
+    p.part_o = static_cast<float*>(ws);
+    p.part_ml = p.part_o + (size_t)B * p.Hq * p.chunks_per_seq * 128;
+}
+
+hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, const xq_cache_t* xc,
+                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
+                                  const BatchI32& len, int max_len, float* out, void* ws,
+                                  const float* rope, const BatchI32* pos0, hipStream_t s);
+
+// query heads per KV head from which the decode step goes through the matrix-core epilogue (the
+// per-query-head vector epilogue runs that many times per tile; measured break-even is about 4)
+constexpr int DECODE_MFMA_EPILOGUE_MIN_GROUP = 4;
+
+hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
+                                 const uint16_t* acc, int B, int cap, int d, const void* wprep,
+                                 const BatchI32& len, int max_len, float* out, void* ws,
+                                 const float* rope, const BatchI32* pos0, hipStream_t s)
+{
+    if (a->n_q_heads / a->n_kv_heads >= DECODE_MFMA_EPILOGUE_MIN_GROUP)     // same layouts and workspace at T = 1
+        return run_remat_attn_prefill(a, q, 1, xc, acc, B, cap, d, wprep, len, max_len, out, ws, rope, pos0, s);
+    const int bits = xc ? xc->fmt.bits : 16;
+    const int G = xc ? xc->fmt.group : 128;
+    const WPrepLayout L = make_wprep_layout(d, G, bits, a->n_kv_heads);
+    RematParams p{};
+    fill_common(p, a, q, B, cap, len, max_len, ws);
+    p.codes = xc ? xc->codes : nullptr;
+    p.zero = xc ? xc->zero : nullptr;
+    p.acc = acc;
+    p.wprep = static_cast<const uint8_t*>(wprep);
+    p.d = d; p.row_d = d; p.grid_heads = p.Hkv;
+    p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
+    p.ng_row = L.ng;
+    p.head_bytes = (long long)L.head_bytes;
+    p.rope = rope;
+    if (rope) p.pos0 = *pos0;
+    uint16_t* eT = reinterpret_cast<uint16_t*>(p.part_ml + (size_t)B * p.Hq * p.chunks_per_seq * 2);
+    p.eT = eT;
+
+    const int grid = p.Hkv * p.B * p.tiles_per_seq;
+    hipError_t e = hipErrorInvalidValue;
+    if (xc) {
+        scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
+            xc->scale, eT, cap, L.ng, L.ng, p.tiles_per_seq, bits, len);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        e = launch_coded<MODE_ATTENTION>(bits, G, p, grid, s);
+    } else {
+        e = launch_with_lds(remat_attn_dense_kernel<DENSE_ATTENTION>, LDS_DENSE_TOTAL, p, grid, s);
+    }
+    if (e != hipSuccess) return e;
+    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len, 1, CHUNK_TOKENS);
+    return hipGetLastError();
+}
+
+// Causal attention of the T newest tokens of every sequence (chunked prefill): the decode launch
+// with T query rows per sequence in the partial buffers and the matrix-core epilogue.
+size_t remat_prefill_workspace_bytes(int B, int T, int Hq, int max_len, int d, int group, bool coded)
+{
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    size_t bytes = ((size_t)B * T * Hq * tiles + 7) / 8 * 8 * (128 + 2) * sizeof(float);    // one partial per tile
+    if (coded) bytes += (size_t)B * tiles * (size_t)(d / group + 1) * TILE_TOKENS * sizeof(uint16_t);
+    return bytes;
+}
+
+hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, const xq_cache_t* xc,
+                                  const uint16_t* acc, int B, int cap, int d, const void* wprep,
+                                  const BatchI32& len, int max_len, float* out, void* ws,
+                                  const float* rope, const BatchI32* pos0, hipStream_t s)
+{
+    const int bits = xc ? xc->fmt.bits : 16;
+    const int G = xc ? xc->fmt.group : 128;
+    const WPrepLayout L = make_wprep_layout(d, G, bits, a->n_kv_heads);
+    RematParams p{};
+    p.q = q; p.Tq = T;
+    p.B = B; p.cap = cap; p.Hq = a->n_q_heads; p.Hkv = a->n_kv_heads;
+    p.tiles_per_seq = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    p.chunks_per_seq = p.tiles_per_seq;                  // the epilogue merges a tile's chunks: one partial per tile
+    p.scale_log2e = a->softmax_scale * 1.44269504088896340736f;
+    p.len = len;
+    const size_t rows = ((size_t)B * T * p.Hq * p.tiles_per_seq + 7) / 8 * 8;   // (keeps the scale copy 16-byte aligned)
+    p.part_o = static_cast<float*>(ws);
+    p.part_ml = p.part_o + rows * 128;
+    p.eT = reinterpret_cast<uint16_t*>(p.part_ml + rows * 2);
+    p.codes = xc ? xc->codes : nullptr;
+    p.zero = xc ? xc->zero : nullptr;
+    p.acc = acc;
+    p.wprep = static_cast<const uint8_t*>(wprep);
+    p.d = d; p.row_d = d; p.grid_heads = p.Hkv;
+    p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
+    p.ng_row = L.ng;
+    p.head_bytes = (long long)L.head_bytes;
+    p.rope = rope;
+    if (rope) p.pos0 = *pos0;
+    const int grid = p.Hkv * p.B * p.tiles_per_seq;
+    hipError_t e;
+    if (xc) {
+        scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
+            xc->scale, const_cast<uint16_t*>(p.eT), cap, L.ng, L.ng, p.tiles_per_seq, bits, len);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        e = launch_coded<MODE_PREFILL>(bits, G, p, grid, s);
+    } else {
+        e = launch_with_lds(remat_attn_dense_kernel<DENSE_PREFILL>, LDS_DENSE_TOTAL, p, grid, s);
+    }
+    if (e != hipSuccess) return e;
+    combine_kernel<<<dim3(p.Hq, p.B * T), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq,
+                                                                            p.chunks_per_seq, p.len, T, TILE_TOKENS);
+    return hipGetLastError();
+}
+
+// Latent cache [X Uk | X Uv] of rank r (Sec. 3.3.1): two passes of the same contraction kernel over
+// the two halves of the cache rows, each with all 256 columns in use -- pass 1 rematerialises the
+// keys of a pair of KV heads from the first r channels and stores the scaled scores, pass 2 the
+// values of the pair from the last r channels and turns scores into softmax partials.
+hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
+                                        const void* wprep, const BatchI32& len, int max_len, float* out, void* ws,
+                                        hipStream_t s)
+{
+    const int bits = xc->fmt.bits, G = xc->fmt.group, r = xc->fmt.d / 2, B = xc->B, cap = xc->cap;
+    const int pairs = a->n_kv_heads / 2;
+    const WPrepLayout L = make_wprep_layout(r, G, bits, pairs);          // one stream per half, "head" = pair
+    RematParams p{};
+    fill_common(p, a, q, B, cap, len, max_len, ws);
+    p.d = r; p.row_d = 2 * r; p.grid_heads = pairs;
+    p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
+    p.ng_row = 2 * L.ng;
+    p.head_bytes = (long long)L.head_bytes;
+    const size_t et_elems = (size_t)B * p.tiles_per_seq * (size_t)(L.ng + 1) * TILE_TOKENS;
+    uint16_t* eT_k = reinterpret_cast<uint16_t*>(p.part_ml + (size_t)B * p.Hq * p.chunks_per_seq * 2);
+    uint16_t* eT_v = eT_k + et_elems;
+    p.scores = reinterpret_cast<float*>(eT_v + et_elems);
+    p.score_stride = p.tiles_per_seq * TILE_TOKENS;
+    const int grid = pairs * B * p.tiles_per_seq;
+
+    scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
+        xc->scale, eT_k, cap, L.ng, 2 * L.ng, p.tiles_per_seq, bits, len);
+    scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
+        xc->scale + L.ng, eT_v, cap, L.ng, 2 * L.ng, p.tiles_per_seq, bits, len);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // pass 1: keys
+    p.codes = xc->codes; p.zero = xc->zero; p.eT = eT_k;
+    p.wprep = static_cast<const uint8_t*>(wprep);
+    e = launch_coded<MODE_SCORES>(bits, G, p, grid, s);
+    if (e != hipSuccess) return e;
+    // pass 2: values
+    p.codes = xc->codes + (size_t)r * bits / 8; p.zero = xc->zero + L.ng; p.eT = eT_v;
+    p.wprep = static_cast<const uint8_t*>(wprep) + L.total_bytes;
+    e = launch_coded<MODE_WEIGHTED_SUM>(bits, G, p, grid, s);
+    if (e != hipSuccess) return e;
+    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len, 1, CHUNK_TOKENS);
+    return hipGetLastError();
+}
+
+// Sec. 3.3.2: acc[b][t][:] += dequant(latent delta cache row) U_kv^T for t < len[b], with the
+// contraction kernel laid over d / 256 column blocks of the hidden size.  ws holds the effective
+// scales only.
+size_t upproject_workspace_bytes(int B, int max_len, int n_lat, int group)
+{
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    return (size_t)B * tiles * (size_t)(n_lat / group + 1) * TILE_TOKENS * sizeof(uint16_t);
+}
+
+hipError_t run_cl_accumulate_latent(uint16_t* acc, const xq_cache_t* xc, int d, const void* uprep,
+                                    const BatchI32& len, int max_len, void* ws, hipStream_t s)
+{
+    const int bits = xc->fmt.bits, G = xc->fmt.group, n_lat = xc->fmt.d, B = xc->B;
+    const int blocks = d / 256;
+    const WPrepLayout L = make_wprep_layout(n_lat, G, bits, blocks);
+    RematParams p{};
+    p.B = B; p.cap = xc->cap; p.Hq = p.Hkv = blocks; p.grid_heads = blocks;
+    p.tiles_per_seq = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    p.chunks_per_seq = p.tiles_per_seq * (TILE_TOKENS / CHUNK_TOKENS);
+    p.len = len;
+    p.codes = xc->codes; p.zero = xc->zero;
+    p.wprep = static_cast<const uint8_t*>(uprep);
+    p.d = n_lat; p.row_d = n_lat;
+    p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
+    p.ng_row = L.ng;
+    p.head_bytes = (long long)L.head_bytes;
+    p.eT = static_cast<uint16_t*>(ws);
+    p.acc_out = acc; p.d_out = d;
+    scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
+        xc->scale, static_cast<uint16_t*>(ws), xc->cap, L.ng, L.ng, p.tiles_per_seq, bits, len);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_coded<MODE_ACCUMULATE>(bits, G, p, blocks * B * p.tiles_per_seq, s);
+}
+
+// ---- per-channel cache (Sec. 3.3.1) ----------------------------------------------------------
+// Pre-pass 1: per block, E = exponent with max_c scale < 2^E, and the block's final factor
+// 2^(E + bits - 1) (the operand factors are scale * 2^(15 - E), the prepared weights carry 2^(-14 - bits)
+// relative to the code bits).  One workgroup per (block, sequence).
+__global__ __launch_bounds__(256) void pc_block_exponent_kernel(const uint16_t* __restrict__ scale, float* __restrict__ fscale,
+                                                                int* __restrict__ eblk, int d, int blocks_cap,
+                                                                int blocks_ws, int bits, BatchI32 nblk)
+{
+    __shared__ uint32_t red[256];
+    const int blk = blockIdx.x, b = blockIdx.y;
+    if (blk >= nblk.v[b]) return;
+    const uint16_t* row = scale + ((long long)b * blocks_cap + blk) * d;
+    uint32_t mx = 0;
+    for (int c = threadIdx.x; c < d; c += 256) mx = max(mx, (uint32_t)row[c]);    // non-negative bf16: ordered as integers
+    red[threadIdx.x] = mx;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+        if ((int)threadIdx.x < st) red[threadIdx.x] = max(red[threadIdx.x], red[threadIdx.x + st]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const int e8 = (int)(red[0] >> 7);                                          // biased exponent of the largest scale
+        const int E = red[0] ? e8 - 126 : 0;                                        // largest scale < 2^E
+        eblk[(long long)b * blocks_ws + blk] = E;                                   // (workspace rows per sequence)
+        fscale[(long long)b * blocks_ws + blk] = ldexpf(1.0f, E + bits - 1);
+    }
+}
+
+// Pre-pass 2: the factor images, [sequence][tile][slab (+1 pad)][block of the tile][k-step][lane half][8] fp16, in
+// the order the unpacked operand dwords hold their channels (the unpack table gives the code of each slot).
+// Blocks past the sequence's last one repeat it (their tokens are masked, but must stay finite).
+struct PcImageArgs {
+    const uint16_t* scale;
+    const int* eblk;
+    uint16_t* img;
+    int d, blocks_cap, blocks_ws, block, tiles_per_seq, n_slabs, G;   // blocks per sequence in the cache / in eblk
+    BatchI32 nblk;
+    UnpackTable tab;
+};
+__global__ __launch_bounds__(256) void pc_factor_image_kernel(PcImageArgs a)
+{
+    const int slab = blockIdx.x, tile = blockIdx.y, b = blockIdx.z;
+    const int bpt = TILE_TOKENS / a.block;                       // blocks per tile
+    if (tile * bpt >= a.nblk.v[b]) return;
+    uint16_t* out = a.img + (((long long)b * a.tiles_per_seq + tile) * (a.n_slabs + 1) + slab) * (LDS_SCALES_BYTES / 2);
+    const int ksg_n = a.G / 16;
+    for (int e = threadIdx.x; e < bpt * 128; e += 256) {
+        const int i = e & 7, half = (e >> 3) & 1, ks = (e >> 4) & 7, bt = e >> 7;
+        const int blk = min(tile * bpt + bt, a.nblk.v[b] - 1);
+        const int gi = ks / ksg_n, ksg = ks % ksg_n;
+        const int c = slab * 128 + gi * a.G + half * (a.G / 2) + (ksg >> 2) * 32 + a.tab.code_of_slot[ksg & 3][i];
+        const float sc = bf16_bits_to_f32(a.scale[((long long)b * a.blocks_cap + blk) * a.d + c]);
+        const float f = ldexpf(sc, 15 - a.eblk[(long long)b * a.blocks_ws + blk]);
+        out[e] = __builtin_bit_cast(uint16_t, (_Float16)f);
+    }
+}
+
+bool unpack_table_for(int bits, UnpackTable* t);
+
+size_t remat_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int d, int block)
+{
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    const size_t chunks = (tiles + 1) * (TILE_TOKENS / CHUNK_TOKENS);
+    const size_t blocks = (size_t)max_len / block + 1;
+    return (size_t)B * Hq * chunks * (128 + 2) * sizeof(float)                    // partials
+         + (size_t)B * tiles * (size_t)(d / 128 + 1) * LDS_SCALES_BYTES           // factor images
+         + (size_t)B * blocks * (size_t)Hkv * 256 * sizeof(float)                 // z W rows
+         + (size_t)B * blocks * 2 * sizeof(float) + 256;                          // block factors and exponents
+}
+
+// Decode attention from a per-channel cache plus the bf16 residual window of the newest len % block tokens.
+hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc, const uint16_t* tail,
+                                    const void* wprep_coded, const void* wprep_dense, const BatchI32& len, int max_len,
+                                    float* out, void* ws, hipStream_t s)
+{
+    const int bits = xc->fmt.bits, blockT = xc->fmt.group, d = xc->fmt.d, B = xc->B, cap = xc->cap;
+    const int blocks_cap = cap / blockT;
+    const WPrepLayout Lc = make_wprep_layout(d, 128, bits, a->n_kv_heads);
+    const WPrepLayout Ld = make_wprep_layout(d, 128, 16, a->n_kv_heads);
+    UnpackTable tab;
+    if (!unpack_table_for(bits, &tab)) return hipErrorInvalidValue;
+    BatchI32 nblk{}, len_coded{}, len_tail{}, chunk0{};
+    int max_coded = 0, max_nblk = 0, any_tail = 0;
+    for (int b = 0; b < B; ++b) {
+        nblk.v[b] = len.v[b] / blockT;
+        len_coded.v[b] = nblk.v[b] * blockT;
+        len_tail.v[b] = len.v[b] - len_coded.v[b];
+        chunk0.v[b] = len_coded.v[b] / CHUNK_TOKENS;
+        max_coded = len_coded.v[b] > max_coded ? len_coded.v[b] : max_coded;
+        max_nblk = nblk.v[b] > max_nblk ? nblk.v[b] : max_nblk;
+        any_tail |= len_tail.v[b];
+    }
+    const int tiles_all = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    const int tiles_coded = (max_coded + TILE_TOKENS - 1) / TILE_TOKENS;
+    const int chunks_stride = (tiles_all + 1) * (TILE_TOKENS / CHUNK_TOKENS);
+    // workspace carve-up (sizes as in remat_pc_workspace_bytes)
+    float* part_o = static_cast<float*>(ws);
+    float* part_ml = part_o + (size_t)B * a->n_q_heads * chunks_stride * 128;
+    uint8_t* img = reinterpret_cast<uint8_t*>(part_ml + (size_t)B * a->n_q_heads * chunks_stride * 2);
+    float* zw = reinterpret_cast<float*>(img + (size_t)B * tiles_all * (size_t)(d / 128 + 1) * LDS_SCALES_BYTES);
+    const size_t blocks_ws = (size_t)max_len / blockT + 1;
+    float* fscale = zw + (size_t)B * blocks_ws * a->n_kv_heads * 256;
+    int* eblk = reinterpret_cast<int*>(fscale + (size_t)B * blocks_ws);
+
+    RematParams p{};
+    p.q = q;
+    p.B = B; p.Hq = a->n_q_heads; p.Hkv = a->n_kv_heads; p.grid_heads = p.Hkv;
+    p.scale_log2e = a->softmax_scale * 1.44269504088896340736f;
+    p.part_o = part_o; p.part_ml = part_ml; p.chunks_per_seq = chunks_stride;
+    p.d = d; p.row_d = d;
+    hipError_t e = hipSuccess;
+    if (max_nblk > 0) {
+        // block exponents, factor images
+        pc_block_exponent_kernel<<<dim3(max_nblk, B), dim3(256), 0, s>>>(xc->scale, fscale, eblk, d, blocks_cap, (int)blocks_ws, bits, nblk);
+        PcImageArgs ia{xc->scale, eblk, reinterpret_cast<uint16_t*>(img), d, blocks_cap, (int)blocks_ws, blockT, tiles_coded, Lc.n_main_slabs, 128,
+                       nblk, tab};
+        pc_factor_image_kernel<<<dim3(Lc.n_main_slabs, tiles_coded, B), dim3(256), 0, s>>>(ia);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        // z_blk [Wk | Wv]: the dense contraction over the zero-point rows, stored
+        RematParams z = p;
+        z.acc = xc->zero; z.cap = blocks_cap; z.len = nblk;                  // source rows: one per block
+        z.tiles_per_seq = (max_nblk + TILE_TOKENS - 1) / TILE_TOKENS;
+        z.wprep = static_cast<const uint8_t*>(wprep_dense);
+        z.n_main_slabs = Ld.n_main_slabs; z.head_bytes = (long long)Ld.head_bytes;
+        z.kv_out = zw; z.pc_blocks_cap = (int)blocks_ws;                     // destination rows per sequence
+        z.store_scale = 1.0f; z.store_add = 0;
+        e = launch_with_lds(remat_attn_dense_kernel<DENSE_STORE>, LDS_DENSE_TOTAL, z, p.Hkv * B * z.tiles_per_seq, s);
+        if (e == hipSuccess && bits == 4) {                                  // + 8 s_blk [Wk | Wv]: the codes enter as code - 8
+            z.acc = xc->scale; z.store_scale = 8.0f; z.store_add = 1;
+            e = launch_with_lds(remat_attn_dense_kernel<DENSE_STORE>, LDS_DENSE_TOTAL, z, p.Hkv * B * z.tiles_per_seq, s);
+        }
+        if (e != hipSuccess) return e;
+        // the coded blocks
+        RematParams m = p;
+        m.codes = xc->codes; m.eT = reinterpret_cast<const uint16_t*>(img);
+        m.cap = cap; m.len = len_coded; m.tiles_per_seq = tiles_coded;
+        m.wprep = static_cast<const uint8_t*>(wprep_coded);
+        m.n_main_slabs = Lc.n_main_slabs; m.n_corr_ksteps = Lc.n_corr_ksteps; m.ng = Lc.ng; m.ng_pad = Lc.ng_pad; m.ng_row = Lc.ng;
+        m.head_bytes = (long long)Lc.head_bytes;
+        m.pc_fscale = fscale; m.pc_zw = zw; m.pc_block = blockT; m.pc_blocks_cap = (int)blocks_ws;
+        const int grid = p.Hkv * B * tiles_coded;
+        switch (bits) {
+            case 2: e = launch_with_lds(remat_attn_coded_kernel<2, 128, MODE_ATTENTION_PC>, lds_coded_total(2), m, grid, s); break;
+            case 3: e = launch_with_lds(remat_attn_coded_kernel<3, 128, MODE_ATTENTION_PC>, lds_coded_total(3), m, grid, s); break;
+            case 4: e = launch_with_lds(remat_attn_coded_kernel<4, 128, MODE_ATTENTION_PC>, lds_coded_total(4), m, grid, s); break;
+            default: e = hipErrorInvalidValue;
+        }
+        if (e != hipSuccess) return e;
+    }
+    if (any_tail) {
+        // the residual window: bf16 rows, dense-source kernel, partial chunks placed after the coded ones
+        RematParams t = p;
+        t.acc = tail; t.cap = blockT; t.len = len_tail; t.tiles_per_seq = 1; t.chunk0 = chunk0;
+        t.wprep = static_cast<const uint8_t*>(wprep_dense);
+        t.n_main_slabs = Ld.n_main_slabs; t.head_bytes = (long long)Ld.head_bytes;
+        e = launch_with_lds(remat_attn_dense_kernel<DENSE_ATTENTION>, LDS_DENSE_TOTAL, t, p.Hkv * B, s);
+        if (e != hipSuccess) return e;
+    }
+    combine_kernel<<<dim3(p.Hq, B), dim3(128 * COMBINE_GROUPS), 0, s>>>(part_o, part_ml, out, p.Hq, chunks_stride, len, 1,
+                                                                      CHUNK_TOKENS);
+    return hipGetLastError();
+}
+
+// ---- the paper's setting for grouped-query models (Sec. 3.3.1): X Uk per channel with a residual
+// window, X Uv per token.  Two passes as in run_remat_attn_decode_latent: pass 1 rematerialises the keys of a
+// head pair from the per-channel K cache (coded blocks, then the window rows through the dense kernel) and
+// stores the scaled scores; pass 2 is the unchanged value pass over the per-token V cache.
+size_t remat_latent_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int r, int block, int v_group)
+{
+    const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    const size_t chunks = tiles * (TILE_TOKENS / CHUNK_TOKENS);
+    const size_t blocks = (size_t)max_len / block + 1;
+    return (size_t)B * Hq * chunks * (128 + 2) * sizeof(float)                          // partials
+         + (size_t)B * Hq * (tiles + 1) * TILE_TOKENS * sizeof(float)                   // scores
+         + (size_t)B * tiles * (size_t)(r / 128 + 1) * LDS_SCALES_BYTES                 // K factor images
+         + (size_t)B * blocks * (size_t)(Hkv / 2) * 256 * sizeof(float)                 // z W rows of the head pairs
+         + (size_t)B * tiles * (size_t)(r / v_group + 1) * TILE_TOKENS * sizeof(uint16_t)    // V effective scales
+         + (size_t)B * blocks * 2 * sizeof(float) + 256;                                // block factors and exponents
+}
+
+hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* kc,
+                                           const uint16_t* ktail, const xq_cache_t* vc, const void* wk_coded,
+                                           const void* wk_dense, const void* wv_coded, const BatchI32& len, int max_len,
+                                           float* out, void* ws, hipStream_t s)
+{
+    const int kbits = kc->fmt.bits, blockT = kc->fmt.group, r = kc->fmt.d, B = kc->B;
+    const int vbits = vc->fmt.bits, vG = vc->fmt.group;
+    const int pairs = a->n_kv_heads / 2;
+    const int blocks_cap = kc->cap / blockT;
+    const WPrepLayout Lk = make_wprep_layout(r, 128, kbits, pairs);
+    const WPrepLayout Ld = make_wprep_layout(r, 128, 16, pairs);
+    const WPrepLayout Lv = make_wprep_layout(r, vG, vbits, pairs);
+    UnpackTable tab;
+    if (!unpack_table_for(kbits, &tab)) return hipErrorInvalidValue;
+    BatchI32 nblk{}, len_coded{}, len_tail{};
+    int max_coded = 0, max_nblk = 0, any_tail = 0;
+    for (int b = 0; b < B; ++b) {
+        nblk.v[b] = len.v[b] / blockT;
+        len_coded.v[b] = nblk.v[b] * blockT;
+        len_tail.v[b] = len.v[b] - len_coded.v[b];
+        max_coded = len_coded.v[b] > max_coded ? len_coded.v[b] : max_coded;
+        max_nblk = nblk.v[b] > max_nblk ? nblk.v[b] : max_nblk;
+        any_tail |= len_tail.v[b];
+    }
+    const int tiles_all = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
+    const int tiles_coded = (max_coded + TILE_TOKENS - 1) / TILE_TOKENS;
+    const int chunks = tiles_all * (TILE_TOKENS / CHUNK_TOKENS);
+    const size_t blocks_ws = (size_t)max_len / blockT + 1;
+    // workspace carve-up (sizes as in remat_latent_pc_workspace_bytes)
+    float* part_o = static_cast<float*>(ws);
+    float* part_ml = part_o + (size_t)B * a->n_q_heads * chunks * 128;
+    float* scores = part_ml + (size_t)B * a->n_q_heads * chunks * 2;
+    const int score_stride = (tiles_all + 1) * TILE_TOKENS;
+    uint8_t* img = reinterpret_cast<uint8_t*>(scores + (size_t)B * a->n_q_heads * score_stride);
+    float* zw = reinterpret_cast<float*>(img + (size_t)B * tiles_all * (size_t)(r / 128 + 1) * LDS_SCALES_BYTES);
+    uint16_t* eT_v = reinterpret_cast<uint16_t*>(zw + (size_t)B * blocks_ws * pairs * 256);      // (16-byte aligned: a DMA source)
+    float* fscale = reinterpret_cast<float*>(eT_v + (size_t)B * tiles_all * (size_t)(r / vG + 1) * TILE_TOKENS);
+    int* eblk = reinterpret_cast<int*>(fscale + (size_t)B * blocks_ws);
+
+    RematParams p{};
+    p.q = q;
+    p.B = B; p.Hq = a->n_q_heads; p.Hkv = a->n_kv_heads; p.grid_heads = pairs;
+    p.scale_log2e = a->softmax_scale * 1.44269504088896340736f;
+    p.part_o = part_o; p.part_ml = part_ml; p.chunks_per_seq = chunks;
+    p.scores = scores; p.score_stride = score_stride;
+    p.d = r; p.row_d = r;
+    hipError_t e = hipSuccess;
+    if (max_nblk > 0) {
+        pc_block_exponent_kernel<<<dim3(max_nblk, B), dim3(256), 0, s>>>(kc->scale, fscale, eblk, r, blocks_cap, (int)blocks_ws, kbits, nblk);
+        PcImageArgs ia{kc->scale, eblk, reinterpret_cast<uint16_t*>(img), r, blocks_cap, (int)blocks_ws, blockT, tiles_coded,
+                       Lk.n_main_slabs, 128, nblk, tab};
+        pc_factor_image_kernel<<<dim3(Lk.n_main_slabs, tiles_coded, B), dim3(256), 0, s>>>(ia);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        RematParams z = p;                                                   // z_blk (Sk Bk^T) of every head pair
+        z.acc = kc->zero; z.cap = blocks_cap; z.len = nblk;
+        z.tiles_per_seq = (max_nblk + TILE_TOKENS - 1) / TILE_TOKENS;
+        z.wprep = static_cast<const uint8_t*>(wk_dense);
+        z.n_main_slabs = Ld.n_main_slabs; z.head_bytes = (long long)Ld.head_bytes;
+        z.kv_out = zw; z.pc_blocks_cap = (int)blocks_ws;
+        z.store_scale = 1.0f; z.store_add = 0;
+        e = launch_with_lds(remat_attn_dense_kernel<DENSE_STORE>, LDS_DENSE_TOTAL, z, pairs * B * z.tiles_per_seq, s);
+        if (e == hipSuccess && kbits == 4) {                                 // + 8 s_blk (Sk Bk^T): the codes enter as code - 8
+            z.acc = kc->scale; z.store_scale = 8.0f; z.store_add = 1;
+            e = launch_with_lds(remat_attn_dense_kernel<DENSE_STORE>, LDS_DENSE_TOTAL, z, pairs * B * z.tiles_per_seq, s);
+        }
+        if (e != hipSuccess) return e;
+        RematParams m = p;                                                   // pass 1, coded blocks
+        m.codes = kc->codes; m.eT = reinterpret_cast<const uint16_t*>(img);
+        m.cap = kc->cap; m.len = len_coded; m.tiles_per_seq = tiles_coded;
+        m.wprep = static_cast<const uint8_t*>(wk_coded);
+        m.n_main_slabs = Lk.n_main_slabs; m.n_corr_ksteps = Lk.n_corr_ksteps; m.ng = Lk.ng; m.ng_pad = Lk.ng_pad; m.ng_row = Lk.ng;
+        m.head_bytes = (long long)Lk.head_bytes;
+        m.pc_fscale = fscale; m.pc_zw = zw; m.pc_block = blockT; m.pc_blocks_cap = (int)blocks_ws;
+        const int grid = pairs * B * tiles_coded;
+        switch (kbits) {
+            case 2: e = launch_with_lds(remat_attn_coded_kernel<2, 128, MODE_SCORES_PC>, lds_coded_total(2), m, grid, s); break;
+            case 3: e = launch_with_lds(remat_attn_coded_kernel<3, 128, MODE_SCORES_PC>, lds_coded_total(3), m, grid, s); break;
+            case 4: e = launch_with_lds(remat_attn_coded_kernel<4, 128, MODE_SCORES_PC>, lds_coded_total(4), m, grid, s); break;
+            default: e = hipErrorInvalidValue;
+        }
+        if (e != hipSuccess) return e;
+    }
+    if (any_tail) {                                                          // pass 1, window rows
+        RematParams t = p;
+        t.acc = ktail; t.cap = blockT; t.len = len_tail; t.tiles_per_seq = 1; t.tok0 = len_coded;
+        t.wprep = static_cast<const uint8_t*>(wk_dense);
+        t.n_main_slabs = Ld.n_main_slabs; t.head_bytes = (long long)Ld.head_bytes;
+        e = launch_with_lds(remat_attn_dense_kernel<DENSE_SCORES>, LDS_DENSE_TOTAL, t, pairs * B, s);
+        if (e != hipSuccess) return e;
+    }
+    // pass 2: values from the per-token cache
+    scale_transpose_kernel<<<dim3(tiles_all, B), dim3(TILE_TOKENS), 0, s>>>(vc->scale, eT_v, vc->cap, Lv.ng, Lv.ng, tiles_all, vbits, len);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    RematParams v = p;
+    v.codes = vc->codes; v.zero = vc->zero; v.eT = eT_v;
+    v.cap = vc->cap; v.len = len; v.tiles_per_seq = tiles_all;
+    v.wprep = static_cast<const uint8_t*>(wv_coded);
+    v.n_main_slabs = Lv.n_main_slabs; v.n_corr_ksteps = Lv.n_corr_ksteps; v.ng = Lv.ng; v.ng_pad = Lv.ng_pad; v.ng_row = Lv.ng;
+    v.head_bytes = (long long)Lv.head_bytes;
+    e = launch_coded<MODE_WEIGHTED_SUM>(vbits, vG, v, pairs * B * tiles_all, s);
+    if (e != hipSuccess) return e;
+    combine_kernel<<<dim3(p.Hq, B), dim3(128 * COMBINE_GROUPS), 0, s>>>(part_o, part_ml, out, p.Hq, chunks, len, 1, CHUNK_TOKENS);
+    return hipGetLastError();
+}
+
+}  // namespace xq
