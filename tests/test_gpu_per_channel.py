@@ -198,3 +198,45 @@ def test_full_size_llama3_8b_latent_per_channel_sampled_pairs(xq):
     lens[3] = w.L
     worst = _latent_pc(xq, w, 2, 128, 2, 64, lens, pairs=xi.sample_pairs(w, 8))
     print(f"c4 latent with per-channel keys, sampled pairs: worst norm-wise rel err {worst:.2e}")
+
+
+def test_decode_loop_fills_the_window_and_completes_blocks(xq):
+    """A decode loop as a caller would run it: every new token goes to the bf16 window; when the window holds
+    a whole block it is quantised per channel into the cache and the window starts again.  Attention is checked
+    against the oracle at block boundaries and in between, for two sequences that are out of phase."""
+    rng = np.random.default_rng(99)
+    B, d, G, bits, Hq, Hkv, hd = 2, 256, 64, 3, 4, 2, 128
+    cap = 4 * G
+    steps = 150
+    wk = xi.to_bf16_bits((rng.standard_normal((d, Hkv * hd)) * d ** -0.5).astype(np.float32))
+    wv = xi.to_bf16_bits((rng.standard_normal((d, Hkv * hd)) * d ** -0.5).astype(np.float32))
+    attn = xq.XQAttn(Hq, Hkv, hd, hd ** -0.5)
+    wpc = xq.xq_prepare_weights(attn, d, 128, bits, bits_to_torch(wk), bits_to_torch(wv))
+    wpd = xq.xq_prepare_weights(attn, d, 0, 16, bits_to_torch(wk), bits_to_torch(wv))
+    cache = xq.alloc_cache_per_channel(B, cap, d, G, bits)
+    tail = torch.zeros((B, G, d), dtype=torch.bfloat16, device="cuda")
+    lens = [37, 0]                                       # sequence 0 starts with 37 tokens already in its window
+    tail[0, :37] = bits_to_torch(xi.to_bf16_bits(rng.standard_normal((37, d)).astype(np.float32)))
+    checked = 0
+    for step in range(steps):
+        x_new = bits_to_torch(xi.to_bf16_bits(rng.standard_normal((B, d)).astype(np.float32)))
+        for b in range(B):
+            rem = lens[b] % G
+            tail[b, rem] = x_new[b]
+            lens[b] += 1
+            if lens[b] % G == 0:                         # the window is a whole block now
+                sub = xq.XQCache(cache.codes[b:b + 1], cache.scale[b:b + 1], cache.zero[b:b + 1], 1, cap, d, G, bits)
+                xq.xq_quantize_blocks_per_channel(sub, tail[b:b + 1].contiguous(), [lens[b] // G - 1])
+        if step % 13 == 0 or any(l % G in (0, 1) for l in lens) or step == steps - 1:
+            q = xi.to_bf16_bits(rng.standard_normal((B, Hq, hd)).astype(np.float32))
+            out = xq.xq_remat_attn_decode_per_channel(attn, bits_to_torch(q), cache, tail, lens, wpc, wpd)
+            torch.cuda.synchronize()
+            pairs = [(b, h) for b in range(B) for h in range(Hq)]
+            ref = xo.remat_attn_pairs_per_channel(q_bf16=q, Wk=wk, Wv=wv, Hq=Hq, Hkv=Hkv, hd=hd, softmax_scale=hd ** -0.5,
+                                                  lens=lens, pairs=pairs, packed=cache.codes.cpu().numpy(),
+                                                  scale=torch_to_bits(cache.scale), zero=torch_to_bits(cache.zero), G=G,
+                                                  bits=bits, tail_bf16=torch_to_bits(tail))
+            normwise, maxwise = rel_errors(out.cpu().numpy().reshape(-1, hd), ref)
+            assert normwise.max() <= TOL and maxwise <= TOL, (step, lens, float(normwise.max()))
+            checked += 1
+    assert lens == [37 + steps, steps] and checked >= 15
