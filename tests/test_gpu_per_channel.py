@@ -240,3 +240,11 @@ def test_decode_loop_fills_the_window_and_completes_blocks(xq):
             assert normwise.max() <= TOL and maxwise <= TOL, (step, lens, float(normwise.max()))
             checked += 1
     assert lens == [37 + steps, steps] and checked >= 15
+
+
+def test_per_channel_maximum_batch(xq):
+    """128 sequences, lengths from a window-only sequence to two blocks plus a window."""
+    w = xi.C2.scaled(B=128, L=192, d=256, Hq=2, Hkv=2, n_outlier=2)
+    lens = [1 + (11 * b) % 190 for b in range(w.B)]
+    pairs = [(b, h) for b in range(0, w.B, 5) for h in range(w.Hq)] + [(127, 0), (127, 1)]
+    _attend(xq, w, 3, 64, lens, pairs=pairs)

@@ -136,3 +136,12 @@ def test_full_size_llama2_7b_chunk_of_32_sampled(xq):
                                                          for _ in range(6)]
     worst = _run(xq, w, T, w.bits, w.G, [w.L] * w.B, triples=triples)
     print(f"c2 prefill chunk of 32, sampled triples: worst norm-wise rel err {worst:.2e}")
+
+
+def test_prefill_maximum_batch(xq):
+    """The largest batch any call accepts (128 sequences), ragged, three queries each."""
+    w = xi.C2.scaled(B=128, L=96, d=256, Hq=2, Hkv=2, n_outlier=2)
+    lens = [3 + (7 * b) % 94 for b in range(w.B)]
+    rng = np.random.default_rng(5)
+    triples = [(int(rng.integers(w.B)), int(rng.integers(3)), int(rng.integers(w.Hq))) for _ in range(40)] + [(127, 2, 1), (0, 0, 0)]
+    _run(xq, w, 3, 3, 128, lens=lens, triples=triples)
