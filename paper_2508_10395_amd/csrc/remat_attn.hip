@@ -475,7 +475,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         for (int j = 0; j < 8; ++j) acc[j] *= E[GPS + j / KSG];
     }
     if constexpr (MODE == MODE_SCORES || MODE == MODE_SCORES_PC) scores_epilogue(p, c, acc);
-    else if constexpr (MODE == MODE_WEIGHTED_SUM) weighted_sum_epilogue(p, c, acc);
+    else if constexpr (MODE == MODE_WEIGHTED_SUM) weighted_sum_epilogue(p, c, acc, lds);
     else if constexpr (MODE == MODE_ACCUMULATE) accumulate_epilogue(p, c, acc, lds);
     else if constexpr (MODE == MODE_PREFILL) prefill_epilogue(p, c, acc, lds);
     else attention_epilogue(p, c, acc);

@@ -124,6 +124,114 @@ __device__ __forceinline__ f32x16 mfma_bf16(const uint4& a, const uint4& b, cons
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// V^T images of the wave's 32 tokens from four accumulator blocks: element i of block nb is V[token tl][n],
+// n = 32 nb + 8 (i/4) + 4 half + i%4
+__device__ __forceinline__ void write_v_images(uint8_t* vt, const TileCtx& c, const f32x16& v0, const f32x16& v1,
+                                               const f32x16& v2, const f32x16& v3)
+{
+    const f32x16* blocks[4] = {&v0, &v1, &v2, &v3};
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int n = nb * 32 + (i >> 2) * 8 + c.half * 4 + (i & 3);
+            const float v = (*blocks[nb])[i];
+            const uint32_t h = pack_bf16x2_rne(v, 0.0f);
+            uint8_t* dst = vt + vt_offset(n, c.tl >> 2) + (c.tl & 3) * 2;
+            *reinterpret_cast<uint16_t*>(dst) = (uint16_t)h;
+            *reinterpret_cast<uint16_t*>(dst + VT_IMAGE_BYTES) = (uint16_t)pack_bf16x2_rne(v - bf16_lo_to_f32(h), 0.0f);
+        }
+}
+
+// Second half of the matrix-core epilogue for one group of up to 32 query rows (row q0 + lane % 32 in this
+// lane): given the wave's chunk maximum m, sum l and weights pr (register r <-> token 8 (r/4) + 4 half + r%4,
+// relative to m) it forms P V against the wave's V images, merges the eight waves of the workgroup (maxima and
+// sums through LDS, rescaled O blocks summed in fixed wave order through the staging area) and stores one
+// partial per query row and tile.  part_row(query index) gives the row's index in the partial buffers; rows at
+// or past n_rows are not stored.  Called by all eight waves (workgroup barriers inside).
+template <class PartRow>
+__device__ __forceinline__ void pv_merge_store(const RematParams& p, const TileCtx& c, uint8_t* lds, const uint8_t* vt,
+                                               bool active, float m, float l, const float (&pr)[16], int q0, int n_rows,
+                                               PartRow part_row)
+{
+    const int jq = c.tl;
+    float* mbuf = reinterpret_cast<float*>(lds + PF_STAGE_OFF);            // [wave][32 queries]
+    float* lbuf = mbuf + 8 * 32;
+    float* stage = reinterpret_cast<float*>(lds + PF_STAGE_OFF);           // [wave][16][64]
+    // maxima and sums of the eight chunks -> the tile's maximum M, this wave's factor 2^(m - M)
+    if (c.half == 0) {
+        mbuf[c.wave * 32 + jq] = m;
+        lbuf[c.wave * 32 + jq] = l;
+    }
+    __syncthreads();
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) M = fmaxf(M, mbuf[w * 32 + jq]);
+    const float Mu = M == -INFINITY ? 0.0f : M;
+    float Lt = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) Lt = __builtin_fmaf(lbuf[w * 32 + jq], __builtin_amdgcn_exp2f(mbuf[w * 32 + jq] - Mu), Lt);
+    const float f = __builtin_amdgcn_exp2f(m - Mu);                        // per lane-query
+    __syncthreads();                                                       // mbuf / lbuf are reused as staging
+    if (c.wave == 0 && c.half == 0 && q0 + jq < n_rows) {
+        const long long pidx = part_row(q0 + jq) * p.chunks_per_seq + c.tile;
+        p.part_ml[pidx * 2] = M;
+        p.part_ml[pidx * 2 + 1] = Lt;
+    }
+    uint4 phi[2], plo[2];
+    float fr[16];                                                          // the factor of register r's query
+    if (active) {
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+            float v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = pr[k2 * 8 + k];
+            split_bf16x8(v, phi[k2], plo[k2]);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) fr[r] = __shfl(f, (r >> 2) * 8 + c.half * 4 + (r & 3));
+    }
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+        f32x16 O;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[i] = 0.0f;
+        if (active) {
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2) {
+                // column n = 32 nb + jq of V, tokens 16 k2 + 4 half + [0, 4) and 16 k2 + 8 + 4 half + [0, 4)
+                const int n = nb * 32 + jq;
+                const uint8_t* v0 = vt + vt_offset(n, 4 * k2 + c.half);
+                const uint8_t* v1 = vt + vt_offset(n, 4 * k2 + c.half + 2);
+                const uint2 h0 = *reinterpret_cast<const uint2*>(v0), h1 = *reinterpret_cast<const uint2*>(v1);
+                const uint2 l0 = *reinterpret_cast<const uint2*>(v0 + VT_IMAGE_BYTES);
+                const uint2 l1 = *reinterpret_cast<const uint2*>(v1 + VT_IMAGE_BYTES);
+                const uint4 vh = make_uint4(h0.x, h0.y, h1.x, h1.y), vl = make_uint4(l0.x, l0.y, l1.x, l1.y);
+                O = mfma_bf16(plo[k2], vh, O);
+                O = mfma_bf16(phi[k2], vl, O);
+                O = mfma_bf16(phi[k2], vh, O);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) O[r] *= fr[r];
+        }
+        // O: lane = column 32 nb + jq, register r <-> query q0 + 8 (r/4) + 4 half + r%4.
+        // Sum over the waves in fixed order; wave w reduces and stores registers 2 w, 2 w + 1.
+#pragma unroll
+        for (int r = 0; r < 16; ++r) stage[(c.wave * 16 + r) * 64 + c.lane] = O[r];
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int r = 2 * c.wave + k;
+            float sum = stage[r * 64 + c.lane];
+#pragma unroll
+            for (int w = 1; w < 8; ++w) sum += stage[(w * 16 + r) * 64 + c.lane];
+            const int qr = q0 + (r >> 2) * 8 + c.half * 4 + (r & 3);
+            if (qr < n_rows) p.part_o[(part_row(qr) * p.chunks_per_seq + c.tile) * 128 + nb * 32 + jq] = sum;
+        }
+        __syncthreads();
+    }
+}
+
 // Called by all eight waves of the workgroup (it contains workgroup barriers); the LDS must not be
 // read or written by anything else any more.
 __device__ __forceinline__ void prefill_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8], uint8_t* lds)
@@ -134,18 +242,7 @@ __device__ __forceinline__ void prefill_epilogue(const RematParams& p, const Til
     uint4 khi[8], klo[8];
     if (active) {
         if (p.rope) rope_rotate(p, c, acc);
-        // V^T images: element i of block 4 + nb is V[token tl][n], n = 32 nb + 8 (i/4) + 4 half + i%4
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int n = nb * 32 + (i >> 2) * 8 + c.half * 4 + (i & 3);
-                const float v = acc[4 + nb][i];
-                const uint32_t h = pack_bf16x2_rne(v, 0.0f);
-                uint8_t* dst = vt + vt_offset(n, c.tl >> 2) + (c.tl & 3) * 2;
-                *reinterpret_cast<uint16_t*>(dst) = (uint16_t)h;
-                *reinterpret_cast<uint16_t*>(dst + VT_IMAGE_BYTES) = (uint16_t)pack_bf16x2_rne(v - bf16_lo_to_f32(h), 0.0f);
-            }
+        write_v_images(vt, c, acc[4], acc[5], acc[6], acc[7]);
         // K fragments: k-step ks covers columns [16 ks, 16 ks + 16); this lane's 8 of them are
         // 16 ks + 4 half + [0, 4) and 16 ks + 8 + 4 half + [0, 4)
 #pragma unroll
@@ -160,14 +257,15 @@ __device__ __forceinline__ void prefill_epilogue(const RematParams& p, const Til
 
     const int gq = p.Hq / p.Hkv, NQ = p.Tq * gq;
     const int jq = c.tl;
-    float* mbuf = reinterpret_cast<float*>(lds + PF_STAGE_OFF);            // [wave][32 queries]
-    float* lbuf = mbuf + 8 * 32;
-    float* stage = reinterpret_cast<float*>(lds + PF_STAGE_OFF);           // [wave][16][64]
+    auto part_row = [&](int qi) -> long long {
+        const int tq = qi / gq;
+        return ((long long)c.b * p.Tq + tq) * p.Hq + c.hk * gq + (qi - tq * gq);
+    };
     for (int q0 = 0; q0 < NQ; q0 += 32) {
         // this lane's query row of the group (rows past NQ repeat the last one and are not stored)
         const int qi = min(q0 + jq, NQ - 1);
-        const int tq = qi / gq, hq = c.hk * gq + (qi - tq * gq);
-        const long long qrow = ((long long)c.b * p.Tq + tq) * p.Hq + hq;
+        const int tq = qi / gq;
+        const long long qrow = part_row(qi);
         float m = -INFINITY, l = 0.0f;
         float pr[16];
         if (active) {
@@ -200,81 +298,7 @@ __device__ __forceinline__ void prefill_epilogue(const RematParams& p, const Til
             }
             l += __shfl_xor(l, 32);
         }
-        // maxima and sums of the eight chunks -> the tile's maximum M, this wave's factor 2^(m - M)
-        if (c.half == 0) {
-            mbuf[c.wave * 32 + jq] = m;
-            lbuf[c.wave * 32 + jq] = l;
-        }
-        __syncthreads();
-        float M = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < 8; ++w) M = fmaxf(M, mbuf[w * 32 + jq]);
-        const float Mu = M == -INFINITY ? 0.0f : M;
-        float Lt = 0.0f;
-#pragma unroll
-        for (int w = 0; w < 8; ++w) Lt = __builtin_fmaf(lbuf[w * 32 + jq], __builtin_amdgcn_exp2f(mbuf[w * 32 + jq] - Mu), Lt);
-        const float f = __builtin_amdgcn_exp2f(m - Mu);                    // per lane-query
-        __syncthreads();                                                   // mbuf / lbuf are reused as staging
-        if (c.wave == 0 && c.half == 0 && q0 + jq < NQ) {
-            const long long pidx = qrow * p.chunks_per_seq + c.tile;
-            p.part_ml[pidx * 2] = M;
-            p.part_ml[pidx * 2 + 1] = Lt;
-        }
-        uint4 phi[2], plo[2];
-        float fr[16];                                                      // the factor of register r's query
-        if (active) {
-#pragma unroll
-            for (int k2 = 0; k2 < 2; ++k2) {
-                float v[8];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) v[k] = pr[k2 * 8 + k];
-                split_bf16x8(v, phi[k2], plo[k2]);
-            }
-#pragma unroll
-            for (int r = 0; r < 16; ++r) fr[r] = __shfl(f, (r >> 2) * 8 + c.half * 4 + (r & 3));
-        }
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb) {
-            f32x16 O;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) O[i] = 0.0f;
-            if (active) {
-#pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2) {
-                    // column n = 32 nb + jq of V, tokens 16 k2 + 4 half + [0, 4) and 16 k2 + 8 + 4 half + [0, 4)
-                    const int n = nb * 32 + jq;
-                    const uint8_t* v0 = vt + vt_offset(n, 4 * k2 + c.half);
-                    const uint8_t* v1 = vt + vt_offset(n, 4 * k2 + c.half + 2);
-                    const uint2 h0 = *reinterpret_cast<const uint2*>(v0), h1 = *reinterpret_cast<const uint2*>(v1);
-                    const uint2 l0 = *reinterpret_cast<const uint2*>(v0 + VT_IMAGE_BYTES);
-                    const uint2 l1 = *reinterpret_cast<const uint2*>(v1 + VT_IMAGE_BYTES);
-                    const uint4 vh = make_uint4(h0.x, h0.y, h1.x, h1.y), vl = make_uint4(l0.x, l0.y, l1.x, l1.y);
-                    O = mfma_bf16(plo[k2], vh, O);
-                    O = mfma_bf16(phi[k2], vl, O);
-                    O = mfma_bf16(phi[k2], vh, O);
-                }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) O[r] *= fr[r];
-            }
-            // O: lane = column 32 nb + jq, register r <-> query q0 + 8 (r/4) + 4 half + r%4.
-            // Sum over the waves in fixed order; wave w reduces and stores registers 2 w, 2 w + 1.
-#pragma unroll
-            for (int r = 0; r < 16; ++r) stage[(c.wave * 16 + r) * 64 + c.lane] = O[r];
-            __syncthreads();
-#pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                const int r = 2 * c.wave + k;
-                float sum = stage[r * 64 + c.lane];
-#pragma unroll
-                for (int w = 1; w < 8; ++w) sum += stage[(w * 16 + r) * 64 + c.lane];
-                const int qr = q0 + (r >> 2) * 8 + c.half * 4 + (r & 3);
-                if (qr < NQ) {
-                    const int tr = qr / gq, hr = c.hk * gq + (qr - tr * gq);
-                    p.part_o[((((long long)c.b * p.Tq + tr) * p.Hq + hr) * p.chunks_per_seq + c.tile) * 128 + nb * 32 + jq] = sum;
-                }
-            }
-            __syncthreads();
-        }
+        pv_merge_store(p, c, lds, vt, active, m, l, pr, q0, NQ, part_row);
     }
 }
 
@@ -310,42 +334,49 @@ __device__ __forceinline__ void scores_epilogue(const RematParams& p, const Tile
     });
 }
 
-// pass 2: blocks 0-3 / 4-7 hold the values of the two KV heads; one partial (m, l, o[128]) per query head
-__device__ __forceinline__ void weighted_sum_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8])
+// pass 2: blocks 0-3 / 4-7 hold the values of the two KV heads.  Per head, the stored scores of its query
+// heads (lane = query head, registers = 16 of the wave's 32 tokens) become softmax weights and go through the
+// second half of the matrix-core epilogue: one partial (m, l, o[128]) per query head and tile.
+// Called by all eight waves of the workgroup.
+__device__ __forceinline__ void weighted_sum_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8], uint8_t* lds)
 {
-    if (c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS >= c.len) return;
+    const int tok0 = c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS;
+    const bool active = tok0 < c.len;
+    uint8_t* vt = lds + c.wave * VT_WAVE_BYTES;
     const int gq = p.Hq / p.Hkv;
-    const int chunk = c.tile * (TILE_TOKENS / CHUNK_TOKENS) + c.wave;
     const long long srow = p.score_stride;
-    static_for<0, 2>([&](auto HH) XQ_INLINE_LAMBDA {
+    static_for<0, 2>([&](auto HH) XQ_INLINE_LAMBDA {       // (compile-time: the accumulator must stay in registers)
         constexpr int hh = decltype(HH)::value;
-        for (int j = 0; j < gq; ++j) {
-            const int hq = (2 * c.hk + hh) * gq + j;
-            float sc = p.scores[((long long)c.b * p.Hq + hq) * srow + min(c.tok, c.len - 1)];
-            sc = c.tok < c.len ? sc : -INFINITY;
-            const float m = wave32_max(sc);
-            const float pv = __builtin_amdgcn_exp2f(sc - m);
-            const float l = wave32_sum(pv);
-            const long long pidx = ((long long)c.b * p.Hq + hq) * p.chunks_per_seq + chunk;
-            float* po = p.part_o + pidx * 128;
+        const int hq0 = (2 * c.hk + hh) * gq;
+        if (active) write_v_images(vt, c, acc[4 * hh], acc[4 * hh + 1], acc[4 * hh + 2], acc[4 * hh + 3]);
+        __builtin_amdgcn_wave_barrier();
+        auto part_row = [&](int qi) -> long long { return (long long)c.b * p.Hq + hq0 + qi; };
+        float m = -INFINITY, l = 0.0f;
+        float pr[16];
+        if (active) {
+            const float* sp = p.scores + ((long long)c.b * p.Hq + hq0 + min(c.tl, gq - 1)) * srow + tok0 + c.half * 4;
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
+            for (int i4 = 0; i4 < 4; ++i4) {
+                // tokens tok0 + 8 i4 + 4 half + [0, 4): 16 bytes; past len the buffer holds other rows' or stale values
+                const float4 s4 = *reinterpret_cast<const float4*>(sp + 8 * i4);
+                const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
 #pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    const f32x16& a = acc[4 * hh + nb];
-                    float o[4];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) o[k] = wave32_sum_upper(pv * a[i4 * 4 + k]);
-                    if (c.tl == 16) {
-                        float4 w; w.x = o[0]; w.y = o[1]; w.z = o[2]; w.w = o[3];
-                        *reinterpret_cast<float4*>(po + nb * 32 + i4 * 8 + c.half * 4) = w;
-                    }
+                for (int k = 0; k < 4; ++k) {
+                    const int tok = tok0 + 8 * i4 + 4 * c.half + k;
+                    pr[4 * i4 + k] = tok < c.len ? sv[k] : -INFINITY;
+                    m = fmaxf(m, pr[4 * i4 + k]);
                 }
-            if (c.lane == 0) {
-                p.part_ml[pidx * 2] = m;
-                p.part_ml[pidx * 2 + 1] = l;
             }
+            m = fmaxf(m, __shfl_xor(m, 32));
+            const float mu = m == -INFINITY ? 0.0f : m;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                pr[r] = __builtin_amdgcn_exp2f(pr[r] - mu);
+                l += pr[r];
+            }
+            l += __shfl_xor(l, 32);
         }
+        pv_merge_store(p, c, lds, vt, active, m, l, pr, 0, gq, part_row);
     });
 }
 

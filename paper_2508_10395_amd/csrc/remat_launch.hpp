@@ -34,11 +34,12 @@ size_t remat_latent_workspace_bytes(int B, int Hq, int max_len, int r, int group
            (size_t)B * Hq * tiles * TILE_TOKENS * sizeof(float);
 }
 
-// the prefill epilogue lays its own images over the whole LDS once the contraction is done
+// the matrix-core epilogues lay their own images over the whole LDS once the contraction is done
 template <int MODE>
 constexpr int lds_for_mode(int bits)
 {
-    return MODE == MODE_PREFILL && LDS_PREFILL_TOTAL > lds_coded_total(bits) ? LDS_PREFILL_TOTAL : lds_coded_total(bits);
+    return (MODE == MODE_PREFILL || MODE == MODE_WEIGHTED_SUM) && LDS_PREFILL_TOTAL > lds_coded_total(bits)
+               ? LDS_PREFILL_TOTAL : lds_coded_total(bits);
 }
 
 template <int MODE>
@@ -209,12 +210,13 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
     p.wprep = static_cast<const uint8_t*>(wprep);
     e = launch_coded<MODE_SCORES>(bits, G, p, grid, s);
     if (e != hipSuccess) return e;
-    // pass 2: values
+    // pass 2: values; its epilogue merges the eight chunks of a tile: one partial per tile
     p.codes = xc->codes + (size_t)r * bits / 8; p.zero = xc->zero + L.ng; p.eT = eT_v;
     p.wprep = static_cast<const uint8_t*>(wprep) + L.total_bytes;
+    p.chunks_per_seq = p.tiles_per_seq;
     e = launch_coded<MODE_WEIGHTED_SUM>(bits, G, p, grid, s);
     if (e != hipSuccess) return e;
-    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len, 1, CHUNK_TOKENS);
+    combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.tiles_per_seq, p.len, 1, TILE_TOKENS);
     return hipGetLastError();
 }
 
@@ -535,9 +537,10 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
     v.wprep = static_cast<const uint8_t*>(wv_coded);
     v.n_main_slabs = Lv.n_main_slabs; v.n_corr_ksteps = Lv.n_corr_ksteps; v.ng = Lv.ng; v.ng_pad = Lv.ng_pad; v.ng_row = Lv.ng;
     v.head_bytes = (long long)Lv.head_bytes;
+    v.chunks_per_seq = tiles_all;                        // one partial per tile
     e = launch_coded<MODE_WEIGHTED_SUM>(vbits, vG, v, pairs * B * tiles_all, s);
     if (e != hipSuccess) return e;
-    combine_kernel<<<dim3(p.Hq, B), dim3(128 * COMBINE_GROUPS), 0, s>>>(part_o, part_ml, out, p.Hq, chunks, len, 1, CHUNK_TOKENS);
+    combine_kernel<<<dim3(p.Hq, B), dim3(128 * COMBINE_GROUPS), 0, s>>>(part_o, part_ml, out, p.Hq, tiles_all, len, 1, TILE_TOKENS);
     return hipGetLastError();
 }
 
