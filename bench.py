@@ -285,6 +285,66 @@ def main():
                               "delta_projection_us": t_d * 1e3,
                               "remat_attn_from_accumulator_ms": t_a}
         del dcache, oacc, uprep, uws, dwp, dws
+        torch.cuda.empty_cache()
+        # config 3: one XQuant-CL decode step through 32 layers (B=8, L=8192, d=4096, MHA): per layer, merge the layer's
+        # 2-bit delta cache into the accumulator, then attend from the accumulator with the layer's weights.  Random
+        # deltas and weights (timing only); the 32 delta caches and weight streams are distinct.
+        w3 = xi.C3
+        a3 = xq.XQAttn(w3.Hq, w3.Hkv, w3.hd, w3.hd ** -0.5)
+        n_layers = 32
+        acc3 = torch.randn((w3.B, w3.L, w3.d), device=dev, generator=gen).to(torch.bfloat16)
+        deltas, streams = [], []
+        for _ in range(n_layers):
+            dcl = xq.alloc_cache(w3.B, w3.L, w3.d, w3.G, 2)
+            dcl.codes.copy_(torch.randint(0, 256, dcl.codes.shape, device=dev, dtype=torch.uint8, generator=gen))
+            dcl.scale.fill_(0.01)
+            dcl.zero.fill_(-0.015)
+            deltas.append(dcl)
+            wk3 = (torch.randn((w3.d, w3.Hkv * w3.hd), device=dev, generator=gen) * w3.d ** -0.5).to(torch.bfloat16)
+            wv3 = (torch.randn((w3.d, w3.Hkv * w3.hd), device=dev, generator=gen) * w3.d ** -0.5).to(torch.bfloat16)
+            streams.append(xq.xq_prepare_weights(a3, w3.d, 0, 16, wk3, wv3))
+            del wk3, wv3
+        q3 = dev_bf16(xi.gen_q(w3))
+        out3 = torch.empty((w3.B, w3.Hq, w3.hd), dtype=torch.float32, device=dev)
+        ws3 = torch.empty(xq.xq_remat_attn_workspace_bytes(a3, w3.B, w3.L, w3.d, 0), dtype=torch.uint8, device=dev)
+        lens3 = [w3.L] * w3.B
+
+        def cl_step():
+            for l in range(n_layers):
+                xq.xq_cl_accumulate(acc3, deltas[l], lens3, False)
+                xq.xq_remat_attn_decode(a3, q3, streams[l], lens3, acc_bf16=acc3, out=out3, workspace=ws3)
+
+        t_cl = timed(cl_step, n=2, warm=1)
+        extra["cl_decode_step_c3_32_layers"] = {"workload": "c3: B=8, L=8192, d=4096 MHA, 2-bit deltas, 32 layers", "ms": t_cl,
+                                                "ms_per_layer": t_cl / n_layers,
+                                                "tokens/s/layer": w3.B * w3.L / (t_cl / n_layers * 1e-3)}
+        del deltas, streams, acc3, ws3
+        torch.cuda.empty_cache()
+        # config 5: 64 decode steps of a long context (B=4, 2-bit, group 128), the length growing from 32704 to 32768
+        w5 = xi.C5
+        a5 = xq.XQAttn(w5.Hq, w5.Hkv, w5.hd, w5.hd ** -0.5)
+        c5 = xq.alloc_cache(w5.B, w5.L, w5.d, w5.G, w5.bits)
+        for b0 in range(w5.B):
+            sub = xq.XQCache(c5.codes[b0:b0 + 1], c5.scale[b0:b0 + 1], c5.zero[b0:b0 + 1], 1, w5.L, w5.d, w5.G, w5.bits)
+            xq.xq_quantize_append(sub, torch.randn((1, w5.L, w5.d), device=dev, generator=gen).to(torch.bfloat16), [0])
+        wk5, wv5 = xi.gen_weights(w5)
+        wp5 = xq.xq_prepare_weights(a5, w5.d, w5.G, w5.bits, dev_bf16(wk5), dev_bf16(wv5))
+        q5 = dev_bf16(xi.gen_q(w5))
+        out5 = torch.empty((w5.B, w5.Hq, w5.hd), dtype=torch.float32, device=dev)
+        ws5 = torch.empty(xq.xq_remat_attn_workspace_bytes(a5, w5.B, w5.L, w5.d, w5.G), dtype=torch.uint8, device=dev)
+        x5 = torch.randn((w5.B, 1, w5.d), device=dev, generator=gen).to(torch.bfloat16)
+
+        def c5_steps():
+            for i in range(64):
+                n = w5.L - 64 + i
+                xq.xq_quantize_append(c5, x5, [n] * w5.B)
+                xq.xq_remat_attn_decode(a5, q5, wp5, [n + 1] * w5.B, xcache=c5, out=out5, workspace=ws5)
+
+        t_c5 = timed(c5_steps, n=1, warm=1)
+        extra["decode_64_steps_c5"] = {"workload": "c5: B=4, context 32704 -> 32768, 2-bit, group 128; 64 x (append 1 token, attend)",
+                                       "ms": t_c5, "ms_per_step": t_c5 / 64,
+                                       "tokens/s/layer": w5.B * w5.L / (t_c5 / 64 * 1e-3)}
+        del c5, wp5, ws5
 
     traffic = K3_HBM_BYTES_PER_LAUNCH
 
