@@ -55,6 +55,7 @@ struct RematParams {
     int B, cap, d, Hq, Hkv;
     int row_d, ng_row;       // coded source: channels / groups per cache row (>= d, ng when a sub-range is contracted)
     int grid_heads;          // heads (or head pairs) the grid is laid over
+    int tile_major;          // workgroup order inside an XCD: 0 = a head's tiles one after the other, 1 = a tile's heads side by side
     float* scores;           // latent passes: q.K * scale * log2(e), [B][Hq][score_stride]
     int score_stride;        // floats per (sequence, query head) in scores
     BatchI32 tok0;           // pass 1: token index of this launch's row 0 in scores (0 unless a launch continues another)
@@ -168,8 +169,15 @@ __device__ __forceinline__ bool locate_tile(const RematParams& p, TileCtx& c)
     int tile_lin;
     if ((p.grid_heads & 7) == 0) {
         const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-        c.hk = xcd + 8 * (j / NT);
-        tile_lin = j % NT;
+        if (p.tile_major) {
+            // the heads of an XCD take the same tile side by side: what they share is then the tile's token rows
+            const int hpx = p.grid_heads >> 3;
+            c.hk = xcd + 8 * (j % hpx);
+            tile_lin = j / hpx;
+        } else {
+            c.hk = xcd + 8 * (j / NT);
+            tile_lin = j % NT;
+        }
     } else {
         c.hk = blockIdx.x / NT;
         tile_lin = blockIdx.x % NT;
