@@ -215,6 +215,20 @@ xq_status_t xq_remat_attn_prefill(const xq_attn_t *a, const uint16_t *q_bf16, in
  *   of pass 1 wait in the workspace).  Arguments as xq_remat_attn_decode with an X cache;
  *   workspace size: xq_remat_attn_latent_workspace_bytes(a, B, max_len, r, group).
  */
+/*
+ * The same projection for prefill-sized M, on the matrix cores through the dense-source contraction
+ * kernel (about ten times the rate of xq_latent_project from a few thousand rows on; same result up to
+ * the order of the fp32 accumulation):
+ *   xq_prepare_projection: offline re-layout of Ut (dev [n_lat][d] bf16) into out, at least
+ *     xq_prepared_projection_bytes(d, n_lat) bytes (0 = unsupported: d multiple of 128, n_lat of 256)
+ *   xq_latent_project_bulk: out_bf16[m][n] = bf16( sum_c x[m][c] * Ut[n][c] ) for M rows; x_bf16 dev [M][d],
+ *     out_bf16 dev [M][n_lat].  M = 0 is a no-op; M * d must stay below 2^31 (split larger inputs).
+ */
+size_t      xq_prepared_projection_bytes(int32_t d, int32_t n_lat);
+xq_status_t xq_prepare_projection(int32_t d, int32_t n_lat, const uint16_t *Ut_bf16, void *out, size_t out_bytes,
+                                  void *stream);
+xq_status_t xq_latent_project_bulk(const uint16_t *x_bf16, const void *proj, int64_t M, int32_t d, int32_t n_lat,
+                                   uint16_t *out_bf16, void *stream);
 size_t      xq_prepared_weights_latent_bytes(const xq_attn_t *a, int32_t r, int32_t group, int32_t src_bits);
 size_t      xq_remat_attn_latent_workspace_bytes(const xq_attn_t *a, int32_t B, int32_t max_len, int32_t r,
                                                  int32_t group);

@@ -16,4 +16,5 @@ from .binding import (  # noqa: F401
     xq_remat_attn_per_channel_workspace_bytes, xq_remat_attn_decode_per_channel,
     xq_prepared_weights_pairs_bytes, xq_prepare_weights_pairs,
     xq_remat_attn_latent_per_channel_workspace_bytes, xq_remat_attn_decode_latent_per_channel,
+    xq_prepare_projection, xq_latent_project_bulk,
 )

@@ -30,6 +30,7 @@ SYMBOLS = [
     "xq_remat_attn_per_channel_workspace_bytes", "xq_remat_attn_decode_per_channel",
     "xq_prepared_weights_pairs_bytes", "xq_prepare_weights_pairs",
     "xq_remat_attn_latent_per_channel_workspace_bytes", "xq_remat_attn_decode_latent_per_channel",
+    "xq_prepared_projection_bytes", "xq_prepare_projection", "xq_latent_project_bulk",
 ]
 
 
@@ -152,6 +153,12 @@ def load_library():
                                                             C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p,
                                                             C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_size_t,
                                                             C.c_void_p]
+    lib.xq_prepared_projection_bytes.restype = C.c_size_t
+    lib.xq_prepared_projection_bytes.argtypes = [C.c_int32, C.c_int32]
+    lib.xq_prepare_projection.restype = C.c_int
+    lib.xq_prepare_projection.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.xq_latent_project_bulk.restype = C.c_int
+    lib.xq_latent_project_bulk.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     _LIB = lib
     return lib
 
@@ -554,4 +561,30 @@ def xq_remat_attn_decode_latent_per_channel(attn, q_bf16, kcache, ktail_bf16, vc
         C.byref(a), _ptr(q_bf16), C.byref(ks), _ptr(ktail_bf16), C.byref(vs), _ptr(wk_coded), _ptr(wk_dense),
         _ptr(wv_coded), _i32(lens, kcache.B), _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
         "xq_remat_attn_decode_latent_per_channel")
+    return out
+
+
+def xq_prepare_projection(Ut_bf16, out=None):
+    """Prepared stream of U (given transposed, [n_lat][d] bf16) for xq_latent_project_bulk."""
+    assert Ut_bf16.dtype == torch.bfloat16 and Ut_bf16.is_contiguous() and Ut_bf16.dim() == 2
+    n_lat, d = Ut_bf16.shape
+    nbytes = load_library().xq_prepared_projection_bytes(d, n_lat)
+    if nbytes == 0:
+        raise XQError("xq_prepare_projection: unsupported shape")
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=Ut_bf16.device)
+    _check(load_library().xq_prepare_projection(d, n_lat, _ptr(Ut_bf16), _ptr(out), out.numel(), _stream()),
+           "xq_prepare_projection")
+    return out
+
+
+def xq_latent_project_bulk(x_bf16, proj, n_lat, out=None):
+    """x [..., d] bf16 times U through the matrix cores -> [..., n_lat] bf16 (proj from xq_prepare_projection)."""
+    assert x_bf16.dtype == torch.bfloat16 and x_bf16.is_contiguous()
+    d = x_bf16.shape[-1]
+    M = x_bf16.numel() // d
+    if out is None:
+        out = torch.empty((*x_bf16.shape[:-1], n_lat), dtype=torch.bfloat16, device=x_bf16.device)
+    _check(load_library().xq_latent_project_bulk(_ptr(x_bf16), _ptr(proj), M, d, n_lat, _ptr(out), _stream()),
+           "xq_latent_project_bulk")
     return out

@@ -11,7 +11,9 @@ hipError_t run_quantize_append(const xq_cache_t* c, const uint16_t* x, const uin
 hipError_t run_cl_accumulate(uint16_t* acc, const xq_cache_t* c, const BatchI32& len, int max_len,
                              bool init, hipStream_t s);
 hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, int ncols,
-                               int head_stride, void* out, hipStream_t s);
+                               int head_stride, void* out, hipStream_t s, bool transposed = false);
+hipError_t run_project_rows_dense(const uint16_t* x, long long M, int d, int n_lat, const void* proj, uint16_t* out,
+                                  hipStream_t s);
 hipError_t run_latent_project(const uint16_t* x, const uint16_t* ut, int M, int d, int n_lat, uint16_t* out,
                               hipStream_t s);
 hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
@@ -485,6 +487,39 @@ xq_status_t xq_remat_attn_decode_latent_per_channel(const xq_attn_t* a, const ui
         return XQ_ERR_WORKSPACE;
     hipError_t e = run_remat_attn_decode_latent_pc(a, q_bf16, kcache, ktail_bf16, vcache, wk_coded, wk_dense, wv_coded, lv,
                                                    max_len, out, workspace, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+// bulk projection (prefill-sized M) through the dense-source contraction kernel
+size_t xq_prepared_projection_bytes(int32_t d, int32_t n_lat)
+{
+    if (d <= 0 || d % 128 != 0 || n_lat <= 0 || n_lat % 256 != 0) return 0;
+    return make_wprep_layout(d, 128, 16, n_lat / 256).total_bytes;
+}
+
+xq_status_t xq_prepare_projection(int32_t d, int32_t n_lat, const uint16_t* Ut_bf16, void* out, size_t out_bytes,
+                                  void* stream)
+{
+    if (!Ut_bf16 || !out || !aligned16(Ut_bf16) || !aligned16(out) || d <= 0 || n_lat <= 0) return XQ_ERR_INVALID_ARG;
+    const size_t need = xq_prepared_projection_bytes(d, n_lat);
+    if (need == 0) return XQ_ERR_UNSUPPORTED;
+    if (out_bytes < need) return XQ_ERR_WORKSPACE;
+    const WPrepLayout L = make_wprep_layout(d, 128, 16, n_lat / 256);
+    hipError_t e = run_prepare_weights(L, Ut_bf16, Ut_bf16 + (size_t)128 * d, n_lat, 256, out,
+                                       static_cast<hipStream_t>(stream), true);
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+xq_status_t xq_latent_project_bulk(const uint16_t* x_bf16, const void* proj, int64_t M, int32_t d, int32_t n_lat,
+                                   uint16_t* out_bf16, void* stream)
+{
+    if (M < 0 || d <= 0 || n_lat <= 0) return XQ_ERR_INVALID_ARG;
+    // (the kernel addresses the rows of a sequence with 32-bit byte offsets)
+    if (xq_prepared_projection_bytes(d, n_lat) == 0 || M * (long long)d * 2 >= (1LL << 32)) return XQ_ERR_UNSUPPORTED;
+    if (M == 0) return XQ_OK;
+    if (!x_bf16 || !proj || !out_bf16 || !aligned16(x_bf16) || !aligned16(proj) || !aligned16(out_bf16))
+        return XQ_ERR_INVALID_ARG;
+    hipError_t e = run_project_rows_dense(x_bf16, M, d, n_lat, proj, out_bf16, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 

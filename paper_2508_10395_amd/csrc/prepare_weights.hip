@@ -19,6 +19,7 @@ struct PrepArgs {
     float* colsum;   // [Hkv][ng][256]: per-group sums of the weight rows
     int d, G, bits, Hkv, ncols;
     int head_stride; // columns between consecutive heads in Wk / Wv (128; 256 when a "head" is a pair of heads)
+    int transposed;  // the matrices are given transposed ([column][d], as the projection matrices are): d = row length
     int n_main_slabs, ng, ng_pad, n_corr_slabs;
     long long head_bytes;
     UnpackTable tab;
@@ -28,7 +29,8 @@ struct PrepArgs {
 __device__ __forceinline__ float wval(const PrepArgs& a, int h, int c, int n)
 {
     const uint16_t* W = n < 128 ? a.Wk : a.Wv;
-    return bf16_bits_to_f32(W[(long long)c * a.ncols + h * a.head_stride + (n & 127)]);
+    const long long col = h * a.head_stride + (n & 127);
+    return bf16_bits_to_f32(a.transposed ? W[col * a.d + c] : W[(long long)c * a.ncols + col]);
 }
 
 __global__ __launch_bounds__(256) void colsum_kernel(PrepArgs a)
@@ -133,10 +135,11 @@ bool unpack_table_for(int bits, UnpackTable* t)
 
 // Wk / Wv: [d][ncols] row-major; head h takes columns [h * head_stride, +128) of each
 hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, int ncols,
-                               int head_stride, void* out, hipStream_t s)
+                               int head_stride, void* out, hipStream_t s, bool transposed)
 {
     PrepArgs a{};
     a.head_stride = head_stride;
+    a.transposed = transposed ? 1 : 0;
     a.Wk = Wk; a.Wv = Wv;
     a.out = static_cast<uint8_t*>(out);
     a.colsum = reinterpret_cast<float*>(a.out + L.stream_bytes);

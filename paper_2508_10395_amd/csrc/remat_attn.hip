@@ -501,8 +501,9 @@ static_assert(LDS_DENSE_TOTAL <= LDS_MAX, "dense kernel LDS");
 
 // DMODE: 0 decode attention, 1 matrix-core epilogue (prefill), 2 store the rematerialised rows
 // as fp32 (used for the zero-point term of a per-channel cache), 3 pass 1 of the latent path (scores of a
-// pair of KV heads) for the rows of a residual window
-constexpr int DENSE_ATTENTION = 0, DENSE_PREFILL = 1, DENSE_STORE = 2, DENSE_SCORES = 3;
+// pair of KV heads) for the rows of a residual window, 4 store the rows as bf16 (a plain GEMM: the bulk
+// projection into the latent space)
+constexpr int DENSE_ATTENTION = 0, DENSE_PREFILL = 1, DENSE_STORE = 2, DENSE_SCORES = 3, DENSE_STORE_BF16 = 4;
 template <int DMODE>
 __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams p)
 {
@@ -621,6 +622,20 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
                     v.z = __builtin_fmaf(p.store_scale, acc[nb][i4 * 4 + 2], v.z);
                     v.w = __builtin_fmaf(p.store_scale, acc[nb][i4 * 4 + 3], v.w);
                     *reinterpret_cast<float4*>(row + nb * 32 + i4 * 8) = v;
+                }
+        }
+    } else if constexpr (DMODE == DENSE_STORE_BF16) {
+        // a plain bf16 GEMM row block: out[token][256 hk + column], one RNE rounding (the bulk projection X U)
+        if (c.tok < c.len) {
+            uint16_t* row = p.rows_out + ((long long)c.tok * p.grid_heads + c.hk) * 256 + c.half * 4;
+#pragma unroll
+            for (int nb = 0; nb < 8; ++nb)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    uint2 v;
+                    v.x = pack_bf16x2_rne(acc[nb][i4 * 4], acc[nb][i4 * 4 + 1]);
+                    v.y = pack_bf16x2_rne(acc[nb][i4 * 4 + 2], acc[nb][i4 * 4 + 3]);
+                    *reinterpret_cast<uint2*>(row + nb * 32 + i4 * 8) = v;
                 }
         }
     } else if constexpr (DMODE == DENSE_SCORES) {

@@ -73,6 +73,7 @@ struct RematParams {
                              //   (4-bit codes: plus 8 times the scales of the block times those columns)
     float store_scale;       // dense store mode: kv_out = (store_add ? kv_out : 0) + store_scale * row
     int store_add;
+    uint16_t* rows_out;      // dense bf16 store mode: [rows][grid_heads * 256] bf16 (one sequence)
     float* kv_out;           // dense store mode: [B][pc_blocks_cap][grid_heads][256] fp32 rematerialised rows
     int pc_block, pc_blocks_cap;   // tokens per block (64 or 128), blocks per sequence in the arrays above
     const float* rope;       // optional [n_pos][64][2] cos, sin: rotate the keys (half-split pairs)

@@ -549,4 +549,22 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
     return hipGetLastError();
 }
 
+// Bulk projection of M rows into the latent space (Sec. 3.3.1), out = bf16(x U): the dense-source contraction
+// kernel over one "sequence" of M rows, the n_lat columns laid over n_lat / 256 column blocks, rows stored as bf16.
+hipError_t run_project_rows_dense(const uint16_t* x, long long M, int d, int n_lat, const void* proj, uint16_t* out,
+                                  hipStream_t s)
+{
+    const int blocks = n_lat / 256;
+    const WPrepLayout L = make_wprep_layout(d, 128, 16, blocks);
+    RematParams p{};
+    p.acc = x; p.B = 1; p.cap = (int)M; p.d = d; p.row_d = d;
+    p.Hq = p.Hkv = blocks; p.grid_heads = blocks; p.tile_major = 1;
+    p.len.v[0] = (int)M;
+    p.tiles_per_seq = (int)((M + TILE_TOKENS - 1) / TILE_TOKENS);
+    p.wprep = static_cast<const uint8_t*>(proj);
+    p.n_main_slabs = L.n_main_slabs; p.head_bytes = (long long)L.head_bytes;
+    p.rows_out = out;
+    return launch_with_lds(remat_attn_dense_kernel<DENSE_STORE_BF16>, LDS_DENSE_TOTAL, p, blocks * p.tiles_per_seq, s);
+}
+
 }  // namespace xq

@@ -136,3 +136,20 @@ def test_full_size_llama3_8b_latent_sampled_pairs(xq):
     w = xi.C4
     worst = _run_latent(xq, w, w.bits, w.G, [w.L] * w.B, pairs=xi.sample_pairs(w, 8))
     print(f"c4 latent sampled pairs: worst norm-wise rel err {worst:.2e}")
+
+
+@pytest.mark.parametrize("M,d,n_lat", [(1, 256, 256), (300, 256, 512), (777, 512, 256), (5000, 384, 768)])
+def test_bulk_projection_matches_oracle(xq, M, d, n_lat):
+    """The matrix-core route of the same projection (dense-source contraction kernel, rows stored as bf16)."""
+    rng = np.random.default_rng(M + d + 1)
+    x = bits(rng.standard_normal((M, d)))
+    ut = bits(rng.standard_normal((n_lat, d)) * d ** -0.5)
+    proj = xq.xq_prepare_projection(bits_to_torch(ut))
+    out = torch.full((M, n_lat), 9.0, dtype=torch.bfloat16, device="cuda")
+    xq.xq_latent_project_bulk(bits_to_torch(x), proj, n_lat, out=out)
+    torch.cuda.synchronize()
+    sample = np.unique(np.concatenate([np.arange(min(M, 40)), np.arange(max(M - 40, 0), M), rng.integers(0, M, 60)]))
+    _check_projection(torch_to_bits(out)[sample], xo.project_rows(x[sample], ut), x[sample], ut)
+    small = xq.xq_latent_project(bits_to_torch(x[sample]), bits_to_torch(ut))
+    assert np.mean(torch_to_bits(small) != torch_to_bits(out)[sample]) < 5e-3      # two accumulation orders of the same sum
+    assert xq.xq_latent_project_bulk(torch.empty((0, d), dtype=torch.bfloat16, device="cuda"), proj, n_lat).shape == (0, n_lat)

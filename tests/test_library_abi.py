@@ -126,6 +126,13 @@ def test_argument_errors_of_the_widened_entry_points():
     assert lib.xq_latent_project(x, x, 4, 200, 64, x, st) == UNSUPPORTED
     assert lib.xq_latent_project(x, x, -1, 256, 64, x, st) == INVALID
     assert lib.xq_latent_project(None, x, 0, 256, 64, x, st) == 0               # no rows: nothing is read
+    assert xq.load_library().xq_prepared_projection_bytes(4096, 2048) == 4096 * 2048 * 2
+    assert xq.load_library().xq_prepared_projection_bytes(4096, 2048 + 128) == 0             # n_lat not a multiple of 256
+    assert lib.xq_prepare_projection(512, 256, x, x, 16, st) == WORKSPACE
+    assert lib.xq_prepare_projection(512, 200, x, x, 1 << 30, st) == UNSUPPORTED
+    assert lib.xq_latent_project_bulk(x, x, 0, 512, 256, x, st) == 0
+    assert lib.xq_latent_project_bulk(None, x, 4, 512, 256, x, st) == INVALID
+    assert lib.xq_latent_project_bulk(x, x, 1 << 22, 4096, 256, x, st) == UNSUPPORTED        # rows beyond 32-bit byte offsets
     dp = lambda **kw: lib.xq_cl_latent_delta_project(*[dict(dict(x=x, acc=x, ut=x, B=1, T=1, cap=8, start=one, d=256,
                                                                  n=64, out=x, st=st), **kw)[k]
                                                        for k in ("x", "acc", "ut", "B", "T", "cap", "start", "d", "n", "out", "st")])
