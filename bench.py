@@ -378,9 +378,14 @@ def main():
         pairs = xi.sample_pairs(w, args.cpu_pairs)
         step()                                   # `out` again holds the XQuant step's result
         torch.cuda.synchronize()
-        codes_h = cache.codes.cpu().numpy()
-        scale_h = cache.scale.cpu().view(torch.int16).numpy().view(np.uint16)
-        zero_h = cache.zero.cpu().view(torch.int16).numpy().view(np.uint16)
+        # the oracle's own cache of the sampled sequences, quantised by the oracle from the same seeded X
+        # (untimed, like the GPU's prefill of the cache; the step's own append of one token is in it)
+        codes_h = np.zeros((B, L, d * bits // 8), np.uint8)
+        scale_h = np.zeros((B, L, d // G), np.uint16)
+        zero_h = np.zeros((B, L, d // G), np.uint16)
+        for b in sorted({b for b, _ in pairs}):
+            c_, s_, z_ = xo.quantize_rows(xi.from_bf16_bits(x_bits[b]), G, bits)
+            codes_h[b], scale_h[b], zero_h[b] = xo.pack_rows(c_, bits), s_, z_
         c0 = time.perf_counter()
         ref = xo.remat_attn_pairs(q_bf16=q_bits, Wk=wk_bits, Wv=wv_bits, Hq=Hq, Hkv=Hkv, hd=hd,
                                   softmax_scale=hd ** -0.5, lens=lens, pairs=pairs, packed=codes_h,

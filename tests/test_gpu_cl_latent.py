@@ -101,7 +101,8 @@ def _accumulate_case(xq, B, cap, d, n_lat, G, b, lens, seed, sample_rows=None, o
     torch.cuda.synchronize()
     got = torch_to_bits(acc)
     a0 = torch_to_bits(acc0)
-    packed, sc, ze = cache.codes.cpu().numpy(), torch_to_bits(cache.scale), torch_to_bits(cache.zero)
+    gp, gs, gz = cache.codes.cpu().numpy(), torch_to_bits(cache.scale), torch_to_bits(cache.zero)
+    lat_bits = torch_to_bits(lat.to(torch.bfloat16))             # the seeded latent rows, as both sides got them
     utf = bf(ut).astype(np.float64)
     worst = 0.0
     for s in range(B):
@@ -110,9 +111,11 @@ def _accumulate_case(xq, B, cap, d, n_lat, G, b, lens, seed, sample_rows=None, o
         if n == 0 or (sample_rows is not None and s >= 3):
             continue
         rows = np.arange(n) if sample_rows is None else np.unique(np.minimum(sample_rows, n - 1))
-        codes = xo.unpack_rows(packed[s, rows], n_lat, b)
-        ref = xo.cl_accumulate_latent_rows(np.ascontiguousarray(a0[s, rows]), codes, sc[s, rows], ze[s, rows], ut, G)
-        dq = xo.dequantize_rows(codes, sc[s, rows], ze[s, rows], G).astype(np.float64)
+        codes, sc, ze = xo.quantize_rows(bf(lat_bits[s, rows]), G, b)           # the oracle's own cache rows
+        assert np.array_equal(gp[s, rows], xo.pack_rows(codes, b))
+        assert np.array_equal(gs[s, rows], sc) and np.array_equal(gz[s, rows], ze)
+        ref = xo.cl_accumulate_latent_rows(np.ascontiguousarray(a0[s, rows]), codes, sc, ze, ut, G)
+        dq = xo.dequantize_rows(codes, sc, ze, G).astype(np.float64)
         exact = bf(a0[s, rows]).astype(np.float64) + dq @ utf
         absum = np.abs(bf(a0[s, rows])).astype(np.float64) + np.abs(dq) @ np.abs(utf)
         worst = max(worst, _check_rounded(got[s, rows], exact, absum, ref, 0.01))
@@ -146,6 +149,7 @@ def test_two_layers_chain_like_the_oracle(xq):
     base = rng.standard_normal((B, L, d))
     acc_bits = bits(base)
     acc = bits_to_torch(acc_bits)
+    acc_ref = acc_bits.copy()
     uprep = xq.xq_prepare_upproject(d, G, b, bits_to_torch(ut))
     x_prev = base
     for layer in (1, 2):
@@ -155,8 +159,7 @@ def test_two_layers_chain_like_the_oracle(xq):
         cache = xq.alloc_cache(B, L, n_lat, G, b)
         xq.xq_quantize_append(cache, lat, [0] * B)
         before = np.abs(bf(xb).astype(np.float64) - bf(torch_to_bits(acc)).astype(np.float64)).mean()
-        # oracle, from the same accumulator bits
-        acc_ref = torch_to_bits(acc).copy()
+        # the oracle's own chain: it starts from the same seeded accumulator and keeps its own afterwards
         lat_ref = xo.project_delta_rows(xb, acc_ref, ut)
         qc, qs, qz = xo.quantize_rows(bf(lat_ref), G, b)
         xo.cl_accumulate_latent_rows(acc_ref.reshape(B * L, d), qc.reshape(B * L, n_lat), qs.reshape(B * L, -1),
@@ -167,7 +170,7 @@ def test_two_layers_chain_like_the_oracle(xq):
         after = np.abs(bf(xb).astype(np.float64) - got).mean()
         assert after < 0.35 * before
         # a latent value that rounds the other way on the GPU moves a code by one step, so the
-        # chain is compared by norm, not bit for bit
+        # two chains are compared by norm, not bit for bit
         normwise, _ = rel_errors(got.reshape(B * L, d), bf(acc_ref).astype(np.float64).reshape(B * L, d))
         assert normwise.max() < 0.02
         x_prev = x_true

@@ -7,7 +7,8 @@ import torch
 
 import xq_inputs as xi
 from oracle import xq_oracle as xo
-from tests.util import bits_to_torch, rel_errors, torch_to_bits
+from tests.util import (assert_cache_equals, assert_cache_per_channel_equals, bits_to_torch, oracle_cache,
+                        oracle_cache_per_channel, rel_errors, torch_to_bits)
 
 pytestmark = pytest.mark.gpu
 
@@ -71,7 +72,8 @@ def test_block_quantiser_noop_and_errors(xq):
 
 def _attend(xq, w, bits, G, lens, pairs=None, scale_spread=1.0):
     """Quantise the complete blocks per channel on the GPU, keep the rest in the bf16 window, attend; the
-    oracle attends over the very same cache bytes and window."""
+    oracle builds its own cache and window from the same rows (the caches must agree byte for byte) and
+    attends over those."""
     x, (wk, wv), q = xi.gen_x(w), xi.gen_weights(w), xi.gen_q(w)
     if scale_spread != 1.0:                              # channels whose scales differ by many powers of two
         xf = bf(x).astype(np.float32)
@@ -95,10 +97,12 @@ def _attend(xq, w, bits, G, lens, pairs=None, scale_spread=1.0):
     got = out.cpu().numpy()
     if pairs is None:
         pairs = [(b, h) for b in range(w.B) for h in range(w.Hq)]
+    seqs = [b for b, _ in pairs]
+    packed, scale, zero, tail_o = oracle_cache_per_channel(x, G, bits, lens, seqs=seqs)
+    assert_cache_per_channel_equals(cache, packed, scale, zero, G, lens, seqs=seqs)
     ref = xo.remat_attn_pairs_per_channel(q_bf16=q, Wk=wk, Wv=wv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd, softmax_scale=w.hd ** -0.5,
-                                          lens=lens, pairs=pairs, packed=cache.codes.cpu().numpy(),
-                                          scale=torch_to_bits(cache.scale), zero=torch_to_bits(cache.zero), G=G, bits=bits,
-                                          tail_bf16=torch_to_bits(tail))
+                                          lens=lens, pairs=pairs, packed=packed, scale=scale, zero=zero, G=G, bits=bits,
+                                          tail_bf16=tail_o)
     sel = np.array([got[b, h] for b, h in pairs])
     normwise, maxwise = rel_errors(sel, ref)
     assert np.all(np.isfinite(got)), w.name
@@ -140,7 +144,8 @@ def test_full_size_llama2_7b_per_channel_sampled_pairs(xq):
 
 def _latent_pc(xq, w, kbits, kG, vbits, vG, lens, pairs=None):
     """Latent rows X Uk, X Uv (synthetic, with the outlier channel of X Uk), keys per channel with a window,
-    values per token; the oracle attends over the same bytes."""
+    values per token; the oracle builds its own caches from the same rows (they must agree byte for byte
+    with the GPU's) and attends over those."""
     r = w.Hkv * w.hd
     rng = np.random.default_rng(w.cfg_id * 7 + kbits)
     lk = rng.standard_normal((w.B, w.L, r)).astype(np.float32)
@@ -171,12 +176,15 @@ def _latent_pc(xq, w, kbits, kG, vbits, vG, lens, pairs=None):
     got = out.cpu().numpy()
     if pairs is None:
         pairs = [(b, h) for b in range(w.B) for h in range(w.Hq)]
+    seqs = [b for b, _ in pairs]
+    kp, ks, kz, kt = oracle_cache_per_channel(lk, kG, kbits, lens, seqs=seqs)
+    assert_cache_per_channel_equals(kc, kp, ks, kz, kG, lens, seqs=seqs)
+    vp, vs, vz = oracle_cache(lv, vG, vbits, seqs=seqs)
+    assert_cache_equals(vc, vp, vs, vz, w.L, seqs=seqs)
     ref = xo.latent_attn_pairs_per_channel(q_bf16=q, Wfk=wfk, Wfv=wfv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd,
                                            softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs,
-                                           k_packed=kc.codes.cpu().numpy(), k_scale=torch_to_bits(kc.scale),
-                                           k_zero=torch_to_bits(kc.zero), k_G=kG, k_bits=kbits,
-                                           k_tail_bf16=torch_to_bits(ktail), v_packed=vc.codes.cpu().numpy(),
-                                           v_scale=torch_to_bits(vc.scale), v_zero=torch_to_bits(vc.zero), v_G=vG, v_bits=vbits)
+                                           k_packed=kp, k_scale=ks, k_zero=kz, k_G=kG, k_bits=kbits,
+                                           k_tail_bf16=kt, v_packed=vp, v_scale=vs, v_zero=vz, v_G=vG, v_bits=vbits)
     sel = np.array([got[b, h] for b, h in pairs])
     normwise, maxwise = rel_errors(sel, ref)
     assert np.all(np.isfinite(got)), w.name
@@ -216,26 +224,38 @@ def test_decode_loop_fills_the_window_and_completes_blocks(xq):
     cache = xq.alloc_cache_per_channel(B, cap, d, G, bits)
     tail = torch.zeros((B, G, d), dtype=torch.bfloat16, device="cuda")
     lens = [37, 0]                                       # sequence 0 starts with 37 tokens already in its window
-    tail[0, :37] = bits_to_torch(xi.to_bf16_bits(rng.standard_normal((37, d)).astype(np.float32)))
+    first = xi.to_bf16_bits(rng.standard_normal((37, d)).astype(np.float32))
+    tail[0, :37] = bits_to_torch(first)
+    # the oracle's own mirror of the cache and the window, kept on the host from the same rows
+    o_packed = np.zeros((B, cap, d * bits // 8), np.uint8)
+    o_scale = np.zeros((B, cap // G, d), np.uint16)
+    o_zero = np.zeros((B, cap // G, d), np.uint16)
+    o_tail = np.zeros((B, G, d), np.uint16)
+    o_tail[0, :37] = first
     checked = 0
     for step in range(steps):
-        x_new = bits_to_torch(xi.to_bf16_bits(rng.standard_normal((B, d)).astype(np.float32)))
+        x_bits = xi.to_bf16_bits(rng.standard_normal((B, d)).astype(np.float32))
+        x_new = bits_to_torch(x_bits)
         for b in range(B):
             rem = lens[b] % G
             tail[b, rem] = x_new[b]
+            o_tail[b, rem] = x_bits[b]
             lens[b] += 1
             if lens[b] % G == 0:                         # the window is a whole block now
+                blk = lens[b] // G - 1
                 sub = xq.XQCache(cache.codes[b:b + 1], cache.scale[b:b + 1], cache.zero[b:b + 1], 1, cap, d, G, bits)
-                xq.xq_quantize_blocks_per_channel(sub, tail[b:b + 1].contiguous(), [lens[b] // G - 1])
+                xq.xq_quantize_blocks_per_channel(sub, tail[b:b + 1].contiguous(), [blk])
+                c, sc, ze = xo.quantize_blocks_per_channel(bf(o_tail[b]), G, bits)
+                o_packed[b, blk * G:(blk + 1) * G], o_scale[b, blk], o_zero[b, blk] = xo.pack_rows(c, bits), sc[0], ze[0]
         if step % 13 == 0 or any(l % G in (0, 1) for l in lens) or step == steps - 1:
             q = xi.to_bf16_bits(rng.standard_normal((B, Hq, hd)).astype(np.float32))
             out = xq.xq_remat_attn_decode_per_channel(attn, bits_to_torch(q), cache, tail, lens, wpc, wpd)
             torch.cuda.synchronize()
             pairs = [(b, h) for b in range(B) for h in range(Hq)]
+            assert_cache_per_channel_equals(cache, o_packed, o_scale, o_zero, G, lens)
             ref = xo.remat_attn_pairs_per_channel(q_bf16=q, Wk=wk, Wv=wv, Hq=Hq, Hkv=Hkv, hd=hd, softmax_scale=hd ** -0.5,
-                                                  lens=lens, pairs=pairs, packed=cache.codes.cpu().numpy(),
-                                                  scale=torch_to_bits(cache.scale), zero=torch_to_bits(cache.zero), G=G,
-                                                  bits=bits, tail_bf16=torch_to_bits(tail))
+                                                  lens=lens, pairs=pairs, packed=o_packed, scale=o_scale, zero=o_zero, G=G,
+                                                  bits=bits, tail_bf16=o_tail)
             normwise, maxwise = rel_errors(out.cpu().numpy().reshape(-1, hd), ref)
             assert normwise.max() <= TOL and maxwise <= TOL, (step, lens, float(normwise.max()))
             checked += 1

@@ -7,7 +7,7 @@ import torch
 
 import xq_inputs as xi
 from oracle import xq_oracle as xo
-from tests.util import bits_to_torch, rel_errors, torch_to_bits
+from tests.util import assert_cache_equals, bits_to_torch, oracle_cache, rel_errors
 
 pytestmark = pytest.mark.gpu
 
@@ -58,8 +58,10 @@ def _run(xq, w, T, bits, G, lens, triples=None, dense=False, rope=None, pos0=Non
         wprep = xq.xq_prepare_weights(attn, w.d, G, bits, bits_to_torch(wk), bits_to_torch(wv))
         out = xq.xq_remat_attn_prefill(attn, bits_to_torch(q), wprep, lens, xcache=cache, **gk)
         torch.cuda.synchronize()
-        ref = xo.prefill_attn_triples(packed=cache.codes.cpu().numpy(), scale=torch_to_bits(cache.scale),
-                                      zero=torch_to_bits(cache.zero), G=G, bits=bits, **common)
+        seqs = [b for b, _, _ in triples]
+        packed, scale, zero = oracle_cache(x, G, bits, seqs=seqs)               # the oracle's own cache
+        assert_cache_equals(cache, packed, scale, zero, w.L, seqs=seqs)
+        ref = xo.prefill_attn_triples(packed=packed, scale=scale, zero=zero, G=G, bits=bits, **common)
     got = out.cpu().numpy()
     sel = np.array([got[b, t, h] for b, t, h in triples])
     normwise, maxwise = rel_errors(sel, ref)

@@ -6,7 +6,7 @@ import torch
 
 import xq_inputs as xi
 from oracle import xq_oracle as xo
-from tests.util import bits_to_torch, rel_errors, torch_to_bits
+from tests.util import assert_cache_equals, bits_to_torch, oracle_cache, rel_errors, torch_to_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -34,8 +34,8 @@ def _check(got, ref, what=""):
 
 
 def _run_xquant(xq, w, bits, G, lens, pairs=None, x_bits=None, cap=None):
-    """Quantise X with the GPU library, attend with the GPU library, and compare with the
-    oracle attending over the very same cache bytes."""
+    """Quantise X and attend with the GPU library; the oracle quantises the same X itself and
+    attends over its own cache.  The two caches must agree byte for byte."""
     x = xi.gen_x(w) if x_bits is None else x_bits
     wk, wv = xi.gen_weights(w)
     q = xi.gen_q(w)
@@ -53,10 +53,12 @@ def _run_xquant(xq, w, bits, G, lens, pairs=None, x_bits=None, cap=None):
     got = out.cpu().numpy()
     if pairs is None:
         pairs = [(b, h) for b in range(w.B) for h in range(w.Hq)]
+    seqs = [b for b, _ in pairs]
+    packed, scale, zero = oracle_cache(x, G, bits, seqs=seqs, cap=cap)
+    assert_cache_equals(cache, packed, scale, zero, w.L, seqs=seqs)
     ref = xo.remat_attn_pairs(q_bf16=q, Wk=wk, Wv=wv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd,
                               softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs,
-                              packed=cache.codes.cpu().numpy(), scale=torch_to_bits(cache.scale),
-                              zero=torch_to_bits(cache.zero), G=G, bits=bits)
+                              packed=packed, scale=scale, zero=zero, G=G, bits=bits)
     sel = np.array([got[b, h] for b, h in pairs])
     return _check(sel, ref, w.name)
 
@@ -153,7 +155,8 @@ def test_full_size_long_context_chunk_then_decode_steps(xq):
     """Config 5 at full size (B=4, d=4096, 32 heads, 2-bit, group 128): the cache is filled to
     32192 rows, a 512-token chunk goes through xq_quantize_append, then 64 decode steps each
     append one token and attend over the grown context (32705 ... 32768 rows = 128 tiles).
-    The appended rows are compared bit for bit, the first and last step's outputs on a sample."""
+    The whole cache is compared bit for bit with the oracle's own, the first and last step's
+    outputs on a sample against the oracle attending over its cache."""
     w = xi.C5
     n_steps, chunk = 64, 512
     L0 = w.L - chunk - n_steps
@@ -175,16 +178,13 @@ def test_full_size_long_context_chunk_then_decode_steps(xq):
         if s in (0, n_steps - 1):
             outs[s], qs[s] = out.cpu().numpy(), q
     torch.cuda.synchronize()
-    gc, gs, gz = cache.codes.cpu().numpy(), torch_to_bits(cache.scale), torch_to_bits(cache.zero)
-    for b in range(w.B):                                      # the chunk and the 64 decode appends, every byte
-        codes, scale, zero = xo.quantize_rows(bf(x[b, L0:]), w.G, w.bits)
-        assert np.array_equal(gs[b, L0:], scale) and np.array_equal(gz[b, L0:], zero), b
-        assert np.array_equal(gc[b, L0:], xo.pack_rows(codes, w.bits)), b
+    packed, scale, zero = oracle_cache(x, w.G, w.bits)        # every sequence, every row, every byte
+    assert_cache_equals(cache, packed, scale, zero, w.L)
     for s in (0, n_steps - 1):
         lens = [L0 + chunk + s + 1] * w.B
         ref = xo.remat_attn_pairs(q_bf16=qs[s], Wk=wk, Wv=wv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd,
-                                  softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs, packed=gc, scale=gs,
-                                  zero=gz, G=w.G, bits=w.bits)
+                                  softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs, packed=packed, scale=scale,
+                                  zero=zero, G=w.G, bits=w.bits)
         sel = np.array([outs[s][b, h] for b, h in pairs])
         worst = _check(sel, ref, f"c5 step {s}")
         print(f"c5 step {s}: worst norm-wise rel err {worst:.2e}")
@@ -192,46 +192,51 @@ def test_full_size_long_context_chunk_then_decode_steps(xq):
 
 def test_full_size_cross_layer_stack_first_layers(xq):
     """Config 3's shape (B=8, L=8192, d=4096, 32 heads; base 4-bit, deltas 2-bit, group 128) for
-    the base layer and two delta layers: accumulator bits on sampled rows against the oracle's
-    own chain, attention from the accumulator on sampled (sequence, head) pairs."""
+    the base layer and two delta layers.  The oracle runs its own chain (quantise, accumulate, take
+    the next delta from its own accumulator) on every row of the sequences the sampled (sequence,
+    head) pairs name and on sampled rows of the others; the GPU's accumulator must hold the same
+    bits there, and the attention outputs are compared with the oracle attending over its own
+    accumulator."""
     w = xi.C3
     G, lens = w.G, [w.L] * w.B
     attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
     rng = np.random.default_rng(3)
-    rows = np.sort(rng.choice(w.L, size=48, replace=False))
-    rows[0], rows[-1] = 0, w.L - 1
+    sampled = np.sort(rng.choice(w.L, size=48, replace=False))
+    sampled[0], sampled[-1] = 0, w.L - 1
     pairs = xi.sample_pairs(w, 4)
+    whole = {b for b, _ in pairs}
+    rows_of = [np.arange(w.L) if b in whole else sampled for b in range(w.B)]
     x = xi.gen_x(w)
     acc = torch.empty((w.B, w.L, w.d), dtype=torch.bfloat16, device="cuda")
     ws = torch.empty(xq.xq_remat_attn_workspace_bytes(attn, w.B, w.L, w.d, 0), dtype=torch.uint8, device="cuda")
-    ref_acc = None                                            # oracle accumulator on the sampled rows [B][48][d]
+    ref_acc = [None] * w.B                                    # the oracle's accumulator on rows_of[b]
     for layer in range(3):
         bits = w.bits if layer == 0 else w.delta_bits
         cache = xq.alloc_cache(w.B, w.L, w.d, G, bits)
-        xs = x[:, rows]
         if layer == 0:
             xq.xq_quantize_append(cache, bits_to_torch(x), [0] * w.B)
-            src = bf(xs)
         else:
             xq.xq_cl_delta_quantize(cache, bits_to_torch(x), acc, [0] * w.B)
-            src = np.stack([xo.cl_delta_rows(xs[b], ref_acc[b]) for b in range(w.B)])
         xq.xq_cl_accumulate(acc, cache, lens, init=(layer == 0))
         torch.cuda.synchronize()
-        new_ref = []
-        for b in range(w.B):
-            c, s, z = xo.quantize_rows(src[b], G, bits)
-            prev = np.zeros_like(xs[b]) if layer == 0 else ref_acc[b]
-            new_ref.append(xo.cl_accumulate_rows(prev, c, s, z, G, layer == 0))
-        ref_acc = np.stack(new_ref)
         acc_bits = torch_to_bits(acc)
-        assert np.array_equal(acc_bits[:, rows], ref_acc), f"accumulator bits, layer {layer}"
+        for b in range(w.B):
+            xs = np.ascontiguousarray(x[b, rows_of[b]])
+            src = bf(xs) if layer == 0 else xo.cl_delta_rows(xs, ref_acc[b])
+            c, s, z = xo.quantize_rows(src, G, bits)
+            prev = np.zeros_like(xs) if layer == 0 else ref_acc[b]
+            ref_acc[b] = xo.cl_accumulate_rows(prev, c, s, z, G, layer == 0)
+            assert np.array_equal(acc_bits[b, rows_of[b]], ref_acc[b]), f"accumulator bits, layer {layer}, sequence {b}"
+        acc_oracle = np.zeros((w.B, w.L, w.d), np.uint16)     # read only on the sequences in `whole`
+        for b in whole:
+            acc_oracle[b] = ref_acc[b]
         wk, wv = xi.gen_weights(w, layer=layer)
         q = xi.gen_q(w, layer=layer)
         wprep = xq.xq_prepare_weights(attn, w.d, 128, 16, bits_to_torch(wk), bits_to_torch(wv))
         out = xq.xq_remat_attn_decode(attn, bits_to_torch(q), wprep, lens, acc_bf16=acc, workspace=ws)
         torch.cuda.synchronize()
         ref = xo.remat_attn_pairs(q_bf16=q, Wk=wk, Wv=wv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd,
-                                  softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs, acc_bf16=acc_bits)
+                                  softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs, acc_bf16=acc_oracle)
         got = out.cpu().numpy()
         worst = _check(np.array([got[b, h] for b, h in pairs]), ref, f"c3 layer {layer}")
         print(f"c3 layer {layer}: worst norm-wise rel err {worst:.2e}")

@@ -6,7 +6,7 @@ import torch
 
 import xq_inputs as xi
 from oracle import xq_oracle as xo
-from tests.util import bits_to_torch, rel_errors, torch_to_bits
+from tests.util import assert_cache_equals, bits_to_torch, oracle_cache, rel_errors
 
 pytestmark = pytest.mark.gpu
 
@@ -53,8 +53,10 @@ def _run(xq, w, bits, G, lens, pos0, n_pos, pairs=None, dense=False):
         xq.xq_quantize_append(cache, bits_to_torch(x), [0] * w.B)
         wprep = xq.xq_prepare_weights(attn, w.d, G, bits, bits_to_torch(wk), bits_to_torch(wv))
         out = xq.xq_remat_attn_decode(attn, bits_to_torch(q), wprep, lens, xcache=cache, rope_cos_sin=t_tab, pos0=pos0)
-        ref = xo.remat_attn_pairs(packed=cache.codes.cpu().numpy(), scale=torch_to_bits(cache.scale),
-                                  zero=torch_to_bits(cache.zero), G=G, bits=bits, **common)
+        seqs = [b for b, _ in pairs]
+        packed, scale, zero = oracle_cache(x, G, bits, seqs=seqs)               # the oracle's own cache
+        assert_cache_equals(cache, packed, scale, zero, w.L, seqs=seqs)
+        ref = xo.remat_attn_pairs(packed=packed, scale=scale, zero=zero, G=G, bits=bits, **common)
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     return _check(np.array([got[b, h] for b, h in pairs]), ref, w.name)
