@@ -313,16 +313,31 @@ xq_status_t xq_quantize_blocks_per_channel(const xq_cache_t *cache, const uint16
  *   wprep_dense  xq_prepare_weights(a, d, 0, 16, Wk, Wv): stream for the window and for the
  *                zero-point term (the zero-points of a block times [Wk | Wv], one row per block)
  *   workspace    dev, xq_remat_attn_per_channel_workspace_bytes(a, B, max len, d, group) bytes
+ *   terms        dev or NULL.  The terms the call derives from the complete blocks (operand factors,
+ *                zero-points times [Wk | Wv], block exponents) change only when a block is completed.
+ *                NULL: they are recomputed in the workspace on every call.  Otherwise a buffer the caller
+ *                keeps per (cache, weights), xq_per_channel_terms_bytes(B, cap, d, group, n_kv_heads)
+ *                bytes, 16-byte aligned, laid out for the cache's capacity:
+ *                  terms_valid = 0  the call computes the terms into it, then uses them;
+ *                  terms_valid != 0 the call only reads it: the caller states that since the last call
+ *                                   with terms_valid = 0 on this buffer no sequence of the batch has
+ *                                   completed a block and the cache, the weights and B are the same.
+ *                                   Wrong use gives wrong numbers, not a fault.
+ *                The library owns nothing here: it keeps no record of what the buffer holds.
  * The per-channel scales enter the contraction on the token operand (one packed fp16 multiply per
  * operand dword), exactly: an 8-bit significand times a 2- or 3-bit code fits fp16, and 4-bit codes
  * enter as code - 8 (the block-constant remainder joins the zero-point term).
  */
 size_t      xq_remat_attn_per_channel_workspace_bytes(const xq_attn_t *a, int32_t B, int32_t max_len,
                                                       int32_t d, int32_t group);
+/* col_blocks: 256-column blocks of the prepared weights: n_kv_heads for xq_remat_attn_decode_per_channel,
+ * n_kv_heads / 2 for xq_remat_attn_decode_latent_per_channel (there d = r).  0 if unsupported. */
+size_t      xq_per_channel_terms_bytes(int32_t B, int32_t cap, int32_t d, int32_t group, int32_t col_blocks);
 xq_status_t xq_remat_attn_decode_per_channel(const xq_attn_t *a, const uint16_t *q_bf16,
                                              const xq_cache_t *cache, const uint16_t *tail_bf16,
                                              const int32_t *len, const void *wprep_coded,
-                                             const void *wprep_dense, float *out, void *workspace,
+                                             const void *wprep_dense, void *terms, size_t terms_bytes,
+                                             int32_t terms_valid, float *out, void *workspace,
                                              size_t workspace_bytes, void *stream);
 
 /*
@@ -341,6 +356,8 @@ xq_status_t xq_remat_attn_decode_per_channel(const xq_attn_t *a, const uint16_t 
  *   wk_dense    xq_prepare_weights_pairs(a, r, 0, 16, Sk Bk^T)
  *   wv_coded    xq_prepare_weights_pairs(a, r, vcache group, vcache bits, Sv Bv^T)
  *   workspace   xq_remat_attn_latent_per_channel_workspace_bytes(a, B, max len, r, kcache group, vcache group)
+ *   terms, terms_bytes, terms_valid   as in xq_remat_attn_decode_per_channel, for the key cache:
+ *               xq_per_channel_terms_bytes(B, kcache cap, r, kcache group, n_kv_heads / 2) bytes, or NULL
  * Two passes as xq_remat_attn_decode_latent; pass 1 takes the keys as xq_remat_attn_decode_per_channel does.
  */
 size_t      xq_prepared_weights_pairs_bytes(const xq_attn_t *a, int32_t r, int32_t group, int32_t src_bits);
@@ -352,7 +369,8 @@ xq_status_t xq_remat_attn_decode_latent_per_channel(const xq_attn_t *a, const ui
                                                     const xq_cache_t *kcache, const uint16_t *ktail_bf16,
                                                     const xq_cache_t *vcache, const void *wk_coded,
                                                     const void *wk_dense, const void *wv_coded,
-                                                    const int32_t *len, float *out, void *workspace,
+                                                    const int32_t *len, void *terms, size_t terms_bytes,
+                                                    int32_t terms_valid, float *out, void *workspace,
                                                     size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     xq_remat_attn_prefill_workspace_bytes, xq_remat_attn_prefill,
     alloc_cache_per_channel, xq_quantize_blocks_per_channel,
     xq_remat_attn_per_channel_workspace_bytes, xq_remat_attn_decode_per_channel,
+    xq_per_channel_terms_bytes, alloc_per_channel_terms,
     xq_prepared_weights_pairs_bytes, xq_prepare_weights_pairs,
     xq_remat_attn_latent_per_channel_workspace_bytes, xq_remat_attn_decode_latent_per_channel,
     xq_prepare_projection, xq_latent_project_bulk,

@@ -27,7 +27,7 @@ SYMBOLS = [
     "xq_cl_accumulate_latent_workspace_bytes", "xq_cl_accumulate_latent",
     "xq_remat_attn_prefill_workspace_bytes", "xq_remat_attn_prefill",
     "xq_quantize_blocks_per_channel",
-    "xq_remat_attn_per_channel_workspace_bytes", "xq_remat_attn_decode_per_channel",
+    "xq_remat_attn_per_channel_workspace_bytes", "xq_per_channel_terms_bytes", "xq_remat_attn_decode_per_channel",
     "xq_prepared_weights_pairs_bytes", "xq_prepare_weights_pairs",
     "xq_remat_attn_latent_per_channel_workspace_bytes", "xq_remat_attn_decode_latent_per_channel",
     "xq_prepared_projection_bytes", "xq_prepare_projection", "xq_latent_project_bulk",
@@ -137,9 +137,11 @@ def load_library():
     lib.xq_remat_attn_per_channel_workspace_bytes.restype = C.c_size_t
     lib.xq_remat_attn_per_channel_workspace_bytes.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.xq_remat_attn_decode_per_channel.restype = C.c_int
+    lib.xq_per_channel_terms_bytes.restype = C.c_size_t
+    lib.xq_per_channel_terms_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.xq_remat_attn_decode_per_channel.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
-                                                     C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_void_p,
-                                                     C.c_void_p, C.c_size_t, C.c_void_p]
+                                                     C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                                     C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.xq_prepared_weights_pairs_bytes.restype = C.c_size_t
     lib.xq_prepared_weights_pairs_bytes.argtypes = [C.POINTER(_Attn), C.c_int32, C.c_int32, C.c_int32]
     lib.xq_prepare_weights_pairs.restype = C.c_int
@@ -151,8 +153,8 @@ def load_library():
     lib.xq_remat_attn_decode_latent_per_channel.restype = C.c_int
     lib.xq_remat_attn_decode_latent_per_channel.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
                                                             C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p,
-                                                            C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_size_t,
-                                                            C.c_void_p]
+                                                            C.POINTER(C.c_int32), C.c_void_p, C.c_size_t, C.c_int32,
+                                                            C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.xq_prepared_projection_bytes.restype = C.c_size_t
     lib.xq_prepared_projection_bytes.argtypes = [C.c_int32, C.c_int32]
     lib.xq_prepare_projection.restype = C.c_int
@@ -497,8 +499,28 @@ def xq_remat_attn_per_channel_workspace_bytes(attn, B, max_len, d, group):
     return load_library().xq_remat_attn_per_channel_workspace_bytes(C.byref(a), B, max_len, d, group)
 
 
+def xq_per_channel_terms_bytes(B, cap, d, group, col_blocks):
+    return load_library().xq_per_channel_terms_bytes(B, cap, d, group, col_blocks)
+
+
+def alloc_per_channel_terms(cache, col_blocks):
+    """A buffer for the per-block terms of `cache` (col_blocks = n_kv_heads, or n_kv_heads / 2 for the latent
+    variant); pass it as `terms` with terms_valid=False after a block was completed, True otherwise."""
+    n = xq_per_channel_terms_bytes(cache.B, cache.cap, cache.d, cache.group, col_blocks)
+    if n == 0:
+        raise XQError("xq_per_channel_terms_bytes: unsupported combination")
+    return torch.empty(n, dtype=torch.uint8, device=cache.codes.device)
+
+
+def _terms_args(terms):
+    if terms is None:
+        return None, 0
+    assert terms.dtype == torch.uint8 and terms.is_contiguous()
+    return _ptr(terms), terms.numel()
+
+
 def xq_remat_attn_decode_per_channel(attn, q_bf16, cache, tail_bf16, lens, wprep_coded, wprep_dense, out=None,
-                                     workspace=None):
+                                     workspace=None, terms=None, terms_valid=False):
     """Decode attention from a per-channel cache plus the bf16 residual window [B][group][d]."""
     assert q_bf16.dtype == torch.bfloat16 and q_bf16.is_contiguous()
     assert tail_bf16.dtype == torch.bfloat16 and tail_bf16.is_contiguous()
@@ -513,6 +535,7 @@ def xq_remat_attn_decode_per_channel(attn, q_bf16, cache, tail_bf16, lens, wprep
         out = torch.empty((cache.B, attn.n_q_heads, attn.head_dim), dtype=torch.float32, device=q_bf16.device)
     _check(load_library().xq_remat_attn_decode_per_channel(C.byref(a), _ptr(q_bf16), C.byref(cs), _ptr(tail_bf16),
                                                            _i32(lens, cache.B), _ptr(wprep_coded), _ptr(wprep_dense),
+                                                           *_terms_args(terms), int(bool(terms_valid)),
                                                            _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
            "xq_remat_attn_decode_per_channel")
     return out
@@ -543,7 +566,7 @@ def xq_remat_attn_latent_per_channel_workspace_bytes(attn, B, max_len, r, k_grou
 
 
 def xq_remat_attn_decode_latent_per_channel(attn, q_bf16, kcache, ktail_bf16, vcache, wk_coded, wk_dense, wv_coded, lens,
-                                            out=None, workspace=None):
+                                            out=None, workspace=None, terms=None, terms_valid=False):
     """Decode attention from a per-channel X Uk cache (+ bf16 window) and a per-token X Uv cache (Sec. 3.3.1)."""
     assert q_bf16.dtype == torch.bfloat16 and q_bf16.is_contiguous()
     assert ktail_bf16.dtype == torch.bfloat16 and ktail_bf16.is_contiguous()
@@ -559,7 +582,8 @@ def xq_remat_attn_decode_latent_per_channel(attn, q_bf16, kcache, ktail_bf16, vc
         out = torch.empty((kcache.B, attn.n_q_heads, attn.head_dim), dtype=torch.float32, device=q_bf16.device)
     _check(load_library().xq_remat_attn_decode_latent_per_channel(
         C.byref(a), _ptr(q_bf16), C.byref(ks), _ptr(ktail_bf16), C.byref(vs), _ptr(wk_coded), _ptr(wk_dense),
-        _ptr(wv_coded), _i32(lens, kcache.B), _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
+        _ptr(wv_coded), _i32(lens, kcache.B), *_terms_args(terms), int(bool(terms_valid)), _ptr(out), _ptr(workspace),
+        workspace.numel(), _stream()),
         "xq_remat_attn_decode_latent_per_channel")
     return out
 

@@ -31,12 +31,13 @@ hipError_t run_quantize_blocks_per_channel(const xq_cache_t* c, const uint16_t* 
 size_t remat_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int d, int block);
 hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc, const uint16_t* tail,
                                     const void* wprep_coded, const void* wprep_dense, const BatchI32& len, int max_len,
-                                    float* out, void* ws, hipStream_t s);
+                                    void* terms, bool terms_valid, float* out, void* ws, hipStream_t s);
+size_t pc_terms_bytes(int B, int cap, int d, int block, int col_blocks);
 size_t remat_latent_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int r, int block, int v_group);
 hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* kc,
                                            const uint16_t* ktail, const xq_cache_t* vc, const void* wk_coded,
                                            const void* wk_dense, const void* wv_coded, const BatchI32& len, int max_len,
-                                           float* out, void* ws, hipStream_t s);
+                                           void* terms, bool terms_valid, float* out, void* ws, hipStream_t s);
 size_t remat_prefill_workspace_bytes(int B, int T, int Hq, int max_len, int d, int group, bool coded);
 hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, const xq_cache_t* xc,
                                   const uint16_t* acc, int B, int cap, int d, const void* wprep,
@@ -393,9 +394,17 @@ size_t xq_remat_attn_per_channel_workspace_bytes(const xq_attn_t* a, int32_t B, 
     return remat_pc_workspace_bytes(B, a->n_q_heads, a->n_kv_heads, max_len, d, group);
 }
 
+size_t xq_per_channel_terms_bytes(int32_t B, int32_t cap, int32_t d, int32_t group, int32_t col_blocks)
+{
+    if (B < 1 || B > XQ_MAX_BATCH || cap < 1 || d <= 0 || d % 128 != 0 || col_blocks < 1) return 0;
+    if ((group != 64 && group != 128) || cap % group != 0) return 0;
+    return pc_terms_bytes(B, cap, d, group, col_blocks);
+}
+
 xq_status_t xq_remat_attn_decode_per_channel(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* cache,
                                              const uint16_t* tail_bf16, const int32_t* len, const void* wprep_coded,
-                                             const void* wprep_dense, float* out, void* workspace,
+                                             const void* wprep_dense, void* terms, size_t terms_bytes,
+                                             int32_t terms_valid, float* out, void* workspace,
                                              size_t workspace_bytes, void* stream)
 {
     xq_status_t st = check_attn(a);
@@ -417,8 +426,12 @@ xq_status_t xq_remat_attn_decode_per_channel(const xq_attn_t* a, const uint16_t*
     }
     if (workspace_bytes < xq_remat_attn_per_channel_workspace_bytes(a, cache->B, max_len, cache->fmt.d, cache->fmt.group))
         return XQ_ERR_WORKSPACE;
-    hipError_t e = run_remat_attn_decode_pc(a, q_bf16, cache, tail_bf16, wprep_coded, wprep_dense, lv, max_len, out,
-                                            workspace, static_cast<hipStream_t>(stream));
+    if (terms) {
+        if (!aligned16(terms)) return XQ_ERR_INVALID_ARG;
+        if (terms_bytes < pc_terms_bytes(cache->B, cache->cap, cache->fmt.d, cache->fmt.group, a->n_kv_heads)) return XQ_ERR_WORKSPACE;
+    }
+    hipError_t e = run_remat_attn_decode_pc(a, q_bf16, cache, tail_bf16, wprep_coded, wprep_dense, lv, max_len, terms,
+                                            terms_valid != 0, out, workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 
@@ -458,8 +471,8 @@ size_t xq_remat_attn_latent_per_channel_workspace_bytes(const xq_attn_t* a, int3
 xq_status_t xq_remat_attn_decode_latent_per_channel(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* kcache,
                                                     const uint16_t* ktail_bf16, const xq_cache_t* vcache,
                                                     const void* wk_coded, const void* wk_dense, const void* wv_coded,
-                                                    const int32_t* len, float* out, void* workspace, size_t workspace_bytes,
-                                                    void* stream)
+                                                    const int32_t* len, void* terms, size_t terms_bytes, int32_t terms_valid,
+                                                    float* out, void* workspace, size_t workspace_bytes, void* stream)
 {
     xq_status_t st = check_attn(a);
     if (st != XQ_OK) return st;
@@ -485,8 +498,14 @@ xq_status_t xq_remat_attn_decode_latent_per_channel(const xq_attn_t* a, const ui
     if (workspace_bytes < xq_remat_attn_latent_per_channel_workspace_bytes(a, kcache->B, max_len, kcache->fmt.d,
                                                                            kcache->fmt.group, vcache->fmt.group))
         return XQ_ERR_WORKSPACE;
+    if (terms) {
+        if (!aligned16(terms)) return XQ_ERR_INVALID_ARG;
+        if (terms_bytes < pc_terms_bytes(kcache->B, kcache->cap, kcache->fmt.d, kcache->fmt.group, a->n_kv_heads / 2))
+            return XQ_ERR_WORKSPACE;
+    }
     hipError_t e = run_remat_attn_decode_latent_pc(a, q_bf16, kcache, ktail_bf16, vcache, wk_coded, wk_dense, wv_coded, lv,
-                                                   max_len, out, workspace, static_cast<hipStream_t>(stream));
+                                                   max_len, terms, terms_valid != 0, out, workspace,
+                                                   static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 

@@ -319,6 +319,38 @@ __global__ __launch_bounds__(256) void pc_factor_image_kernel(PcImageArgs a)
 
 bool unpack_table_for(int bits, UnpackTable* t);
 
+// The per-block terms of a per-channel cache (factor images, z W rows, block factors and exponents) depend on the
+// complete blocks only, so a caller may keep them in a buffer of its own between decode steps and have them
+// recomputed only after a block was completed.  That buffer is laid out for the cache's capacity, so that the
+// positions do not move while the sequences grow; col_blocks = 256-column blocks of the prepared weights.
+struct PcTerms {
+    uint8_t* img;
+    float* zw;
+    float* fscale;
+    int* eblk;
+    size_t blocks_ws;      // rows per sequence of zw, fscale, eblk
+};
+
+size_t pc_terms_bytes(int B, int cap, int d, int block, int col_blocks)
+{
+    const size_t tiles = ((size_t)cap + TILE_TOKENS - 1) / TILE_TOKENS;
+    const size_t blocks = (size_t)cap / block + 1;
+    return (size_t)B * tiles * (size_t)(d / 128 + 1) * LDS_SCALES_BYTES + (size_t)B * blocks * (size_t)col_blocks * 256 * sizeof(float)
+         + (size_t)B * blocks * 2 * sizeof(float) + 256;
+}
+
+static PcTerms carve_pc_terms(void* base, int B, int cap, int d, int block, int col_blocks)
+{
+    const size_t tiles = ((size_t)cap + TILE_TOKENS - 1) / TILE_TOKENS;
+    PcTerms t{};
+    t.blocks_ws = (size_t)cap / block + 1;
+    t.img = static_cast<uint8_t*>(base);
+    t.zw = reinterpret_cast<float*>(t.img + (size_t)B * tiles * (size_t)(d / 128 + 1) * LDS_SCALES_BYTES);
+    t.fscale = t.zw + (size_t)B * t.blocks_ws * col_blocks * 256;
+    t.eblk = reinterpret_cast<int*>(t.fscale + (size_t)B * t.blocks_ws);
+    return t;
+}
+
 size_t remat_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int d, int block)
 {
     const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
@@ -333,7 +365,7 @@ size_t remat_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int d, int 
 // Decode attention from a per-channel cache plus the bf16 residual window of the newest len % block tokens.
 hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc, const uint16_t* tail,
                                     const void* wprep_coded, const void* wprep_dense, const BatchI32& len, int max_len,
-                                    float* out, void* ws, hipStream_t s)
+                                    void* terms, bool terms_valid, float* out, void* ws, hipStream_t s)
 {
     const int bits = xc->fmt.bits, blockT = xc->fmt.group, d = xc->fmt.d, B = xc->B, cap = xc->cap;
     const int blocks_cap = cap / blockT;
@@ -360,9 +392,14 @@ hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const
     float* part_ml = part_o + (size_t)B * a->n_q_heads * chunks_stride * 128;
     uint8_t* img = reinterpret_cast<uint8_t*>(part_ml + (size_t)B * a->n_q_heads * chunks_stride * 2);
     float* zw = reinterpret_cast<float*>(img + (size_t)B * tiles_all * (size_t)(d / 128 + 1) * LDS_SCALES_BYTES);
-    const size_t blocks_ws = (size_t)max_len / blockT + 1;
+    size_t blocks_ws = (size_t)max_len / blockT + 1;
     float* fscale = zw + (size_t)B * blocks_ws * a->n_kv_heads * 256;
     int* eblk = reinterpret_cast<int*>(fscale + (size_t)B * blocks_ws);
+    if (terms) {                                                             // the caller's own buffer for the per-block terms
+        const PcTerms t = carve_pc_terms(terms, B, cap, d, blockT, a->n_kv_heads);
+        img = t.img; zw = t.zw; fscale = t.fscale; eblk = t.eblk; blocks_ws = t.blocks_ws;
+    }
+    const bool compute_terms = !(terms && terms_valid);
 
     RematParams p{};
     p.q = q;
@@ -371,7 +408,7 @@ hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const
     p.part_o = part_o; p.part_ml = part_ml; p.chunks_per_seq = chunks_stride;
     p.d = d; p.row_d = d;
     hipError_t e = hipSuccess;
-    if (max_nblk > 0) {
+    if (max_nblk > 0 && compute_terms) {
         // block exponents, factor images
         pc_block_exponent_kernel<<<dim3(max_nblk, B), dim3(256), 0, s>>>(xc->scale, fscale, eblk, d, blocks_cap, (int)blocks_ws, bits, nblk);
         PcImageArgs ia{xc->scale, eblk, reinterpret_cast<uint16_t*>(img), d, blocks_cap, (int)blocks_ws, blockT, tiles_coded, Lc.n_main_slabs, 128,
@@ -393,6 +430,8 @@ hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const
             e = launch_with_lds(remat_attn_dense_kernel<DENSE_STORE>, LDS_DENSE_TOTAL, z, p.Hkv * B * z.tiles_per_seq, s);
         }
         if (e != hipSuccess) return e;
+    }
+    if (max_nblk > 0) {
         // the coded blocks
         RematParams m = p;
         m.codes = xc->codes; m.eT = reinterpret_cast<const uint16_t*>(img);
@@ -444,7 +483,7 @@ size_t remat_latent_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int 
 hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* kc,
                                            const uint16_t* ktail, const xq_cache_t* vc, const void* wk_coded,
                                            const void* wk_dense, const void* wv_coded, const BatchI32& len, int max_len,
-                                           float* out, void* ws, hipStream_t s)
+                                           void* terms, bool terms_valid, float* out, void* ws, hipStream_t s)
 {
     const int kbits = kc->fmt.bits, blockT = kc->fmt.group, r = kc->fmt.d, B = kc->B;
     const int vbits = vc->fmt.bits, vG = vc->fmt.group;
@@ -468,7 +507,7 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
     const int tiles_all = (max_len + TILE_TOKENS - 1) / TILE_TOKENS;
     const int tiles_coded = (max_coded + TILE_TOKENS - 1) / TILE_TOKENS;
     const int chunks = tiles_all * (TILE_TOKENS / CHUNK_TOKENS);
-    const size_t blocks_ws = (size_t)max_len / blockT + 1;
+    size_t blocks_ws = (size_t)max_len / blockT + 1;
     // workspace carve-up (sizes as in remat_latent_pc_workspace_bytes)
     float* part_o = static_cast<float*>(ws);
     float* part_ml = part_o + (size_t)B * a->n_q_heads * chunks * 128;
@@ -479,6 +518,11 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
     uint16_t* eT_v = reinterpret_cast<uint16_t*>(zw + (size_t)B * blocks_ws * pairs * 256);      // (16-byte aligned: a DMA source)
     float* fscale = reinterpret_cast<float*>(eT_v + (size_t)B * tiles_all * (size_t)(r / vG + 1) * TILE_TOKENS);
     int* eblk = reinterpret_cast<int*>(fscale + (size_t)B * blocks_ws);
+    if (terms) {                                                             // the caller's own buffer for the per-block terms
+        const PcTerms t = carve_pc_terms(terms, B, kc->cap, r, blockT, pairs);
+        img = t.img; zw = t.zw; fscale = t.fscale; eblk = t.eblk; blocks_ws = t.blocks_ws;
+    }
+    const bool compute_terms = !(terms && terms_valid);
 
     RematParams p{};
     p.q = q;
@@ -488,7 +532,7 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
     p.scores = scores; p.score_stride = score_stride;
     p.d = r; p.row_d = r;
     hipError_t e = hipSuccess;
-    if (max_nblk > 0) {
+    if (max_nblk > 0 && compute_terms) {
         pc_block_exponent_kernel<<<dim3(max_nblk, B), dim3(256), 0, s>>>(kc->scale, fscale, eblk, r, blocks_cap, (int)blocks_ws, kbits, nblk);
         PcImageArgs ia{kc->scale, eblk, reinterpret_cast<uint16_t*>(img), r, blocks_cap, (int)blocks_ws, blockT, tiles_coded,
                        Lk.n_main_slabs, 128, nblk, tab};
@@ -508,6 +552,8 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
             e = launch_with_lds(remat_attn_dense_kernel<DENSE_STORE>, LDS_DENSE_TOTAL, z, pairs * B * z.tiles_per_seq, s);
         }
         if (e != hipSuccess) return e;
+    }
+    if (max_nblk > 0) {
         RematParams m = p;                                                   // pass 1, coded blocks
         m.codes = kc->codes; m.eT = reinterpret_cast<const uint16_t*>(img);
         m.cap = kc->cap; m.len = len_coded; m.tiles_per_seq = tiles_coded;

@@ -223,6 +223,11 @@ def test_decode_loop_fills_the_window_and_completes_blocks(xq):
     wpd = xq.xq_prepare_weights(attn, d, 0, 16, bits_to_torch(wk), bits_to_torch(wv))
     cache = xq.alloc_cache_per_channel(B, cap, d, G, bits)
     tail = torch.zeros((B, G, d), dtype=torch.bfloat16, device="cuda")
+    # the per-block terms live in a buffer of the caller's, recomputed only after a block was completed; it starts
+    # as all-ones bytes so that anything the call reads without having written it shows up as NaN
+    terms = xq.alloc_per_channel_terms(cache, Hkv)
+    terms.fill_(0xFF)
+    terms_dirty, reused = True, 0
     lens = [37, 0]                                       # sequence 0 starts with 37 tokens already in its window
     first = xi.to_bf16_bits(rng.standard_normal((37, d)).astype(np.float32))
     tail[0, :37] = bits_to_torch(first)
@@ -247,10 +252,16 @@ def test_decode_loop_fills_the_window_and_completes_blocks(xq):
                 xq.xq_quantize_blocks_per_channel(sub, tail[b:b + 1].contiguous(), [blk])
                 c, sc, ze = xo.quantize_blocks_per_channel(bf(o_tail[b]), G, bits)
                 o_packed[b, blk * G:(blk + 1) * G], o_scale[b, blk], o_zero[b, blk] = xo.pack_rows(c, bits), sc[0], ze[0]
+                terms_dirty = True
         if step % 13 == 0 or any(l % G in (0, 1) for l in lens) or step == steps - 1:
             q = xi.to_bf16_bits(rng.standard_normal((B, Hq, hd)).astype(np.float32))
-            out = xq.xq_remat_attn_decode_per_channel(attn, bits_to_torch(q), cache, tail, lens, wpc, wpd)
+            out = xq.xq_remat_attn_decode_per_channel(attn, bits_to_torch(q), cache, tail, lens, wpc, wpd, terms=terms,
+                                                      terms_valid=not terms_dirty)
+            reused += not terms_dirty
+            terms_dirty = False
+            plain = xq.xq_remat_attn_decode_per_channel(attn, bits_to_torch(q), cache, tail, lens, wpc, wpd)
             torch.cuda.synchronize()
+            assert torch.equal(out, plain), (step, lens)          # kept terms or fresh ones: the same bits
             pairs = [(b, h) for b in range(B) for h in range(Hq)]
             assert_cache_per_channel_equals(cache, o_packed, o_scale, o_zero, G, lens)
             ref = xo.remat_attn_pairs_per_channel(q_bf16=q, Wk=wk, Wv=wv, Hq=Hq, Hkv=Hkv, hd=hd, softmax_scale=hd ** -0.5,
@@ -259,7 +270,7 @@ def test_decode_loop_fills_the_window_and_completes_blocks(xq):
             normwise, maxwise = rel_errors(out.cpu().numpy().reshape(-1, hd), ref)
             assert normwise.max() <= TOL and maxwise <= TOL, (step, lens, float(normwise.max()))
             checked += 1
-    assert lens == [37 + steps, steps] and checked >= 15
+    assert lens == [37 + steps, steps] and checked >= 15 and reused >= 8
 
 
 def test_per_channel_maximum_batch(xq):
@@ -268,3 +279,37 @@ def test_per_channel_maximum_batch(xq):
     lens = [1 + (11 * b) % 190 for b in range(w.B)]
     pairs = [(b, h) for b in range(0, w.B, 5) for h in range(w.Hq)] + [(127, 0), (127, 1)]
     _attend(xq, w, 3, 64, lens, pairs=pairs)
+
+
+def test_kept_terms_latent_variant_and_errors(xq):
+    """The key cache's per-block terms kept across calls of the latent variant: computed once, read by later calls
+    while the sequences grow inside their windows; same bits as the calls that recompute them."""
+    w = xi.C4.scaled(B=2, L=420, d=512, Hq=8, Hkv=2, n_outlier=5)
+    r, kG, kbits, vG, vbits = w.Hkv * w.hd, 128, 4, 64, 2
+    rng = np.random.default_rng(11)
+    lk = bits_to_torch(xi.to_bf16_bits(rng.standard_normal((w.B, w.L, r)).astype(np.float32)))
+    lv = bits_to_torch(xi.to_bf16_bits(rng.standard_normal((w.B, w.L, r)).astype(np.float32)))
+    wf = [bits_to_torch(xi.to_bf16_bits((rng.standard_normal((r, r)) * r ** -0.5).astype(np.float32))) for _ in range(2)]
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    kc = xq.alloc_cache_per_channel(w.B, 512, r, kG, kbits)
+    xq.xq_quantize_blocks_per_channel(kc, lk[:, :384].contiguous(), [0, 0])          # three complete blocks each
+    vc = xq.alloc_cache(w.B, w.L, r, vG, vbits)
+    xq.xq_quantize_append(vc, lv, [0] * w.B)
+    wkc = xq.xq_prepare_weights_pairs(attn, r, 128, kbits, wf[0])
+    wkd = xq.xq_prepare_weights_pairs(attn, r, 0, 16, wf[0])
+    wvc = xq.xq_prepare_weights_pairs(attn, r, vG, vbits, wf[1])
+    terms = xq.alloc_per_channel_terms(kc, w.Hkv // 2)
+    terms.fill_(0xFF)
+    ktail = torch.zeros((w.B, kG, r), dtype=torch.bfloat16, device="cuda")
+    q = bits_to_torch(xi.gen_q(w))
+    for i, lens in enumerate([[384, 390], [385, 400], [420, 411]]):                 # windows of 0 .. 36 tokens
+        for b in range(w.B):
+            ktail[b, :lens[b] - 384] = lk[b, 384:lens[b]]
+        kept = xq.xq_remat_attn_decode_latent_per_channel(attn, q, kc, ktail, vc, wkc, wkd, wvc, lens, terms=terms,
+                                                          terms_valid=i > 0)
+        fresh = xq.xq_remat_attn_decode_latent_per_channel(attn, q, kc, ktail, vc, wkc, wkd, wvc, lens)
+        torch.cuda.synchronize()
+        assert torch.equal(kept, fresh) and bool(torch.isfinite(kept).all()), lens
+    with pytest.raises(xq.XQError):                                                  # a buffer too small for the cache
+        xq.xq_remat_attn_decode_latent_per_channel(attn, q, kc, ktail, vc, wkc, wkd, wvc, [384, 390], terms=terms[:4096])
+    assert xq.xq_per_channel_terms_bytes(2, 500, 512, 128, 2) == 0                   # capacity not in whole blocks

@@ -174,13 +174,17 @@ def test_argument_errors_of_the_widened_entry_points():
     assert qb(pc(cap=200)) == INVALID                                           # capacity not a whole number of blocks
     assert qb(pc(group=32)) == UNSUPPORTED
     assert qb(pc(d=192)) == UNSUPPORTED
-    pa = lambda c=None, ln=130, tail=x, wsb=1 << 30: lib.xq_remat_attn_decode_per_channel(
-        C.byref(la), x, C.byref(c if c is not None else pc()), tail, (C.c_int32 * 1)(ln), x, x, x, x, wsb, st)
+    pa = lambda c=None, ln=130, tail=x, wsb=1 << 30, terms=None, tb=0: lib.xq_remat_attn_decode_per_channel(
+        C.byref(la), x, C.byref(c if c is not None else pc()), tail, (C.c_int32 * 1)(ln), x, x, terms, tb, 0, x, x, wsb, st)
     assert pa(ln=0) == INVALID
     assert pa(ln=400) == INVALID                                                # three blocks do not fit a cache of two
     assert pa(tail=None) == INVALID
     assert pa(wsb=64) == WORKSPACE
     assert pa(c=pc(bits=8)) == UNSUPPORTED
+    assert pa(terms=x, tb=64) == WORKSPACE                                      # a terms buffer too small for the cache
+    assert xq.xq_per_channel_terms_bytes(1, 256, 256, 128, 2) > 0
+    assert xq.xq_per_channel_terms_bytes(1, 200, 256, 128, 2) == 0              # capacity not a whole number of blocks
+    assert xq.xq_per_channel_terms_bytes(1, 256, 256, 32, 2) == 0
     assert xq.xq_remat_attn_per_channel_workspace_bytes(xq.XQAttn(4, 2, 128, 0.1), 1, 300, 256, 32) == 0
     assert xq.xq_remat_attn_per_channel_workspace_bytes(xq.XQAttn(4, 2, 128, 0.1), 1, 300, 256, 128) > 0
     # latent keys per channel, latent values per token
@@ -191,13 +195,14 @@ def test_argument_errors_of_the_widened_entry_points():
     assert lib.xq_prepare_weights_pairs(C.byref(la), 256, 128, 3, x, x, 16, st) == WORKSPACE
     assert lib.xq_prepare_weights_pairs(C.byref(la), 256, 128, 3, None, x, 1 << 30, st) == INVALID
     kc, vc = pc(d=256), _cache(cap=256, d=256, group=64, bits=2)
-    lp = lambda k=kc, v=vc, ln=130, wsb=1 << 30: lib.xq_remat_attn_decode_latent_per_channel(
-        C.byref(la), x, C.byref(k), x, C.byref(v), x, x, x, (C.c_int32 * 1)(ln), x, x, wsb, st)
+    lp = lambda k=kc, v=vc, ln=130, wsb=1 << 30, terms=None, tb=0: lib.xq_remat_attn_decode_latent_per_channel(
+        C.byref(la), x, C.byref(k), x, C.byref(v), x, x, x, (C.c_int32 * 1)(ln), terms, tb, 0, x, x, wsb, st)
     assert lp(ln=0) == INVALID
     assert lp(ln=300) == INVALID                                                # longer than the value cache
     assert lp(v=_cache(cap=256, d=512, group=64, bits=2)) == INVALID            # widths differ
     assert lp(wsb=64) == WORKSPACE
     assert lp(k=pc(d=256, bits=8)) == UNSUPPORTED
+    assert lp(terms=x, tb=64) == WORKSPACE
     assert xq.xq_remat_attn_latent_per_channel_workspace_bytes(at2, 1, 300, 256, 128, 64) > 0
     assert xq.xq_remat_attn_latent_per_channel_workspace_bytes(at2, 1, 300, 256, 128, 32) == 0
 
