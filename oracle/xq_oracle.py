@@ -291,10 +291,14 @@ def remat_attn_pairs_per_channel(*, q_bf16, Wk, Wv, Hq, Hkv, hd, softmax_scale, 
 
 def latent_attn_pairs_per_channel(*, q_bf16, Wfk, Wfv, Hq, Hkv, hd, softmax_scale, lens, pairs,
                                   k_packed, k_scale, k_zero, k_G, k_bits, k_tail_bf16,
-                                  v_packed, v_scale, v_zero, v_G, v_bits):
+                                  v_packed, v_scale, v_zero, v_G, v_bits, k0_f16=None):
     """Sec. 3.3.1's setting for grouped-query models: keys from a per-channel cache of X Uk (complete blocks
     of k_G tokens, the rest in the bf16 window k_tail) through Wfk = Sk Bk^T, values from a per-token cache
-    of X Uv through Wfv = Sv Bv^T.  Composition of pinned pieces only.  Returns [npairs][hd] fp32."""
+    of X Uv through Wfv = Sv Bv^T.  Composition of pinned pieces only.  Returns [npairs][hd] fp32.
+
+    k0_f16 (App. B): [B][>= lens[b]] IEEE half bit patterns.  If given, the first channel of X Uk, the one that
+    collects the outliers, is kept in fp16 instead of being quantised: channel 0 of every latent key row
+    (cache blocks and window alike) is k0_f16[b][t]; whatever the cache and the window hold there is unused."""
     q = _c(q_bf16, np.uint16)
     r = Wfk.shape[0]
     g = Hq // Hkv
@@ -309,6 +313,8 @@ def latent_attn_pairs_per_channel(*, q_bf16, Wfk, Wfv, Hq, Hkv, hd, softmax_scal
                 coded = dequantize_blocks_per_channel(unpack_rows(_c(k_packed, np.uint8)[b, :nblk * k_G], r, k_bits),
                                                       k_scale[b, :nblk], k_zero[b, :nblk], k_G)
             xk = np.concatenate([coded, bf16_to_f32(_c(k_tail_bf16, np.uint16)[b, :rem])], axis=0)
+            if k0_f16 is not None:
+                xk[:, 0] = _c(k0_f16, np.uint16)[b, :n].view(np.float16).astype(np.float32)
             xv = dequantize_rows(unpack_rows(_c(v_packed, np.uint8)[b, :n], r, v_bits), v_scale[b, :n], v_zero[b, :n], v_G)
             cache[b] = (xk, xv)
         xk, xv = cache[b]

@@ -144,3 +144,80 @@ def test_latent_attention_with_per_channel_keys_equals_brute_force():
         V = xv[b, :lens[b]].astype(np.float64) @ bf(wfv)[:, hk * hd:(hk + 1) * hd].astype(np.float64)
         ref = softmax(K @ bf(q)[b, hq].astype(np.float64) * hd ** -0.5) @ V
         assert np.allclose(got[i], ref, rtol=1e-5, atol=1e-6)
+
+
+def _latent_case(seed, lens, B=2, L=70, r=256, Gk=32, Gv=64, kb=2, vb=4, Hq=4, Hkv=2, hd=128, ch0=None):
+    """Caches of synthetic latent rows; ch0(b) may overwrite channel 0 of X Uk before quantising."""
+    rng = np.random.default_rng(seed)
+    lkf = rng.standard_normal((B, L, r)).astype(np.float32)
+    lkf[..., 0] *= 30.0                                                           # the outlier channel of X Uk
+    if ch0 is not None:
+        lkf[..., 0] = ch0
+    lk = xi.to_bf16_bits(lkf)
+    lv = xi.to_bf16_bits(rng.standard_normal((B, L, r)).astype(np.float32))
+    wfk = xi.to_bf16_bits((rng.standard_normal((r, Hkv * hd)) * r ** -0.5).astype(np.float32))
+    wfv = xi.to_bf16_bits((rng.standard_normal((r, Hkv * hd)) * r ** -0.5).astype(np.float32))
+    q = xi.to_bf16_bits(rng.standard_normal((B, Hq, hd)).astype(np.float32))
+    cap = (L + Gk - 1) // Gk * Gk
+    kcodes = np.zeros((B, cap, r), np.uint8)
+    kscale = np.zeros((B, cap // Gk, r), np.uint16)
+    kzero = np.zeros_like(kscale)
+    ktail = np.zeros((B, Gk, r), np.uint16)
+    xk = []
+    for b in range(B):
+        nblk, rem = lens[b] // Gk, lens[b] % Gk
+        c, s, z = xo.quantize_blocks_per_channel(bf(lk[b, :nblk * Gk]), Gk, kb)
+        kcodes[b, :nblk * Gk], kscale[b, :nblk], kzero[b, :nblk] = c, s, z
+        ktail[b, :rem] = lk[b, nblk * Gk:lens[b]]
+        xk.append(np.concatenate([xo.dequantize_blocks_per_channel(c, s, z, Gk), bf(lk[b, nblk * Gk:lens[b]])]))
+    vc, vs, vz = xo.quantize_rows(bf(lv), Gv, vb)
+    kw = dict(q_bf16=q, Wfk=wfk, Wfv=wfv, Hq=Hq, Hkv=Hkv, hd=hd, softmax_scale=hd ** -0.5, lens=lens,
+              pairs=[(b, h) for b in range(B) for h in range(Hq)], k_packed=xo.pack_rows(kcodes, kb), k_scale=kscale,
+              k_zero=kzero, k_G=Gk, k_bits=kb, k_tail_bf16=ktail, v_packed=xo.pack_rows(vc, vb), v_scale=vs, v_zero=vz,
+              v_G=Gv, v_bits=vb)
+    return kw, xk, xo.dequantize_rows(vc, vs, vz, Gv), lkf
+
+
+def test_fp16_outlier_channel_equals_brute_force():
+    """App. B: channel 0 of X Uk kept in fp16.  Brute force: the dequantised latent keys with column 0 (and no
+    other column) replaced by the fp16 values, then textbook attention."""
+    from scipy.special import softmax
+    lens = [70, 64]
+    kw, xk, xv, lkf = _latent_case(41, lens)
+    k0 = lkf[..., 0].astype(np.float16)                                           # [B][L] IEEE half
+    got = xo.latent_attn_pairs_per_channel(k0_f16=k0.view(np.uint16), **kw)
+    plain = xo.latent_attn_pairs_per_channel(**kw)
+    Hq, Hkv, hd = kw["Hq"], kw["Hkv"], kw["hd"]
+    for i, (b, hq) in enumerate(kw["pairs"]):
+        hk = hq // (Hq // Hkv)
+        lat = xk[b].astype(np.float64).copy()
+        lat[:, 0] = k0[b, :lens[b]].astype(np.float64)
+        K = lat @ bf(kw["Wfk"])[:, hk * hd:(hk + 1) * hd].astype(np.float64)
+        V = xv[b, :lens[b]].astype(np.float64) @ bf(kw["Wfv"])[:, hk * hd:(hk + 1) * hd].astype(np.float64)
+        ref = softmax(K @ bf(kw["q_bf16"])[b, hq].astype(np.float64) * hd ** -0.5) @ V
+        assert np.allclose(got[i], ref, rtol=1e-5, atol=1e-6)
+    # 2-bit codes of a channel thirty times wider than the others: keeping it in fp16 must matter
+    assert np.abs(got - plain).max() > 1e-3 * np.abs(plain).max()
+
+
+def test_fp16_outlier_channel_special_cases():
+    lens = [70, 64]
+    # a constant channel 0 dequantises to its zero-point exactly (scale 0), a small bf16 number that fp16 holds
+    # exactly, and so do the window rows: the fp16 copy then changes nothing at all
+    kw, _, _, lkf = _latent_case(42, lens, ch0=1.25)
+    k0 = lkf[..., 0].astype(np.float16)
+    assert np.array_equal(xo.latent_attn_pairs_per_channel(k0_f16=k0.view(np.uint16), **kw),
+                          xo.latent_attn_pairs_per_channel(**kw))
+    # with a zero first row of Sk Bk^T the channel cannot reach the keys, whatever it holds
+    kw, _, _, lkf = _latent_case(43, lens)
+    wz = kw["Wfk"].copy()
+    wz[0, :] = 0
+    a = xo.latent_attn_pairs_per_channel(**dict(kw, Wfk=wz))
+    junk = np.random.default_rng(1).standard_normal(lkf[..., 0].shape).astype(np.float16)
+    assert np.array_equal(xo.latent_attn_pairs_per_channel(k0_f16=junk.view(np.uint16), **dict(kw, Wfk=wz)), a)
+    # rows past lens[b] of the fp16 array are not read
+    k0 = lkf[..., 0].astype(np.float16)
+    k0b = k0.copy()
+    k0b[1, lens[1]:] = np.float16(np.nan)
+    assert np.array_equal(xo.latent_attn_pairs_per_channel(k0_f16=k0.view(np.uint16), **kw),
+                          xo.latent_attn_pairs_per_channel(k0_f16=k0b.view(np.uint16), **kw))
