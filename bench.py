@@ -269,9 +269,19 @@ def main():
         t_lpk = timed(lambda: xq.xq_remat_attn_decode_latent_per_channel(oattn, oq, kc, ktail, vc, wkc, wkd, wvc, plens,
                                                                          out=oout, workspace=pws, terms=kterms,
                                                                          terms_valid=True), n=5, warm=3)
+        # App. B: the first channel of X Uk in fp16 (its share of the scores is added between the passes; the zeroed row
+        # 0 of the key streams does not change the timing, so the same streams serve here)
+        k0 = lat[:, :, 0].to(torch.float16).contiguous()
+        w_row0 = wfk[0].contiguous()
+        t_lpo = timed(lambda: xq.xq_remat_attn_decode_latent_per_channel(oattn, oq, kc, ktail, vc, wkc, wkd, wvc, plens,
+                                                                         out=oout, workspace=pws, terms=kterms,
+                                                                         terms_valid=True, k0_f16=k0, wk_row0=w_row0),
+                      n=5, warm=3)
         extra["remat_attn_c4_latent_keys_per_channel"] = {
             "workload": "c4 layer, X Uk per channel (2-bit, blocks of 128, 100 window tokens), X Uv per token (2-bit, group 64)",
-            "ms": t_lp, "tokens/s/layer": ow.B * (ow.L - 28) / (t_lp * 1e-3), "ms_with_kept_block_terms": t_lpk}
+            "ms": t_lp, "tokens/s/layer": ow.B * (ow.L - 28) / (t_lp * 1e-3), "ms_with_kept_block_terms": t_lpk,
+            "ms_with_kept_block_terms_and_fp16_outlier_channel": t_lpo}
+        del k0, w_row0
         del kc, vc, ktail, wkc, wkd, wvc, pws, kterms
         del lcache, lat, lwp, lws
         # the cross-layer step of the same GQA layer (Sec. 3.3.2): latent delta of the new token, quantise,

@@ -356,6 +356,14 @@ xq_status_t xq_remat_attn_decode_per_channel(const xq_attn_t *a, const uint16_t 
  *   wk_dense    xq_prepare_weights_pairs(a, r, 0, 16, Sk Bk^T)
  *   wv_coded    xq_prepare_weights_pairs(a, r, vcache group, vcache bits, Sv Bv^T)
  *   workspace   xq_remat_attn_latent_per_channel_workspace_bytes(a, B, max len, r, kcache group, vcache group)
+ *   k0_f16      dev or NULL.  App. B: the first channel of X Uk, which collects the outliers, kept in fp16
+ *               instead of being quantised.  If not NULL: [B][k0_stride] IEEE half bit patterns (finite),
+ *               k0_stride >= every len[b]; latent key channel 0 of token t of sequence b is
+ *               k0_f16[b*k0_stride + t] for all t < len[b], cache blocks and window alike.  The caller
+ *               then prepares wk_coded and wk_dense from Sk Bk^T with its row 0 set to zero (so that
+ *               whatever the cache and the window hold in channel 0 reaches nothing) and passes that row:
+ *   wk_row0_bf16  dev [n_kv_heads*head_dim] bf16, row 0 of Sk Bk^T; read only if k0_f16 != NULL.
+ *               The channel's share of a score, k0 * (q . row 0), is added in fp32 between the two passes.
  *   terms, terms_bytes, terms_valid   as in xq_remat_attn_decode_per_channel, for the key cache:
  *               xq_per_channel_terms_bytes(B, kcache cap, r, kcache group, n_kv_heads / 2) bytes, or NULL
  * Two passes as xq_remat_attn_decode_latent; pass 1 takes the keys as xq_remat_attn_decode_per_channel does.
@@ -369,9 +377,11 @@ xq_status_t xq_remat_attn_decode_latent_per_channel(const xq_attn_t *a, const ui
                                                     const xq_cache_t *kcache, const uint16_t *ktail_bf16,
                                                     const xq_cache_t *vcache, const void *wk_coded,
                                                     const void *wk_dense, const void *wv_coded,
-                                                    const int32_t *len, void *terms, size_t terms_bytes,
-                                                    int32_t terms_valid, float *out, void *workspace,
-                                                    size_t workspace_bytes, void *stream);
+                                                    const int32_t *len, const uint16_t *k0_f16,
+                                                    int64_t k0_stride, const uint16_t *wk_row0_bf16,
+                                                    void *terms, size_t terms_bytes, int32_t terms_valid,
+                                                    float *out, void *workspace, size_t workspace_bytes,
+                                                    void *stream);
 
 #ifdef __cplusplus
 }

@@ -153,7 +153,8 @@ def load_library():
     lib.xq_remat_attn_decode_latent_per_channel.restype = C.c_int
     lib.xq_remat_attn_decode_latent_per_channel.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
                                                             C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p,
-                                                            C.POINTER(C.c_int32), C.c_void_p, C.c_size_t, C.c_int32,
+                                                            C.POINTER(C.c_int32), C.c_void_p, C.c_int64, C.c_void_p,
+                                                            C.c_void_p, C.c_size_t, C.c_int32,
                                                             C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.xq_prepared_projection_bytes.restype = C.c_size_t
     lib.xq_prepared_projection_bytes.argtypes = [C.c_int32, C.c_int32]
@@ -566,8 +567,16 @@ def xq_remat_attn_latent_per_channel_workspace_bytes(attn, B, max_len, r, k_grou
 
 
 def xq_remat_attn_decode_latent_per_channel(attn, q_bf16, kcache, ktail_bf16, vcache, wk_coded, wk_dense, wv_coded, lens,
-                                            out=None, workspace=None, terms=None, terms_valid=False):
-    """Decode attention from a per-channel X Uk cache (+ bf16 window) and a per-token X Uv cache (Sec. 3.3.1)."""
+                                            out=None, workspace=None, terms=None, terms_valid=False, k0_f16=None,
+                                            wk_row0=None):
+    """Decode attention from a per-channel X Uk cache (+ bf16 window) and a per-token X Uv cache (Sec. 3.3.1).
+    k0_f16 [B][stride] float16 with wk_row0 [Hkv*hd] bfloat16: the outlier channel of X Uk kept in fp16 (App. B)."""
+    k0_stride = 0
+    if k0_f16 is not None:
+        assert k0_f16.dtype == torch.float16 and k0_f16.is_contiguous() and k0_f16.dim() == 2 and k0_f16.shape[0] == kcache.B
+        assert wk_row0 is not None and wk_row0.dtype == torch.bfloat16 and wk_row0.is_contiguous()
+        assert wk_row0.numel() == attn.n_kv_heads * attn.head_dim
+        k0_stride = k0_f16.shape[1]
     assert q_bf16.dtype == torch.bfloat16 and q_bf16.is_contiguous()
     assert ktail_bf16.dtype == torch.bfloat16 and ktail_bf16.is_contiguous()
     assert tuple(ktail_bf16.shape) == (kcache.B, kcache.group, kcache.d)
@@ -582,7 +591,8 @@ def xq_remat_attn_decode_latent_per_channel(attn, q_bf16, kcache, ktail_bf16, vc
         out = torch.empty((kcache.B, attn.n_q_heads, attn.head_dim), dtype=torch.float32, device=q_bf16.device)
     _check(load_library().xq_remat_attn_decode_latent_per_channel(
         C.byref(a), _ptr(q_bf16), C.byref(ks), _ptr(ktail_bf16), C.byref(vs), _ptr(wk_coded), _ptr(wk_dense),
-        _ptr(wv_coded), _i32(lens, kcache.B), *_terms_args(terms), int(bool(terms_valid)), _ptr(out), _ptr(workspace),
+        _ptr(wv_coded), _i32(lens, kcache.B), _ptr(k0_f16), k0_stride, _ptr(wk_row0), *_terms_args(terms),
+        int(bool(terms_valid)), _ptr(out), _ptr(workspace),
         workspace.numel(), _stream()),
         "xq_remat_attn_decode_latent_per_channel")
     return out

@@ -37,6 +37,7 @@ size_t remat_latent_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int 
 hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* kc,
                                            const uint16_t* ktail, const xq_cache_t* vc, const void* wk_coded,
                                            const void* wk_dense, const void* wv_coded, const BatchI32& len, int max_len,
+                                           const uint16_t* k0_f16, long long k0_stride, const uint16_t* wk_row0,
                                            void* terms, bool terms_valid, float* out, void* ws, hipStream_t s);
 size_t remat_prefill_workspace_bytes(int B, int T, int Hq, int max_len, int d, int group, bool coded);
 hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, const xq_cache_t* xc,
@@ -471,8 +472,10 @@ size_t xq_remat_attn_latent_per_channel_workspace_bytes(const xq_attn_t* a, int3
 xq_status_t xq_remat_attn_decode_latent_per_channel(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* kcache,
                                                     const uint16_t* ktail_bf16, const xq_cache_t* vcache,
                                                     const void* wk_coded, const void* wk_dense, const void* wv_coded,
-                                                    const int32_t* len, void* terms, size_t terms_bytes, int32_t terms_valid,
-                                                    float* out, void* workspace, size_t workspace_bytes, void* stream)
+                                                    const int32_t* len, const uint16_t* k0_f16, int64_t k0_stride,
+                                                    const uint16_t* wk_row0_bf16, void* terms, size_t terms_bytes,
+                                                    int32_t terms_valid, float* out, void* workspace,
+                                                    size_t workspace_bytes, void* stream)
 {
     xq_status_t st = check_attn(a);
     if (st != XQ_OK) return st;
@@ -503,9 +506,10 @@ xq_status_t xq_remat_attn_decode_latent_per_channel(const xq_attn_t* a, const ui
         if (terms_bytes < pc_terms_bytes(kcache->B, kcache->cap, kcache->fmt.d, kcache->fmt.group, a->n_kv_heads / 2))
             return XQ_ERR_WORKSPACE;
     }
+    if (k0_f16 && (!wk_row0_bf16 || k0_stride < max_len)) return XQ_ERR_INVALID_ARG;
     hipError_t e = run_remat_attn_decode_latent_pc(a, q_bf16, kcache, ktail_bf16, vcache, wk_coded, wk_dense, wv_coded, lv,
-                                                   max_len, terms, terms_valid != 0, out, workspace,
-                                                   static_cast<hipStream_t>(stream));
+                                                   max_len, k0_f16, k0_stride, wk_row0_bf16, terms, terms_valid != 0, out,
+                                                   workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 

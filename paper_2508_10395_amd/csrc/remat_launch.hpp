@@ -463,6 +463,32 @@ hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const
     return hipGetLastError();
 }
 
+// App. B: the first channel of X Uk, which collects the outliers, kept in fp16 instead of being quantised.  Its share
+// of the keys is the rank-1 term k0[t] * W[0][:], so its share of a query head's score is k0[t] * (q . W[0][columns of
+// the head]); this kernel adds it to the stored scores between the two passes (the prepared key streams carry a zero
+// row 0, so nothing else of that channel reaches the keys).  Grid (token chunks, query heads, sequences).
+__global__ __launch_bounds__(256) void outlier_scores_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ w_row0,
+                                                             const uint16_t* __restrict__ k0, long long k0_stride,
+                                                             float* __restrict__ scores, long long score_stride, int Hq,
+                                                             int Hkv, float scale_log2e, BatchI32 len)
+{
+    const int hq = blockIdx.y, b = blockIdx.z;
+    const int hk = hq / (Hq / Hkv);
+    const int lane = threadIdx.x & 63;
+    const uint16_t* qv = q + ((long long)b * Hq + hq) * 128;
+    const uint16_t* wv = w_row0 + hk * 128;
+    float dot = bf16_bits_to_f32(qv[lane]) * bf16_bits_to_f32(wv[lane]);
+    dot = __builtin_fmaf(bf16_bits_to_f32(qv[lane + 64]), bf16_bits_to_f32(wv[lane + 64]), dot);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) dot += __shfl_xor(dot, off);          // every wave holds the whole sum
+    const float f = dot * scale_log2e;
+    float* srow = scores + ((long long)b * Hq + hq) * score_stride;
+    const uint16_t* krow = k0 + (long long)b * k0_stride;
+    const int n = len.v[b];
+    for (int t = blockIdx.x * 256 + threadIdx.x; t < n; t += gridDim.x * 256)
+        srow[t] = __builtin_fmaf((float)__builtin_bit_cast(_Float16, krow[t]), f, srow[t]);
+}
+
 // ---- the paper's setting for grouped-query models (Sec. 3.3.1): X Uk per channel with a residual
 // window, X Uv per token.  Two passes as in run_remat_attn_decode_latent: pass 1 rematerialises the keys of a
 // head pair from the per-channel K cache (coded blocks, then the window rows through the dense kernel) and
@@ -483,6 +509,7 @@ size_t remat_latent_pc_workspace_bytes(int B, int Hq, int Hkv, int max_len, int 
 hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* kc,
                                            const uint16_t* ktail, const xq_cache_t* vc, const void* wk_coded,
                                            const void* wk_dense, const void* wv_coded, const BatchI32& len, int max_len,
+                                           const uint16_t* k0_f16, long long k0_stride, const uint16_t* wk_row0,
                                            void* terms, bool terms_valid, float* out, void* ws, hipStream_t s)
 {
     const int kbits = kc->fmt.bits, blockT = kc->fmt.group, r = kc->fmt.d, B = kc->B;
@@ -576,6 +603,12 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
         t.wprep = static_cast<const uint8_t*>(wk_dense);
         t.n_main_slabs = Ld.n_main_slabs; t.head_bytes = (long long)Ld.head_bytes;
         e = launch_with_lds(remat_attn_dense_kernel<DENSE_SCORES>, LDS_DENSE_TOTAL, t, pairs * B, s);
+        if (e != hipSuccess) return e;
+    }
+    if (k0_f16) {                                                            // the fp16 channel's share of the scores
+        outlier_scores_kernel<<<dim3((max_len + 1023) / 1024, p.Hq, B), dim3(256), 0, s>>>(
+            q, wk_row0, k0_f16, k0_stride, scores, score_stride, p.Hq, p.Hkv, p.scale_log2e, len);
+        e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     // pass 2: values from the per-token cache

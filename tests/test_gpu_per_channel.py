@@ -142,7 +142,7 @@ def test_full_size_llama2_7b_per_channel_sampled_pairs(xq):
     print(f"c2 per-channel sampled pairs: worst norm-wise rel err {worst:.2e}")
 
 
-def _latent_pc(xq, w, kbits, kG, vbits, vG, lens, pairs=None):
+def _latent_pc(xq, w, kbits, kG, vbits, vG, lens, pairs=None, fp16_channel=False):
     """Latent rows X Uk, X Uv (synthetic, with the outlier channel of X Uk), keys per channel with a window,
     values per token; the oracle builds its own caches from the same rows (they must agree byte for byte
     with the GPU's) and attends over those."""
@@ -150,6 +150,7 @@ def _latent_pc(xq, w, kbits, kG, vbits, vG, lens, pairs=None):
     rng = np.random.default_rng(w.cfg_id * 7 + kbits)
     lk = rng.standard_normal((w.B, w.L, r)).astype(np.float32)
     lk[..., 0] *= 25.0
+    k0 = np.ascontiguousarray(lk[..., 0].astype(np.float16))                 # App. B: the outlier channel in fp16
     lk = xi.to_bf16_bits(lk)
     lv = xi.to_bf16_bits(rng.standard_normal((w.B, w.L, r)).astype(np.float32))
     wfk = xi.to_bf16_bits((rng.standard_normal((r, r)) * r ** -0.5).astype(np.float32))
@@ -168,10 +169,16 @@ def _latent_pc(xq, w, kbits, kG, vbits, vG, lens, pairs=None):
     vc = xq.alloc_cache(w.B, w.L, r, vG, vbits)
     xq.xq_quantize_append(vc, bits_to_torch(lv), [0] * w.B)
     attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
-    wkc = xq.xq_prepare_weights_pairs(attn, r, 128, kbits, bits_to_torch(wfk))
-    wkd = xq.xq_prepare_weights_pairs(attn, r, 0, 16, bits_to_torch(wfk))
+    wfk_streams, extra, okw = wfk, {}, {}
+    if fp16_channel:                        # the key streams carry a zero row 0, the row itself goes in separately
+        wfk_streams = wfk.copy()
+        wfk_streams[0, :] = 0
+        extra = dict(k0_f16=torch.from_numpy(k0).cuda(), wk_row0=bits_to_torch(np.ascontiguousarray(wfk[0])))
+        okw = dict(k0_f16=k0.view(np.uint16))
+    wkc = xq.xq_prepare_weights_pairs(attn, r, 128, kbits, bits_to_torch(wfk_streams))
+    wkd = xq.xq_prepare_weights_pairs(attn, r, 0, 16, bits_to_torch(wfk_streams))
     wvc = xq.xq_prepare_weights_pairs(attn, r, vG, vbits, bits_to_torch(wfv))
-    out = xq.xq_remat_attn_decode_latent_per_channel(attn, bits_to_torch(q), kc, ktail, vc, wkc, wkd, wvc, lens)
+    out = xq.xq_remat_attn_decode_latent_per_channel(attn, bits_to_torch(q), kc, ktail, vc, wkc, wkd, wvc, lens, **extra)
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     if pairs is None:
@@ -184,7 +191,7 @@ def _latent_pc(xq, w, kbits, kG, vbits, vG, lens, pairs=None):
     ref = xo.latent_attn_pairs_per_channel(q_bf16=q, Wfk=wfk, Wfv=wfv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd,
                                            softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs,
                                            k_packed=kp, k_scale=ks, k_zero=kz, k_G=kG, k_bits=kbits,
-                                           k_tail_bf16=kt, v_packed=vp, v_scale=vs, v_zero=vz, v_G=vG, v_bits=vbits)
+                                           k_tail_bf16=kt, v_packed=vp, v_scale=vs, v_zero=vz, v_G=vG, v_bits=vbits, **okw)
     sel = np.array([got[b, h] for b, h in pairs])
     normwise, maxwise = rel_errors(sel, ref)
     assert np.all(np.isfinite(got)), w.name
@@ -196,6 +203,23 @@ def _latent_pc(xq, w, kbits, kG, vbits, vG, lens, pairs=None):
 def test_latent_with_per_channel_keys(xq, kbits, kG, vbits, vG):
     w = xi.C4.scaled(B=3, L=420, d=512, Hq=8, Hkv=2, n_outlier=5)          # r = 256, 4 query heads per KV head
     _latent_pc(xq, w, kbits, kG, vbits, vG, lens=[420, 256, 31])
+
+
+@pytest.mark.parametrize("kbits,kG,vbits,vG", [(2, 128, 2, 64), (3, 64, 3, 128), (4, 128, 4, 128)])
+def test_latent_with_fp16_outlier_channel(xq, kbits, kG, vbits, vG):
+    """App. B: channel 0 of X Uk in fp16; sequences with several blocks and a window, a block boundary, a window only."""
+    w = xi.C4.scaled(B=3, L=420, d=512, Hq=8, Hkv=2, n_outlier=5)
+    _latent_pc(xq, w, kbits, kG, vbits, vG, lens=[420, 256, 31], fp16_channel=True)
+
+
+def test_full_size_llama3_8b_latent_fp16_outlier_channel_sampled_pairs(xq):
+    """Config 4's shape as below with the first channel of X Uk in fp16, sampled pairs."""
+    w = xi.C4
+    lens = [w.L - 28] * w.B
+    lens[3] = w.L
+    pairs = xi.sample_pairs(w, 8)
+    worst = _latent_pc(xq, w, 2, 128, 2, 64, lens, pairs=pairs, fp16_channel=True)
+    print(f"c4 latent with per-channel keys and the fp16 channel, sampled pairs: worst norm-wise rel err {worst:.2e}")
 
 
 def test_full_size_llama3_8b_latent_per_channel_sampled_pairs(xq):

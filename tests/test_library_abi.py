@@ -195,14 +195,17 @@ def test_argument_errors_of_the_widened_entry_points():
     assert lib.xq_prepare_weights_pairs(C.byref(la), 256, 128, 3, x, x, 16, st) == WORKSPACE
     assert lib.xq_prepare_weights_pairs(C.byref(la), 256, 128, 3, None, x, 1 << 30, st) == INVALID
     kc, vc = pc(d=256), _cache(cap=256, d=256, group=64, bits=2)
-    lp = lambda k=kc, v=vc, ln=130, wsb=1 << 30, terms=None, tb=0: lib.xq_remat_attn_decode_latent_per_channel(
-        C.byref(la), x, C.byref(k), x, C.byref(v), x, x, x, (C.c_int32 * 1)(ln), terms, tb, 0, x, x, wsb, st)
+    lp = lambda k=kc, v=vc, ln=130, wsb=1 << 30, terms=None, tb=0, k0=None, k0s=0, w0=None: \
+        lib.xq_remat_attn_decode_latent_per_channel(C.byref(la), x, C.byref(k), x, C.byref(v), x, x, x, (C.c_int32 * 1)(ln),
+                                                    k0, k0s, w0, terms, tb, 0, x, x, wsb, st)
     assert lp(ln=0) == INVALID
     assert lp(ln=300) == INVALID                                                # longer than the value cache
     assert lp(v=_cache(cap=256, d=512, group=64, bits=2)) == INVALID            # widths differ
     assert lp(wsb=64) == WORKSPACE
     assert lp(k=pc(d=256, bits=8)) == UNSUPPORTED
     assert lp(terms=x, tb=64) == WORKSPACE
+    assert lp(k0=x, k0s=256, w0=None) == INVALID                                # the fp16 channel without its weight row
+    assert lp(k0=x, k0s=100, w0=x) == INVALID                                   # fewer fp16 values than tokens
     assert xq.xq_remat_attn_latent_per_channel_workspace_bytes(at2, 1, 300, 256, 128, 64) > 0
     assert xq.xq_remat_attn_latent_per_channel_workspace_bytes(at2, 1, 300, 256, 128, 32) == 0
 
