@@ -29,8 +29,8 @@ K3_HBM_BYTES_PER_LAUNCH = 2.25e9
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--cpu-pairs", type=int, default=96, help="(sequence, head) pairs the oracle times")
     ap.add_argument("--profile-copy", action="store_true",
