@@ -303,6 +303,22 @@ def main():
         dws = torch.empty(xq.xq_remat_attn_workspace_bytes(oattn, ow.B, ow.L, ow.d, 0), dtype=torch.uint8, device=dev)
         t_a = timed(lambda: xq.xq_remat_attn_decode(oattn, oq, dwp, olens, acc_bf16=oacc, out=oout, workspace=dws),
                     n=5, warm=2)
+        # prefill-sized projections on the matrix cores: a chunk of 1024 new tokens per sequence into the latent
+        # space, plain (Sec. 3.3.1) and as the cross-layer delta against the accumulator (Sec. 3.3.2)
+        Tb = 1024
+        xchunk = torch.randn((ow.B, Tb, ow.d), device=dev, generator=gen).to(torch.bfloat16)
+        proj = xq.xq_prepare_projection(ut)
+        blat = torch.empty((ow.B, Tb, n_lat), dtype=torch.bfloat16, device=dev)
+        t_pb = timed(lambda: xq.xq_latent_project_bulk(xchunk.view(ow.B * Tb, ow.d), proj, n_lat,
+                                                       out=blat.view(ow.B * Tb, n_lat)), n=10, warm=3)
+        t_db = timed(lambda: xq.xq_cl_latent_delta_project_bulk(xchunk, oacc, proj, n_lat, [ow.L - Tb] * ow.B, out=blat),
+                     n=10, warm=3)
+        pflops = 2.0 * ow.B * Tb * ow.d * n_lat
+        extra["latent_projection_bulk_c4"] = {
+            "workload": "16 x 1024 new rows of width 4096 into 2048 latent channels (dense-source contraction kernel)",
+            "project_ms": t_pb, "project_TFLOP/s": pflops / t_pb / 1e9,
+            "delta_project_ms": t_db, "delta_project_TFLOP/s_of_matrix_work": 2.0 * pflops / t_db / 1e9}
+        del xchunk, proj, blat
         uflops = 2.0 * ow.B * ow.L * n_lat * ow.d
         extra["cl_gqa_c4"] = {"workload": "c4 shape, cross-layer step of a GQA layer (latent width 2048, 2-bit, group 64); "
                                           "random latent deltas and U_kv (timing only)",

@@ -256,6 +256,14 @@ xq_status_t xq_remat_attn_decode_latent(const xq_attn_t *a, const uint16_t *q_bf
  *   x_bf16 dev [B][T][d]; acc_bf16 dev [B][cap][d]; start host [B], 0 <= start[b], start[b]+T <= cap;
  *   out_bf16 dev [B][T][n_lat].  d multiple of 128, n_lat multiple of 32.  T = 0 is a no-op.
  *
+ * xq_cl_latent_delta_project_bulk: the same for prefill-sized T, on the matrix cores (the dense-source
+ *   contraction kernel, as xq_latent_project_bulk): proj is xq_prepare_projection(d, n_lat, Ut) and is walked
+ *   twice, against the rows of x and against the matching accumulator rows with flipped signs, so that
+ *   x U - acc U is summed in one fp32 accumulator and rounded once.  The result equals the one above up to
+ *   fp32 accumulation error, which here is relative to sum_c (|x| + |acc|) |U| rather than to the smaller
+ *   sum_c |x - acc| |U| (about 2^-16 of it at most, against the output's own 2^-9 rounding).
+ *   n_lat multiple of 256; B*T*d and B*cap*d below 2^31 elements (split larger inputs).
+ *
  * xq_prepare_upproject: offline re-layout of Ut for xq_cl_accumulate_latent (src_bits 2, 3, 4 of
  *   the delta cache; d multiple of 256, n_lat multiple of 128); out dev, at least
  *   xq_prepared_upproject_bytes(d, n_lat, group, src_bits) bytes (0 = unsupported).
@@ -274,6 +282,9 @@ xq_status_t xq_cl_latent_delta_project(const uint16_t *x_bf16, const uint16_t *a
                                        const uint16_t *Ut_bf16, int32_t B, int32_t T, int32_t cap,
                                        const int32_t *start, int32_t d, int32_t n_lat,
                                        uint16_t *out_bf16, void *stream);
+xq_status_t xq_cl_latent_delta_project_bulk(const uint16_t *x_bf16, const uint16_t *acc_bf16, const void *proj,
+                                            int32_t B, int32_t T, int32_t cap, const int32_t *start,
+                                            int32_t d, int32_t n_lat, uint16_t *out_bf16, void *stream);
 size_t      xq_prepared_upproject_bytes(int32_t d, int32_t n_lat, int32_t group, int32_t src_bits);
 xq_status_t xq_prepare_upproject(int32_t d, int32_t n_lat, int32_t group, int32_t src_bits,
                                  const uint16_t *Ut_bf16, void *out, size_t out_bytes, void *stream);

@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     xq_remat_attn_workspace_bytes, xq_remat_attn_decode,
     xq_latent_project, xq_prepare_weights_latent, xq_remat_attn_decode_latent,
     xq_prepared_weights_latent_bytes, xq_remat_attn_latent_workspace_bytes,
-    xq_cl_latent_delta_project, xq_prepared_upproject_bytes, xq_prepare_upproject,
+    xq_cl_latent_delta_project, xq_cl_latent_delta_project_bulk, xq_prepared_upproject_bytes, xq_prepare_upproject,
     xq_cl_accumulate_latent_workspace_bytes, xq_cl_accumulate_latent,
     xq_remat_attn_prefill_workspace_bytes, xq_remat_attn_prefill,
     alloc_cache_per_channel, xq_quantize_blocks_per_channel,

@@ -23,7 +23,7 @@ SYMBOLS = [
     "xq_latent_project", "xq_prepare_weights_latent", "xq_remat_attn_decode_latent",
     "xq_remat_attn_decode_rope",
     "xq_prepared_weights_latent_bytes", "xq_remat_attn_latent_workspace_bytes",
-    "xq_cl_latent_delta_project", "xq_prepared_upproject_bytes", "xq_prepare_upproject",
+    "xq_cl_latent_delta_project", "xq_cl_latent_delta_project_bulk", "xq_prepared_upproject_bytes", "xq_prepare_upproject",
     "xq_cl_accumulate_latent_workspace_bytes", "xq_cl_accumulate_latent",
     "xq_remat_attn_prefill_workspace_bytes", "xq_remat_attn_prefill",
     "xq_quantize_blocks_per_channel",
@@ -110,6 +110,9 @@ def load_library():
     lib.xq_remat_attn_decode_latent.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
                                                 C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_size_t,
                                                 C.c_void_p]
+    lib.xq_cl_latent_delta_project_bulk.restype = C.c_int
+    lib.xq_cl_latent_delta_project_bulk.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                                    C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.xq_cl_latent_delta_project.restype = C.c_int
     lib.xq_cl_latent_delta_project.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                                C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
@@ -398,6 +401,20 @@ def xq_cl_latent_delta_project(x_bf16, acc_bf16, Ut_bf16, start, out=None):
     _check(load_library().xq_cl_latent_delta_project(_ptr(x_bf16), _ptr(acc_bf16), _ptr(Ut_bf16), B, T,
                                                      acc_bf16.shape[1], _i32(start, B), d, n_lat, _ptr(out),
                                                      _stream()), "xq_cl_latent_delta_project")
+    return out
+
+
+def xq_cl_latent_delta_project_bulk(x_bf16, acc_bf16, proj, n_lat, start, out=None):
+    """The same for prefill-sized T, on the matrix cores; proj = xq_prepare_projection(Ut)."""
+    for t in (x_bf16, acc_bf16):
+        assert t.dtype == torch.bfloat16 and t.is_contiguous()
+    B, T, d = x_bf16.shape
+    assert acc_bf16.dim() == 3 and acc_bf16.shape[0] == B and acc_bf16.shape[2] == d
+    if out is None:
+        out = torch.empty((B, T, n_lat), dtype=torch.bfloat16, device=x_bf16.device)
+    _check(load_library().xq_cl_latent_delta_project_bulk(_ptr(x_bf16), _ptr(acc_bf16), _ptr(proj), B, T,
+                                                          acc_bf16.shape[1], _i32(start, B), d, n_lat, _ptr(out),
+                                                          _stream()), "xq_cl_latent_delta_project_bulk")
     return out
 
 

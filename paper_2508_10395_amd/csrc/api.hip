@@ -14,6 +14,8 @@ hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const u
                                int head_stride, void* out, hipStream_t s, bool transposed = false);
 hipError_t run_project_rows_dense(const uint16_t* x, long long M, int d, int n_lat, const void* proj, uint16_t* out,
                                   hipStream_t s);
+hipError_t run_project_delta_rows_dense(const uint16_t* x, const uint16_t* acc, int B, int T, int cap, const BatchI32& start,
+                                        int d, int n_lat, const void* proj, uint16_t* out, hipStream_t s);
 hipError_t run_latent_project(const uint16_t* x, const uint16_t* ut, int M, int d, int n_lat, uint16_t* out,
                               hipStream_t s);
 hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq_cache_t* xc,
@@ -543,6 +545,27 @@ xq_status_t xq_latent_project_bulk(const uint16_t* x_bf16, const void* proj, int
     if (!x_bf16 || !proj || !out_bf16 || !aligned16(x_bf16) || !aligned16(proj) || !aligned16(out_bf16))
         return XQ_ERR_INVALID_ARG;
     hipError_t e = run_project_rows_dense(x_bf16, M, d, n_lat, proj, out_bf16, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+xq_status_t xq_cl_latent_delta_project_bulk(const uint16_t* x_bf16, const uint16_t* acc_bf16, const void* proj, int32_t B,
+                                            int32_t T, int32_t cap, const int32_t* start, int32_t d, int32_t n_lat,
+                                            uint16_t* out_bf16, void* stream)
+{
+    if (B < 1 || T < 0 || cap < 1 || d <= 0 || n_lat <= 0 || !start) return XQ_ERR_INVALID_ARG;
+    if (B > XQ_MAX_BATCH || xq_prepared_projection_bytes(d, n_lat) == 0) return XQ_ERR_UNSUPPORTED;
+    // (the kernel addresses the rows of either tensor with 32-bit byte offsets)
+    if ((long long)B * T * d * 2 >= (1LL << 32) || (long long)B * cap * d * 2 >= (1LL << 32)) return XQ_ERR_UNSUPPORTED;
+    BatchI32 sv{};
+    for (int b = 0; b < B; ++b) {
+        if (start[b] < 0 || (long long)start[b] + T > cap) return XQ_ERR_INVALID_ARG;
+        sv.v[b] = start[b];
+    }
+    if (T == 0) return XQ_OK;
+    if (!x_bf16 || !acc_bf16 || !proj || !out_bf16) return XQ_ERR_INVALID_ARG;
+    if (!aligned16(x_bf16) || !aligned16(acc_bf16) || !aligned16(proj) || !aligned16(out_bf16)) return XQ_ERR_INVALID_ARG;
+    hipError_t e = run_project_delta_rows_dense(x_bf16, acc_bf16, B, T, cap, sv, d, n_lat, proj, out_bf16,
+                                                static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 

@@ -532,20 +532,51 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
             xvoff[j] = (uint32_t)min(tok, c.len - 1) * row_bytes + (uint32_t)piece * 16u;
         }
     }
+    // second source of the bf16 store mode (rows of another tensor, subtracted): its row offsets and base
+    uint32_t xvoff2[4] = {0u, 0u, 0u, 0u};
+    const uint8_t* cbase2 = nullptr;
+    int split_halves = 0x7FFFFFFF;                        // first half slab that reads the second source
+    if constexpr (DMODE == DENSE_STORE_BF16) {
+        if (p.acc2) {
+            cbase2 = reinterpret_cast<const uint8_t*>(p.acc2);
+            split_halves = 2 * p.w_slabs;
+            const int r8 = lane >> 3, sc = lane & 7;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int piece = sc ^ ((r8 >> 1) | ((j & 1) << 2));
+                const int tok = min(c.tile * TILE_TOKENS + wave * CHUNK_TOKENS + 8 * j + r8, c.len - 1);
+                const int sb = tok / p.Tq, st = tok - sb * p.Tq;
+                const uint32_t row2 = (uint32_t)sb * (uint32_t)p.cap2 + (uint32_t)(p.tok0.v[sb] + st);
+                xvoff2[j] = row2 * row_bytes + (uint32_t)piece * 16u;
+            }
+        }
+    }
     const uint32_t stage = lds_base + LDS_DENSE_STAGE_OFF + wave * LDS_DENSE_STAGE_BYTES;
     // fragment side: this lane's token tl, k-step kk of the half slab -> piece 2 kk + half
     const uint8_t* my_stage = lds + LDS_DENSE_STAGE_OFF + wave * LDS_DENSE_STAGE_BYTES + (tl >> 3) * 1024 + (tl & 7) * 128;
     const int fx = ((tl & 7) >> 1) | (((tl >> 3) & 1) << 2);
     auto issue_x = [&](int h) {                           // token rows of half slab h -> staging
         const int hc = min(h, n_halves - 1);              // (past the end: a harmless repeat)
-        const uint8_t* src = cbase + (long long)hc * 128;
+        if (DMODE == DENSE_STORE_BF16 && hc >= split_halves) {
+            const uint8_t* src = cbase2 + (long long)(hc - split_halves) * 128;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) dma_b128(src, xvoff[j], stage + j * 1024);
+            for (int j = 0; j < 4; ++j) dma_b128(src, xvoff2[j], stage + j * 1024);
+        } else {
+            const uint8_t* src = cbase + (long long)hc * 128;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dma_b128(src, xvoff[j], stage + j * 1024);
+        }
     };
-    auto take_x = [&](uint4 (&dst)[4]) {
+    auto take_x = [&](uint4 (&dst)[4], int h) {           // h: the half slab these rows belong to
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
             dst[kk] = *reinterpret_cast<const uint4*>(my_stage + (((2 * kk + half) ^ fx) * 16));
+        if (DMODE == DENSE_STORE_BF16 && h >= split_halves) {          // the second source is subtracted
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                dst[kk].x ^= 0x80008000u; dst[kk].y ^= 0x80008000u; dst[kk].z ^= 0x80008000u; dst[kk].w ^= 0x80008000u;
+            }
+        }
     };
 
     f32x16 acc[8];
@@ -561,7 +592,7 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
     issue_x(0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    take_x(bd[0]);
+    take_x(bd[0], 0);
 #pragma unroll
     for (int sl = 0; sl < 7; ++sl) af[sl] = *reinterpret_cast<const uint4*>(my_slab + sl * 1024);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staging has been read: it may be refilled
@@ -571,7 +602,9 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
         const bool more_main = it + 1 < p.n_main_slabs;
         const int s_next = more_main ? it + 1 : it;       // (the last iteration repeats itself into unused buffers)
         const uint32_t wdst = lds_w + (uint32_t)(((it + 1) & 1) * SLAB_BYTES);
-        const uint8_t* wnext = wsrc + (long long)s_next * SLAB_BYTES;
+        // (bf16 store mode with a second source: the weight stream is walked a second time)
+        const int s_w = (DMODE == DENSE_STORE_BF16 && s_next >= p.w_slabs) ? s_next - p.w_slabs : s_next;
+        const uint8_t* wnext = wsrc + (long long)s_w * SLAB_BYTES;
         const uint8_t* slab = my_slab + (it & 1) * SLAB_BYTES;
         const uint8_t* slab_next = my_slab + ((it + 1) & 1) * SLAB_BYTES;
         __builtin_amdgcn_sched_barrier(0);
@@ -587,7 +620,7 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
             // token rows: outstanding behind the DMA of the next half are this half's 4 weight steps
             if constexpr (hs == 16) {
                 asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-                take_x(bd[hf ^ 1]);
+                take_x(bd[hf ^ 1], 2 * it + hf + 1);
             }
             if constexpr (hs == 20) {
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");

@@ -74,6 +74,12 @@ struct RematParams {
     float store_scale;       // dense store mode: kv_out = (store_add ? kv_out : 0) + store_scale * row
     int store_add;
     uint16_t* rows_out;      // dense bf16 store mode: [rows][grid_heads * 256] bf16 (one sequence)
+    // dense bf16 store mode, optional second source: out = (x - acc2) W.  The walk covers 2 w_slabs slabs: the
+    // first w_slabs take the rows of `acc` (= x, M rows), the others the matching rows of acc2 with flipped
+    // signs against the same weights (the stream is walked twice).  Row m = b * Tq + t of x matches row
+    // b * cap2 + tok0[b] + t of acc2.  acc2 == nullptr: one source, w_slabs == n_main_slabs.
+    const uint16_t* acc2;
+    int w_slabs, cap2;
     float* kv_out;           // dense store mode: [B][pc_blocks_cap][grid_heads][256] fp32 rematerialised rows
     int pc_block, pc_blocks_cap;   // tokens per block (64 or 128), blocks per sequence in the arrays above
     const float* rope;       // optional [n_pos][64][2] cos, sin: rotate the keys (half-split pairs)

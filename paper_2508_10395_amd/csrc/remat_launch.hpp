@@ -641,7 +641,28 @@ hipError_t run_project_rows_dense(const uint16_t* x, long long M, int d, int n_l
     p.len.v[0] = (int)M;
     p.tiles_per_seq = (int)((M + TILE_TOKENS - 1) / TILE_TOKENS);
     p.wprep = static_cast<const uint8_t*>(proj);
-    p.n_main_slabs = L.n_main_slabs; p.head_bytes = (long long)L.head_bytes;
+    p.n_main_slabs = L.n_main_slabs; p.w_slabs = L.n_main_slabs; p.head_bytes = (long long)L.head_bytes;
+    p.rows_out = out;
+    return launch_with_lds(remat_attn_dense_kernel<DENSE_STORE_BF16>, LDS_DENSE_TOTAL, p, blocks * p.tiles_per_seq, s);
+}
+
+// Bulk cross-layer latent delta (Sec. 3.3.2), out = bf16((x - acc rows) U) for T rows of each of B sequences: the
+// same kernel walks the prepared stream of U twice, first against the rows of x, then against the matching
+// accumulator rows with flipped signs, so that x U - acc U is summed in one fp32 accumulator and rounded once.
+hipError_t run_project_delta_rows_dense(const uint16_t* x, const uint16_t* acc, int B, int T, int cap, const BatchI32& start,
+                                        int d, int n_lat, const void* proj, uint16_t* out, hipStream_t s)
+{
+    const int blocks = n_lat / 256;
+    const long long M = (long long)B * T;
+    const WPrepLayout L = make_wprep_layout(d, 128, 16, blocks);
+    RematParams p{};
+    p.acc = x; p.B = 1; p.cap = (int)M; p.d = d; p.row_d = d;
+    p.Hq = p.Hkv = blocks; p.grid_heads = blocks; p.tile_major = 1;
+    p.len.v[0] = (int)M;
+    p.tiles_per_seq = (int)((M + TILE_TOKENS - 1) / TILE_TOKENS);
+    p.wprep = static_cast<const uint8_t*>(proj);
+    p.w_slabs = L.n_main_slabs; p.n_main_slabs = 2 * L.n_main_slabs; p.head_bytes = (long long)L.head_bytes;
+    p.acc2 = acc; p.Tq = T; p.cap2 = cap; p.tok0 = start;
     p.rows_out = out;
     return launch_with_lds(remat_attn_dense_kernel<DENSE_STORE_BF16>, LDS_DENSE_TOTAL, p, blocks * p.tiles_per_seq, s);
 }

@@ -186,3 +186,47 @@ def test_full_size_llama3_8b_accumulate_sampled_rows(xq):
     worst = _accumulate_case(xq, B=w.B, cap=w.L, d=w.d, n_lat=n_lat, G=w.G, b=w.bits, lens=lens, seed=4,
                              sample_rows=np.array([0, 1, 255, 256, 4095, 7891, 7892, 8191]))
     print(f"c4 up-projecting accumulate: share of elements off by one bf16 ulp {worst:.2e}")
+
+
+@pytest.mark.parametrize("B,T,cap,d,n_lat", [(1, 300, 400, 256, 256), (3, 17, 64, 384, 256), (4, 700, 900, 512, 512),
+                                             (2, 256, 256, 128, 256)])
+def test_bulk_delta_projection_matches_oracle(xq, B, T, cap, d, n_lat):
+    """The matrix-core route of the delta projection: x U - acc U summed in one fp32 accumulator.  Its
+    accumulation error is relative to sum (|x| + |acc|) |U|, so that is the sum the bound uses; T = 17 makes
+    the 256-row tiles straddle sequences, whose accumulator rows start at different offsets."""
+    rng = np.random.default_rng(1000 * B + T)
+    ut = bits(rng.standard_normal((n_lat, d)) * d ** -0.5)
+    acc = bits(rng.standard_normal((B, cap, d)))
+    start = [int(v) for v in rng.integers(0, cap - T + 1, size=B)]
+    rows = np.stack([acc[b, start[b]:start[b] + T] for b in range(B)])           # [B][T][d]
+    x = bits(bf(rows) + 0.2 * rng.standard_normal((B, T, d)))
+    proj = xq.xq_prepare_projection(bits_to_torch(ut))
+    out = torch.full((B, T, n_lat), 7.0, dtype=torch.bfloat16, device="cuda")
+    xq.xq_cl_latent_delta_project_bulk(bits_to_torch(x), bits_to_torch(acc), proj, n_lat, start, out=out)
+    small = xq.xq_cl_latent_delta_project(bits_to_torch(x), bits_to_torch(acc), bits_to_torch(ut), start)
+    torch.cuda.synchronize()
+    ref = xo.project_delta_rows(x, rows, ut)
+    uf = np.abs(bf(ut)).astype(np.float64).T
+    exact = (bf(x).astype(np.float64) - bf(rows).astype(np.float64)) @ bf(ut).astype(np.float64).T
+    absum = (np.abs(bf(x)).astype(np.float64) + np.abs(bf(rows)).astype(np.float64)) @ uf
+    mismatch = _check_rounded(torch_to_bits(out), exact, absum, ref, 0.05)
+    assert np.mean(torch_to_bits(out) != torch_to_bits(small)) <= 0.05            # two routes to the same sum
+    print(f"bulk delta projection B={B} T={T}: share of elements off the oracle's bits {mismatch:.2e}")
+
+
+def test_bulk_delta_projection_edge_cases(xq):
+    rng = np.random.default_rng(8)
+    d, n_lat = 256, 256
+    ut = bits(rng.standard_normal((n_lat, d)) * d ** -0.5)
+    proj = xq.xq_prepare_projection(bits_to_torch(ut))
+    acc = bits(rng.standard_normal((2, 300, d)))
+    # an unchanged input: x U and acc U cancel up to the fp32 accumulation error of either sum
+    out = xq.xq_cl_latent_delta_project_bulk(bits_to_torch(acc[:, 10:290]), bits_to_torch(acc), proj, n_lat, [10, 10])
+    torch.cuda.synchronize()
+    absum = 2.0 * np.abs(bf(acc[:, 10:290])).astype(np.float64) @ np.abs(bf(ut)).astype(np.float64).T
+    assert np.all(np.abs(bf(torch_to_bits(out)).astype(np.float64)) <= absum * 2.0 ** -16)
+    e = xq.xq_cl_latent_delta_project_bulk(torch.empty((2, 0, d), dtype=torch.bfloat16, device="cuda"), bits_to_torch(acc),
+                                           proj, n_lat, [0, 0])
+    assert e.shape == (2, 0, n_lat)
+    with pytest.raises(xq.XQError):                                               # rows past the accumulator's capacity
+        xq.xq_cl_latent_delta_project_bulk(bits_to_torch(acc[:, :100]), bits_to_torch(acc), proj, n_lat, [0, 201])

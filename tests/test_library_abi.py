@@ -141,6 +141,14 @@ def test_argument_errors_of_the_widened_entry_points():
     assert dp(d=200) == UNSUPPORTED
     assert dp(n=48) == UNSUPPORTED
     assert dp(T=0, x=None) == 0
+    dpb = lambda **kw: lib.xq_cl_latent_delta_project_bulk(*[dict(dict(x=x, acc=x, proj=x, B=1, T=1, cap=8, start=one, d=256,
+                                                                       n=256, out=x, st=st), **kw)[k]
+                                                             for k in ("x", "acc", "proj", "B", "T", "cap", "start", "d", "n", "out", "st")])
+    assert dpb(acc=None) == INVALID
+    assert dpb(start=(C.c_int32 * 1)(8)) == INVALID     # start + T > cap
+    assert dpb(n=64) == UNSUPPORTED                     # the matrix-core route needs whole 256-column blocks
+    assert dpb(cap=1 << 21, d=4096) == UNSUPPORTED      # accumulator beyond 32-bit byte offsets
+    assert dpb(T=0, x=None) == 0
     # up-projection stream and accumulate
     assert xq.xq_prepared_upproject_bytes(4096, 2048, 64, 2) > 2048 * 4096 * 2
     assert xq.xq_prepared_upproject_bytes(4096 + 128, 2048, 64, 2) == 0         # d not a multiple of 256
