@@ -23,7 +23,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, published
 # HBM-side bytes of one launch of the fused kernel on this workload: rocprofv3 FETCH_SIZE + WRITE_SIZE,
 # each scaled by the factor that makes the counter read 256 MiB for a plain 256 MiB device copy
 # (profiles/remat_attn_coded_c2_hbm_traffic.txt; counters cannot be read from inside this process)
-K3_HBM_BYTES_PER_LAUNCH = 2.25e9
+K3_HBM_BYTES_PER_LAUNCH = 2.18e9
 
 
 def parse():
