@@ -268,3 +268,18 @@ def test_maximum_batch(xq):
     ref = xo.remat_attn_pairs(q_bf16=q, Wk=wk, Wv=wv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd,
                               softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs, acc_bf16=acc)
     _check(out.cpu().numpy().reshape(-1, w.hd), ref, "dense, B=128")
+
+
+@pytest.mark.parametrize("d,bits,G", [(8192, 3, 128), (5120, 2, 64)])
+def test_wide_hidden_sizes(xq, d, bits, G):
+    """Hidden sizes of larger models (64 and 40 weight slabs per tile)."""
+    w = xi.C2.scaled(B=2, L=300, d=d, Hq=2, Hkv=2, n_outlier=5)
+    _run_xquant(xq, w, bits, G, lens=[300, 77])
+
+
+@pytest.mark.parametrize("Hq,d,bits,G", [(4, 512, 3, 128), (6, 512, 3, 64), (16, 1024, 4, 128), (32, 512, 3, 128)])
+def test_query_heads_per_kv_head(xq, Hq, d, bits, G):
+    """2, 3, 8 and 16 query heads per KV head: below four the in-wave epilogue runs once per query head,
+    from four on the matrix-core epilogue takes them as rows."""
+    w = xi.C2.scaled(B=2, L=300, d=d, Hq=Hq, Hkv=2, n_outlier=2)
+    _run_xquant(xq, w, bits, G, lens=[300, 31])
