@@ -283,3 +283,11 @@ def test_query_heads_per_kv_head(xq, Hq, d, bits, G):
     from four on the matrix-core epilogue takes them as rows."""
     w = xi.C2.scaled(B=2, L=300, d=d, Hq=Hq, Hkv=2, n_outlier=2)
     _run_xquant(xq, w, bits, G, lens=[300, 31])
+
+
+def test_context_of_128k_tokens(xq):
+    """One sequence of 131067 rows in a cache of 131072 (512 tiles, 4096 partial chunks per head, a ragged last
+    tile), hidden size 1024 so that the oracle finishes in seconds."""
+    w = xi.C5.scaled(B=1, L=131072, d=1024, Hq=2, Hkv=2, n_outlier=3)
+    worst = _run_xquant(xq, w, 2, 128, [131072 - 5], pairs=[(0, 0), (0, 1)])
+    print(f"128k context: worst norm-wise rel err {worst:.2e}")
