@@ -54,7 +54,8 @@ typedef enum {
 /* Quantisation format: hidden size d, group size (64 or 128, must divide d), bits in {2,3,4,8}. */
 typedef struct { int32_t d, group, bits; } xq_qfmt_t;
 
-/* A view of a caller-owned quantised cache (layout above).  cap = rows allocated per sequence. */
+/* A view of a caller-owned quantised cache (layout above).  cap = rows allocated per sequence; one
+ * sequence's codes must stay below 4 GiB (cap * d * bits / 8 < 2^32), else XQ_ERR_UNSUPPORTED. */
 typedef struct {
     uint8_t  *codes;   /* dev */
     uint16_t *scale;   /* dev */
@@ -130,7 +131,8 @@ xq_status_t xq_prepare_weights(const xq_attn_t *a, int32_t d, int32_t group, int
  *   out[b][h] = softmax(q[b][h] K^T * softmax_scale) V.
  * Exactly one source of X^ is given:
  *   xcache != NULL   an X cache (XQuant), x^ = code*scale + zero;
- *   acc_bf16 != NULL the cross-layer accumulator [B][cap][d] (XQuant-CL).
+ *   acc_bf16 != NULL the cross-layer accumulator [B][cap][d] (XQuant-CL); one sequence's rows must stay
+ *                    below 4 GiB (cap * d * 2 < 2^32), else XQ_ERR_UNSUPPORTED.
  *   q_bf16   dev [B][n_q_heads][head_dim] bf16
  *   wprep    dev, from xq_prepare_weights with matching d / group / src_bits
  *   len      host [B], 1 <= len[b] <= cap

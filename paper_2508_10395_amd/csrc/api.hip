@@ -66,6 +66,8 @@ static xq_status_t check_cache(const xq_cache_t* c)
     if (c->fmt.d <= 0 || c->fmt.group <= 0 || c->fmt.d % c->fmt.group != 0) return XQ_ERR_INVALID_ARG;
     if (!fmt_ok(c->fmt)) return XQ_ERR_UNSUPPORTED;
     if (!aligned16(c->codes) || !aligned16(c->scale) || !aligned16(c->zero)) return XQ_ERR_INVALID_ARG;
+    // (the kernels address the rows of one sequence with 32-bit byte offsets)
+    if ((long long)c->cap * c->fmt.d * c->fmt.bits / 8 >= (1LL << 32)) return XQ_ERR_UNSUPPORTED;
     return XQ_OK;
 }
 
@@ -266,6 +268,7 @@ static xq_status_t remat_attn_common(const xq_attn_t* a, const uint16_t* q_bf16,
     } else {
         if (!aligned16(acc_bf16) || B < 1 || cap < 1 || d <= 0) return XQ_ERR_INVALID_ARG;
         if (B > XQ_MAX_BATCH || d % 128 != 0) return XQ_ERR_UNSUPPORTED;
+        if ((long long)cap * d * 2 >= (1LL << 32)) return XQ_ERR_UNSUPPORTED;     // (32-bit row offsets within a sequence)
     }
     BatchI32 lv{};
     int max_len = 0;
@@ -369,6 +372,7 @@ static xq_status_t check_cache_per_channel(const xq_cache_t* c)
     if (c->fmt.d % 128 != 0) return XQ_ERR_UNSUPPORTED;
     if (c->cap % c->fmt.group != 0) return XQ_ERR_INVALID_ARG;
     if (!aligned16(c->codes) || !aligned16(c->scale) || !aligned16(c->zero)) return XQ_ERR_INVALID_ARG;
+    if ((long long)c->cap * c->fmt.d * c->fmt.bits / 8 >= (1LL << 32)) return XQ_ERR_UNSUPPORTED;   // (32-bit row offsets)
     return XQ_OK;
 }
 

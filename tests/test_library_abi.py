@@ -173,6 +173,10 @@ def test_argument_errors_of_the_widened_entry_points():
     assert lat_call(wsb=16) == WORKSPACE
     assert lat_call(attn=B._Attn(3, 3, 128, 0.1), c=_cache(d=768, group=128, bits=3)) == UNSUPPORTED   # odd number of KV heads
     assert lat_call(c=_cache(d=384, group=128, bits=3)) == UNSUPPORTED          # latent width not a multiple of 256
+    # one sequence's rows are addressed with 32-bit byte offsets
+    assert lib.xq_remat_attn_decode(C.byref(la), x, None, x, 1, 1 << 20, 4096, x, (C.c_int32 * 1)(8), x, x, 1 << 30, st) == UNSUPPORTED
+    assert lib.xq_remat_attn_decode(C.byref(la), x, C.byref(_cache(cap=1 << 23, d=4096, group=128, bits=4)), None, 0, 0, 0, x,
+                                    (C.c_int32 * 1)(8), x, x, 1 << 30, st) == UNSUPPORTED
     # per-channel cache: block quantiser and attention
     pc = lambda **kw: _cache(**dict(dict(cap=256, d=256, group=128, bits=3), **kw))
     qb = lambda c, nblk=1, b0=0, xx=x: lib.xq_quantize_blocks_per_channel(C.byref(c), xx, nblk, (C.c_int32 * 1)(b0), st)
