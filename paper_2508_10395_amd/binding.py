@@ -57,13 +57,14 @@ def lib_path():
 
 
 def load_library():
-    """Load the built library (build it first if it was never built)."""
+    """Load the built library.  It is built first if it was never built or if its recorded source digest does
+    not match the sources in the tree, so a stale library is never the one under test."""
     global _LIB
     if _LIB is not None:
         return _LIB
     path = lib_path()
-    if not os.path.exists(path):
-        from . import build as _build
+    from . import build as _build
+    if _build.needs_build():
         _build.build(force=True)
     lib = C.CDLL(path)
     lib.xq_status_string.restype = C.c_char_p

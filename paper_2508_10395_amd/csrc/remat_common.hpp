@@ -89,8 +89,8 @@ struct RematParams {
 // LDS-DMA: every active lane copies 16 bytes from saddr + voff to LDS at lds_dst + 16 * lane.
 // Issued through inline asm so that the compiler's wait-count insertion does not serialise
 // later LDS reads of other buffers against it; completion is awaited explicitly
-// (s_waitcnt vmcnt(0) + workgroup barrier) before the data is read.  M0 is not otherwise
-// used by these kernels.
+// (s_waitcnt vmcnt(0) + workgroup barrier) before the data is read.  The asm overwrites M0 (the
+// LDS destination of the DMA) and says so in its clobber list, so the compiler keeps nothing live in it.
 __device__ __forceinline__ void dma_b128(const void* saddr, uint32_t voff, uint32_t lds_dst)
 {
     const uint64_t a = reinterpret_cast<uint64_t>(saddr);      // wave-uniform by construction
@@ -98,7 +98,7 @@ __device__ __forceinline__ void dma_b128(const void* saddr, uint32_t voff, uint3
     const uint32_t a_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);           //  returns int)
     const uint64_t ua = ((uint64_t)a_hi << 32) | (uint64_t)a_lo;
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(ua), "s"(lds_dst) : "memory");
+                 :: "v"(voff), "s"(ua), "s"(lds_dst) : "memory", "m0");
 }
 
 // one 64 KiB weight slab: 8 DMA instructions per wave (src / lds_dst already offset by the wave's 1 KiB)
