@@ -68,12 +68,18 @@ def _svd_factors(w, cfg_seed):
 
 
 def _run_latent(xq, w, bits_, G, lens, pairs=None):
-    """Project on the GPU and on the oracle and compare every row of the sequences that the pairs name.
-    The two projections differ by a bf16 ulp in a few elements per thousand (fp32 against double
-    accumulation), and such an element can move a code by a whole step, so the later stages start from
-    one set of latent rows: the oracle's, which replace the GPU's on those sequences.  Both sides then
-    quantise them (the caches must agree byte for byte) and attend over their own cache, the oracle
-    with the block-diagonal fused weights."""
+    """The latent path twice on the GPU against ONE reference, the oracle's own chain (project, quantise, attend
+    with the block-diagonal fused weights), on the sequences that the pairs name.
+
+    End to end: the library keeps its own latent rows, quantises them and attends; nothing of the oracle's
+    enters.  Its projection accumulates in fp32, the oracle's in double, so a few elements per thousand come
+    out as the neighbouring bf16 number; such an element changes its own dequantised value by at most one
+    quantisation step when it sits on a rounding boundary, and the scale or zero-point of its group by one
+    bf16 ulp when it is the group's extreme.  The outputs are held to the same 2e-3 as everything else; the
+    share of cache bytes that differ is reported.
+
+    Stage by stage: the oracle's latent rows replace the library's on those sequences; now both sides quantise
+    the same rows, so the caches must agree byte for byte, and each side attends over its own cache."""
     r = w.Hkv * w.hd
     x = xi.gen_x(w)
     wk, wv = xi.gen_weights(w)
@@ -84,30 +90,47 @@ def _run_latent(xq, w, bits_, G, lens, pairs=None):
     if pairs is None:
         pairs = [(b, h) for b in range(w.B) for h in range(w.Hq)]
     seqs = sorted({b for b, _ in pairs})
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    wprep = xq.xq_prepare_weights_latent(attn, r, G, bits_, bits_to_torch(wfk), bits_to_torch(wfv))
     lat = xq.xq_latent_project(bits_to_torch(x), bits_to_torch(ut))     # [B][L][2r]
+    cache_own = xq.alloc_cache(w.B, w.L, 2 * r, G, bits_)
+    xq.xq_quantize_append(cache_own, lat, [0] * w.B)
+    out_own = xq.xq_remat_attn_decode_latent(attn, bits_to_torch(q), wprep, lens, cache_own)
     torch.cuda.synchronize()
+    got_own = out_own.cpu().numpy()
+    # the oracle's chain
     lat_ref = np.zeros((w.B, w.L, 2 * r), np.uint16)
     for b in seqs:
         lat_ref[b] = xo.project_rows(x[b], ut)
         _check_projection(torch_to_bits(lat[b]), lat_ref[b], x[b], ut)
-        lat[b] = bits_to_torch(lat_ref[b])
-    cache = xq.alloc_cache(w.B, w.L, 2 * r, G, bits_)
-    xq.xq_quantize_append(cache, lat, [0] * w.B)
-    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
-    wprep = xq.xq_prepare_weights_latent(attn, r, G, bits_, bits_to_torch(wfk), bits_to_torch(wfv))
-    out = xq.xq_remat_attn_decode_latent(attn, bits_to_torch(q), wprep, lens, cache)
-    torch.cuda.synchronize()
-    got = out.cpu().numpy()
     packed, scale, zero = oracle_cache(lat_ref, G, bits_, seqs=seqs)
-    assert_cache_equals(cache, packed, scale, zero, w.L, seqs=seqs)
     zk, zv = np.zeros_like(wfk), np.zeros_like(wfv)
     ref = xo.remat_attn_pairs(q_bf16=q, Wk=np.concatenate([wfk, zv], axis=0), Wv=np.concatenate([zk, wfv], axis=0),
                               Hq=w.Hq, Hkv=w.Hkv, hd=w.hd, softmax_scale=w.hd ** -0.5, lens=lens, pairs=pairs,
                               packed=packed, scale=scale, zero=zero, G=G, bits=bits_)
+    # end to end
+    sel = np.array([got_own[b, h] for b, h in pairs])
+    normwise, maxwise = rel_errors(sel, ref)
+    assert np.all(np.isfinite(sel)) and normwise.max() <= TOL and maxwise <= TOL, ("end to end", float(normwise.max()), float(maxwise))
+    own_codes = cache_own.codes.cpu().numpy()
+    byte_share = float(np.mean([np.mean(own_codes[b, :lens[b]] != packed[b, :lens[b]]) for b in seqs]))
+    assert byte_share < 0.02, byte_share
+    e2e = float(normwise.max())
+    # stage by stage
+    for b in seqs:
+        lat[b] = bits_to_torch(lat_ref[b])
+    cache = xq.alloc_cache(w.B, w.L, 2 * r, G, bits_)
+    xq.xq_quantize_append(cache, lat, [0] * w.B)
+    out = xq.xq_remat_attn_decode_latent(attn, bits_to_torch(q), wprep, lens, cache)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert_cache_equals(cache, packed, scale, zero, w.L, seqs=seqs)
     sel = np.array([got[b, h] for b, h in pairs])
     normwise, maxwise = rel_errors(sel, ref)
     assert np.all(np.isfinite(sel)) and normwise.max() <= TOL and maxwise <= TOL, (float(normwise.max()), float(maxwise))
-    return float(normwise.max())
+    print(f"latent {w.name} {bits_}-bit G={G}: end to end {e2e:.2e} (cache bytes differing {byte_share:.2e}), "
+          f"from shared latent rows {float(normwise.max()):.2e}")
+    return float(normwise.max()), e2e
 
 
 @pytest.mark.parametrize("bits_,G", [(2, 64), (3, 128), (4, 128)])
@@ -145,8 +168,8 @@ def test_full_size_llama3_8b_latent_sampled_pairs(xq):
     # the oracle projects every row of the compared sequences (13 s each on 8 cores): the sample keeps
     # to the first and the last sequence, with all four query heads of one KV head among its pairs
     pairs = [p for p in xi.sample_pairs(w, 8) if p[0] in (0, w.B - 1)] + [(w.B - 1, 9), (w.B - 1, 20)]
-    worst = _run_latent(xq, w, w.bits, w.G, [w.L] * w.B, pairs=pairs)
-    print(f"c4 latent sampled pairs: worst norm-wise rel err {worst:.2e}")
+    worst, e2e = _run_latent(xq, w, w.bits, w.G, [w.L] * w.B, pairs=pairs)
+    print(f"c4 latent sampled pairs: worst norm-wise rel err {worst:.2e}, end to end {e2e:.2e}")
 
 
 @pytest.mark.parametrize("M,d,n_lat", [(1, 256, 256), (300, 256, 512), (777, 512, 256), (5000, 384, 768)])

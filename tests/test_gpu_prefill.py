@@ -140,6 +140,28 @@ def test_full_size_llama2_7b_chunk_of_32_sampled(xq):
     print(f"c2 prefill chunk of 32, sampled triples: worst norm-wise rel err {worst:.2e}")
 
 
+def test_full_size_chunk_of_128_sampled(xq):
+    """Config 2's layer at full hidden size and context, two sequences, a chunk of 128 new tokens each (four
+    passes of 32 query rows per tile).  Sampled queries: the first and the last of the chunk and the two
+    either side of a pass boundary, three heads each."""
+    w = xi.C2.scaled(B=2)
+    T = 128
+    triples = [(b, t, h) for t in (0, 31, 32, T - 1) for b, h in ((0, 0), (1, w.Hq - 1), (1, 13))]
+    worst = _run(xq, w, T, w.bits, w.G, [w.L, w.L - 77], triples=triples, seed=128)
+    print(f"c2 shape, prefill chunk of 128, sampled triples: worst norm-wise rel err {worst:.2e}")
+
+
+def test_full_size_long_context_chunk_of_512_sampled(xq):
+    """Config 5's 512-token chunk attending causally over the whole 32768-row context (2-bit, group 128, d=4096,
+    32 heads), one sequence of the four: 16 passes of 32 query rows per tile, 128 tiles, the last two tiles cut
+    by the causal mask.  The oracle redoes the first and the last query of the chunk on three heads each."""
+    w = xi.C5.scaled(B=1)
+    T = 512
+    triples = [(0, t, h) for t in (0, T - 1) for h in (0, 17, w.Hq - 1)]
+    worst = _run(xq, w, T, w.bits, w.G, [w.L], triples=triples, seed=512)
+    print(f"c5 shape, prefill chunk of 512, sampled triples: worst norm-wise rel err {worst:.2e}")
+
+
 def test_prefill_maximum_batch(xq):
     """The largest batch any call accepts (128 sequences), ragged, three queries each."""
     w = xi.C2.scaled(B=128, L=96, d=256, Hq=2, Hkv=2, n_outlier=2)

@@ -244,6 +244,61 @@ def test_full_size_cross_layer_stack_first_layers(xq):
             x = xi.gen_next_layer_x(w, x, layer + 1)
 
 
+def test_full_size_cross_layer_stack_32_layers(xq, capsys):
+    """Config 3 at its full depth, hidden size and context (32 layers, d=4096, L=8192, 32 heads; base 4-bit,
+    deltas 2-bit, group 128) for one sequence: the batch is what is cut to fit the host, not the depth (the
+    recurrence of Sec. 3.2 is per token row, and the batch of 8 is covered by the three-layer case above).  Layer l is
+    fed its own input X_l = bf16(X_{l-1} + N(0, 0.1)).  The library and the oracle each run their own chain
+    (delta against their own accumulator, quantise, accumulate); after every layer the delta cache and the
+    accumulator must hold the oracle's bytes on every row, and at layers 0, 1, 15 and 31 the attention output
+    from the accumulator is compared on sampled heads.  The distance of the accumulator from the true X_l must
+    not grow with depth."""
+    w = xi.C3.scaled(B=1)
+    G, lens = w.G, [w.L]
+    attn = xq.XQAttn(w.Hq, w.Hkv, w.hd, w.hd ** -0.5)
+    pairs = [(0, 0), (0, w.Hq - 1), (0, 11), (0, 22)]
+    x = xi.gen_x(w)
+    acc = torch.empty((w.B, w.L, w.d), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(xq.xq_remat_attn_workspace_bytes(attn, w.B, w.L, w.d, 0), dtype=torch.uint8, device="cuda")
+    ref_acc = np.zeros((w.L, w.d), np.uint16)
+    dist = {}
+    for layer in range(w.layers):
+        bits = w.bits if layer == 0 else w.delta_bits
+        cache = xq.alloc_cache(w.B, w.L, w.d, G, bits)
+        if layer == 0:
+            xq.xq_quantize_append(cache, bits_to_torch(x), [0])
+        else:
+            xq.xq_cl_delta_quantize(cache, bits_to_torch(x), acc, [0])
+        xq.xq_cl_accumulate(acc, cache, lens, init=(layer == 0))
+        torch.cuda.synchronize()
+        src = bf(x[0]) if layer == 0 else xo.cl_delta_rows(x[0], ref_acc)
+        c, s, z = xo.quantize_rows(src, G, bits)
+        assert np.array_equal(cache.codes[0].cpu().numpy(), xo.pack_rows(c, bits)), f"delta codes, layer {layer}"
+        assert np.array_equal(torch_to_bits(cache.scale[0]), s) and np.array_equal(torch_to_bits(cache.zero[0]), z), layer
+        ref_acc = xo.cl_accumulate_rows(ref_acc, c, s, z, G, layer == 0)
+        assert np.array_equal(torch_to_bits(acc[0]), ref_acc), f"accumulator bits, layer {layer}"
+        dist[layer] = float(np.abs(bf(x[0]) - bf(ref_acc)).max())
+        if layer in (0, 1, 15, 31):
+            wk, wv = xi.gen_weights(w, layer=layer)
+            q = xi.gen_q(w, layer=layer)
+            wprep = xq.xq_prepare_weights(attn, w.d, 128, 16, bits_to_torch(wk), bits_to_torch(wv))
+            out = xq.xq_remat_attn_decode(attn, bits_to_torch(q), wprep, lens, acc_bf16=acc, workspace=ws)
+            torch.cuda.synchronize()
+            ref = xo.remat_attn_pairs(q_bf16=q, Wk=wk, Wv=wv, Hq=w.Hq, Hkv=w.Hkv, hd=w.hd, softmax_scale=w.hd ** -0.5,
+                                      lens=lens, pairs=pairs, acc_bf16=ref_acc[None])
+            got = out.cpu().numpy()
+            worst = _check(np.array([got[b, h] for b, h in pairs]), ref, f"c3 layer {layer}")
+            with capsys.disabled():
+                print(f"[c3 depth] layer {layer}: accumulator and delta cache bit-exact, attention rel err {worst:.2e}, "
+                      f"max |X_l - acc| {dist[layer]:.3f}", flush=True)
+        del cache
+        if layer + 1 < w.layers:
+            x = xi.gen_next_layer_x(w, x, layer + 1)
+    # Sec. 3.2: each delta is taken against the accumulated approximation, so the error is one layer's
+    # quantisation step at any depth (2-bit deltas of std 0.32 + the 4-bit base's residue: steps of about 0.9)
+    assert max(dist[l] for l in range(16, 32)) <= 1.25 * max(dist[l] for l in range(1, 16)), dist
+
+
 @pytest.mark.parametrize("d", [128, 256])
 @pytest.mark.parametrize("bits,G", [(3, 128), (2, 64), (4, 64)])
 def test_smallest_hidden_sizes(xq, d, bits, G):
