@@ -152,6 +152,25 @@ xq_status_t xq_remat_attn_decode(const xq_attn_t *a, const uint16_t *q_bf16,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * xq_remat_attn_decode for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid it): same arguments, same kernels and same result, but
+ * the workspace is a buffer built into the library, XQ_STATIC_SCRATCH_BYTES per GPU, instead of a
+ * caller buffer.  The call allocates and frees nothing.  A problem whose
+ * xq_remat_attn_workspace_bytes(...) exceeds XQ_STATIC_SCRATCH_BYTES is refused with
+ * XQ_ERR_WORKSPACE before anything is launched (the 32 MiB cover e.g. B=8, 32 query heads, context
+ * 4096, d=4096, group 128: 19.5 MB).  The buffer belongs to the device that is current at the call
+ * (which must be the stream's device); its address is looked up on the first call on each device.
+ * All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (different
+ * streams or threads) race and must be serialised by the caller; the buffer's contents between calls
+ * are scratch.
+ */
+#define XQ_STATIC_SCRATCH_BYTES (32u << 20)
+xq_status_t xq_remat_attn_decode_static(const xq_attn_t *a, const uint16_t *q_bf16,
+                                        const xq_cache_t *xcache,
+                                        const uint16_t *acc_bf16, int32_t B, int32_t cap, int32_t d,
+                                        const void *wprep, const int32_t *len, float *out, void *stream);
+
+/*
  * xq_remat_attn_decode with rotary position embedding applied to the rematerialised keys (K = X^ Wk
  * is the key before the rotation; the models the method targets rotate it; RoFormer, cited in
  * Sec. 2).  Pairing: element i with i + head_dim/2.  For cache row t of sequence b, at position

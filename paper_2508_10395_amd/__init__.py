@@ -6,7 +6,7 @@ from .binding import (  # noqa: F401
     xq_version, xq_status_string, xq_codes_row_bytes, xq_meta_row_elems,
     xq_quantize_append, xq_cl_delta_quantize, xq_cl_accumulate,
     xq_prepared_weights_bytes, xq_prepare_weights,
-    xq_remat_attn_workspace_bytes, xq_remat_attn_decode,
+    xq_remat_attn_workspace_bytes, xq_remat_attn_decode, xq_remat_attn_decode_static, XQ_STATIC_SCRATCH_BYTES,
     xq_latent_project, xq_prepare_weights_latent, xq_remat_attn_decode_latent,
     xq_prepared_weights_latent_bytes, xq_remat_attn_latent_workspace_bytes,
     xq_cl_latent_delta_project, xq_cl_latent_delta_project_bulk, xq_prepared_upproject_bytes, xq_prepare_upproject,

@@ -19,7 +19,7 @@ SYMBOLS = [
     "xq_status_string", "xq_version", "xq_codes_row_bytes", "xq_meta_row_elems",
     "xq_quantize_append", "xq_cl_delta_quantize", "xq_cl_accumulate",
     "xq_prepared_weights_bytes", "xq_prepare_weights",
-    "xq_remat_attn_workspace_bytes", "xq_remat_attn_decode",
+    "xq_remat_attn_workspace_bytes", "xq_remat_attn_decode", "xq_remat_attn_decode_static",
     "xq_latent_project", "xq_prepare_weights_latent", "xq_remat_attn_decode_latent",
     "xq_remat_attn_decode_rope",
     "xq_prepared_weights_latent_bytes", "xq_remat_attn_latent_workspace_bytes",
@@ -92,6 +92,10 @@ def load_library():
                                          C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                          C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_size_t,
                                          C.c_void_p]
+    lib.xq_remat_attn_decode_static.restype = C.c_int
+    lib.xq_remat_attn_decode_static.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
+                                                C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                                C.POINTER(C.c_int32), C.c_void_p, C.c_void_p]
     lib.xq_remat_attn_decode_rope.restype = C.c_int
     lib.xq_remat_attn_decode_rope.argtypes = [C.POINTER(_Attn), C.c_void_p, C.POINTER(_Cache), C.c_void_p,
                                               C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
@@ -328,6 +332,29 @@ def xq_remat_attn_decode(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=Non
     _check(load_library().xq_remat_attn_decode(C.byref(a), _ptr(q_bf16), cptr, _ptr(acc_bf16), B, cap, d,
                                                _ptr(wprep), _i32(lens, B), _ptr(out), _ptr(workspace),
                                                workspace.numel(), _stream()), "xq_remat_attn_decode")
+    return out
+
+
+XQ_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def xq_remat_attn_decode_static(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=None, out):
+    """xq_remat_attn_decode with the library's built-in workspace: the call allocates nothing, so `out` is
+    the caller's (fp32 [B][Hq][head_dim])."""
+    assert q_bf16.dtype == torch.bfloat16 and q_bf16.is_contiguous()
+    assert out.dtype == torch.float32 and out.is_contiguous()
+    if xcache is not None:
+        B, cap, d = xcache.B, xcache.cap, xcache.d
+        cs = xcache.c_struct()
+        cptr = C.byref(cs)
+    else:
+        assert acc_bf16.dtype == torch.bfloat16 and acc_bf16.is_contiguous() and acc_bf16.dim() == 3
+        B, cap, d = acc_bf16.shape
+        cptr = None
+    a = attn.c_struct()
+    _check(load_library().xq_remat_attn_decode_static(C.byref(a), _ptr(q_bf16), cptr, _ptr(acc_bf16), B, cap, d,
+                                                      _ptr(wprep), _i32([int(v) for v in lens], B), _ptr(out),
+                                                      _stream()), "xq_remat_attn_decode_static")
     return out
 
 

@@ -1,4 +1,6 @@
 // C ABI of libxquant: argument validation on the host, then dispatch to the kernels.
+#include <mutex>
+
 #include "common.hpp"
 #include "remat_layout.hpp"
 
@@ -644,6 +646,66 @@ xq_status_t xq_cl_accumulate_latent(uint16_t* acc_bf16, const xq_cache_t* delta,
     hipError_t e = run_cl_accumulate_latent(acc_bf16, delta, d, uprep, lv, max_len, workspace,
                                             static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
+}
+
+// ---- decode attention for callers that cannot allocate ------------------------------------------
+// The workspace of xq_remat_attn_decode (softmax partials + the tile-ordered scale copy) lives in a
+// file-scope device array instead of a caller buffer.  Every GPU the library runs on holds its own
+// copy of the array at its own address until the process ends; the address is looked up once per
+// device, with that device current, and kept.  In host code the array's name is only a handle for
+// that lookup: kernels and memory calls get the looked-up pointer.
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[XQ_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES];
+std::mutex g_scratch_mutex;
+
+xq_status_t static_scratch_of_current_device(void** ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return XQ_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return XQ_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return XQ_OK;
+}
+}  // namespace
+
+xq_status_t xq_remat_attn_decode_static(const xq_attn_t* a, const uint16_t* q_bf16, const xq_cache_t* xcache,
+                                        const uint16_t* acc_bf16, int32_t B, int32_t cap, int32_t d,
+                                        const void* wprep, const int32_t* len, float* out, void* stream)
+{
+    // size check first, on the host, from the same query the caller-workspace entry point uses
+    xq_status_t st = check_attn(a);
+    if (st != XQ_OK) return st;
+    if ((xcache != nullptr) == (acc_bf16 != nullptr) || !len) return XQ_ERR_INVALID_ARG;
+    if (xcache) {
+        st = check_cache(xcache);
+        if (st != XQ_OK) return st;
+        B = xcache->B; cap = xcache->cap; d = xcache->fmt.d;
+    } else if (B < 1 || B > XQ_MAX_BATCH) {
+        return B < 1 ? XQ_ERR_INVALID_ARG : XQ_ERR_UNSUPPORTED;
+    }
+    int max_len = 0;
+    for (int b = 0; b < B; ++b) {
+        if (len[b] < 1 || len[b] > cap) return XQ_ERR_INVALID_ARG;
+        if (len[b] > max_len) max_len = len[b];
+    }
+    const size_t need = xq_remat_attn_workspace_bytes(a, B, max_len, d, xcache ? xcache->fmt.group : 0);
+    if (need == 0) return XQ_ERR_UNSUPPORTED;
+    if (need > (size_t)XQ_STATIC_SCRATCH_BYTES) return XQ_ERR_WORKSPACE;     // beyond the built-in buffer
+    void* ws = nullptr;
+    st = static_scratch_of_current_device(&ws);
+    if (st != XQ_OK) return st;
+    // nothing in the buffer has to start at zero: the scale pre-pass and the attention kernel write every
+    // element that the combine reads for these lengths
+    return remat_attn_common(a, q_bf16, xcache, acc_bf16, B, cap, d, wprep, len, out, ws, XQ_STATIC_SCRATCH_BYTES,
+                             nullptr, 0, nullptr, stream);
 }
 
 }  // extern "C"
