@@ -247,6 +247,22 @@ def main():
         del rot_caches, rot_streams
         torch.cuda.empty_cache()
 
+        # The same launch (same cache, same instruction stream) with other weight VALUES: all weights zero, and all
+        # weights one constant.  The matrix pipe's power draw depends on the bits that toggle in its operands and the
+        # GPU lowers its clock under it, so this separates what the kernel's structure allows from what the data costs.
+        dep = {}
+        for tag, fillv in (("all_zero", 0.0), ("all_equal", 2.0 ** -6)):
+            wc = torch.full((d, Hkv * hd), fillv, dtype=torch.bfloat16, device=dev)
+            wpc = xq.xq_prepare_weights(attn, d, G, bits, wc, wc)
+            t_w = timed(lambda: xq.xq_remat_attn_decode(attn, q, wpc, lens, xcache=cache, out=out, workspace=ws), n=20, warm=10)
+            dep[tag + "_ms"] = t_w
+            dep[tag + "_frac_mfma_peak"] = flops / t_w / 1e9 / PEAK_BF16_TFLOPS
+            del wc, wpc
+        dep["workload_weights_ms"] = remat_ms
+        dep["note"] = ("xq_remat_attn_decode on c2 with the workload's N(0, 1/d) weights against the same call with constant "
+                       "weights: identical work and instruction stream, the time follows the operand data (clock under load)")
+        extra["remat_attn_c2_weight_data_dependence"] = dep
+
         # config 4 (GQA, B=16, L=8192, 2-bit, group 64): the naive X cache, and the latent cache of Sec. 3.3.1
         w4 = xi.C4
         a4 = xq.XQAttn(w4.Hq, w4.Hkv, w4.hd, w4.hd ** -0.5)

@@ -116,6 +116,11 @@ xq_status_t xq_cl_accumulate(uint16_t *acc_bf16, const xq_cache_t *src, const in
  *   src_bits 2, 3 or 4: prepared for an X cache of that bit width and group size
  *            `group`; 16: prepared for the bf16 cross-layer accumulator (group ignored)
  *   out      dev, at least xq_prepared_weights_bytes(...) bytes
+ * Range of the weights: any finite bf16 values.  For src_bits 2, 3, 4 the stream holds fp16 numbers;
+ * each KV head's [Wk_h | Wv_h] is scaled by one power of two so that its largest entry sits at the top
+ * of the fp16 range (the kernels take the factor out again, exactly), so a layer of uniformly tiny or
+ * large weights loses nothing; within one head, entries more than 2^-29 below the head's largest are
+ * rounded at 2^-40 of the largest.
  * xq_prepared_weights_bytes returns 0 for an unsupported combination.
  */
 size_t      xq_prepared_weights_bytes(const xq_attn_t *a, int32_t d, int32_t group, int32_t src_bits);

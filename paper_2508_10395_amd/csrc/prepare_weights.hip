@@ -4,8 +4,11 @@
 // remat_layout.hpp and appends the per-group column sums the kernel needs to apply the
 // zero-points.  For coded sources the stream holds fp16 (the codes are fp16 operands, see
 // unpack.hpp): a bf16 weight times a power of two is exact in fp16 unless it falls below
-// 2^-14 (then it is rounded to the fp16 subnormal grid, an error of at most 2^-25) or above
-// 65504 (clamped; weights that large are outside the supported range).
+// 2^-14 (then it is rounded to the fp16 subnormal grid) or above 65504.  Neither happens to a weight that
+// matters: each head's stream is first normalised by a power of two, 2^shift[h], that puts the head's
+// largest entry just below 2^15 (shift_kernel), so only entries 2^-29 below the largest reach the
+// subnormal grid, with an error of at most 2^-40 of the largest.  The kernels undo the shift in their
+// final scale.  Dense (bf16) streams need none: shift = 0.
 #include "common.hpp"
 #include "remat_layout.hpp"
 #include "unpack.hpp"
@@ -17,6 +20,7 @@ struct PrepArgs {
     const uint16_t* Wv;
     uint8_t* out;
     float* colsum;   // [Hkv][ng][256]: per-group sums of the weight rows
+    int32_t* shift;  // [Hkv]: exponent shift of the head's fp16 stream (0 for bf16 streams)
     int d, G, bits, Hkv, ncols;
     int head_stride; // columns between consecutive heads in Wk / Wv (128; 256 when a "head" is a pair of heads)
     int transposed;  // the matrices are given transposed ([column][d], as the projection matrices are): d = row length
@@ -31,6 +35,35 @@ __device__ __forceinline__ float wval(const PrepArgs& a, int h, int c, int n)
     const uint16_t* W = n < 128 ? a.Wk : a.Wv;
     const long long col = h * a.head_stride + (n & 127);
     return bf16_bits_to_f32(a.transposed ? W[col * a.d + c] : W[(long long)c * a.ncols + col]);
+}
+
+// shift[h] = 12 - ceil(log2(max |w|)) over the head's d x 256 entries: max |w| 2^shift <= 2^12, and with the
+// largest per-slot factor of the unpack table (2^3) the stream's largest entry is at most 2^15.
+__global__ __launch_bounds__(256) void shift_kernel(PrepArgs a)
+{
+    __shared__ uint32_t red[256];
+    const int h = blockIdx.x, n = threadIdx.x;
+    uint32_t mx = 0;                                      // |w| as bf16 bits: ordered as integers
+    for (int c = 0; c < a.d; ++c) {
+        const uint16_t* W = n < 128 ? a.Wk : a.Wv;
+        const long long col = h * a.head_stride + (n & 127);
+        mx = max(mx, (uint32_t)(a.transposed ? W[col * a.d + c] : W[(long long)c * a.ncols + col]) & 0x7FFFu);
+    }
+    red[n] = mx;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+        if (n < st) red[n] = max(red[n], red[n + st]);
+        __syncthreads();
+    }
+    if (n == 0) {
+        int sh = 0;
+        if (red[0]) {
+            const int e = (int)(red[0] >> 7) - 127;       // max = m 2^e, 1 <= m < 2 (bf16 subnormals: e = -127, m < 1)
+            const int ceil_log2 = (red[0] & 0x7Fu) ? e + 1 : e;
+            sh = min(max(12 - ceil_log2, -60), 60);
+        }
+        a.shift[h] = sh;
+    }
 }
 
 __global__ __launch_bounds__(256) void colsum_kernel(PrepArgs a)
@@ -49,6 +82,7 @@ __global__ __launch_bounds__(256) void pack_main_kernel(PrepArgs a)
     const bool dense = a.bits == 16;
     const int ksg_n = a.G / 16;
     const int n_ksteps = a.n_main_slabs * SLAB_KSTEPS;
+    const int head_shift = dense ? 0 : a.shift[h];
     for (int f = threadIdx.x; f < SLAB_KSTEPS * 8 * 64; f += blockDim.x) {
         const int lane = f & 63, nb = (f >> 6) & 7, ks = f >> 9;
         const int half = lane >> 5, n = nb * 32 + (lane & 31);
@@ -67,7 +101,7 @@ __global__ __launch_bounds__(256) void pack_main_kernel(PrepArgs a)
                 const int u = ksg >> 2, j = ksg & 3;
                 const int p = a.tab.code_of_slot[j][i];
                 c = cs_ * 128 + gi * a.G + half * (a.G / 2) + u * 32 + p;
-                e = a.tab.wexp_of_code[p];
+                e = a.tab.wexp_of_code[p] + head_shift;
             }
             const float wv = ldexpf(wval(a, h, c, n), e);          // exact: power-of-two scaling
             if (dense) {
@@ -143,10 +177,12 @@ hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const u
     a.Wk = Wk; a.Wv = Wv;
     a.out = static_cast<uint8_t*>(out);
     a.colsum = reinterpret_cast<float*>(a.out + L.stream_bytes);
+    a.shift = reinterpret_cast<int32_t*>(a.out + L.stream_bytes + L.colsum_bytes);
     a.d = L.d; a.G = L.G; a.bits = L.bits; a.Hkv = L.Hkv; a.ncols = ncols;
     a.n_main_slabs = L.n_main_slabs; a.ng = L.ng; a.ng_pad = L.ng_pad; a.n_corr_slabs = L.n_corr_slabs;
     a.head_bytes = (long long)L.head_bytes;
     if (!unpack_table_for(L.bits, &a.tab)) return hipErrorInvalidValue;
+    if (L.bits != 16) shift_kernel<<<dim3(L.Hkv), dim3(256), 0, s>>>(a);
     pack_main_kernel<<<dim3(L.n_main_slabs, L.Hkv), dim3(256), 0, s>>>(a);
     if (L.bits != 16) {
         colsum_kernel<<<dim3(L.ng, L.Hkv), dim3(256), 0, s>>>(a);

@@ -82,6 +82,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     const int lane = c.lane, wave = c.wave, half = c.half, tl = c.tl;
 
     const int n_corr_slabs = (p.n_corr_ksteps + SLAB_KSTEPS - 1) / SLAB_KSTEPS;
+    const int head_shift = p.head_shift[c.hk];         // the head's stream holds its weights times 2^head_shift
     const uint8_t* wsrc = p.wprep + (long long)c.hk * p.head_bytes + wave * 1024;   // this wave's DMA share
     const uint32_t dma_voff = (uint32_t)lane * 16u;
     const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds;
@@ -314,7 +315,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         if constexpr (!PC) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const float r0 = __builtin_amdgcn_rcpf(E[floordiv_c(j - 8, KSG) + GPS]);
+                const float r0 = ldexpf(__builtin_amdgcn_rcpf(E[floordiv_c(j - 8, KSG) + GPS]), head_shift);
                 acc[j] *= r0;
             }
 #pragma unroll
@@ -457,7 +458,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         // K | V = accumulator * 2^(E_blk + bits - 1) + z_blk [Wk_h | Wv_h]; waves past len take the last block's
         const int blk = min((c.tile * TILE_TOKENS + wave * CHUNK_TOKENS) / p.pc_block, (c.len - 1) / p.pc_block);
         const long long brow = (long long)c.b * p.pc_blocks_cap + blk;
-        const float fs = p.pc_fscale[brow];
+        const float fs = ldexpf(p.pc_fscale[brow], -head_shift);
         const float* zw = p.pc_zw + (brow * p.grid_heads + c.hk) * 256 + half * 4;
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb)
@@ -472,7 +473,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     } else {
         // every block ends in the slab it started in; leave its group's scale: the accumulator is K | V
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] *= E[GPS + j / KSG];
+        for (int j = 0; j < 8; ++j) acc[j] *= ldexpf(E[GPS + j / KSG], -head_shift);
     }
     if constexpr (MODE == MODE_SCORES || MODE == MODE_SCORES_PC) scores_epilogue(p, c, acc);
     else if constexpr (MODE == MODE_WEIGHTED_SUM) weighted_sum_epilogue(p, c, acc, lds);

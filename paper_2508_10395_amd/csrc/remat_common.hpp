@@ -49,6 +49,7 @@ struct RematParams {
     const uint16_t* zero;
     const uint16_t* acc;     // dense source
     const uint8_t* wprep;
+    const int32_t* head_shift;   // coded source: per-head exponent shift of the fp16 stream (taken out with the final scale)
     const uint16_t* eT;      // coded source: effective scales [B][tiles][ng (+1 pad)][256], bf16
     float* part_o;           // [B][Hq][chunks_per_seq][128]  (prefill: [B][Tq][Hq][tiles_per_seq][128])
     float* part_ml;          // [B][Hq][chunks_per_seq][2]

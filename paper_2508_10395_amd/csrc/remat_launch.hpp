@@ -4,6 +4,12 @@
 
 namespace xq {
 
+// the per-head shift array of a prepared stream (after the slabs and the column sums)
+static const int32_t* stream_shifts(const void* wprep, const WPrepLayout& L)
+{
+    return reinterpret_cast<const int32_t*>(static_cast<const uint8_t*>(wprep) + L.stream_bytes + L.colsum_bytes);
+}
+
 template <typename K>
 static hipError_t launch_with_lds(K kernel, int lds_bytes, const RematParams& p, int grid, hipStream_t s)
 {
@@ -94,6 +100,7 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
     p.zero = xc ? xc->zero : nullptr;
     p.acc = acc;
     p.wprep = static_cast<const uint8_t*>(wprep);
+    p.head_shift = stream_shifts(wprep, L);
     p.d = d; p.row_d = d; p.grid_heads = p.Hkv;
     p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
     p.ng_row = L.ng;
@@ -156,6 +163,7 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
     p.zero = xc ? xc->zero : nullptr;
     p.acc = acc;
     p.wprep = static_cast<const uint8_t*>(wprep);
+    p.head_shift = stream_shifts(wprep, L);
     p.d = d; p.row_d = d; p.grid_heads = p.Hkv;
     p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
     p.ng_row = L.ng;
@@ -213,11 +221,13 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
     // pass 1: keys
     p.codes = xc->codes; p.zero = xc->zero; p.eT = eT_k;
     p.wprep = static_cast<const uint8_t*>(wprep);
+    p.head_shift = stream_shifts(p.wprep, L);
     e = launch_coded<MODE_SCORES>(bits, G, p, grid, s);
     if (e != hipSuccess) return e;
     // pass 2: values; its epilogue merges the eight chunks of a tile: one partial per tile
     p.codes = xc->codes + (size_t)r * bits / 8; p.zero = xc->zero + L.ng; p.eT = eT_v;
     p.wprep = static_cast<const uint8_t*>(wprep) + L.total_bytes;
+    p.head_shift = stream_shifts(p.wprep, L);
     p.chunks_per_seq = p.tiles_per_seq;
     e = launch_coded<MODE_WEIGHTED_SUM>(bits, G, p, grid, s);
     if (e != hipSuccess) return e;
@@ -247,6 +257,7 @@ hipError_t run_cl_accumulate_latent(uint16_t* acc, const xq_cache_t* xc, int d, 
     p.len = len;
     p.codes = xc->codes; p.zero = xc->zero;
     p.wprep = static_cast<const uint8_t*>(uprep);
+    p.head_shift = stream_shifts(uprep, L);
     p.d = n_lat; p.row_d = n_lat;
     p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
     p.ng_row = L.ng;
@@ -437,6 +448,7 @@ hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const
         m.codes = xc->codes; m.eT = reinterpret_cast<const uint16_t*>(img);
         m.cap = cap; m.len = len_coded; m.tiles_per_seq = tiles_coded;
         m.wprep = static_cast<const uint8_t*>(wprep_coded);
+        m.head_shift = stream_shifts(wprep_coded, Lc);
         m.n_main_slabs = Lc.n_main_slabs; m.n_corr_ksteps = Lc.n_corr_ksteps; m.ng = Lc.ng; m.ng_pad = Lc.ng_pad; m.ng_row = Lc.ng;
         m.head_bytes = (long long)Lc.head_bytes;
         m.pc_fscale = fscale; m.pc_zw = zw; m.pc_block = blockT; m.pc_blocks_cap = (int)blocks_ws;
@@ -585,6 +597,7 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
         m.codes = kc->codes; m.eT = reinterpret_cast<const uint16_t*>(img);
         m.cap = kc->cap; m.len = len_coded; m.tiles_per_seq = tiles_coded;
         m.wprep = static_cast<const uint8_t*>(wk_coded);
+        m.head_shift = stream_shifts(wk_coded, Lk);
         m.n_main_slabs = Lk.n_main_slabs; m.n_corr_ksteps = Lk.n_corr_ksteps; m.ng = Lk.ng; m.ng_pad = Lk.ng_pad; m.ng_row = Lk.ng;
         m.head_bytes = (long long)Lk.head_bytes;
         m.pc_fscale = fscale; m.pc_zw = zw; m.pc_block = blockT; m.pc_blocks_cap = (int)blocks_ws;
@@ -619,6 +632,7 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
     v.codes = vc->codes; v.zero = vc->zero; v.eT = eT_v;
     v.cap = vc->cap; v.len = len; v.tiles_per_seq = tiles_all;
     v.wprep = static_cast<const uint8_t*>(wv_coded);
+    v.head_shift = stream_shifts(wv_coded, Lv);
     v.n_main_slabs = Lv.n_main_slabs; v.n_corr_ksteps = Lv.n_corr_ksteps; v.ng = Lv.ng; v.ng_pad = Lv.ng_pad; v.ng_row = Lv.ng;
     v.head_bytes = (long long)Lv.head_bytes;
     v.chunks_per_seq = tiles_all;                        // one partial per tile

@@ -17,7 +17,11 @@
 //                  inside the unit;
 //                  channel = 128 s' + G gi + (G/2) half + 32 u + code_of_slot[j][i],
 //                  value scaled by 2^wexp_of_code (see unpack.hpp).
-// Main slabs hold bf16 for the dense source and fp16 for coded sources.
+// Main slabs hold bf16 for the dense source and fp16 for coded sources.  fp16 has five exponent bits, so a
+// coded stream is normalised per head: every weight of head h is multiplied by 2^shift[h], chosen so
+// that the head's largest entry sits at the top of the fp16 range (exact: a power of two; entries
+// more than 2^-29 below the largest are then still normal numbers).  shift[Hkv] (int32) follows the
+// column sums; the kernel takes 2^-shift[h] out again with its final scale.
 // Correction slabs (coded sources only, bf16) hold, for contraction index
 // kappa = 16 kk + 8 half + i, term = kappa / ng_pad, group g = kappa % ng_pad:
 //   term 0,1,2: bf16 hi, mid, lo parts of S_g[n] = sum of the group's weight rows
@@ -38,7 +42,7 @@ constexpr int CHUNK_TOKENS = 32;     // tokens per wave = one softmax partial
 struct WPrepLayout {
     int d, G, bits, Hkv;
     int n_main_slabs, ng, ng_pad, n_corr_ksteps, n_corr_slabs;
-    size_t head_bytes, stream_bytes, colsum_bytes, total_bytes;
+    size_t head_bytes, stream_bytes, colsum_bytes, shift_bytes, total_bytes;
 };
 
 inline WPrepLayout make_wprep_layout(int d, int G, int bits, int Hkv)
@@ -57,7 +61,8 @@ inline WPrepLayout make_wprep_layout(int d, int G, int bits, int Hkv)
     L.head_bytes = (size_t)(L.n_main_slabs + L.n_corr_slabs) * SLAB_BYTES;
     L.stream_bytes = L.head_bytes * Hkv;
     L.colsum_bytes = (size_t)Hkv * L.ng * 256 * sizeof(float);
-    L.total_bytes = L.stream_bytes + L.colsum_bytes;
+    L.shift_bytes = bits == 16 ? 0 : ((size_t)Hkv * sizeof(int32_t) + 15) / 16 * 16;   // per-head exponent shift of the fp16 stream
+    L.total_bytes = L.stream_bytes + L.colsum_bytes + L.shift_bytes;
     return L;
 }
 

@@ -33,11 +33,16 @@ def _check(got, ref, what=""):
     return float(normwise.max())
 
 
-def _run_xquant(xq, w, bits, G, lens, pairs=None, x_bits=None, cap=None):
+def _run_xquant(xq, w, bits, G, lens, pairs=None, x_bits=None, cap=None, weight_exp=0, head_exps=None):
     """Quantise X and attend with the GPU library; the oracle quantises the same X itself and
-    attends over its own cache.  The two caches must agree byte for byte."""
+    attends over its own cache.  The two caches must agree byte for byte.  weight_exp scales both
+    weight matrices by 2^weight_exp (exact in bf16); head_exps gives every KV head its own exponent."""
     x = xi.gen_x(w) if x_bits is None else x_bits
     wk, wv = xi.gen_weights(w)
+    if weight_exp or head_exps is not None:
+        e = np.full(w.Hkv, weight_exp) if head_exps is None else np.asarray(head_exps)
+        col = np.repeat(np.exp2(e.astype(np.float64)), w.hd).astype(np.float32)
+        wk, wv = xi.to_bf16_bits(bf(wk) * col), xi.to_bf16_bits(bf(wv) * col)
     q = xi.gen_q(w)
     cap = w.L if cap is None else cap
     cache = xq.alloc_cache(w.B, cap, w.d, G, bits)
@@ -97,6 +102,24 @@ def test_constant_groups_and_wide_scale_range(xq):
     x[0, 7, :] = -1.25                           # a fully constant token
     _run_xquant(xq, w, 3, 128, [256], x_bits=xi.to_bf16_bits(x))
     _run_xquant(xq, w, 4, 64, [256], x_bits=xi.to_bf16_bits(x))
+
+
+@pytest.mark.parametrize("weight_exp", [-12, 6, -30])
+@pytest.mark.parametrize("bits,G", [(3, 128), (2, 64), (4, 128)])
+def test_weight_magnitude_does_not_matter(xq, weight_exp, bits, G):
+    """Weights 2^-12, 2^6 and 2^-30 times the N(0, 1/d) of the workloads: the fp16 weight stream is normalised
+    per head by a power of two, so the same relative accuracy holds (without it, 2^-12 pushes most weights into
+    fp16's subnormal range and 2^-30 flushes all of them to zero)."""
+    w = xi.C2.scaled(B=2, L=300, d=512, Hq=4, Hkv=4, n_outlier=5)
+    _run_xquant(xq, w, bits, G, lens=[300, 77], weight_exp=weight_exp)
+
+
+def test_heads_of_very_different_magnitude(xq):
+    """Every KV head has its own normalisation: heads 2^20 apart in one layer; GQA heads share theirs."""
+    w = xi.C2.scaled(B=2, L=300, d=512, Hq=4, Hkv=4, n_outlier=5)
+    _run_xquant(xq, w, 3, 128, lens=[300, 77], head_exps=[-14, 6, 0, -3])
+    g = xi.C4.scaled(B=2, L=300, d=768, Hq=8, Hkv=2)
+    _run_xquant(xq, g, 2, 64, lens=[300, 130], head_exps=[5, -9])
 
 
 def test_dense_accumulator_source(xq):
