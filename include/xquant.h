@@ -113,8 +113,9 @@ xq_status_t xq_cl_accumulate(uint16_t *acc_bf16, const xq_cache_t *src, const in
  * fragment order the rematerialisation kernel streams, together with per-group
  * column sums used to apply the zero-points exactly.
  *   Wk, Wv   dev [d][n_kv_heads*head_dim] bf16, row-major
- *   src_bits 2, 3 or 4: prepared for an X cache of that bit width and group size
- *            `group`; 16: prepared for the bf16 cross-layer accumulator (group ignored)
+ *   src_bits 2, 3, 4 or 8: prepared for an X cache of that bit width and group size
+ *            `group`; 16: prepared for the bf16 cross-layer accumulator (group ignored).
+ *            (8: for xq_remat_attn_decode / _rope / _prefill over a per-token cache only.)
  *   out      dev, at least xq_prepared_weights_bytes(...) bytes
  * Range of the weights: any finite bf16 values.  For src_bits 2, 3, 4 the stream holds fp16 numbers;
  * each KV head's [Wk_h | Wv_h] is scaled by one power of two so that its largest entry sits at the top
@@ -147,6 +148,10 @@ xq_status_t xq_prepare_weights(const xq_attn_t *a, int32_t d, int32_t group, int
  * B is taken from xcache->B, or passed in `B` when acc_bf16 is the source.
  * xq_remat_attn_workspace_bytes: max_len = max_b len[b]; d and group are those of the X cache,
  * group = 0 when the accumulator is the source.  Returns 0 for an invalid combination.
+ * 8-bit caches (the XQuant-8bit rows of Table 1) are served too: the kernel walks the two nibbles of a
+ * code as two 4-bit codes (the high one against 16 times the weight row; x^ = (16 hi + lo) scale + zero
+ * exactly), at twice the matrix work of a 4-bit cache.  Size the workspace for such a cache with
+ * d = 2 * fmt.d and group = 128 (likewise xq_remat_attn_prefill_workspace_bytes).
  */
 size_t      xq_remat_attn_workspace_bytes(const xq_attn_t *a, int32_t B, int32_t max_len, int32_t d,
                                           int32_t group);

@@ -292,6 +292,14 @@ def xq_prepare_weights(attn, d, group, src_bits, Wk, Wv, out=None):
     return out
 
 
+def _walk_of(xcache, d):
+    """(d, group) to size the attention workspace with: the cache's own, except that an 8-bit cache is walked as
+    4-bit groups of 128 nibbles over twice the width; group 0 for the accumulator source."""
+    if xcache is None:
+        return d, 0
+    return (2 * xcache.d, 128) if xcache.bits == 8 else (xcache.d, xcache.group)
+
+
 def xq_remat_attn_workspace_bytes(attn, B, max_len, d, group):
     """group = the X cache's group size, or 0 when the bf16 accumulator is the source."""
     a = attn.c_struct()
@@ -314,8 +322,7 @@ def xq_remat_attn_decode(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=Non
         cptr = None
     lens = [int(v) for v in lens]
     a = attn.c_struct()
-    need = xq_remat_attn_workspace_bytes(attn, B, max(lens) if lens else 1, d,
-                                         xcache.group if xcache is not None else 0)
+    need = xq_remat_attn_workspace_bytes(attn, B, max(lens) if lens else 1, *_walk_of(xcache, d))
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q_bf16.device)
     if out is None:
@@ -503,8 +510,7 @@ def xq_remat_attn_prefill(attn, q_bf16, wprep, lens, *, xcache=None, acc_bf16=No
         cptr = None
     lens = [int(v) for v in lens]
     a = attn.c_struct()
-    need = xq_remat_attn_prefill_workspace_bytes(attn, B, T, max(lens) if lens else 1, d,
-                                                 xcache.group if xcache is not None else 0)
+    need = xq_remat_attn_prefill_workspace_bytes(attn, B, T, max(lens) if lens else 1, *_walk_of(xcache, d))
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q_bf16.device)
     if out is None:

@@ -13,7 +13,7 @@ hipError_t run_quantize_append(const xq_cache_t* c, const uint16_t* x, const uin
 hipError_t run_cl_accumulate(uint16_t* acc, const xq_cache_t* c, const BatchI32& len, int max_len,
                              bool init, hipStream_t s);
 hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, int ncols,
-                               int head_stride, void* out, hipStream_t s, bool transposed = false);
+                               int head_stride, void* out, hipStream_t s, bool transposed = false, bool nibbles = false);
 hipError_t run_project_rows_dense(const uint16_t* x, long long M, int d, int n_lat, const void* proj, uint16_t* out,
                                   hipStream_t s);
 hipError_t run_project_delta_rows_dense(const uint16_t* x, const uint16_t* acc, int B, int T, int cap, const BatchI32& start,
@@ -87,6 +87,13 @@ static bool wprep_combo_ok(int d, int group, int src_bits)
     if (d <= 0 || d % 128 != 0) return false;
     if (src_bits == 16) return true;
     return (src_bits == 2 || src_bits == 3 || src_bits == 4) && (group == 64 || group == 128);
+}
+
+// ... plus 8-bit per-token caches, which only the plain decode / prefill attention calls walk
+static bool wprep_cache_combo_ok(int d, int group, int src_bits)
+{
+    if (src_bits == 8) return d > 0 && d % 128 == 0 && (group == 64 || group == 128);
+    return wprep_combo_ok(d, group, src_bits);
 }
 
 }  // namespace xq
@@ -170,8 +177,8 @@ xq_status_t xq_cl_accumulate(uint16_t* acc_bf16, const xq_cache_t* src, const in
 
 size_t xq_prepared_weights_bytes(const xq_attn_t* a, int32_t d, int32_t group, int32_t src_bits)
 {
-    if (check_attn(a) != XQ_OK || !wprep_combo_ok(d, group, src_bits)) return 0;
-    return make_wprep_layout(d, src_bits == 16 ? 128 : group, src_bits, a->n_kv_heads).total_bytes;
+    if (check_attn(a) != XQ_OK || !wprep_cache_combo_ok(d, group, src_bits)) return 0;
+    return make_wprep_layout_for_cache(d, group, src_bits, a->n_kv_heads).total_bytes;
 }
 
 xq_status_t xq_prepare_weights(const xq_attn_t* a, int32_t d, int32_t group, int32_t src_bits,
@@ -182,10 +189,11 @@ xq_status_t xq_prepare_weights(const xq_attn_t* a, int32_t d, int32_t group, int
     if (st != XQ_OK) return st;
     if (!Wk || !Wv || !out || !aligned16(Wk) || !aligned16(Wv) || !aligned16(out)) return XQ_ERR_INVALID_ARG;
     if (d <= 0) return XQ_ERR_INVALID_ARG;
-    if (!wprep_combo_ok(d, group, src_bits)) return XQ_ERR_UNSUPPORTED;
-    const WPrepLayout L = make_wprep_layout(d, src_bits == 16 ? 128 : group, src_bits, a->n_kv_heads);
+    if (!wprep_cache_combo_ok(d, group, src_bits)) return XQ_ERR_UNSUPPORTED;
+    const WPrepLayout L = make_wprep_layout_for_cache(d, group, src_bits, a->n_kv_heads);
     if (out_bytes < L.total_bytes) return XQ_ERR_WORKSPACE;
-    hipError_t e = run_prepare_weights(L, Wk, Wv, a->n_kv_heads * 128, 128, out, static_cast<hipStream_t>(stream));
+    hipError_t e = run_prepare_weights(L, Wk, Wv, a->n_kv_heads * 128, 128, out, static_cast<hipStream_t>(stream), false,
+                                       src_bits == 8);
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;
 }
 
@@ -265,7 +273,6 @@ static xq_status_t remat_attn_common(const xq_attn_t* a, const uint16_t* q_bf16,
     if (xcache) {
         st = check_cache(xcache);
         if (st != XQ_OK) return st;
-        if (xcache->fmt.bits == 8) return XQ_ERR_UNSUPPORTED;
         B = xcache->B; cap = xcache->cap; d = xcache->fmt.d;
     } else {
         if (!aligned16(acc_bf16) || B < 1 || cap < 1 || d <= 0) return XQ_ERR_INVALID_ARG;
@@ -280,8 +287,11 @@ static xq_status_t remat_attn_common(const xq_attn_t* a, const uint16_t* q_bf16,
         if (len[b] > max_len) max_len = len[b];
     }
     if (T > 0 && (long long)B * T > 65535) return XQ_ERR_UNSUPPORTED;
-    const size_t need = T > 0 ? xq_remat_attn_prefill_workspace_bytes(a, B, T, max_len, d, xcache ? xcache->fmt.group : 0)
-                              : xq_remat_attn_workspace_bytes(a, B, max_len, d, xcache ? xcache->fmt.group : 0);
+    // (an 8-bit cache is walked as 4-bit groups of 128 nibbles over twice the width)
+    const bool nib = xcache && xcache->fmt.bits == 8;
+    const int wd = nib ? 2 * d : d, wg = nib ? 128 : xcache ? xcache->fmt.group : 0;
+    const size_t need = T > 0 ? xq_remat_attn_prefill_workspace_bytes(a, B, T, max_len, wd, wg)
+                              : xq_remat_attn_workspace_bytes(a, B, max_len, wd, wg);
     if (need == 0) return XQ_ERR_UNSUPPORTED;
     if (workspace_bytes < need) return XQ_ERR_WORKSPACE;
     BatchI32 pv{};
@@ -696,7 +706,8 @@ xq_status_t xq_remat_attn_decode_static(const xq_attn_t* a, const uint16_t* q_bf
         if (len[b] < 1 || len[b] > cap) return XQ_ERR_INVALID_ARG;
         if (len[b] > max_len) max_len = len[b];
     }
-    const size_t need = xq_remat_attn_workspace_bytes(a, B, max_len, d, xcache ? xcache->fmt.group : 0);
+    const bool nib = xcache && xcache->fmt.bits == 8;
+    const size_t need = xq_remat_attn_workspace_bytes(a, B, max_len, nib ? 2 * d : d, nib ? 128 : xcache ? xcache->fmt.group : 0);
     if (need == 0) return XQ_ERR_UNSUPPORTED;
     if (need > (size_t)XQ_STATIC_SCRATCH_BYTES) return XQ_ERR_WORKSPACE;     // beyond the built-in buffer
     void* ws = nullptr;

@@ -24,6 +24,8 @@ struct PrepArgs {
     int d, G, bits, Hkv, ncols;
     int head_stride; // columns between consecutive heads in Wk / Wv (128; 256 when a "head" is a pair of heads)
     int transposed;  // the matrices are given transposed ([column][d], as the projection matrices are): d = row length
+    int nibbles;     // stream for an 8-bit cache read as 4-bit codes: channel c stands for nibble c & 1 of code c >> 1,
+                     //   i.e. weight row c >> 1 times 16^(c & 1); d counts nibbles, the matrices have d / 2 rows
     int n_main_slabs, ng, ng_pad, n_corr_slabs;
     long long head_bytes;
     UnpackTable tab;
@@ -34,6 +36,11 @@ __device__ __forceinline__ float wval(const PrepArgs& a, int h, int c, int n)
 {
     const uint16_t* W = n < 128 ? a.Wk : a.Wv;
     const long long col = h * a.head_stride + (n & 127);
+    if (a.nibbles) {
+        const int row = c >> 1, rows = a.d >> 1;
+        const float w = bf16_bits_to_f32(a.transposed ? W[col * rows + row] : W[(long long)row * a.ncols + col]);
+        return (c & 1) ? 16.0f * w : w;
+    }
     return bf16_bits_to_f32(a.transposed ? W[col * a.d + c] : W[(long long)c * a.ncols + col]);
 }
 
@@ -43,12 +50,8 @@ __global__ __launch_bounds__(256) void shift_kernel(PrepArgs a)
 {
     __shared__ uint32_t red[256];
     const int h = blockIdx.x, n = threadIdx.x;
-    uint32_t mx = 0;                                      // |w| as bf16 bits: ordered as integers
-    for (int c = 0; c < a.d; ++c) {
-        const uint16_t* W = n < 128 ? a.Wk : a.Wv;
-        const long long col = h * a.head_stride + (n & 127);
-        mx = max(mx, (uint32_t)(a.transposed ? W[col * a.d + c] : W[(long long)c * a.ncols + col]) & 0x7FFFu);
-    }
+    uint32_t mx = 0;                                      // |w| as fp32 bits: ordered as integers
+    for (int c = 0; c < a.d; ++c) mx = max(mx, __float_as_uint(wval(a, h, c, n)) & 0x7FFFFFFFu);
     red[n] = mx;
     __syncthreads();
     for (int st = 128; st > 0; st >>= 1) {
@@ -58,8 +61,8 @@ __global__ __launch_bounds__(256) void shift_kernel(PrepArgs a)
     if (n == 0) {
         int sh = 0;
         if (red[0]) {
-            const int e = (int)(red[0] >> 7) - 127;       // max = m 2^e, 1 <= m < 2 (bf16 subnormals: e = -127, m < 1)
-            const int ceil_log2 = (red[0] & 0x7Fu) ? e + 1 : e;
+            const int e = (int)(red[0] >> 23) - 127;      // max = m 2^e, 1 <= m < 2 (subnormals: e = -127, m < 1)
+            const int ceil_log2 = (red[0] & 0x7FFFFFu) ? e + 1 : e;
             sh = min(max(12 - ceil_log2, -60), 60);
         }
         a.shift[h] = sh;
@@ -71,7 +74,8 @@ __global__ __launch_bounds__(256) void colsum_kernel(PrepArgs a)
     const int n = threadIdx.x;
     const int g = blockIdx.x, h = blockIdx.y;
     float s = 0.0f;
-    for (int k = 0; k < a.G; ++k) s += wval(a, h, g * a.G + k, n);
+    // (nibble streams: the zero-point of a code multiplies its weight row once: the even channels)
+    for (int k = 0; k < a.G; k += a.nibbles ? 2 : 1) s += wval(a, h, g * a.G + k, n);
     a.colsum[((long long)h * a.ng + g) * 256 + n] = s;
 }
 
@@ -169,9 +173,10 @@ bool unpack_table_for(int bits, UnpackTable* t)
 
 // Wk / Wv: [d][ncols] row-major; head h takes columns [h * head_stride, +128) of each
 hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const uint16_t* Wv, int ncols,
-                               int head_stride, void* out, hipStream_t s, bool transposed)
+                               int head_stride, void* out, hipStream_t s, bool transposed, bool nibbles)
 {
     PrepArgs a{};
+    a.nibbles = nibbles ? 1 : 0;
     a.head_stride = head_stride;
     a.transposed = transposed ? 1 : 0;
     a.Wk = Wk; a.Wv = Wv;

@@ -204,7 +204,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     // first thing, so their latency hides behind the first weight DMA.  The codes and scales of the
     // slab that cyclically precedes the first one arrive meanwhile: the lagging column blocks start
     // inside it (see phase 2).
-    const bool vec_meta = (p.ng & 7) == 0 && (p.ng_row & 7) == 0 && ((size_t)zbase & 15) == 0;
+    const bool vec_meta = (p.ng & 7) == 0 && (p.ng_row & 7) == 0 && ((size_t)zbase & 15) == 0 && p.meta_shift == 0;
     auto load_meta = [&](int kk) -> uint4 {
         const int kappa0 = kk * 16 + half * 8;
         const int term = kappa0 / p.ng_pad, g0 = kappa0 % p.ng_pad;
@@ -218,7 +218,7 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const int g = g0 + i;
-                    const uint32_t x = mbase[moff + min(g, p.ng - 1)];
+                    const uint32_t x = mbase[moff + (min(g, p.ng - 1) >> p.meta_shift)];
                     h[i] = g < p.ng ? x : 0u;               // padding groups contribute nothing
                 }
                 v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16);
@@ -684,7 +684,8 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
 // one group are contiguous (tokens past len repeat the last row).
 __global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __restrict__ scale,
                                                               uint16_t* __restrict__ eT, int cap, int ng,
-                                                              int ng_row, int tiles_per_seq, int bits, BatchI32 len)
+                                                              int ng_row, int tiles_per_seq, int bits, BatchI32 len,
+                                                              int meta_shift = 0)
 {
     const int tile = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
     const int L = len.v[b];
@@ -692,7 +693,7 @@ __global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __
     const long long row = (long long)b * cap + min(tile * TILE_TOKENS + t, L - 1);
     uint16_t* dst = eT + ((long long)b * tiles_per_seq + tile) * (long long)(ng + 1) * TILE_TOKENS + t;
     for (int g = 0; g < ng; ++g) {
-        const uint32_t sb = scale[row * ng_row + g];
+        const uint32_t sb = scale[row * ng_row + (g >> meta_shift)];
         const uint32_t e = sb ? sb + ((uint32_t)(bits + F16_SUBNORMAL_EXP - F16_MANT_BITS) << 7) : 0x3F80u;
         dst[(long long)g * TILE_TOKENS] = (uint16_t)e;
     }

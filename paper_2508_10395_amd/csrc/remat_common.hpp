@@ -55,6 +55,8 @@ struct RematParams {
     float* part_ml;          // [B][Hq][chunks_per_seq][2]
     int B, cap, d, Hq, Hkv;
     int row_d, ng_row;       // coded source: channels / groups per cache row (>= d, ng when a sub-range is contracted)
+    int meta_shift;          // coded source: group g of the walk takes scale and zero-point g >> meta_shift of the row
+                             //   (1 when an 8-bit cache with groups of 128 is walked as 4-bit groups of 128 nibbles)
     int grid_heads;          // heads (or head pairs) the grid is laid over
     int tile_major;          // workgroup order inside an XCD: 0 = a head's tiles one after the other, 1 = a tile's heads side by side
     float* scores;           // latent passes: q.K * scale * log2(e), [B][Hq][score_stride]

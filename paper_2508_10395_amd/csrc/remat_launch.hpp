@@ -1,6 +1,8 @@
 // Host side of the rematerialisation kernels: workspace sizes, kernel parameters, launches.  Included at the
 // end of remat_attn.hip (the kernels are templates of that translation unit).
 #pragma once
+#include <mutex>
+#include <vector>
 
 namespace xq {
 
@@ -10,16 +12,33 @@ static const int32_t* stream_shifts(const void* wprep, const WPrepLayout& L)
     return reinterpret_cast<const int32_t*>(static_cast<const uint8_t*>(wprep) + L.stream_bytes + L.colsum_bytes);
 }
 
+// Kernels that use more than 64 KiB of LDS must be told so once (per device); remember which have been.
+static hipError_t allow_large_lds(const void* kernel, int lds_bytes)
+{
+    struct Done { const void* kernel; int device; int bytes; };
+    static std::mutex mu;
+    static std::vector<Done> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const Done& d : done)
+        if (d.kernel == kernel && d.device == dev && d.bytes >= lds_bytes) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e == hipSuccess) done.push_back({kernel, dev, lds_bytes});
+    return e;
+}
+
 template <typename K>
 static hipError_t launch_with_lds(K kernel, int lds_bytes, const RematParams& p, int grid, hipStream_t s)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    hipError_t e = allow_large_lds(reinterpret_cast<const void*>(kernel), lds_bytes);
     if (e != hipSuccess) return e;
     kernel<<<dim3(grid), dim3(512), lds_bytes, s>>>(p);
     return hipGetLastError();
 }
 
+// (d, group): of the walk -- for an 8-bit cache twice the hidden size and 128, see make_wprep_layout_for_cache
 size_t remat_workspace_bytes(int B, int Hq, int max_len, int d, int group, bool coded)
 {
     const size_t tiles = ((size_t)max_len + TILE_TOKENS - 1) / TILE_TOKENS;
@@ -91,9 +110,10 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
 {
     if (a->n_q_heads / a->n_kv_heads >= DECODE_MFMA_EPILOGUE_MIN_GROUP)     // same layouts and workspace at T = 1
         return run_remat_attn_prefill(a, q, 1, xc, acc, B, cap, d, wprep, len, max_len, out, ws, rope, pos0, s);
-    const int bits = xc ? xc->fmt.bits : 16;
-    const int G = xc ? xc->fmt.group : 128;
-    const WPrepLayout L = make_wprep_layout(d, G, bits, a->n_kv_heads);
+    const int cache_bits = xc ? xc->fmt.bits : 16;
+    const int bits = cache_bits == 8 ? 4 : cache_bits;                   // (an 8-bit cache is walked nibble by nibble)
+    const int G = cache_bits == 8 ? 128 : xc ? xc->fmt.group : 128;
+    const WPrepLayout L = make_wprep_layout_for_cache(d, xc ? xc->fmt.group : 128, cache_bits, a->n_kv_heads);
     RematParams p{};
     fill_common(p, a, q, B, cap, len, max_len, ws);
     p.codes = xc ? xc->codes : nullptr;
@@ -101,9 +121,10 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
     p.acc = acc;
     p.wprep = static_cast<const uint8_t*>(wprep);
     p.head_shift = stream_shifts(wprep, L);
-    p.d = d; p.row_d = d; p.grid_heads = p.Hkv;
+    p.d = L.d; p.row_d = L.d; p.grid_heads = p.Hkv;
     p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
-    p.ng_row = L.ng;
+    p.ng_row = xc ? d / xc->fmt.group : 0;
+    p.meta_shift = (cache_bits == 8 && xc->fmt.group == 128) ? 1 : 0;
     p.head_bytes = (long long)L.head_bytes;
     p.rope = rope;
     if (rope) p.pos0 = *pos0;
@@ -114,7 +135,7 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
     hipError_t e = hipErrorInvalidValue;
     if (xc) {
         scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
-            xc->scale, eT, cap, L.ng, L.ng, p.tiles_per_seq, bits, len);
+            xc->scale, eT, cap, L.ng, p.ng_row, p.tiles_per_seq, bits, len, p.meta_shift);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         e = launch_coded<MODE_ATTENTION>(bits, G, p, grid, s);
@@ -145,9 +166,10 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
                                   const BatchI32& len, int max_len, float* out, void* ws,
                                   const float* rope, const BatchI32* pos0, hipStream_t s)
 {
-    const int bits = xc ? xc->fmt.bits : 16;
-    const int G = xc ? xc->fmt.group : 128;
-    const WPrepLayout L = make_wprep_layout(d, G, bits, a->n_kv_heads);
+    const int cache_bits = xc ? xc->fmt.bits : 16;
+    const int bits = cache_bits == 8 ? 4 : cache_bits;                   // (an 8-bit cache is walked nibble by nibble)
+    const int G = cache_bits == 8 ? 128 : xc ? xc->fmt.group : 128;
+    const WPrepLayout L = make_wprep_layout_for_cache(d, xc ? xc->fmt.group : 128, cache_bits, a->n_kv_heads);
     RematParams p{};
     p.q = q; p.Tq = T;
     p.B = B; p.cap = cap; p.Hq = a->n_q_heads; p.Hkv = a->n_kv_heads;
@@ -164,9 +186,10 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
     p.acc = acc;
     p.wprep = static_cast<const uint8_t*>(wprep);
     p.head_shift = stream_shifts(wprep, L);
-    p.d = d; p.row_d = d; p.grid_heads = p.Hkv;
+    p.d = L.d; p.row_d = L.d; p.grid_heads = p.Hkv;
     p.n_main_slabs = L.n_main_slabs; p.n_corr_ksteps = L.n_corr_ksteps; p.ng = L.ng; p.ng_pad = L.ng_pad;
-    p.ng_row = L.ng;
+    p.ng_row = xc ? d / xc->fmt.group : 0;
+    p.meta_shift = (cache_bits == 8 && xc->fmt.group == 128) ? 1 : 0;
     p.head_bytes = (long long)L.head_bytes;
     p.rope = rope;
     if (rope) p.pos0 = *pos0;
@@ -174,7 +197,7 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
     hipError_t e;
     if (xc) {
         scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
-            xc->scale, const_cast<uint16_t*>(p.eT), cap, L.ng, L.ng, p.tiles_per_seq, bits, len);
+            xc->scale, const_cast<uint16_t*>(p.eT), cap, L.ng, p.ng_row, p.tiles_per_seq, bits, len, p.meta_shift);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         e = launch_coded<MODE_PREFILL>(bits, G, p, grid, s);

@@ -66,4 +66,14 @@ inline WPrepLayout make_wprep_layout(int d, int G, int bits, int Hkv)
     return L;
 }
 
+// An 8-bit per-token cache is walked as a 4-bit cache of twice the width: a code's low and high nibble are
+// two adjacent 4-bit codes of the row's bit string, the weight row of the high nibble is 16 times the code's
+// (exact), and a group of G codes is 2 G / 128 groups of 128 nibbles that share its scale and zero-point.
+// Twice the matrix work of a 4-bit cache; x^ = (16 hi + lo) scale + zero comes out exactly as for the
+// other widths.
+inline WPrepLayout make_wprep_layout_for_cache(int d, int G, int bits, int Hkv)
+{
+    return bits == 8 ? make_wprep_layout(2 * d, 128, 4, Hkv) : make_wprep_layout(d, bits == 16 ? 128 : G, bits, Hkv);
+}
+
 }  // namespace xq

@@ -78,7 +78,7 @@ def test_prefill_mha_ragged(xq, T):
     _run(xq, w, T, 3, 128, lens=[600, 257 + T // 2, T, 512], seed=T)
 
 
-@pytest.mark.parametrize("bits,G", [(2, 64), (2, 128), (4, 64), (4, 128)])
+@pytest.mark.parametrize("bits,G", [(2, 64), (2, 128), (4, 64), (4, 128), (8, 64), (8, 128)])
 def test_prefill_formats(xq, bits, G):
     w = xi.C2.scaled(B=2, L=300, d=512, Hq=4, Hkv=4, n_outlier=5)
     _run(xq, w, 7, bits, G, lens=[300, 40], seed=bits + G)

@@ -122,6 +122,21 @@ def test_heads_of_very_different_magnitude(xq):
     _run_xquant(xq, g, 2, 64, lens=[300, 130], head_exps=[5, -9])
 
 
+@pytest.mark.parametrize("G", [64, 128])
+def test_eight_bit_cache(xq, G):
+    """The XQuant-8bit setting of Table 1: an 8-bit cache is walked as 4-bit codes, two nibbles per code (group
+    128: two nibble groups share a scale and a zero-point).  Ragged lengths, several tiles, outlier channels."""
+    w = xi.C2.scaled(B=3, L=600, d=512, Hq=4, Hkv=4, n_outlier=5)
+    _run_xquant(xq, w, 8, G, lens=[600, 257, 31], cap=640)
+
+
+def test_eight_bit_config1_and_gqa(xq):
+    """Config 1's layer with an 8-bit cache (all heads), and grouped-query heads through the matrix-core epilogue."""
+    _run_xquant(xq, xi.C1, 8, 128, [xi.C1.L])
+    g = xi.C4.scaled(B=2, L=300, d=768, Hq=8, Hkv=2)
+    _run_xquant(xq, g, 8, 64, lens=[300, 130])
+
+
 def test_dense_accumulator_source(xq):
     """XQuant-CL mode: the bf16 accumulator is the source of X^."""
     w = xi.C3.scaled(B=3, L=330, d=512, Hq=4, Hkv=4)

@@ -78,7 +78,8 @@ def test_argument_errors_are_reported_before_any_launch():
     bad_ratio = B._Attn(5, 2, 128, 0.1)
     assert lib.xq_prepare_weights(C.byref(bad_hd), 256, 128, 4, x, x, x, 1 << 30, st) == UNSUPPORTED
     assert lib.xq_prepare_weights(C.byref(bad_ratio), 256, 128, 4, x, x, x, 1 << 30, st) == INVALID
-    assert lib.xq_prepare_weights(C.byref(a), 256, 128, 8, x, x, x, 1 << 30, st) == UNSUPPORTED
+    assert lib.xq_prepare_weights(C.byref(a), 256, 128, 5, x, x, x, 1 << 30, st) == UNSUPPORTED
+    assert lib.xq_prepare_weights(C.byref(a), 256, 128, 8, x, x, x, 16, st) == WORKSPACE     # 8-bit caches are served
     assert lib.xq_prepare_weights(C.byref(a), 256, 128, 4, x, x, x, 16, st) == WORKSPACE
     cache = _cache()
     ok_len = (C.c_int32 * 1)(8)
@@ -95,7 +96,8 @@ def test_argument_errors_are_reported_before_any_launch():
     assert call(len=(C.c_int32 * 1)(0)) == INVALID      # empty sequence
     assert call(len=(C.c_int32 * 1)(9)) == INVALID      # longer than the cache
     assert call(wsb=64) == WORKSPACE
-    assert call(xc=C.byref(_cache(bits=8))) == UNSUPPORTED
+    assert call(xc=C.byref(_cache(bits=8)), wsb=64) == WORKSPACE      # 8-bit caches are served (walked nibble by nibble)
+    assert call(xc=C.byref(_cache(bits=5))) == UNSUPPORTED
     assert call(a=C.byref(bad_hd)) == UNSUPPORTED
     assert call(out=None) == INVALID
 
@@ -116,7 +118,7 @@ def test_argument_errors_of_the_widened_entry_points():
     assert pre(5, 4) == INVALID                         # fewer rows than queries
     assert pre(2, 9) == INVALID                         # longer than the cache
     assert pre(2, 8, wsb=64) == WORKSPACE
-    assert pre(2, 8, xc=_cache(bits=8)) == UNSUPPORTED
+    assert pre(2, 8, xc=_cache(bits=8), wsb=64) == WORKSPACE
     assert lib.xq_remat_attn_prefill(C.byref(a), x, 2, C.byref(cache), None, 1, 8, 256, x, (C.c_int32 * 1)(8), x, 4,
                                      None, x, x, 1 << 30, st) == INVALID        # table without positions
     at = xq.XQAttn(4, 2, 128, 0.1)
