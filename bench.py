@@ -22,8 +22,11 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, published
 # HBM-side bytes of one launch of the fused kernel on this workload: rocprofv3 FETCH_SIZE + WRITE_SIZE,
 # each scaled by the factor that makes the counter read 256 MiB for a plain 256 MiB device copy
-# (profiles/remat_attn_coded_c2_hbm_traffic.txt; counters cannot be read from inside this process)
+# (profiles/remat_attn_hbm_traffic.txt; counters cannot be read from inside this process, so this is a
+# recorded constant: measured with the library built from the commit named here; remat_attn.hip's tiling,
+# which fixes the figure, has not changed since)
 K3_HBM_BYTES_PER_LAUNCH = 2.18e9
+K3_HBM_BYTES_MEASURED_AT = "9002d93"
 
 
 def parse():
@@ -31,11 +34,18 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--settle", type=int, default=40,
+                    help="launches of the fused kernel during set-up, before the warm-up steps: from an idle GPU the clock "
+                         "takes some 15 launches to settle (the first ones run 1.8 - 2.2 ms against 1.7), which a short "
+                         "--warmup alone would put inside the timed steps; reported as config.settle_launches")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--cpu-pairs", type=int, default=96, help="(sequence, head) pairs the oracle times")
     ap.add_argument("--profile-copy", action="store_true",
                     help="also run one plain device copy of the 256 MiB X tensor (calibrates HBM byte counters)")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary kernels (profiling runs)")
+    ap.add_argument("--profile-kernels", action="store_true",
+                    help="after the timed loop also launch, three times each, the accumulator-source kernel on the c2 shape and "
+                         "the fused kernel on the c4 (GQA) shape, so that one counter run covers all three (profiling runs)")
     ap.add_argument("--other-configs", action="store_true",
                     help="also time the fused kernel on the GQA (c4) and long-context (c5) shapes; reported under extra")
     return ap.parse_args()
@@ -86,6 +96,8 @@ def main():
         if ev is not None:
             ev[1].record()
 
+    for _ in range(args.settle):                 # set-up: bring the GPU to its clock under this load
+        xq.xq_remat_attn_decode(attn, q, wprep, lens, xcache=cache, out=out, workspace=ws)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -110,6 +122,29 @@ def main():
         y.copy_(x)
         torch.cuda.synchronize()
         del y
+
+    if args.profile_kernels:
+        wprep_d = xq.xq_prepare_weights(attn, d, 128, 16, dev_bf16(wk_bits), dev_bf16(wv_bits))
+        for _ in range(3):
+            xq.xq_remat_attn_decode(attn, q, wprep_d, lens, acc_bf16=x, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        del wprep_d
+        w4p = xi.C4
+        a4p = xq.XQAttn(w4p.Hq, w4p.Hkv, w4p.hd, w4p.hd ** -0.5)
+        gp = torch.Generator(device=dev).manual_seed(4)
+        c4p = xq.alloc_cache(w4p.B, w4p.L, w4p.d, w4p.G, w4p.bits)
+        for b0 in range(w4p.B):
+            sub = xq.XQCache(c4p.codes[b0:b0 + 1], c4p.scale[b0:b0 + 1], c4p.zero[b0:b0 + 1], 1, w4p.L, w4p.d, w4p.G, w4p.bits)
+            xq.xq_quantize_append(sub, torch.randn((1, w4p.L, w4p.d), device=dev, generator=gp).to(torch.bfloat16), [0])
+        wk4p, wv4p = xi.gen_weights(w4p)
+        wp4p = xq.xq_prepare_weights(a4p, w4p.d, w4p.G, w4p.bits, dev_bf16(wk4p), dev_bf16(wv4p))
+        out4p = torch.empty((w4p.B, w4p.Hq, w4p.hd), dtype=torch.float32, device=dev)
+        ws4p = torch.empty(xq.xq_remat_attn_workspace_bytes(a4p, w4p.B, w4p.L, w4p.d, w4p.G), dtype=torch.uint8, device=dev)
+        q4p = dev_bf16(xi.gen_q(w4p))
+        for _ in range(3):
+            xq.xq_remat_attn_decode(a4p, q4p, wp4p, [w4p.L] * w4p.B, xcache=c4p, out=out4p, workspace=ws4p)
+        torch.cuda.synchronize()
+        del c4p, wp4p, ws4p
 
     # ---- secondary kernels of the path (reported, not part of `value`)
     def timed(fn, n=10, warm=2):
@@ -568,10 +603,12 @@ def main():
         "config": {"workload": "c2 Llama-2-7B-shaped decode step, one layer: d=4096, 32x128 MHA, batch 8, "
                                "context 4096, X cache 3-bit asym group 128; step = quantize+append 1 token/seq "
                                "then fused dequant-remat-attention",
-                   "batch": B, "context": L, "d": d, "heads": Hq, "kv_heads": Hkv, "bits": bits, "group": G},
-        "roofline": {"bound": "mfma", "kernel": "remat_attn_coded_kernel<3,128> (events bracket xq_remat_attn_decode: + scale pre-pass and combine, ~1%)",
+                   "batch": B, "context": L, "d": d, "heads": Hq, "kv_heads": Hkv, "bits": bits, "group": G,
+                   "settle_launches": args.settle},
+        "roofline": {"bound": "mfma", "kernel": "remat_attn_coded_kernel<3,128,0> (events bracket xq_remat_attn_decode: + scale pre-pass and combine, ~1%)",
                      "achieved": achieved_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "traffic_measured_at_commit": K3_HBM_BYTES_MEASURED_AT,
                      "avg_ms": remat_ms, "flops_per_launch": flops},
         "extra": extra,
     }
