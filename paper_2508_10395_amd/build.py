@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libxquant.so")
 SOURCES = ["api.hip", "quantize.hip", "cl_accumulate.hip", "prepare_weights.hip", "remat_attn.hip",
-           "latent_project.hip"]
+           "remat_attn16.hip", "latent_project.hip"]
 HEADERS = ["common.hpp", "remat_layout.hpp", "unpack.hpp", "remat_common.hpp", "remat_epilogues.hpp", "remat_launch.hpp"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

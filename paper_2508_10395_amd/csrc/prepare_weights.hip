@@ -159,6 +159,57 @@ __global__ __launch_bounds__(256) void pack_corr_kernel(PrepArgs a)
     }
 }
 
+// ---- the second stream: 16-column fragments for the v_mfma_f32_16x16x32 kernel (layout in remat_layout.hpp)
+__global__ __launch_bounds__(256) void pack_main16_kernel(PrepArgs a, uint8_t* out16, long long head_bytes16)
+{
+    const int s = blockIdx.x, h = blockIdx.y;
+    const int n_k32 = a.n_main_slabs * TILE16_TICKS;
+    const int head_shift = a.shift[h];
+    for (int f = threadIdx.x; f < TILE16_TICKS * 16 * 64; f += blockDim.x) {
+        const int lane = f & 63, ct = (f >> 6) & 15, j = f >> 10;
+        const int q = lane >> 4, n = ct * 16 + (lane & 15);
+        int kappa = s * TILE16_TICKS + j - tile16_lag(ct);
+        if (kappa < 0) kappa += n_k32;
+        const int cs_ = kappa / TILE16_TICKS, cj = kappa % TILE16_TICKS;
+        uint32_t v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int p = a.tab.code_of_slot[cj][i];
+            const int c = cs_ * 128 + q * 32 + p;
+            const float wv = ldexpf(wval(a, h, c, n), a.tab.wexp_of_code[p] + head_shift);          // exact: power-of-two scaling
+            const _Float16 hv = (_Float16)fminf(fmaxf(wv, -65504.0f), 65504.0f);
+            v[i] = (uint32_t)__builtin_bit_cast(uint16_t, hv);
+        }
+        uint4 o;
+        o.x = v[0] | (v[1] << 16); o.y = v[2] | (v[3] << 16);
+        o.z = v[4] | (v[5] << 16); o.w = v[6] | (v[7] << 16);
+        *reinterpret_cast<uint4*>(out16 + (long long)h * head_bytes16 + (long long)s * SLAB_BYTES + (long long)f * 16) = o;
+    }
+}
+
+__global__ __launch_bounds__(256) void pack_corr16_kernel(PrepArgs a, uint8_t* out16, long long head_bytes16)
+{
+    const int cs = blockIdx.x, h = blockIdx.y;
+    for (int f = threadIdx.x; f < TILE16_TICKS * 16 * 64; f += blockDim.x) {
+        const int lane = f & 63, ct = (f >> 6) & 15, j = f >> 10;
+        const int q = lane >> 4, n = ct * 16 + (lane & 15);
+        uint32_t v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int kappa = (cs * TILE16_TICKS + j) * 32 + q * 8 + i;
+            const int term = kappa / a.ng_pad, g = kappa % a.ng_pad;
+            uint32_t bits = 0;
+            if (term < N_CORR_TERMS && g < a.ng) bits = split_part(a.colsum[((long long)h * a.ng + g) * 256 + n], term);
+            v[i] = bits;
+        }
+        uint4 o;
+        o.x = v[0] | (v[1] << 16); o.y = v[2] | (v[3] << 16);
+        o.z = v[4] | (v[5] << 16); o.w = v[6] | (v[7] << 16);
+        *reinterpret_cast<uint4*>(out16 + (long long)h * head_bytes16 +
+                                  (long long)(a.n_main_slabs + cs) * SLAB_BYTES + (long long)f * 16) = o;
+    }
+}
+
 bool unpack_table_for(int bits, UnpackTable* t)
 {
     switch (bits) {
@@ -192,6 +243,11 @@ hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const u
     if (L.bits != 16) {
         colsum_kernel<<<dim3(L.ng, L.Hkv), dim3(256), 0, s>>>(a);
         pack_corr_kernel<<<dim3(L.n_corr_slabs, L.Hkv), dim3(256), 0, s>>>(a);
+    }
+    if (L.t16_bytes) {
+        uint8_t* out16 = a.out + L.t16_offset;
+        pack_main16_kernel<<<dim3(L.n_main_slabs, L.Hkv), dim3(256), 0, s>>>(a, out16, (long long)L.t16_head_bytes);
+        pack_corr16_kernel<<<dim3(L.t16_n_corr_slabs, L.Hkv), dim3(256), 0, s>>>(a, out16, (long long)L.t16_head_bytes);
     }
     return hipGetLastError();
 }

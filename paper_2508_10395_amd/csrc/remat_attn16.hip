@@ -1,0 +1,467 @@
+// Decode attention over a per-token X cache with groups of 128 codes, built on v_mfma_f32_16x16x32
+// (Sec. 3.1 and the cost model of Sec. 3.4 in arxiv 2508.10395).  Same mathematics, same partials and the same
+// workgroup shape as remat_attn_coded_kernel<BITS, 128, MODE_ATTENTION> in remat_attn.hip -- eight waves, a
+// wave owns 32 tokens and all 256 columns of [Wk_h | Wv_h], codes enter the fp16 MFMA as subnormals, one
+// accumulator carried through the groups by Horner rescaling, zero-points through a few bf16 k-steps -- but
+// the 32 x 256 block of a wave is cut into 2 x 16 accumulator tiles of 16 x 16 and every MFMA contracts 32
+// indices.  The matrix pipe does the same multiply-adds with half the accumulator updates, and on this chip
+// that is what counts: the kernel's time is set by the clock the chip can hold under the matrix cores' power
+// draw, and a register-resident loop of 16x16x32 MFMAs sustains about 97 % of the nominal rate on these
+// operands (3-bit codes against 8-bit significands) where 32x32x16 sustains about 82 %.
+//
+// Lane l of a wave: c16 = l % 16, quarter q = l / 16.  It holds the tokens 32 wave + 16 s + c16, s = 0, 1, and
+// of every accumulator tile (s, ct) the four columns 16 ct + 4 q + [0, 4) of its token.  Of a slab's 128
+// codes per token it unpacks unit q (codes [32 q, 32 q + 32)), whose four k-steps are the slab's four ticks.
+// The weights come from the second prepared stream (16-column fragments, remat_layout.hpp), tile ct running
+// 3 - ct / 4 ticks behind the walk so that every tick rescales four tiles.
+#include <mutex>
+
+#include "remat_common.hpp"
+
+namespace xq {
+
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+__device__ __forceinline__ float row16_max(float v)      // all-reduce over each row of 16 lanes
+{
+    v = fmaxf(v, dpp_f32<DPP_QUAD_XOR1>(v));
+    v = fmaxf(v, dpp_f32<DPP_QUAD_XOR2>(v));
+    v = fmaxf(v, dpp_f32<DPP_ROW_HALF_MIRROR>(v));
+    v = fmaxf(v, dpp_f32<DPP_ROW_MIRROR>(v));
+    return v;
+}
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_f32<DPP_QUAD_XOR1>(v);
+    v += dpp_f32<DPP_QUAD_XOR2>(v);
+    v += dpp_f32<DPP_ROW_HALF_MIRROR>(v);
+    v += dpp_f32<DPP_ROW_MIRROR>(v);
+    return v;
+}
+
+// ---- attention on the rematerialised chunk, accumulator layout of the 16 x 16 tiles: tiles 0-7 are K, 8-15 V;
+// element i of tile (s, ct) is column 16 (ct % 8) + 4 q + i of token 32 wave + 16 s + c16.  Scores, softmax
+// weights and the weighted sum of V stay inside the wave; one partial (m, l, o[128]) per query head.
+__device__ __forceinline__ void attention_epilogue16(const RematParams& p, const TileCtx& c, f32x4 (&acc)[2][16])
+{
+    const int tok_base = c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS;
+    if (tok_base >= c.len) return;                                         // chunk entirely past len
+    const int c16 = c.lane & 15, q = c.lane >> 4;
+    if (p.rope) {
+        // column n < 64 pairs with n + 64: tile ct with tile ct + 4, same element
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int tok = min(tok_base + 16 * s + c16, c.len - 1);
+            const float* tab = p.rope + (long long)(p.pos0.v[c.b] + tok) * 128;
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct) {
+                const float* cs = tab + 2 * (16 * ct + 4 * q);
+                const float4 cs0 = *reinterpret_cast<const float4*>(cs);
+                const float4 cs1 = *reinterpret_cast<const float4*>(cs + 4);
+                const float co[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, si[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float a = acc[s][ct][k], b = acc[s][ct + 4][k];
+                    acc[s][ct][k] = __builtin_fmaf(a, co[k], -b * si[k]);
+                    acc[s][ct + 4][k] = __builtin_fmaf(b, co[k], a * si[k]);
+                }
+            }
+        }
+    }
+    const int gq = p.Hq / p.Hkv;
+    const int chunk = p.chunk0.v[c.b] + c.tile * (TILE_TOKENS / CHUNK_TOKENS) + c.wave;
+    for (int j = 0; j < gq; ++j) {
+        const int hq = c.hk * gq + j;
+        const uint16_t* qv = p.q + ((long long)c.b * p.Hq + hq) * 128 + 4 * q;
+        float dot[2] = {0.0f, 0.0f};
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) {
+            const uint2 qq = *reinterpret_cast<const uint2*>(qv + 16 * ct);
+            const float q0 = bf16_lo_to_f32(qq.x), q1 = bf16_hi_to_f32(qq.x), q2 = bf16_lo_to_f32(qq.y), q3 = bf16_hi_to_f32(qq.y);
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                dot[s] = __builtin_fmaf(q0, acc[s][ct][0], dot[s]);
+                dot[s] = __builtin_fmaf(q1, acc[s][ct][1], dot[s]);
+                dot[s] = __builtin_fmaf(q2, acc[s][ct][2], dot[s]);
+                dot[s] = __builtin_fmaf(q3, acc[s][ct][3], dot[s]);
+            }
+        }
+        float sc[2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            float d = dot[s] + __shfl_xor(dot[s], 16);                    // the four quarters hold 32 columns each
+            d += __shfl_xor(d, 32);
+            sc[s] = tok_base + 16 * s + c16 < c.len ? d * p.scale_log2e : -INFINITY;
+        }
+        const float m = row16_max(fmaxf(sc[0], sc[1]));                    // (every row holds all 32 tokens)
+        const float p0 = __builtin_amdgcn_exp2f(sc[0] - m), p1 = __builtin_amdgcn_exp2f(sc[1] - m);
+        const float l = row16_sum(p0 + p1);
+        const long long pidx = ((long long)c.b * p.Hq + hq) * p.chunks_per_seq + chunk;
+        float* po = p.part_o + pidx * 128 + 4 * q;
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) {
+            float o[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)   // masked tokens have weight 0 and their rows are clamped copies: finite
+                o[k] = row16_sum(__builtin_fmaf(p0, acc[0][8 + ct][k], p1 * acc[1][8 + ct][k]));
+            if (c16 == 0) {
+                float4 w; w.x = o[0]; w.y = o[1]; w.z = o[2]; w.w = o[3];
+                *reinterpret_cast<float4*>(po + 16 * ct) = w;
+            }
+        }
+        if (c.lane == 0) {
+            p.part_ml[pidx * 2] = m;
+            p.part_ml[pidx * 2 + 1] = l;
+        }
+    }
+}
+
+template <int BITS>
+__global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParams p)
+{
+    constexpr int ROW_SLAB_BYTES = 16 * BITS;          // packed bytes of 128 channels of one token
+    constexpr int UNIT_BYTES = 4 * BITS;               // ... of a unit of 32 codes
+    constexpr int NCI = 4 * BITS;                      // code-DMA wave instructions per slab per workgroup
+    constexpr int IMG_BYTES = code_image_bytes(BITS);
+    constexpr int NIMG = n_code_images(BITS);
+    constexpr int LDS_SCALES_OFF = lds_scales_off(BITS);
+    constexpr int NT = TILE16_TICKS;                   // ticks (k32-steps) per slab
+    constexpr int AHEAD = 5;                           // slots between the LDS read of a weight fragment and its use
+    constexpr int NRING = 8;                           // (divides 64: the ring runs on from slab to slab)
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    TileCtx c;
+    if (!locate_tile(p, c)) return;
+    const int lane = c.lane, wave = c.wave;
+    const int c16 = lane & 15, q = lane >> 4;
+
+    const int n_corr_slabs = (p.n_corr_ksteps + NT - 1) / NT;            // (n_corr_ksteps counts ticks here)
+    const int head_shift = p.head_shift[c.hk];         // the head's stream holds its weights times 2^head_shift
+    const uint8_t* wsrc = p.wprep + (long long)c.hk * p.head_bytes + wave * 1024;   // this wave's DMA share
+    const uint32_t dma_voff = (uint32_t)lane * 16u;
+    const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds;
+    const uint32_t lds_w = lds_base + wave * 1024;
+    const uint8_t* my_slab = lds + lane * 16;          // + buffer * SLAB_BYTES + (tick * 16 + tile) * 1024
+
+    // ---- token-side sources
+    const long long seq_row0 = (long long)c.b * p.cap;
+    const uint32_t row_bytes = (uint32_t)(p.row_d * BITS / 8);
+    const uint8_t* cbase = p.codes + seq_row0 * row_bytes;
+    const uint16_t* zbase = p.zero + seq_row0 * p.ng_row;
+    const uint8_t* ebase = reinterpret_cast<const uint8_t*>(p.eT) +
+                           ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.ng + 1) * 512;
+    int my_row[2];
+    uint32_t moff[2];
+    const uint8_t* my_codes[2];
+    const uint16_t* my_scale[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        my_row[s] = wave * CHUNK_TOKENS + 16 * s + c16;
+        moff[s] = (uint32_t)min(c.tile * TILE_TOKENS + my_row[s], c.len - 1) * (uint32_t)p.ng_row;
+        my_codes[s] = lds + LDS_CODES_OFF + my_row[s] * ROW_SLAB_BYTES + q * UNIT_BYTES;
+        my_scale[s] = reinterpret_cast<const uint16_t*>(lds + LDS_SCALES_OFF) + my_row[s];
+    }
+    // code DMA: 16-byte piece pc of the tile's slab image = (row pc / BITS, part pc % BITS);
+    // wave instruction i covers pieces [64 i, 64 i + 64); this wave issues i = wave and wave + 8
+    uint32_t cvoff[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int pc = (wave + 8 * k) * 64 + lane;
+        const int rl = pc / BITS, prt = pc % BITS;
+        cvoff[k] = (uint32_t)min(c.tile * TILE_TOKENS + rl, c.len - 1) * row_bytes + prt * 16;
+    }
+
+    f32x4 acc[2][16];                    // [token half][column tile]: tiles 0-7 K, 8-15 V
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int ct = 0; ct < 16; ++ct)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[s][ct][i] = 0.0f;
+
+    uint4 af[8];                         // weight fragments, ring over slots (loaded AHEAD slots ahead)
+    uint32_t ub[2][NT][4];               // token fragments, ring over ticks
+    uint32_t cur[2][BITS];               // packed codes (unit q) of the current slab, per token half
+    float E_prev[2], E_cur[2];           // effective scales of the previous and the current slab's group
+    float hr[2];                         // Horner factors E_prev / E_cur of the boundaries seen this slab
+
+    auto fetch_scales = [&](int sbuf, float (&e)[2]) XQ_INLINE_LAMBDA {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) e[s] = __uint_as_float((uint32_t)my_scale[s][sbuf * (LDS_SCALES_BYTES / 2)] << 16);
+    };
+    auto fetch_tokens = [&](int img) XQ_INLINE_LAMBDA {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const uint8_t* src = my_codes[s] + img * IMG_BYTES;
+            if constexpr (BITS == 4) {
+                const uint4 v = *reinterpret_cast<const uint4*>(src);
+                cur[s][0] = v.x; cur[s][1] = v.y; cur[s][2] = v.z; cur[s][3] = v.w;
+            } else if constexpr (BITS == 2) {
+                const uint2 v = *reinterpret_cast<const uint2*>(src);
+                cur[s][0] = v.x; cur[s][1] = v.y;
+            } else {
+#pragma unroll
+                for (int i = 0; i < BITS; ++i) cur[s][i] = reinterpret_cast<const uint32_t*>(src)[i];
+            }
+        }
+    };
+    auto make_fragment = [&](auto S, auto J) XQ_INLINE_LAMBDA {           // tick J of the slab whose codes are in cur
+        constexpr int s = decltype(S)::value, j = decltype(J)::value;
+        unpack_kstep<BITS>(&cur[s][0], j, ub[s][j]);
+    };
+    auto make_half_fragment = [&](auto S, auto J, auto H) XQ_INLINE_LAMBDA {   // operand dwords 2 H, 2 H + 1 of it
+        constexpr int s = decltype(S)::value, j = decltype(J)::value, h = decltype(H)::value;
+        uint32_t t[4];
+        unpack_kstep<BITS>(&cur[s][0], j, t);
+        ub[s][j][2 * h] = t[2 * h];
+        ub[s][j][2 * h + 1] = t[2 * h + 1];
+    };
+    // one piece of the DMA that brings in main slab `slab` (weights to `wdst`): steps 0,1 this wave's
+    // code pieces (to code image `img`), 2 scales (wave 7; of slab `slab2`, into scale buffer `sbuf`),
+    // 3..10 the weight chunks
+    auto dma_step = [&](int step, int slab, int img, int slab2, bool with_scales2, int sbuf, uint32_t wdst) XQ_INLINE_LAMBDA {
+        if (step < 2) {
+            if (wave + 8 * step < NCI)
+                dma_b128(cbase + slab * ROW_SLAB_BYTES, cvoff[step],
+                         lds_base + LDS_CODES_OFF + (uint32_t)(img * IMG_BYTES) + (wave + 8 * step) * 1024);
+        } else if (step == 2) {
+            if (with_scales2 && wave == 7)
+                dma_b128(ebase + (long long)slab2 * 512, dma_voff, lds_base + LDS_SCALES_OFF + (uint32_t)(sbuf * LDS_SCALES_BYTES));
+        } else {
+            dma_b128(wsrc + (long long)slab * SLAB_BYTES + (step - 3) * 8192, dma_voff, wdst + (step - 3) * 8192);
+        }
+    };
+
+    // ==== phase 1: the zero-point correction (scale 1): bf16 ticks whose token-side operands are the stored
+    // zero-points of 8 groups per lane.  The codes and scales of the slab that cyclically precedes the first
+    // one arrive meanwhile: the lagging tiles start inside it.
+    const bool vec_meta = (p.ng & 7) == 0 && (p.ng_row & 7) == 0 && ((size_t)zbase & 15) == 0 && p.meta_shift == 0;
+    auto load_meta = [&](int s, int kk) -> uint4 {
+        const int kappa0 = kk * 32 + q * 8;
+        const int term = kappa0 / p.ng_pad, g0 = kappa0 % p.ng_pad;
+        uint4 v = {0u, 0u, 0u, 0u};
+        if (kk < p.n_corr_ksteps && term < N_CORR_TERMS) {
+            if (vec_meta) {
+                v = *reinterpret_cast<const uint4*>(zbase + moff[s] + g0);
+            } else {
+                uint32_t h[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int g = g0 + i;
+                    const uint32_t x = zbase[moff[s] + (min(g, p.ng - 1) >> p.meta_shift)];
+                    h[i] = g < p.ng ? x : 0u;               // padding groups contribute nothing
+                }
+                v.x = h[0] | (h[1] << 16); v.y = h[2] | (h[3] << 16);
+                v.z = h[4] | (h[5] << 16); v.w = h[6] | (h[7] << 16);
+            }
+        }
+        return v;
+    };
+    const int slab_prev = p.n_main_slabs - 1;           // the walk is cyclic: the slab "before" slab 0
+    issue_slab(wsrc + (long long)p.n_main_slabs * SLAB_BYTES, lds_w, dma_voff);        // correction slab 0 -> buffer 0
+    dma_step(0, slab_prev, NIMG - 1, 0, false, 0, 0);                                  // predecessor codes -> last image
+    dma_step(1, slab_prev, NIMG - 1, 0, false, 0, 0);
+    dma_step(2, 0, 0, slab_prev, true, 2, 0);                                          // its scales -> scale buffer 2
+    dma_step(2, 0, 0, 0, true, 0, 0);                                                  // first slab's scales -> buffer 0
+    if (p.n_main_slabs > 1) dma_step(2, 0, 0, 1, true, 1, 0);                          // second slab's -> buffer 1
+    if constexpr (NIMG == 2) {                                                         // first slab's codes -> image 0
+        dma_step(0, 0, 0, 0, false, 0, 0);
+        dma_step(1, 0, 0, 0, false, 0, 0);
+    }
+    uint4 mfr[2][NT];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) mfr[s][j] = load_meta(s, j);
+    for (int cs = 0; cs < n_corr_slabs; ++cs) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        const uint32_t wdst = lds_w + (uint32_t)(((cs + 1) & 1) * SLAB_BYTES);
+        if (cs + 1 < n_corr_slabs) issue_slab(wsrc + (long long)(p.n_main_slabs + cs + 1) * SLAB_BYTES, wdst, dma_voff);
+        else issue_slab(wsrc, wdst, dma_voff);                                                   // the first main slab
+        if (cs == 0) {
+            fetch_tokens(NIMG - 1);
+            fetch_scales(2, E_prev);
+        }
+        const uint8_t* slab = my_slab + (cs & 1) * SLAB_BYTES;
+        const int nj = min(NT, p.n_corr_ksteps - cs * NT);
+#pragma unroll
+        for (int sl = 0; sl < AHEAD; ++sl) af[sl] = *reinterpret_cast<const uint4*>(slab + sl * 1024);
+        static_for<0, NT * 16>([&](auto SIDX) XQ_INLINE_LAMBDA {
+            constexpr int sidx = decltype(SIDX)::value, j = sidx >> 4, ct = sidx & 15;
+            if (j < nj) {
+                acc[0][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[sidx & 7]),
+                                                                     __builtin_bit_cast(bf16x8, mfr[0][j]), acc[0][ct], 0, 0, 0);
+                acc[1][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[sidx & 7]),
+                                                                     __builtin_bit_cast(bf16x8, mfr[1][j]), acc[1][ct], 0, 0, 0);
+            }
+            if constexpr (sidx + AHEAD < NT * 16) af[(sidx + AHEAD) & 7] = *reinterpret_cast<const uint4*>(slab + (sidx + AHEAD) * 1024);
+            if constexpr (NIMG == 1) {
+                if constexpr (sidx == 0) {
+                    if (cs == 0) {
+                        // every wave now holds its predecessor codes in registers: the first slab's
+                        // codes may overwrite the only image
+                        __syncthreads();
+                        dma_step(0, 0, 0, 0, false, 0, 0);
+                        dma_step(1, 0, 0, 0, false, 0, 0);
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        if (cs + 1 < n_corr_slabs) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) mfr[s][j] = load_meta(s, (cs + 1) * NT + j);
+        }
+    }
+
+    // ==== phase 2: the d x 256 contraction, a cyclic walk over the d/32 ticks that starts at slab 0.  Tile ct
+    // runs lag(ct) = 3 - ct / 4 ticks behind: at tick tau it multiplies the weights of tick tau - lag (the
+    // stream is laid out in this order) with the token fragment unpacked lag ticks ago, which waits in a 4-deep
+    // ring.  A tile enters the current slab's group at tick lag(ct); its 8 accumulator registers are rescaled
+    // in the slots before that, so every tick rescales four tiles: eight slots of a tick multiply four registers
+    // each, four others unpack half a token fragment each, and no slot carries more than five such instructions.
+    //
+    // Set-up: the ring's lagging fragments are ticks 1..3 of the predecessor slab, in whose group the lagging
+    // tiles start; the accumulators (holding the correction in units of 1) are brought to those scales.
+    static_for<1, NT>([&](auto J) XQ_INLINE_LAMBDA {
+        make_fragment(std::integral_constant<int, 0>{}, J);
+        make_fragment(std::integral_constant<int, 1>{}, J);
+    });
+    const int par0 = n_corr_slabs & 1;                 // weight buffer of main iteration 0
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    fetch_tokens(0);
+    fetch_scales(0, E_cur);
+    {
+        const uint8_t* slab0 = my_slab + par0 * SLAB_BYTES;
+#pragma unroll
+        for (int sl = 0; sl < AHEAD; ++sl) af[sl] = *reinterpret_cast<const uint4*>(slab0 + sl * 1024);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            // (every tile starts in the predecessor's units: those without lag are rescaled at tick 0 like the others later)
+            const float r_prev = ldexpf(__builtin_amdgcn_rcpf(E_prev[s]), head_shift);
+#pragma unroll
+            for (int ct = 0; ct < 16; ++ct) acc[s][ct] *= r_prev;
+            hr[s] = E_prev[s] * __builtin_amdgcn_rcpf(E_cur[s]);
+        }
+    }
+
+    for (int it = 0; it < p.n_main_slabs; ++it) {
+        // With a single code image, everyone must have taken the previous slab's codes out of it before
+        // this slab's DMA refills it; iteration 0 keeps a barrier for the scale buffer the set-up has just read.
+        if (NIMG == 1 || it == 0) __syncthreads();
+        const int img_next = NIMG == 2 ? (it + 1) & 1 : 0;
+        const bool more_main = it + 1 < p.n_main_slabs;
+        const bool more_main2 = it + 2 < p.n_main_slabs;
+        // (the last iterations issue their DMA all the same, from slabs that exist into buffers that
+        // are not read again: no branches around the issue slots)
+        const int s_next = more_main ? it + 1 : it;
+        const int s_next2 = more_main2 ? it + 2 : it;
+        const uint32_t wdst = lds_w + (uint32_t)(((it + 1 + par0) & 1) * SLAB_BYTES);
+        const uint8_t* slab = my_slab + ((it + par0) & 1) * SLAB_BYTES;
+        const uint8_t* slab_next = my_slab + ((it + 1 + par0) & 1) * SLAB_BYTES;
+        float e_nxt[2] = {1.0f, 1.0f};                       // scales of the next slab (landed one slab ago)
+        float hr_n[2] = {1.0f, 1.0f};                        // boundary factors of the next iteration
+        __builtin_amdgcn_sched_barrier(0);
+
+        static_for<0, NT * 16>([&](auto SIDX) XQ_INLINE_LAMBDA {
+            constexpr int sidx = decltype(SIDX)::value;
+            constexpr int j = sidx >> 4, ct = sidx & 15;
+            constexpr int ring = (j - tile16_lag(ct)) & (NT - 1);
+            acc[0][ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                __builtin_bit_cast(f16x8, af[sidx % NRING]), as_frag(ub[0][ring][0], ub[0][ring][1], ub[0][ring][2], ub[0][ring][3]),
+                acc[0][ct], 0, 0, 0);
+            acc[1][ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                __builtin_bit_cast(f16x8, af[sidx % NRING]), as_frag(ub[1][ring][0], ub[1][ring][1], ub[1][ring][2], ub[1][ring][3]),
+                acc[1][ct], 0, 0, 0);
+
+            // DMA of the next slab: 11 steps per wave, one every other slot
+            if constexpr ((sidx >> 1) < 11 && (sidx & 1) == 0)
+                dma_step(sidx >> 1, s_next, img_next, s_next2, true, it & 1, wdst);
+            // the old codes are no longer needed: wait until the next slab has landed for everyone,
+            // then take the next slab's codes
+            if constexpr (sidx == 64 - AHEAD) {               // (after the last read of this slab's weights, before the first of the next's)
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                if (more_main) fetch_tokens(img_next);
+            }
+            // weight fragment of the slot AHEAD ahead (the last slots of a slab read the next slab, which has landed by then)
+            if constexpr (sidx + AHEAD < 64) af[(sidx + AHEAD) % NRING] = *reinterpret_cast<const uint4*>(slab + (sidx + AHEAD) * 1024);
+            else if (more_main) af[(sidx + AHEAD) % NRING] = *reinterpret_cast<const uint4*>(slab_next + (sidx + AHEAD - 64) * 1024);
+            // token fragments, half a fragment (two operand dwords) per slot in the four slots of every tick that
+            // rescale nothing.  Tick j + 1's ring entry was last read by tick j's tiles 0-3 (lag 3) and is first
+            // read by tick j + 1's tiles 12-15; tick 0's is made in the slab's first four slots, from the codes
+            // taken out of LDS at the end of the previous slab.
+            if constexpr (sidx < 4) make_half_fragment(std::integral_constant<int, (sidx >> 1)>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, (sidx & 1)>{});
+            if constexpr (j + 1 < NT && ct >= 12 - 4 * j && ct < 16 - 4 * j)
+                make_half_fragment(std::integral_constant<int, ((ct - (12 - 4 * j)) >> 1)>{}, std::integral_constant<int, j + 1>{}, std::integral_constant<int, ((ct - (12 - 4 * j)) & 1)>{});
+            // the next slab's scales are in LDS since the previous slab
+            if constexpr (sidx == 40) { if (more_main) fetch_scales((it + 1) & 1, e_nxt); }
+            if constexpr (sidx == 58) {
+                if (more_main) { hr_n[0] = E_cur[0] * __builtin_amdgcn_rcpf(e_nxt[0]); hr_n[1] = E_cur[1] * __builtin_amdgcn_rcpf(e_nxt[1]); }
+            }
+            // Horner: the four tiles that enter this slab's group at tick jj (tiles 4 (3 - jj) + i) are rescaled half
+            // a tile per slot in the eight slots 12 jj + 4 + [0, 8): after the tile's MFMAs of the previous tick
+            // have long retired, before its slot of tick jj, and in none of the slots that unpack codes
+            {
+                constexpr int r = sidx - 4, jj = r / 12, o = r % 12;
+                if constexpr (sidx >= 4 && jj < NT && o < 8) {
+                    constexpr int s = o & 1, ct2 = 4 * (3 - jj) + (o >> 1);
+                    static_assert(tile16_lag(ct2) == jj && sidx < 16 * jj + ct2 && sidx + 16 > 16 * jj + ct2 + 2, "Horner slot outside the tile's window");
+                    float x0 = acc[s][ct2][0] * hr[s], x1 = acc[s][ct2][1] * hr[s], x2 = acc[s][ct2][2] * hr[s], x3 = acc[s][ct2][3] * hr[s];
+                    asm volatile("" :: "v"(x0), "v"(x1), "v"(x2), "v"(x3));
+                    acc[s][ct2][0] = x0; acc[s][ct2][1] = x1; acc[s][ct2][2] = x2; acc[s][ct2][3] = x3;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        if (more_main) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s) { E_prev[s] = E_cur[s]; E_cur[s] = e_nxt[s]; hr[s] = hr_n[s]; }
+        }
+    }
+    // every tile has ended in the last slab's group; leave its scale: the accumulator is K | V
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const float f = ldexpf(E_cur[s], -head_shift);
+#pragma unroll
+        for (int ct = 0; ct < 16; ++ct) acc[s][ct] *= f;
+    }
+    attention_epilogue16(p, c, acc);
+}
+
+hipError_t launch_tile16(int bits, const RematParams& p, int grid, hipStream_t s)
+{
+    const void* k = nullptr;
+    switch (bits) {
+        case 2: k = reinterpret_cast<const void*>(remat_attn_tile16_kernel<2>); break;
+        case 3: k = reinterpret_cast<const void*>(remat_attn_tile16_kernel<3>); break;
+        case 4: k = reinterpret_cast<const void*>(remat_attn_tile16_kernel<4>); break;
+        default: return hipErrorInvalidValue;
+    }
+    const int lds_bytes = lds_coded_total(bits);
+    static std::mutex mu;
+    static bool done[64][5];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (dev < 64 && !done[dev][bits]) {
+            e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (e != hipSuccess) return e;
+            done[dev][bits] = true;
+        }
+    }
+    switch (bits) {
+        case 2: remat_attn_tile16_kernel<2><<<dim3(grid), dim3(512), lds_bytes, s>>>(p); break;
+        case 3: remat_attn_tile16_kernel<3><<<dim3(grid), dim3(512), lds_bytes, s>>>(p); break;
+        default: remat_attn_tile16_kernel<4><<<dim3(grid), dim3(512), lds_bytes, s>>>(p); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace xq

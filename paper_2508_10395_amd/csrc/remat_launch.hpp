@@ -99,6 +99,9 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
                                   const BatchI32& len, int max_len, float* out, void* ws,
                                   const float* rope, const BatchI32* pos0, hipStream_t s);
 
+// the decode kernel on 16 x 16 x 32 MFMAs (remat_attn16.hip): groups of 128 codes, up to 3 query heads per KV head
+hipError_t launch_tile16(int bits, const RematParams& p, int grid, hipStream_t s);
+
 // query heads per KV head from which the decode step goes through the matrix-core epilogue (the
 // per-query-head vector epilogue runs that many times per tile; measured break-even is about 4)
 constexpr int DECODE_MFMA_EPILOGUE_MIN_GROUP = 4;
@@ -113,7 +116,8 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
     const int cache_bits = xc ? xc->fmt.bits : 16;
     const int bits = cache_bits == 8 ? 4 : cache_bits;                   // (an 8-bit cache is walked nibble by nibble)
     const int G = cache_bits == 8 ? 128 : xc ? xc->fmt.group : 128;
-    const WPrepLayout L = make_wprep_layout_for_cache(d, xc ? xc->fmt.group : 128, cache_bits, a->n_kv_heads);
+    const WPrepLayout L = make_wprep_layout_for_cache(d, xc ? xc->fmt.group : 128, cache_bits, a->n_kv_heads,
+                                                      a->n_q_heads / a->n_kv_heads);
     RematParams p{};
     fill_common(p, a, q, B, cap, len, max_len, ws);
     p.codes = xc ? xc->codes : nullptr;
@@ -138,7 +142,14 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
             xc->scale, eT, cap, L.ng, p.ng_row, p.tiles_per_seq, bits, len, p.meta_shift);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        e = launch_coded<MODE_ATTENTION>(bits, G, p, grid, s);
+        if (L.t16_bytes) {                                   // the stream of 16-column fragments and its kernel
+            p.wprep += L.t16_offset;
+            p.head_bytes = (long long)L.t16_head_bytes;
+            p.n_corr_ksteps = L.t16_n_corr_ticks;
+            e = launch_tile16(bits, p, grid, s);
+        } else {
+            e = launch_coded<MODE_ATTENTION>(bits, G, p, grid, s);
+        }
     } else {
         // bf16 token rows are 5 times the bytes of 3-bit codes and every head reads them: let the heads of an
         // XCD take the same tile side by side, so that its L2 serves all but the first (measured: 1.80 -> 1.66 ms
