@@ -164,16 +164,21 @@ __global__ __launch_bounds__(256) void pack_main16_kernel(PrepArgs a, uint8_t* o
 {
     const int s = blockIdx.x, h = blockIdx.y;
     const int n_k32 = a.n_main_slabs * TILE16_TICKS;
-    const int head_shift = a.shift[h];
+    const bool dense = a.bits == 16;
+    const int head_shift = dense ? 0 : a.shift[h];
     for (int f = threadIdx.x; f < TILE16_TICKS * 16 * 64; f += blockDim.x) {
         const int lane = f & 63, ct = (f >> 6) & 15, j = f >> 10;
         const int q = lane >> 4, n = ct * 16 + (lane & 15);
-        int kappa = s * TILE16_TICKS + j - tile16_lag(ct);
+        int kappa = s * TILE16_TICKS + j - (dense ? 0 : tile16_lag(ct));
         if (kappa < 0) kappa += n_k32;
         const int cs_ = kappa / TILE16_TICKS, cj = kappa % TILE16_TICKS;
         uint32_t v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
+            if (dense) {
+                v[i] = f32_to_bf16_rne(wval(a, h, cs_ * 128 + cj * 32 + q * 8 + i, n));              // (exact: the weights are bf16)
+                continue;
+            }
             const int p = a.tab.code_of_slot[cj][i];
             const int c = cs_ * 128 + q * 32 + p;
             const float wv = ldexpf(wval(a, h, c, n), a.tab.wexp_of_code[p] + head_shift);          // exact: power-of-two scaling
@@ -247,7 +252,8 @@ hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const u
     if (L.t16_bytes) {
         uint8_t* out16 = a.out + L.t16_offset;
         pack_main16_kernel<<<dim3(L.n_main_slabs, L.Hkv), dim3(256), 0, s>>>(a, out16, (long long)L.t16_head_bytes);
-        pack_corr16_kernel<<<dim3(L.t16_n_corr_slabs, L.Hkv), dim3(256), 0, s>>>(a, out16, (long long)L.t16_head_bytes);
+        if (L.t16_n_corr_slabs)
+            pack_corr16_kernel<<<dim3(L.t16_n_corr_slabs, L.Hkv), dim3(256), 0, s>>>(a, out16, (long long)L.t16_head_bytes);
     }
     return hipGetLastError();
 }

@@ -433,6 +433,160 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     attention_epilogue16(p, c, acc);
 }
 
+// =====================================================================================
+// Dense source (the bf16 accumulator of XQuant-CL, Sec. 3.2) on the same 16 x 16 tiles: no codes, no scales,
+// no lag -- slab s, tick j multiplies channels 128 s + 32 j + [0, 32) for every tile.  A wave needs, per half
+// slab (2 ticks = 64 channels), 128 contiguous bytes of each of its 32 token rows: 4 LDS-DMA instructions
+// fetch 8 rows x 128 B each into a 4 KiB staging area private to the wave (the hand-over needs s_waitcnt, no
+// barrier), and 4 ds_read_b128 per lane bring the fragments into registers -- lane (c16, q) takes, of token
+// 16 s + c16, the 16 bytes of quarter q of tick jj.  The 16-byte piece p of row r of block j (tokens 8 j ..
+// 8 j + 7) sits in slot 8 (r % 8) + (p ^ f), f = ((r % 8) >> 1) | ((j & 1) << 2), which keeps both the
+// DMA's linear LDS write and the fragment read free of bank conflicts.
+// Per half slab (32 slots): slot 16 takes the fragments of the next half out of staging, slot 20 issues the
+// DMA of the half after it.
+// =====================================================================================
+constexpr int LDS_DENSE16_STAGE_OFF = 2 * SLAB_BYTES;
+constexpr int LDS_DENSE16_STAGE_BYTES = 4096;          // per wave
+constexpr int LDS_DENSE16_TOTAL = LDS_DENSE16_STAGE_OFF + 8 * LDS_DENSE16_STAGE_BYTES;
+static_assert(LDS_DENSE16_TOTAL <= LDS_MAX, "dense kernel LDS");
+
+__global__ __launch_bounds__(512) void remat_attn_dense16_kernel(const RematParams p)
+{
+    constexpr int AHEAD = 5;                           // slots between the LDS read of a weight fragment and its use
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    TileCtx c;
+    if (!locate_tile(p, c)) return;
+    const int lane = c.lane, wave = c.wave;
+    const int c16 = lane & 15, q = lane >> 4;
+
+    const uint8_t* wsrc = p.wprep + (long long)c.hk * p.head_bytes + wave * 1024;
+    const uint32_t dma_voff = (uint32_t)lane * 16u;
+    const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)lds;
+    const uint32_t lds_w = lds_base + wave * 1024;
+    const uint8_t* my_slab = lds + lane * 16;
+    const uint8_t* cbase = reinterpret_cast<const uint8_t*>(p.acc) + (long long)c.b * p.cap * p.d * 2;
+    const uint32_t row_bytes = (uint32_t)p.d * 2u;
+    const int n_halves = 2 * p.n_main_slabs;
+
+    // DMA side: lane = (row r8 of the block, slot column); block j covers the wave's tokens 8 j .. 8 j + 7
+    uint32_t xvoff[4];
+    {
+        const int r8 = lane >> 3, sc = lane & 7;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int piece = sc ^ ((r8 >> 1) | ((j & 1) << 2));
+            const int tok = c.tile * TILE_TOKENS + wave * CHUNK_TOKENS + 8 * j + r8;
+            xvoff[j] = (uint32_t)min(tok, c.len - 1) * row_bytes + (uint32_t)piece * 16u;
+        }
+    }
+    const uint32_t stage = lds_base + LDS_DENSE16_STAGE_OFF + wave * LDS_DENSE16_STAGE_BYTES;
+    // fragment side: token 16 s + c16 is row c16 % 8 of block 2 s + c16 / 8; piece 4 jj + q
+    const uint8_t* my_stage = lds + LDS_DENSE16_STAGE_OFF + wave * LDS_DENSE16_STAGE_BYTES + (c16 >> 3) * 1024 + (c16 & 7) * 128;
+    const int fx = ((c16 & 7) >> 1) | ((c16 >> 3) << 2);
+    auto issue_x = [&](int h) {                           // token rows of half slab h -> staging
+        const int hc = min(h, n_halves - 1);              // (past the end: a harmless repeat)
+        const uint8_t* src = cbase + (long long)hc * 128;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dma_b128(src, xvoff[j], stage + j * 1024);
+    };
+    auto take_x = [&](uint4 (&dst)[2][2]) {               // [token half s][tick jj of the half slab]
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+                dst[s][jj] = *reinterpret_cast<const uint4*>(my_stage + s * 2048 + (((4 * jj + q) ^ fx) * 16));
+    };
+
+    f32x4 acc[2][16];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int ct = 0; ct < 16; ++ct)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[s][ct][i] = 0.0f;
+
+    uint4 af[8];                         // weight fragments, ring over slots (loaded AHEAD slots ahead)
+    uint4 bd[2][2][2];                   // token fragments of the two halves of a slab
+
+    issue_slab(wsrc, lds_w, dma_voff);
+    issue_x(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    take_x(bd[0]);
+#pragma unroll
+    for (int sl = 0; sl < AHEAD; ++sl) af[sl] = *reinterpret_cast<const uint4*>(my_slab + sl * 1024);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // staging has been read: it may be refilled
+    issue_x(1);
+
+    for (int it = 0; it < p.n_main_slabs; ++it) {
+        const bool more_main = it + 1 < p.n_main_slabs;
+        const int s_next = more_main ? it + 1 : it;       // (the last iteration repeats itself into unused buffers)
+        const uint32_t wdst = lds_w + (uint32_t)(((it + 1) & 1) * SLAB_BYTES);
+        const uint8_t* wnext = wsrc + (long long)s_next * SLAB_BYTES;
+        const uint8_t* slab = my_slab + (it & 1) * SLAB_BYTES;
+        const uint8_t* slab_next = my_slab + ((it + 1) & 1) * SLAB_BYTES;
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, 64>([&](auto SIDX) XQ_INLINE_LAMBDA {
+            constexpr int sidx = decltype(SIDX)::value;
+            constexpr int j = sidx >> 4, ct = sidx & 15;
+            constexpr int hs = sidx & 31, hf = sidx >> 5;            // slot inside the half slab, which half
+            acc[0][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8, af[sidx & 7]), __builtin_bit_cast(bf16x8, bd[hf][0][j & 1]), acc[0][ct], 0, 0, 0);
+            acc[1][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8, af[sidx & 7]), __builtin_bit_cast(bf16x8, bd[hf][1][j & 1]), acc[1][ct], 0, 0, 0);
+            // next slab's weights: 4 DMA steps per half slab, one every other slot
+            if constexpr (hs < 8 && (hs & 1) == 0)
+                dma_b128(wnext + (hf * 4 + (hs >> 1)) * 8192, dma_voff, wdst + (hf * 4 + (hs >> 1)) * 8192);
+            // token rows: outstanding behind the DMA of the next half are this half's 4 weight steps
+            if constexpr (hs == 16) {
+                asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                take_x(bd[hf ^ 1]);
+            }
+            if constexpr (hs == 20) {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                issue_x(2 * it + hf + 2);
+            }
+            // the next slab's weights have landed for everyone (its buffer was last read one slab ago, and this
+            // slab's last fragment has been read in the slot before); the newest 4 DMAs, the token rows just
+            // issued, may still be in flight
+            if constexpr (sidx == 64 - AHEAD) {
+                asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                __syncthreads();
+            }
+            if constexpr (sidx + AHEAD < 64) af[(sidx + AHEAD) & 7] = *reinterpret_cast<const uint4*>(slab + (sidx + AHEAD) * 1024);
+            else if (more_main) af[(sidx + AHEAD) & 7] = *reinterpret_cast<const uint4*>(slab_next + (sidx + AHEAD - 64) * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing may still be writing this workgroup's LDS
+    attention_epilogue16(p, c, acc);
+}
+
+static hipError_t allow_lds_once(const void* k, int lds_bytes, int slot)
+{
+    static std::mutex mu;
+    static bool done[64][6];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!done[dev][slot]) {
+        e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        done[dev][slot] = true;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_tile16_dense(const RematParams& p, int grid, hipStream_t s)
+{
+    hipError_t e = allow_lds_once(reinterpret_cast<const void*>(remat_attn_dense16_kernel), LDS_DENSE16_TOTAL, 5);
+    if (e != hipSuccess) return e;
+    remat_attn_dense16_kernel<<<dim3(grid), dim3(512), LDS_DENSE16_TOTAL, s>>>(p);
+    return hipGetLastError();
+}
+
 hipError_t launch_tile16(int bits, const RematParams& p, int grid, hipStream_t s)
 {
     const void* k = nullptr;
@@ -443,19 +597,8 @@ hipError_t launch_tile16(int bits, const RematParams& p, int grid, hipStream_t s
         default: return hipErrorInvalidValue;
     }
     const int lds_bytes = lds_coded_total(bits);
-    static std::mutex mu;
-    static bool done[64][5];
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    const hipError_t e = allow_lds_once(k, lds_bytes, bits);
     if (e != hipSuccess) return e;
-    {
-        std::lock_guard<std::mutex> lock(mu);
-        if (dev < 64 && !done[dev][bits]) {
-            e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-            if (e != hipSuccess) return e;
-            done[dev][bits] = true;
-        }
-    }
     switch (bits) {
         case 2: remat_attn_tile16_kernel<2><<<dim3(grid), dim3(512), lds_bytes, s>>>(p); break;
         case 3: remat_attn_tile16_kernel<3><<<dim3(grid), dim3(512), lds_bytes, s>>>(p); break;

@@ -101,6 +101,7 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
 
 // the decode kernel on 16 x 16 x 32 MFMAs (remat_attn16.hip): groups of 128 codes, up to 3 query heads per KV head
 hipError_t launch_tile16(int bits, const RematParams& p, int grid, hipStream_t s);
+hipError_t launch_tile16_dense(const RematParams& p, int grid, hipStream_t s);
 
 // query heads per KV head from which the decode step goes through the matrix-core epilogue (the
 // per-query-head vector epilogue runs that many times per tile; measured break-even is about 4)
@@ -155,7 +156,13 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
         // XCD take the same tile side by side, so that its L2 serves all but the first (measured: 1.80 -> 1.66 ms
         // on the Llama-2-7B shape; the coded kernel gains nothing from it)
         p.tile_major = 1;
-        e = launch_with_lds(remat_attn_dense_kernel<DENSE_ATTENTION>, LDS_DENSE_TOTAL, p, grid, s);
+        if (L.t16_bytes) {
+            p.wprep += L.t16_offset;
+            p.head_bytes = (long long)L.t16_head_bytes;
+            e = launch_tile16_dense(p, grid, s);
+        } else {
+            e = launch_with_lds(remat_attn_dense_kernel<DENSE_ATTENTION>, LDS_DENSE_TOTAL, p, grid, s);
+        }
     }
     if (e != hipSuccess) return e;
     combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len, 1, CHUNK_TOKENS);
