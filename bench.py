@@ -23,10 +23,10 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, published
 # HBM-side bytes of one launch of the fused kernel on this workload: rocprofv3 FETCH_SIZE + WRITE_SIZE,
 # each scaled by the factor that makes the counter read 256 MiB for a plain 256 MiB device copy
 # (profiles/remat_attn_hbm_traffic.txt; counters cannot be read from inside this process, so this is a
-# recorded constant: measured with the library built from the commit named here; remat_attn.hip's tiling,
+# recorded constant: measured with the library built from the commit named here; remat_attn16.hip's tiling,
 # which fixes the figure, has not changed since)
 K3_HBM_BYTES_PER_LAUNCH = 2.18e9
-K3_HBM_BYTES_MEASURED_AT = "9002d93"
+K3_HBM_BYTES_MEASURED_AT = "e41161c"
 
 
 def parse():
