@@ -178,7 +178,7 @@ xq_status_t xq_cl_accumulate(uint16_t* acc_bf16, const xq_cache_t* src, const in
 size_t xq_prepared_weights_bytes(const xq_attn_t* a, int32_t d, int32_t group, int32_t src_bits)
 {
     if (check_attn(a) != XQ_OK || !wprep_cache_combo_ok(d, group, src_bits)) return 0;
-    return make_wprep_layout_for_cache(d, group, src_bits, a->n_kv_heads, a->n_q_heads / a->n_kv_heads).total_bytes;
+    return make_wprep_layout_for_cache(d, group, src_bits, a->n_kv_heads).total_bytes;
 }
 
 xq_status_t xq_prepare_weights(const xq_attn_t* a, int32_t d, int32_t group, int32_t src_bits,
@@ -190,7 +190,7 @@ xq_status_t xq_prepare_weights(const xq_attn_t* a, int32_t d, int32_t group, int
     if (!Wk || !Wv || !out || !aligned16(Wk) || !aligned16(Wv) || !aligned16(out)) return XQ_ERR_INVALID_ARG;
     if (d <= 0) return XQ_ERR_INVALID_ARG;
     if (!wprep_cache_combo_ok(d, group, src_bits)) return XQ_ERR_UNSUPPORTED;
-    const WPrepLayout L = make_wprep_layout_for_cache(d, group, src_bits, a->n_kv_heads, a->n_q_heads / a->n_kv_heads);
+    const WPrepLayout L = make_wprep_layout_for_cache(d, group, src_bits, a->n_kv_heads);
     if (out_bytes < L.total_bytes) return XQ_ERR_WORKSPACE;
     hipError_t e = run_prepare_weights(L, Wk, Wv, a->n_kv_heads * 128, 128, out, static_cast<hipStream_t>(stream), false,
                                        src_bits == 8);

@@ -39,6 +39,32 @@ __device__ __forceinline__ float row16_sum(float v)
     return v;
 }
 
+// rotary embedding of the rematerialised keys (tiles 0-7): column n < 64 pairs with n + 64, i.e. tile ct with tile
+// ct + 4, same element; the table row is the token's position
+__device__ __forceinline__ void rope_rotate16(const RematParams& p, const TileCtx& c, f32x4 (&acc)[2][16])
+{
+    const int tok_base = c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS;
+    const int c16 = c.lane & 15, q = c.lane >> 4;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int tok = min(tok_base + 16 * s + c16, c.len - 1);
+        const float* tab = p.rope + (long long)(p.pos0.v[c.b] + tok) * 128;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            const float* cs = tab + 2 * (16 * ct + 4 * q);
+            const float4 cs0 = *reinterpret_cast<const float4*>(cs);
+            const float4 cs1 = *reinterpret_cast<const float4*>(cs + 4);
+            const float co[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, si[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float a = acc[s][ct][k], b = acc[s][ct + 4][k];
+                acc[s][ct][k] = __builtin_fmaf(a, co[k], -b * si[k]);
+                acc[s][ct + 4][k] = __builtin_fmaf(b, co[k], a * si[k]);
+            }
+        }
+    }
+}
+
 // ---- attention on the rematerialised chunk, accumulator layout of the 16 x 16 tiles: tiles 0-7 are K, 8-15 V;
 // element i of tile (s, ct) is column 16 (ct % 8) + 4 q + i of token 32 wave + 16 s + c16.  Scores, softmax
 // weights and the weighted sum of V stay inside the wave; one partial (m, l, o[128]) per query head.
@@ -47,27 +73,7 @@ __device__ __forceinline__ void attention_epilogue16(const RematParams& p, const
     const int tok_base = c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS;
     if (tok_base >= c.len) return;                                         // chunk entirely past len
     const int c16 = c.lane & 15, q = c.lane >> 4;
-    if (p.rope) {
-        // column n < 64 pairs with n + 64: tile ct with tile ct + 4, same element
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const int tok = min(tok_base + 16 * s + c16, c.len - 1);
-            const float* tab = p.rope + (long long)(p.pos0.v[c.b] + tok) * 128;
-#pragma unroll
-            for (int ct = 0; ct < 4; ++ct) {
-                const float* cs = tab + 2 * (16 * ct + 4 * q);
-                const float4 cs0 = *reinterpret_cast<const float4*>(cs);
-                const float4 cs1 = *reinterpret_cast<const float4*>(cs + 4);
-                const float co[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, si[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float a = acc[s][ct][k], b = acc[s][ct + 4][k];
-                    acc[s][ct][k] = __builtin_fmaf(a, co[k], -b * si[k]);
-                    acc[s][ct + 4][k] = __builtin_fmaf(b, co[k], a * si[k]);
-                }
-            }
-        }
-    }
+    if (p.rope) rope_rotate16(p, c, acc);
     const int gq = p.Hq / p.Hkv;
     const int chunk = p.chunk0.v[c.b] + c.tile * (TILE_TOKENS / CHUNK_TOKENS) + c.wave;
     for (int j = 0; j < gq; ++j) {
@@ -116,7 +122,240 @@ __device__ __forceinline__ void attention_epilogue16(const RematParams& p, const
     }
 }
 
-template <int BITS>
+// =====================================================================================
+// Attention for many query rows (chunked prefill, App. A; decode with four or more query heads per KV head) on the
+// matrix cores, for the 16 x 16 tile layout.  Query rows (a query token and one of the KV head's query heads) are
+// taken 16 at a time:
+//   S^T[token][query] = K Q^T : A = the wave's K tiles straight from the accumulator registers -- the 8 values a lane
+//       holds of two adjacent tiles are 8 contraction indices in a fixed permuted order, which the Q fragment loads
+//       mirror -- split into bf16 hi + lo (8 MFMAs per token half).  The result has lane = (query c16, tokens
+//       16 s + 4 q + [0, 4)): mask, max, exp2 and sum are per-lane loops plus exchanges between the four quarters.
+//   The eight waves exchange their maxima through LDS (barrier), so every wave forms its softmax weights against the
+//   tile's maximum, and writes them (bf16 hi + lo) to LDS exactly as its lanes hold them: 16 bytes per lane, which
+//   is one lane's share of an A fragment of P (query rows x 32 tokens).  Barrier.
+//   O[query][n] = P V : wave w owns the 16 value columns 16 w + [0, 16) and contracts over all 256 tokens of the
+//       tile: per 32-token chunk one P fragment (from LDS, as written) against the chunk's V read column-wise, for
+//       which every wave has transposed its V once per tile into bf16 hi and lo images [n][32 tokens] in LDS
+//       (64-byte rows whose 8-byte pieces are XOR-swizzled by the row: conflict-free fragment reads);
+//       hi*hi + lo*hi + hi*lo, the lo*lo term (2^-16 relative) is dropped.  Each wave stores its 16 columns of the
+//       partial (m, l, o[128]) per (query row, 256-token tile): no sum over waves is left.
+// Two workgroup barriers per 16 query rows, and P V of one group overlaps the scores of the next.  LDS: 8 x 16 KiB of V images over the dead slab buffers, 16 KiB of
+// softmax weights, 1 KiB of maxima and sums.  Called by all eight waves; nothing else may touch the LDS any more.
+// =====================================================================================
+constexpr int PF16_VT_IMAGE_BYTES = 128 * 64;
+constexpr int PF16_VT_WAVE_BYTES = 2 * PF16_VT_IMAGE_BYTES;
+constexpr int PF16_P_OFF = 8 * PF16_VT_WAVE_BYTES;
+constexpr int PF16_P_BYTES = 2 * 8 * 1024;             // hi and lo, [chunk 8][lane 64][16 B]
+constexpr int PF16_M_OFF = PF16_P_OFF + PF16_P_BYTES;   // float [8 waves][16 queries] maxima, then sums
+constexpr int PF16_TOTAL = PF16_M_OFF + 2 * 8 * 16 * 4;
+
+// byte offset of the 8-byte piece (4 tokens) `piece` of row n inside a V image
+__device__ __forceinline__ int vt16_offset(int n, int piece) { return n * 64 + ((piece ^ (2 * ((n >> 2) & 3))) << 3); }
+
+__device__ __forceinline__ void split_hi_lo(const float (&v)[8], uint4& hi, uint4& lo)
+{
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        h[i] = pack_bf16x2_rne(v[2 * i], v[2 * i + 1]);
+        l[i] = pack_bf16x2_rne(v[2 * i] - bf16_lo_to_f32(h[i]), v[2 * i + 1] - bf16_hi_to_f32(h[i]));
+    }
+    hi = make_uint4(h[0], h[1], h[2], h[3]);
+    lo = make_uint4(l[0], l[1], l[2], l[3]);
+}
+
+__device__ __forceinline__ f32x4 mfma16_bf16(const uint4& a, const uint4& b, const f32x4& c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ void prefill_epilogue16(const RematParams& p, const TileCtx& c, f32x4 (&acc)[2][16], uint8_t* lds)
+{
+    const int tok0 = c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS;
+    const bool active = tok0 < c.len;                                      // wave-uniform: chunk not entirely past len
+    const int c16 = c.lane & 15, q = c.lane >> 4;
+    __syncthreads();                                                       // every wave is done with the slab buffers
+    uint4 khi[2][4], klo[2][4];
+    if (active) {
+        if (p.rope) rope_rotate16(p, c, acc);
+        // V^T images of the wave's 32 tokens: element i of tile (s, 8 + ct) is V[token 16 s + c16][n = 16 ct + 4 q + i]
+        uint8_t* vt = lds + c.wave * PF16_VT_WAVE_BYTES;
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int ct = 0; ct < 8; ++ct)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int n = 16 * ct + 4 * q + i, t = 16 * s + c16;
+                    const float v = acc[s][8 + ct][i];
+                    const uint32_t h = pack_bf16x2_rne(v, 0.0f);
+                    uint8_t* dst = vt + vt16_offset(n, t >> 2) + (t & 3) * 2;
+                    *reinterpret_cast<uint16_t*>(dst) = (uint16_t)h;
+                    *reinterpret_cast<uint16_t*>(dst + PF16_VT_IMAGE_BYTES) = (uint16_t)pack_bf16x2_rne(v - bf16_lo_to_f32(h), 0.0f);
+                }
+        // K fragments: contraction block kb covers columns [32 kb, 32 kb + 32) = tiles 2 kb, 2 kb + 1; this lane's 8
+        // of them are 32 kb + 4 q + [0, 4) and 32 kb + 16 + 4 q + [0, 4)
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+                float v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = acc[s][2 * kb + (k >> 2)][k & 3];
+                split_hi_lo(v, khi[s][kb], klo[s][kb]);
+            }
+    } else {
+        // a chunk entirely past len contributes nothing: zero V images (and zero weights below) let every wave
+        // contract over all eight chunks without a branch
+        uint8_t* vt = lds + c.wave * PF16_VT_WAVE_BYTES;
+#pragma unroll
+        for (int k = 0; k < PF16_VT_WAVE_BYTES / 1024; ++k)
+            *reinterpret_cast<uint4*>(vt + k * 1024 + c.lane * 16) = make_uint4(0u, 0u, 0u, 0u);
+    }
+
+    const int gq = p.Hq / p.Hkv, NQ = p.Tq * gq;
+    float* mbuf = reinterpret_cast<float*>(lds + PF16_M_OFF);             // [wave][16 queries]
+    float* lbuf = mbuf + 8 * 16;
+    uint8_t* pbuf = lds + PF16_P_OFF;
+    // query row qi = (query token tq, head j of the KV head's gq): qi / gq by a multiply (exact while qi gq < 2^32;
+    // the host admits no more than 65535 query tokens per launch)
+    const uint32_t gq_magic = 0xFFFFFFFFu / (uint32_t)gq + 1u;
+    auto token_of = [&](int qi) -> int { return gq == 1 ? qi : (int)__umulhi((uint32_t)qi, gq_magic); };
+    auto part_row = [&](int qi) -> long long {
+        const int tq = token_of(qi);
+        return ((long long)c.b * p.Tq + tq) * p.Hq + c.hk * gq + (qi - tq * gq);
+    };
+    const int ncol = 16 * c.wave + c16;                                    // the value column this lane reads and stores
+    // Q fragments of the group that starts at query row q0, for this lane's query row of it (rows past NQ repeat the
+    // last one and are not stored)
+    auto load_q = [&](int q0, uint4 (&qf)[4]) XQ_INLINE_LAMBDA {
+        const uint16_t* qv = p.q + part_row(min(q0 + c16, NQ - 1)) * 128 + 4 * q;
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+            const uint2 a = *reinterpret_cast<const uint2*>(qv + 32 * kb);
+            const uint2 b = *reinterpret_cast<const uint2*>(qv + 32 * kb + 16);
+            qf[kb] = make_uint4(a.x, a.y, b.x, b.y);
+        }
+    };
+    // scores of the wave's 32 tokens against the group's 16 query rows, masked and scaled; their maximum per query row
+    // goes to mbuf
+    auto scores = [&](int q0, const uint4 (&qf)[4], f32x4 (&S)[2]) XQ_INLINE_LAMBDA {
+        float m = -INFINITY;
+        if (active) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) S[s][i] = 0.0f;
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    S[s] = mfma16_bf16(khi[s][kb], qf[kb], S[s]);
+                    S[s] = mfma16_bf16(klo[s][kb], qf[kb], S[s]);
+                }
+            // element i of S[s] <-> token tok0 + 16 s + 4 q + i; visible up to the query's own row
+            const int tq = token_of(min(q0 + c16, NQ - 1));
+            const int limit = c.len - p.Tq + tq - tok0;
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int rel = 16 * s + 4 * q + i;
+                    S[s][i] = rel <= limit ? S[s][i] * p.scale_log2e : -INFINITY;
+                    m = fmaxf(m, S[s][i]);
+                }
+            m = fmaxf(m, __shfl_xor(m, 16));
+            m = fmaxf(m, __shfl_xor(m, 32));
+        }
+        if (q == 0) mbuf[c.wave * 16 + c16] = m;
+    };
+
+    // Software pipeline over the groups: between the two barriers of group g the softmax weights are formed; after
+    // the second one P V of group g runs alongside the scores of group g + 1 (independent work: the matrix pipe and
+    // the LDS latencies of one hide behind the other), and the queries of group g + 2 are already on their way --
+    // the barriers wait for this wave's LDS accesses only, not for its global loads and stores.
+    auto lds_barrier = [&]() XQ_INLINE_LAMBDA { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+    uint4 qf[4];
+    f32x4 S[2];
+    load_q(0, qf);
+    scores(0, qf, S);
+    if (16 < NQ) load_q(16, qf);
+    for (int q0 = 0; q0 < NQ; q0 += 16) {
+        lds_barrier();                                                     // the group's maxima are in mbuf
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) M = fmaxf(M, mbuf[w * 16 + c16]);
+        const float Mu = M == -INFINITY ? 0.0f : M;                        // nothing visible: all weights 0
+        float l = 0.0f;
+        uint4 phi = make_uint4(0u, 0u, 0u, 0u), plo = phi;
+        if (active) {
+            float pr[8];
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    pr[4 * s + i] = __builtin_amdgcn_exp2f(S[s][i] - Mu);
+                    l += pr[4 * s + i];
+                }
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            split_hi_lo(pr, phi, plo);
+        }
+        *reinterpret_cast<uint4*>(pbuf + (c.wave * 64 + c.lane) * 16) = phi;
+        *reinterpret_cast<uint4*>(pbuf + PF16_P_BYTES / 2 + (c.wave * 64 + c.lane) * 16) = plo;
+        if (q == 0) lbuf[c.wave * 16 + c16] = l;
+        lds_barrier();                                                     // weights and sums of all eight chunks are in LDS
+        // operands of P V, four chunks ahead: contraction index (quarter q', element 4 s + i) of chunk cw <-> its
+        // token 16 s + 4 q' + i, for the P fragment as written above and for the V pieces q' and 4 + q' alike
+        uint4 ph[4], pl[4], vh[4], vl[4];
+        auto load_chunk = [&](auto CW) XQ_INLINE_LAMBDA {
+            constexpr int cw = decltype(CW)::value, k = cw & 3;
+            ph[k] = *reinterpret_cast<const uint4*>(pbuf + (cw * 64 + c.lane) * 16);
+            pl[k] = *reinterpret_cast<const uint4*>(pbuf + PF16_P_BYTES / 2 + (cw * 64 + c.lane) * 16);
+            const uint8_t* v0 = lds + cw * PF16_VT_WAVE_BYTES + vt16_offset(ncol, q);
+            const uint8_t* v1 = lds + cw * PF16_VT_WAVE_BYTES + vt16_offset(ncol, 4 + q);
+            const uint2 h0 = *reinterpret_cast<const uint2*>(v0), h1 = *reinterpret_cast<const uint2*>(v1);
+            const uint2 l0 = *reinterpret_cast<const uint2*>(v0 + PF16_VT_IMAGE_BYTES);
+            const uint2 l1 = *reinterpret_cast<const uint2*>(v1 + PF16_VT_IMAGE_BYTES);
+            vh[k] = make_uint4(h0.x, h0.y, h1.x, h1.y);
+            vl[k] = make_uint4(l0.x, l0.y, l1.x, l1.y);
+        };
+        static_for<0, 4>(load_chunk);
+        float Lt = 0.0f;
+        if (c.wave == 0 && q == 0) {
+#pragma unroll
+            for (int w = 0; w < 8; ++w) Lt += lbuf[w * 16 + c16];
+        }
+        // the next group's scores (its maxima go to mbuf, which nobody reads any more before the next barrier), then
+        // the queries of the group after it
+        if (q0 + 16 < NQ) {
+            scores(q0 + 16, qf, S);
+            if (q0 + 32 < NQ) load_q(q0 + 32, qf);
+        }
+        f32x4 O0 = {0.0f, 0.0f, 0.0f, 0.0f}, O1 = O0, O2 = O0;             // hi*hi, lo*hi, hi*lo: three independent chains
+        static_for<0, 8>([&](auto CW) XQ_INLINE_LAMBDA {
+            constexpr int cw = decltype(CW)::value, k = cw & 3;
+            O0 = mfma16_bf16(ph[k], vh[k], O0);
+            O1 = mfma16_bf16(pl[k], vh[k], O1);
+            O2 = mfma16_bf16(ph[k], vl[k], O2);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (cw + 4 < 8) load_chunk(std::integral_constant<int, cw + 4>{});
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        if (c.wave == 0 && q == 0 && q0 + c16 < NQ) {
+            const long long pidx = part_row(q0 + c16) * p.chunks_per_seq + c.tile;
+            p.part_ml[pidx * 2] = M;
+            p.part_ml[pidx * 2 + 1] = Lt;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int qr = q0 + 4 * q + i;
+            if (qr < NQ) p.part_o[(part_row(qr) * p.chunks_per_seq + c.tile) * 128 + ncol] = (O1[i] + O2[i]) + O0[i];
+        }
+    }
+}
+
+template <int BITS, int MODE>
 __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParams p)
 {
     constexpr int ROW_SLAB_BYTES = 16 * BITS;          // packed bytes of 128 channels of one token
@@ -126,7 +365,8 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     constexpr int NIMG = n_code_images(BITS);
     constexpr int LDS_SCALES_OFF = lds_scales_off(BITS);
     constexpr int NT = TILE16_TICKS;                   // ticks (k32-steps) per slab
-    constexpr int AHEAD = 5;                           // slots between the LDS read of a weight fragment and its use
+    // slots between the LDS read of a weight fragment and its use (one fewer where the epilogue keeps more alive)
+    constexpr int AHEAD = MODE == MODE_PREFILL ? 4 : 5;
     constexpr int NRING = 8;                           // (divides 64: the ring runs on from slab to slab)
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -430,7 +670,8 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
 #pragma unroll
         for (int ct = 0; ct < 16; ++ct) acc[s][ct] *= f;
     }
-    attention_epilogue16(p, c, acc);
+    if constexpr (MODE == MODE_PREFILL) prefill_epilogue16(p, c, acc, lds);
+    else attention_epilogue16(p, c, acc);
 }
 
 // =====================================================================================
@@ -450,6 +691,7 @@ constexpr int LDS_DENSE16_STAGE_BYTES = 4096;          // per wave
 constexpr int LDS_DENSE16_TOTAL = LDS_DENSE16_STAGE_OFF + 8 * LDS_DENSE16_STAGE_BYTES;
 static_assert(LDS_DENSE16_TOTAL <= LDS_MAX, "dense kernel LDS");
 
+template <int MODE>
 __global__ __launch_bounds__(512) void remat_attn_dense16_kernel(const RematParams p)
 {
     constexpr int AHEAD = 5;                           // slots between the LDS read of a weight fragment and its use
@@ -559,13 +801,14 @@ __global__ __launch_bounds__(512) void remat_attn_dense16_kernel(const RematPara
         });
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing may still be writing this workgroup's LDS
-    attention_epilogue16(p, c, acc);
+    if constexpr (MODE == MODE_PREFILL) prefill_epilogue16(p, c, acc, lds);   // (starts with a workgroup barrier)
+    else attention_epilogue16(p, c, acc);
 }
 
 static hipError_t allow_lds_once(const void* k, int lds_bytes, int slot)
 {
     static std::mutex mu;
-    static bool done[64][6];
+    static bool done[64][10];                     // [device][kernel: bits (+ 4: prefill), 5 / 9: dense]
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
@@ -579,31 +822,37 @@ static hipError_t allow_lds_once(const void* k, int lds_bytes, int slot)
     return hipSuccess;
 }
 
-hipError_t launch_tile16_dense(const RematParams& p, int grid, hipStream_t s)
+static_assert(PF16_TOTAL <= lds_coded_total(2) && PF16_TOTAL <= lds_coded_total(3) && PF16_TOTAL <= lds_coded_total(4) &&
+              PF16_TOTAL <= LDS_DENSE16_TOTAL, "the matrix-core epilogue fits the LDS the contraction loop has");
+
+// prefill: the matrix-core epilogue (many query rows) instead of the per-query-head vector epilogue
+hipError_t launch_tile16_dense(const RematParams& p, int grid, hipStream_t s, bool prefill)
 {
-    hipError_t e = allow_lds_once(reinterpret_cast<const void*>(remat_attn_dense16_kernel), LDS_DENSE16_TOTAL, 5);
+    typedef void (*Kernel)(const RematParams);
+    const Kernel k = prefill ? remat_attn_dense16_kernel<MODE_PREFILL> : remat_attn_dense16_kernel<MODE_ATTENTION>;
+    hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), LDS_DENSE16_TOTAL, prefill ? 9 : 5);
     if (e != hipSuccess) return e;
-    remat_attn_dense16_kernel<<<dim3(grid), dim3(512), LDS_DENSE16_TOTAL, s>>>(p);
+    k<<<dim3(grid), dim3(512), LDS_DENSE16_TOTAL, s>>>(p);
     return hipGetLastError();
 }
 
-hipError_t launch_tile16(int bits, const RematParams& p, int grid, hipStream_t s)
+hipError_t launch_tile16(int bits, const RematParams& p, int grid, hipStream_t s, bool prefill)
 {
-    const void* k = nullptr;
-    switch (bits) {
-        case 2: k = reinterpret_cast<const void*>(remat_attn_tile16_kernel<2>); break;
-        case 3: k = reinterpret_cast<const void*>(remat_attn_tile16_kernel<3>); break;
-        case 4: k = reinterpret_cast<const void*>(remat_attn_tile16_kernel<4>); break;
+    typedef void (*Kernel)(const RematParams);
+    Kernel k = nullptr;
+    switch (bits * 2 + (prefill ? 1 : 0)) {
+        case 4: k = remat_attn_tile16_kernel<2, MODE_ATTENTION>; break;
+        case 5: k = remat_attn_tile16_kernel<2, MODE_PREFILL>; break;
+        case 6: k = remat_attn_tile16_kernel<3, MODE_ATTENTION>; break;
+        case 7: k = remat_attn_tile16_kernel<3, MODE_PREFILL>; break;
+        case 8: k = remat_attn_tile16_kernel<4, MODE_ATTENTION>; break;
+        case 9: k = remat_attn_tile16_kernel<4, MODE_PREFILL>; break;
         default: return hipErrorInvalidValue;
     }
     const int lds_bytes = lds_coded_total(bits);
-    const hipError_t e = allow_lds_once(k, lds_bytes, bits);
+    const hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), lds_bytes, bits + (prefill ? 4 : 0));
     if (e != hipSuccess) return e;
-    switch (bits) {
-        case 2: remat_attn_tile16_kernel<2><<<dim3(grid), dim3(512), lds_bytes, s>>>(p); break;
-        case 3: remat_attn_tile16_kernel<3><<<dim3(grid), dim3(512), lds_bytes, s>>>(p); break;
-        default: remat_attn_tile16_kernel<4><<<dim3(grid), dim3(512), lds_bytes, s>>>(p); break;
-    }
+    k<<<dim3(grid), dim3(512), lds_bytes, s>>>(p);
     return hipGetLastError();
 }
 

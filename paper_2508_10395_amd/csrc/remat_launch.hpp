@@ -99,9 +99,10 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
                                   const BatchI32& len, int max_len, float* out, void* ws,
                                   const float* rope, const BatchI32* pos0, hipStream_t s);
 
-// the decode kernel on 16 x 16 x 32 MFMAs (remat_attn16.hip): groups of 128 codes, up to 3 query heads per KV head
-hipError_t launch_tile16(int bits, const RematParams& p, int grid, hipStream_t s);
-hipError_t launch_tile16_dense(const RematParams& p, int grid, hipStream_t s);
+// the kernels on 16 x 16 x 32 MFMAs (remat_attn16.hip): groups of 128 codes or the dense source; prefill = the
+// matrix-core epilogue for many query rows instead of the per-query-head vector epilogue
+hipError_t launch_tile16(int bits, const RematParams& p, int grid, hipStream_t s, bool prefill);
+hipError_t launch_tile16_dense(const RematParams& p, int grid, hipStream_t s, bool prefill);
 
 // query heads per KV head from which the decode step goes through the matrix-core epilogue (the
 // per-query-head vector epilogue runs that many times per tile; measured break-even is about 4)
@@ -117,8 +118,7 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
     const int cache_bits = xc ? xc->fmt.bits : 16;
     const int bits = cache_bits == 8 ? 4 : cache_bits;                   // (an 8-bit cache is walked nibble by nibble)
     const int G = cache_bits == 8 ? 128 : xc ? xc->fmt.group : 128;
-    const WPrepLayout L = make_wprep_layout_for_cache(d, xc ? xc->fmt.group : 128, cache_bits, a->n_kv_heads,
-                                                      a->n_q_heads / a->n_kv_heads);
+    const WPrepLayout L = make_wprep_layout_for_cache(d, xc ? xc->fmt.group : 128, cache_bits, a->n_kv_heads);
     RematParams p{};
     fill_common(p, a, q, B, cap, len, max_len, ws);
     p.codes = xc ? xc->codes : nullptr;
@@ -147,7 +147,7 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
             p.wprep += L.t16_offset;
             p.head_bytes = (long long)L.t16_head_bytes;
             p.n_corr_ksteps = L.t16_n_corr_ticks;
-            e = launch_tile16(bits, p, grid, s);
+            e = launch_tile16(bits, p, grid, s, false);
         } else {
             e = launch_coded<MODE_ATTENTION>(bits, G, p, grid, s);
         }
@@ -159,7 +159,7 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
         if (L.t16_bytes) {
             p.wprep += L.t16_offset;
             p.head_bytes = (long long)L.t16_head_bytes;
-            e = launch_tile16_dense(p, grid, s);
+            e = launch_tile16_dense(p, grid, s, false);
         } else {
             e = launch_with_lds(remat_attn_dense_kernel<DENSE_ATTENTION>, LDS_DENSE_TOTAL, p, grid, s);
         }
@@ -218,10 +218,23 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
             xc->scale, const_cast<uint16_t*>(p.eT), cap, L.ng, p.ng_row, p.tiles_per_seq, bits, len, p.meta_shift);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        e = launch_coded<MODE_PREFILL>(bits, G, p, grid, s);
+        if (L.t16_bytes) {                                   // the stream of 16-column fragments and its kernel
+            p.wprep += L.t16_offset;
+            p.head_bytes = (long long)L.t16_head_bytes;
+            p.n_corr_ksteps = L.t16_n_corr_ticks;
+            e = launch_tile16(bits, p, grid, s, true);
+        } else {
+            e = launch_coded<MODE_PREFILL>(bits, G, p, grid, s);
+        }
     } else {
         p.tile_major = 1;                                    // (as in the decode launch)
-        e = launch_with_lds(remat_attn_dense_kernel<DENSE_PREFILL>, LDS_DENSE_TOTAL, p, grid, s);
+        if (L.t16_bytes) {
+            p.wprep += L.t16_offset;
+            p.head_bytes = (long long)L.t16_head_bytes;
+            e = launch_tile16_dense(p, grid, s, true);
+        } else {
+            e = launch_with_lds(remat_attn_dense_kernel<DENSE_PREFILL>, LDS_DENSE_TOTAL, p, grid, s);
+        }
     }
     if (e != hipSuccess) return e;
     combine_kernel<<<dim3(p.Hq, p.B * T), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq,
