@@ -743,6 +743,35 @@ __global__ __launch_bounds__(128 * COMBINE_GROUPS) void combine_kernel(const flo
     }
 }
 
+// The same merge for partials that come one per 256-token tile (the matrix-core epilogue: prefill chunks, decode with
+// many query heads per KV head): few per row but many rows.  One wave per row (query token, head), two output columns
+// per lane, four rows per workgroup, no LDS; the tiles are summed in order (deterministic).
+__global__ __launch_bounds__(256) void combine_rows_kernel(const float* __restrict__ part_o,
+                                                           const float* __restrict__ part_ml,
+                                                           float* __restrict__ out, int Hq, int chunks_per_seq,
+                                                           BatchI32 len, int rows_per_seq, int chunk_tokens, int n_rows)
+{
+    const int row = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    const int lane = threadIdx.x & 63;
+    if (row >= n_rows) return;
+    const int seq = row / (Hq * rows_per_seq);
+    const int nchunks = (len.v[seq] + chunk_tokens - 1) / chunk_tokens;
+    const long long base = (long long)row * chunks_per_seq;
+    float M = -INFINITY;
+    for (int c = 0; c < nchunks; ++c) M = fmaxf(M, part_ml[(base + c) * 2]);
+    float L = 0.0f, ox = 0.0f, oy = 0.0f;
+#pragma unroll 4
+    for (int c = 0; c < nchunks; ++c) {
+        const float w = __builtin_amdgcn_exp2f(part_ml[(base + c) * 2] - M);
+        const float2 o = *reinterpret_cast<const float2*>(part_o + (base + c) * 128 + 2 * lane);
+        L = __builtin_fmaf(w, part_ml[(base + c) * 2 + 1], L);
+        ox = __builtin_fmaf(w, o.x, ox);
+        oy = __builtin_fmaf(w, o.y, oy);
+    }
+    float2 r; r.x = ox / L; r.y = oy / L;
+    *reinterpret_cast<float2*>(out + (long long)row * 128 + 2 * lane) = r;
+}
+
 }  // namespace xq
 
 #include "remat_launch.hpp"

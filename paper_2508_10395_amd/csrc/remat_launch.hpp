@@ -237,8 +237,9 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
         }
     }
     if (e != hipSuccess) return e;
-    combine_kernel<<<dim3(p.Hq, p.B * T), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq,
-                                                                            p.chunks_per_seq, p.len, T, TILE_TOKENS);
+    const int n_rows = p.B * T * p.Hq;
+    combine_rows_kernel<<<dim3((n_rows + 3) / 4), dim3(256), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.chunks_per_seq, p.len, T,
+                                                                    TILE_TOKENS, n_rows);
     return hipGetLastError();
 }
 
