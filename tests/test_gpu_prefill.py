@@ -91,6 +91,15 @@ def test_prefill_gqa(xq, T):
     _run(xq, w, T, 2, 64, lens=[300, 130], seed=T)
 
 
+@pytest.mark.parametrize("Hq,T,dense", [(8, 5, False), (6, 11, False), (10, 7, False), (6, 9, True)])
+def test_prefill_gqa_groups_of_128(xq, Hq, T, dense):
+    """4, 3 and 5 query heads per KV head with groups of 128 (and from the accumulator): the epilogue of the
+    16x16x32 kernels takes the (token, head) rows 16 at a time -- 20, 33, 35 and 27 rows, so the last pass is
+    ragged and a pass straddles query tokens; lengths put the rows across a tile boundary."""
+    w = xi.C4.scaled(B=2, L=600, d=512, Hq=Hq, Hkv=2)
+    _run(xq, w, T, 3, 128, lens=[600, 253 + T], seed=Hq + T, dense=dense)
+
+
 def test_prefill_dense_source_and_rope(xq):
     w3 = xi.C3.scaled(B=2, L=330, d=512, Hq=4, Hkv=4)
     _run(xq, w3, 9, 0, 0, lens=[330, 100], dense=True)
