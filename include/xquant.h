@@ -122,6 +122,9 @@ xq_status_t xq_cl_accumulate(uint16_t *acc_bf16, const xq_cache_t *src, const in
  * of the fp16 range (the kernels take the factor out again, exactly), so a layer of uniformly tiny or
  * large weights loses nothing; within one head, entries more than 2^-29 below the head's largest are
  * rounded at 2^-40 of the largest.
+ * Size: d x 2 n_kv_heads head_dim 16-bit entries plus the column sums; twice that for groups of 128, for
+ * src_bits 8 and for src_bits 16, whose kernels read the weights in a second fragment order that is stored
+ * alongside the first (the query below is the authority).
  * xq_prepared_weights_bytes returns 0 for an unsupported combination.
  */
 size_t      xq_prepared_weights_bytes(const xq_attn_t *a, int32_t d, int32_t group, int32_t src_bits);
