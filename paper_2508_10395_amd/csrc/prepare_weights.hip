@@ -179,8 +179,10 @@ __global__ __launch_bounds__(256) void pack_main16_kernel(PrepArgs a, uint8_t* o
                 v[i] = f32_to_bf16_rne(wval(a, h, cs_ * 128 + cj * 32 + q * 8 + i, n));              // (exact: the weights are bf16)
                 continue;
             }
-            const int p = a.tab.code_of_slot[cj][i];
-            const int c = cs_ * 128 + q * 32 + p;
+            // groups of 128: quarter q unpacks unit q, tick cj is its k-step; groups of 64: tick cj is unit cj, quarter
+            // q its k-step (a tick then lies inside one group)
+            const int p = a.G == 64 ? a.tab.code_of_slot[q][i] : a.tab.code_of_slot[cj][i];
+            const int c = a.G == 64 ? cs_ * 128 + cj * 32 + p : cs_ * 128 + q * 32 + p;
             const float wv = ldexpf(wval(a, h, c, n), a.tab.wexp_of_code[p] + head_shift);          // exact: power-of-two scaling
             const _Float16 hv = (_Float16)fminf(fmaxf(wv, -65504.0f), 65504.0f);
             v[i] = (uint32_t)__builtin_bit_cast(uint16_t, hv);

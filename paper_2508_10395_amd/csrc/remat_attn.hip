@@ -685,19 +685,24 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
 __global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __restrict__ scale,
                                                               uint16_t* __restrict__ eT, int cap, int ng,
                                                               int ng_row, int tiles_per_seq, int bits, BatchI32 len,
-                                                              int meta_shift = 0)
+                                                              int meta_shift = 0, bool with_normaliser = false)
 {
     const int tile = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
     const int L = len.v[b];
     if (tile * TILE_TOKENS >= L) return;
     const long long row = (long long)b * cap + min(tile * TILE_TOKENS + t, L - 1);
     uint16_t* dst = eT + ((long long)b * tiles_per_seq + tile) * (long long)(ng + 1) * TILE_TOKENS + t;
+    uint32_t emax = 0;                                // (positive bf16 bit patterns order as integers)
     for (int g = 0; g < ng; ++g) {
         const uint32_t sb = scale[row * ng_row + (g >> meta_shift)];
         const uint32_t e = sb ? sb + ((uint32_t)(bits + F16_SUBNORMAL_EXP - F16_MANT_BITS) << 7) : 0x3F80u;
         dst[(long long)g * TILE_TOKENS] = (uint16_t)e;
+        emax = max(emax, e);
     }
-    dst[(long long)ng * TILE_TOKENS] = 0x3F80u;       // pad group (fetched, never used)
+    // spare group row (fetched with the last slab's scales, not used as a scale): 1, or on request the token's
+    // normaliser, the power of two at or above its largest effective scale
+    const uint32_t norm = (emax & 0x7F80u) + ((emax & 0x7Fu) ? 0x80u : 0u);
+    dst[(long long)ng * TILE_TOKENS] = with_normaliser ? (uint16_t)norm : (uint16_t)0x3F80u;
 }
 
 // ---- split-context combine: out[b][h][:] = sum_c w_c o_c / sum_c w_c l_c, w_c = 2^(m_c - M).

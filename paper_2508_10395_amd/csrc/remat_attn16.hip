@@ -1,4 +1,4 @@
-// Decode attention over a per-token X cache with groups of 128 codes, built on v_mfma_f32_16x16x32
+// Decode attention over a per-token X cache with groups of 128 codes (2-bit: also 64), built on v_mfma_f32_16x16x32
 // (Sec. 3.1 and the cost model of Sec. 3.4 in arxiv 2508.10395).  Same mathematics, same partials and the same
 // workgroup shape as remat_attn_coded_kernel<BITS, 128, MODE_ATTENTION> in remat_attn.hip -- eight waves, a
 // wave owns 32 tokens and all 256 columns of [Wk_h | Wv_h], codes enter the fp16 MFMA as subnormals, one
@@ -355,9 +355,21 @@ __device__ __forceinline__ void prefill_epilogue16(const RematParams& p, const T
     }
 }
 
-template <int BITS, int MODE>
+// G = 64 (2-bit codes only): "scales on the token operand".  With groups of 64 a tile would meet two group boundaries
+// per slab, and rescaling 128 accumulator registers twice per slab makes the loop wait for vector-instruction issue
+// (measured: no faster than the 32x32x16 kernel).  Instead the group's scale goes into the token fragment: tick j takes
+// the 32 codes of unit j of the slab (quarter q its k-step q, so that a tick lies inside one group; possible because the
+// 2-bit k-steps differ by a rotation only), and every operand dword is multiplied, right after the unpack, by the packed
+// fp16 factor f = 2^15 e_group / N_token, N_token = the power of two at or above the token's largest effective scale
+// (the pre-pass leaves it in the spare group row of the transposed scales).  A 2-bit code times an 8-bit significand is
+// exact in fp16, and a group 2^11 below the token's largest reaches the subnormal grid with an absolute error of 2^-24
+// of the largest: no Horner pass, no scale state in the loop, one scaling by N_token 2^-15 at the end.
+template <int BITS, int G, int MODE>
 __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParams p)
 {
+    static_assert(G == 128 || (G == 64 && BITS == 2), "group size");
+    constexpr int GPS = 128 / G;                       // groups per slab
+    constexpr int NCUR = G == 64 ? 4 : BITS;           // dwords of packed codes a lane keeps per slab and token half
     constexpr int ROW_SLAB_BYTES = 16 * BITS;          // packed bytes of 128 channels of one token
     constexpr int UNIT_BYTES = 4 * BITS;               // ... of a unit of 32 codes
     constexpr int NCI = 4 * BITS;                      // code-DMA wave instructions per slab per workgroup
@@ -398,7 +410,8 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     for (int s = 0; s < 2; ++s) {
         my_row[s] = wave * CHUNK_TOKENS + 16 * s + c16;
         moff[s] = (uint32_t)min(c.tile * TILE_TOKENS + my_row[s], c.len - 1) * (uint32_t)p.ng_row;
-        my_codes[s] = lds + LDS_CODES_OFF + my_row[s] * ROW_SLAB_BYTES + q * UNIT_BYTES;
+        // groups of 128: unit q; groups of 64: of every unit j the dword that holds its k-step q (2 bits: dword q / 2)
+        my_codes[s] = lds + LDS_CODES_OFF + my_row[s] * ROW_SLAB_BYTES + (G == 128 ? q * UNIT_BYTES : (q >> 1) * 4);
         my_scale[s] = reinterpret_cast<const uint16_t*>(lds + LDS_SCALES_OFF) + my_row[s];
     }
     // code DMA: 16-byte piece pc of the tile's slab image = (row pc / BITS, part pc % BITS);
@@ -421,19 +434,41 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
 
     uint4 af[8];                         // weight fragments, ring over slots (loaded AHEAD slots ahead)
     uint32_t ub[2][NT][4];               // token fragments, ring over ticks
-    uint32_t cur[2][BITS];               // packed codes (unit q) of the current slab, per token half
-    float E_prev[2], E_cur[2];           // effective scales of the previous and the current slab's group
-    float hr[2];                         // Horner factors E_prev / E_cur of the boundaries seen this slab
+    uint32_t cur[2][NCUR];               // packed codes of the current slab, per token half
+    float E_prev[2], E_cur[2];           // groups of 128: effective scales of the previous and the current slab's group
+    float hr[2];                         // ... and the Horner factors E_prev / E_cur of the boundaries seen this slab
+    // groups of 64: packed fp16 factors (f, f) of the slab's two groups per token half, for the slab whose codes are in
+    // cur; the token's normaliser and 2^15 / normaliser
+    uint32_t fac[2][2];
+    float tok_norm[2], tok_inv15[2];
+    // 2-bit codes, groups of 64: k-step q of a unit is its dword q / 2 rotated left by 6 and 2 (q even) or by 30 and
+    // 26 (q odd: a right shift by 2 and 6; what the rotation brings in falls outside the masks)
+    const int rot_a = (q & 1) ? 30 : 6, rot_b = (q & 1) ? 26 : 2;
 
     auto fetch_scales = [&](int sbuf, float (&e)[2]) XQ_INLINE_LAMBDA {
 #pragma unroll
         for (int s = 0; s < 2; ++s) e[s] = __uint_as_float((uint32_t)my_scale[s][sbuf * (LDS_SCALES_BYTES / 2)] << 16);
     };
+    // groups of 64: the factors of the slab whose scales are in buffer sbuf
+    auto fetch_factors = [&](int sbuf, uint32_t (&f)[2][2]) XQ_INLINE_LAMBDA {
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const float e = __uint_as_float((uint32_t)my_scale[s][sbuf * (LDS_SCALES_BYTES / 2) + g * TILE_TOKENS] << 16);
+                const _Float16 h = (_Float16)(e * tok_inv15[s]);            // exact: 8-bit significand, at most 2^15
+                const xq_f16x2 hh = {h, h};
+                f[s][g] = __builtin_bit_cast(uint32_t, hh);
+            }
+    };
     auto fetch_tokens = [&](int img) XQ_INLINE_LAMBDA {
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const uint8_t* src = my_codes[s] + img * IMG_BYTES;
-            if constexpr (BITS == 4) {
+            if constexpr (G == 64) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) cur[s][j] = *reinterpret_cast<const uint32_t*>(src + j * UNIT_BYTES);
+            } else if constexpr (BITS == 4) {
                 const uint4 v = *reinterpret_cast<const uint4*>(src);
                 cur[s][0] = v.x; cur[s][1] = v.y; cur[s][2] = v.z; cur[s][3] = v.w;
             } else if constexpr (BITS == 2) {
@@ -445,14 +480,26 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
             }
         }
     };
-    auto make_fragment = [&](auto S, auto J) XQ_INLINE_LAMBDA {           // tick J of the slab whose codes are in cur
+    // the 4 operand dwords of tick j of the slab whose codes are in cur (groups of 64: times the group's factor)
+    auto unpack_tick = [&](int s, int j, uint32_t (&t)[4]) XQ_INLINE_LAMBDA {
+        if constexpr (G == 128) {
+            unpack_kstep<BITS>(&cur[s][0], j, t);
+        } else {
+            const uint32_t d = cur[s][j];
+            const uint32_t a = __builtin_amdgcn_alignbit(d, d, 32 - rot_a), b = __builtin_amdgcn_alignbit(d, d, 32 - rot_b);
+            const uint32_t f = fac[s][j >> 1];
+            t[0] = pk_mul_f16(a & 0x00C000C0u, f); t[1] = pk_mul_f16(a & 0x03000300u, f);
+            t[2] = pk_mul_f16(b & 0x00C000C0u, f); t[3] = pk_mul_f16(b & 0x03000300u, f);
+        }
+    };
+    auto make_fragment = [&](auto S, auto J) XQ_INLINE_LAMBDA {
         constexpr int s = decltype(S)::value, j = decltype(J)::value;
-        unpack_kstep<BITS>(&cur[s][0], j, ub[s][j]);
+        unpack_tick(s, j, ub[s][j]);
     };
     auto make_half_fragment = [&](auto S, auto J, auto H) XQ_INLINE_LAMBDA {   // operand dwords 2 H, 2 H + 1 of it
         constexpr int s = decltype(S)::value, j = decltype(J)::value, h = decltype(H)::value;
         uint32_t t[4];
-        unpack_kstep<BITS>(&cur[s][0], j, t);
+        unpack_tick(s, j, t);
         ub[s][j][2 * h] = t[2 * h];
         ub[s][j][2 * h + 1] = t[2 * h + 1];
     };
@@ -466,7 +513,7 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
                          lds_base + LDS_CODES_OFF + (uint32_t)(img * IMG_BYTES) + (wave + 8 * step) * 1024);
         } else if (step == 2) {
             if (with_scales2 && wave == 7)
-                dma_b128(ebase + (long long)slab2 * 512, dma_voff, lds_base + LDS_SCALES_OFF + (uint32_t)(sbuf * LDS_SCALES_BYTES));
+                dma_b128(ebase + (long long)slab2 * (512 * GPS), dma_voff, lds_base + LDS_SCALES_OFF + (uint32_t)(sbuf * LDS_SCALES_BYTES));
         } else {
             dma_b128(wsrc + (long long)slab * SLAB_BYTES + (step - 3) * 8192, dma_voff, wdst + (step - 3) * 8192);
         }
@@ -498,6 +545,16 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
         return v;
     };
     const int slab_prev = p.n_main_slabs - 1;           // the walk is cyclic: the slab "before" slab 0
+    if constexpr (G == 64) {
+        // the tokens' normalisers (powers of two): the spare group row of the transposed scales
+        const uint16_t* nrm = reinterpret_cast<const uint16_t*>(ebase + (long long)p.ng * 512);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const uint32_t nb = (uint32_t)nrm[my_row[s]] << 16;
+            tok_norm[s] = __uint_as_float(nb);
+            tok_inv15[s] = __uint_as_float(0x7F000000u - nb + (15u << 23));   // 2^15 / normaliser, exactly
+        }
+    }
     issue_slab(wsrc + (long long)p.n_main_slabs * SLAB_BYTES, lds_w, dma_voff);        // correction slab 0 -> buffer 0
     dma_step(0, slab_prev, NIMG - 1, 0, false, 0, 0);                                  // predecessor codes -> last image
     dma_step(1, slab_prev, NIMG - 1, 0, false, 0, 0);
@@ -521,7 +578,8 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
         else issue_slab(wsrc, wdst, dma_voff);                                                   // the first main slab
         if (cs == 0) {
             fetch_tokens(NIMG - 1);
-            fetch_scales(2, E_prev);
+            if constexpr (G == 64) fetch_factors(2, fac);
+            else fetch_scales(2, E_prev);
         }
         const uint8_t* slab = my_slab + (cs & 1) * SLAB_BYTES;
         const int nj = min(NT, p.n_corr_ksteps - cs * NT);
@@ -574,18 +632,20 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     fetch_tokens(0);
-    fetch_scales(0, E_cur);
+    if constexpr (G == 64) fetch_factors(0, fac);
+    else fetch_scales(0, E_cur);
     {
         const uint8_t* slab0 = my_slab + par0 * SLAB_BYTES;
 #pragma unroll
         for (int sl = 0; sl < AHEAD; ++sl) af[sl] = *reinterpret_cast<const uint4*>(slab0 + sl * 1024);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            // (every tile starts in the predecessor's units: those without lag are rescaled at tick 0 like the others later)
-            const float r_prev = ldexpf(__builtin_amdgcn_rcpf(E_prev[s]), head_shift);
+            // (every tile starts in the predecessor's units: those without lag are rescaled at tick 0 like the others
+            // later; groups of 64: in the token's own units, 2^15 / normaliser, for the whole walk)
+            const float r_prev = G == 64 ? ldexpf(tok_inv15[s], head_shift) : ldexpf(__builtin_amdgcn_rcpf(E_prev[s]), head_shift);
 #pragma unroll
             for (int ct = 0; ct < 16; ++ct) acc[s][ct] *= r_prev;
-            hr[s] = E_prev[s] * __builtin_amdgcn_rcpf(E_cur[s]);
+            if constexpr (G == 128) hr[s] = E_prev[s] * __builtin_amdgcn_rcpf(E_cur[s]);
         }
     }
 
@@ -605,6 +665,7 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
         const uint8_t* slab_next = my_slab + ((it + 1 + par0) & 1) * SLAB_BYTES;
         float e_nxt[2] = {1.0f, 1.0f};                       // scales of the next slab (landed one slab ago)
         float hr_n[2] = {1.0f, 1.0f};                        // boundary factors of the next iteration
+        uint32_t fac_nxt[2][2] = {{fac[0][0], fac[0][1]}, {fac[1][0], fac[1][1]}};   // groups of 64: the next slab's factors
         __builtin_amdgcn_sched_barrier(0);
 
         static_for<0, NT * 16>([&](auto SIDX) XQ_INLINE_LAMBDA {
@@ -639,14 +700,19 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
             if constexpr (j + 1 < NT && ct >= 12 - 4 * j && ct < 16 - 4 * j)
                 make_half_fragment(std::integral_constant<int, ((ct - (12 - 4 * j)) >> 1)>{}, std::integral_constant<int, j + 1>{}, std::integral_constant<int, ((ct - (12 - 4 * j)) & 1)>{});
             // the next slab's scales are in LDS since the previous slab
-            if constexpr (sidx == 40) { if (more_main) fetch_scales((it + 1) & 1, e_nxt); }
-            if constexpr (sidx == 58) {
+            if constexpr (sidx == 40) {
+                if (more_main) {
+                    if constexpr (G == 64) fetch_factors((it + 1) & 1, fac_nxt);
+                    else fetch_scales((it + 1) & 1, e_nxt);
+                }
+            }
+            if constexpr (G == 128 && sidx == 58) {
                 if (more_main) { hr_n[0] = E_cur[0] * __builtin_amdgcn_rcpf(e_nxt[0]); hr_n[1] = E_cur[1] * __builtin_amdgcn_rcpf(e_nxt[1]); }
             }
             // Horner: the four tiles that enter this slab's group at tick jj (tiles 4 (3 - jj) + i) are rescaled half
             // a tile per slot in the eight slots 12 jj + 4 + [0, 8): after the tile's MFMAs of the previous tick
             // have long retired, before its slot of tick jj, and in none of the slots that unpack codes
-            {
+            if constexpr (G == 128) {
                 constexpr int r = sidx - 4, jj = r / 12, o = r % 12;
                 if constexpr (sidx >= 4 && jj < NT && o < 8) {
                     constexpr int s = o & 1, ct2 = 4 * (3 - jj) + (o >> 1);
@@ -660,13 +726,17 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
         });
         if (more_main) {
 #pragma unroll
-            for (int s = 0; s < 2; ++s) { E_prev[s] = E_cur[s]; E_cur[s] = e_nxt[s]; hr[s] = hr_n[s]; }
+            for (int s = 0; s < 2; ++s) {
+                if constexpr (G == 64) { fac[s][0] = fac_nxt[s][0]; fac[s][1] = fac_nxt[s][1]; }
+                else { E_prev[s] = E_cur[s]; E_cur[s] = e_nxt[s]; hr[s] = hr_n[s]; }
+            }
         }
     }
-    // every tile has ended in the last slab's group; leave its scale: the accumulator is K | V
+    // every tile has ended in the last slab's group (groups of 64: the token's units all along); leave that scale:
+    // the accumulator is K | V
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-        const float f = ldexpf(E_cur[s], -head_shift);
+        const float f = G == 64 ? ldexpf(tok_norm[s], -head_shift - 15) : ldexpf(E_cur[s], -head_shift);
 #pragma unroll
         for (int ct = 0; ct < 16; ++ct) acc[s][ct] *= f;
     }
@@ -808,7 +878,7 @@ __global__ __launch_bounds__(512) void remat_attn_dense16_kernel(const RematPara
 static hipError_t allow_lds_once(const void* k, int lds_bytes, int slot)
 {
     static std::mutex mu;
-    static bool done[64][10];                     // [device][kernel: bits (+ 4: prefill), 5 / 9: dense]
+    static bool done[64][10];                     // [device][kernel: 2 (format) + prefill; 8, 9: dense]
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
@@ -830,27 +900,26 @@ hipError_t launch_tile16_dense(const RematParams& p, int grid, hipStream_t s, bo
 {
     typedef void (*Kernel)(const RematParams);
     const Kernel k = prefill ? remat_attn_dense16_kernel<MODE_PREFILL> : remat_attn_dense16_kernel<MODE_ATTENTION>;
-    hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), LDS_DENSE16_TOTAL, prefill ? 9 : 5);
+    hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), LDS_DENSE16_TOTAL, prefill ? 9 : 8);
     if (e != hipSuccess) return e;
     k<<<dim3(grid), dim3(512), LDS_DENSE16_TOTAL, s>>>(p);
     return hipGetLastError();
 }
 
-hipError_t launch_tile16(int bits, const RematParams& p, int grid, hipStream_t s, bool prefill)
+hipError_t launch_tile16(int bits, int G, const RematParams& p, int grid, hipStream_t s, bool prefill)
 {
     typedef void (*Kernel)(const RematParams);
     Kernel k = nullptr;
-    switch (bits * 2 + (prefill ? 1 : 0)) {
-        case 4: k = remat_attn_tile16_kernel<2, MODE_ATTENTION>; break;
-        case 5: k = remat_attn_tile16_kernel<2, MODE_PREFILL>; break;
-        case 6: k = remat_attn_tile16_kernel<3, MODE_ATTENTION>; break;
-        case 7: k = remat_attn_tile16_kernel<3, MODE_PREFILL>; break;
-        case 8: k = remat_attn_tile16_kernel<4, MODE_ATTENTION>; break;
-        case 9: k = remat_attn_tile16_kernel<4, MODE_PREFILL>; break;
+    int slot = -1;
+    switch (bits * 1000 + G) {
+        case 2128: k = prefill ? remat_attn_tile16_kernel<2, 128, MODE_PREFILL> : remat_attn_tile16_kernel<2, 128, MODE_ATTENTION>; slot = 0; break;
+        case 3128: k = prefill ? remat_attn_tile16_kernel<3, 128, MODE_PREFILL> : remat_attn_tile16_kernel<3, 128, MODE_ATTENTION>; slot = 1; break;
+        case 4128: k = prefill ? remat_attn_tile16_kernel<4, 128, MODE_PREFILL> : remat_attn_tile16_kernel<4, 128, MODE_ATTENTION>; slot = 2; break;
+        case 2064: k = prefill ? remat_attn_tile16_kernel<2, 64, MODE_PREFILL> : remat_attn_tile16_kernel<2, 64, MODE_ATTENTION>; slot = 3; break;
         default: return hipErrorInvalidValue;
     }
     const int lds_bytes = lds_coded_total(bits);
-    const hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), lds_bytes, bits + (prefill ? 4 : 0));
+    const hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), lds_bytes, 2 * slot + (prefill ? 1 : 0));
     if (e != hipSuccess) return e;
     k<<<dim3(grid), dim3(512), lds_bytes, s>>>(p);
     return hipGetLastError();

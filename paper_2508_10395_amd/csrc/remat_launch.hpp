@@ -101,7 +101,7 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
 
 // the kernels on 16 x 16 x 32 MFMAs (remat_attn16.hip): groups of 128 codes or the dense source; prefill = the
 // matrix-core epilogue for many query rows instead of the per-query-head vector epilogue
-hipError_t launch_tile16(int bits, const RematParams& p, int grid, hipStream_t s, bool prefill);
+hipError_t launch_tile16(int bits, int G, const RematParams& p, int grid, hipStream_t s, bool prefill);
 hipError_t launch_tile16_dense(const RematParams& p, int grid, hipStream_t s, bool prefill);
 
 // query heads per KV head from which the decode step goes through the matrix-core epilogue (the
@@ -140,14 +140,14 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
     hipError_t e = hipErrorInvalidValue;
     if (xc) {
         scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
-            xc->scale, eT, cap, L.ng, p.ng_row, p.tiles_per_seq, bits, len, p.meta_shift);
+            xc->scale, eT, cap, L.ng, p.ng_row, p.tiles_per_seq, bits, len, p.meta_shift, L.t16_bytes && G == 64);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         if (L.t16_bytes) {                                   // the stream of 16-column fragments and its kernel
             p.wprep += L.t16_offset;
             p.head_bytes = (long long)L.t16_head_bytes;
             p.n_corr_ksteps = L.t16_n_corr_ticks;
-            e = launch_tile16(bits, p, grid, s, false);
+            e = launch_tile16(bits, G, p, grid, s, false);
         } else {
             e = launch_coded<MODE_ATTENTION>(bits, G, p, grid, s);
         }
@@ -215,14 +215,15 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
     hipError_t e;
     if (xc) {
         scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
-            xc->scale, const_cast<uint16_t*>(p.eT), cap, L.ng, p.ng_row, p.tiles_per_seq, bits, len, p.meta_shift);
+            xc->scale, const_cast<uint16_t*>(p.eT), cap, L.ng, p.ng_row, p.tiles_per_seq, bits, len, p.meta_shift,
+            L.t16_bytes && G == 64);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         if (L.t16_bytes) {                                   // the stream of 16-column fragments and its kernel
             p.wprep += L.t16_offset;
             p.head_bytes = (long long)L.t16_head_bytes;
             p.n_corr_ksteps = L.t16_n_corr_ticks;
-            e = launch_tile16(bits, p, grid, s, true);
+            e = launch_tile16(bits, G, p, grid, s, true);
         } else {
             e = launch_coded<MODE_PREFILL>(bits, G, p, grid, s);
         }

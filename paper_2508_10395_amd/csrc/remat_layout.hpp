@@ -76,11 +76,12 @@ inline WPrepLayout make_wprep_layout(int d, int G, int bits, int Hkv)
 // other widths.
 //
 // Second stream ("16-column fragments"), for the kernels built on v_mfma_f32_16x16x32 (remat_attn16.hip; coded
-// sources with groups of 128 codes and the dense source, decode and prefill).  With groups of 64 there is none: a
-// tick takes 8 codes from each of the slab's four units of 32, so it straddles the slab's two groups.  Same slabs of 64 KiB, but a slab is 4 ticks of 32
+// sources with groups of 128 codes -- 2-bit codes also with groups of 64 -- and the dense source, decode and prefill).  Same slabs of 64 KiB, but a slab is 4 ticks of 32
 // contraction indices x 16 column tiles:  [tick 4][tile 16][lane 64][8 fp16], one 1 KiB 16 x 32 fragment per
 // (tick, tile); lane l feeds column 16 tile + l % 16 and, with quarter q = l / 16, the slots
 //   channel = 128 s' + 32 q + code_of_slot[j'][i]      (unit q of the slab's 128 codes, k-step j' of the unit)
+// (groups of 64: channel = 128 s' + 32 j' + code_of_slot[q][i]: tick j' is unit j' of the slab, quarter q its k-step
+// q, so that a tick stays inside one group)
 // of the k32-step kappa = 4 s' + j' that the position holds: tile ct runs TILE16_LAG(ct) ticks behind the walk,
 // so position (slab s, tick j, tile ct) holds kappa = (4 s + j - lag) mod (d / 32).  Correction slabs (bf16):
 // contraction index 32 kk + 8 q + i -> term, group as in the first stream.  It follows the first stream's
@@ -92,7 +93,7 @@ constexpr int tile16_lag(int ct) { return 3 - (ct >> 2); }
 inline WPrepLayout make_wprep_layout_for_cache(int d, int G, int bits, int Hkv)
 {
     WPrepLayout L = bits == 8 ? make_wprep_layout(2 * d, 128, 4, Hkv) : make_wprep_layout(d, bits == 16 ? 128 : G, bits, Hkv);
-    if (L.bits == 16 || L.G == 128) {
+    if (L.bits == 16 || L.G == 128 || (L.G == 64 && L.bits == 2)) {
         L.t16_n_corr_ticks = L.bits == 16 ? 0 : (N_CORR_TERMS * L.ng_pad + 31) / 32;
         L.t16_n_corr_slabs = (L.t16_n_corr_ticks + TILE16_TICKS - 1) / TILE16_TICKS;
         L.t16_head_bytes = (size_t)(L.n_main_slabs + L.t16_n_corr_slabs) * SLAB_BYTES;

@@ -102,6 +102,10 @@ def test_constant_groups_and_wide_scale_range(xq):
     x[0, 7, :] = -1.25                           # a fully constant token
     _run_xquant(xq, w, 3, 128, [256], x_bits=xi.to_bf16_bits(x))
     _run_xquant(xq, w, 4, 64, [256], x_bits=xi.to_bf16_bits(x))
+    # 2-bit codes with groups of 64 carry the group's scale in the fp16 token operand, normalised by the token's
+    # largest: a token whose groups differ by 10^6 and more puts the small ones on the fp16 subnormal grid
+    x[0, 2::4, 64:128] *= 1e-4
+    _run_xquant(xq, w, 2, 64, [256], x_bits=xi.to_bf16_bits(x))
 
 
 @pytest.mark.parametrize("weight_exp", [-12, 6, -30])
