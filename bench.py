@@ -605,7 +605,7 @@ def main():
                                "then fused dequant-remat-attention",
                    "batch": B, "context": L, "d": d, "heads": Hq, "kv_heads": Hkv, "bits": bits, "group": G,
                    "settle_launches": args.settle},
-        "roofline": {"bound": "mfma", "kernel": "remat_attn_tile16_kernel<3,0> (events bracket xq_remat_attn_decode: + scale pre-pass and combine, ~1%)",
+        "roofline": {"bound": "mfma", "kernel": "remat_attn_tile16_kernel<3,128,0> (events bracket xq_remat_attn_decode: + scale pre-pass and combine, ~1%)",
                      "achieved": achieved_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "traffic_measured_at_commit": K3_HBM_BYTES_MEASURED_AT,
