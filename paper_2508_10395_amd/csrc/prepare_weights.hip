@@ -46,19 +46,19 @@ __device__ __forceinline__ float wval(const PrepArgs& a, int h, int c, int n)
 
 // shift[h] = 12 - ceil(log2(max |w|)) over the head's d x 256 entries: max |w| 2^shift <= 2^12, and with the
 // largest per-slot factor of the unpack table (2^3) the stream's largest entry is at most 2^15.
-__global__ __launch_bounds__(256) void shift_kernel(PrepArgs a)
+__global__ __launch_bounds__(1024) void shift_kernel(PrepArgs a)
 {
-    __shared__ uint32_t red[256];
-    const int h = blockIdx.x, n = threadIdx.x;
+    __shared__ uint32_t red[1024];
+    const int h = blockIdx.x, n = threadIdx.x & 255, part = threadIdx.x >> 8;     // column, quarter of the rows
     uint32_t mx = 0;                                      // |w| as fp32 bits: ordered as integers
-    for (int c = 0; c < a.d; ++c) mx = max(mx, __float_as_uint(wval(a, h, c, n)) & 0x7FFFFFFFu);
-    red[n] = mx;
+    for (int c = part; c < a.d; c += 4) mx = max(mx, __float_as_uint(wval(a, h, c, n)) & 0x7FFFFFFFu);
+    red[threadIdx.x] = mx;
     __syncthreads();
-    for (int st = 128; st > 0; st >>= 1) {
-        if (n < st) red[n] = max(red[n], red[n + st]);
+    for (int st = 512; st > 0; st >>= 1) {
+        if ((int)threadIdx.x < st) red[threadIdx.x] = max(red[threadIdx.x], red[threadIdx.x + st]);
         __syncthreads();
     }
-    if (n == 0) {
+    if (threadIdx.x == 0) {
         int sh = 0;
         if (red[0]) {
             const int e = (int)(red[0] >> 23) - 127;      // max = m 2^e, 1 <= m < 2 (subnormals: e = -127, m < 1)
@@ -245,7 +245,7 @@ hipError_t run_prepare_weights(const WPrepLayout& L, const uint16_t* Wk, const u
     a.n_main_slabs = L.n_main_slabs; a.ng = L.ng; a.ng_pad = L.ng_pad; a.n_corr_slabs = L.n_corr_slabs;
     a.head_bytes = (long long)L.head_bytes;
     if (!unpack_table_for(L.bits, &a.tab)) return hipErrorInvalidValue;
-    if (L.bits != 16) shift_kernel<<<dim3(L.Hkv), dim3(256), 0, s>>>(a);
+    if (L.bits != 16) shift_kernel<<<dim3(L.Hkv), dim3(1024), 0, s>>>(a);
     pack_main_kernel<<<dim3(L.n_main_slabs, L.Hkv), dim3(256), 0, s>>>(a);
     if (L.bits != 16) {
         colsum_kernel<<<dim3(L.ng, L.Hkv), dim3(256), 0, s>>>(a);

@@ -1,5 +1,7 @@
-// Decode attention over a per-token X cache with groups of 128 codes (2-bit: also 64), built on v_mfma_f32_16x16x32
-// (Sec. 3.1 and the cost model of Sec. 3.4 in arxiv 2508.10395).  Same mathematics, same partials and the same
+// Attention over a per-token X cache with groups of 128 codes (2-bit: also 64) or over the bf16 cross-layer
+// accumulator, built on v_mfma_f32_16x16x32: decode (one query row per head) and, through a matrix-core epilogue,
+// prefill chunks and decode with many query heads per KV head
+// (Sec. 3.1, Sec. 3.2, App. A and the cost model of Sec. 3.4 in arxiv 2508.10395).  Same mathematics, same partials and the same
 // workgroup shape as remat_attn_coded_kernel<BITS, 128, MODE_ATTENTION> in remat_attn.hip -- eight waves, a
 // wave owns 32 tokens and all 256 columns of [Wk_h | Wv_h], codes enter the fp16 MFMA as subnormals, one
 // accumulator carried through the groups by Horner rescaling, zero-points through a few bf16 k-steps -- but
