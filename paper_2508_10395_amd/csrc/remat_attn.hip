@@ -51,8 +51,9 @@ namespace xq {
 // 256 hidden channels); or attention for many (query, head) rows per KV head through the
 // matrix-core epilogue (prefill chunks, and decode when a KV head serves several query heads).
 //
-// MODE_ATTENTION_PC reads a per-channel cache (Sec. 3.3.1: one scale and zero-point per channel and
-// block of 64 or 128 tokens).  The scale now varies along the contraction, so it moves to the token
+// MODE_SCORES_PC (pass 1 of the latent path with per-channel keys; the decode attention over a per-channel X
+// cache, MODE_ATTENTION_PC, runs the same scheme on the 16 x 16 tiles of remat_attn16.hip) reads a per-channel
+// cache (Sec. 3.3.1: one scale and zero-point per channel and block of 64 or 128 tokens).  The scale now varies along the contraction, so it moves to the token
 // operand: each unpacked operand dword is multiplied (packed fp16) by the block's factors
 // scale * 2^(15 - E_blk) of its two channels -- an 8-bit significand times a code of at most 3 bits
 // is exact in fp16 (4-bit codes enter as code - 8, which makes their products exact too: the

@@ -1,7 +1,7 @@
-// Attention over a per-token X cache with groups of 128 codes (2-bit: also 64) or over the bf16 cross-layer
-// accumulator, built on v_mfma_f32_16x16x32: decode (one query row per head) and, through a matrix-core epilogue,
-// prefill chunks and decode with many query heads per KV head
-// (Sec. 3.1, Sec. 3.2, App. A and the cost model of Sec. 3.4 in arxiv 2508.10395).  Same mathematics, same partials and the same
+// Attention over a per-token X cache with groups of 128 codes (2-bit: also 64), over the complete blocks of a
+// per-channel X cache, or over the bf16 cross-layer accumulator, built on v_mfma_f32_16x16x32: decode (one query row
+// per head) and, through a matrix-core epilogue, prefill chunks and decode with many query heads per KV head
+// (Sec. 3.1, Sec. 3.2, Sec. 3.3.1, App. A and the cost model of Sec. 3.4 in arxiv 2508.10395).  Same mathematics, same partials and the same
 // workgroup shape as remat_attn_coded_kernel<BITS, 128, MODE_ATTENTION> in remat_attn.hip -- eight waves, a
 // wave owns 32 tokens and all 256 columns of [Wk_h | Wv_h], codes enter the fp16 MFMA as subnormals, one
 // accumulator carried through the groups by Horner rescaling, zero-points through a few bf16 k-steps -- but
@@ -366,10 +366,21 @@ __device__ __forceinline__ void prefill_epilogue16(const RematParams& p, const T
 // (the pre-pass leaves it in the spare group row of the transposed scales).  A 2-bit code times an 8-bit significand is
 // exact in fp16, and a group 2^11 below the token's largest reaches the subnormal grid with an absolute error of 2^-24
 // of the largest: no Horner pass, no scale state in the loop, one scaling by N_token 2^-15 at the end.
+//
+// MODE_ATTENTION_PC (per-channel cache, Sec. 3.3.1: one scale and zero-point per channel and block of 64 or 128
+// tokens; codes packed per token row as in a per-token cache, walked in the layout of groups of 128).  The scale
+// varies along the contraction, so it too goes to the token operand: every unpacked operand dword is multiplied
+// (packed fp16) by the block's factors scale 2^(15 - E_blk) of its two channels -- exact for codes of at most 3 bits;
+// 4-bit codes enter as code - 8, whose products are exact too, and the block-constant 8 scale W term joins the
+// zero-point term.  A wave's 32 tokens lie in one block, so all lanes of a quarter read the same factors from a 1 KiB
+// image per slab that the scale DMA brings into three rotating buffers.  No Horner pass, no correction phase: the
+// epilogue scales by the block's power of two and adds z_blk [Wk_h | Wv_h], which a pre-pass has left in memory.
 template <int BITS, int G, int MODE>
 __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParams p)
 {
     static_assert(G == 128 || (G == 64 && BITS == 2), "group size");
+    constexpr bool PC = MODE == MODE_ATTENTION_PC;     // per-channel source: block factors on the token operand
+    static_assert(!PC || G == 128, "the per-channel source unpacks like groups of 128");
     constexpr int GPS = 128 / G;                       // groups per slab
     constexpr int NCUR = G == 64 ? 4 : BITS;           // dwords of packed codes a lane keeps per slab and token half
     constexpr int ROW_SLAB_BYTES = 16 * BITS;          // packed bytes of 128 channels of one token
@@ -389,7 +400,9 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     const int lane = c.lane, wave = c.wave;
     const int c16 = lane & 15, q = lane >> 4;
 
-    const int n_corr_slabs = (p.n_corr_ksteps + NT - 1) / NT;            // (n_corr_ksteps counts ticks here)
+    // (n_corr_ksteps counts ticks here; the per-channel source has no correction phase: its zero-point term
+    // comes from a pre-pass)
+    const int n_corr_slabs = PC ? 0 : (p.n_corr_ksteps + NT - 1) / NT;
     const int head_shift = p.head_shift[c.hk];         // the head's stream holds its weights times 2^head_shift
     const uint8_t* wsrc = p.wprep + (long long)c.hk * p.head_bytes + wave * 1024;   // this wave's DMA share
     const uint32_t dma_voff = (uint32_t)lane * 16u;
@@ -402,8 +415,11 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     const uint32_t row_bytes = (uint32_t)(p.row_d * BITS / 8);
     const uint8_t* cbase = p.codes + seq_row0 * row_bytes;
     const uint16_t* zbase = p.zero + seq_row0 * p.ng_row;
+    // per-token source: effective scales, GPS * 512 bytes per slab; per-channel: one 1 KiB factor image per slab
+    constexpr int E_SLAB_BYTES = PC ? LDS_SCALES_BYTES : 512 * GPS;
     const uint8_t* ebase = reinterpret_cast<const uint8_t*>(p.eT) +
-                           ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.ng + 1) * 512;
+                           (PC ? ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.n_main_slabs + 1) * LDS_SCALES_BYTES
+                               : ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.ng + 1) * 512);
     int my_row[2];
     uint32_t moff[2];
     const uint8_t* my_codes[2];
@@ -446,6 +462,14 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     // 2-bit codes, groups of 64: k-step q of a unit is its dword q / 2 rotated left by 6 and 2 (q even) or by 30 and
     // 26 (q odd: a right shift by 2 and 6; what the rotation brings in falls outside the masks)
     const int rot_a = (q & 1) ? 30 : 6, rot_b = (q & 1) ? 26 : 2;
+    // per-channel source: the block's factors scale 2^(15 - E_blk) of this quarter's channels, in the order the operand
+    // dwords hold them, from the slab's image in a scale buffer ([block of the tile][tick][quarter][8 fp16]: every lane
+    // of a quarter reads the same 16 bytes); pcf = those of the tick whose fragments are made next
+    const uint8_t* my_factors = lds + LDS_SCALES_OFF + (PC ? ((wave * CHUNK_TOKENS) / p.pc_block) * 256 + q * 16 : 0);
+    uint4 pcf = {0u, 0u, 0u, 0u};
+    auto fetch_tick_factors = [&](int sbuf, int j) XQ_INLINE_LAMBDA {
+        pcf = *reinterpret_cast<const uint4*>(my_factors + sbuf * LDS_SCALES_BYTES + j * 64);
+    };
 
     auto fetch_scales = [&](int sbuf, float (&e)[2]) XQ_INLINE_LAMBDA {
 #pragma unroll
@@ -484,7 +508,20 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     };
     // the 4 operand dwords of tick j of the slab whose codes are in cur (groups of 64: times the group's factor)
     auto unpack_tick = [&](int s, int j, uint32_t (&t)[4]) XQ_INLINE_LAMBDA {
-        if constexpr (G == 128) {
+        if constexpr (PC) {
+            unpack_kstep<BITS>(&cur[s][0], j, t);
+            if constexpr (BITS == 4) {
+                // a 4-bit code times an 8-bit significand needs 12 bits; (code - 8) times it needs 11 and is exact in
+                // fp16.  All 4-bit fields sit at mantissa offset 6, so 8 is the subnormal 2^-15 in both halves; the
+                // 8 * scale * W that this takes out is the same for every token of the block and comes back with
+                // the zero-point term.
+                constexpr uint32_t MINUS_EIGHT = 0x82008200u;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) t[i] = pk_add_f16(t[i], MINUS_EIGHT);
+            }
+            t[0] = pk_mul_f16(t[0], pcf.x); t[1] = pk_mul_f16(t[1], pcf.y);
+            t[2] = pk_mul_f16(t[2], pcf.z); t[3] = pk_mul_f16(t[3], pcf.w);
+        } else if constexpr (G == 128) {
             unpack_kstep<BITS>(&cur[s][0], j, t);
         } else {
             const uint32_t d = cur[s][j];
@@ -515,7 +552,7 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
                          lds_base + LDS_CODES_OFF + (uint32_t)(img * IMG_BYTES) + (wave + 8 * step) * 1024);
         } else if (step == 2) {
             if (with_scales2 && wave == 7)
-                dma_b128(ebase + (long long)slab2 * (512 * GPS), dma_voff, lds_base + LDS_SCALES_OFF + (uint32_t)(sbuf * LDS_SCALES_BYTES));
+                dma_b128(ebase + (long long)slab2 * E_SLAB_BYTES, dma_voff, lds_base + LDS_SCALES_OFF + (uint32_t)(sbuf * LDS_SCALES_BYTES));
         } else {
             dma_b128(wsrc + (long long)slab * SLAB_BYTES + (step - 3) * 8192, dma_voff, wdst + (step - 3) * 8192);
         }
@@ -557,7 +594,8 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
             tok_inv15[s] = __uint_as_float(0x7F000000u - nb + (15u << 23));   // 2^15 / normaliser, exactly
         }
     }
-    issue_slab(wsrc + (long long)p.n_main_slabs * SLAB_BYTES, lds_w, dma_voff);        // correction slab 0 -> buffer 0
+    if constexpr (PC) issue_slab(wsrc, lds_w, dma_voff);                               // the first main slab -> buffer 0
+    else issue_slab(wsrc + (long long)p.n_main_slabs * SLAB_BYTES, lds_w, dma_voff);   // correction slab 0 -> buffer 0
     dma_step(0, slab_prev, NIMG - 1, 0, false, 0, 0);                                  // predecessor codes -> last image
     dma_step(1, slab_prev, NIMG - 1, 0, false, 0, 0);
     dma_step(2, 0, 0, slab_prev, true, 2, 0);                                          // its scales -> scale buffer 2
@@ -568,10 +606,22 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
         dma_step(1, 0, 0, 0, false, 0, 0);
     }
     uint4 mfr[2][NT];
+    if constexpr (PC) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        fetch_tokens(NIMG - 1);
+        if constexpr (NIMG == 1) {
+            // every wave now holds its predecessor codes in registers: the first slab's codes may overwrite the only image
+            __syncthreads();
+            dma_step(0, 0, 0, 0, false, 0, 0);
+            dma_step(1, 0, 0, 0, false, 0, 0);
+        }
+    } else {
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+        for (int s = 0; s < 2; ++s)
 #pragma unroll
-        for (int j = 0; j < NT; ++j) mfr[s][j] = load_meta(s, j);
+            for (int j = 0; j < NT; ++j) mfr[s][j] = load_meta(s, j);
+    }
     for (int cs = 0; cs < n_corr_slabs; ++cs) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
@@ -627,6 +677,7 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     // Set-up: the ring's lagging fragments are ticks 1..3 of the predecessor slab, in whose group the lagging
     // tiles start; the accumulators (holding the correction in units of 1) are brought to those scales.
     static_for<1, NT>([&](auto J) XQ_INLINE_LAMBDA {
+        if constexpr (PC) fetch_tick_factors(2, decltype(J)::value);       // (the predecessor slab's factors wait in buffer 2)
         make_fragment(std::integral_constant<int, 0>{}, J);
         make_fragment(std::integral_constant<int, 1>{}, J);
     });
@@ -634,7 +685,8 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     fetch_tokens(0);
-    if constexpr (G == 64) fetch_factors(0, fac);
+    if constexpr (PC) fetch_tick_factors(0, 0);
+    else if constexpr (G == 64) fetch_factors(0, fac);
     else fetch_scales(0, E_cur);
     {
         const uint8_t* slab0 = my_slab + par0 * SLAB_BYTES;
@@ -644,10 +696,12 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
         for (int s = 0; s < 2; ++s) {
             // (every tile starts in the predecessor's units: those without lag are rescaled at tick 0 like the others
             // later; groups of 64: in the token's own units, 2^15 / normaliser, for the whole walk)
-            const float r_prev = G == 64 ? ldexpf(tok_inv15[s], head_shift) : ldexpf(__builtin_amdgcn_rcpf(E_prev[s]), head_shift);
+            if constexpr (!PC) {
+                const float r_prev = G == 64 ? ldexpf(tok_inv15[s], head_shift) : ldexpf(__builtin_amdgcn_rcpf(E_prev[s]), head_shift);
 #pragma unroll
-            for (int ct = 0; ct < 16; ++ct) acc[s][ct] *= r_prev;
-            if constexpr (G == 128) hr[s] = E_prev[s] * __builtin_amdgcn_rcpf(E_cur[s]);
+                for (int ct = 0; ct < 16; ++ct) acc[s][ct] *= r_prev;
+                if constexpr (G == 128) hr[s] = E_prev[s] * __builtin_amdgcn_rcpf(E_cur[s]);
+            }
         }
     }
 
@@ -668,6 +722,10 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
         float e_nxt[2] = {1.0f, 1.0f};                       // scales of the next slab (landed one slab ago)
         float hr_n[2] = {1.0f, 1.0f};                        // boundary factors of the next iteration
         uint32_t fac_nxt[2][2] = {{fac[0][0], fac[0][1]}, {fac[1][0], fac[1][1]}};   // groups of 64: the next slab's factors
+        // scale buffers: per-token source, slab s in buffer s & 1 (its scales are taken into registers one slab ahead);
+        // per-channel source, slab s in buffer s % 3 (its factors are read all through its own iteration)
+        const int sb_dma = PC ? (it + 2) % 3 : (it & 1);
+        const int sb_cur = it % 3, sb_nxt = (it + 1) % 3;
         __builtin_amdgcn_sched_barrier(0);
 
         static_for<0, NT * 16>([&](auto SIDX) XQ_INLINE_LAMBDA {
@@ -683,7 +741,7 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
 
             // DMA of the next slab: 11 steps per wave, one every other slot
             if constexpr ((sidx >> 1) < 11 && (sidx & 1) == 0)
-                dma_step(sidx >> 1, s_next, img_next, s_next2, true, it & 1, wdst);
+                dma_step(sidx >> 1, s_next, img_next, s_next2, true, sb_dma, wdst);
             // the old codes are no longer needed: wait until the next slab has landed for everyone,
             // then take the next slab's codes
             if constexpr (sidx == 64 - AHEAD) {               // (after the last read of this slab's weights, before the first of the next's)
@@ -698,23 +756,26 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
             // rescale nothing.  Tick j + 1's ring entry was last read by tick j's tiles 0-3 (lag 3) and is first
             // read by tick j + 1's tiles 12-15; tick 0's is made in the slab's first four slots, from the codes
             // taken out of LDS at the end of the previous slab.
+            // (per-channel source: the tick's factors come out of LDS four slots before its first half fragment)
+            if constexpr (PC && j + 1 < NT && ct == 8 - 4 * j) fetch_tick_factors(sb_cur, j + 1);
+            if constexpr (PC && sidx == 61) fetch_tick_factors(sb_nxt, 0);
             if constexpr (sidx < 4) make_half_fragment(std::integral_constant<int, (sidx >> 1)>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, (sidx & 1)>{});
             if constexpr (j + 1 < NT && ct >= 12 - 4 * j && ct < 16 - 4 * j)
                 make_half_fragment(std::integral_constant<int, ((ct - (12 - 4 * j)) >> 1)>{}, std::integral_constant<int, j + 1>{}, std::integral_constant<int, ((ct - (12 - 4 * j)) & 1)>{});
             // the next slab's scales are in LDS since the previous slab
-            if constexpr (sidx == 40) {
+            if constexpr (!PC && sidx == 40) {
                 if (more_main) {
                     if constexpr (G == 64) fetch_factors((it + 1) & 1, fac_nxt);
                     else fetch_scales((it + 1) & 1, e_nxt);
                 }
             }
-            if constexpr (G == 128 && sidx == 58) {
+            if constexpr (G == 128 && !PC && sidx == 58) {
                 if (more_main) { hr_n[0] = E_cur[0] * __builtin_amdgcn_rcpf(e_nxt[0]); hr_n[1] = E_cur[1] * __builtin_amdgcn_rcpf(e_nxt[1]); }
             }
             // Horner: the four tiles that enter this slab's group at tick jj (tiles 4 (3 - jj) + i) are rescaled half
             // a tile per slot in the eight slots 12 jj + 4 + [0, 8): after the tile's MFMAs of the previous tick
             // have long retired, before its slot of tick jj, and in none of the slots that unpack codes
-            if constexpr (G == 128) {
+            if constexpr (G == 128 && !PC) {
                 constexpr int r = sidx - 4, jj = r / 12, o = r % 12;
                 if constexpr (sidx >= 4 && jj < NT && o < 8) {
                     constexpr int s = o & 1, ct2 = 4 * (3 - jj) + (o >> 1);
@@ -726,7 +787,7 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
             }
             __builtin_amdgcn_sched_barrier(0);
         });
-        if (more_main) {
+        if (more_main && !PC) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 if constexpr (G == 64) { fac[s][0] = fac_nxt[s][0]; fac[s][1] = fac_nxt[s][1]; }
@@ -736,11 +797,30 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     }
     // every tile has ended in the last slab's group (groups of 64: the token's units all along); leave that scale:
     // the accumulator is K | V
+    if constexpr (PC) {
+        // K | V = accumulator * 2^(E_blk + bits - 1) + z_blk [Wk_h | Wv_h]; waves past len take the last block's
+        const int blk = min((c.tile * TILE_TOKENS + wave * CHUNK_TOKENS) / p.pc_block, (c.len - 1) / p.pc_block);
+        const long long brow = (long long)c.b * p.pc_blocks_cap + blk;
+        const float fs = ldexpf(p.pc_fscale[brow], -head_shift);
+        const float* zw = p.pc_zw + (brow * p.grid_heads + c.hk) * 256 + 4 * q;
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const float f = G == 64 ? ldexpf(tok_norm[s], -head_shift - 15) : ldexpf(E_cur[s], -head_shift);
+        for (int ct = 0; ct < 16; ++ct) {
+            const float4 z = *reinterpret_cast<const float4*>(zw + 16 * ct);
 #pragma unroll
-        for (int ct = 0; ct < 16; ++ct) acc[s][ct] *= f;
+            for (int s = 0; s < 2; ++s) {
+                acc[s][ct][0] = __builtin_fmaf(acc[s][ct][0], fs, z.x);
+                acc[s][ct][1] = __builtin_fmaf(acc[s][ct][1], fs, z.y);
+                acc[s][ct][2] = __builtin_fmaf(acc[s][ct][2], fs, z.z);
+                acc[s][ct][3] = __builtin_fmaf(acc[s][ct][3], fs, z.w);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const float f = G == 64 ? ldexpf(tok_norm[s], -head_shift - 15) : ldexpf(E_cur[s], -head_shift);
+#pragma unroll
+            for (int ct = 0; ct < 16; ++ct) acc[s][ct] *= f;
+        }
     }
     if constexpr (MODE == MODE_PREFILL) prefill_epilogue16(p, c, acc, lds);
     else attention_epilogue16(p, c, acc);
@@ -880,7 +960,7 @@ __global__ __launch_bounds__(512) void remat_attn_dense16_kernel(const RematPara
 static hipError_t allow_lds_once(const void* k, int lds_bytes, int slot)
 {
     static std::mutex mu;
-    static bool done[64][10];                     // [device][kernel: 2 (format) + prefill; 8, 9: dense]
+    static bool done[64][13];                     // [device][kernel: 2 (format) + prefill; 8, 9: dense; 10-12: per-channel]
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
@@ -922,6 +1002,24 @@ hipError_t launch_tile16(int bits, int G, const RematParams& p, int grid, hipStr
     }
     const int lds_bytes = lds_coded_total(bits);
     const hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), lds_bytes, 2 * slot + (prefill ? 1 : 0));
+    if (e != hipSuccess) return e;
+    k<<<dim3(grid), dim3(512), lds_bytes, s>>>(p);
+    return hipGetLastError();
+}
+
+// decode attention over the complete blocks of a per-channel cache (Sec. 3.3.1); the stream is that of groups of 128
+hipError_t launch_tile16_per_channel(int bits, const RematParams& p, int grid, hipStream_t s)
+{
+    typedef void (*Kernel)(const RematParams);
+    Kernel k = nullptr;
+    switch (bits) {
+        case 2: k = remat_attn_tile16_kernel<2, 128, MODE_ATTENTION_PC>; break;
+        case 3: k = remat_attn_tile16_kernel<3, 128, MODE_ATTENTION_PC>; break;
+        case 4: k = remat_attn_tile16_kernel<4, 128, MODE_ATTENTION_PC>; break;
+        default: return hipErrorInvalidValue;
+    }
+    const int lds_bytes = lds_coded_total(bits);
+    const hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), lds_bytes, 8 + bits);
     if (e != hipSuccess) return e;
     k<<<dim3(grid), dim3(512), lds_bytes, s>>>(p);
     return hipGetLastError();

@@ -103,6 +103,7 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
 // matrix-core epilogue for many query rows instead of the per-query-head vector epilogue
 hipError_t launch_tile16(int bits, int G, const RematParams& p, int grid, hipStream_t s, bool prefill);
 hipError_t launch_tile16_dense(const RematParams& p, int grid, hipStream_t s, bool prefill);
+hipError_t launch_tile16_per_channel(int bits, const RematParams& p, int grid, hipStream_t s);
 
 // query heads per KV head from which the decode step goes through the matrix-core epilogue (the
 // per-query-head vector epilogue runs that many times per tile; measured break-even is about 4)
@@ -355,7 +356,8 @@ __global__ __launch_bounds__(256) void pc_block_exponent_kernel(const uint16_t* 
     }
 }
 
-// Pre-pass 2: the factor images, [sequence][tile][slab (+1 pad)][block of the tile][k-step][lane half][8] fp16, in
+// Pre-pass 2: the factor images, [sequence][tile][slab (+1 pad)][block of the tile][k-step][lane half][8] fp16 (for the
+// kernels on 16-column fragments: ...[block of the tile][tick][lane quarter][8], quarter q = unit q of the slab), in
 // the order the unpacked operand dwords hold their channels (the unpack table gives the code of each slot).
 // Blocks past the sequence's last one repeat it (their tokens are masked, but must stay finite).
 struct PcImageArgs {
@@ -363,6 +365,7 @@ struct PcImageArgs {
     const int* eblk;
     uint16_t* img;
     int d, blocks_cap, blocks_ws, block, tiles_per_seq, n_slabs, G;   // blocks per sequence in the cache / in eblk
+    int tile16;                                                       // the order of the 16-column-fragment kernels
     BatchI32 nblk;
     UnpackTable tab;
 };
@@ -377,7 +380,8 @@ __global__ __launch_bounds__(256) void pc_factor_image_kernel(PcImageArgs a)
         const int i = e & 7, half = (e >> 3) & 1, ks = (e >> 4) & 7, bt = e >> 7;
         const int blk = min(tile * bpt + bt, a.nblk.v[b] - 1);
         const int gi = ks / ksg_n, ksg = ks % ksg_n;
-        const int c = slab * 128 + gi * a.G + half * (a.G / 2) + (ksg >> 2) * 32 + a.tab.code_of_slot[ksg & 3][i];
+        int c = slab * 128 + gi * a.G + half * (a.G / 2) + (ksg >> 2) * 32 + a.tab.code_of_slot[ksg & 3][i];
+        if (a.tile16) c = slab * 128 + ((e >> 3) & 3) * 32 + a.tab.code_of_slot[(e >> 5) & 3][i];   // [tick][quarter][8]
         const float sc = bf16_bits_to_f32(a.scale[((long long)b * a.blocks_cap + blk) * a.d + c]);
         const float f = ldexpf(sc, 15 - a.eblk[(long long)b * a.blocks_ws + blk]);
         out[e] = __builtin_bit_cast(uint16_t, (_Float16)f);
@@ -436,7 +440,7 @@ hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const
 {
     const int bits = xc->fmt.bits, blockT = xc->fmt.group, d = xc->fmt.d, B = xc->B, cap = xc->cap;
     const int blocks_cap = cap / blockT;
-    const WPrepLayout Lc = make_wprep_layout(d, 128, bits, a->n_kv_heads);
+    const WPrepLayout Lc = make_wprep_layout_for_cache(d, 128, bits, a->n_kv_heads);    // (has the 16-column fragments)
     const WPrepLayout Ld = make_wprep_layout(d, 128, 16, a->n_kv_heads);
     UnpackTable tab;
     if (!unpack_table_for(bits, &tab)) return hipErrorInvalidValue;
@@ -479,7 +483,7 @@ hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const
         // block exponents, factor images
         pc_block_exponent_kernel<<<dim3(max_nblk, B), dim3(256), 0, s>>>(xc->scale, fscale, eblk, d, blocks_cap, (int)blocks_ws, bits, nblk);
         PcImageArgs ia{xc->scale, eblk, reinterpret_cast<uint16_t*>(img), d, blocks_cap, (int)blocks_ws, blockT, tiles_coded, Lc.n_main_slabs, 128,
-                       nblk, tab};
+                       1, nblk, tab};
         pc_factor_image_kernel<<<dim3(Lc.n_main_slabs, tiles_coded, B), dim3(256), 0, s>>>(ia);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -506,15 +510,10 @@ hipError_t run_remat_attn_decode_pc(const xq_attn_t* a, const uint16_t* q, const
         m.wprep = static_cast<const uint8_t*>(wprep_coded);
         m.head_shift = stream_shifts(wprep_coded, Lc);
         m.n_main_slabs = Lc.n_main_slabs; m.n_corr_ksteps = Lc.n_corr_ksteps; m.ng = Lc.ng; m.ng_pad = Lc.ng_pad; m.ng_row = Lc.ng;
-        m.head_bytes = (long long)Lc.head_bytes;
+        m.wprep += Lc.t16_offset;                                            // the stream of 16-column fragments
+        m.head_bytes = (long long)Lc.t16_head_bytes;
         m.pc_fscale = fscale; m.pc_zw = zw; m.pc_block = blockT; m.pc_blocks_cap = (int)blocks_ws;
-        const int grid = p.Hkv * B * tiles_coded;
-        switch (bits) {
-            case 2: e = launch_with_lds(remat_attn_coded_kernel<2, 128, MODE_ATTENTION_PC>, lds_coded_total(2), m, grid, s); break;
-            case 3: e = launch_with_lds(remat_attn_coded_kernel<3, 128, MODE_ATTENTION_PC>, lds_coded_total(3), m, grid, s); break;
-            case 4: e = launch_with_lds(remat_attn_coded_kernel<4, 128, MODE_ATTENTION_PC>, lds_coded_total(4), m, grid, s); break;
-            default: e = hipErrorInvalidValue;
-        }
+        e = launch_tile16_per_channel(bits, m, p.Hkv * B * tiles_coded, s);
         if (e != hipSuccess) return e;
     }
     if (any_tail) {
@@ -630,7 +629,7 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
     if (max_nblk > 0 && compute_terms) {
         pc_block_exponent_kernel<<<dim3(max_nblk, B), dim3(256), 0, s>>>(kc->scale, fscale, eblk, r, blocks_cap, (int)blocks_ws, kbits, nblk);
         PcImageArgs ia{kc->scale, eblk, reinterpret_cast<uint16_t*>(img), r, blocks_cap, (int)blocks_ws, blockT, tiles_coded,
-                       Lk.n_main_slabs, 128, nblk, tab};
+                       Lk.n_main_slabs, 128, 0, nblk, tab};
         pc_factor_image_kernel<<<dim3(Lk.n_main_slabs, tiles_coded, B), dim3(256), 0, s>>>(ia);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
