@@ -247,6 +247,17 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
     for (int cs = 0; cs < n_corr_slabs; ++cs) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        // The zero-points have arrived with that wait, but the compiler counts only its own loads, not the DMA: left
+        // alone it waits for them at their first use, with vmcnt(0), behind the DMA issued next, and the correction
+        // would start only after that slab has landed.  Using the registers here puts its wait here, where it is free.
+        if constexpr (!PC) {
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh)
+                asm volatile("" :: "v"(mfr[4 * kh].x), "v"(mfr[4 * kh].y), "v"(mfr[4 * kh].z), "v"(mfr[4 * kh].w),
+                                   "v"(mfr[4 * kh + 1].x), "v"(mfr[4 * kh + 1].y), "v"(mfr[4 * kh + 1].z), "v"(mfr[4 * kh + 1].w),
+                                   "v"(mfr[4 * kh + 2].x), "v"(mfr[4 * kh + 2].y), "v"(mfr[4 * kh + 2].z), "v"(mfr[4 * kh + 2].w),
+                                   "v"(mfr[4 * kh + 3].x), "v"(mfr[4 * kh + 3].y), "v"(mfr[4 * kh + 3].z), "v"(mfr[4 * kh + 3].w));
+        }
         const uint32_t wdst = lds_w + (uint32_t)(((cs + 1) & 1) * SLAB_BYTES);
         if (cs + 1 < n_corr_slabs) issue_slab(wsrc + (long long)(p.n_main_slabs + cs + 1) * SLAB_BYTES, wdst, dma_voff);
         else issue_slab(wsrc, wdst, dma_voff);                                                   // the first main slab
@@ -476,7 +487,8 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] *= ldexpf(E[GPS + j / KSG], -head_shift);
     }
-    if constexpr (MODE == MODE_SCORES || MODE == MODE_SCORES_PC) scores_epilogue(p, c, acc);
+    // (after the last barrier of the walk nothing reads or writes the slab buffers any more)
+    if constexpr (MODE == MODE_SCORES || MODE == MODE_SCORES_PC) scores_epilogue(p, c, acc, lds + wave * 8192, 8192);
     else if constexpr (MODE == MODE_WEIGHTED_SUM) weighted_sum_epilogue(p, c, acc, lds);
     else if constexpr (MODE == MODE_ACCUMULATE) accumulate_epilogue(p, c, acc, lds);
     else if constexpr (MODE == MODE_PREFILL) prefill_epilogue(p, c, acc, lds);
@@ -674,7 +686,7 @@ __global__ __launch_bounds__(512) void remat_attn_dense_kernel(const RematParams
                 }
         }
     } else if constexpr (DMODE == DENSE_SCORES) {
-        scores_epilogue(p, c, acc);
+        scores_epilogue(p, c, acc, lds + LDS_DENSE_STAGE_OFF + wave * LDS_DENSE_STAGE_BYTES, LDS_DENSE_STAGE_BYTES);   // (the wave's own, idle now)
     } else {
         attention_epilogue(p, c, acc);
     }

@@ -625,6 +625,15 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     for (int cs = 0; cs < n_corr_slabs; ++cs) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        // The zero-points have arrived with that wait, but the compiler counts only its own loads, not the DMA: left
+        // alone it waits for them at their first use, with vmcnt(0), behind the DMA issued next, and the correction
+        // would start only after that slab has landed.  Using the registers here puts its wait here, where it is free.
+#pragma unroll
+        for (int ss = 0; ss < 2; ++ss)
+            asm volatile("" :: "v"(mfr[ss][0].x), "v"(mfr[ss][0].y), "v"(mfr[ss][0].z), "v"(mfr[ss][0].w),
+                               "v"(mfr[ss][1].x), "v"(mfr[ss][1].y), "v"(mfr[ss][1].z), "v"(mfr[ss][1].w),
+                               "v"(mfr[ss][2].x), "v"(mfr[ss][2].y), "v"(mfr[ss][2].z), "v"(mfr[ss][2].w),
+                               "v"(mfr[ss][3].x), "v"(mfr[ss][3].y), "v"(mfr[ss][3].z), "v"(mfr[ss][3].w));
         const uint32_t wdst = lds_w + (uint32_t)(((cs + 1) & 1) * SLAB_BYTES);
         if (cs + 1 < n_corr_slabs) issue_slab(wsrc + (long long)(p.n_main_slabs + cs + 1) * SLAB_BYTES, wdst, dma_voff);
         else issue_slab(wsrc, wdst, dma_voff);                                                   // the first main slab

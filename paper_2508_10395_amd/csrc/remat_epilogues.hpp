@@ -305,29 +305,64 @@ __device__ __forceinline__ void prefill_epilogue(const RematParams& p, const Til
 // ---- latent cache (Sec. 3.3.1), pass 1: the wave holds the keys of two KV heads of its 32 tokens
 // (blocks 0-3: head 2 pair, blocks 4-7: head 2 pair + 1) and stores the scaled scores of their
 // query heads; pass 2 turns them into softmax partials against the values.
-__device__ __forceinline__ void scores_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8])
+// The epilogue is bound by vector-instruction issue (all eight waves are in it at once), so the query vectors of the
+// pair's heads (contiguous in q) are first converted to fp32 and put into LDS -- `qstage`, a region of qstage_bytes
+// that only this wave touches any more: a head then costs 16 ds_read_b128 and 64 fma per lane, without the
+// conversions and without one memory latency per head.  Pairs with more query heads than fit read q from memory.
+__device__ __forceinline__ void scores_epilogue(const RematParams& p, const TileCtx& c, f32x16 (&acc)[8], uint8_t* qstage,
+                                                int qstage_bytes)
 {
     if (c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS >= c.len) return;
     const int gq = p.Hq / p.Hkv;
     const long long srow = p.score_stride;
     const int tok_out = p.tok0.v[c.b] + c.tok;
+    const uint16_t* qpair = p.q + ((long long)c.b * p.Hq + 2 * c.hk * gq) * 128;     // 2 gq heads x 128 bf16
+    const int n_q = 2 * gq * 128;
+    const bool staged = n_q * 4 <= qstage_bytes && (reinterpret_cast<size_t>(p.q) & 15) == 0;   // (wave-uniform)
+    float* qf = reinterpret_cast<float*>(qstage);
+    if (staged) {
+        for (int i0 = c.lane * 8; i0 < n_q; i0 += 512) {
+            const uint4 v = *reinterpret_cast<const uint4*>(qpair + i0);
+            float4 lo, hi;
+            lo.x = bf16_lo_to_f32(v.x); lo.y = bf16_hi_to_f32(v.x); lo.z = bf16_lo_to_f32(v.y); lo.w = bf16_hi_to_f32(v.y);
+            hi.x = bf16_lo_to_f32(v.z); hi.y = bf16_hi_to_f32(v.z); hi.z = bf16_lo_to_f32(v.w); hi.w = bf16_hi_to_f32(v.w);
+            *reinterpret_cast<float4*>(qf + i0) = lo;
+            *reinterpret_cast<float4*>(qf + i0 + 4) = hi;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
     static_for<0, 2>([&](auto HH) XQ_INLINE_LAMBDA {       // (compile-time: the accumulator must stay in registers)
         constexpr int hh = decltype(HH)::value;
         for (int j = 0; j < gq; ++j) {
             const int hq = (2 * c.hk + hh) * gq + j;
-            const uint16_t* qv = p.q + ((long long)c.b * p.Hq + hq) * 128;
             float dot = 0.0f;
+            if (staged) {
+                const float* qv = qf + (hh * gq + j) * 128 + c.half * 4;
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
+                for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    const uint2 qq = *reinterpret_cast<const uint2*>(qv + nb * 32 + i4 * 8 + c.half * 4);
-                    const f32x16& a = acc[4 * hh + nb];
-                    dot = __builtin_fmaf(bf16_lo_to_f32(qq.x), a[i4 * 4 + 0], dot);
-                    dot = __builtin_fmaf(bf16_hi_to_f32(qq.x), a[i4 * 4 + 1], dot);
-                    dot = __builtin_fmaf(bf16_lo_to_f32(qq.y), a[i4 * 4 + 2], dot);
-                    dot = __builtin_fmaf(bf16_hi_to_f32(qq.y), a[i4 * 4 + 3], dot);
-                }
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        const float4 qq = *reinterpret_cast<const float4*>(qv + nb * 32 + i4 * 8);
+                        const f32x16& a = acc[4 * hh + nb];
+                        dot = __builtin_fmaf(qq.x, a[i4 * 4 + 0], dot);
+                        dot = __builtin_fmaf(qq.y, a[i4 * 4 + 1], dot);
+                        dot = __builtin_fmaf(qq.z, a[i4 * 4 + 2], dot);
+                        dot = __builtin_fmaf(qq.w, a[i4 * 4 + 3], dot);
+                    }
+            } else {
+                const uint16_t* qv = p.q + ((long long)c.b * p.Hq + hq) * 128;
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        const uint2 qq = *reinterpret_cast<const uint2*>(qv + nb * 32 + i4 * 8 + c.half * 4);
+                        const f32x16& a = acc[4 * hh + nb];
+                        dot = __builtin_fmaf(bf16_lo_to_f32(qq.x), a[i4 * 4 + 0], dot);
+                        dot = __builtin_fmaf(bf16_hi_to_f32(qq.x), a[i4 * 4 + 1], dot);
+                        dot = __builtin_fmaf(bf16_lo_to_f32(qq.y), a[i4 * 4 + 2], dot);
+                        dot = __builtin_fmaf(bf16_hi_to_f32(qq.y), a[i4 * 4 + 3], dot);
+                    }
+            }
             const float sc = (dot + __shfl_xor(dot, 32)) * p.scale_log2e;
             if (c.half == 0 && c.tok < c.len) p.scores[((long long)c.b * p.Hq + hq) * srow + tok_out] = sc;
         }
