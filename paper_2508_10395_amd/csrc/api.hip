@@ -205,7 +205,7 @@ static bool latent_combo_ok(const xq_attn_t* a, int r, int group, int src_bits)
 size_t xq_prepared_weights_latent_bytes(const xq_attn_t* a, int32_t r, int32_t group, int32_t src_bits)
 {
     if (check_attn(a) != XQ_OK || !latent_combo_ok(a, r, group, src_bits)) return 0;
-    return 2 * make_wprep_layout(r, group, src_bits, a->n_kv_heads / 2).total_bytes;
+    return 2 * make_wprep_layout_for_cache(r, group, src_bits, a->n_kv_heads / 2).total_bytes;
 }
 
 xq_status_t xq_prepare_weights_latent(const xq_attn_t* a, int32_t r, int32_t group, int32_t src_bits,
@@ -218,7 +218,7 @@ xq_status_t xq_prepare_weights_latent(const xq_attn_t* a, int32_t r, int32_t gro
     if (r <= 0) return XQ_ERR_INVALID_ARG;
     if (!latent_combo_ok(a, r, group, src_bits)) return XQ_ERR_UNSUPPORTED;
     // one stream per half; a stream's "head" is a pair of KV heads = 256 adjacent columns of the fused matrix
-    const WPrepLayout L = make_wprep_layout(r, group, src_bits, a->n_kv_heads / 2);
+    const WPrepLayout L = make_wprep_layout_for_cache(r, group, src_bits, a->n_kv_heads / 2);
     if (out_bytes < 2 * L.total_bytes) return XQ_ERR_WORKSPACE;
     const int ncols = a->n_kv_heads * 128;
     hipError_t e = run_prepare_weights(L, Wfk, Wfk + 128, ncols, 256, out, static_cast<hipStream_t>(stream));
@@ -463,7 +463,7 @@ static bool pairs_combo_ok(const xq_attn_t* a, int r, int group, int src_bits)
 size_t xq_prepared_weights_pairs_bytes(const xq_attn_t* a, int32_t r, int32_t group, int32_t src_bits)
 {
     if (check_attn(a) != XQ_OK || !pairs_combo_ok(a, r, group, src_bits)) return 0;
-    return make_wprep_layout(r, src_bits == 16 ? 128 : group, src_bits, a->n_kv_heads / 2).total_bytes;
+    return pairs_layout(r, group, src_bits, a->n_kv_heads / 2).total_bytes;
 }
 
 xq_status_t xq_prepare_weights_pairs(const xq_attn_t* a, int32_t r, int32_t group, int32_t src_bits, const uint16_t* Wf,
@@ -473,7 +473,7 @@ xq_status_t xq_prepare_weights_pairs(const xq_attn_t* a, int32_t r, int32_t grou
     if (st != XQ_OK) return st;
     if (!Wf || !out || !aligned16(Wf) || !aligned16(out) || r <= 0) return XQ_ERR_INVALID_ARG;
     if (!pairs_combo_ok(a, r, group, src_bits)) return XQ_ERR_UNSUPPORTED;
-    const WPrepLayout L = make_wprep_layout(r, src_bits == 16 ? 128 : group, src_bits, a->n_kv_heads / 2);
+    const WPrepLayout L = pairs_layout(r, group, src_bits, a->n_kv_heads / 2);
     if (out_bytes < L.total_bytes) return XQ_ERR_WORKSPACE;
     hipError_t e = run_prepare_weights(L, Wf, Wf + 128, a->n_kv_heads * 128, 256, out, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XQ_OK : XQ_ERR_HIP;

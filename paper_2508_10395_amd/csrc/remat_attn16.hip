@@ -357,6 +357,128 @@ __device__ __forceinline__ void prefill_epilogue16(const RematParams& p, const T
     }
 }
 
+// ---- latent cache (Sec. 3.3.1), pass 2 on the 16 x 16 tiles (pass 1, the scores, stays with the 32x32x16 kernel: its
+// loop is as fast on the eight slabs of a latent half and its epilogue is lighter; measured 273 against 296 us on
+// config 4).  tiles 0-7 / 8-15 hold the values of the pair's two KV heads.  One head after the other goes through the second
+// half of the matrix-core epilogue above: the wave writes the head's V images, turns the stored scores of the head's
+// query heads (lane = query head c16, eight of the wave's tokens: 16 s + 4 q + [0, 4)) into softmax weights against the
+// tile's maximum, and contracts its 16 value columns over the tile's 256 tokens: one partial (m, l, o[128]) per query
+// head and tile.  Called by all eight waves; nothing else may touch the LDS any more.  At most 16 query heads per KV head.
+__device__ __forceinline__ void weighted_sum_epilogue16(const RematParams& p, const TileCtx& c, f32x4 (&acc)[2][16], uint8_t* lds)
+{
+    const int tok0 = c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS;
+    const bool active = tok0 < c.len;                                      // wave-uniform: chunk not entirely past len
+    const int c16 = c.lane & 15, q = c.lane >> 4;
+    const int gq = p.Hq / p.Hkv;
+    const long long srow = p.score_stride;
+    float* mbuf = reinterpret_cast<float*>(lds + PF16_M_OFF);             // [wave][16 queries]
+    float* lbuf = mbuf + 8 * 16;
+    uint8_t* pbuf = lds + PF16_P_OFF;
+    uint8_t* vt = lds + c.wave * PF16_VT_WAVE_BYTES;
+    const int ncol = 16 * c.wave + c16;                                    // the value column this lane reads and stores
+    auto lds_barrier = [&]() XQ_INLINE_LAMBDA { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+    // the stored scores of both heads, masked (rows past the head's query heads repeat the last one and are not stored)
+    float S[2][8];
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        if (active) {
+            const float* sp = p.scores + ((long long)c.b * p.Hq + (2 * c.hk + hh) * gq + min(c16, gq - 1)) * srow + tok0 + 4 * q;
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const float4 s4 = *reinterpret_cast<const float4*>(sp + 16 * s);      // past len: other rows' or stale values
+                const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) S[hh][4 * s + i] = tok0 + 16 * s + 4 * q + i < c.len ? sv[i] : -INFINITY;
+            }
+        }
+    }
+    __syncthreads();                                                       // every wave is done with the slab buffers
+    static_for<0, 2>([&](auto HH) XQ_INLINE_LAMBDA {       // (compile-time: the accumulator must stay in registers)
+        constexpr int hh = decltype(HH)::value;
+        const int hq0 = (2 * c.hk + hh) * gq;
+        if constexpr (hh == 1) lds_barrier();                              // the first head's images and weights have been read
+        float m = -INFINITY;
+        if (active) {
+            // V^T images: element i of tile (s, 8 hh + ct) is V[token 16 s + c16][n = 16 ct + 4 q + i]
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int ct = 0; ct < 8; ++ct)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int n = 16 * ct + 4 * q + i, t = 16 * s + c16;
+                        const float v = acc[s][8 * hh + ct][i];
+                        const uint32_t h = pack_bf16x2_rne(v, 0.0f);
+                        uint8_t* dst = vt + vt16_offset(n, t >> 2) + (t & 3) * 2;
+                        *reinterpret_cast<uint16_t*>(dst) = (uint16_t)h;
+                        *reinterpret_cast<uint16_t*>(dst + PF16_VT_IMAGE_BYTES) = (uint16_t)pack_bf16x2_rne(v - bf16_lo_to_f32(h), 0.0f);
+                    }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) m = fmaxf(m, S[hh][k]);
+            m = fmaxf(m, __shfl_xor(m, 16));
+            m = fmaxf(m, __shfl_xor(m, 32));
+        } else {
+            // a chunk entirely past len contributes nothing: zero images and zero weights
+#pragma unroll
+            for (int k = 0; k < PF16_VT_WAVE_BYTES / 1024; ++k)
+                *reinterpret_cast<uint4*>(vt + k * 1024 + c.lane * 16) = make_uint4(0u, 0u, 0u, 0u);
+        }
+        if (q == 0) mbuf[c.wave * 16 + c16] = m;
+        lds_barrier();                                                     // the maxima are in mbuf
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) M = fmaxf(M, mbuf[w * 16 + c16]);
+        const float Mu = M == -INFINITY ? 0.0f : M;
+        float l = 0.0f;
+        uint4 phi = make_uint4(0u, 0u, 0u, 0u), plo = phi;
+        if (active) {
+            float pr[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                pr[k] = __builtin_amdgcn_exp2f(S[hh][k] - Mu);
+                l += pr[k];
+            }
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            split_hi_lo(pr, phi, plo);
+        }
+        *reinterpret_cast<uint4*>(pbuf + (c.wave * 64 + c.lane) * 16) = phi;
+        *reinterpret_cast<uint4*>(pbuf + PF16_P_BYTES / 2 + (c.wave * 64 + c.lane) * 16) = plo;
+        if (q == 0) lbuf[c.wave * 16 + c16] = l;
+        lds_barrier();                                                     // images, weights and sums of all eight chunks are in LDS
+        float Lt = 0.0f;
+        if (c.wave == 0 && q == 0) {
+#pragma unroll
+            for (int w = 0; w < 8; ++w) Lt += lbuf[w * 16 + c16];
+        }
+        f32x4 O0 = {0.0f, 0.0f, 0.0f, 0.0f}, O1 = O0, O2 = O0;             // hi*hi, lo*hi, hi*lo: three independent chains
+        static_for<0, 8>([&](auto CW) XQ_INLINE_LAMBDA {
+            constexpr int cw = decltype(CW)::value;
+            const uint4 ph = *reinterpret_cast<const uint4*>(pbuf + (cw * 64 + c.lane) * 16);
+            const uint4 pl = *reinterpret_cast<const uint4*>(pbuf + PF16_P_BYTES / 2 + (cw * 64 + c.lane) * 16);
+            const uint8_t* v0 = lds + cw * PF16_VT_WAVE_BYTES + vt16_offset(ncol, q);
+            const uint8_t* v1 = lds + cw * PF16_VT_WAVE_BYTES + vt16_offset(ncol, 4 + q);
+            const uint2 h0 = *reinterpret_cast<const uint2*>(v0), h1 = *reinterpret_cast<const uint2*>(v1);
+            const uint2 l0 = *reinterpret_cast<const uint2*>(v0 + PF16_VT_IMAGE_BYTES);
+            const uint2 l1 = *reinterpret_cast<const uint2*>(v1 + PF16_VT_IMAGE_BYTES);
+            const uint4 vh = make_uint4(h0.x, h0.y, h1.x, h1.y), vl = make_uint4(l0.x, l0.y, l1.x, l1.y);
+            O0 = mfma16_bf16(ph, vh, O0);
+            O1 = mfma16_bf16(pl, vh, O1);
+            O2 = mfma16_bf16(ph, vl, O2);
+        });
+        if (c.wave == 0 && q == 0 && c16 < gq) {
+            const long long pidx = ((long long)c.b * p.Hq + hq0 + c16) * p.chunks_per_seq + c.tile;
+            p.part_ml[pidx * 2] = M;
+            p.part_ml[pidx * 2 + 1] = Lt;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int qr = 4 * q + i;
+            if (qr < gq) p.part_o[(((long long)c.b * p.Hq + hq0 + qr) * p.chunks_per_seq + c.tile) * 128 + ncol] = (O1[i] + O2[i]) + O0[i];
+        }
+    });
+}
+
 // G = 64 (2-bit codes only): "scales on the token operand".  With groups of 64 a tile would meet two group boundaries
 // per slab, and rescaling 128 accumulator registers twice per slab makes the loop wait for vector-instruction issue
 // (measured: no faster than the 32x32x16 kernel).  Instead the group's scale goes into the token fragment: tick j takes
@@ -391,7 +513,7 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     constexpr int LDS_SCALES_OFF = lds_scales_off(BITS);
     constexpr int NT = TILE16_TICKS;                   // ticks (k32-steps) per slab
     // slots between the LDS read of a weight fragment and its use (one fewer where the epilogue keeps more alive)
-    constexpr int AHEAD = MODE == MODE_PREFILL ? 4 : 5;
+    constexpr int AHEAD = (MODE == MODE_PREFILL || MODE == MODE_WEIGHTED_SUM) ? 4 : 5;
     constexpr int NRING = 8;                           // (divides 64: the ring runs on from slab to slab)
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -831,7 +953,9 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
             for (int ct = 0; ct < 16; ++ct) acc[s][ct] *= f;
         }
     }
+    // (after the last barrier of the walk nothing reads or writes the slab buffers any more)
     if constexpr (MODE == MODE_PREFILL) prefill_epilogue16(p, c, acc, lds);
+    else if constexpr (MODE == MODE_WEIGHTED_SUM) weighted_sum_epilogue16(p, c, acc, lds);
     else attention_epilogue16(p, c, acc);
 }
 
@@ -969,7 +1093,7 @@ __global__ __launch_bounds__(512) void remat_attn_dense16_kernel(const RematPara
 static hipError_t allow_lds_once(const void* k, int lds_bytes, int slot)
 {
     static std::mutex mu;
-    static bool done[64][13];                     // [device][kernel: 2 (format) + prefill; 8, 9: dense; 10-12: per-channel]
+    static bool done[64][24];                     // [device][kernel: 4 format + mode; 16, 17: dense; 18-20: per-channel]
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
@@ -991,26 +1115,40 @@ hipError_t launch_tile16_dense(const RematParams& p, int grid, hipStream_t s, bo
 {
     typedef void (*Kernel)(const RematParams);
     const Kernel k = prefill ? remat_attn_dense16_kernel<MODE_PREFILL> : remat_attn_dense16_kernel<MODE_ATTENTION>;
-    hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), LDS_DENSE16_TOTAL, prefill ? 9 : 8);
+    hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), LDS_DENSE16_TOTAL, prefill ? 17 : 16);
     if (e != hipSuccess) return e;
     k<<<dim3(grid), dim3(512), LDS_DENSE16_TOTAL, s>>>(p);
     return hipGetLastError();
 }
 
-hipError_t launch_tile16(int bits, int G, const RematParams& p, int grid, hipStream_t s, bool prefill)
+typedef void (*Tile16Kernel)(const RematParams);
+template <int BITS, int G>
+static Tile16Kernel tile16_kernel_for(int mode)
 {
-    typedef void (*Kernel)(const RematParams);
-    Kernel k = nullptr;
-    int slot = -1;
-    switch (bits * 1000 + G) {
-        case 2128: k = prefill ? remat_attn_tile16_kernel<2, 128, MODE_PREFILL> : remat_attn_tile16_kernel<2, 128, MODE_ATTENTION>; slot = 0; break;
-        case 3128: k = prefill ? remat_attn_tile16_kernel<3, 128, MODE_PREFILL> : remat_attn_tile16_kernel<3, 128, MODE_ATTENTION>; slot = 1; break;
-        case 4128: k = prefill ? remat_attn_tile16_kernel<4, 128, MODE_PREFILL> : remat_attn_tile16_kernel<4, 128, MODE_ATTENTION>; slot = 2; break;
-        case 2064: k = prefill ? remat_attn_tile16_kernel<2, 64, MODE_PREFILL> : remat_attn_tile16_kernel<2, 64, MODE_ATTENTION>; slot = 3; break;
-        default: return hipErrorInvalidValue;
+    switch (mode) {
+        case MODE_ATTENTION: return remat_attn_tile16_kernel<BITS, G, MODE_ATTENTION>;
+        case MODE_PREFILL: return remat_attn_tile16_kernel<BITS, G, MODE_PREFILL>;
+        case MODE_WEIGHTED_SUM: return remat_attn_tile16_kernel<BITS, G, MODE_WEIGHTED_SUM>;
     }
+    return nullptr;
+}
+
+// mode: MODE_ATTENTION (decode, vector epilogue), MODE_PREFILL (matrix-core epilogue for many query rows),
+// MODE_WEIGHTED_SUM (the second pass over a latent cache)
+hipError_t launch_tile16(int bits, int G, const RematParams& p, int grid, hipStream_t s, int mode)
+{
+    Tile16Kernel k = nullptr;
+    int format = -1;
+    switch (bits * 1000 + G) {
+        case 2128: k = tile16_kernel_for<2, 128>(mode); format = 0; break;
+        case 3128: k = tile16_kernel_for<3, 128>(mode); format = 1; break;
+        case 4128: k = tile16_kernel_for<4, 128>(mode); format = 2; break;
+        case 2064: k = tile16_kernel_for<2, 64>(mode); format = 3; break;
+    }
+    if (!k) return hipErrorInvalidValue;
+    const int mode_slot = mode == MODE_ATTENTION ? 0 : mode == MODE_PREFILL ? 1 : 2;
     const int lds_bytes = lds_coded_total(bits);
-    const hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), lds_bytes, 2 * slot + (prefill ? 1 : 0));
+    const hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), lds_bytes, 4 * format + mode_slot);
     if (e != hipSuccess) return e;
     k<<<dim3(grid), dim3(512), lds_bytes, s>>>(p);
     return hipGetLastError();
@@ -1028,7 +1166,7 @@ hipError_t launch_tile16_per_channel(int bits, const RematParams& p, int grid, h
         default: return hipErrorInvalidValue;
     }
     const int lds_bytes = lds_coded_total(bits);
-    const hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), lds_bytes, 8 + bits);
+    const hipError_t e = allow_lds_once(reinterpret_cast<const void*>(k), lds_bytes, 16 + bits);
     if (e != hipSuccess) return e;
     k<<<dim3(grid), dim3(512), lds_bytes, s>>>(p);
     return hipGetLastError();

@@ -99,9 +99,10 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
                                   const BatchI32& len, int max_len, float* out, void* ws,
                                   const float* rope, const BatchI32* pos0, hipStream_t s);
 
-// the kernels on 16 x 16 x 32 MFMAs (remat_attn16.hip): groups of 128 codes or the dense source; prefill = the
-// matrix-core epilogue for many query rows instead of the per-query-head vector epilogue
-hipError_t launch_tile16(int bits, int G, const RematParams& p, int grid, hipStream_t s, bool prefill);
+// the kernels on 16 x 16 x 32 MFMAs (remat_attn16.hip): groups of 128 codes (2-bit: also 64) or the dense source;
+// mode = MODE_ATTENTION, MODE_PREFILL (the matrix-core epilogue for many query rows instead of the per-query-head
+// vector epilogue) or MODE_WEIGHTED_SUM (the second pass over a latent cache)
+hipError_t launch_tile16(int bits, int G, const RematParams& p, int grid, hipStream_t s, int mode);
 hipError_t launch_tile16_dense(const RematParams& p, int grid, hipStream_t s, bool prefill);
 hipError_t launch_tile16_per_channel(int bits, const RematParams& p, int grid, hipStream_t s);
 
@@ -148,7 +149,7 @@ hipError_t run_remat_attn_decode(const xq_attn_t* a, const uint16_t* q, const xq
             p.wprep += L.t16_offset;
             p.head_bytes = (long long)L.t16_head_bytes;
             p.n_corr_ksteps = L.t16_n_corr_ticks;
-            e = launch_tile16(bits, G, p, grid, s, false);
+            e = launch_tile16(bits, G, p, grid, s, MODE_ATTENTION);
         } else {
             e = launch_coded<MODE_ATTENTION>(bits, G, p, grid, s);
         }
@@ -224,7 +225,7 @@ hipError_t run_remat_attn_prefill(const xq_attn_t* a, const uint16_t* q, int T, 
             p.wprep += L.t16_offset;
             p.head_bytes = (long long)L.t16_head_bytes;
             p.n_corr_ksteps = L.t16_n_corr_ticks;
-            e = launch_tile16(bits, G, p, grid, s, true);
+            e = launch_tile16(bits, G, p, grid, s, MODE_PREFILL);
         } else {
             e = launch_coded<MODE_PREFILL>(bits, G, p, grid, s);
         }
@@ -255,7 +256,9 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
 {
     const int bits = xc->fmt.bits, G = xc->fmt.group, r = xc->fmt.d / 2, B = xc->B, cap = xc->cap;
     const int pairs = a->n_kv_heads / 2;
-    const WPrepLayout L = make_wprep_layout(r, G, bits, pairs);          // one stream per half, "head" = pair
+    const WPrepLayout L = make_wprep_layout_for_cache(r, G, bits, pairs);          // one stream per half, "head" = pair
+    // pass 2 runs on the 16-column fragments where the format has them (that epilogue takes 16 query rows per KV head)
+    const bool t16 = L.t16_bytes != 0 && a->n_q_heads / a->n_kv_heads <= 16;
     RematParams p{};
     fill_common(p, a, q, B, cap, len, max_len, ws);
     p.d = r; p.row_d = 2 * r; p.grid_heads = pairs;
@@ -269,10 +272,11 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
     p.score_stride = p.tiles_per_seq * TILE_TOKENS;
     const int grid = pairs * B * p.tiles_per_seq;
 
+    const bool normaliser = t16 && G == 64;                 // (the scaled-operand loop wants the tokens' normalisers)
     scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
         xc->scale, eT_k, cap, L.ng, 2 * L.ng, p.tiles_per_seq, bits, len);
     scale_transpose_kernel<<<dim3(p.tiles_per_seq, B), dim3(TILE_TOKENS), 0, s>>>(
-        xc->scale + L.ng, eT_v, cap, L.ng, 2 * L.ng, p.tiles_per_seq, bits, len);
+        xc->scale + L.ng, eT_v, cap, L.ng, 2 * L.ng, p.tiles_per_seq, bits, len, 0, normaliser);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // pass 1: keys
@@ -286,7 +290,14 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
     p.wprep = static_cast<const uint8_t*>(wprep) + L.total_bytes;
     p.head_shift = stream_shifts(p.wprep, L);
     p.chunks_per_seq = p.tiles_per_seq;
-    e = launch_coded<MODE_WEIGHTED_SUM>(bits, G, p, grid, s);
+    if (t16) {
+        p.wprep += L.t16_offset;
+        p.head_bytes = (long long)L.t16_head_bytes;
+        p.n_corr_ksteps = L.t16_n_corr_ticks;
+        e = launch_tile16(bits, G, p, grid, s, MODE_WEIGHTED_SUM);
+    } else {
+        e = launch_coded<MODE_WEIGHTED_SUM>(bits, G, p, grid, s);
+    }
     if (e != hipSuccess) return e;
     combine_kernel<<<dim3(p.Hq, p.B), dim3(128 * COMBINE_GROUPS), 0, s>>>(p.part_o, p.part_ml, out, p.Hq, p.tiles_per_seq, p.len, 1, TILE_TOKENS);
     return hipGetLastError();
@@ -583,9 +594,10 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
     const int vbits = vc->fmt.bits, vG = vc->fmt.group;
     const int pairs = a->n_kv_heads / 2;
     const int blocks_cap = kc->cap / blockT;
-    const WPrepLayout Lk = make_wprep_layout(r, 128, kbits, pairs);
-    const WPrepLayout Ld = make_wprep_layout(r, 128, 16, pairs);
-    const WPrepLayout Lv = make_wprep_layout(r, vG, vbits, pairs);
+    const WPrepLayout Lk = pairs_layout(r, 128, kbits, pairs);
+    const WPrepLayout Ld = pairs_layout(r, 128, 16, pairs);
+    const WPrepLayout Lv = pairs_layout(r, vG, vbits, pairs);
+    const bool v16 = Lv.t16_bytes != 0 && a->n_q_heads / a->n_kv_heads <= 16;   // pass 2 on the 16-column fragments
     UnpackTable tab;
     if (!unpack_table_for(kbits, &tab)) return hipErrorInvalidValue;
     BatchI32 nblk{}, len_coded{}, len_tail{};
@@ -680,7 +692,8 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
         if (e != hipSuccess) return e;
     }
     // pass 2: values from the per-token cache
-    scale_transpose_kernel<<<dim3(tiles_all, B), dim3(TILE_TOKENS), 0, s>>>(vc->scale, eT_v, vc->cap, Lv.ng, Lv.ng, tiles_all, vbits, len);
+    scale_transpose_kernel<<<dim3(tiles_all, B), dim3(TILE_TOKENS), 0, s>>>(vc->scale, eT_v, vc->cap, Lv.ng, Lv.ng, tiles_all, vbits, len, 0,
+                                                                            v16 && vG == 64);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     RematParams v = p;
@@ -691,7 +704,14 @@ hipError_t run_remat_attn_decode_latent_pc(const xq_attn_t* a, const uint16_t* q
     v.n_main_slabs = Lv.n_main_slabs; v.n_corr_ksteps = Lv.n_corr_ksteps; v.ng = Lv.ng; v.ng_pad = Lv.ng_pad; v.ng_row = Lv.ng;
     v.head_bytes = (long long)Lv.head_bytes;
     v.chunks_per_seq = tiles_all;                        // one partial per tile
-    e = launch_coded<MODE_WEIGHTED_SUM>(vbits, vG, v, pairs * B * tiles_all, s);
+    if (v16) {
+        v.wprep += Lv.t16_offset;
+        v.head_bytes = (long long)Lv.t16_head_bytes;
+        v.n_corr_ksteps = Lv.t16_n_corr_ticks;
+        e = launch_tile16(vbits, vG, v, pairs * B * tiles_all, s, MODE_WEIGHTED_SUM);
+    } else {
+        e = launch_coded<MODE_WEIGHTED_SUM>(vbits, vG, v, pairs * B * tiles_all, s);
+    }
     if (e != hipSuccess) return e;
     combine_kernel<<<dim3(p.Hq, B), dim3(128 * COMBINE_GROUPS), 0, s>>>(part_o, part_ml, out, p.Hq, tiles_all, len, 1, TILE_TOKENS);
     return hipGetLastError();

@@ -104,4 +104,11 @@ inline WPrepLayout make_wprep_layout_for_cache(int d, int G, int bits, int Hkv)
     return L;
 }
 
+// A stream whose "head" is a pair of KV heads (one fused latent matrix, Sec. 3.3.1): coded streams carry the
+// 16-column fragments too (the value pass runs on them), dense ones (the window's and the zero-point rows') do not.
+inline WPrepLayout pairs_layout(int r, int G, int bits, int pairs)
+{
+    return bits == 16 ? make_wprep_layout(r, 128, 16, pairs) : make_wprep_layout_for_cache(r, G, bits, pairs);
+}
+
 }  // namespace xq
