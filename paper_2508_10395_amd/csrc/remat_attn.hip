@@ -229,7 +229,8 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
         return v;
     };
     const int slab_prev = p.n_main_slabs - 1;           // the walk is cyclic: the slab "before" slab 0
-    issue_slab(wsrc + (long long)p.n_main_slabs * SLAB_BYTES, lds_w, dma_voff);        // correction slab 0 -> buffer 0
+    issue_slab_chunks(wsrc + (long long)p.n_main_slabs * SLAB_BYTES, lds_w, dma_voff,  // correction slab 0 -> buffer 0
+                      min(SLAB_KSTEPS, p.n_corr_ksteps));                              // (a chunk is a k-step)
     dma_step(0, slab_prev, NIMG - 1, 0, false, 0, 0);                                  // predecessor codes -> last image
     dma_step(1, slab_prev, NIMG - 1, 0, false, 0, 0);
     dma_step(2, 0, 0, slab_prev, true, 2, 0);                                          // its scales -> scale buffer 2
@@ -259,7 +260,9 @@ __global__ __launch_bounds__(512) void remat_attn_coded_kernel(const RematParams
                                    "v"(mfr[4 * kh + 3].x), "v"(mfr[4 * kh + 3].y), "v"(mfr[4 * kh + 3].z), "v"(mfr[4 * kh + 3].w));
         }
         const uint32_t wdst = lds_w + (uint32_t)(((cs + 1) & 1) * SLAB_BYTES);
-        if (cs + 1 < n_corr_slabs) issue_slab(wsrc + (long long)(p.n_main_slabs + cs + 1) * SLAB_BYTES, wdst, dma_voff);
+        if (cs + 1 < n_corr_slabs)
+            issue_slab_chunks(wsrc + (long long)(p.n_main_slabs + cs + 1) * SLAB_BYTES, wdst, dma_voff,
+                              min(SLAB_KSTEPS, p.n_corr_ksteps - (cs + 1) * SLAB_KSTEPS));
         else issue_slab(wsrc, wdst, dma_voff);                                                   // the first main slab
         if (cs == 0) {
             fetch_tokens(NIMG - 1);

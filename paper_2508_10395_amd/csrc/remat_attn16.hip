@@ -717,7 +717,8 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
         }
     }
     if constexpr (PC) issue_slab(wsrc, lds_w, dma_voff);                               // the first main slab -> buffer 0
-    else issue_slab(wsrc + (long long)p.n_main_slabs * SLAB_BYTES, lds_w, dma_voff);   // correction slab 0 -> buffer 0
+    else issue_slab_chunks(wsrc + (long long)p.n_main_slabs * SLAB_BYTES, lds_w, dma_voff,   // correction slab 0 -> buffer 0
+                           2 * min(NT, p.n_corr_ksteps));                                    // (a tick is two chunks)
     dma_step(0, slab_prev, NIMG - 1, 0, false, 0, 0);                                  // predecessor codes -> last image
     dma_step(1, slab_prev, NIMG - 1, 0, false, 0, 0);
     dma_step(2, 0, 0, slab_prev, true, 2, 0);                                          // its scales -> scale buffer 2
@@ -757,7 +758,9 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
                                "v"(mfr[ss][2].x), "v"(mfr[ss][2].y), "v"(mfr[ss][2].z), "v"(mfr[ss][2].w),
                                "v"(mfr[ss][3].x), "v"(mfr[ss][3].y), "v"(mfr[ss][3].z), "v"(mfr[ss][3].w));
         const uint32_t wdst = lds_w + (uint32_t)(((cs + 1) & 1) * SLAB_BYTES);
-        if (cs + 1 < n_corr_slabs) issue_slab(wsrc + (long long)(p.n_main_slabs + cs + 1) * SLAB_BYTES, wdst, dma_voff);
+        if (cs + 1 < n_corr_slabs)
+            issue_slab_chunks(wsrc + (long long)(p.n_main_slabs + cs + 1) * SLAB_BYTES, wdst, dma_voff,
+                              2 * min(NT, p.n_corr_ksteps - (cs + 1) * NT));
         else issue_slab(wsrc, wdst, dma_voff);                                                   // the first main slab
         if (cs == 0) {
             fetch_tokens(NIMG - 1);

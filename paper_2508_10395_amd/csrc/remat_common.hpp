@@ -111,6 +111,14 @@ __device__ __forceinline__ void issue_slab(const uint8_t* src, uint32_t lds_dst,
     for (int c = 0; c < 8; ++c) dma_b128(src + c * 8192, voff, lds_dst + c * 8192);
 }
 
+// the first n_chunks 8 KiB chunks of a slab only (a correction slab's k-steps past the last one hold nothing)
+__device__ __forceinline__ void issue_slab_chunks(const uint8_t* src, uint32_t lds_dst, uint32_t voff, int n_chunks)
+{
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+        if (c < n_chunks) dma_b128(src + c * 8192, voff, lds_dst + c * 8192);
+}
+
 __device__ __forceinline__ f16x8 as_frag(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
 {
     uint4 v; v.x = a; v.y = b; v.z = c; v.w = d;
