@@ -257,7 +257,8 @@ hipError_t run_remat_attn_decode_latent(const xq_attn_t* a, const uint16_t* q, c
     const int bits = xc->fmt.bits, G = xc->fmt.group, r = xc->fmt.d / 2, B = xc->B, cap = xc->cap;
     const int pairs = a->n_kv_heads / 2;
     const WPrepLayout L = make_wprep_layout_for_cache(r, G, bits, pairs);          // one stream per half, "head" = pair
-    // pass 2 runs on the 16-column fragments where the format has them (that epilogue takes 16 query rows per KV head)
+    // pass 2 runs on the 16-column fragments where the format has them (that epilogue takes 16 query rows per KV head,
+    // which is the most an attention descriptor may ask for)
     const bool t16 = L.t16_bytes != 0 && a->n_q_heads / a->n_kv_heads <= 16;
     RematParams p{};
     fill_common(p, a, q, B, cap, len, max_len, ws);

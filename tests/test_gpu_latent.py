@@ -133,10 +133,20 @@ def _run_latent(xq, w, bits_, G, lens, pairs=None):
     return float(normwise.max()), e2e
 
 
-@pytest.mark.parametrize("bits_,G", [(2, 64), (3, 128), (4, 128)])
+# (3- and 4-bit groups of 64 have no stream of 16-column fragments: their value pass runs on the 32x32x16 kernel)
+@pytest.mark.parametrize("bits_,G", [(2, 64), (3, 128), (4, 128), (2, 128), (3, 64), (4, 64)])
 def test_latent_pipeline_small(xq, bits_, G):
     w = xi.C4.scaled(B=3, L=420, d=512, Hq=8, Hkv=2, n_outlier=5)      # r = 256, g = 4
     _run_latent(xq, w, bits_, G, lens=[420, 257, 31])
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (4, 2), (12, 4), (16, 2), (32, 2)])
+def test_latent_query_heads_per_kv_head(xq, Hq, Hkv):
+    """1, 2, 3, 8 and 16 (the library's maximum) query heads per KV head: the value pass takes its 16 query rows per
+    KV head in one group; ragged lengths across a tile boundary."""
+    w = xi.C4.scaled(B=2, L=300, d=512, Hq=Hq, Hkv=Hkv, n_outlier=3)
+    _run_latent(xq, w, 2, 64, lens=[300, 256])
+    _run_latent(xq, w, 3, 128, lens=[1, 289])
 
 
 def test_latent_close_to_plain_gqa_at_high_precision(xq):
