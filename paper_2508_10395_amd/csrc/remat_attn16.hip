@@ -279,6 +279,7 @@ __device__ __forceinline__ void prefill_epilogue16(const RematParams& p, const T
     auto lds_barrier = [&]() XQ_INLINE_LAMBDA { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
     uint4 qf[4];
     f32x4 S[2];
+    uint4 vh[8], vl[8];
     load_q(0, qf);
     scores(0, qf, S);
     if (16 < NQ) load_q(16, qf);
@@ -309,20 +310,27 @@ __device__ __forceinline__ void prefill_epilogue16(const RematParams& p, const T
         lds_barrier();                                                     // weights and sums of all eight chunks are in LDS
         // operands of P V, four chunks ahead: contraction index (quarter q', element 4 s + i) of chunk cw <-> its
         // token 16 s + 4 q' + i, for the P fragment as written above and for the V pieces q' and 4 + q' alike
-        uint4 ph[4], pl[4], vh[4], vl[4];
+        uint4 ph[4], pl[4];
         auto load_chunk = [&](auto CW) XQ_INLINE_LAMBDA {
             constexpr int cw = decltype(CW)::value, k = cw & 3;
             ph[k] = *reinterpret_cast<const uint4*>(pbuf + (cw * 64 + c.lane) * 16);
             pl[k] = *reinterpret_cast<const uint4*>(pbuf + PF16_P_BYTES / 2 + (cw * 64 + c.lane) * 16);
-            const uint8_t* v0 = lds + cw * PF16_VT_WAVE_BYTES + vt16_offset(ncol, q);
-            const uint8_t* v1 = lds + cw * PF16_VT_WAVE_BYTES + vt16_offset(ncol, 4 + q);
-            const uint2 h0 = *reinterpret_cast<const uint2*>(v0), h1 = *reinterpret_cast<const uint2*>(v1);
-            const uint2 l0 = *reinterpret_cast<const uint2*>(v0 + PF16_VT_IMAGE_BYTES);
-            const uint2 l1 = *reinterpret_cast<const uint2*>(v1 + PF16_VT_IMAGE_BYTES);
-            vh[k] = make_uint4(h0.x, h0.y, h1.x, h1.y);
-            vl[k] = make_uint4(l0.x, l0.y, l1.x, l1.y);
         };
         static_for<0, 4>(load_chunk);
+        // the V fragments of this wave's 16 columns are the same for every group of query rows: they are taken out of
+        // the images once and stay in registers (the accumulator's are free by now)
+        if (q0 == 0) {
+            static_for<0, 8>([&](auto CW) XQ_INLINE_LAMBDA {
+                constexpr int cw = decltype(CW)::value;
+                const uint8_t* v0 = lds + cw * PF16_VT_WAVE_BYTES + vt16_offset(ncol, q);
+                const uint8_t* v1 = lds + cw * PF16_VT_WAVE_BYTES + vt16_offset(ncol, 4 + q);
+                const uint2 h0 = *reinterpret_cast<const uint2*>(v0), h1 = *reinterpret_cast<const uint2*>(v1);
+                const uint2 l0 = *reinterpret_cast<const uint2*>(v0 + PF16_VT_IMAGE_BYTES);
+                const uint2 l1 = *reinterpret_cast<const uint2*>(v1 + PF16_VT_IMAGE_BYTES);
+                vh[cw] = make_uint4(h0.x, h0.y, h1.x, h1.y);
+                vl[cw] = make_uint4(l0.x, l0.y, l1.x, l1.y);
+            });
+        }
         float Lt = 0.0f;
         if (c.wave == 0 && q == 0) {
 #pragma unroll
@@ -337,9 +345,9 @@ __device__ __forceinline__ void prefill_epilogue16(const RematParams& p, const T
         f32x4 O0 = {0.0f, 0.0f, 0.0f, 0.0f}, O1 = O0, O2 = O0;             // hi*hi, lo*hi, hi*lo: three independent chains
         static_for<0, 8>([&](auto CW) XQ_INLINE_LAMBDA {
             constexpr int cw = decltype(CW)::value, k = cw & 3;
-            O0 = mfma16_bf16(ph[k], vh[k], O0);
-            O1 = mfma16_bf16(pl[k], vh[k], O1);
-            O2 = mfma16_bf16(ph[k], vl[k], O2);
+            O0 = mfma16_bf16(ph[k], vh[cw], O0);
+            O1 = mfma16_bf16(pl[k], vh[cw], O1);
+            O2 = mfma16_bf16(ph[k], vl[cw], O2);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (cw + 4 < 8) load_chunk(std::integral_constant<int, cw + 4>{});
             __builtin_amdgcn_sched_barrier(0);
