@@ -175,7 +175,11 @@ __device__ __forceinline__ void prefill_epilogue16(const RematParams& p, const T
 {
     const int tok0 = c.tile * TILE_TOKENS + c.wave * CHUNK_TOKENS;
     const bool active = tok0 < c.len;                                      // wave-uniform: chunk not entirely past len
-    const int c16 = c.lane & 15, q = c.lane >> 4;
+    // (the lane index passes through an empty asm statement: the addresses derived from it below are then not
+    // computed ahead of the contraction loop, where they would cost registers the loop does not have)
+    int lane_here = c.lane;
+    asm volatile("" : "+v"(lane_here));
+    const int c16 = lane_here & 15, q = lane_here >> 4;
     __syncthreads();                                                       // every wave is done with the slab buffers
     uint4 khi[2][4], klo[2][4];
     if (active) {
@@ -228,10 +232,30 @@ __device__ __forceinline__ void prefill_epilogue16(const RematParams& p, const T
         return ((long long)c.b * p.Tq + tq) * p.Hq + c.hk * gq + (qi - tq * gq);
     };
     const int ncol = 16 * c.wave + c16;                                    // the value column this lane reads and stores
+    // Where a group of 16 rows is a whole number of query tokens (1, 2, 4, 8 or 16 heads per KV head), the rows of
+    // consecutive groups are a fixed stride apart, and the addresses of a group follow from those of the previous one by
+    // an addition: the 64-bit multiplies of part_row (quarter-rate instructions, six uses per group) were a third of the
+    // group loop's issue time.  load_q and scores are called for the groups in order, which the running values rely on.
+    const bool lin = 16 % gq == 0;
+    const int tok_per_group = lin ? 16 / gq : 0;
+    const long long rows_per_group = (long long)tok_per_group * p.Hq;
+    const uint16_t* q_run = p.q + part_row(c16) * 128 + 4 * q;            // this lane's query row of the next group to load
+    int tq_run = token_of(c16);                                            // ... its query token, of the next group to score
+    float* po_run = p.part_o + (part_row(4 * q) * p.chunks_per_seq + c.tile) * 128 + ncol;   // row 4 q of the group to store
+    float* pml_run = p.part_ml + (part_row(c16) * p.chunks_per_seq + c.tile) * 2;
+    long long po_step[4];                                                  // rows 4 q + i against row 4 q: the same for every lane
+#pragma unroll
+    for (int i = 0; i < 4; ++i) po_step[i] = (gq >= 4 ? i : (long long)(i / gq) * p.Hq + i % gq) * p.chunks_per_seq * 128;
     // Q fragments of the group that starts at query row q0, for this lane's query row of it (rows past NQ repeat the
     // last one and are not stored)
     auto load_q = [&](int q0, uint4 (&qf)[4]) XQ_INLINE_LAMBDA {
-        const uint16_t* qv = p.q + part_row(min(q0 + c16, NQ - 1)) * 128 + 4 * q;
+        const uint16_t* qv;
+        if (lin && q0 + 16 <= NQ) {
+            qv = q_run;
+            q_run += rows_per_group * 128;
+        } else {
+            qv = p.q + part_row(min(q0 + c16, NQ - 1)) * 128 + 4 * q;
+        }
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb) {
             const uint2 a = *reinterpret_cast<const uint2*>(qv + 32 * kb);
@@ -256,7 +280,8 @@ __device__ __forceinline__ void prefill_epilogue16(const RematParams& p, const T
                     S[s] = mfma16_bf16(klo[s][kb], qf[kb], S[s]);
                 }
             // element i of S[s] <-> token tok0 + 16 s + 4 q + i; visible up to the query's own row
-            const int tq = token_of(min(q0 + c16, NQ - 1));
+            // (rows past NQ, which are not stored, take whatever token the running value names)
+            const int tq = lin ? tq_run : token_of(min(q0 + c16, NQ - 1));
             const int limit = c.len - p.Tq + tq - tok0;
 #pragma unroll
             for (int s = 0; s < 2; ++s)
@@ -269,6 +294,7 @@ __device__ __forceinline__ void prefill_epilogue16(const RematParams& p, const T
             m = fmaxf(m, __shfl_xor(m, 16));
             m = fmaxf(m, __shfl_xor(m, 32));
         }
+        tq_run += tok_per_group;
         if (q == 0) mbuf[c.wave * 16 + c16] = m;
     };
 
@@ -353,15 +379,18 @@ __device__ __forceinline__ void prefill_epilogue16(const RematParams& p, const T
             __builtin_amdgcn_sched_barrier(0);
         });
         if (c.wave == 0 && q == 0 && q0 + c16 < NQ) {
-            const long long pidx = part_row(q0 + c16) * p.chunks_per_seq + c.tile;
-            p.part_ml[pidx * 2] = M;
-            p.part_ml[pidx * 2 + 1] = Lt;
+            float* ml = lin ? pml_run : p.part_ml + (part_row(q0 + c16) * p.chunks_per_seq + c.tile) * 2;
+            ml[0] = M;
+            ml[1] = Lt;
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int qr = q0 + 4 * q + i;
-            if (qr < NQ) p.part_o[(part_row(qr) * p.chunks_per_seq + c.tile) * 128 + ncol] = (O1[i] + O2[i]) + O0[i];
+            float* o = lin ? po_run + po_step[i] : p.part_o + (part_row(qr) * p.chunks_per_seq + c.tile) * 128 + ncol;
+            if (qr < NQ) *o = (O1[i] + O2[i]) + O0[i];
         }
+        po_run += rows_per_group * p.chunks_per_seq * 128;
+        pml_run += rows_per_group * p.chunks_per_seq * 2;
     }
 }
 
@@ -552,15 +581,18 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
                                : ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.ng + 1) * 512);
     int my_row[2];
     uint32_t moff[2];
-    const uint8_t* my_codes[2];
-    const uint16_t* my_scale[2];
+    // (the second token half sits 16 rows further on: one base each, so that the loop keeps one register per pointer)
+    const uint8_t* my_codes0;
+    const uint16_t* my_scale0;
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
         my_row[s] = wave * CHUNK_TOKENS + 16 * s + c16;
         moff[s] = (uint32_t)min(c.tile * TILE_TOKENS + my_row[s], c.len - 1) * (uint32_t)p.ng_row;
         // groups of 128: unit q; groups of 64: of every unit j the dword that holds its k-step q (2 bits: dword q / 2)
-        my_codes[s] = lds + LDS_CODES_OFF + my_row[s] * ROW_SLAB_BYTES + (G == 128 ? q * UNIT_BYTES : (q >> 1) * 4);
-        my_scale[s] = reinterpret_cast<const uint16_t*>(lds + LDS_SCALES_OFF) + my_row[s];
+        if (s == 0) {
+            my_codes0 = lds + LDS_CODES_OFF + my_row[0] * ROW_SLAB_BYTES + (G == 128 ? q * UNIT_BYTES : (q >> 1) * 4);
+            my_scale0 = reinterpret_cast<const uint16_t*>(lds + LDS_SCALES_OFF) + my_row[0];
+        }
     }
     // code DMA: 16-byte piece pc of the tile's slab image = (row pc / BITS, part pc % BITS);
     // wave instruction i covers pieces [64 i, 64 i + 64); this wave issues i = wave and wave + 8
@@ -603,7 +635,7 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
 
     auto fetch_scales = [&](int sbuf, float (&e)[2]) XQ_INLINE_LAMBDA {
 #pragma unroll
-        for (int s = 0; s < 2; ++s) e[s] = __uint_as_float((uint32_t)my_scale[s][sbuf * (LDS_SCALES_BYTES / 2)] << 16);
+        for (int s = 0; s < 2; ++s) e[s] = __uint_as_float((uint32_t)my_scale0[16 * s + sbuf * (LDS_SCALES_BYTES / 2)] << 16);
     };
     // groups of 64: the factors of the slab whose scales are in buffer sbuf
     auto fetch_factors = [&](int sbuf, uint32_t (&f)[2][2]) XQ_INLINE_LAMBDA {
@@ -611,7 +643,7 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
         for (int s = 0; s < 2; ++s)
 #pragma unroll
             for (int g = 0; g < 2; ++g) {
-                const float e = __uint_as_float((uint32_t)my_scale[s][sbuf * (LDS_SCALES_BYTES / 2) + g * TILE_TOKENS] << 16);
+                const float e = __uint_as_float((uint32_t)my_scale0[16 * s + sbuf * (LDS_SCALES_BYTES / 2) + g * TILE_TOKENS] << 16);
                 const _Float16 h = (_Float16)(e * tok_inv15[s]);            // exact: 8-bit significand, at most 2^15
                 const xq_f16x2 hh = {h, h};
                 f[s][g] = __builtin_bit_cast(uint32_t, hh);
@@ -620,7 +652,7 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
     auto fetch_tokens = [&](int img) XQ_INLINE_LAMBDA {
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            const uint8_t* src = my_codes[s] + img * IMG_BYTES;
+            const uint8_t* src = my_codes0 + s * 16 * ROW_SLAB_BYTES + img * IMG_BYTES;
             if constexpr (G == 64) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) cur[s][j] = *reinterpret_cast<const uint32_t*>(src + j * UNIT_BYTES);
@@ -863,7 +895,6 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
         const uint8_t* slab_next = my_slab + ((it + 1 + par0) & 1) * SLAB_BYTES;
         float e_nxt[2] = {1.0f, 1.0f};                       // scales of the next slab (landed one slab ago)
         float hr_n[2] = {1.0f, 1.0f};                        // boundary factors of the next iteration
-        uint32_t fac_nxt[2][2] = {{fac[0][0], fac[0][1]}, {fac[1][0], fac[1][1]}};   // groups of 64: the next slab's factors
         // scale buffers: per-token source, slab s in buffer s & 1 (its scales are taken into registers one slab ahead);
         // per-channel source, slab s in buffer s % 3 (its factors are read all through its own iteration)
         const int sb_dma = PC ? (it + 2) % 3 : (it & 1);
@@ -907,7 +938,8 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
             // the next slab's scales are in LDS since the previous slab
             if constexpr (!PC && sidx == 40) {
                 if (more_main) {
-                    if constexpr (G == 64) fetch_factors((it + 1) & 1, fac_nxt);
+                    // (groups of 64: the slab's last fragment was made in slot 39, the factors may be replaced)
+                    if constexpr (G == 64) fetch_factors((it + 1) & 1, fac);
                     else fetch_scales((it + 1) & 1, e_nxt);
                 }
             }
@@ -932,8 +964,7 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
         if (more_main && !PC) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                if constexpr (G == 64) { fac[s][0] = fac_nxt[s][0]; fac[s][1] = fac_nxt[s][1]; }
-                else { E_prev[s] = E_cur[s]; E_cur[s] = e_nxt[s]; hr[s] = hr_n[s]; }
+                if constexpr (G == 128) { E_prev[s] = E_cur[s]; E_cur[s] = e_nxt[s]; hr[s] = hr_n[s]; }
             }
         }
     }
