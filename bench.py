@@ -413,7 +413,7 @@ def main():
                               device=dev)
             olens = [ow.L] * ow.B
             t_o = timed(lambda: xq.xq_remat_attn_decode(oattn, oq, owp, olens, xcache=ocache, out=oout, workspace=ows),
-                        n=5, warm=2)
+                        n=10, warm=12)    # (from an idle GPU the clock takes some 10 launches to settle)
             oflops = 2.0 * ow.B * ow.L * ow.d * (2 * ow.Hkv * ow.hd) + 4.0 * ow.B * ow.L * ow.Hq * ow.hd
             extra["remat_attn_" + ow.name] = {"ms": t_o, "tokens/s/layer": ow.B * ow.L / (t_o * 1e-3),
                                               "TFLOP/s": oflops / t_o / 1e9,
@@ -435,7 +435,7 @@ def main():
         oout = torch.empty((ow.B, ow.Hq, ow.hd), dtype=torch.float32, device=dev)
         olens = [ow.L] * ow.B
         t_l = timed(lambda: xq.xq_remat_attn_decode_latent(oattn, oq, lwp, olens, lcache, out=oout, workspace=lws),
-                    n=5, warm=2)
+                    n=10, warm=12)    # (from an idle GPU the clock takes some 10 launches to settle)
         lflops = 2.0 * ow.B * ow.L * r * (2 * r) + 4.0 * ow.B * ow.L * ow.Hq * ow.hd
         ut = (torch.randn((2 * r, ow.d), device=dev, generator=gen) * ow.d ** -0.5).to(torch.bfloat16)
         xnew = torch.randn((ow.B, 1, ow.d), device=dev, generator=gen).to(torch.bfloat16)
@@ -499,7 +499,7 @@ def main():
         dwp = xq.xq_prepare_weights(oattn, ow.d, 0, 16, dev_bf16(owk), dev_bf16(owv))
         dws = torch.empty(xq.xq_remat_attn_workspace_bytes(oattn, ow.B, ow.L, ow.d, 0), dtype=torch.uint8, device=dev)
         t_a = timed(lambda: xq.xq_remat_attn_decode(oattn, oq, dwp, olens, acc_bf16=oacc, out=oout, workspace=dws),
-                    n=5, warm=2)
+                    n=10, warm=12)    # (from an idle GPU the clock takes some 10 launches to settle)
         # prefill-sized projections on the matrix cores: a chunk of 1024 new tokens per sequence into the latent
         # space, plain (Sec. 3.3.1) and as the cross-layer delta against the accumulator (Sec. 3.3.2)
         Tb = 1024
