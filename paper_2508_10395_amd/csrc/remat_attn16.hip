@@ -581,19 +581,16 @@ __global__ __launch_bounds__(512) void remat_attn_tile16_kernel(const RematParam
                                : ((long long)c.b * p.tiles_per_seq + c.tile) * (long long)(p.ng + 1) * 512);
     int my_row[2];
     uint32_t moff[2];
-    // (the second token half sits 16 rows further on: one base each, so that the loop keeps one register per pointer)
-    const uint8_t* my_codes0;
-    const uint16_t* my_scale0;
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
         my_row[s] = wave * CHUNK_TOKENS + 16 * s + c16;
         moff[s] = (uint32_t)min(c.tile * TILE_TOKENS + my_row[s], c.len - 1) * (uint32_t)p.ng_row;
-        // groups of 128: unit q; groups of 64: of every unit j the dword that holds its k-step q (2 bits: dword q / 2)
-        if (s == 0) {
-            my_codes0 = lds + LDS_CODES_OFF + my_row[0] * ROW_SLAB_BYTES + (G == 128 ? q * UNIT_BYTES : (q >> 1) * 4);
-            my_scale0 = reinterpret_cast<const uint16_t*>(lds + LDS_SCALES_OFF) + my_row[0];
-        }
     }
+    // this lane's codes and scales in the LDS images, for its first token; the second one sits 16 rows further on (one
+    // base each, so that the loop keeps one register per pointer).  Groups of 128: unit q; groups of 64: of every unit j
+    // the dword that holds its k-step q (2 bits: dword q / 2)
+    const uint8_t* my_codes0 = lds + LDS_CODES_OFF + my_row[0] * ROW_SLAB_BYTES + (G == 128 ? q * UNIT_BYTES : (q >> 1) * 4);
+    const uint16_t* my_scale0 = reinterpret_cast<const uint16_t*>(lds + LDS_SCALES_OFF) + my_row[0];
     // code DMA: 16-byte piece pc of the tile's slab image = (row pc / BITS, part pc % BITS);
     // wave instruction i covers pieces [64 i, 64 i + 64); this wave issues i = wave and wave + 8
     uint32_t cvoff[2];
